@@ -1,0 +1,176 @@
+"""numpy front end of the CPU oracle (oracle/abq_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, the smoke check and bench.py's cpu_baseline
+leg.  Holds no arithmetic of its own beyond argument marshalling; every function forwards to
+the C file, which cites the passages of the paper it follows.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+from .build import LIB, build as _build
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB):
+            _build()
+        lib = ctypes.CDLL(LIB)
+        lib.abq_oracle_threads.restype = ctypes.c_int
+        lib.abq_oracle_half_bits.restype = ctypes.c_uint16
+        lib.abq_oracle_half_bits.argtypes = [ctypes.c_double]
+        _lib = lib
+    return _lib
+
+
+def _p(a):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _u8(a):
+    a = np.ascontiguousarray(a)
+    assert a.dtype == np.uint8, a.dtype
+    return a
+
+
+def _i32(a):
+    return np.ascontiguousarray(np.asarray(a), dtype=np.int32)
+
+
+def threads() -> int:
+    return int(_load().abq_oracle_threads())
+
+
+def acc(A, W):
+    """int64 [M,N] = sum_k A[m,k]*W[n,k] over raw codes (Sec. 3.4, Appendix B)."""
+    A, W = _u8(A), _u8(W)
+    M, K = A.shape
+    N, K2 = W.shape
+    assert K == K2
+    out = np.empty((M, N), dtype=np.int64)
+    _load().abq_oracle_acc(M, N, K, _p(A), _p(W), _p(out))
+    return out
+
+
+def acc_sampled(A, W, ms, ns):
+    A, W = _u8(A), _u8(W)
+    M, K = A.shape
+    N, _ = W.shape
+    ms, ns = _i32(ms), _i32(ns)
+    assert ms.shape == ns.shape and ms.ndim == 1
+    assert ms.min(initial=0) >= 0 and ms.max(initial=0) < M and ns.min(initial=0) >= 0 and ns.max(initial=0) < N
+    out = np.empty(ms.shape[0], dtype=np.int64)
+    _load().abq_oracle_acc_sampled(M, N, K, _p(A), _p(W), ctypes.c_int64(ms.shape[0]), _p(ms), _p(ns), _p(out))
+    return out
+
+
+def acc_centered(A, W, az, wz):
+    """int64 [M,N] = sum_k (A-az[m])*(W-wz[n]), computed term by term (Eq. 3 semantics)."""
+    A, W = _u8(A), _u8(W)
+    M, K = A.shape
+    N, _ = W.shape
+    az, wz = _i32(az), _i32(wz)
+    assert az.shape == (M,) and wz.shape == (N,)
+    out = np.empty((M, N), dtype=np.int64)
+    _load().abq_oracle_acc_centered(M, N, K, _p(A), _p(W), _p(az), _p(wz), _p(out))
+    return out
+
+
+def acc_centered_sampled(A, W, az, wz, ms, ns):
+    A, W = _u8(A), _u8(W)
+    M, K = A.shape
+    N, _ = W.shape
+    az, wz, ms, ns = _i32(az), _i32(wz), _i32(ms), _i32(ns)
+    assert az.shape == (M,) and wz.shape == (N,)
+    assert ms.min(initial=0) >= 0 and ms.max(initial=0) < M and ns.min(initial=0) >= 0 and ns.max(initial=0) < N
+    out = np.empty(ms.shape[0], dtype=np.int64)
+    _load().abq_oracle_acc_centered_sampled(M, N, K, _p(A), _p(W), _p(az), _p(wz),
+                                            ctypes.c_int64(ms.shape[0]), _p(ms), _p(ns), _p(out))
+    return out
+
+
+def dequant(accc, a_scale, w_scale):
+    """(double Y, uint16 half bits) from the centered accumulator and the two scale vectors."""
+    accc = np.ascontiguousarray(accc, dtype=np.int64)
+    M, N = accc.shape
+    a_scale = np.ascontiguousarray(a_scale, dtype=np.float32)
+    w_scale = np.ascontiguousarray(w_scale, dtype=np.float32)
+    assert a_scale.shape == (M,) and w_scale.shape == (N,)
+    y = np.empty((M, N), dtype=np.float64)
+    y16 = np.empty((M, N), dtype=np.uint16)
+    _load().abq_oracle_dequant(M, N, _p(accc), _p(a_scale), _p(w_scale), _p(y), _p(y16))
+    return y, y16
+
+
+def dequant_flat(accc, a_scale_per_elem, w_scale_per_elem):
+    """Same as dequant for a flat list of sampled elements with their own scales."""
+    accc = np.ascontiguousarray(accc, dtype=np.int64).reshape(-1)
+    n = accc.shape[0]
+    y = np.empty(n, dtype=np.float64)
+    y16 = np.empty(n, dtype=np.uint16)
+    a = np.ascontiguousarray(a_scale_per_elem, dtype=np.float32).reshape(-1)
+    w = np.ascontiguousarray(w_scale_per_elem, dtype=np.float32).reshape(-1)
+    lib = _load()
+    one = np.empty(1, dtype=np.float64)
+    one16 = np.empty(1, dtype=np.uint16)
+    for i in range(n):
+        lib.abq_oracle_dequant(1, 1, _p(accc[i:i + 1]), _p(a[i:i + 1]), _p(w[i:i + 1]), _p(one), _p(one16))
+        y[i] = one[0]
+        y16[i] = one16[0]
+    return y, y16
+
+
+def half_bits(v: float) -> int:
+    return int(_load().abq_oracle_half_bits(float(v)))
+
+
+def plane_words(K: int) -> int:
+    """Words per plane row used by the oracle's packers (K rounded up to 32 bits)."""
+    return (K + 31) // 32
+
+
+def pack_planes(codes, bits, Kw=None):
+    """uint32 [bits,R,Kw]: plane s = (codes >> s) & 1, bit k%32 of word k/32 (Sec. 3.4 step 1)."""
+    codes = _u8(codes)
+    R, K = codes.shape
+    Kw = plane_words(K) if Kw is None else Kw
+    assert Kw * 32 >= K
+    out = np.empty((bits, R, Kw), dtype=np.uint32)
+    _load().abq_oracle_pack_planes(bits, R, K, Kw, _p(codes), _p(out))
+    return out
+
+
+def unpack_planes(planes, K):
+    planes = np.ascontiguousarray(planes, dtype=np.uint32)
+    bits, R, Kw = planes.shape
+    out = np.empty((R, K), dtype=np.uint8)
+    _load().abq_oracle_unpack_planes(bits, R, K, Kw, _p(planes), _p(out))
+    return out
+
+
+def acc_bitplane(a_planes, w_planes):
+    """Literal Appendix B: sum_{s,t} 2^(s+t) popcount(A_t AND W_s) on packed planes."""
+    a_planes = np.ascontiguousarray(a_planes, dtype=np.uint32)
+    w_planes = np.ascontiguousarray(w_planes, dtype=np.uint32)
+    q, M, Kw = a_planes.shape
+    p, N, Kw2 = w_planes.shape
+    assert Kw == Kw2
+    out = np.empty((M, N), dtype=np.int64)
+    _load().abq_oracle_acc_bitplane(p, q, M, N, Kw, _p(a_planes), _p(w_planes), _p(out))
+    return out
+
+
+def quant_act(x_half, q):
+    """Per-token quantizer: (codes uint8 [M,K], a_scale float32 [M], a_zero int32 [M])."""
+    x_half = np.ascontiguousarray(x_half)
+    assert x_half.dtype == np.float16
+    M, K = x_half.shape
+    codes = np.empty((M, K), dtype=np.uint8)
+    sc = np.empty(M, dtype=np.float32)
+    zp = np.empty(M, dtype=np.int32)
+    _load().abq_oracle_quant_act(q, M, K, _p(x_half.view(np.uint16)), _p(codes), _p(sc), _p(zp))
+    return codes, sc, zp

@@ -1,0 +1,256 @@
+/*
+ * CPU oracle for the arbitrary-precision quantized matmul of ABQ-LLM (arXiv 2408.08554).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition the GPU library is
+ * checked against.  It shares no code, header, table or helper with the HIP path and the
+ * product never calls it: only tests, the smoke check and the bench's cpu_baseline leg do.
+ *
+ * Notation (Appendix B of the paper; p = weight bits, q = activation bits):
+ *   A  uint8 [M,K] row-major activation codes, 0 <= A < 2^q
+ *   W  uint8 [N,K] row-major weight codes,     0 <= W < 2^p
+ *   acc[m,n] = sum_k A[m,k] * W[n,k]                         ("32-bit output Y = W X", Sec. 3.4)
+ *
+ * The bit-plane method of Sec. 3.4 / Appendix B (Eq. "formula:matrix") reaches this integer
+ * exactly, so the oracle for the accumulator is the plain product sum in int64;
+ * abq_oracle_acc_bitplane() is the literal decomposition, kept as an independent second path.
+ *
+ * Affine semantics (Eq. 3: codes are clamp(round(x/Delta)+z, 0, 2^n-1), so the real value
+ * of a code c is Delta*(c - z); weights per output channel, activations per token, Sec. 4.1):
+ *   accc[m,n] = sum_k (A[m,k]-az[m]) * (W[n,k]-wz[n])         computed directly, term by term
+ *   Y[m,n]    = (double)accc * (double)a_scale[m] * (double)w_scale[n], then RNE to binary16.
+ * The paper names the DeQuant step (Fig. 3b) but prints no formula; the lines above are the
+ * reading this build takes.
+ *
+ * Parity status: accumulator, centered accumulator, dequant, half rounding, plane packing are
+ * pinned by tests (brute force, library matmul, closed forms, long-double dequantise-then-
+ * multiply, numpy's float16 conversion).  abq_oracle_quant_act: PARITY UNPINNED by the paper
+ * (it only says "per-token"); pinned by invariants only.
+ */
+#include <stdint.h>
+#include <stddef.h>
+#include <string.h>
+#include <math.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+int abq_oracle_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* acc[m,n] = sum_k A[m,k]*W[n,k]  (Sec. 3.4: Y = W X with a 32-bit result; here int64). */
+void abq_oracle_acc(int M, int N, int K, const uint8_t* A, const uint8_t* W, int64_t* acc)
+{
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int m = 0; m < M; ++m) {
+        for (int n = 0; n < N; ++n) {
+            int64_t s = 0;
+            for (int k = 0; k < K; ++k)
+                s += (int64_t)A[(size_t)m * K + k] * (int64_t)W[(size_t)n * K + k];
+            acc[(size_t)m * N + n] = s;
+        }
+    }
+}
+
+/* Same sum, but only at the listed (m,n) pairs: for sampled checks at sizes where the full
+ * triple loop would take minutes. */
+void abq_oracle_acc_sampled(int M, int N, int K, const uint8_t* A, const uint8_t* W,
+                            int64_t count, const int32_t* ms, const int32_t* ns, int64_t* acc)
+{
+    (void)M; (void)N;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < count; ++i) {
+        const uint8_t* a = A + (size_t)ms[i] * K;
+        const uint8_t* w = W + (size_t)ns[i] * K;
+        int64_t s = 0;
+        for (int k = 0; k < K; ++k) s += (int64_t)a[k] * (int64_t)w[k];
+        acc[i] = s;
+    }
+}
+
+/* accc[m,n] = sum_k (A[m,k]-az[m]) * (W[n,k]-wz[n])   (Eq. 3 semantics, direct form). */
+void abq_oracle_acc_centered(int M, int N, int K, const uint8_t* A, const uint8_t* W,
+                             const int32_t* az, const int32_t* wz, int64_t* accc)
+{
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int m = 0; m < M; ++m) {
+        for (int n = 0; n < N; ++n) {
+            int64_t s = 0;
+            for (int k = 0; k < K; ++k)
+                s += ((int64_t)A[(size_t)m * K + k] - az[m]) * ((int64_t)W[(size_t)n * K + k] - wz[n]);
+            accc[(size_t)m * N + n] = s;
+        }
+    }
+}
+
+void abq_oracle_acc_centered_sampled(int M, int N, int K, const uint8_t* A, const uint8_t* W,
+                                     const int32_t* az, const int32_t* wz, int64_t count,
+                                     const int32_t* ms, const int32_t* ns, int64_t* accc)
+{
+    (void)M; (void)N;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < count; ++i) {
+        const int m = ms[i], n = ns[i];
+        int64_t s = 0;
+        for (int k = 0; k < K; ++k)
+            s += ((int64_t)A[(size_t)m * K + k] - az[m]) * ((int64_t)W[(size_t)n * K + k] - wz[n]);
+        accc[i] = s;
+    }
+}
+
+/* Round a double to IEEE binary16, round-to-nearest-even, returned as its bit pattern.
+ * Written from the format definition: 1 sign, 5 exponent (bias 15), 10 fraction bits;
+ * smallest subnormal 2^-24, largest finite 65504, overflow to infinity. */
+uint16_t abq_oracle_half_bits(double v)
+{
+    uint16_t sign = 0;
+    if (signbit(v)) { sign = 0x8000u; v = -v; }
+    if (isnan(v)) return (uint16_t)(sign | 0x7E00u);
+    if (isinf(v)) return (uint16_t)(sign | 0x7C00u);
+    if (v == 0.0) return sign;
+    int e;
+    (void)frexp(v, &e);            /* v = f * 2^e with f in [0.5,1)  =>  v in [2^(e-1), 2^e) */
+    int ex = e - 1;                /* unbiased exponent of the leading bit */
+    if (ex < -14) ex = -14;        /* subnormal range: fixed quantum 2^-24 */
+    /* quantum of the target grid at this exponent */
+    const double quantum = ldexp(1.0, ex - 10);
+    double scaled = v / quantum;   /* exact: division by a power of two */
+    double r = nearbyint(scaled);  /* default rounding mode = nearest-even */
+    /* r is an integer in [0, 2048]; 2048 means carry into the next binade */
+    double back = r * quantum;
+    if (back >= 65520.0) return (uint16_t)(sign | 0x7C00u);   /* rounds past the largest finite */
+    if (back == 0.0) return sign;
+    int e2;
+    (void)frexp(back, &e2);
+    int ex2 = e2 - 1;
+    if (ex2 < -14) {
+        /* subnormal: fraction field counts multiples of 2^-24 */
+        uint16_t frac = (uint16_t)(back / ldexp(1.0, -24));
+        return (uint16_t)(sign | frac);
+    }
+    uint16_t frac = (uint16_t)(back / ldexp(1.0, ex2 - 10) - 1024.0);
+    return (uint16_t)(sign | (uint16_t)((ex2 + 15) << 10) | frac);
+}
+
+/* Y = accc * a_scale[m] * w_scale[n] in double; y16 = RNE(binary16).  Either output may be NULL. */
+void abq_oracle_dequant(int M, int N, const int64_t* accc, const float* a_scale,
+                        const float* w_scale, double* y, uint16_t* y16)
+{
+#pragma omp parallel for schedule(static)
+    for (int m = 0; m < M; ++m) {
+        for (int n = 0; n < N; ++n) {
+            double v = (double)accc[(size_t)m * N + n] * (double)a_scale[m] * (double)w_scale[n];
+            if (y) y[(size_t)m * N + n] = v;
+            if (y16) y16[(size_t)m * N + n] = abq_oracle_half_bits(v);
+        }
+    }
+}
+
+/* BitPacking (Sec. 3.4 step 1): bit view [R,K,bits] -> [bits,R,K]; plane s holds
+ * (code >> s) & 1 (Appendix B).  Each plane row is stored as 32-bit words, bit (k mod 32) of
+ * word k/32, zero padded to Kw words (the word order inside a plane is this build's choice,
+ * the paper only fixes the [bits,R,K] order). */
+void abq_oracle_pack_planes(int bits, int R, int K, int Kw, const uint8_t* codes, uint32_t* planes)
+{
+    memset(planes, 0, (size_t)bits * R * Kw * sizeof(uint32_t));
+    for (int s = 0; s < bits; ++s)
+        for (int r = 0; r < R; ++r)
+            for (int k = 0; k < K; ++k)
+                if ((codes[(size_t)r * K + k] >> s) & 1u)
+                    planes[((size_t)s * R + r) * Kw + (k >> 5)] |= (uint32_t)1u << (k & 31);
+}
+
+void abq_oracle_unpack_planes(int bits, int R, int K, int Kw, const uint32_t* planes, uint8_t* codes)
+{
+    for (int r = 0; r < R; ++r)
+        for (int k = 0; k < K; ++k) {
+            unsigned c = 0;
+            for (int s = 0; s < bits; ++s)
+                c |= ((planes[((size_t)s * R + r) * Kw + (k >> 5)] >> (k & 31)) & 1u) << s;
+            codes[(size_t)r * K + k] = (uint8_t)c;
+        }
+}
+
+static int popcount32(uint32_t v)
+{
+    int c = 0;
+    while (v) { c += (int)(v & 1u); v >>= 1; }
+    return c;
+}
+
+/* The literal method (Appendix B): Y = sum_{s<p} sum_{t<q} 2^(s+t) * BMMA(W^s, X^t), where the
+ * 1-bit product is AND and the 1-bit matmul counts the set bits of (A_t AND W_s) along K.
+ * Takes host-packed planes as laid out by abq_oracle_pack_planes. */
+void abq_oracle_acc_bitplane(int p, int q, int M, int N, int Kw,
+                             const uint32_t* a_planes, const uint32_t* w_planes, int64_t* acc)
+{
+    for (int m = 0; m < M; ++m)
+        for (int n = 0; n < N; ++n) {
+            int64_t y = 0;
+            for (int s = 0; s < p; ++s)
+                for (int t = 0; t < q; ++t) {
+                    int64_t yst = 0;
+                    const uint32_t* wr = w_planes + ((size_t)s * N + n) * Kw;
+                    const uint32_t* ar = a_planes + ((size_t)t * M + m) * Kw;
+                    for (int kw = 0; kw < Kw; ++kw) yst += popcount32(ar[kw] & wr[kw]);
+                    y += yst * ((int64_t)1 << (s + t));
+                }
+            acc[(size_t)m * N + n] = y;
+        }
+}
+
+/* binary16 bit pattern -> float (exact). */
+static float half_to_float(uint16_t h)
+{
+    const int sign = (h >> 15) & 1, ex = (h >> 10) & 0x1F, fr = h & 0x3FF;
+    double v;
+    if (ex == 0) v = ldexp((double)fr, -24);
+    else if (ex == 31) v = fr ? NAN : INFINITY;
+    else v = ldexp((double)(fr + 1024), ex - 25);
+    return (float)(sign ? -v : v);
+}
+
+/* Per-token activation quantizer (the paper says only "per-token", Sec. 4.1; Eq. 3 gives the
+ * clamp(round(x/Delta)+z) form).  PARITY UNPINNED by the paper.  Reading taken here, all in
+ * IEEE binary32 because the float results decide integer codes:
+ *   lo = min(min_k x, 0), hi = max(max_k x, 0); Delta = (hi-lo)/(2^q-1); if hi==lo: Delta=1,z=0
+ *   z = clamp(rint(-lo/Delta), 0, 2^q-1); code = clamp(rint(x/Delta)+z, 0, 2^q-1)
+ * rint = round-half-to-even.  NaN/Inf inputs are undefined. */
+void abq_oracle_quant_act(int q, int M, int K, const uint16_t* x_half, uint8_t* codes,
+                          float* a_scale, int32_t* a_zero)
+{
+    const int qmax = (1 << q) - 1;
+    for (int m = 0; m < M; ++m) {
+        float lo = 0.0f, hi = 0.0f;
+        for (int k = 0; k < K; ++k) {
+            float x = half_to_float(x_half[(size_t)m * K + k]);
+            if (x < lo) lo = x;
+            if (x > hi) hi = x;
+        }
+        volatile float delta;
+        int z;
+        if (hi == lo) { delta = 1.0f; z = 0; }
+        else {
+            volatile float range = hi - lo;
+            delta = range / (float)qmax;
+            volatile float zr = (-lo) / delta;
+            float zf = nearbyintf(zr);
+            z = zf < 0.0f ? 0 : (zf > (float)qmax ? qmax : (int)zf);
+        }
+        a_scale[m] = delta;
+        a_zero[m] = z;
+        for (int k = 0; k < K; ++k) {
+            float x = half_to_float(x_half[(size_t)m * K + k]);
+            volatile float t = x / delta;
+            float r = nearbyintf(t);
+            /* r is integral and |r| <= 2^q-1 here, so the int sum is exact */
+            int c = (int)r + z;
+            codes[(size_t)m * K + k] = (uint8_t)(c < 0 ? 0 : (c > qmax ? qmax : c));
+        }
+    }
+}

@@ -1,0 +1,287 @@
+"""Pins for the CPU oracle: every check here compares the oracle with something that is not
+the oracle — brute force on the bits, a library matmul, closed forms, long-double
+dequantise-then-multiply, numpy's own float16 conversion — so that a dropped term, a wrong
+sign/index or a transposed operand in oracle/abq_oracle.c fails at least one of them.
+CPU only."""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2408_08554_amd import synth, metrics
+
+RNG = np.random.Generator(np.random.PCG64(20240808))
+
+
+def codes(shape, bits):
+    return RNG.integers(0, 1 << bits, size=shape, dtype=np.uint8)
+
+
+def brute_bits(A, W, p, q):
+    """Literal Appendix B in pure Python ints: sum_{s<p,t<q} 2^(s+t) sum_k w^s_k AND x^t_k."""
+    M, K = A.shape
+    N = W.shape[0]
+    out = np.zeros((M, N), dtype=object)
+    for m in range(M):
+        for n in range(N):
+            y = 0
+            for s in range(p):
+                for t in range(q):
+                    c = 0
+                    for k in range(K):
+                        c += ((int(W[n, k]) >> s) & 1) & ((int(A[m, k]) >> t) & 1)
+                    y += c << (s + t)
+            out[m, n] = y
+    return out.astype(np.int64)
+
+
+# ---- P1: brute force on tiny inputs -------------------------------------------------------
+
+@pytest.mark.parametrize("p,q", list(itertools.product(range(1, 9), range(1, 9))))
+def test_exhaustive_k1_all_codes(p, q):
+    # every (a,w) code pair once: M = 2^q rows, N = 2^p rows, K = 1
+    A = np.arange(1 << q, dtype=np.uint8).reshape(-1, 1)
+    W = np.arange(1 << p, dtype=np.uint8).reshape(-1, 1)
+    s = np.arange(p).reshape(1, 1, p, 1)
+    t = np.arange(q).reshape(1, 1, 1, q)
+    wb = (W.astype(np.int64).reshape(1, -1, 1, 1) >> s) & 1
+    ab = (A.astype(np.int64).reshape(-1, 1, 1, 1) >> t) & 1
+    expect = ((wb & ab) << (s + t)).sum(axis=(2, 3))
+    assert np.array_equal(oracle.acc(A, W), expect)
+    assert np.array_equal(oracle.acc_bitplane(oracle.pack_planes(A, q), oracle.pack_planes(W, p)), expect)
+
+
+@pytest.mark.parametrize("p,q", [(1, 1), (2, 8), (3, 5), (4, 4), (8, 2), (8, 8), (7, 6), (1, 8)])
+@pytest.mark.parametrize("K", [1, 2, 3, 31, 32, 33, 130])
+def test_bruteforce_random_small(p, q, K):
+    M, N = int(RNG.integers(1, 6)), int(RNG.integers(1, 6))
+    A, W = codes((M, K), q), codes((N, K), p)
+    expect = brute_bits(A, W, p, q)
+    assert np.array_equal(oracle.acc(A, W), expect)
+    assert np.array_equal(oracle.acc_bitplane(oracle.pack_planes(A, q), oracle.pack_planes(W, p)), expect)
+
+
+def test_two_bit_worked_identity():
+    # Sec. 3.4: w*x = OP(w,x^1)*2 + OP(w,x^0) for a 2-bit x; with 1-bit w, OP is AND.
+    for w in (0, 1):
+        for x in range(4):
+            x1, x0 = (x >> 1) & 1, x & 1
+            got = oracle.acc(np.array([[x]], dtype=np.uint8), np.array([[w]], dtype=np.uint8))[0, 0]
+            assert got == (w & x1) * 2 + (w & x0) == w * x
+
+
+# ---- P2: p = q = 8 is an ordinary integer matmul ------------------------------------------
+
+@pytest.mark.parametrize("M,N,K", [(1, 7, 64), (5, 33, 257), (16, 48, 1000)])
+def test_w8a8_equals_library_matmul(M, N, K):
+    A, W = codes((M, K), 8), codes((N, K), 8)
+    lib = A.astype(np.int64) @ W.astype(np.int64).T
+    assert np.array_equal(oracle.acc(A, W), lib)
+    assert np.array_equal(oracle.acc_bitplane(oracle.pack_planes(A, 8), oracle.pack_planes(W, 8)), lib)
+    ms = RNG.integers(0, M, size=50)
+    ns = RNG.integers(0, N, size=50)
+    assert np.array_equal(oracle.acc_sampled(A, W, ms, ns), lib[ms, ns])
+
+
+def test_operand_roles_not_transposed():
+    # acc is [M,N] with A indexed by m and W by n: a non-square, asymmetric case.
+    A = np.array([[1, 2, 3]], dtype=np.uint8)           # M=1
+    W = np.array([[1, 0, 0], [0, 1, 0], [0, 0, 1], [1, 1, 1]], dtype=np.uint8)  # N=4
+    assert oracle.acc(A, W).tolist() == [[1, 2, 3, 6]]
+
+
+# ---- P3: closed forms ---------------------------------------------------------------------
+
+@pytest.mark.parametrize("p,q", [(1, 1), (2, 8), (6, 6), (8, 8), (3, 7)])
+def test_closed_forms(p, q):
+    M, N, K = 3, 4, 517
+    amax, wmax = (1 << q) - 1, (1 << p) - 1
+    A = np.full((M, K), amax, dtype=np.uint8)
+    W = np.full((N, K), wmax, dtype=np.uint8)
+    assert (oracle.acc(A, W) == K * amax * wmax).all()
+    assert (oracle.acc_bitplane(oracle.pack_planes(A, q), oracle.pack_planes(W, p)) == K * amax * wmax).all()
+    Z = np.zeros_like(A)
+    Wr = codes((N, K), p)
+    assert (oracle.acc(Z, Wr) == 0).all()
+    # one-hot activation row picks out one weight column, scaled
+    k0, v = 123, amax
+    H = np.zeros((1, K), dtype=np.uint8)
+    H[0, k0] = v
+    assert np.array_equal(oracle.acc(H, Wr)[0], v * Wr[:, k0].astype(np.int64))
+
+
+# ---- P4: invariants -----------------------------------------------------------------------
+
+def test_plane_composition_and_padding_and_symmetry():
+    p, q, M, N, K = 5, 7, 4, 6, 200
+    A, W = codes((M, K), q), codes((N, K), p)
+    full = oracle.acc(A, W)
+    # (1,1) kernel composes every other: acc(p,q) = sum 2^(s+t) acc(1,1)(A_t, W_s)
+    comp = np.zeros_like(full)
+    for s in range(p):
+        for t in range(q):
+            comp += oracle.acc(((A >> t) & 1).astype(np.uint8), ((W >> s) & 1).astype(np.uint8)) << (s + t)
+    assert np.array_equal(comp, full)
+    # zero-padding K changes nothing
+    Ap = np.concatenate([A, np.zeros((M, 56), np.uint8)], axis=1)
+    Wp = np.concatenate([W, codes((N, 56), p)], axis=1)
+    assert np.array_equal(oracle.acc(Ap, Wp), full)
+    # row / column permutation equivariance
+    pm, pn, pk = RNG.permutation(M), RNG.permutation(N), RNG.permutation(K)
+    assert np.array_equal(oracle.acc(A[pm][:, pk], W[pn][:, pk]), full[pm][:, pn])
+    # transposition symmetry with the roles (and p,q) swapped
+    assert np.array_equal(oracle.acc(W, A), full.T)
+    # masking to the low p' bits == dropping the upper planes
+    pl = oracle.pack_planes(W, p)
+    assert np.array_equal(oracle.acc_bitplane(oracle.pack_planes(A, q), pl[:3]),
+                          oracle.acc(A, (W & 7).astype(np.uint8)))
+
+
+# ---- P5/P6/P7: zero points and dequant ----------------------------------------------------
+
+@pytest.mark.parametrize("p,q,M,N,K", [(2, 8, 1, 9, 512), (6, 6, 7, 5, 333), (8, 8, 3, 3, 1024), (1, 1, 2, 2, 65)])
+def test_centered_equals_four_term_expansion(p, q, M, N, K):
+    A, W = codes((M, K), q), codes((N, K), p)
+    az = RNG.integers(0, 1 << q, size=M).astype(np.int32)
+    wz = RNG.integers(0, 1 << p, size=N).astype(np.int32)
+    direct = oracle.acc_centered(A, W, az, wz)
+    A64, W64 = A.astype(np.int64), W.astype(np.int64)
+    raw = A64 @ W64.T
+    asum = A64.sum(axis=1)[:, None]
+    wsum = W64.sum(axis=1)[None, :]
+    expanded = raw - wz[None, :].astype(np.int64) * asum - az[:, None].astype(np.int64) * wsum \
+        + K * az[:, None].astype(np.int64) * wz[None, :].astype(np.int64)
+    assert np.array_equal(direct, expanded)
+    ms = RNG.integers(0, M, size=20)
+    ns = RNG.integers(0, N, size=20)
+    assert np.array_equal(oracle.acc_centered_sampled(A, W, az, wz, ms, ns), expanded[ms, ns])
+
+
+def test_unit_scales_zero_points_give_exact_half():
+    A, W = codes((2, 40), 3), codes((5, 40), 3)     # acc <= 40*49 = 1960 < 2048: exact in fp16
+    raw = oracle.acc(A, W)
+    accc = oracle.acc_centered(A, W, np.zeros(2, np.int32), np.zeros(5, np.int32))
+    assert np.array_equal(accc, raw)
+    y, y16 = oracle.dequant(accc, np.ones(2, np.float32), np.ones(5, np.float32))
+    assert np.array_equal(y, raw.astype(np.float64))
+    assert np.array_equal(y16.view(np.float16).astype(np.int64), raw)
+
+
+def test_dequant_equals_dequantise_then_multiply_longdouble():
+    c = synth.make_case(4, 8, 3, 17, 300, seed=77)
+    accc = oracle.acc_centered(c.A, c.W, c.a_zero, c.w_zero)
+    y, _ = oracle.dequant(accc, c.a_scale, c.w_scale)
+    ld = np.longdouble
+    Ar = c.a_scale.astype(ld)[:, None] * (c.A.astype(ld) - c.a_zero.astype(ld)[:, None])
+    Wr = c.w_scale.astype(ld)[:, None] * (c.W.astype(ld) - c.w_zero.astype(ld)[:, None])
+    ref = np.zeros((c.M, c.N), dtype=ld)
+    for k in range(c.K):
+        ref += Ar[:, k][:, None] * Wr[:, k][None, :]
+    scale = np.abs(Ar).astype(ld) @ np.abs(Wr).astype(ld).T
+    assert np.all(np.abs(y.astype(ld) - ref) <= 1e-12 * scale + 1e-300)
+
+
+def test_dequant_scale_roles_not_swapped():
+    accc = np.array([[1, 1], [1, 1], [1, 1]], dtype=np.int64)      # M=3, N=2
+    y, _ = oracle.dequant(accc, np.array([1, 2, 4], np.float32), np.array([8, 16], np.float32))
+    assert y.tolist() == [[8, 16], [16, 32], [32, 64]]
+
+
+# ---- P8: binary16 rounding against the library conversion ---------------------------------
+
+def test_half_rounding_matches_numpy():
+    probes = [0.0, -0.0, 1.0, -1.0, 65504.0, 65519.99, 65520.0, 70000.0, -65520.0, 1e-8, 2.0 ** -24,
+              2.0 ** -25, 2.0 ** -25 * 1.0000001, 3 * 2.0 ** -25, 2.0 ** -14, 2.0 ** -14 - 2.0 ** -25,
+              1.0 + 2.0 ** -11, 1.0 + 3 * 2.0 ** -11, 1.0 + 2.0 ** -11 + 1e-9, 2047.5, 2048.5, 2049.5, 0.1, 1 / 3,
+              float("inf"), float("-inf")]
+    vals = np.concatenate([
+        np.array(probes, dtype=np.float64),
+        RNG.normal(0, 1, 4000) * np.exp(RNG.uniform(-20, 12, 4000)),
+        # exact ties between neighbouring halves
+        (np.arange(1024, 1536) + 0.5) * 2.0 ** -10,
+    ])
+    with np.errstate(over="ignore"):
+        lib = vals.astype(np.float16).view(np.uint16)
+    mine = np.array([oracle.half_bits(v) for v in vals], dtype=np.uint16)
+    assert np.array_equal(mine, lib)
+    assert oracle.half_bits(float("nan")) & 0x7C00 == 0x7C00 and oracle.half_bits(float("nan")) & 0x3FF
+
+
+# ---- P9: packers --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("bits,R,K", [(1, 3, 1), (2, 4, 33), (5, 2, 100), (8, 3, 256), (7, 1, 1000)])
+def test_pack_unpack_planes(bits, R, K):
+    c = codes((R, K), bits)
+    pl = oracle.pack_planes(c, bits)
+    assert pl.shape == (bits, R, (K + 31) // 32)
+    assert np.array_equal(oracle.unpack_planes(pl, K), c)
+    # popcount of plane s over a row = number of codes with bit s set; bit order k%32 LSB-first
+    for s in range(bits):
+        for r in range(R):
+            row_bits = np.unpackbits(pl[s, r].view(np.uint8), bitorder="little")
+            assert np.array_equal(row_bits[:K], (c[r] >> s) & 1)
+            assert row_bits[K:].sum() == 0
+    # wider row stride keeps the same bits
+    pl2 = oracle.pack_planes(c, bits, Kw=(K + 31) // 32 + 3)
+    assert np.array_equal(pl2[:, :, :pl.shape[2]], pl) and pl2[:, :, pl.shape[2]:].sum() == 0
+
+
+# ---- activation quantizer: invariants only (parity unpinned by the paper) -----------------
+
+@pytest.mark.parametrize("q", [1, 2, 4, 6, 8])
+def test_quant_act_invariants(q):
+    x = synth.act_fp16(1234 + q, 6, 300)
+    x[4] = 0                      # degenerate row
+    x[5] = np.abs(x[5])           # one-sided row: lo = 0
+    cd, sc, zp = oracle.quant_act(x, q)
+    qmax = (1 << q) - 1
+    assert cd.max() <= qmax and zp.min() >= 0 and zp.max() <= qmax
+    assert sc[4] == 1.0 and zp[4] == 0 and (cd[4] == 0).all()
+    assert zp[5] == 0
+    xf = x.astype(np.float64)
+    recon = sc.astype(np.float64)[:, None] * (cd.astype(np.float64) - zp[:, None])
+    # inside the representable range the error is at most half a step (plus fp32 slack);
+    # the zero-point rounding can clip up to half a step more at the two ends
+    lo = np.minimum(xf.min(axis=1), 0)
+    hi = np.maximum(xf.max(axis=1), 0)
+    step = sc.astype(np.float64)[:, None]
+    assert np.all(np.abs(recon - xf) <= step * (1.0 + 1e-3))
+    inner = (xf > (lo[:, None] + step)) & (xf < (hi[:, None] - step))
+    assert np.all(np.abs(recon - xf)[inner] <= step.repeat(x.shape[1], 1)[inner] * (0.5 + 1e-3))
+    # a row that already lies on a grid round-trips exactly
+    grid = (np.arange(300) % (qmax + 1)).astype(np.float16).reshape(1, -1)
+    cg, sg, zg = oracle.quant_act(grid, q)
+    assert sg[0] == 1.0 and zg[0] == 0 and np.array_equal(cg[0], grid[0].astype(np.uint8))
+    # monotone: larger x never gets a smaller code
+    order = np.argsort(xf[0], kind="stable")
+    assert np.all(np.diff(cd[0][order].astype(np.int32)) >= 0)
+
+
+# ---- the metric itself, against the values the paper prints -------------------------------
+
+def test_tops_definition_matches_table4():
+    path = os.path.join(os.path.dirname(__file__), "golden", "table4_latency_tops.txt")
+    rows = [l.split() for l in open(path) if l.strip() and not l.startswith("#")]
+    assert len(rows) == 5
+    for M, N, K, us, tops in rows:
+        got = metrics.effective_tops(int(M), int(N), int(K), float(us) * 1e-6)
+        assert abs(got - float(tops)) <= 0.015, (us, got, tops)
+    assert metrics.packed_weight_stream_bytes(4, 4096, 4096) == 8 * 1024 * 1024
+    assert metrics.packed_weight_stream_bytes(2, 4096, 11008) == 11272192
+
+
+# ---- generator sanity (ranges, determinism) -----------------------------------------------
+
+def test_synth_cases():
+    c = synth.config1()
+    assert (c.p, c.q, c.M, c.N, c.K) == (2, 8, 1, 256, 512)
+    assert c.W.max() <= 3 and c.A.dtype == np.uint8 and c.w_zero.max() <= 3
+    assert np.array_equal(c.w_scale, c.w_scale.astype(np.float16).astype(np.float32))
+    c2 = synth.config1()
+    assert np.array_equal(c.W, c2.W) and np.array_equal(c.a_scale, c2.a_scale)
+    g = synth.make_case(2, 8, 2, 8, 2048, seed=5, act="gauss")
+    assert (g.a_zero == 128).all() and 100 < g.A.mean() < 156
+    y, _ = oracle.dequant(oracle.acc_centered(c.A, c.W, c.a_zero, c.w_zero), c.a_scale, c.w_scale)
+    assert np.abs(y).max() < 410
