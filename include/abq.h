@@ -1,0 +1,147 @@
+/*
+ * abq.h — C ABI of the MI355X (gfx950) arbitrary-precision quantized matmul
+ *
+ *      Y = dequant( A_q · W_pᵀ ),   p = weight bits, q = activation bits, both in 1..8
+ *
+ * after ABQ-LLM (arXiv 2408.08554), Sec. 3.4 "Custom Software Engine" and Appendix B
+ * "Arbitrary Bit Matrix Calculation".  The integer accumulator is the paper's
+ * Y = sum_{s<p} sum_{t<q} 2^(s+t) · BMMA(W^s, X^t)  with  w^s = (w >> s) & 1  (Appendix B),
+ * i.e. exactly sum_k A[m,k]·W[n,k] over the unsigned codes; the epilogue applies the affine
+ * quantizer of Eq. 3 backwards (value = Delta·(code − z); per output channel for weights,
+ * per token for activations, Sec. 4.1).
+ *
+ * Conventions
+ *  - Plain C, every call returns an int status (ABQ_OK or a negative ABQ_ERR_*), nothing is
+ *    printed, no exception crosses the boundary.
+ *  - Every data pointer is a DEVICE pointer (caller-owned; the library never allocates or
+ *    frees device memory) and must be 16-byte aligned.  Sizes come from the *_bytes queries.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
+ *    enqueued asynchronously on it; no call synchronises unless its comment says so.
+ *  - Argument validation happens before the first HIP call, so the error paths can be
+ *    exercised on a host without a GPU.
+ *  - Shapes: A is [M,K] row-major, W is [N,K] row-major (K contiguous on both), Y is [M,N]
+ *    row-major.  Any M,N >= 1; 1 <= K <= ABQ_MAX_K and K·(2^p−1)·(2^q−1) <= INT32_MAX
+ *    (the paper's "32-bit output"); K need not be a multiple of anything (packers pad with
+ *    zero bits, which add nothing to any popcount).
+ *  - Same inputs give bit-identical outputs from run to run.
+ *
+ * Packed operands are opaque blobs whose internal order is private to the kernels.  `layout`
+ * says which representations a blob carries and must be the same value at pack time and at
+ * every later call that reads the blob:
+ *    ABQ_LAYOUT_PLANES  the paper's BitPacking (Sec. 3.4 step 1): [bits][rows][K] 1-bit planes;
+ *                       consumed by the AND+popcount bit-serial kernels.
+ *    ABQ_LAYOUT_FIELDS  bit-planes kept interleaved in groups of 1/2/4/8 planes (weights) or
+ *                       as whole int8 codes (activations), tiled for the int8 MFMA kernels.
+ *    ABQ_LAYOUT_BOTH    both of the above.
+ *    ABQ_LAYOUT_AUTO    the library's default (currently FIELDS).
+ */
+#ifndef ABQ_H
+#define ABQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ABQ_OK            0
+#define ABQ_ERR_NULL     (-1)  /* a required pointer is NULL */
+#define ABQ_ERR_BITS     (-2)  /* p or q outside 1..8 */
+#define ABQ_ERR_SHAPE    (-3)  /* M,N,K <= 0, K > ABQ_MAX_K, or K·(2^p−1)(2^q−1) > INT32_MAX */
+#define ABQ_ERR_ALIGN    (-4)  /* a device pointer is not 16-byte aligned */
+#define ABQ_ERR_SIZE     (-5)  /* a caller buffer is smaller than its size query */
+#define ABQ_ERR_LAYOUT   (-6)  /* unknown layout value, or the blob lacks what the call needs */
+#define ABQ_ERR_HIP      (-7)  /* a HIP call failed; see abq_last_hip_error() */
+
+#define ABQ_LAYOUT_AUTO    0
+#define ABQ_LAYOUT_PLANES  1
+#define ABQ_LAYOUT_FIELDS  2
+#define ABQ_LAYOUT_BOTH    3
+/* abq_gemm only: OR one of these onto a BOTH layout to force a kernel family (A/B timing). */
+#define ABQ_USE_PLANES     0x10
+#define ABQ_USE_FIELDS     0x20
+
+#define ABQ_MAX_K          131072
+
+int         abq_version(void);                 /* major*10000 + minor*100 + patch */
+const char* abq_status_string(int status);     /* static string, never NULL */
+int         abq_last_hip_error(void);          /* hipError_t of the last failing HIP call on this thread */
+
+/* ------------------------------------------------------------------------------------------
+ * Weights, offline (Sec. 3.4 step 1 "BitPacking"; "weight BitPacking is implemented offline").
+ * ------------------------------------------------------------------------------------------ */
+
+/* Bytes of the packed-weight blob; 0 on invalid arguments. */
+size_t abq_packed_weight_bytes(int p, int N, int K, int layout);
+
+/* Packs p-bit weight codes.  Also stores per-channel sum_k W[n,k] (needed by the zero-point
+ * correction), w_scale and w_zero inside the blob.
+ *   w_codes  [N,K] uint8, values < 2^p (higher bits are ignored)
+ *   w_scale  [N] float, Delta_w per output channel
+ *   w_zero   [N] int32, integer zero-point in 0..2^p−1
+ *   packed_out / packed_bytes: caller buffer of at least abq_packed_weight_bytes(...) bytes;
+ *   fully overwritten.  Inputs are not modified. */
+int abq_pack_weights(int p, int N, int K,
+                     const uint8_t* w_codes, const float* w_scale, const int32_t* w_zero,
+                     int layout, void* packed_out, size_t packed_bytes, void* stream);
+
+/* Test hook: recovers the codes from a blob.  `which` is ABQ_LAYOUT_PLANES or ABQ_LAYOUT_FIELDS
+ * and selects the representation to decode (it must be present in the blob).
+ *   w_codes_out [N,K] uint8. */
+int abq_unpack_weights(int p, int N, int K, int layout, const void* packed, int which,
+                       uint8_t* w_codes_out, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Activations, online (Fig. 3b "ReQuant" + "BitPacking": [M,K,q] -> [q,M,K]).
+ * ------------------------------------------------------------------------------------------ */
+
+size_t abq_packed_act_bytes(int q, int M, int K, int layout);
+
+/* Per-token quantize + pack.  For each row m (all float steps in IEEE binary32):
+ *   lo = min(min_k x, 0), hi = max(max_k x, 0), Delta = (hi−lo)/(2^q−1)  (Delta=1, z=0 if hi==lo)
+ *   z = clamp(rint(−lo/Delta), 0, 2^q−1),  code = clamp(rint(x/Delta) + z, 0, 2^q−1)
+ * (the clamp(round(x/Delta)+z) form of Eq. 3; the paper fixes only "per-token").  Stores the
+ * codes, Delta, z and sum_k code inside the blob.  NaN/Inf inputs: undefined.
+ *   x_fp16 [M,K] IEEE binary16 bit patterns. */
+int abq_quant_pack_act(int q, int M, int K, const uint16_t* x_fp16,
+                       int layout, void* packed_out, size_t packed_bytes, void* stream);
+
+/* Packs activation codes that are already quantized.
+ *   a_codes [M,K] uint8 (< 2^q; higher bits ignored), a_scale [M] float, a_zero [M] int32. */
+int abq_pack_act_codes(int q, int M, int K,
+                       const uint8_t* a_codes, const float* a_scale, const int32_t* a_zero,
+                       int layout, void* packed_out, size_t packed_bytes, void* stream);
+
+/* Test hook: decodes an activation blob.  Any output pointer may be NULL.
+ *   a_codes_out [M,K] uint8, a_scale_out [M] float, a_zero_out [M] int32, a_sum_out [M] int32. */
+int abq_unpack_act(int q, int M, int K, int layout, const void* packed, int which,
+                   uint8_t* a_codes_out, float* a_scale_out, int32_t* a_zero_out,
+                   int32_t* a_sum_out, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Matmul + bit reduction + fused dequant (Sec. 3.4 steps 2–6, Appendix B, Fig. 3b "DeQuant").
+ * ------------------------------------------------------------------------------------------ */
+
+/* Scratch bytes abq_gemm needs for this problem (may be 0). */
+size_t abq_gemm_workspace_bytes(int p, int q, int M, int N, int K);
+
+/* acc[m,n]  = sum_k A[m,k]·W[n,k]                                  (exact, int32)
+ * acc'[m,n] = acc − wz[n]·sum_k A[m,k] − az[m]·sum_k W[n,k] + K·az[m]·wz[n]   (exact, int32)
+ * Y[m,n]    = half_rne( float(acc') · a_scale[m] · w_scale[n] )
+ *   packed_act, packed_w: blobs written by the pack calls above with the same q,M,K / p,N,K
+ *   a_layout, w_layout: the layout value each blob was packed with; w_layout may carry an
+ *                 ABQ_USE_* flag.  The kernel family is chosen from what both blobs carry.
+ *   y_fp16    [M,N] binary16 bit patterns, required, fully overwritten
+ *   acc_i32   [M,N] raw acc, optional (NULL to skip)
+ *   workspace at least abq_gemm_workspace_bytes(...) bytes (may be NULL when that is 0);
+ *             contents on entry are irrelevant, contents on return are unspecified. */
+int abq_gemm(int p, int q, int M, int N, int K,
+             const void* packed_act, int a_layout, const void* packed_w, int w_layout,
+             uint16_t* y_fp16, int32_t* acc_i32,
+             void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ABQ_H */

@@ -1,0 +1,178 @@
+"""ctypes binding of libabq.so — the same names as include/abq.h, argument marshalling only.
+
+torch is used for device memory (tensors own every buffer) and for the current stream; every
+step of the path runs in the library's HIP kernels.  A missing library is an error: there is
+no fallback of any kind.
+"""
+import ctypes
+import os
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libabq.so")
+
+ABQ_OK = 0
+ABQ_ERR_NULL, ABQ_ERR_BITS, ABQ_ERR_SHAPE, ABQ_ERR_ALIGN = -1, -2, -3, -4
+ABQ_ERR_SIZE, ABQ_ERR_LAYOUT, ABQ_ERR_HIP = -5, -6, -7
+ABQ_LAYOUT_AUTO, ABQ_LAYOUT_PLANES, ABQ_LAYOUT_FIELDS, ABQ_LAYOUT_BOTH = 0, 1, 2, 3
+ABQ_USE_PLANES, ABQ_USE_FIELDS = 0x10, 0x20
+ABQ_MAX_K = 131072
+
+# every symbol include/abq.h declares: (restype, argtypes)
+_c = ctypes
+_SIGNATURES = {
+    "abq_version": (_c.c_int, []),
+    "abq_status_string": (_c.c_char_p, [_c.c_int]),
+    "abq_last_hip_error": (_c.c_int, []),
+    "abq_packed_weight_bytes": (_c.c_size_t, [_c.c_int] * 4),
+    "abq_pack_weights": (_c.c_int, [_c.c_int] * 3 + [_c.c_void_p] * 3 + [_c.c_int, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
+    "abq_unpack_weights": (_c.c_int, [_c.c_int] * 4 + [_c.c_void_p, _c.c_int, _c.c_void_p, _c.c_void_p]),
+    "abq_packed_act_bytes": (_c.c_size_t, [_c.c_int] * 4),
+    "abq_quant_pack_act": (_c.c_int, [_c.c_int] * 3 + [_c.c_void_p, _c.c_int, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
+    "abq_pack_act_codes": (_c.c_int, [_c.c_int] * 3 + [_c.c_void_p] * 3 + [_c.c_int, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
+    "abq_unpack_act": (_c.c_int, [_c.c_int] * 4 + [_c.c_void_p, _c.c_int] + [_c.c_void_p] * 5),
+    "abq_gemm_workspace_bytes": (_c.c_size_t, [_c.c_int] * 5),
+    "abq_gemm": (_c.c_int, [_c.c_int] * 5 + [_c.c_void_p, _c.c_int, _c.c_void_p, _c.c_int, _c.c_void_p, _c.c_void_p,
+                                             _c.c_void_p, _c.c_size_t, _c.c_void_p]),
+}
+
+_lib = None
+
+
+class AbqError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        msg = _lib.abq_status_string(status).decode() if _lib is not None else "?"
+        extra = f" (hipError {_lib.abq_last_hip_error()})" if status == ABQ_ERR_HIP and _lib is not None else ""
+        super().__init__(f"{where}: {msg} [{status}]{extra}")
+
+
+def load():
+    """Load libabq.so (built by paper_2408_08554_amd.build); raises if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2408_08554_amd.build` "
+                               "(there is no fallback path)")
+        lib = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(lib, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = lib
+    return _lib
+
+
+def raw():
+    """The ctypes library object, for tests that exercise the error paths directly."""
+    return load()
+
+
+def _check(status, where):
+    if status != ABQ_OK:
+        raise AbqError(status, where)
+
+
+def _ptr(t):
+    return 0 if t is None else t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dev(t, dtype, shape=None):
+    assert t.is_cuda and t.is_contiguous() and t.dtype == dtype, (t.device, t.dtype, t.is_contiguous())
+    if shape is not None:
+        assert tuple(t.shape) == tuple(shape), (tuple(t.shape), shape)
+    return t
+
+
+def abq_version():
+    return load().abq_version()
+
+
+def abq_packed_weight_bytes(p, N, K, layout=ABQ_LAYOUT_AUTO):
+    return load().abq_packed_weight_bytes(p, N, K, layout)
+
+
+def abq_packed_act_bytes(q, M, K, layout=ABQ_LAYOUT_AUTO):
+    return load().abq_packed_act_bytes(q, M, K, layout)
+
+
+def abq_gemm_workspace_bytes(p, q, M, N, K):
+    return load().abq_gemm_workspace_bytes(p, q, M, N, K)
+
+
+def abq_pack_weights(p, w_codes, w_scale, w_zero, layout=ABQ_LAYOUT_AUTO, out=None):
+    """w_codes uint8 [N,K], w_scale float32 [N], w_zero int32 [N] (device) -> packed uint8 blob."""
+    lib = load()
+    N, K = w_codes.shape
+    _dev(w_codes, torch.uint8), _dev(w_scale, torch.float32, (N,)), _dev(w_zero, torch.int32, (N,))
+    nbytes = lib.abq_packed_weight_bytes(p, N, K, layout)
+    if out is None:
+        out = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=w_codes.device)
+    _check(lib.abq_pack_weights(p, N, K, _ptr(w_codes), _ptr(w_scale), _ptr(w_zero), layout, _ptr(out), out.numel(),
+                                _stream()), "abq_pack_weights")
+    return out
+
+
+def abq_unpack_weights(p, N, K, layout, packed, which):
+    lib = load()
+    out = torch.empty((N, K), dtype=torch.uint8, device=packed.device)
+    _check(lib.abq_unpack_weights(p, N, K, layout, _ptr(packed), which, _ptr(out), _stream()), "abq_unpack_weights")
+    return out
+
+
+def abq_quant_pack_act(q, x_fp16, layout=ABQ_LAYOUT_AUTO, out=None):
+    """x_fp16 float16 [M,K] (device) -> packed activation blob."""
+    lib = load()
+    M, K = x_fp16.shape
+    _dev(x_fp16, torch.float16)
+    nbytes = lib.abq_packed_act_bytes(q, M, K, layout)
+    if out is None:
+        out = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=x_fp16.device)
+    _check(lib.abq_quant_pack_act(q, M, K, _ptr(x_fp16), layout, _ptr(out), out.numel(), _stream()), "abq_quant_pack_act")
+    return out
+
+
+def abq_pack_act_codes(q, a_codes, a_scale, a_zero, layout=ABQ_LAYOUT_AUTO, out=None):
+    lib = load()
+    M, K = a_codes.shape
+    _dev(a_codes, torch.uint8), _dev(a_scale, torch.float32, (M,)), _dev(a_zero, torch.int32, (M,))
+    nbytes = lib.abq_packed_act_bytes(q, M, K, layout)
+    if out is None:
+        out = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=a_codes.device)
+    _check(lib.abq_pack_act_codes(q, M, K, _ptr(a_codes), _ptr(a_scale), _ptr(a_zero), layout, _ptr(out), out.numel(),
+                                  _stream()), "abq_pack_act_codes")
+    return out
+
+
+def abq_unpack_act(q, M, K, layout, packed, which):
+    """-> (codes uint8 [M,K], scale float32 [M], zero int32 [M], sum int32 [M])."""
+    lib = load()
+    dev = packed.device
+    codes = torch.empty((M, K), dtype=torch.uint8, device=dev)
+    scale = torch.empty(M, dtype=torch.float32, device=dev)
+    zero = torch.empty(M, dtype=torch.int32, device=dev)
+    asum = torch.empty(M, dtype=torch.int32, device=dev)
+    _check(lib.abq_unpack_act(q, M, K, layout, _ptr(packed), which, _ptr(codes), _ptr(scale), _ptr(zero), _ptr(asum),
+                              _stream()), "abq_unpack_act")
+    return codes, scale, zero, asum
+
+
+def abq_gemm(p, q, M, N, K, packed_act, a_layout, packed_w, w_layout, y=None, acc=None, want_acc=False, workspace=None):
+    """-> (y float16 [M,N], acc int32 [M,N] or None).  Buffers are allocated when not given."""
+    lib = load()
+    dev = packed_w.device
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.float16, device=dev)
+    if acc is None and want_acc:
+        acc = torch.empty((M, N), dtype=torch.int32, device=dev)
+    need = lib.abq_gemm_workspace_bytes(p, q, M, N, K)
+    if need and workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    _check(lib.abq_gemm(p, q, M, N, K, _ptr(packed_act), a_layout, _ptr(packed_w), w_layout, _ptr(y), _ptr(acc),
+                        _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream()), "abq_gemm")
+    return y, acc

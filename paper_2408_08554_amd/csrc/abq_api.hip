@@ -1,0 +1,247 @@
+// Host side of the C ABI (include/abq.h): argument validation, blob layouts, dispatch.
+// No device code here; validation runs before the first HIP call so that every error path
+// can be exercised on a machine without a GPU.
+#include "abq_internal.h"
+#include "../../include/abq.h"
+
+#include <limits.h>
+
+namespace abq {
+
+static thread_local int g_last_hip_error = 0;
+
+static int hip_status(hipError_t e)
+{
+    if (e == hipSuccess) return ABQ_OK;
+    g_last_hip_error = (int)e;
+    return ABQ_ERR_HIP;
+}
+
+static bool layout_bits(int layout, bool* planes, bool* fields)
+{
+    switch (layout) {
+        case ABQ_LAYOUT_AUTO:
+        case ABQ_LAYOUT_FIELDS: *planes = false; *fields = true; return true;
+        case ABQ_LAYOUT_PLANES: *planes = true; *fields = false; return true;
+        case ABQ_LAYOUT_BOTH: *planes = true; *fields = true; return true;
+        default: return false;
+    }
+}
+
+bool make_weight_layout(int p, int N, int K, int layout, WeightLayout* L)
+{
+    if (p < 1 || p > 8 || N < 1 || K < 1 || K > ABQ_MAX_K) return false;
+    if (!layout_bits(layout, &L->has_planes, &L->has_fields)) return false;
+    L->p = p; L->N = N; L->K = K; L->layout = layout;
+    L->NT = (N + kTileN - 1) / kTileN;
+    L->Kw = (K + 127) / 128 * 4;
+    L->ngroups = group_count(p);
+    size_t off = kHeaderBytes;
+    L->off_params = off;
+    off = align_up(off + (size_t)N * sizeof(RowParams), 256);
+    L->off_planes = 0;
+    if (L->has_planes) {
+        L->off_planes = off;
+        off = align_up(off + (size_t)p * N * L->Kw * 4, 256);
+    }
+    for (int g = 0; g < 3; ++g) { L->gb[g] = 0; L->gs[g] = 0; L->chunks[g] = 0; L->off_fields[g] = 0; }
+    if (L->has_fields) {
+        for (int g = 0; g < L->ngroups; ++g) {
+            L->gb[g] = group_width(p, g);
+            L->gs[g] = group_shift(p, g);
+            L->chunks[g] = (int)(((size_t)K * L->gb[g] + kSuperK - 1) / kSuperK);
+            L->off_fields[g] = off;
+            off = align_up(off + (size_t)L->NT * L->chunks[g] * 1024, 256);
+        }
+    }
+    L->total = off;
+    return true;
+}
+
+bool make_act_layout(int q, int M, int K, int layout, ActLayout* L)
+{
+    if (q < 1 || q > 8 || M < 1 || K < 1 || K > ABQ_MAX_K) return false;
+    if (!layout_bits(layout, &L->has_planes, &L->has_fields)) return false;
+    L->q = q; L->M = M; L->K = K; L->layout = layout;
+    L->Kp = (K + kSuperK - 1) / kSuperK * kSuperK;
+    L->Kw = (K + 127) / 128 * 4;
+    size_t off = kHeaderBytes;
+    L->off_params = off;
+    off = align_up(off + (size_t)M * sizeof(RowParams), 256);
+    L->off_planes = 0;
+    L->off_codes = 0;
+    if (L->has_planes) {
+        L->off_planes = off;
+        off = align_up(off + (size_t)q * M * L->Kw * 4, 256);
+    }
+    if (L->has_fields) {
+        L->off_codes = off;
+        off = align_up(off + (size_t)M * L->Kp, 256);
+    }
+    L->total = off;
+    return true;
+}
+
+static bool misaligned(const void* p) { return ((uintptr_t)p & 15u) != 0; }
+
+static int check_bits_shape(int bits, int R, int K)
+{
+    if (bits < 1 || bits > 8) return ABQ_ERR_BITS;
+    if (R < 1 || K < 1 || K > ABQ_MAX_K) return ABQ_ERR_SHAPE;
+    return ABQ_OK;
+}
+
+}  // namespace abq
+
+using namespace abq;
+
+extern "C" {
+
+int abq_version(void) { return 100; }
+
+const char* abq_status_string(int status)
+{
+    switch (status) {
+        case ABQ_OK: return "ok";
+        case ABQ_ERR_NULL: return "a required pointer is NULL";
+        case ABQ_ERR_BITS: return "bit width outside 1..8";
+        case ABQ_ERR_SHAPE: return "invalid shape (M,N,K must be >= 1, K <= ABQ_MAX_K, K*(2^p-1)*(2^q-1) <= INT32_MAX)";
+        case ABQ_ERR_ALIGN: return "device pointer not 16-byte aligned";
+        case ABQ_ERR_SIZE: return "caller buffer smaller than its size query";
+        case ABQ_ERR_LAYOUT: return "unknown layout or the blob lacks the representation this call needs";
+        case ABQ_ERR_HIP: return "a HIP call failed (see abq_last_hip_error)";
+        default: return "unknown status";
+    }
+}
+
+int abq_last_hip_error(void) { return g_last_hip_error; }
+
+size_t abq_packed_weight_bytes(int p, int N, int K, int layout)
+{
+    WeightLayout L;
+    return make_weight_layout(p, N, K, layout, &L) ? L.total : 0;
+}
+
+size_t abq_packed_act_bytes(int q, int M, int K, int layout)
+{
+    ActLayout L;
+    return make_act_layout(q, M, K, layout, &L) ? L.total : 0;
+}
+
+int abq_pack_weights(int p, int N, int K, const uint8_t* w_codes, const float* w_scale, const int32_t* w_zero,
+                     int layout, void* packed_out, size_t packed_bytes, void* stream)
+{
+    if (!w_codes || !w_scale || !w_zero || !packed_out) return ABQ_ERR_NULL;
+    if (int e = check_bits_shape(p, N, K)) return e;
+    WeightLayout L;
+    if (!make_weight_layout(p, N, K, layout, &L)) return ABQ_ERR_LAYOUT;
+    if (misaligned(w_codes) || misaligned(w_scale) || misaligned(w_zero) || misaligned(packed_out)) return ABQ_ERR_ALIGN;
+    if (packed_bytes < L.total) return ABQ_ERR_SIZE;
+    return hip_status(launch_pack_weights(L, w_codes, w_scale, w_zero, (uint8_t*)packed_out, (hipStream_t)stream));
+}
+
+int abq_unpack_weights(int p, int N, int K, int layout, const void* packed, int which, uint8_t* w_codes_out, void* stream)
+{
+    if (!packed || !w_codes_out) return ABQ_ERR_NULL;
+    if (int e = check_bits_shape(p, N, K)) return e;
+    WeightLayout L;
+    if (!make_weight_layout(p, N, K, layout, &L)) return ABQ_ERR_LAYOUT;
+    if (!((which == ABQ_LAYOUT_PLANES && L.has_planes) || (which == ABQ_LAYOUT_FIELDS && L.has_fields))) return ABQ_ERR_LAYOUT;
+    if (misaligned(packed) || misaligned(w_codes_out)) return ABQ_ERR_ALIGN;
+    return hip_status(launch_unpack_weights(L, (const uint8_t*)packed, which, w_codes_out, (hipStream_t)stream));
+}
+
+int abq_quant_pack_act(int q, int M, int K, const uint16_t* x_fp16, int layout, void* packed_out, size_t packed_bytes,
+                       void* stream)
+{
+    if (!x_fp16 || !packed_out) return ABQ_ERR_NULL;
+    if (int e = check_bits_shape(q, M, K)) return e;
+    ActLayout L;
+    if (!make_act_layout(q, M, K, layout, &L)) return ABQ_ERR_LAYOUT;
+    if (misaligned(x_fp16) || misaligned(packed_out)) return ABQ_ERR_ALIGN;
+    if (packed_bytes < L.total) return ABQ_ERR_SIZE;
+    return hip_status(launch_quant_pack_act(L, x_fp16, (uint8_t*)packed_out, (hipStream_t)stream));
+}
+
+int abq_pack_act_codes(int q, int M, int K, const uint8_t* a_codes, const float* a_scale, const int32_t* a_zero,
+                       int layout, void* packed_out, size_t packed_bytes, void* stream)
+{
+    if (!a_codes || !a_scale || !a_zero || !packed_out) return ABQ_ERR_NULL;
+    if (int e = check_bits_shape(q, M, K)) return e;
+    ActLayout L;
+    if (!make_act_layout(q, M, K, layout, &L)) return ABQ_ERR_LAYOUT;
+    if (misaligned(a_codes) || misaligned(a_scale) || misaligned(a_zero) || misaligned(packed_out)) return ABQ_ERR_ALIGN;
+    if (packed_bytes < L.total) return ABQ_ERR_SIZE;
+    return hip_status(launch_pack_act_codes(L, a_codes, a_scale, a_zero, (uint8_t*)packed_out, (hipStream_t)stream));
+}
+
+int abq_unpack_act(int q, int M, int K, int layout, const void* packed, int which, uint8_t* a_codes_out,
+                   float* a_scale_out, int32_t* a_zero_out, int32_t* a_sum_out, void* stream)
+{
+    if (!packed) return ABQ_ERR_NULL;
+    if (int e = check_bits_shape(q, M, K)) return e;
+    ActLayout L;
+    if (!make_act_layout(q, M, K, layout, &L)) return ABQ_ERR_LAYOUT;
+    if (a_codes_out && !((which == ABQ_LAYOUT_PLANES && L.has_planes) || (which == ABQ_LAYOUT_FIELDS && L.has_fields)))
+        return ABQ_ERR_LAYOUT;
+    if (misaligned(packed) || misaligned(a_codes_out) || misaligned(a_scale_out) || misaligned(a_zero_out) ||
+        misaligned(a_sum_out))
+        return ABQ_ERR_ALIGN;
+    return hip_status(launch_unpack_act(L, (const uint8_t*)packed, which, a_codes_out, a_scale_out, a_zero_out,
+                                        a_sum_out, (hipStream_t)stream));
+}
+
+static int check_gemm_shape(int p, int q, int M, int N, int K)
+{
+    if (p < 1 || p > 8 || q < 1 || q > 8) return ABQ_ERR_BITS;
+    if (M < 1 || N < 1 || K < 1 || K > ABQ_MAX_K) return ABQ_ERR_SHAPE;
+    const int64_t bound = (int64_t)K * ((1 << p) - 1) * ((1 << q) - 1);
+    if (bound > (int64_t)INT32_MAX) return ABQ_ERR_SHAPE;
+    return ABQ_OK;
+}
+
+// Kernel family for a problem: true = int8-MFMA on field-packed operands, false = bit-serial.
+static bool choose_fields(bool can_fields, bool can_planes, int force)
+{
+    (void)can_planes;
+    if (force == ABQ_USE_PLANES) return false;
+    if (force == ABQ_USE_FIELDS) return true;
+    return can_fields;   // measured: the MFMA path is never slower on gfx950 (see profiles/)
+}
+
+static const int kSkinnyMaxM = 64;
+
+size_t abq_gemm_workspace_bytes(int p, int q, int M, int N, int K)
+{
+    if (check_gemm_shape(p, q, M, N, K) != ABQ_OK) return 0;
+    if (M <= kSkinnyMaxM) return 0;
+    return gemm_tiled_workspace_bytes(p, q, M, N, K);
+}
+
+int abq_gemm(int p, int q, int M, int N, int K, const void* packed_act, int a_layout, const void* packed_w,
+             int w_layout, uint16_t* y_fp16, int32_t* acc_i32, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!packed_act || !packed_w || !y_fp16) return ABQ_ERR_NULL;
+    if (int e = check_gemm_shape(p, q, M, N, K)) return e;
+    const int force = w_layout & (ABQ_USE_PLANES | ABQ_USE_FIELDS);
+    w_layout &= ~(ABQ_USE_PLANES | ABQ_USE_FIELDS);
+    if (force == (ABQ_USE_PLANES | ABQ_USE_FIELDS)) return ABQ_ERR_LAYOUT;
+    ActLayout A;
+    WeightLayout W;
+    if (!make_act_layout(q, M, K, a_layout, &A) || !make_weight_layout(p, N, K, w_layout, &W)) return ABQ_ERR_LAYOUT;
+    const bool can_fields = A.has_fields && W.has_fields, can_planes = A.has_planes && W.has_planes;
+    if (!can_fields && !can_planes) return ABQ_ERR_LAYOUT;
+    if ((force == ABQ_USE_PLANES && !can_planes) || (force == ABQ_USE_FIELDS && !can_fields)) return ABQ_ERR_LAYOUT;
+    if (misaligned(packed_act) || misaligned(packed_w) || misaligned(y_fp16) || misaligned(acc_i32) || misaligned(workspace))
+        return ABQ_ERR_ALIGN;
+    const size_t need = abq_gemm_workspace_bytes(p, q, M, N, K);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return workspace ? ABQ_ERR_SIZE : ABQ_ERR_NULL;
+
+    GemmArgs g{p, q, M, N, K, (const uint8_t*)packed_act, (const uint8_t*)packed_w, y_fp16, acc_i32, workspace, workspace_bytes};
+    hipStream_t s = (hipStream_t)stream;
+    if (!choose_fields(can_fields, can_planes, force)) return hip_status(launch_gemm_bitserial(g, A, W, s));
+    if (M <= kSkinnyMaxM) return hip_status(launch_gemm_skinny(g, A, W, s));
+    return hip_status(launch_gemm_tiled(g, A, W, s));
+}
+
+}  // extern "C"

@@ -1,0 +1,107 @@
+// Internal declarations shared by the HIP translation units of libabq (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace abq {
+
+// ---- plane groups ---------------------------------------------------------------------------
+// A p-bit weight is stored as 1..3 "plane groups": runs of 4, 2 or 1 adjacent bit-planes
+// (8 planes when p == 8) kept interleaved per element, lowest planes first:
+//   p : 1:(1)  2:(2)  3:(2,1)  4:(4)  5:(4,1)  6:(4,2)  7:(4,2,1)  8:(8)
+// w = sum_g field_g << shift_g is the bit-plane sum of Appendix B with the inner sum over the
+// planes of one group already carried out by the storage format.
+__host__ __device__ constexpr int group_count(int p) { return (p == 7) ? 3 : ((p == 3 || p == 5 || p == 6) ? 2 : 1); }
+__host__ __device__ constexpr int group_width(int p, int g)
+{
+    return p == 8 ? 8
+         : p >= 4 ? (g == 0 ? 4 : (p == 5 ? 1 : (p == 6 ? 2 : (g == 1 ? 2 : 1))))   // 4 | 4,1 | 4,2 | 4,2,1
+         : p == 3 ? (g == 0 ? 2 : 1)
+         : p;                                                                      // 1 or 2
+}
+__host__ __device__ constexpr int group_shift(int p, int g)
+{
+    return g == 0 ? 0 : (g == 1 ? group_width(p, 0) : group_width(p, 0) + group_width(p, 1));
+}
+
+constexpr int kTileN = 16;        // rows of W per MFMA tile
+constexpr int kSuperK = 512;      // k-extent all groups tile evenly: one 1 KiB wave load of a b-bit group spans 512/b
+constexpr int kHeaderBytes = 256;
+constexpr uint32_t kMagicW = 0x57514241u;   // "ABQW"
+constexpr uint32_t kMagicA = 0x41514241u;   // "ABQA"
+
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Packed-weight blob:
+//   [header 256 B][wparams N x {int32 wsum, float scale, int32 zero, int32 0}]
+//   [planes  uint32 [p][N][Kw]]                               if PLANES/BOTH   (Kw = ceil(K/128)*4)
+//   [group g: uint4 [NT][C_g][64 lanes]] for each group       if FIELDS/BOTH   (NT = ceil(N/16), C_g = ceil(K*b_g/512))
+struct WeightLayout {
+    int p, N, K, layout;
+    bool has_planes, has_fields;
+    int ngroups, gb[3], gs[3], chunks[3];
+    int NT, Kw;
+    size_t off_params, off_planes, off_fields[3], total;
+};
+
+// Packed-activation blob:
+//   [header 256 B][aparams M x {int32 asum, float scale, int32 zero, int32 0}]
+//   [planes uint32 [q][M][Kw]]                                if PLANES/BOTH
+//   [codes  int8 [M][Kp], value a - (q==8 ? 128 : 0), zero padded to Kp = ceil(K/512)*512]   if FIELDS/BOTH
+struct ActLayout {
+    int q, M, K, layout;
+    bool has_planes, has_fields;
+    int Kp, Kw;
+    size_t off_params, off_planes, off_codes, total;
+};
+
+bool make_weight_layout(int p, int N, int K, int layout, WeightLayout* out);
+bool make_act_layout(int q, int M, int K, int layout, ActLayout* out);
+
+// ---- kernel launchers (each returns the hipError_t of the launch) --------------------------
+hipError_t launch_pack_weights(const WeightLayout& L, const uint8_t* w_codes, const float* w_scale,
+                               const int32_t* w_zero, uint8_t* blob, hipStream_t s);
+hipError_t launch_unpack_weights(const WeightLayout& L, const uint8_t* blob, int which, uint8_t* out, hipStream_t s);
+hipError_t launch_pack_act_codes(const ActLayout& L, const uint8_t* codes, const float* a_scale,
+                                 const int32_t* a_zero, uint8_t* blob, hipStream_t s);
+hipError_t launch_quant_pack_act(const ActLayout& L, const uint16_t* x, uint8_t* blob, hipStream_t s);
+hipError_t launch_unpack_act(const ActLayout& L, const uint8_t* blob, int which, uint8_t* codes, float* scale,
+                             int32_t* zero, int32_t* sum, hipStream_t s);
+
+struct GemmArgs {
+    int p, q, M, N, K;
+    const uint8_t* act_blob;
+    const uint8_t* w_blob;
+    uint16_t* y;
+    int32_t* acc;      // may be null
+    void* workspace;
+    size_t workspace_bytes;
+};
+hipError_t launch_gemm_skinny(const GemmArgs& g, const ActLayout& A, const WeightLayout& W, hipStream_t s);
+hipError_t launch_gemm_tiled(const GemmArgs& g, const ActLayout& A, const WeightLayout& W, hipStream_t s);
+hipError_t launch_gemm_bitserial(const GemmArgs& g, const ActLayout& A, const WeightLayout& W, hipStream_t s);
+size_t gemm_tiled_workspace_bytes(int p, int q, int M, int N, int K);
+
+// ---- device helpers -------------------------------------------------------------------------
+struct alignas(16) RowParams { int32_t sum; float scale; int32_t zero; int32_t pad; };
+
+// Fused dequant epilogue (the "DeQuant" box of Fig. 3b with the affine semantics of Eq. 3).
+// S is the kernel's sum over (a - oa)(w - ow); the exact integer zero-point correction is
+// applied before any float operation.  Unsigned arithmetic: intermediate wrap-around is
+// harmless because the final value fits in int32.
+__device__ __forceinline__ void epilogue_store(int32_t S, int oa, int ow, int K, const RowParams& ap,
+                                               const RowParams& wp, size_t idx, uint16_t* y, int32_t* acc)
+{
+    const uint32_t asum = (uint32_t)ap.sum, wsum = (uint32_t)wp.sum;
+    const uint32_t uK = (uint32_t)K, uoa = (uint32_t)oa, uow = (uint32_t)ow;
+    const uint32_t raw = (uint32_t)S + uow * asum + uoa * wsum - uK * uoa * uow;
+    if (acc) acc[idx] = (int32_t)raw;
+    const uint32_t az = (uint32_t)ap.zero, wz = (uint32_t)wp.zero;
+    const int32_t centered = (int32_t)(raw - wz * asum - az * wsum + uK * az * wz);
+    const float v = ((float)centered * ap.scale) * wp.scale;
+    y[idx] = __half_as_ushort(__float2half_rn(v));
+}
+
+}  // namespace abq

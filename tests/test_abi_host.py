@@ -1,0 +1,110 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2408_08554_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B.load()
+    header = open(os.path.join(ROOT, "include", "abq.h")).read()
+    declared = set(re.findall(r"\b(abq_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(B._SIGNATURES), declared ^ set(B._SIGNATURES)
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert lib.abq_version() >= 100
+    assert lib.abq_status_string(0) == b"ok"
+    for st in range(-7, 0):
+        assert len(lib.abq_status_string(st)) > 3
+
+
+def test_size_queries():
+    lib = B.load()
+    # header + params + fields for W4 4096x4096: the streamed part is exactly p*N*K/8
+    nb = lib.abq_packed_weight_bytes(4, 4096, 4096, B.ABQ_LAYOUT_FIELDS)
+    assert nb == 256 + 4096 * 16 + 4 * 4096 * 4096 // 8
+    both = lib.abq_packed_weight_bytes(4, 4096, 4096, B.ABQ_LAYOUT_BOTH)
+    planes = lib.abq_packed_weight_bytes(4, 4096, 4096, B.ABQ_LAYOUT_PLANES)
+    assert both == nb + planes - 256 - 4096 * 16
+    assert lib.abq_packed_weight_bytes(0, 16, 16, 0) == 0
+    assert lib.abq_packed_weight_bytes(9, 16, 16, 0) == 0
+    assert lib.abq_packed_weight_bytes(4, 0, 16, 0) == 0
+    assert lib.abq_packed_weight_bytes(4, 16, B.ABQ_MAX_K + 1, 0) == 0
+    assert lib.abq_packed_weight_bytes(4, 16, 16, 7) == 0
+    assert lib.abq_packed_act_bytes(8, 1, 4096, B.ABQ_LAYOUT_FIELDS) == 256 + 256 + 4096
+    assert lib.abq_packed_act_bytes(8, 3, 100, B.ABQ_LAYOUT_PLANES) == 256 + 256 + 512   # 8 planes x 3 rows x 4 words x 4 B = 384, sections are 256-B aligned
+    assert lib.abq_gemm_workspace_bytes(2, 8, 1, 4096, 4096) == 0
+    assert lib.abq_gemm_workspace_bytes(8, 8, 1, 16, 40000) == 0   # overflow bound -> 0
+
+
+A16 = 0x1000  # any non-null 16-byte aligned value; validation fails before it is dereferenced
+
+
+@pytest.mark.parametrize("args,want", [
+    ((4, 16, 64, 0, A16, A16, 0, A16, 1 << 20, None), B.ABQ_ERR_NULL),
+    ((0, 16, 64, A16, A16, A16, 0, A16, 1 << 20, None), B.ABQ_ERR_BITS),
+    ((9, 16, 64, A16, A16, A16, 0, A16, 1 << 20, None), B.ABQ_ERR_BITS),
+    ((4, 0, 64, A16, A16, A16, 0, A16, 1 << 20, None), B.ABQ_ERR_SHAPE),
+    ((4, 16, B.ABQ_MAX_K + 1, A16, A16, A16, 0, A16, 1 << 30, None), B.ABQ_ERR_SHAPE),
+    ((4, 16, 64, A16, A16, A16, 9, A16, 1 << 20, None), B.ABQ_ERR_LAYOUT),
+    ((4, 16, 64, A16 + 4, A16, A16, 0, A16, 1 << 20, None), B.ABQ_ERR_ALIGN),
+    ((4, 16, 64, A16, A16, A16, 0, A16, 100, None), B.ABQ_ERR_SIZE),
+])
+def test_pack_weights_rejects(args, want):
+    assert B.load().abq_pack_weights(*args) == want
+
+
+@pytest.mark.parametrize("args,want", [
+    ((8, 1, 64, None, 0, A16, 1 << 20, None), B.ABQ_ERR_NULL),
+    ((0, 1, 64, A16, 0, A16, 1 << 20, None), B.ABQ_ERR_BITS),
+    ((8, 1, 0, A16, 0, A16, 1 << 20, None), B.ABQ_ERR_SHAPE),
+    ((8, 1, 64, A16 + 2, 0, A16, 1 << 20, None), B.ABQ_ERR_ALIGN),
+    ((8, 1, 64, A16, 0, A16, 10, None), B.ABQ_ERR_SIZE),
+    ((8, 1, 64, A16, 5, A16, 1 << 20, None), B.ABQ_ERR_LAYOUT),
+])
+def test_quant_pack_act_rejects(args, want):
+    assert B.load().abq_quant_pack_act(*args) == want
+
+
+def test_pack_act_codes_rejects():
+    lib = B.load()
+    assert lib.abq_pack_act_codes(8, 1, 64, A16, None, A16, 0, A16, 1 << 20, None) == B.ABQ_ERR_NULL
+    assert lib.abq_pack_act_codes(8, -1, 64, A16, A16, A16, 0, A16, 1 << 20, None) == B.ABQ_ERR_SHAPE
+    assert lib.abq_pack_act_codes(12, 1, 64, A16, A16, A16, 0, A16, 1 << 20, None) == B.ABQ_ERR_BITS
+    assert lib.abq_pack_act_codes(8, 1, 64, A16, A16, A16, 0, A16, 16, None) == B.ABQ_ERR_SIZE
+
+
+def gemm(lib, p=4, q=8, M=1, N=16, K=64, pa=A16, al=0, pw=A16, wl=0, y=A16, acc=None, ws=None, wsb=0):
+    return lib.abq_gemm(p, q, M, N, K, pa, al, pw, wl, y, acc, ws, wsb, None)
+
+
+def test_gemm_rejects():
+    lib = B.load()
+    assert gemm(lib, pa=None) == B.ABQ_ERR_NULL
+    assert gemm(lib, y=None) == B.ABQ_ERR_NULL
+    assert gemm(lib, p=0) == B.ABQ_ERR_BITS
+    assert gemm(lib, q=9) == B.ABQ_ERR_BITS
+    assert gemm(lib, M=0) == B.ABQ_ERR_SHAPE
+    # 32-bit accumulator bound: K*(2^p-1)*(2^q-1) must fit int32
+    assert gemm(lib, p=8, q=8, K=33026) == B.ABQ_ERR_SHAPE
+    assert gemm(lib, p=8, q=8, K=33025, y=A16 + 8) == B.ABQ_ERR_ALIGN   # shape accepted, next check trips
+    assert gemm(lib, K=B.ABQ_MAX_K + 1) == B.ABQ_ERR_SHAPE
+    # the two blobs must share a representation
+    assert gemm(lib, al=B.ABQ_LAYOUT_PLANES, wl=B.ABQ_LAYOUT_FIELDS) == B.ABQ_ERR_LAYOUT
+    assert gemm(lib, al=B.ABQ_LAYOUT_FIELDS, wl=B.ABQ_LAYOUT_FIELDS | B.ABQ_USE_PLANES) == B.ABQ_ERR_LAYOUT
+    assert gemm(lib, al=B.ABQ_LAYOUT_BOTH, wl=B.ABQ_LAYOUT_BOTH | B.ABQ_USE_PLANES | B.ABQ_USE_FIELDS) == B.ABQ_ERR_LAYOUT
+    assert gemm(lib, al=4) == B.ABQ_ERR_LAYOUT
+    assert gemm(lib, acc=A16 + 4) == B.ABQ_ERR_ALIGN
+
+
+def test_unpack_rejects():
+    lib = B.load()
+    assert lib.abq_unpack_weights(4, 16, 64, B.ABQ_LAYOUT_FIELDS, A16, B.ABQ_LAYOUT_PLANES, A16, None) == B.ABQ_ERR_LAYOUT
+    assert lib.abq_unpack_weights(4, 16, 64, B.ABQ_LAYOUT_FIELDS, None, B.ABQ_LAYOUT_FIELDS, A16, None) == B.ABQ_ERR_NULL
+    assert lib.abq_unpack_act(8, 1, 64, B.ABQ_LAYOUT_PLANES, A16, B.ABQ_LAYOUT_FIELDS, A16, None, None, None, None) == B.ABQ_ERR_LAYOUT

@@ -1,0 +1,179 @@
+"""GPU parity: every step of the hot path through the C ABI against the CPU oracle.
+int32 accumulator bit-exact, codes/planes bit-exact, fp16 output within the stated tolerance."""
+import itertools
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2408_08554_amd import synth
+from helpers import check_against_oracle, check_sampled, gpu_gemm, to_dev
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+PLANES, FIELDS, BOTH = 1, 2, 3
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+# ---- packers ------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("p,N,K", [(1, 16, 512), (2, 33, 100), (3, 17, 1000), (4, 64, 4096), (5, 7, 96),
+                                   (6, 100, 640), (7, 31, 513), (8, 48, 32), (8, 5, 2049)])
+def test_weight_pack_roundtrip(abq, p, N, K):
+    say("weights roundtrip", p, N, K)
+    c = synth.make_case(p, 8, 1, N, K, seed=1000 + p)
+    pw = abq.abq_pack_weights(p, to_dev(torch, c.W), to_dev(torch, c.w_scale), to_dev(torch, c.w_zero), BOTH)
+    for which in (PLANES, FIELDS):
+        back = abq.abq_unpack_weights(p, N, K, BOTH, pw, which).cpu().numpy()
+        assert np.array_equal(back, c.W), which
+    # the plane section is the paper's [p][N][K] BitPacking: compare with the oracle's packer word for word
+    lib_bytes = pw.cpu().numpy()
+    Kw = (K + 127) // 128 * 4
+    off = 256 + (N * 16 + 255) // 256 * 256
+    planes = lib_bytes[off:off + p * N * Kw * 4].view(np.uint32).reshape(p, N, Kw)
+    assert np.array_equal(planes, oracle.pack_planes(c.W, p, Kw=Kw))
+
+
+@pytest.mark.parametrize("q,M,K", [(1, 1, 512), (2, 3, 100), (4, 16, 4096), (6, 5, 1000), (8, 2, 96), (8, 9, 11008), (7, 1, 31)])
+def test_act_pack_roundtrip(abq, q, M, K):
+    say("acts roundtrip", q, M, K)
+    c = synth.make_case(2, q, M, 16, K, seed=2000 + q)
+    pa = abq.abq_pack_act_codes(q, to_dev(torch, c.A), to_dev(torch, c.a_scale), to_dev(torch, c.a_zero), BOTH)
+    for which in (PLANES, FIELDS):
+        codes, sc, zp, sm = abq.abq_unpack_act(q, M, K, BOTH, pa, which)
+        assert np.array_equal(codes.cpu().numpy(), c.A)
+        assert np.array_equal(sc.cpu().numpy(), c.a_scale) and np.array_equal(zp.cpu().numpy(), c.a_zero)
+        assert np.array_equal(sm.cpu().numpy().astype(np.int64), c.A.astype(np.int64).sum(axis=1))
+
+
+@pytest.mark.parametrize("q", [1, 2, 3, 4, 5, 6, 7, 8])
+@pytest.mark.parametrize("M,K", [(1, 4096), (5, 1000), (3, 96)])
+def test_quant_pack_act_matches_oracle(abq, q, M, K):
+    say("quantizer", q, M, K)
+    x = synth.act_fp16(3000 + 10 * q + M, M, K)
+    if M >= 3:
+        x[1] = 0
+        x[2] = np.abs(x[2])
+    ref_codes, ref_scale, ref_zero = oracle.quant_act(x, q)
+    pa = abq.abq_quant_pack_act(q, to_dev(torch, x), BOTH)
+    for which in (PLANES, FIELDS):
+        codes, sc, zp, sm = abq.abq_unpack_act(q, M, K, BOTH, pa, which)
+        assert np.array_equal(sc.cpu().numpy(), ref_scale)
+        assert np.array_equal(zp.cpu().numpy(), ref_zero)
+        assert np.array_equal(codes.cpu().numpy(), ref_codes)
+        assert np.array_equal(sm.cpu().numpy().astype(np.int64), ref_codes.astype(np.int64).sum(axis=1))
+
+
+# ---- matmul: every (p,q), both kernel families -------------------------------------------------
+
+@pytest.mark.parametrize("layout", [FIELDS, PLANES], ids=["mfma", "bitserial"])
+@pytest.mark.parametrize("p,q", list(itertools.product(range(1, 9), range(1, 9))))
+def test_all_pq_small(abq, layout, p, q):
+    say("all pq", layout, p, q)
+    c = synth.make_case(p, q, 3, 40, 1100, seed=synth.case_seed(9, p, q), name=f"W{p}A{q} 3x40x1100")
+    y, acc = gpu_gemm(torch, abq, c, layout, layout)
+    check_against_oracle(c, y, acc)
+
+
+SHAPES = [(1, 256, 512), (1, 17, 100), (2, 16, 32), (8, 100, 96), (16, 64, 2048), (5, 33, 1), (7, 1, 513),
+          (1, 48, 5120), (4, 31, 13824), (17, 20, 700), (33, 50, 1536), (64, 16, 640)]
+
+
+@pytest.mark.parametrize("layout", [FIELDS, PLANES], ids=["mfma", "bitserial"])
+@pytest.mark.parametrize("M,N,K", SHAPES)
+@pytest.mark.parametrize("p,q", [(2, 8), (4, 8), (6, 6), (8, 8), (3, 5), (7, 7), (1, 1), (5, 2)])
+def test_shapes(abq, layout, M, N, K, p, q):
+    say("shape", layout, M, N, K, p, q)
+    c = synth.make_case(p, q, M, N, K, seed=synth.case_seed(8, p, q) + M + N + K, name=f"W{p}A{q} {M}x{N}x{K}")
+    y, acc = gpu_gemm(torch, abq, c, layout, layout)
+    check_against_oracle(c, y, acc)
+
+
+def test_both_layout_and_forced_family(abq):
+    c = synth.make_case(4, 8, 2, 48, 1024, seed=77)
+    for flag in (0, 0x10, 0x20):
+        y, acc = gpu_gemm(torch, abq, c, BOTH, BOTH, gemm_w_layout=BOTH | flag)
+        check_against_oracle(c, y, acc)
+
+
+def test_extreme_codes_and_no_acc_output(abq):
+    # all-max codes hit the largest accumulator value the ABI admits for this K; acc pointer NULL
+    for p, q, K in [(8, 8, 33025), (1, 8, 4096), (8, 1, 700), (4, 4, 8192)]:
+        M, N = 2, 20
+        c = synth.make_case(p, q, M, N, K, seed=5)
+        c.A[:] = (1 << q) - 1
+        c.W[:] = (1 << p) - 1
+        c.a_zero[:] = 0
+        c.w_zero[:] = 0
+        c.a_scale[:] = np.float32(2.0 ** -20)
+        c.w_scale[:] = np.float32(2.0 ** -8)
+        for layout in (FIELDS, PLANES):
+            y, acc = gpu_gemm(torch, abq, c, layout, layout)
+            assert (acc == K * ((1 << p) - 1) * ((1 << q) - 1)).all()
+            check_against_oracle(c, y, acc)
+            y2, none = gpu_gemm(torch, abq, c, layout, layout, want_acc=False)
+            assert none is None and np.array_equal(y2.view(np.uint16), y.view(np.uint16))
+
+
+def test_output_overwrites_poison_and_is_deterministic(abq):
+    c = synth.make_case(2, 8, 3, 70, 1500, seed=11)
+    pw = abq.abq_pack_weights(c.p, to_dev(torch, c.W), to_dev(torch, c.w_scale), to_dev(torch, c.w_zero), FIELDS)
+    pa = abq.abq_pack_act_codes(c.q, to_dev(torch, c.A), to_dev(torch, c.a_scale), to_dev(torch, c.a_zero), FIELDS)
+    outs = []
+    for fill in (0xFF, 0x00):
+        y = torch.full((c.M, c.N), 0, dtype=torch.float16, device="cuda").view(torch.uint8).fill_(fill).view(torch.float16)
+        acc = torch.full((c.M, c.N), -1 if fill else 0, dtype=torch.int32, device="cuda")
+        abq.abq_gemm(c.p, c.q, c.M, c.N, c.K, pa, FIELDS, pw, FIELDS, y=y, acc=acc)
+        torch.cuda.synchronize()
+        outs.append((y.cpu().numpy().view(np.uint16), acc.cpu().numpy()))
+    assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1])
+    check_against_oracle(c, outs[0][0].view(np.float16), outs[0][1])
+
+
+# ---- the benchmark configurations at full size -------------------------------------------------
+
+def test_config1_tiny(abq):
+    c = synth.config1()
+    for layout in (FIELDS, PLANES):
+        y, acc = gpu_gemm(torch, abq, c, layout, layout)
+        check_against_oracle(c, y, acc)
+
+
+def test_config2_w4a8_gemv_full(abq):
+    c = synth.config2()
+    y, acc = gpu_gemm(torch, abq, c, FIELDS, FIELDS)
+    check_against_oracle(c, y, acc)
+    y, acc = gpu_gemm(torch, abq, c, PLANES, PLANES)
+    check_against_oracle(c, y, acc)
+
+
+@pytest.mark.parametrize("M", [1, 3, 8])
+def test_config3_w2a8_gemv_full(abq, M):
+    c = synth.config3(M)
+    y, acc = gpu_gemm(torch, abq, c, FIELDS, FIELDS)
+    check_against_oracle(c, y, acc)
+
+
+def test_config3_bitserial(abq):
+    c = synth.config3(2)
+    y, acc = gpu_gemm(torch, abq, c, PLANES, PLANES)
+    check_against_oracle(c, y, acc)
+
+
+def test_quantize_then_gemm_end_to_end(abq):
+    # fp16 activations -> online quantizer -> matmul; the oracle follows the same two steps
+    p, q, M, N, K = 4, 8, 4, 64, 2048
+    c = synth.make_case(p, q, M, N, K, seed=4242)
+    x = synth.act_fp16(4243, M, K)
+    codes, sc, zp = oracle.quant_act(x, q)
+    c.A, c.a_scale, c.a_zero = codes, sc, zp
+    pw = abq.abq_pack_weights(p, to_dev(torch, c.W), to_dev(torch, c.w_scale), to_dev(torch, c.w_zero), FIELDS)
+    pa = abq.abq_quant_pack_act(q, to_dev(torch, x), FIELDS)
+    y, acc = abq.abq_gemm(p, q, M, N, K, pa, FIELDS, pw, FIELDS, want_acc=True)
+    torch.cuda.synchronize()
+    check_against_oracle(c, y.cpu().numpy(), acc.cpu().numpy())
