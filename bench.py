@@ -1,0 +1,201 @@
+#!/usr/bin/env python3
+"""Benchmark of the quantized-matmul hot path on one MI355X.
+
+A step is one pass of the online path over one batch of synthetic input: activation
+BitPacking (abq_pack_act_codes) followed by the matmul with fused bit reduction and dequant
+(abq_gemm), against packed weights that were prepared offline.  Successive steps use
+different weight buffers (round-robin over >= 1 GiB) so that the 256 MB last-level cache
+cannot serve the weight stream — as in real decoding, where every layer has its own weights.
+
+Prints one JSON line.  `value` is effective TOPS = 2*M*N*K / time (the paper's metric,
+independent of p and q).  `roofline` prices the matmul kernel alone against the HBM peak on
+algorithmic bytes, from HIP-event timing of a gemm-only region on the launch stream.
+`cpu_baseline` is the CPU oracle timed on this machine's host cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0           # MI355X published HBM3E bandwidth
+INT8_MFMA_PEAK_TOPS = 5000.0    # MI355X published dense int8
+
+
+def build_case(name):
+    from paper_2408_08554_amd import synth
+    if name == "c1":
+        return synth.config1()
+    if name == "c2":
+        return synth.config2()
+    if name.startswith("c3"):
+        return synth.config3(int(name.split("m")[1]) if "m" in name else 1)
+    if name.startswith("c4"):
+        return synth.config4(int(name.split("m")[1]) if "m" in name else 128)
+    if name.startswith("c5"):
+        # c5:p,q,shape_idx,m_idx
+        p, q, s, m = (int(v) for v in name.split(":")[1].split(","))
+        return synth.config5(p, q, s, m)
+    if name.startswith("custom:"):
+        p, q, M, N, K = (int(v) for v in name.split(":")[1].split(","))
+        return synth.make_case(p, q, M, N, K, seed=12345, name=name)
+    raise SystemExit(f"unknown workload {name}")
+
+
+def cpu_baseline(c, budget_s):
+    """The oracle as it stands, on the host cores, repeated over the same workload."""
+    import oracle
+    from paper_2408_08554_amd import metrics
+    reps, t0 = 0, time.perf_counter()
+    while True:
+        accc = oracle.acc_centered(c.A, c.W, c.a_zero, c.w_zero)
+        oracle.dequant(accc, c.a_scale, c.w_scale)
+        reps += 1
+        el = time.perf_counter() - t0
+        if el >= budget_s or reps >= 100000:
+            break
+    return {"value": metrics.effective_tops(c.M, c.N, c.K, el / reps), "unit": "TOPS", "cores": oracle.threads(),
+            "kind": "oracle", "sample": f"{reps} full passes of the workload (int64 centered product sum + double "
+            f"dequant + half rounding) in {el:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--workload", default="c2", help="c1 | c2 | c3m<M> | c4m<M> | c5:p,q,shape,m | custom:p,q,M,N,K")
+    ap.add_argument("--mode", default="graph", choices=["graph", "eager"],
+                    help="graph: the timed steps are replayed from one captured HIP graph; eager: launched one by one")
+    ap.add_argument("--family", default="auto", choices=["auto", "mfma", "bitserial"])
+    ap.add_argument("--rotate-gib", type=float, default=1.0, help="total size of the rotating weight buffers")
+    ap.add_argument("--cpu-seconds", type=float, default=10.0, help="time budget of the cpu_baseline leg (0 = skip)")
+    ap.add_argument("--no-check", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+
+    import numpy as np
+    import torch
+    from paper_2408_08554_amd import binding as abq, metrics
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    abq.load()
+
+    c = build_case(args.workload)
+    p, q, M, N, K = c.p, c.q, c.M, c.N, c.K
+    layout = {"auto": abq.ABQ_LAYOUT_FIELDS, "mfma": abq.ABQ_LAYOUT_FIELDS, "bitserial": abq.ABQ_LAYOUT_PLANES}[args.family]
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+    # offline: pack the weights once, then replicate the blob into the rotation set
+    w_codes, w_scale, w_zero = dev(c.W), dev(c.w_scale), dev(c.w_zero)
+    blob0 = abq.abq_pack_weights(p, w_codes, w_scale, w_zero, layout)
+    blob_bytes = blob0.numel()
+    R = max(2, int(np.ceil(args.rotate_gib * 2 ** 30 / blob_bytes)))
+    R = min(R, max(2, args.steps))
+    stride = (blob_bytes + 255) // 256 * 256
+    pool = torch.empty(R * stride, dtype=torch.uint8, device="cuda")
+    blobs = [pool[i * stride:i * stride + blob_bytes] for i in range(R)]
+    for b in blobs:
+        b.copy_(blob0)
+    del w_codes
+
+    a_codes, a_scale, a_zero = dev(c.A), dev(c.a_scale), dev(c.a_zero)
+    pa = torch.empty(abq.abq_packed_act_bytes(q, M, K, layout), dtype=torch.uint8, device="cuda")
+    y = torch.empty((M, N), dtype=torch.float16, device="cuda")
+    ws_bytes = abq.abq_gemm_workspace_bytes(p, q, M, N, K)
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
+
+    def step(i):
+        abq.abq_pack_act_codes(q, a_codes, a_scale, a_zero, layout, out=pa)
+        abq.abq_gemm(p, q, M, N, K, pa, layout, blobs[i % R], layout, y=y, workspace=ws)
+
+    def gemm_only(i):
+        abq.abq_gemm(p, q, M, N, K, pa, layout, blobs[i % R], layout, y=y, workspace=ws)
+
+    # parity on the buffers that are timed (first and last rotation slot)
+    if not args.no_check:
+        import oracle
+        acc = torch.empty((M, N), dtype=torch.int32, device="cuda")
+        abq.abq_pack_act_codes(q, a_codes, a_scale, a_zero, layout, out=pa)
+        rng = np.random.Generator(np.random.PCG64(7))
+        ms = rng.integers(0, M, 2048).astype(np.int32)
+        ns = rng.integers(0, N, 2048).astype(np.int32)
+        ref = oracle.acc_sampled(c.A, c.W, ms, ns)
+        for slot in (0, R - 1):
+            abq.abq_gemm(p, q, M, N, K, pa, layout, blobs[slot], layout, y=y, acc=acc, workspace=ws)
+            torch.cuda.synchronize()
+            got = acc.cpu().numpy()[ms, ns].astype(np.int64)
+            assert np.array_equal(got, ref), f"parity failure on rotation slot {slot}"
+
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        for i in range(args.warmup):
+            step(i)
+        stream.synchronize()
+
+        def timed_region(fn, n):
+            """(wall seconds, HIP-event seconds) for n calls of fn on `stream`."""
+            if args.mode == "graph":
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=stream):
+                    for i in range(n):
+                        fn(i)
+                g.replay()            # one untimed replay: uploads the graph
+                stream.synchronize()
+                run = g.replay
+            else:
+                def run():
+                    for i in range(n):
+                        fn(i)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            e0.record(stream)
+            run()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            return t1 - t0, e0.elapsed_time(e1) * 1e-3
+
+        wall, ev = timed_region(step, args.steps)
+        _, ev_gemm = timed_region(gemm_only, args.steps)
+
+    sec_per_step = wall / args.steps
+    gemm_s = ev_gemm / args.steps
+    alg_bytes = metrics.gemm_algorithmic_bytes(p, q, M, N, K)
+    hbm_bound = M <= 39 * p
+    if hbm_bound:
+        achieved = alg_bytes / gemm_s / 1e9
+        roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBS, "traffic": None}
+    else:
+        achieved = 2.0 * M * N * K / gemm_s / 1e12
+        roof = {"bound": "mfma", "achieved": achieved, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
+                "frac": achieved / INT8_MFMA_PEAK_TOPS, "traffic": None}
+    roof.update({"kernel": "abq_gemm", "kernel_us_hip_events": gemm_s * 1e6, "algorithmic_bytes": alg_bytes,
+                 "launches": args.steps})
+
+    out = {
+        "metric": "effective TOPS (2*M*N*K/s)", "value": metrics.effective_tops(M, N, K, sec_per_step), "unit": "TOPS",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": sec_per_step * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "config": {"workload": c.name, "p": p, "q": q, "M": M, "N": N, "K": K, "mode": args.mode,
+                   "family": args.family, "rotating_weight_buffers": R, "rotating_bytes": R * stride,
+                   "step": "abq_pack_act_codes + abq_gemm"},
+        "weight_gbs": metrics.weight_gbs(p, N, K, sec_per_step),
+        "gemm_only": {"us": gemm_s * 1e6, "tops": metrics.effective_tops(M, N, K, gemm_s),
+                      "weight_gbs": metrics.weight_gbs(p, N, K, gemm_s)},
+        "hip_event_ms_per_step": ev / args.steps * 1e3,
+        "roofline": roof,
+    }
+    if args.cpu_seconds > 0:
+        out["cpu_baseline"] = cpu_baseline(c, args.cpu_seconds)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -49,7 +49,7 @@ bool make_weight_layout(int p, int N, int K, int layout, WeightLayout* L)
         for (int g = 0; g < L->ngroups; ++g) {
             L->gb[g] = group_width(p, g);
             L->gs[g] = group_shift(p, g);
-            L->chunks[g] = (int)(((size_t)K * L->gb[g] + kSuperK - 1) / kSuperK);
+            L->chunks[g] = (K + kSuperK - 1) / kSuperK * L->gb[g];   // whole super-chunks of 512 k
             L->off_fields[g] = off;
             off = align_up(off + (size_t)L->NT * L->chunks[g] * 1024, 256);
         }

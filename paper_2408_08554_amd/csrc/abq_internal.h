@@ -37,7 +37,7 @@ static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; 
 // Packed-weight blob:
 //   [header 256 B][wparams N x {int32 wsum, float scale, int32 zero, int32 0}]
 //   [planes  uint32 [p][N][Kw]]                               if PLANES/BOTH   (Kw = ceil(K/128)*4)
-//   [group g: uint4 [NT][C_g][64 lanes]] for each group       if FIELDS/BOTH   (NT = ceil(N/16), C_g = ceil(K*b_g/512))
+//   [group g: uint4 [NT][C_g][64 lanes]] for each group       if FIELDS/BOTH   (NT = ceil(N/16), C_g = b_g*ceil(K/512))
 struct WeightLayout {
     int p, N, K, layout;
     bool has_planes, has_fields;

@@ -226,6 +226,123 @@ __global__ __launch_bounds__(BLOCK) void act_rows_kernel(const void* __restrict_
     }
 }
 
+// ---- fast path of the same step: int8 rows only (no planes), rows 16-byte aligned -----------------
+// One workgroup per token; a thread handles 16 consecutive k per step with 128-bit loads and
+// stores.  The first two steps of a thread stay in registers between the min/max pass and the
+// quantizing pass (rows up to 32*BLOCK elements are read once).
+__device__ __forceinline__ void half8_to_float(const uint4& v, float* f)
+{
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        f[2 * i] = half_bits_to_float((uint16_t)(w[i] & 0xFFFFu));
+        f[2 * i + 1] = half_bits_to_float((uint16_t)(w[i] >> 16));
+    }
+}
+
+template <bool SRC_HALF, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void act_rows_fast_kernel(const void* __restrict__ src, const float* __restrict__ a_scale,
+                                                              const int32_t* __restrict__ a_zero, ActLayout L,
+                                                              uint8_t* __restrict__ blob)
+{
+    __shared__ float s_lo[BLOCK / 64], s_hi[BLOCK / 64];
+    __shared__ int32_t s_sum[BLOCK / 64];
+    const int m = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int q = L.q, K = L.K, qmax = (1 << q) - 1;
+    const int nvalid = K / 16, nblk = L.Kp / 16;       // 16-element blocks with data / in the padded row
+    if (m == 0 && tid < kHeaderBytes / 4) {
+        uint32_t v = 0;
+        if (tid == 0) v = kMagicA; else if (tid == 1) v = 1; else if (tid == 2) v = (uint32_t)q;
+        else if (tid == 3) v = (uint32_t)L.M; else if (tid == 4) v = (uint32_t)K; else if (tid == 5) v = (uint32_t)L.layout;
+        ((uint32_t*)blob)[tid] = v;
+    }
+    // SRC_HALF: 16 halves = two uint4; codes: one uint4
+    constexpr int VPB = SRC_HALF ? 2 : 1;
+    const uint4* row = (const uint4*)src + (size_t)m * nvalid * VPB;
+    uint4 keep[2][VPB];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int e = tid + i * BLOCK;
+#pragma unroll
+        for (int v = 0; v < VPB; ++v) keep[i][v] = e < nvalid ? row[(size_t)e * VPB + v] : make_uint4(0, 0, 0, 0);
+    }
+    float delta = 1.0f;
+    int z = 0;
+    if (SRC_HALF) {
+        float lo = 0.0f, hi = 0.0f;
+        for (int e = tid; e < nvalid; e += BLOCK) {
+            float f[16];
+            if (e < 2 * BLOCK) {
+                half8_to_float(keep[e >= BLOCK ? 1 : 0][0], f);
+                half8_to_float(keep[e >= BLOCK ? 1 : 0][VPB - 1], f + 8);
+            } else {
+                half8_to_float(row[(size_t)e * VPB], f);
+                half8_to_float(row[(size_t)e * VPB + VPB - 1], f + 8);
+            }
+#pragma unroll
+            for (int i = 0; i < 16; ++i) { lo = fminf(lo, f[i]); hi = fmaxf(hi, f[i]); }
+        }
+        for (int off = 32; off > 0; off >>= 1) {
+            lo = fminf(lo, __shfl_xor(lo, off, 64));
+            hi = fmaxf(hi, __shfl_xor(hi, off, 64));
+        }
+        if (lane == 0) { s_lo[wave] = lo; s_hi[wave] = hi; }
+        __syncthreads();
+#pragma unroll
+        for (int w = 0; w < BLOCK / 64; ++w) { lo = fminf(lo, s_lo[w]); hi = fmaxf(hi, s_hi[w]); }
+        if (hi != lo) {
+            delta = __fdiv_rn(__fsub_rn(hi, lo), (float)qmax);
+            const float zf = rintf(__fdiv_rn(-lo, delta));
+            z = zf < 0.0f ? 0 : (zf > (float)qmax ? qmax : (int)zf);
+        }
+    }
+    const uint32_t oa4 = (q == 8) ? 0x80808080u : 0u;           // a - 128 as a byte == a ^ 0x80
+    const uint32_t mask4 = (uint32_t)qmax * 0x01010101u;
+    int8_t* out = (int8_t*)(blob + L.off_codes) + (size_t)m * L.Kp;
+    uint32_t sum = 0;
+    for (int e = tid; e < nblk; e += BLOCK) {
+        uint32_t dw[4] = {0, 0, 0, 0};
+        if (e < nvalid) {
+            if (SRC_HALF) {
+                float f[16];
+                if (e < 2 * BLOCK) {
+                    half8_to_float(keep[e >= BLOCK ? 1 : 0][0], f);
+                    half8_to_float(keep[e >= BLOCK ? 1 : 0][VPB - 1], f + 8);
+                } else {
+                    half8_to_float(row[(size_t)e * VPB], f);
+                    half8_to_float(row[(size_t)e * VPB + VPB - 1], f + 8);
+                }
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    int c = (int)rintf(__fdiv_rn(f[i], delta)) + z;
+                    c = c < 0 ? 0 : (c > qmax ? qmax : c);
+                    dw[i >> 2] |= (uint32_t)c << (8 * (i & 3));
+                }
+            } else {
+                const uint4 v = e < 2 * BLOCK ? keep[e >= BLOCK ? 1 : 0][0] : row[e];
+                dw[0] = v.x & mask4; dw[1] = v.y & mask4; dw[2] = v.z & mask4; dw[3] = v.w & mask4;
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                sum = __builtin_amdgcn_udot4(dw[i], 0x01010101u, sum, false);   // sum of the four codes
+                dw[i] ^= oa4;
+            }
+        }
+        *reinterpret_cast<uint4*>(out + (size_t)e * 16) = make_uint4(dw[0], dw[1], dw[2], dw[3]);
+    }
+    int32_t isum = (int32_t)sum;
+    for (int off = 32; off > 0; off >>= 1) isum += __shfl_xor(isum, off, 64);
+    if (lane == 0) s_sum[wave] = isum;
+    __syncthreads();
+    if (tid == 0) {
+        int32_t t = 0;
+#pragma unroll
+        for (int w = 0; w < BLOCK / 64; ++w) t += s_sum[w];
+        RowParams* params = (RowParams*)(blob + L.off_params);
+        params[m] = SRC_HALF ? RowParams{t, delta, z, 0} : RowParams{t, a_scale[m], a_zero[m], 0};
+    }
+}
+
 __global__ void unpack_act_bytes_kernel(const int8_t* __restrict__ in, int q, int M, int K, int Kp,
                                         uint8_t* __restrict__ codes)
 {
@@ -281,13 +398,19 @@ hipError_t launch_unpack_weights(const WeightLayout& L, const uint8_t* blob, int
 hipError_t launch_pack_act_codes(const ActLayout& L, const uint8_t* codes, const float* a_scale, const int32_t* a_zero,
                                  uint8_t* blob, hipStream_t s)
 {
-    act_rows_kernel<false, 256><<<L.M, 256, 0, s>>>(codes, a_scale, a_zero, L, blob);
+    if (!L.has_planes && L.K % 16 == 0)
+        act_rows_fast_kernel<false, 256><<<L.M, 256, 0, s>>>(codes, a_scale, a_zero, L, blob);
+    else
+        act_rows_kernel<false, 256><<<L.M, 256, 0, s>>>(codes, a_scale, a_zero, L, blob);
     return hipGetLastError();
 }
 
 hipError_t launch_quant_pack_act(const ActLayout& L, const uint16_t* x, uint8_t* blob, hipStream_t s)
 {
-    act_rows_kernel<true, 256><<<L.M, 256, 0, s>>>(x, nullptr, nullptr, L, blob);
+    if (!L.has_planes && L.K % 16 == 0)
+        act_rows_fast_kernel<true, 256><<<L.M, 256, 0, s>>>(x, nullptr, nullptr, L, blob);
+    else
+        act_rows_kernel<true, 256><<<L.M, 256, 0, s>>>(x, nullptr, nullptr, L, blob);
     return hipGetLastError();
 }
 

@@ -1,15 +1,18 @@
 // Decode-shaped matmul (M = 1 .. 64): the packed weight plane groups are streamed from HBM
-// exactly once with 128-bit coalesced loads, expanded to signed bytes in registers with one
-// AND per dword, and contracted against the int8 activation codes on the 16x16x64 int8 MFMA.
-// Bit reduction (Sec. 3.4 step 5 / Appendix B: the 2^(s+t) factors) happens in registers:
-// the activation side carries all q planes at once as the int8 code, the weight side one
-// plane group per accumulator, recombined with shifts after the K loop.  The dequant
-// epilogue is fused (Fig. 3b).
+// exactly once with 128-bit coalesced non-temporal loads, expanded to signed bytes in
+// registers with one AND per dword, and contracted against the int8 activation codes on the
+// 16x16x64 int8 MFMA.  Bit reduction (Sec. 3.4 step 5 / Appendix B: the 2^(s+t) factors)
+// happens in registers: the activation side carries all q planes at once as the int8 code,
+// the weight side one plane group per accumulator, recombined with shifts after the K loop.
+// The dequant epilogue is fused (Fig. 3b).
 //
-// Work decomposition: one workgroup per 16 output channels (one MFMA tile of W rows); its
-// waves split K in units of 512 (a "super-chunk": every plane group tiles 512 k-values with
-// whole 1 KiB wave loads) and are summed through LDS at the end.  The M <= 16 rows of A for
-// the K range in flight are staged in LDS once per workgroup.
+// Work decomposition: a workgroup of S waves owns one 16-row tile of W at a time (and walks
+// several tiles when the grid is smaller than the tile count).  Its waves split K in units
+// of 512 (a "super-chunk": every plane group tiles 512 k-values with whole 1 KiB wave loads),
+// wave w taking super-chunks w, w+S, ...  Each wave keeps a ring of D super-chunks of weight
+// loads in flight, running ahead across tile boundaries, so the stream never drains between
+// tiles.  The rows of A a wave needs are staged once into its own part of LDS (no barrier on
+// the way to the first MFMA).  Per tile the S partial tiles are summed through LDS.
 #include "abq_internal.h"
 #include "../../include/abq.h"
 
@@ -18,9 +21,20 @@
 namespace abq {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
+typedef unsigned int u4v __attribute__((ext_vector_type(4)));
+
+// Phase timestamps for kernel tuning; compiled out unless a harness defines ABQ_PHASE_TRACE.
+#ifdef ABQ_PHASE_TRACE
+__device__ unsigned long long g_phase_trace[1024 * 8 * 8];
+#define ABQ_TS(i) ts[i] = wall_clock64()
+#define ABQ_TSS(i) st.ts[i] = wall_clock64()
+#else
+#define ABQ_TS(i)
+#define ABQ_TSS(i)
+#endif
 
 struct SkinnyParams {
-    const uint4* fields[3];   // per plane group
+    const u4v* fields[3];     // per plane group
     int chunks[3];
     const int8_t* a_codes;    // [M][Kp]
     const RowParams* aparams;
@@ -29,10 +43,15 @@ struct SkinnyParams {
     int32_t* acc;
     int M, N, K, Kp;
     int oa, ow;
-    int kseg;                 // k-extent of A staged in LDS at a time (multiple of 512)
-    int lds_stride;           // bytes per staged row (kseg + 16: rows land 16 B apart in bank space)
+    int ntiles;               // 16-row tiles of W
+    int nsuper;               // Kp / 512
+    int sc_q, sc_r;           // nsuper = sc_q * S + sc_r   (S = waves per workgroup): wave w owns sc_q + (w < sc_r) super-chunks
+    int tl_q, tl_r;           // ntiles = tl_q * gridDim.x + tl_r: workgroup b owns tl_q + (b < tl_r) tiles
+    int mrows;                // rows of A per workgroup (<= 16); blockIdx.y walks row groups
+    int a_stride;             // bytes per staged row of A (Kp + 16: rows land 16 B apart in bank space)
+    int par_off;              // byte offset in LDS of the staged per-row / per-channel parameters
+    int red_off;              // byte offset in LDS of the two reduction buffers
 };
-
 // Field t of a b-bit group as a signed-byte MFMA operand dword, and the power of two it is
 // scaled by.  The field that would touch the byte's sign bit is moved down one bit instead
 // (b = 2, 4) or taken as is with weight -128 (b = 1).
@@ -54,7 +73,7 @@ __device__ __forceinline__ int32_t field_unscale(int32_t acc)
 }
 
 template <int B, int T>
-__device__ __forceinline__ v4i field_operand(const uint4& w)
+__device__ __forceinline__ v4i field_operand(const u4v& w)
 {
     v4i r;
     r.x = (int)field_bytes<B, T>(w.x);
@@ -79,7 +98,7 @@ template <int P> struct GroupInfo {
 
 // MFMAs of one chunk (index I inside the super-chunk) of group width B: slices I*T .. I*T+T-1.
 template <int B, int I, int T0 = 0>
-__device__ __forceinline__ void chunk_mfma(const uint4& w, const v4i* aop, v4i* acc)
+__device__ __forceinline__ void chunk_mfma(const u4v& w, const v4i* aop, v4i* acc)
 {
     constexpr int T = 8 / B;
     if constexpr (T0 < T) {
@@ -88,7 +107,7 @@ __device__ __forceinline__ void chunk_mfma(const uint4& w, const v4i* aop, v4i* 
     }
 }
 template <int B, int I = 0>
-__device__ __forceinline__ void group_mfma(const uint4* w, const v4i* aop, v4i* acc)
+__device__ __forceinline__ void group_mfma(const u4v* w, const v4i* aop, v4i* acc)
 {
     if constexpr (I < B) {   // a b-bit group has b chunks per super-chunk
         chunk_mfma<B, I>(w[I], aop, acc);
@@ -108,131 +127,265 @@ __device__ __forceinline__ v4i group_combine(const v4i* acc)
     return r;
 }
 
+// One super-chunk of one tile: P wave loads of 1 KiB.  Every group stores whole super-chunks
+// (chunk count = b * Kp/512), so no load is conditional.
 template <int P>
-__device__ __forceinline__ void load_super(const SkinnyParams& prm, int nt, int sc, int lane, uint4* w)
+__device__ __forceinline__ void load_super(const SkinnyParams& prm, int nsuper, int tile, int sc, int lane, u4v* w)
 {
     using GI = GroupInfo<P>;
 #pragma unroll
     for (int g = 0; g < GI::NG; ++g) {
         const int b = GI::b(g);
+        const u4v* base = prm.fields[g] + ((size_t)tile * nsuper + sc) * (b * 64) + lane;
 #pragma unroll
-        for (int i = 0; i < b; ++i) {
-            const int c = sc * b + i;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (c < prm.chunks[g]) v = prm.fields[g][((size_t)nt * prm.chunks[g] + c) * 64 + lane];
-            w[GI::load_base(g) + i] = v;
-        }
+        for (int i = 0; i < b; ++i)   // read once: non-temporal, so the stream does not displace A and the parameters in L2
+            w[GI::load_base(g) + i] = __builtin_nontemporal_load(base + i * 64);
     }
 }
 
 template <int P>
-__device__ __forceinline__ void compute_super(const uint4* w, const uint8_t* lds_row, bool row_valid, v4i* acc)
+__device__ __forceinline__ void compute_super(const u4v* w, const uint8_t* lds_row, bool row_valid, v4i* acc)
 {
     using GI = GroupInfo<P>;
     v4i aop[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-        v4i v = {0, 0, 0, 0};
-        if (row_valid) v = *reinterpret_cast<const v4i*>(lds_row + j * 64);
-        aop[j] = v;
+        v4i v = *reinterpret_cast<const v4i*>(lds_row + j * 64);
+        aop[j] = row_valid ? v : v4i{0, 0, 0, 0};
     }
     group_mfma<GI::b(0)>(w + GI::load_base(0), aop, acc + GI::acc_base(0));
     if constexpr (GI::NG > 1) group_mfma<GI::b(1)>(w + GI::load_base(1), aop, acc + GI::acc_base(1));
     if constexpr (GI::NG > 2) group_mfma<GI::b(2)>(w + GI::load_base(2), aop, acc + GI::acc_base(2));
 }
 
+// Per-wave streaming state (lives in registers once everything is inlined).
 template <int P>
+struct WaveState {
+    int nsuper, S, nsw, nitems;
+    int tile0, tstride;            // this workgroup's tiles: tile0 + i * tstride
+    int p_ti, p_lsc;               // next item to prefetch
+    int ti, lsc, parity;           // item being consumed
+    int lane, wave, tid, m0;
+    bool row_valid;
+    const uint8_t* lds_lane;       // this lane's A operand base in LDS
+    const RowParams* par;          // LDS: [16] rows of A, then [nmy][16] channels
+    int32_t* red;
+    v4i acc[GroupInfo<P>::NACC];
+#ifdef ABQ_PHASE_TRACE
+    unsigned long long* ts;
+#endif
+};
+
+template <int P>
+__device__ __forceinline__ void prefetch_item(const SkinnyParams& prm, WaveState<P>& st, u4v* slot)
+{
+    load_super<P>(prm, st.nsuper, st.tile0 + st.p_ti * st.tstride, st.wave + st.p_lsc * st.S, st.lane, slot);
+    if (++st.p_lsc == st.nsw) { st.p_lsc = 0; ++st.p_ti; }
+}
+
+// End of a tile on this wave: bit reduction over the plane groups, sum over the S waves
+// through LDS (two buffers alternate, so one barrier per tile is enough), fused epilogue.
+template <int P, int EPT>
+__device__ __forceinline__ void finish_tile(const SkinnyParams& prm, WaveState<P>& st)
+{
+    using GI = GroupInfo<P>;
+    ABQ_TSS(3);
+    v4i total = group_combine<GI::b(0)>(st.acc + GI::acc_base(0));
+    if constexpr (GI::NG > 1) total += group_combine<GI::b(1)>(st.acc + GI::acc_base(1)) << GI::load_base(1);
+    if constexpr (GI::NG > 2) total += group_combine<GI::b(2)>(st.acc + GI::acc_base(2)) << GI::load_base(2);
+#pragma unroll
+    for (int i = 0; i < GI::NACC; ++i) st.acc[i] = v4i{0, 0, 0, 0};
+    int32_t* rb = st.red + st.parity * (st.S * 256);
+#pragma unroll
+    for (int reg = 0; reg < 4; ++reg) rb[(st.wave * 4 + reg) * 64 + st.lane] = total[reg];
+    ABQ_TSS(4);
+    __syncthreads();
+    ABQ_TSS(5);
+    // thread t finishes C elements e = t + i*blockDim < 256; element e is register e/64 of lane e%64:
+    // row 4*((e%64)/16) + e/64 of A, column e%16 of the tile (the 16x16 MFMA accumulator layout)
+    const int tile = st.tile0 + st.ti * st.tstride;
+    const int n = tile * kTileN + (st.tid & 15);
+    const RowParams pw = st.par[16 + st.ti * 16 + (st.tid & 15)];
+#pragma unroll
+    for (int i = 0; i < EPT; ++i) {
+        const int e = st.tid + i * (int)blockDim.x;
+        const int row = 4 * ((e & 63) >> 4) + (e >> 6);
+        const int m = st.m0 + row;
+        if ((EPT > 1 || e < 256) && m < prm.M && n < prm.N) {
+            int32_t part[8];
+#pragma unroll
+            for (int ww = 0; ww < 8; ++ww) part[ww] = ww < st.S ? rb[ww * 256 + e] : 0;   // independent reads, one wait
+            const int32_t s = ((part[0] + part[1]) + (part[2] + part[3])) + ((part[4] + part[5]) + (part[6] + part[7]));
+            epilogue_store(s, prm.oa, prm.ow, prm.K, st.par[row], pw, (size_t)m * prm.N + n, prm.y, prm.acc);
+        }
+    }
+    st.parity ^= 1;
+    st.lsc = 0;
+    ++st.ti;
+}
+
+template <int P, int EPT, bool REFILL>
+__device__ __forceinline__ void item_step(const SkinnyParams& prm, WaveState<P>& st, u4v* slot, bool refill)
+{
+    compute_super<P>(slot, st.lds_lane + (st.wave + st.lsc * st.S) * kSuperK, st.row_valid, st.acc);
+    if (REFILL) prefetch_item<P>(prm, st, slot);
+    else if (refill) prefetch_item<P>(prm, st, slot);
+    if (++st.lsc == st.nsw) finish_tile<P, EPT>(prm, st);
+}
+
+// D = super-chunks of weight loads each wave keeps in flight; EPT = C elements per thread in
+// the epilogue (1 for >= 4 waves, 2 for two waves, 4 for one).
+template <int P, int D, int EPT>
 __global__ __launch_bounds__(512) void skinny_kernel(SkinnyParams prm)
 {
     using GI = GroupInfo<P>;
     extern __shared__ __align__(16) uint8_t lds[];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nwaves = blockDim.x >> 6;
-    const int nt = blockIdx.x;
-    const int m0 = blockIdx.y * 16;
-    const int mt = min(16, prm.M - m0);
-    const int r = lane & 15, G = lane >> 4;
-    const bool row_valid = r < mt;
-    const int nsuper = prm.Kp / kSuperK;
+    WaveState<P> st;
+    st.tid = threadIdx.x; st.lane = st.tid & 63; st.wave = st.tid >> 6; st.S = blockDim.x >> 6;
+    st.m0 = blockIdx.y * prm.mrows;
+    const int mt = min(prm.mrows, prm.M - st.m0);
+    const int r = st.lane & 15, G = st.lane >> 4;
+    st.row_valid = r < mt;
+    st.nsuper = prm.nsuper;
+    st.tile0 = blockIdx.x; st.tstride = gridDim.x;
+    st.p_ti = 0; st.p_lsc = 0; st.ti = 0; st.lsc = 0; st.parity = 0;
+#ifdef ABQ_PHASE_TRACE
+    unsigned long long ts[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    st.ts = ts;
+#endif
+    ABQ_TS(0);
 
-    v4i acc[GI::NACC];
+    // ---- the stream starts before anything else: first item = (tile0, super-chunk `wave`)
+    u4v w[D][P];
+    load_super<P>(prm, st.nsuper, st.tile0, st.wave, st.lane, w[0]);
+    st.nsw = prm.sc_q + (st.wave < prm.sc_r ? 1 : 0);                       // this wave's super-chunks per tile (>= 1)
+    const int nmy = prm.tl_q + ((int)blockIdx.x < prm.tl_r ? 1 : 0);         // this workgroup's tiles (>= 1)
+    st.nitems = nmy * st.nsw;
+    if (++st.p_lsc == st.nsw) { st.p_lsc = 0; ++st.p_ti; }
 #pragma unroll
-    for (int i = 0; i < GI::NACC; ++i) acc[i] = v4i{0, 0, 0, 0};
+    for (int d = 1; d < D; ++d)
+        if (d < st.nitems) prefetch_item<P>(prm, st, w[d]);
 
-    // epilogue operands are fetched up front so that their latency hides under the stream
-    RowParams ep_a = {0, 0.0f, 0, 0}, ep_w = {0, 0.0f, 0, 0};
-    const int ep_m = m0 + 4 * ((tid & 63) >> 4) + (tid >> 6);   // thread tid < 256 finishes C register tid/64 of lane tid%64
-    const int ep_n = nt * kTileN + (tid & 15);
-    const bool ep_valid = tid < 256 && ep_m < prm.M && ep_n < prm.N;
-    if (ep_valid) { ep_a = prm.aparams[ep_m]; ep_w = prm.wparams[ep_n]; }
+    // ---- epilogue parameters: entry i < 16 is row m0+i of A, entry 16 + 16*t + c is channel c of this
+    // workgroup's t-th tile.  Loads use clamped indices so that none is conditional.
+    RowParams* par = reinterpret_cast<RowParams*>(lds + prm.par_off);
+    const int npar = 16 + nmy * 16;
+    auto load_par = [&](int i) -> RowParams {
+        const RowParams* src = i < 16 ? prm.aparams + min(st.m0 + i, prm.M - 1)
+                                      : prm.wparams + min((st.tile0 + ((i - 16) >> 4) * st.tstride) * kTileN + (i & 15), prm.N - 1);
+        return *src;   // one unconditional load
+    };
+    const RowParams par_first = load_par(min(st.tid, npar - 1));
 
-    const int super_per_seg = prm.kseg / kSuperK;
-    for (int seg0 = 0; seg0 < nsuper; seg0 += super_per_seg) {
-        const int seg1 = min(nsuper, seg0 + super_per_seg);
-        const int vec_per_row = (seg1 - seg0) * (kSuperK / 16);
-        const int nvec = mt * vec_per_row;
-        const int8_t* a_seg = prm.a_codes + (size_t)m0 * prm.Kp + (size_t)seg0 * kSuperK;
-        // order of issue: first slice of A, then this wave's first weight loads, so that waiting
-        // for A leaves the weight loads in flight
-        uint4 a_first = make_uint4(0, 0, 0, 0);
-        if (tid < nvec) a_first = *reinterpret_cast<const uint4*>(a_seg + (size_t)(tid / vec_per_row) * prm.Kp + (tid % vec_per_row) * 16);
-        uint4 wa[P], wb[P];
-        int sc = seg0 + wave;
-        if (sc < seg1) load_super<P>(prm, nt, sc, lane, wa);
-        if (seg0 > 0) __syncthreads();   // every wave is done reading the previous segment
-        if (tid < nvec) *reinterpret_cast<uint4*>(lds + (tid / vec_per_row) * prm.lds_stride + (tid % vec_per_row) * 16) = a_first;
-        for (int i = tid + blockDim.x; i < nvec; i += blockDim.x) {
-            const int row = i / vec_per_row, col = (i % vec_per_row) * 16;
-            *reinterpret_cast<uint4*>(lds + row * prm.lds_stride + col) =
-                *reinterpret_cast<const uint4*>(a_seg + (size_t)row * prm.Kp + col);
+    // ---- stage this wave's part of A: columns of its own super-chunks, in every row (wave-private:
+    // only this wave reads what it writes, so no barrier is needed before the first MFMA).
+    // A load instruction covers two super-chunks of one row (2 x 32 vectors of 16 B).
+    const int8_t* a_base = prm.a_codes + (size_t)st.m0 * prm.Kp;
+    const int half = st.lane >> 5, vec = st.lane & 31;
+    for (int pr = 0; pr < st.nsw; pr += 2) {
+        const bool lv = pr + half < st.nsw;
+        const int col = (st.wave + min(pr + half, st.nsw - 1) * st.S) * kSuperK + vec * 16;
+        for (int row0 = 0; row0 < mt; row0 += 4) {
+            uint4 areg[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                areg[u] = *reinterpret_cast<const uint4*>(a_base + (size_t)min(row0 + u, mt - 1) * prm.Kp + col);
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (lv && row0 + u < mt) *reinterpret_cast<uint4*>(lds + (row0 + u) * prm.a_stride + col) = areg[u];
         }
-        __syncthreads();
-        const uint8_t* lds_lane = lds + r * prm.lds_stride + G * 16;
-        // double-buffered stream over this wave's super-chunks
-        for (; sc < seg1; sc += 2 * nwaves) {
-            const int sc_b = sc + nwaves;
-            if (sc_b < seg1) load_super<P>(prm, nt, sc_b, lane, wb);
-            compute_super<P>(wa, lds_lane + (sc - seg0) * kSuperK, row_valid, acc);
-            if (sc_b < seg1) {
-                const int sc_c = sc_b + nwaves;
-                if (sc_c < seg1) load_super<P>(prm, nt, sc_c, lane, wa);
-                compute_super<P>(wb, lds_lane + (sc_b - seg0) * kSuperK, row_valid, acc);
+    }
+    if (st.tid < npar) par[st.tid] = par_first;
+    for (int i = st.tid + blockDim.x; i < npar; i += blockDim.x) par[i] = load_par(i);
+    // same-wave LDS accesses execute in order; keep the compiler from moving the operand reads above
+    // the staging writes (the parameters are read only after the first per-tile barrier)
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    ABQ_TS(1);
+#ifdef ABQ_PHASE_TRACE
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    ABQ_TS(2);
+#endif
+
+    st.lds_lane = lds + min(r, mt - 1) * prm.a_stride + G * 16;   // rows past mt re-read a valid row; their operand is zeroed
+    st.par = par;
+    st.red = reinterpret_cast<int32_t*>(lds + prm.red_off);
+#pragma unroll
+    for (int i = 0; i < GI::NACC; ++i) st.acc[i] = v4i{0, 0, 0, 0};
+
+    int it = 0;
+    if (nmy == 1) {
+        // One tile per workgroup (the usual case): the K loop holds loads only, so the compiler's
+        // waits are exact and P*(D-1) loads stay in flight; the tile is finished after the loop.
+        for (; it + 2 * D <= st.nitems; it += D) {
+#pragma unroll
+            for (int d = 0; d < D; ++d) {
+                compute_super<P>(w[d], st.lds_lane + (st.wave + st.lsc * st.S) * kSuperK, st.row_valid, st.acc);
+                prefetch_item<P>(prm, st, w[d]);
+                ++st.lsc;
             }
         }
-    }
-
-    // bit reduction across the plane groups of this wave
-    v4i total = group_combine<GI::b(0)>(acc + GI::acc_base(0));
-    if constexpr (GI::NG > 1) {
-        v4i t1 = group_combine<GI::b(1)>(acc + GI::acc_base(1));
-        total += t1 << GroupInfo<P>::load_base(1);
-    }
-    if constexpr (GI::NG > 2) {
-        v4i t2 = group_combine<GI::b(2)>(acc + GI::acc_base(2));
-        total += t2 << GroupInfo<P>::load_base(2);
-    }
-
-    // sum over the waves (split K) through LDS, then the fused epilogue
-    __syncthreads();
-    int32_t* red = reinterpret_cast<int32_t*>(lds);
+        for (; it < st.nitems; it += D) {
 #pragma unroll
-    for (int reg = 0; reg < 4; ++reg) red[(wave * 4 + reg) * 64 + lane] = total[reg];
-    __syncthreads();
-    if (tid < 256) {
-        int32_t s = 0;
-        for (int w = 0; w < nwaves; ++w) s += red[w * 256 + tid];
-        // MFMA C layout: lane l, register reg holds row 4*(l/16)+reg (A side: m), column l%16 (B side: n);
-        // thread tid sums register tid/64 of lane tid%64
-        if (ep_valid) epilogue_store(s, prm.oa, prm.ow, prm.K, ep_a, ep_w, (size_t)ep_m * prm.N + ep_n, prm.y, prm.acc);
+            for (int d = 0; d < D; ++d)
+                if (it + d < st.nitems) {
+                    compute_super<P>(w[d], st.lds_lane + (st.wave + st.lsc * st.S) * kSuperK, st.row_valid, st.acc);
+                    if (it + d + D < st.nitems) prefetch_item<P>(prm, st, w[d]);
+                    ++st.lsc;
+                }
+        }
+        finish_tile<P, EPT>(prm, st);
+    } else {
+        // Several tiles per workgroup: the ring runs ahead across tile boundaries.
+        for (; it + 2 * D <= st.nitems; it += D) {
+#pragma unroll
+            for (int d = 0; d < D; ++d) item_step<P, EPT, true>(prm, st, w[d], true);
+        }
+        for (; it < st.nitems; it += D) {
+#pragma unroll
+            for (int d = 0; d < D; ++d)
+                if (it + d < st.nitems) item_step<P, EPT, false>(prm, st, w[d], it + d + D < st.nitems);
+        }
     }
+#ifdef ABQ_PHASE_TRACE
+    ABQ_TS(6);
+    if (st.lane == 0 && blockIdx.x < 1024 && st.wave < 8)
+        for (int i = 0; i < 8; ++i) g_phase_trace[((size_t)blockIdx.x * 8 + st.wave) * 8 + i] = ts[i];
+#endif
 }
 
-// Waves per workgroup (4..8): as many as there are super-chunks to split when K is short (one
-// memory round trip), otherwise the count that leaves the fewest idle wave-slots.
-static int pick_waves(int nsuper)
+// ---- host side -------------------------------------------------------------------------------------
+
+static int g_num_cus = 0;
+
+static int num_cus()
 {
-    if (nsuper <= 8) return nsuper < 4 ? 4 : nsuper;
-    int best = 8, best_waste = 1 << 30;
-    for (int w = 8; w >= 4; --w) {
+    if (g_num_cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+            g_num_cus = n;
+        else
+            g_num_cus = 256;
+    }
+    return g_num_cus;
+}
+
+// The kernels use up to 256 VGPRs, i.e. two waves per SIMD, eight per CU.
+static const int kWavesPerCu = 8;
+
+// Waves per workgroup (= K split of a tile).  All workgroups should be resident at once, so that
+// uneven tile counts per CU even out through shared bandwidth: S <= 8*CUs/tiles.  Within that,
+// 4..8 waves are chosen to leave the fewest idle wave-slots in the last round over K.
+static int pick_waves(int nsuper, int ntiles, int cus)
+{
+    int smax = kWavesPerCu * cus / ntiles;
+    if (smax > 8) smax = 8;
+    if (smax > nsuper) smax = nsuper;
+    if (smax <= 1) return 1;
+    if (smax <= 3) return 2;
+    int best = smax, best_waste = 1 << 30;
+    for (int w = smax; w >= 4; --w) {
         const int rounds = (nsuper + w - 1) / w;
         const int waste = rounds * w - nsuper;
         if (waste < best_waste) { best_waste = waste; best = w; }
@@ -240,24 +393,32 @@ static int pick_waves(int nsuper)
     return best;
 }
 
-template <int P>
-static hipError_t launch_p(const SkinnyParams& prm, dim3 grid, int waves, size_t lds_bytes, hipStream_t s)
+template <int P, int D, int EPT>
+static hipError_t launch_pde(const SkinnyParams& prm, dim3 grid, int waves, size_t lds_bytes, hipStream_t s)
 {
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)skinny_kernel<P>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        hipError_t e = hipFuncSetAttribute((const void*)skinny_kernel<P, D, EPT>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    skinny_kernel<P><<<grid, waves * 64, lds_bytes, s>>>(prm);
+    skinny_kernel<P, D, EPT><<<grid, waves * 64, lds_bytes, s>>>(prm);
     return hipGetLastError();
+}
+
+template <int P, int D>
+static hipError_t launch_pd(const SkinnyParams& prm, dim3 grid, int waves, size_t lds_bytes, hipStream_t s)
+{
+    if (waves >= 4) return launch_pde<P, D, 1>(prm, grid, waves, lds_bytes, s);
+    if (waves == 2) return launch_pde<P, D, 2>(prm, grid, waves, lds_bytes, s);
+    return launch_pde<P, D, 4>(prm, grid, waves, lds_bytes, s);
 }
 
 hipError_t launch_gemm_skinny(const GemmArgs& g, const ActLayout& A, const WeightLayout& W, hipStream_t s)
 {
     SkinnyParams prm;
     for (int i = 0; i < 3; ++i) {
-        prm.fields[i] = (const uint4*)(g.w_blob + W.off_fields[i]);
+        prm.fields[i] = (const u4v*)(g.w_blob + W.off_fields[i]);
         prm.chunks[i] = W.chunks[i];
     }
     prm.a_codes = (const int8_t*)(g.act_blob + A.off_codes);
@@ -268,29 +429,40 @@ hipError_t launch_gemm_skinny(const GemmArgs& g, const ActLayout& A, const Weigh
     prm.M = g.M; prm.N = g.N; prm.K = g.K; prm.Kp = A.Kp;
     prm.oa = (g.q == 8) ? 128 : 0;
     prm.ow = (g.p == 8) ? 128 : 0;
+    prm.ntiles = W.NT;
+    const int cus = num_cus();
     const int nsuper = A.Kp / kSuperK;
-    const int waves = pick_waves(nsuper);
-    const int mt = g.M < 16 ? g.M : 16;
-    // LDS: staged rows (<= 128 KiB) and, afterwards, the 1 KiB per wave reduction buffer
-    const int budget = 128 * 1024;
-    int super_per_seg = (budget / mt - 16) / kSuperK;
-    if (super_per_seg > nsuper) super_per_seg = nsuper;
-    if (super_per_seg < 1) super_per_seg = 1;
-    prm.kseg = super_per_seg * kSuperK;
-    prm.lds_stride = prm.kseg + 16;
-    size_t lds_bytes = (size_t)mt * prm.lds_stride;
-    const size_t red_bytes = (size_t)waves * 1024;
-    if (lds_bytes < red_bytes) lds_bytes = red_bytes;
-    dim3 grid((unsigned)W.NT, (unsigned)((g.M + 15) / 16));
+    const int waves = pick_waves(nsuper, W.NT, cus);
+    // grid: every tile its own workgroup while they can all be resident, else a resident set that walks the tiles
+    int gx = W.NT;
+    const int resident = cus * (kWavesPerCu / waves);
+    if (gx > resident) gx = resident;
+    const int nmy_max = (W.NT + gx - 1) / gx;
+    // LDS: staged rows of A (all of K), the epilogue parameters, two reduction buffers of 1 KiB per wave
+    const size_t par_bytes = (size_t)(16 + nmy_max * 16) * sizeof(RowParams);
+    const size_t red_bytes = 2 * (size_t)waves * 1024;
+    const size_t budget = 160 * 1024 - red_bytes - par_bytes - 64;
+    prm.a_stride = A.Kp + 16;
+    int mrows = g.M < 16 ? g.M : 16;
+    if ((size_t)mrows * prm.a_stride > budget) mrows = (int)(budget / prm.a_stride);
+    if (mrows < 1) return hipErrorInvalidValue;   // cannot happen for K <= ABQ_MAX_K
+    prm.mrows = mrows;
+    prm.par_off = (int)align_up((size_t)mrows * prm.a_stride, 16);
+    prm.red_off = prm.par_off + (int)par_bytes;
+    const size_t lds_bytes = prm.red_off + red_bytes;
+    prm.nsuper = nsuper;
+    prm.sc_q = nsuper / waves; prm.sc_r = nsuper % waves;
+    prm.tl_q = W.NT / gx; prm.tl_r = W.NT % gx;
+    dim3 grid((unsigned)gx, (unsigned)((g.M + mrows - 1) / mrows));
     switch (g.p) {
-        case 1: return launch_p<1>(prm, grid, waves, lds_bytes, s);
-        case 2: return launch_p<2>(prm, grid, waves, lds_bytes, s);
-        case 3: return launch_p<3>(prm, grid, waves, lds_bytes, s);
-        case 4: return launch_p<4>(prm, grid, waves, lds_bytes, s);
-        case 5: return launch_p<5>(prm, grid, waves, lds_bytes, s);
-        case 6: return launch_p<6>(prm, grid, waves, lds_bytes, s);
-        case 7: return launch_p<7>(prm, grid, waves, lds_bytes, s);
-        default: return launch_p<8>(prm, grid, waves, lds_bytes, s);
+        case 1: return launch_pd<1, 8>(prm, grid, waves, lds_bytes, s);
+        case 2: return launch_pd<2, 8>(prm, grid, waves, lds_bytes, s);
+        case 3: return launch_pd<3, 4>(prm, grid, waves, lds_bytes, s);
+        case 4: return launch_pd<4, 4>(prm, grid, waves, lds_bytes, s);
+        case 5: return launch_pd<5, 2>(prm, grid, waves, lds_bytes, s);
+        case 6: return launch_pd<6, 2>(prm, grid, waves, lds_bytes, s);
+        case 7: return launch_pd<7, 2>(prm, grid, waves, lds_bytes, s);
+        default: return launch_pd<8, 2>(prm, grid, waves, lds_bytes, s);
     }
 }
 
