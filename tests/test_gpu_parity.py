@@ -94,6 +94,24 @@ def test_shapes(abq, layout, M, N, K, p, q):
     check_against_oracle(c, y, acc)
 
 
+TILED_SHAPES = [(65, 40, 700), (128, 128, 512), (200, 150, 1100), (129, 257, 64), (300, 16, 2048), (257, 130, 1536)]
+
+
+@pytest.mark.parametrize("M,N,K", TILED_SHAPES)
+@pytest.mark.parametrize("p,q", [(1, 1), (2, 8), (3, 3), (4, 8), (5, 5), (6, 6), (7, 7), (8, 8), (8, 2)])
+def test_prefill_shapes(abq, M, N, K, p, q):
+    say("prefill shape", M, N, K, p, q)
+    c = synth.make_case(p, q, M, N, K, seed=synth.case_seed(7, p, q) + M + N + K, name=f"W{p}A{q} {M}x{N}x{K}")
+    y, acc = gpu_gemm(torch, abq, c, FIELDS, FIELDS)
+    check_against_oracle(c, y, acc)
+
+
+def test_prefill_bitserial(abq):
+    c = synth.make_case(3, 5, 70, 50, 600, seed=123)
+    y, acc = gpu_gemm(torch, abq, c, PLANES, PLANES)
+    check_against_oracle(c, y, acc)
+
+
 def test_both_layout_and_forced_family(abq):
     c = synth.make_case(4, 8, 2, 48, 1024, seed=77)
     for flag in (0, 0x10, 0x20):
@@ -177,3 +195,17 @@ def test_quantize_then_gemm_end_to_end(abq):
     y, acc = abq.abq_gemm(p, q, M, N, K, pa, FIELDS, pw, FIELDS, want_acc=True)
     torch.cuda.synchronize()
     check_against_oracle(c, y.cpu().numpy(), acc.cpu().numpy())
+
+
+@pytest.mark.parametrize("M", [128, 512])
+def test_config4_w6a6_gemm_sampled(abq, M):
+    c = synth.config4(M)
+    y, acc = gpu_gemm(torch, abq, c, FIELDS, FIELDS)
+    check_sampled(c, y, acc)
+
+
+@pytest.mark.parametrize("p,q,shape_idx,m_idx", [(4, 8, 0, 1), (2, 4, 1, 2), (8, 8, 0, 2), (3, 8, 1, 0), (1, 1, 0, 2)])
+def test_config5_sweep_samples(abq, p, q, shape_idx, m_idx):
+    c = synth.config5(p, q, shape_idx, m_idx)
+    y, acc = gpu_gemm(torch, abq, c, FIELDS, FIELDS)
+    check_sampled(c, y, acc)
