@@ -1,14 +1,16 @@
 // Prefill-shaped matmul (M > 64): a dense int8 contraction on the 16x16x64 MFMA.
 //
-// Workgroup tile 128 (rows of A) x 128 (rows of W), four waves side by side along N, each owning
-// two 16-row tiles of W for all 128 rows of A (8 x 2 accumulator tiles).  The packed weight
+// Workgroup tile 128 (rows of A) x 256 (rows of W), four waves side by side along N, each owning
+// four 16-row tiles of W for all 128 rows of A (8 x 4 accumulator tiles; one wave per SIMD, so the
+// whole 512-entry register file is the wave's).  The packed weight
 // plane groups go from HBM straight into registers in the same tiled layout the decode kernel
 // streams (one super-chunk of 512 k ahead) and are expanded there: for every 64-k slice the
 // fields of all groups are shifted to their bit position and OR-ed into one signed byte per
 // weight, so a slice costs one MFMA per accumulator tile whatever p is.  (This is the bit
 // reduction of Sec. 3.4 step 5 / Appendix B folded into the operand: the 2^s factors are bit
 // positions inside the byte, the 2^t factors are the activation code itself.)  The rows of A
-// pass through LDS in 128-k steps, double buffered, one barrier per step.  The dequant epilogue
+// go from global memory straight into LDS (direct 128-bit loads) in 256-k steps, double buffered,
+// one barrier per step.  The dequant epilogue
 // is fused (Fig. 3b).
 #include "abq_internal.h"
 #include "../../include/abq.h"
@@ -18,8 +20,9 @@ namespace abq {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef unsigned int u4v __attribute__((ext_vector_type(4)));
 
-constexpr int kBM = 128, kBN = 128, kStepK = 128;
-constexpr int kARow = kStepK + 16;   // LDS row stride: the 16 rows of an operand read fall into distinct 16-B bank groups
+constexpr int kNTW = 4;                                   // 16-row tiles of W per wave
+constexpr int kBM = 128, kBN = 4 * kNTW * kTileN, kStepK = 256;   // one step = one phase = four 64-k slices
+constexpr int kARow = kStepK;        // LDS row stride (unpadded; the 16-B vectors of a row are XOR-swizzled by the row index)
 
 struct TiledParams {
     const u4v* fields[3];
@@ -30,16 +33,28 @@ struct TiledParams {
     int32_t* acc;
     int M, N, K, Kp, nsuper, ntiles;
     int oa, ow;
+    int tiles_m, tiles_n;     // workgroup tiles along M and N (1-D grid of tiles_m * tiles_n workgroups)
 };
 
+// Weights are held one phase (half a super-chunk, 256 k, four 64-k slices) at a time.  A b-bit
+// group needs max(b/2, 1) of its 1 KiB chunks per phase (a 1-bit chunk spans both phases and is
+// simply fetched for each).
+__host__ __device__ constexpr int phase_chunks(int b) { return b >= 2 ? b / 2 : 1; }
+__host__ __device__ constexpr int phase_base(int p, int g)
+{
+    return g == 0 ? 0 : (g == 1 ? phase_chunks(group_width(p, 0)) : phase_chunks(group_width(p, 0)) + phase_chunks(group_width(p, 1)));
+}
+__host__ __device__ constexpr int phase_regs(int p) { return phase_base(p, group_count(p) - 1) + phase_chunks(group_width(p, group_count(p) - 1)); }
+
 // Operand dword of k-slice `SL` (0..7 inside a super-chunk) for one 16-row tile: all plane groups
-// merged into one byte per weight.
+// merged into one byte per weight.  `w` is the tile's register set of the phase SL/4.
 template <int P, int SL, int G0 = 0>
 __device__ __forceinline__ uint32_t merged_dword(const u4v* w, int j)
 {
     constexpr int b = group_width(P, G0), shift = group_shift(P, G0), T = 8 / b;
     constexpr int chunk = SL / T, t = SL % T;
-    const uint32_t x = w[shift + chunk][j];   // the group's chunks start at index `shift` (= sum of lower widths)
+    constexpr int local = b == 1 ? 0 : chunk - phase_chunks(b) * (SL / 4);
+    const uint32_t x = w[phase_base(P, G0) + local][j];
     uint32_t v;
     if constexpr (b == 8) {
         v = x;
@@ -65,33 +80,64 @@ __device__ __forceinline__ v4i merged_operand(const u4v* w)
     return r;
 }
 
-template <int P, int SL>
-__device__ __forceinline__ void slice_mfma(const u4v (*w)[P], const uint8_t* a_lane, v4i (*acc)[2])
+// A tile in LDS: [128 rows][16 vectors of 16 B], vector v of row `row` stored at position v ^ (row & 15),
+// so that the 16 rows an operand read touches (same v) land in 16 different 16-byte bank groups.
+// Lane (r = lane%16, G = lane/16) reads, for m-tile mt and slice sl, vector 4*sl + G of row 16*mt + r.
+__device__ __forceinline__ void read_a_operands(const uint8_t* a_buf, int r, int G, int sl, v4i* aop)
 {
-    // a_lane: this lane's A operand address for m-tile 0 of the slice; m-tiles are 16 rows apart
-    v4i aop[8];
+    const uint8_t* p = a_buf + r * kARow + (((4 * sl + G) ^ r) << 4);
 #pragma unroll
-    for (int mt = 0; mt < 8; ++mt) aop[mt] = *reinterpret_cast<const v4i*>(a_lane + mt * 16 * kARow);
+    for (int mt = 0; mt < 8; ++mt) aop[mt] = *reinterpret_cast<const v4i*>(p + mt * 16 * kARow);
+}
+
+template <int P, int SL>
+__device__ __forceinline__ void slice_mfma(const u4v (*w)[phase_regs(P)], const v4i* aop, v4i (*acc)[kNTW])
+{
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt) {
+    for (int nt = 0; nt < kNTW; ++nt) {
         const v4i bop = merged_operand<P, SL>(w[nt]);
 #pragma unroll
         for (int mt = 0; mt < 8; ++mt) acc[mt][nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[mt], bop, acc[mt][nt], 0, 0, 0);
     }
 }
 
-template <int P>
-__device__ __forceinline__ void load_tiles(const TiledParams& prm, int tile0, int sc, int lane, u4v (*w)[P])
+// The four 64-k slices of one step (phase PH of a super-chunk): the A operands of two slices are
+// requested from LDS, then their 2 x 32 MFMAs run as one uninterrupted burst.  The scheduling
+// barriers pin that order: left alone, the machine scheduler sinks the reads next to their uses
+// and the matrix pipe (one wave per SIMD, nobody else to feed it) idles on every wait.
+template <int P, int PH>
+__device__ __forceinline__ void step_mfma(const u4v (*w)[phase_regs(P)], const uint8_t* a_buf, int r, int G, v4i (*acc)[kNTW])
 {
+    v4i a0[8], a1[8];
+    read_a_operands(a_buf, r, G, 0, a0);
+    read_a_operands(a_buf, r, G, 1, a1);
+    __builtin_amdgcn_sched_barrier(0);
+    slice_mfma<P, 4 * PH + 0>(w, a0, acc);
+    slice_mfma<P, 4 * PH + 1>(w, a1, acc);
+    __builtin_amdgcn_sched_barrier(0);
+    read_a_operands(a_buf, r, G, 2, a0);
+    read_a_operands(a_buf, r, G, 3, a1);
+    __builtin_amdgcn_sched_barrier(0);
+    slice_mfma<P, 4 * PH + 2>(w, a0, acc);
+    slice_mfma<P, 4 * PH + 3>(w, a1, acc);
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+// Loads phase `ph` (0 or 1) of super-chunk `sc` for this wave's tiles.
+template <int P>
+__device__ __forceinline__ void load_tiles(const TiledParams& prm, int tile0, int sc, int ph, int lane, u4v (*w)[phase_regs(P)])
+{
+    // tile0, sc and ph are wave-uniform: the chunk base is a scalar address, the lane adds 16*lane
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt) {
+    for (int nt = 0; nt < kNTW; ++nt) {
         const int tile = min(tile0 + nt, prm.ntiles - 1);   // past the last tile: re-read a valid one, never stored
 #pragma unroll
         for (int g = 0; g < group_count(P); ++g) {
-            const int b = group_width(P, g);
-            const u4v* base = prm.fields[g] + ((size_t)tile * prm.nsuper + sc) * (b * 64) + lane;
+            const int b = group_width(P, g), cpp = phase_chunks(b);
+            const int first = b == 1 ? 0 : cpp * ph;
+            const u4v* base = prm.fields[g] + (((size_t)tile * prm.nsuper + sc) * b + first) * 64;
 #pragma unroll
-            for (int i = 0; i < b; ++i) w[nt][group_shift(P, g) + i] = base[i * 64];
+            for (int i = 0; i < cpp; ++i) w[nt][phase_base(P, g) + i] = base[i * 64 + lane];
         }
     }
 }
@@ -99,82 +145,84 @@ __device__ __forceinline__ void load_tiles(const TiledParams& prm, int tile0, in
 template <int P>
 __global__ __launch_bounds__(256) void tiled_kernel(TiledParams prm)
 {
-    __shared__ __align__(16) uint8_t lds_a[2][kBM * kARow];
+    __shared__ __align__(16) uint8_t lds_a0[kBM * kARow];   // two separate objects: the loads that fill one must
+    __shared__ __align__(16) uint8_t lds_a1[kBM * kARow];   // not be taken to alias the reads of the other
     __shared__ RowParams par_a[kBM], par_w[kBN];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps the weight addresses scalar
     const int r = lane & 15, G = lane >> 4;
-    const int m0 = blockIdx.y * kBM, n0 = blockIdx.x * kBN;
-    const int tile0 = blockIdx.x * (kBN / kTileN) + wave * 2;
+    // Workgroup b runs on XCD b % 8 (round-robin dispatch) and each XCD has its own L2.  Give every
+    // XCD a contiguous run of the tile order, M fastest: the workgroups resident on one XCD then share
+    // a few column blocks of W and all row blocks of A through that L2 instead of each fetching its own.
+    const int nwg = prm.tiles_m * prm.tiles_n;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int per = nwg >> 3, rem = nwg & 7;                     // XCD x owns per + (x < rem) workgroups
+    const int vid = xcd * per + min(xcd, rem) + slot;
+    const int m_blk = vid % prm.tiles_m, n_blk = vid / prm.tiles_m;
+    const int m0 = m_blk * kBM, n0 = n_blk * kBN;
+    const int tile0 = n_blk * (kBN / kTileN) + wave * kNTW;
 
-    // weights of super-chunk 0
-    u4v wa[2][P], wb[2][P];
-    load_tiles<P>(prm, tile0, 0, lane, wa);
+    // weights of the first phase
+    u4v wa[kNTW][phase_regs(P)], wb[kNTW][phase_regs(P)];
+    load_tiles<P>(prm, tile0, 0, 0, lane, wa);
 
     // epilogue parameters
     if (tid < kBM) par_a[tid] = prm.aparams[min(m0 + tid, prm.M - 1)];
-    else par_w[tid - kBM] = prm.wparams[min(n0 + tid - kBM, prm.N - 1)];
+    for (int i = tid; i < kBN; i += 256) par_w[i] = prm.wparams[min(n0 + i, prm.N - 1)];
 
-    // A tile of one 128-k step: 128 rows x 8 vectors of 16 B; thread t moves vectors t, t+256, t+512, t+768
-    int a_row[4], a_vec[4];
-    bool a_ok[4];
+    // A tile of one 256-k step goes from global memory straight into LDS (128-bit direct loads, no
+    // registers in between): wave w issues loads j = 8w .. 8w+7, load j fills rows 4j .. 4j+3 (1 KiB,
+    // lane L -> LDS position 16*L of that KiB = row 4j + L/16, position L%16, which holds vector
+    // (L%16) ^ (row & 15) of the row).  Rows past M re-read row M-1; their outputs are never stored.
+    unsigned a_goff[8];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        const int idx = tid + 256 * u;
-        a_row[u] = idx >> 3; a_vec[u] = idx & 7;
-        a_ok[u] = m0 + a_row[u] < prm.M;
+    for (int u = 0; u < 8; ++u) {
+        const int row = 4 * (wave * 8 + u) + (lane >> 4);
+        const int vec = (lane & 15) ^ (row & 15);
+        a_goff[u] = (unsigned)(min(m0 + row, prm.M - 1) - m0) * (unsigned)prm.Kp + vec * 16;
     }
-    const int8_t* a_src[4];
+    const int8_t* a_tile = prm.a_codes + (size_t)m0 * prm.Kp;   // uniform
+    auto a_prefetch = [&](int step, uint8_t* buf) {
+        const int8_t* base = a_tile + (size_t)step * kStepK;     // uniform
 #pragma unroll
-    for (int u = 0; u < 4; ++u) a_src[u] = prm.a_codes + (size_t)min(m0 + a_row[u], prm.M - 1) * prm.Kp + a_vec[u] * 16;
-    uint4 areg[4];
-    auto a_load = [&](int step) {
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const uint4 v = *reinterpret_cast<const uint4*>(a_src[u] + (size_t)step * kStepK);
-            areg[u] = a_ok[u] ? v : make_uint4(0, 0, 0, 0);
-        }
-    };
-    auto a_store = [&](int buf) {
-#pragma unroll
-        for (int u = 0; u < 4; ++u) *reinterpret_cast<uint4*>(&lds_a[buf][a_row[u] * kARow + a_vec[u] * 16]) = areg[u];
+        for (int u = 0; u < 8; ++u)
+            __builtin_amdgcn_global_load_lds((const void*)(base + a_goff[u]),
+                                             (__attribute__((address_space(3))) void*)(buf + (wave * 8 + u) * 1024), 16, 0, 0);
     };
 
-    v4i acc[8][2];
+    v4i acc[8][kNTW];
 #pragma unroll
     for (int mt = 0; mt < 8; ++mt)
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt) acc[mt][nt] = v4i{0, 0, 0, 0};
+        for (int nt = 0; nt < kNTW; ++nt) acc[mt][nt] = v4i{0, 0, 0, 0};
 
-    a_load(0);
-    a_store(0);
-    __syncthreads();
+    a_prefetch(0, lds_a0);
+    __syncthreads();   // (the compiler waits for the direct loads before the barrier)
 
-    const int nsteps = prm.nsuper * 4;
-    // one super-chunk (4 steps of 128 k, 8 slices of 64 k) per iteration; weights one super-chunk ahead
-    auto super_chunk = [&](const u4v (*wc)[P], u4v (*wn)[P], int sc) {
-        if (sc + 1 < prm.nsuper) load_tiles<P>(prm, tile0, sc + 1, lane, wn);
-#pragma unroll
-        for (int st = 0; st < 4; ++st) {
-            const int step = sc * 4 + st, buf = st & 1;   // 4 steps per super-chunk: the buffer parity is static
-            if (step + 1 < nsteps) a_load(step + 1);
-            const uint8_t* a_lane = &lds_a[buf][r * kARow + G * 16];
-            if (st == 0) { slice_mfma<P, 0>(wc, a_lane, acc); slice_mfma<P, 1>(wc, a_lane + 64, acc); }
-            if (st == 1) { slice_mfma<P, 2>(wc, a_lane, acc); slice_mfma<P, 3>(wc, a_lane + 64, acc); }
-            if (st == 2) { slice_mfma<P, 4>(wc, a_lane, acc); slice_mfma<P, 5>(wc, a_lane + 64, acc); }
-            if (st == 3) { slice_mfma<P, 6>(wc, a_lane, acc); slice_mfma<P, 7>(wc, a_lane + 64, acc); }
-            if (step + 1 < nsteps) a_store(buf ^ 1);
+    const int nsteps = prm.nsuper * 2;
+    // one super-chunk per iteration: two steps (= phases) of four 64-k slices; the weights and the A
+    // tile of the next step are fetched while the current one is multiplied.  Loads past the end are
+    // clamped to the last step instead of being skipped, so that every load in the loop is unconditional.
+    for (int sc = 0; sc < prm.nsuper; ++sc) {
+        const int scn = min(sc + 1, prm.nsuper - 1);
+        {   // step 2*sc: weights in wa, A in buffer 0
+            load_tiles<P>(prm, tile0, sc, 1, lane, wb);
+            a_prefetch(2 * sc + 1, lds_a1);
+            step_mfma<P, 0>(wa, lds_a0, r, G, acc);
             __syncthreads();
         }
-    };
-    for (int sc = 0; sc < prm.nsuper; sc += 2) {
-        super_chunk(wa, wb, sc);
-        if (sc + 1 < prm.nsuper) super_chunk(wb, wa, sc + 1);
+        {   // step 2*sc+1: weights in wb, A in buffer 1
+            load_tiles<P>(prm, tile0, scn, 0, lane, wa);
+            a_prefetch(min(2 * sc + 2, nsteps - 1), lds_a0);
+            step_mfma<P, 1>(wb, lds_a1, r, G, acc);
+            __syncthreads();
+        }
     }
 
     // fused epilogue: lane l, register reg of accumulator tile (mt, nt) is row 16*mt + 4*(l/16) + reg, column 16*nt + l%16
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt) {
-        const int nl = wave * 32 + nt * 16 + r;
+    for (int nt = 0; nt < kNTW; ++nt) {
+        const int nl = wave * (kNTW * kTileN) + nt * 16 + r;
         const int n = n0 + nl;
         const RowParams pw = par_w[nl];
 #pragma unroll
@@ -213,7 +261,9 @@ hipError_t launch_gemm_tiled(const GemmArgs& g, const ActLayout& A, const Weight
     prm.ntiles = W.NT;
     prm.oa = (g.q == 8) ? 128 : 0;
     prm.ow = (g.p == 8) ? 128 : 0;
-    dim3 grid((unsigned)((g.N + kBN - 1) / kBN), (unsigned)((g.M + kBM - 1) / kBM));
+    prm.tiles_m = (g.M + kBM - 1) / kBM;
+    prm.tiles_n = (g.N + kBN - 1) / kBN;
+    dim3 grid((unsigned)(prm.tiles_m * prm.tiles_n));
     switch (g.p) {
         case 1: return launch_p<1>(prm, grid, s);
         case 2: return launch_p<2>(prm, grid, s);
