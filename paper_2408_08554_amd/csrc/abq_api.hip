@@ -209,13 +209,12 @@ static bool choose_fields(bool can_fields, bool can_planes, int force)
     return can_fields;   // measured: the MFMA path is never slower on gfx950 (see profiles/)
 }
 
-static const int kSkinnyMaxM = 64;
+static const int kSkinnyMaxM = 16;   // one MFMA tile of activation rows: the streaming kernel; above it the tiled kernel
 
 size_t abq_gemm_workspace_bytes(int p, int q, int M, int N, int K)
 {
     if (check_gemm_shape(p, q, M, N, K) != ABQ_OK) return 0;
-    if (M <= kSkinnyMaxM) return 0;
-    return gemm_tiled_workspace_bytes(p, q, M, N, K);
+    return 0;   // no kernel needs scratch at present
 }
 
 int abq_gemm(int p, int q, int M, int N, int K, const void* packed_act, int a_layout, const void* packed_w,
@@ -241,6 +240,10 @@ int abq_gemm(int p, int q, int M, int N, int K, const void* packed_act, int a_la
     hipStream_t s = (hipStream_t)stream;
     if (!choose_fields(can_fields, can_planes, force)) return hip_status(launch_gemm_bitserial(g, A, W, s));
     if (M <= kSkinnyMaxM) return hip_status(launch_gemm_skinny(g, A, W, s));
+    // Few output tiles and M <= 64: the tiled kernel would occupy a fraction of the chip with long K
+    // loops; the streaming kernel splits K over waves instead (one pass over W per 16 rows of A).
+    const long tiled_wgs = (long)((M + 63) / 64) * ((N + 63) / 64);
+    if (M <= 64 && tiled_wgs < 128) return hip_status(launch_gemm_skinny(g, A, W, s));
     return hip_status(launch_gemm_tiled(g, A, W, s));
 }
 

@@ -15,13 +15,17 @@
 #include "abq_internal.h"
 #include "../../include/abq.h"
 
+#include <stdlib.h>
+
 namespace abq {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef unsigned int u4v __attribute__((ext_vector_type(4)));
 
-constexpr int kNTW = 4;                                   // 16-row tiles of W per wave
-constexpr int kBM = 128, kBN = 4 * kNTW * kTileN, kStepK = 256;   // one step = one phase = four 64-k slices
+// Tile shape: MT 16-row tiles of A per workgroup (4 or 8: 64 or 128 rows), NTW 16-row tiles of W per
+// wave (1, 2 or 4: workgroup covers 64, 128 or 256 rows of W).  Narrow shapes give more workgroups
+// when M and N are small; wide ones reuse each A operand read for more MFMAs.
+constexpr int kStepK = 256;          // one step = one phase = four 64-k slices
 constexpr int kARow = kStepK;        // LDS row stride (unpadded; the 16-B vectors of a row are XOR-swizzled by the row index)
 
 struct TiledParams {
@@ -83,21 +87,22 @@ __device__ __forceinline__ v4i merged_operand(const u4v* w)
 // A tile in LDS: [128 rows][16 vectors of 16 B], vector v of row `row` stored at position v ^ (row & 15),
 // so that the 16 rows an operand read touches (same v) land in 16 different 16-byte bank groups.
 // Lane (r = lane%16, G = lane/16) reads, for m-tile mt and slice sl, vector 4*sl + G of row 16*mt + r.
+template <int MT>
 __device__ __forceinline__ void read_a_operands(const uint8_t* a_buf, int r, int G, int sl, v4i* aop)
 {
     const uint8_t* p = a_buf + r * kARow + (((4 * sl + G) ^ r) << 4);
 #pragma unroll
-    for (int mt = 0; mt < 8; ++mt) aop[mt] = *reinterpret_cast<const v4i*>(p + mt * 16 * kARow);
+    for (int mt = 0; mt < MT; ++mt) aop[mt] = *reinterpret_cast<const v4i*>(p + mt * 16 * kARow);
 }
 
-template <int P, int SL>
-__device__ __forceinline__ void slice_mfma(const u4v (*w)[phase_regs(P)], const v4i* aop, v4i (*acc)[kNTW])
+template <int P, int NTW, int MT, int SL>
+__device__ __forceinline__ void slice_mfma(const u4v (*w)[phase_regs(P)], const v4i* aop, v4i (*acc)[NTW])
 {
 #pragma unroll
-    for (int nt = 0; nt < kNTW; ++nt) {
+    for (int nt = 0; nt < NTW; ++nt) {
         const v4i bop = merged_operand<P, SL>(w[nt]);
 #pragma unroll
-        for (int mt = 0; mt < 8; ++mt) acc[mt][nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[mt], bop, acc[mt][nt], 0, 0, 0);
+        for (int mt = 0; mt < MT; ++mt) acc[mt][nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[mt], bop, acc[mt][nt], 0, 0, 0);
     }
 }
 
@@ -105,31 +110,31 @@ __device__ __forceinline__ void slice_mfma(const u4v (*w)[phase_regs(P)], const 
 // requested from LDS, then their 2 x 32 MFMAs run as one uninterrupted burst.  The scheduling
 // barriers pin that order: left alone, the machine scheduler sinks the reads next to their uses
 // and the matrix pipe (one wave per SIMD, nobody else to feed it) idles on every wait.
-template <int P, int PH>
-__device__ __forceinline__ void step_mfma(const u4v (*w)[phase_regs(P)], const uint8_t* a_buf, int r, int G, v4i (*acc)[kNTW])
+template <int P, int NTW, int MT, int PH>
+__device__ __forceinline__ void step_mfma(const u4v (*w)[phase_regs(P)], const uint8_t* a_buf, int r, int G, v4i (*acc)[NTW])
 {
-    v4i a0[8], a1[8];
-    read_a_operands(a_buf, r, G, 0, a0);
-    read_a_operands(a_buf, r, G, 1, a1);
+    v4i a0[MT], a1[MT];
+    read_a_operands<MT>(a_buf, r, G, 0, a0);
+    read_a_operands<MT>(a_buf, r, G, 1, a1);
     __builtin_amdgcn_sched_barrier(0);
-    slice_mfma<P, 4 * PH + 0>(w, a0, acc);
-    slice_mfma<P, 4 * PH + 1>(w, a1, acc);
+    slice_mfma<P, NTW, MT, 4 * PH + 0>(w, a0, acc);
+    slice_mfma<P, NTW, MT, 4 * PH + 1>(w, a1, acc);
     __builtin_amdgcn_sched_barrier(0);
-    read_a_operands(a_buf, r, G, 2, a0);
-    read_a_operands(a_buf, r, G, 3, a1);
+    read_a_operands<MT>(a_buf, r, G, 2, a0);
+    read_a_operands<MT>(a_buf, r, G, 3, a1);
     __builtin_amdgcn_sched_barrier(0);
-    slice_mfma<P, 4 * PH + 2>(w, a0, acc);
-    slice_mfma<P, 4 * PH + 3>(w, a1, acc);
+    slice_mfma<P, NTW, MT, 4 * PH + 2>(w, a0, acc);
+    slice_mfma<P, NTW, MT, 4 * PH + 3>(w, a1, acc);
     __builtin_amdgcn_sched_barrier(0);
 }
 
 // Loads phase `ph` (0 or 1) of super-chunk `sc` for this wave's tiles.
-template <int P>
+template <int P, int NTW>
 __device__ __forceinline__ void load_tiles(const TiledParams& prm, int tile0, int sc, int ph, int lane, u4v (*w)[phase_regs(P)])
 {
     // tile0, sc and ph are wave-uniform: the chunk base is a scalar address, the lane adds 16*lane
 #pragma unroll
-    for (int nt = 0; nt < kNTW; ++nt) {
+    for (int nt = 0; nt < NTW; ++nt) {
         const int tile = min(tile0 + nt, prm.ntiles - 1);   // past the last tile: re-read a valid one, never stored
 #pragma unroll
         for (int g = 0; g < group_count(P); ++g) {
@@ -142,9 +147,10 @@ __device__ __forceinline__ void load_tiles(const TiledParams& prm, int tile0, in
     }
 }
 
-template <int P>
+template <int P, int NTW, int MT>
 __global__ __launch_bounds__(256) void tiled_kernel(TiledParams prm)
 {
+    constexpr int kBM = MT * 16, kBN = 4 * NTW * kTileN;
     __shared__ __align__(16) uint8_t lds_a0[kBM * kARow];   // two separate objects: the loads that fill one must
     __shared__ __align__(16) uint8_t lds_a1[kBM * kARow];   // not be taken to alias the reads of the other
     __shared__ RowParams par_a[kBM], par_w[kBN];
@@ -160,24 +166,24 @@ __global__ __launch_bounds__(256) void tiled_kernel(TiledParams prm)
     const int vid = xcd * per + min(xcd, rem) + slot;
     const int m_blk = vid % prm.tiles_m, n_blk = vid / prm.tiles_m;
     const int m0 = m_blk * kBM, n0 = n_blk * kBN;
-    const int tile0 = n_blk * (kBN / kTileN) + wave * kNTW;
+    const int tile0 = n_blk * (kBN / kTileN) + wave * NTW;
 
     // weights of the first phase
-    u4v wa[kNTW][phase_regs(P)], wb[kNTW][phase_regs(P)];
-    load_tiles<P>(prm, tile0, 0, 0, lane, wa);
+    u4v wa[NTW][phase_regs(P)], wb[NTW][phase_regs(P)];
+    load_tiles<P, NTW>(prm, tile0, 0, 0, lane, wa);
 
     // epilogue parameters
     if (tid < kBM) par_a[tid] = prm.aparams[min(m0 + tid, prm.M - 1)];
-    for (int i = tid; i < kBN; i += 256) par_w[i] = prm.wparams[min(n0 + i, prm.N - 1)];
+    if (tid < kBN) par_w[tid] = prm.wparams[min(n0 + tid, prm.N - 1)];
 
     // A tile of one 256-k step goes from global memory straight into LDS (128-bit direct loads, no
-    // registers in between): wave w issues loads j = 8w .. 8w+7, load j fills rows 4j .. 4j+3 (1 KiB,
+    // registers in between): wave w issues loads j = MT*w .. MT*w+MT-1, load j fills rows 4j .. 4j+3 (1 KiB,
     // lane L -> LDS position 16*L of that KiB = row 4j + L/16, position L%16, which holds vector
     // (L%16) ^ (row & 15) of the row).  Rows past M re-read row M-1; their outputs are never stored.
-    unsigned a_goff[8];
+    unsigned a_goff[MT];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
-        const int row = 4 * (wave * 8 + u) + (lane >> 4);
+    for (int u = 0; u < MT; ++u) {
+        const int row = 4 * (wave * MT + u) + (lane >> 4);
         const int vec = (lane & 15) ^ (row & 15);
         a_goff[u] = (unsigned)(min(m0 + row, prm.M - 1) - m0) * (unsigned)prm.Kp + vec * 16;
     }
@@ -185,16 +191,16 @@ __global__ __launch_bounds__(256) void tiled_kernel(TiledParams prm)
     auto a_prefetch = [&](int step, uint8_t* buf) {
         const int8_t* base = a_tile + (size_t)step * kStepK;     // uniform
 #pragma unroll
-        for (int u = 0; u < 8; ++u)
+        for (int u = 0; u < MT; ++u)
             __builtin_amdgcn_global_load_lds((const void*)(base + a_goff[u]),
-                                             (__attribute__((address_space(3))) void*)(buf + (wave * 8 + u) * 1024), 16, 0, 0);
+                                             (__attribute__((address_space(3))) void*)(buf + (wave * MT + u) * 1024), 16, 0, 0);
     };
 
-    v4i acc[8][kNTW];
+    v4i acc[MT][NTW];
 #pragma unroll
-    for (int mt = 0; mt < 8; ++mt)
+    for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-        for (int nt = 0; nt < kNTW; ++nt) acc[mt][nt] = v4i{0, 0, 0, 0};
+        for (int nt = 0; nt < NTW; ++nt) acc[mt][nt] = v4i{0, 0, 0, 0};
 
     a_prefetch(0, lds_a0);
     __syncthreads();   // (the compiler waits for the direct loads before the barrier)
@@ -206,27 +212,27 @@ __global__ __launch_bounds__(256) void tiled_kernel(TiledParams prm)
     for (int sc = 0; sc < prm.nsuper; ++sc) {
         const int scn = min(sc + 1, prm.nsuper - 1);
         {   // step 2*sc: weights in wa, A in buffer 0
-            load_tiles<P>(prm, tile0, sc, 1, lane, wb);
+            load_tiles<P, NTW>(prm, tile0, sc, 1, lane, wb);
             a_prefetch(2 * sc + 1, lds_a1);
-            step_mfma<P, 0>(wa, lds_a0, r, G, acc);
+            step_mfma<P, NTW, MT, 0>(wa, lds_a0, r, G, acc);
             __syncthreads();
         }
         {   // step 2*sc+1: weights in wb, A in buffer 1
-            load_tiles<P>(prm, tile0, scn, 0, lane, wa);
+            load_tiles<P, NTW>(prm, tile0, scn, 0, lane, wa);
             a_prefetch(min(2 * sc + 2, nsteps - 1), lds_a0);
-            step_mfma<P, 1>(wb, lds_a1, r, G, acc);
+            step_mfma<P, NTW, MT, 1>(wb, lds_a1, r, G, acc);
             __syncthreads();
         }
     }
 
     // fused epilogue: lane l, register reg of accumulator tile (mt, nt) is row 16*mt + 4*(l/16) + reg, column 16*nt + l%16
 #pragma unroll
-    for (int nt = 0; nt < kNTW; ++nt) {
-        const int nl = wave * (kNTW * kTileN) + nt * 16 + r;
+    for (int nt = 0; nt < NTW; ++nt) {
+        const int nl = wave * (NTW * kTileN) + nt * 16 + r;
         const int n = n0 + nl;
         const RowParams pw = par_w[nl];
 #pragma unroll
-        for (int mt = 0; mt < 8; ++mt) {
+        for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
             for (int reg = 0; reg < 4; ++reg) {
                 const int ml = mt * 16 + 4 * G + reg;
@@ -238,13 +244,24 @@ __global__ __launch_bounds__(256) void tiled_kernel(TiledParams prm)
     }
 }
 
-size_t gemm_tiled_workspace_bytes(int, int, int, int, int) { return 0; }
+template <int P, int NTW, int MT>
+static hipError_t launch_shape(const TiledParams& prm, dim3 grid, hipStream_t s)
+{
+    tiled_kernel<P, NTW, MT><<<grid, 256, 0, s>>>(prm);
+    return hipGetLastError();
+}
 
 template <int P>
-static hipError_t launch_p(const TiledParams& prm, dim3 grid, hipStream_t s)
+static hipError_t launch_p(const TiledParams& prm, int ntw, int mt, dim3 grid, hipStream_t s)
 {
-    tiled_kernel<P><<<grid, 256, 0, s>>>(prm);
-    return hipGetLastError();
+    if (mt == 4) {
+        if (ntw == 1) return launch_shape<P, 1, 4>(prm, grid, s);
+        if (ntw == 2) return launch_shape<P, 2, 4>(prm, grid, s);
+        return launch_shape<P, 4, 4>(prm, grid, s);
+    }
+    if (ntw == 1) return launch_shape<P, 1, 8>(prm, grid, s);
+    if (ntw == 2) return launch_shape<P, 2, 8>(prm, grid, s);
+    return launch_shape<P, 4, 8>(prm, grid, s);
 }
 
 hipError_t launch_gemm_tiled(const GemmArgs& g, const ActLayout& A, const WeightLayout& W, hipStream_t s)
@@ -261,18 +278,29 @@ hipError_t launch_gemm_tiled(const GemmArgs& g, const ActLayout& A, const Weight
     prm.ntiles = W.NT;
     prm.oa = (g.q == 8) ? 128 : 0;
     prm.ow = (g.p == 8) ? 128 : 0;
-    prm.tiles_m = (g.M + kBM - 1) / kBM;
-    prm.tiles_n = (g.N + kBN - 1) / kBN;
+    // tile shape: 64 rows of A when M <= 64; the widest N tile that still yields about one workgroup per CU
+    int cus = 256, dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+    const int mt = g.M <= 64 ? 4 : 8;
+    prm.tiles_m = (g.M + mt * 16 - 1) / (mt * 16);
+    int ntw = 4;
+    while (ntw > 1 && prm.tiles_m * ((g.N + 64 * ntw - 1) / (64 * ntw)) < cus) ntw >>= 1;
+    {
+        static int forced = -1;   // tuning override, read once: ABQ_TILED_NTW=<1|2|4>
+        if (forced < 0) { const char* e = getenv("ABQ_TILED_NTW"); forced = e ? atoi(e) : 0; }
+        if (forced == 1 || forced == 2 || forced == 4) ntw = forced;
+    }
+    prm.tiles_n = (g.N + 64 * ntw - 1) / (64 * ntw);
     dim3 grid((unsigned)(prm.tiles_m * prm.tiles_n));
     switch (g.p) {
-        case 1: return launch_p<1>(prm, grid, s);
-        case 2: return launch_p<2>(prm, grid, s);
-        case 3: return launch_p<3>(prm, grid, s);
-        case 4: return launch_p<4>(prm, grid, s);
-        case 5: return launch_p<5>(prm, grid, s);
-        case 6: return launch_p<6>(prm, grid, s);
-        case 7: return launch_p<7>(prm, grid, s);
-        default: return launch_p<8>(prm, grid, s);
+        case 1: return launch_p<1>(prm, ntw, mt, grid, s);
+        case 2: return launch_p<2>(prm, ntw, mt, grid, s);
+        case 3: return launch_p<3>(prm, ntw, mt, grid, s);
+        case 4: return launch_p<4>(prm, ntw, mt, grid, s);
+        case 5: return launch_p<5>(prm, ntw, mt, grid, s);
+        case 6: return launch_p<6>(prm, ntw, mt, grid, s);
+        case 7: return launch_p<7>(prm, ntw, mt, grid, s);
+        default: return launch_p<8>(prm, ntw, mt, grid, s);
     }
 }
 

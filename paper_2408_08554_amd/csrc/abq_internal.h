@@ -82,7 +82,6 @@ struct GemmArgs {
 hipError_t launch_gemm_skinny(const GemmArgs& g, const ActLayout& A, const WeightLayout& W, hipStream_t s);
 hipError_t launch_gemm_tiled(const GemmArgs& g, const ActLayout& A, const WeightLayout& W, hipStream_t s);
 hipError_t launch_gemm_bitserial(const GemmArgs& g, const ActLayout& A, const WeightLayout& W, hipStream_t s);
-size_t gemm_tiled_workspace_bytes(int p, int q, int M, int N, int K);
 
 // ---- device helpers -------------------------------------------------------------------------
 struct alignas(16) RowParams { int32_t sum; float scale; int32_t zero; int32_t pad; };

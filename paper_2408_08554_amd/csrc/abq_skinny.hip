@@ -17,6 +17,7 @@
 #include "../../include/abq.h"
 
 #include <hip/hip_fp16.h>
+#include <stdlib.h>
 
 namespace abq {
 
@@ -373,24 +374,73 @@ static int num_cus()
 
 // The kernels use up to 256 VGPRs, i.e. two waves per SIMD, eight per CU.
 static const int kWavesPerCu = 8;
+static const size_t kLdsPerCu = 160 * 1024;
 
-// Waves per workgroup (= K split of a tile).  All workgroups should be resident at once, so that
-// uneven tile counts per CU even out through shared bandwidth: S <= 8*CUs/tiles.  Within that,
-// 4..8 waves are chosen to leave the fewest idle wave-slots in the last round over K.
-static int pick_waves(int nsuper, int ntiles, int cus)
+// Launch plan: S waves per workgroup (= K split of a tile) and gx workgroups walking the tiles.
+// What it trades off (the analogue of the paper's tile-shape search, Appendix D "Auto Kernel
+// Search", as a closed-form score instead of timed trials):
+//   - waves resident per CU (LDS for the staged rows of A and the 8-wave register limit bound it),
+//   - idle wave-slots in the last round over K when S does not divide the super-chunk count,
+//   - idle workgroup-slots in the last round over the tiles.
+struct SkinnyPlan { int waves, gx, mrows; size_t par_bytes, red_bytes, lds_bytes; };
+
+static bool make_plan(int S, int M, int Kp, int ntiles, int cus, SkinnyPlan* out, double* score)
 {
-    int smax = kWavesPerCu * cus / ntiles;
-    if (smax > 8) smax = 8;
-    if (smax > nsuper) smax = nsuper;
-    if (smax <= 1) return 1;
-    if (smax <= 3) return 2;
-    int best = smax, best_waste = 1 << 30;
-    for (int w = smax; w >= 4; --w) {
-        const int rounds = (nsuper + w - 1) / w;
-        const int waste = rounds * w - nsuper;
-        if (waste < best_waste) { best_waste = waste; best = w; }
+    const int nsuper = Kp / kSuperK;
+    if (S > nsuper) return false;
+    const size_t a_stride = (size_t)Kp + 16;
+    const size_t red_bytes = 2 * (size_t)S * 1024;
+    int mrows = M < 16 ? M : 16;
+    // first guess of the per-workgroup tile count (for the parameter area), refined once gx is known
+    size_t par_bytes = (size_t)(16 + 16) * sizeof(RowParams);
+    for (int pass = 0; pass < 2; ++pass) {
+        const size_t budget = kLdsPerCu - red_bytes - par_bytes - 64;
+        if ((size_t)mrows * a_stride > budget) mrows = (int)(budget / a_stride);
+        if (mrows < 1) return false;
+        const size_t lds = align_up((size_t)mrows * a_stride, 16) + par_bytes + red_bytes;
+        int per_cu = (int)(kLdsPerCu / lds);
+        if (per_cu > kWavesPerCu / S) per_cu = kWavesPerCu / S;
+        if (per_cu < 1) per_cu = 1;
+        int gx = ntiles < cus * per_cu ? ntiles : cus * per_cu;
+        const int rounds = (ntiles + gx - 1) / gx;
+        par_bytes = (size_t)(16 + rounds * 16) * sizeof(RowParams);
+        if (pass == 1) {
+            out->waves = S; out->gx = gx; out->mrows = mrows;
+            out->par_bytes = par_bytes; out->red_bytes = red_bytes;
+            out->lds_bytes = align_up((size_t)mrows * a_stride, 16) + par_bytes + red_bytes;
+            if (out->lds_bytes > kLdsPerCu) return false;
+            const double waves_cu = (double)per_cu * S < kWavesPerCu ? (double)per_cu * S : kWavesPerCu;
+            const double occupancy = (double)gx * S / cus < waves_cu ? (double)gx * S / cus : waves_cu;
+            const int krounds = (nsuper + S - 1) / S;
+            const double k_eff = (double)nsuper / (krounds * S);
+            const double t_eff = (double)ntiles / ((double)rounds * gx);
+            const double m_eff = (double)(M < 16 ? M : 16) / (((M < 16 ? M : 16) + mrows - 1) / mrows * mrows);
+            *score = (occupancy / kWavesPerCu) * k_eff * t_eff * m_eff;
+        }
     }
-    return best;
+    return true;
+}
+
+static bool pick_plan(int M, int Kp, int ntiles, int cus, SkinnyPlan* best)
+{
+    static const int candidates[] = {8, 7, 6, 5, 4, 2, 1};
+    // tuning override: ABQ_SKINNY_WAVES=<S> forces the K split (read once)
+    static int forced = -1;
+    if (forced < 0) {
+        const char* e = getenv("ABQ_SKINNY_WAVES");
+        forced = e ? atoi(e) : 0;
+    }
+    double best_score = -1.0;
+    bool ok = false;
+    for (int S : candidates) {
+        if (forced > 0 && S != forced) continue;
+        SkinnyPlan pl;
+        double sc;
+        if (!make_plan(S, M, Kp, ntiles, cus, &pl, &sc)) continue;
+        if (sc > best_score + 1e-9) { best_score = sc; *best = pl; ok = true; }
+    }
+    if (!ok && forced > 0) { forced = 0; return pick_plan(M, Kp, ntiles, cus, best); }
+    return ok;
 }
 
 template <int P, int D, int EPT>
@@ -432,24 +482,15 @@ hipError_t launch_gemm_skinny(const GemmArgs& g, const ActLayout& A, const Weigh
     prm.ntiles = W.NT;
     const int cus = num_cus();
     const int nsuper = A.Kp / kSuperK;
-    const int waves = pick_waves(nsuper, W.NT, cus);
-    // grid: every tile its own workgroup while they can all be resident, else a resident set that walks the tiles
-    int gx = W.NT;
-    const int resident = cus * (kWavesPerCu / waves);
-    if (gx > resident) gx = resident;
-    const int nmy_max = (W.NT + gx - 1) / gx;
+    SkinnyPlan pl;
+    if (!pick_plan(g.M, A.Kp, W.NT, cus, &pl)) return hipErrorInvalidValue;   // cannot happen for K <= ABQ_MAX_K
+    const int waves = pl.waves, gx = pl.gx, mrows = pl.mrows;
     // LDS: staged rows of A (all of K), the epilogue parameters, two reduction buffers of 1 KiB per wave
-    const size_t par_bytes = (size_t)(16 + nmy_max * 16) * sizeof(RowParams);
-    const size_t red_bytes = 2 * (size_t)waves * 1024;
-    const size_t budget = 160 * 1024 - red_bytes - par_bytes - 64;
     prm.a_stride = A.Kp + 16;
-    int mrows = g.M < 16 ? g.M : 16;
-    if ((size_t)mrows * prm.a_stride > budget) mrows = (int)(budget / prm.a_stride);
-    if (mrows < 1) return hipErrorInvalidValue;   // cannot happen for K <= ABQ_MAX_K
     prm.mrows = mrows;
     prm.par_off = (int)align_up((size_t)mrows * prm.a_stride, 16);
-    prm.red_off = prm.par_off + (int)par_bytes;
-    const size_t lds_bytes = prm.red_off + red_bytes;
+    prm.red_off = prm.par_off + (int)pl.par_bytes;
+    const size_t lds_bytes = pl.lds_bytes;
     prm.nsuper = nsuper;
     prm.sc_q = nsuper / waves; prm.sc_r = nsuper % waves;
     prm.tl_q = W.NT / gx; prm.tl_r = W.NT % gx;

@@ -204,7 +204,8 @@ def test_config4_w6a6_gemm_sampled(abq, M):
     check_sampled(c, y, acc)
 
 
-@pytest.mark.parametrize("p,q,shape_idx,m_idx", [(4, 8, 0, 1), (2, 4, 1, 2), (8, 8, 0, 2), (3, 8, 1, 0), (1, 1, 0, 2)])
+@pytest.mark.parametrize("p,q,shape_idx,m_idx", [(4, 8, 0, 1), (2, 4, 1, 2), (8, 8, 0, 2), (3, 8, 1, 0), (1, 1, 0, 2),
+                                                 (4, 4, 0, 3), (7, 8, 1, 3)])
 def test_config5_sweep_samples(abq, p, q, shape_idx, m_idx):
     c = synth.config5(p, q, shape_idx, m_idx)
     y, acc = gpu_gemm(torch, abq, c, FIELDS, FIELDS)
