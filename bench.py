@@ -24,6 +24,14 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0           # MI355X published HBM3E bandwidth
 INT8_MFMA_PEAK_TOPS = 5000.0    # MI355X published dense int8
 
+# HBM bytes per abq_gemm launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch), each
+# scaled by what the same counter reads for a plain copy of known size in the same run (FETCH_SIZE
+# reads 0.5015x on this chip, WRITE_SIZE 1.000x); figures and commands are in profiles/.
+MEASURED_TRAFFIC_BYTES = {
+    "C2 W4A8 GEMV 4096x4096": int((4217.0 * 8256.25 / 4140.6 + 8.0) * 1024),
+    "C3 W2A8 GEMV M=1 11008->4096": int((5807.0 * 11328.25 / 5677.3 + 8.0) * 1024),
+}
+
 
 def build_case(name):
     from paper_2408_08554_amd import synth
@@ -176,6 +184,7 @@ def main():
         achieved = 2.0 * M * N * K / gemm_s / 1e12
         roof = {"bound": "mfma", "achieved": achieved, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
                 "frac": achieved / INT8_MFMA_PEAK_TOPS, "traffic": None}
+    roof["traffic"] = MEASURED_TRAFFIC_BYTES.get(c.name)
     roof.update({"kernel": "abq_gemm", "kernel_us_hip_events": gemm_s * 1e6, "algorithmic_bytes": alg_bytes,
                  "launches": args.steps})
 
