@@ -225,10 +225,16 @@ __global__ __launch_bounds__(256) void tiled_kernel(TiledParams prm)
         }
     }
 
-    // fused epilogue: lane l, register reg of accumulator tile (mt, nt) is row 16*mt + 4*(l/16) + reg, column 16*nt + l%16
+    // Fused epilogue.  Lane l, register reg of accumulator tile (mt, nt) is row 16*mt + 4*(l/16) + reg,
+    // column 16*nt + l%16.  The fp16 values are transposed through LDS (the A buffers are free now; waves
+    // 0,1 use the first, waves 2,3 the second) so that each lane then stores 16 contiguous bytes of a row
+    // of Y instead of 2: full 32..128-byte row segments per wave instead of scattered halves.
+    __syncthreads();   // every wave is done reading A
+    constexpr int kWCols = NTW * kTileN;                       // columns of Y this wave owns
+    uint16_t* stage = reinterpret_cast<uint16_t*>((wave < 2 ? lds_a0 : lds_a1) + (wave & 1) * (kBM * kWCols * 2));
 #pragma unroll
     for (int nt = 0; nt < NTW; ++nt) {
-        const int nl = wave * (NTW * kTileN) + nt * 16 + r;
+        const int nl = wave * kWCols + nt * 16 + r;
         const int n = n0 + nl;
         const RowParams pw = par_w[nl];
 #pragma unroll
@@ -237,8 +243,33 @@ __global__ __launch_bounds__(256) void tiled_kernel(TiledParams prm)
             for (int reg = 0; reg < 4; ++reg) {
                 const int ml = mt * 16 + 4 * G + reg;
                 const int m = m0 + ml;
-                if (m < prm.M && n < prm.N)
-                    epilogue_store(acc[mt][nt][reg], prm.oa, prm.ow, prm.K, par_a[ml], pw, (size_t)m * prm.N + n, prm.y, prm.acc);
+                int32_t raw;
+                stage[ml * kWCols + nt * 16 + r] = epilogue_value(acc[mt][nt][reg], prm.oa, prm.ow, prm.K, par_a[ml], pw, &raw);
+                if (prm.acc && m < prm.M && n < prm.N) prm.acc[(size_t)m * prm.N + n] = raw;
+            }
+        }
+    }
+    // only this wave reads what it wrote; same-wave LDS accesses execute in order
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    constexpr int kPieces = kWCols / 8;                        // 16-byte pieces per row of the wave's block
+    const bool vec_ok = (prm.N & 7) == 0;                       // rows of Y 16-byte aligned
+#pragma unroll
+    for (int it = 0; it < kBM * kPieces / 64; ++it) {
+        const int idx = it * 64 + lane;
+        const int ml = idx / kPieces, piece = idx % kPieces;
+        const int m = m0 + ml, n = n0 + wave * kWCols + piece * 8;
+        if (m < prm.M && n < prm.N) {
+            const uint4 v = *reinterpret_cast<const uint4*>(stage + ml * kWCols + piece * 8);
+            uint16_t* dst = prm.y + (size_t)m * prm.N + n;
+            if (vec_ok && n + 8 <= prm.N) {
+                *reinterpret_cast<uint4*>(dst) = v;
+            } else {
+                const uint32_t w4[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (n + e < prm.N) dst[e] = (uint16_t)(w4[e >> 1] >> (16 * (e & 1)));
             }
         }
     }

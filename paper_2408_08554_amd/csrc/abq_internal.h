@@ -90,17 +90,25 @@ struct alignas(16) RowParams { int32_t sum; float scale; int32_t zero; int32_t p
 // S is the kernel's sum over (a - oa)(w - ow); the exact integer zero-point correction is
 // applied before any float operation.  Unsigned arithmetic: intermediate wrap-around is
 // harmless because the final value fits in int32.
-__device__ __forceinline__ void epilogue_store(int32_t S, int oa, int ow, int K, const RowParams& ap,
-                                               const RowParams& wp, size_t idx, uint16_t* y, int32_t* acc)
+__device__ __forceinline__ uint16_t epilogue_value(int32_t S, int oa, int ow, int K, const RowParams& ap,
+                                                   const RowParams& wp, int32_t* raw_out)
 {
     const uint32_t asum = (uint32_t)ap.sum, wsum = (uint32_t)wp.sum;
     const uint32_t uK = (uint32_t)K, uoa = (uint32_t)oa, uow = (uint32_t)ow;
     const uint32_t raw = (uint32_t)S + uow * asum + uoa * wsum - uK * uoa * uow;
-    if (acc) acc[idx] = (int32_t)raw;
+    *raw_out = (int32_t)raw;
     const uint32_t az = (uint32_t)ap.zero, wz = (uint32_t)wp.zero;
     const int32_t centered = (int32_t)(raw - wz * asum - az * wsum + uK * az * wz);
     const float v = ((float)centered * ap.scale) * wp.scale;
-    y[idx] = __half_as_ushort(__float2half_rn(v));
+    return __half_as_ushort(__float2half_rn(v));
+}
+
+__device__ __forceinline__ void epilogue_store(int32_t S, int oa, int ow, int K, const RowParams& ap,
+                                               const RowParams& wp, size_t idx, uint16_t* y, int32_t* acc)
+{
+    int32_t raw;
+    y[idx] = epilogue_value(S, oa, ow, K, ap, wp, &raw);
+    if (acc) acc[idx] = raw;
 }
 
 }  // namespace abq

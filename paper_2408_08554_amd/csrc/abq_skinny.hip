@@ -421,7 +421,7 @@ static bool make_plan(int S, int M, int Kp, int ntiles, int cus, SkinnyPlan* out
     return true;
 }
 
-static bool pick_plan(int M, int Kp, int ntiles, int cus, SkinnyPlan* best)
+static bool pick_plan(int M, int Kp, int ntiles, int cus, size_t stream_bytes, SkinnyPlan* best)
 {
     static const int candidates[] = {8, 7, 6, 5, 4, 2, 1};
     // tuning override: ABQ_SKINNY_WAVES=<S> forces the K split (read once)
@@ -432,6 +432,19 @@ static bool pick_plan(int M, int Kp, int ntiles, int cus, SkinnyPlan* best)
     }
     double best_score = -1.0;
     bool ok = false;
+    // Long streams over many tiles (measured: >= 48 MB, >= 2 tiles per CU) run best as one resident
+    // workgroup per CU that walks its tiles with 6..8 waves: the ring never drains between tiles and
+    // A is staged once per workgroup.  Among 6..8 the split that wastes the fewest wave-slots over K.
+    if (forced <= 0 && stream_bytes >= ((size_t)48 << 20) && ntiles >= 2 * cus) {
+        const int nsuper = Kp / kSuperK;
+        int pick = 0, waste = 1 << 30;
+        for (int S = 8; S >= 6; --S) {
+            const int w = (nsuper + S - 1) / S * S - nsuper;
+            if (S <= nsuper && w < waste) { waste = w; pick = S; }
+        }
+        double sc;
+        if (pick && make_plan(pick, M, Kp, ntiles, cus, best, &sc)) return true;
+    }
     for (int S : candidates) {
         if (forced > 0 && S != forced) continue;
         SkinnyPlan pl;
@@ -439,7 +452,7 @@ static bool pick_plan(int M, int Kp, int ntiles, int cus, SkinnyPlan* best)
         if (!make_plan(S, M, Kp, ntiles, cus, &pl, &sc)) continue;
         if (sc > best_score + 1e-9) { best_score = sc; *best = pl; ok = true; }
     }
-    if (!ok && forced > 0) { forced = 0; return pick_plan(M, Kp, ntiles, cus, best); }
+    if (!ok && forced > 0) { forced = 0; return pick_plan(M, Kp, ntiles, cus, stream_bytes, best); }
     return ok;
 }
 
@@ -483,7 +496,8 @@ hipError_t launch_gemm_skinny(const GemmArgs& g, const ActLayout& A, const Weigh
     const int cus = num_cus();
     const int nsuper = A.Kp / kSuperK;
     SkinnyPlan pl;
-    if (!pick_plan(g.M, A.Kp, W.NT, cus, &pl)) return hipErrorInvalidValue;   // cannot happen for K <= ABQ_MAX_K
+    const size_t stream_bytes = (size_t)g.p * W.NT * 16 * (size_t)A.Kp / 8;
+    if (!pick_plan(g.M, A.Kp, W.NT, cus, stream_bytes, &pl)) return hipErrorInvalidValue;   // cannot happen for K <= ABQ_MAX_K
     const int waves = pl.waves, gx = pl.gx, mrows = pl.mrows;
     // LDS: staged rows of A (all of K), the epilogue parameters, two reduction buffers of 1 KiB per wave
     prm.a_stride = A.Kp + 16;
