@@ -232,19 +232,21 @@ __global__ __launch_bounds__(256) void tiled_kernel(TiledParams prm)
     __syncthreads();   // every wave is done reading A
     constexpr int kWCols = NTW * kTileN;                       // columns of Y this wave owns
     uint16_t* stage = reinterpret_cast<uint16_t*>((wave < 2 ? lds_a0 : lds_a1) + (wave & 1) * (kBM * kWCols * 2));
+    RowParams pw[NTW];
 #pragma unroll
-    for (int nt = 0; nt < NTW; ++nt) {
-        const int nl = wave * kWCols + nt * 16 + r;
-        const int n = n0 + nl;
-        const RowParams pw = par_w[nl];
+    for (int nt = 0; nt < NTW; ++nt) pw[nt] = par_w[wave * kWCols + nt * 16 + r];
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
+    for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
-            for (int reg = 0; reg < 4; ++reg) {
-                const int ml = mt * 16 + 4 * G + reg;
-                const int m = m0 + ml;
+        for (int reg = 0; reg < 4; ++reg) {
+            const int ml = mt * 16 + 4 * G + reg;
+            const int m = m0 + ml;
+            const RowParams pa = par_a[ml];
+#pragma unroll
+            for (int nt = 0; nt < NTW; ++nt) {
+                const int n = n0 + wave * kWCols + nt * 16 + r;
                 int32_t raw;
-                stage[ml * kWCols + nt * 16 + r] = epilogue_value(acc[mt][nt][reg], prm.oa, prm.ow, prm.K, par_a[ml], pw, &raw);
+                stage[ml * kWCols + nt * 16 + r] = epilogue_value(acc[mt][nt][reg], prm.oa, prm.ow, prm.K, pa, pw[nt], &raw);
                 if (prm.acc && m < prm.M && n < prm.N) prm.acc[(size_t)m * prm.N + n] = raw;
             }
         }
