@@ -147,8 +147,10 @@ __device__ __forceinline__ void load_tiles(const TiledParams& prm, int tile0, in
     }
 }
 
+// Up to two 16-row tiles of W per wave the kernel is held to 256 registers, so that two workgroups
+// share a CU and each hides the other's waits; the four-tile shape takes the whole register file.
 template <int P, int NTW, int MT>
-__global__ __launch_bounds__(256) void tiled_kernel(TiledParams prm)
+__global__ __launch_bounds__(256, (NTW <= 2 ? 2 : 1)) void tiled_kernel(TiledParams prm)
 {
     constexpr int kBM = MT * 16, kBN = 4 * NTW * kTileN;
     __shared__ __align__(16) uint8_t lds_a0[kBM * kARow];   // two separate objects: the loads that fill one must
@@ -311,13 +313,15 @@ hipError_t launch_gemm_tiled(const GemmArgs& g, const ActLayout& A, const Weight
     prm.ntiles = W.NT;
     prm.oa = (g.q == 8) ? 128 : 0;
     prm.ow = (g.p == 8) ? 128 : 0;
-    // tile shape: 64 rows of A when M <= 64; the widest N tile that still yields about one workgroup per CU
+    // tile shape: 64 rows of A when M <= 64
     int cus = 256, dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
     const int mt = g.M <= 64 ? 4 : 8;
     prm.tiles_m = (g.M + mt * 16 - 1) / (mt * 16);
-    int ntw = 4;
-    while (ntw > 1 && prm.tiles_m * ((g.N + 64 * ntw - 1) / (64 * ntw)) < cus) ntw >>= 1;
+    // measured: two tiles of W per wave (128-wide workgroup tile, two workgroups per CU) beats the 256-wide
+    // shape on every prefill shape tried; one tile per wave when that would leave CUs without a workgroup
+    int ntw = 2;
+    if (prm.tiles_m * ((g.N + 127) / 128) < cus) ntw = 1;
     {
         static int forced = -1;   // tuning override, read once: ABQ_TILED_NTW=<1|2|4>
         if (forced < 0) { const char* e = getenv("ABQ_TILED_NTW"); forced = e ? atoi(e) : 0; }
