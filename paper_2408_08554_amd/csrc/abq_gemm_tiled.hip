@@ -1,17 +1,16 @@
-// Prefill-shaped matmul (M > 64): a dense int8 contraction on the 16x16x64 MFMA.
+// Prefill-shaped matmul (M > 16): a dense int8 contraction on the 16x16x64 MFMA.
 //
-// Workgroup tile 128 (rows of A) x 256 (rows of W), four waves side by side along N, each owning
-// four 16-row tiles of W for all 128 rows of A (8 x 4 accumulator tiles; one wave per SIMD, so the
-// whole 512-entry register file is the wave's).  The packed weight
-// plane groups go from HBM straight into registers in the same tiled layout the decode kernel
-// streams (one super-chunk of 512 k ahead) and are expanded there: for every 64-k slice the
-// fields of all groups are shifted to their bit position and OR-ed into one signed byte per
-// weight, so a slice costs one MFMA per accumulator tile whatever p is.  (This is the bit
-// reduction of Sec. 3.4 step 5 / Appendix B folded into the operand: the 2^s factors are bit
-// positions inside the byte, the 2^t factors are the activation code itself.)  The rows of A
-// go from global memory straight into LDS (direct 128-bit loads) in 256-k steps, double buffered,
-// one barrier per step.  The dequant epilogue
-// is fused (Fig. 3b).
+// Workgroup tile (16*MT rows of A) x (64*NTW rows of W), four waves side by side along N, each owning
+// NTW 16-row tiles of W for all rows of A (MT x NTW accumulator tiles).  The packed weight plane
+// groups go from HBM straight into registers in the same tiled layout the decode kernel streams
+// (one 256-k phase ahead) and are expanded there: for every 64-k slice the fields of all groups are
+// shifted to their bit position and OR-ed into one signed byte per weight, so a slice costs one
+// MFMA per accumulator tile whatever p is.  (This is the bit reduction of Sec. 3.4 step 5 /
+// Appendix B folded into the operand: the 2^s factors are bit positions inside the byte, the 2^t
+// factors are the activation code itself.)  The rows of A go from global memory straight into LDS
+// (direct 128-bit loads, XOR-swizzled so that operand reads have no bank conflicts) in 256-k steps,
+// double buffered, one barrier per step.  The dequant epilogue is fused (Fig. 3b) and leaves
+// through LDS so that rows of Y are written in 16-byte pieces.
 #include "abq_internal.h"
 #include "../../include/abq.h"
 
@@ -109,7 +108,7 @@ __device__ __forceinline__ void slice_mfma(const u4v (*w)[phase_regs(P)], const 
 // The four 64-k slices of one step (phase PH of a super-chunk): the A operands of two slices are
 // requested from LDS, then their 2 x 32 MFMAs run as one uninterrupted burst.  The scheduling
 // barriers pin that order: left alone, the machine scheduler sinks the reads next to their uses
-// and the matrix pipe (one wave per SIMD, nobody else to feed it) idles on every wait.
+// and the matrix pipe idles on every wait.
 template <int P, int NTW, int MT, int PH>
 __device__ __forceinline__ void step_mfma(const u4v (*w)[phase_regs(P)], const uint8_t* a_buf, int r, int G, v4i (*acc)[NTW])
 {
@@ -150,7 +149,7 @@ __device__ __forceinline__ void load_tiles(const TiledParams& prm, int tile0, in
 // Up to two 16-row tiles of W per wave the kernel is held to 256 registers, so that two workgroups
 // share a CU and each hides the other's waits; the four-tile shape takes the whole register file.
 template <int P, int NTW, int MT>
-__global__ __launch_bounds__(256, (NTW <= 2 ? 2 : 1)) void tiled_kernel(TiledParams prm)
+__global__ __launch_bounds__(256, (NTW <= 2 ? (MT == 4 ? 3 : 2) : 1)) void tiled_kernel(TiledParams prm)
 {
     constexpr int kBM = MT * 16, kBN = 4 * NTW * kTileN;
     __shared__ __align__(16) uint8_t lds_a0[kBM * kARow];   // two separate objects: the loads that fill one must
@@ -313,20 +312,22 @@ hipError_t launch_gemm_tiled(const GemmArgs& g, const ActLayout& A, const Weight
     prm.ntiles = W.NT;
     prm.oa = (g.q == 8) ? 128 : 0;
     prm.ow = (g.p == 8) ? 128 : 0;
-    // tile shape: 64 rows of A when M <= 64
+    // Tile shape (rows of A x rows of W per workgroup), measured on LLaMA-7B/13B prefill shapes: 128x128
+    // while it yields at least 1.5 workgroups per CU (two or three share a CU), else 64x128, else 64x64.
     int cus = 256, dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
-    const int mt = g.M <= 64 ? 4 : 8;
-    prm.tiles_m = (g.M + mt * 16 - 1) / (mt * 16);
-    // measured: two tiles of W per wave (128-wide workgroup tile, two workgroups per CU) beats the 256-wide
-    // shape on every prefill shape tried; one tile per wave when that would leave CUs without a workgroup
-    int ntw = 2;
-    if (prm.tiles_m * ((g.N + 127) / 128) < cus) ntw = 1;
+    auto wgs = [&](int mt_, int ntw_) { return (long)((g.M + mt_ * 16 - 1) / (mt_ * 16)) * ((g.N + 64 * ntw_ - 1) / (64 * ntw_)); };
+    int mt = 8, ntw = 2;
+    if (g.M <= 64 || 2 * wgs(8, 2) < 3L * cus) { mt = 4; ntw = 2; }
+    if (mt == 4 && 2 * wgs(4, 2) < 3L * cus) ntw = 1;
     {
-        static int forced = -1;   // tuning override, read once: ABQ_TILED_NTW=<1|2|4>
-        if (forced < 0) { const char* e = getenv("ABQ_TILED_NTW"); forced = e ? atoi(e) : 0; }
-        if (forced == 1 || forced == 2 || forced == 4) ntw = forced;
+        static int forced_mt = -1, forced_ntw = -1;   // tuning overrides, read once: ABQ_TILED_MT=<4|8>, ABQ_TILED_NTW=<1|2|4>
+        if (forced_mt < 0) { const char* e = getenv("ABQ_TILED_MT"); forced_mt = e ? atoi(e) : 0; }
+        if (forced_ntw < 0) { const char* e = getenv("ABQ_TILED_NTW"); forced_ntw = e ? atoi(e) : 0; }
+        if (forced_mt == 4 || forced_mt == 8) mt = forced_mt;
+        if (forced_ntw == 1 || forced_ntw == 2 || forced_ntw == 4) ntw = forced_ntw;
     }
+    prm.tiles_m = (g.M + mt * 16 - 1) / (mt * 16);
     prm.tiles_n = (g.N + 64 * ntw - 1) / (64 * ntw);
     dim3 grid((unsigned)(prm.tiles_m * prm.tiles_n));
     switch (g.p) {
