@@ -200,13 +200,17 @@ static int check_gemm_shape(int p, int q, int M, int N, int K)
     return ABQ_OK;
 }
 
-// Kernel family for a problem: true = int8-MFMA on field-packed operands, false = bit-serial.
-static bool choose_fields(bool can_fields, bool can_planes, int force)
+// Kernel family for a problem: true = int8-MFMA on field-packed operands, false = bit-serial
+// AND+popcount on the 1-bit planes.  Measured on MI355X (profiles/): the bit-serial kernel wins only
+// for a single token with very narrow operands over many output tiles (M = 1, p <= 2, q <= 4,
+// N >= 8192: 4.7 vs 6.3 us at W1A1 5120->13824), where its shorter fixed path matters more than
+// its 2*q VALU ops per weight word; everywhere else the MFMA path is faster, by up to 200x in prefill.
+static bool choose_fields(bool can_fields, bool can_planes, int force, int p, int q, int M, int N)
 {
-    (void)can_planes;
     if (force == ABQ_USE_PLANES) return false;
     if (force == ABQ_USE_FIELDS) return true;
-    return can_fields;   // measured: the MFMA path is never slower on gfx950 (see profiles/)
+    if (can_fields && can_planes && M == 1 && p <= 2 && q <= 4 && N >= 8192) return false;
+    return can_fields;
 }
 
 static const int kSkinnyMaxM = 16;   // one MFMA tile of activation rows: the streaming kernel; above it the tiled kernel
@@ -238,7 +242,7 @@ int abq_gemm(int p, int q, int M, int N, int K, const void* packed_act, int a_la
 
     GemmArgs g{p, q, M, N, K, (const uint8_t*)packed_act, (const uint8_t*)packed_w, y_fp16, acc_i32, workspace, workspace_bytes};
     hipStream_t s = (hipStream_t)stream;
-    if (!choose_fields(can_fields, can_planes, force)) return hip_status(launch_gemm_bitserial(g, A, W, s));
+    if (!choose_fields(can_fields, can_planes, force, p, q, M, N)) return hip_status(launch_gemm_bitserial(g, A, W, s));
     if (M <= kSkinnyMaxM) return hip_status(launch_gemm_skinny(g, A, W, s));
     // Few output tiles and M <= 64: the tiled kernel would occupy a fraction of the chip with long K
     // loops; the streaming kernel splits K over waves instead (one pass over W per 16 rows of A).

@@ -119,6 +119,50 @@ def test_both_layout_and_forced_family(abq):
         check_against_oracle(c, y, acc)
 
 
+def test_auto_dispatch_on_both_blobs_narrow_single_token(abq):
+    # M = 1, p <= 2, q <= 4, many output tiles: the dispatcher takes the bit-serial kernel when both
+    # representations are present; the result must not depend on that choice
+    c = synth.make_case(2, 4, 1, 8200, 640, seed=31)
+    y0, acc0 = gpu_gemm(torch, abq, c, BOTH, BOTH)
+    check_against_oracle(c, y0, acc0)
+    y1, acc1 = gpu_gemm(torch, abq, c, BOTH, BOTH, gemm_w_layout=BOTH | 0x20)
+    assert np.array_equal(acc0, acc1) and np.array_equal(y0.view(np.uint16), y1.view(np.uint16))
+
+
+@pytest.mark.parametrize("layout", [FIELDS, PLANES], ids=["mfma", "bitserial"])
+def test_degenerate_shapes(abq, layout):
+    for p, q, M, N, K in [(1, 1, 1, 1, 1), (8, 8, 1, 1, 1), (3, 7, 2, 1, 5), (5, 2, 1, 3, 17), (4, 4, 17, 1, 64)]:
+        c = synth.make_case(p, q, M, N, K, seed=900 + p + q + M + N + K)
+        y, acc = gpu_gemm(torch, abq, c, layout, layout)
+        check_against_oracle(c, y, acc)
+
+
+def test_longest_k(abq):
+    # K at the ABI limit (131072); W1A1 keeps the accumulator far inside int32
+    K = 131072
+    c = synth.make_case(1, 1, 2, 20, K, seed=4)
+    for layout in (FIELDS, PLANES):
+        y, acc = gpu_gemm(torch, abq, c, layout, layout)
+        check_against_oracle(c, y, acc)
+    c = synth.make_case(2, 6, 1, 16, K, seed=5)       # 131072*3*63 < 2^31
+    y, acc = gpu_gemm(torch, abq, c, FIELDS, FIELDS)
+    check_against_oracle(c, y, acc)
+
+
+def test_zero_and_constant_operands(abq):
+    c = synth.make_case(4, 8, 3, 40, 1000, seed=6)
+    c.A[:] = 0
+    y, acc = gpu_gemm(torch, abq, c, FIELDS, FIELDS)
+    assert (acc == 0).all()
+    check_against_oracle(c, y, acc)
+    c = synth.make_case(4, 8, 3, 40, 1000, seed=7)
+    c.A[1] = 255
+    c.W[:] = 15
+    y, acc = gpu_gemm(torch, abq, c, FIELDS, FIELDS)
+    assert (acc[1] == 1000 * 255 * 15).all()
+    check_against_oracle(c, y, acc)
+
+
 def test_extreme_codes_and_no_acc_output(abq):
     # all-max codes hit the largest accumulator value the ABI admits for this K; acc pointer NULL
     for p, q, K in [(8, 8, 33025), (1, 8, 4096), (8, 1, 700), (4, 4, 8192)]:
