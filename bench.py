@@ -2,8 +2,10 @@
 """Benchmark of the quantized-matmul hot path on one MI355X.
 
 A step is one pass of the online path over one batch of synthetic input: activation
-BitPacking (abq_pack_act_codes) followed by the matmul with fused bit reduction and dequant
-(abq_gemm), against packed weights that were prepared offline.  Successive steps use
+BitPacking, then the matmul with fused bit reduction and dequant, against packed weights that
+were prepared offline.  For the decode shapes the two run as ONE kernel (abq_gemm_act_codes:
+the codes are offset and their row sums taken while the matmul kernel stages them); for every
+other shape, or with --step two, as abq_pack_act_codes followed by abq_gemm.  Successive steps use
 different weight buffers (round-robin over >= 1 GiB) so that the 256 MB last-level cache
 cannot serve the weight stream — as in real decoding, where every layer has its own weights.
 
@@ -79,6 +81,8 @@ def main():
     ap.add_argument("--mode", default="graph", choices=["graph", "eager"],
                     help="graph: the timed steps are replayed from one captured HIP graph; eager: launched one by one")
     ap.add_argument("--family", default="auto", choices=["auto", "mfma", "bitserial"])
+    ap.add_argument("--step", default="auto", choices=["auto", "fused", "two"],
+                    help="fused: abq_gemm_act_codes; two: abq_pack_act_codes + abq_gemm; auto: fused where that is one kernel")
     ap.add_argument("--rotate-gib", type=float, default=1.0, help="total size of the rotating weight buffers")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="time budget of the cpu_baseline leg (0 = skip)")
     ap.add_argument("--no-check", action="store_true")
@@ -117,12 +121,23 @@ def main():
     ws_bytes = abq.abq_gemm_workspace_bytes(p, q, M, N, K)
     ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
 
-    def step(i):
+    fused_ws_bytes = abq.abq_gemm_act_codes_workspace_bytes(p, q, M, N, K, layout)
+    fused = args.step == "fused" or (args.step == "auto" and fused_ws_bytes == 0)
+    fws = torch.empty(max(fused_ws_bytes, 16), dtype=torch.uint8, device="cuda")
+
+    def two_step(i):
         abq.abq_pack_act_codes(q, a_codes, a_scale, a_zero, layout, out=pa)
         abq.abq_gemm(p, q, M, N, K, pa, layout, blobs[i % R], layout, y=y, workspace=ws)
 
-    def gemm_only(i):
+    def fused_step(i):
+        abq.abq_gemm_act_codes(p, q, M, N, K, a_codes, a_scale, a_zero, blobs[i % R], layout, y=y, workspace=fws)
+
+    def gemm_alone(i):
         abq.abq_gemm(p, q, M, N, K, pa, layout, blobs[i % R], layout, y=y, workspace=ws)
+
+    step = fused_step if fused else two_step
+    # the kernel the roofline prices: the one launch of the fused step, else the matmul of the two-call step
+    gemm_only = fused_step if fused and fused_ws_bytes == 0 else gemm_alone
 
     # parity on the buffers that are timed (first and last rotation slot)
     if not args.no_check:
@@ -133,11 +148,22 @@ def main():
         ms = rng.integers(0, M, 2048).astype(np.int32)
         ns = rng.integers(0, N, 2048).astype(np.int32)
         ref = oracle.acc_sampled(c.A, c.W, ms, ns)
+        accc = oracle.acc_centered_sampled(c.A, c.W, c.a_zero, c.w_zero, ms, ns)
+        yref = accc.astype(np.float64) * c.a_scale[ms].astype(np.float64) * c.w_scale[ns].astype(np.float64)
+        ytol = np.maximum(np.maximum(1e-2 * np.abs(yref), 2.0 ** (np.floor(np.log2(np.maximum(np.abs(yref), 2.0 ** -14))) - 9)),
+                          2.0 ** -24)
         for slot in (0, R - 1):
-            abq.abq_gemm(p, q, M, N, K, pa, layout, blobs[slot], layout, y=y, acc=acc, workspace=ws)
-            torch.cuda.synchronize()
-            got = acc.cpu().numpy()[ms, ns].astype(np.int64)
-            assert np.array_equal(got, ref), f"parity failure on rotation slot {slot}"
+            for name in ("two calls", "fused"):
+                if name == "fused":
+                    abq.abq_gemm_act_codes(p, q, M, N, K, a_codes, a_scale, a_zero, blobs[slot], layout, y=y, acc=acc,
+                                           workspace=fws)
+                else:
+                    abq.abq_gemm(p, q, M, N, K, pa, layout, blobs[slot], layout, y=y, acc=acc, workspace=ws)
+                torch.cuda.synchronize()
+                got = acc.cpu().numpy()[ms, ns].astype(np.int64)
+                assert np.array_equal(got, ref), f"int32 parity failure ({name}) on rotation slot {slot}"
+                yerr = np.abs(y.cpu().numpy()[ms, ns].astype(np.float64) - yref)
+                assert np.all(yerr <= ytol), f"fp16 parity failure ({name}) on rotation slot {slot}"
 
     stream = torch.cuda.Stream()
     with torch.cuda.stream(stream):
@@ -171,6 +197,7 @@ def main():
 
         wall, ev = timed_region(step, args.steps)
         _, ev_gemm = timed_region(gemm_only, args.steps)
+        _, ev_two = timed_region(two_step, args.steps) if fused else (wall, ev)
 
     sec_per_step = wall / args.steps
     gemm_s = ev_gemm / args.steps
@@ -185,7 +212,7 @@ def main():
         roof = {"bound": "mfma", "achieved": achieved, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
                 "frac": achieved / INT8_MFMA_PEAK_TOPS, "traffic": None}
     roof["traffic"] = MEASURED_TRAFFIC_BYTES.get(c.name)
-    roof.update({"kernel": "abq_gemm", "kernel_us_hip_events": gemm_s * 1e6, "algorithmic_bytes": alg_bytes,
+    roof.update({"kernel": "abq_gemm_act_codes" if gemm_only is fused_step else "abq_gemm", "kernel_us_hip_events": gemm_s * 1e6, "algorithmic_bytes": alg_bytes,
                  "launches": args.steps})
 
     out = {
@@ -194,11 +221,14 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
         "config": {"workload": c.name, "p": p, "q": q, "M": M, "N": N, "K": K, "mode": args.mode,
                    "family": args.family, "rotating_weight_buffers": R, "rotating_bytes": R * stride,
-                   "step": "abq_pack_act_codes + abq_gemm"},
+                   "step": "abq_gemm_act_codes" + ("" if fused_ws_bytes == 0 else " (two kernels)") if fused
+                           else "abq_pack_act_codes + abq_gemm"},
         "weight_gbs": metrics.weight_gbs(p, N, K, sec_per_step),
         "gemm_only": {"us": gemm_s * 1e6, "tops": metrics.effective_tops(M, N, K, gemm_s),
                       "weight_gbs": metrics.weight_gbs(p, N, K, gemm_s)},
         "hip_event_ms_per_step": ev / args.steps * 1e3,
+        "two_call_step": {"ms_per_step": ev_two / args.steps * 1e3, "tops": metrics.effective_tops(M, N, K, ev_two / args.steps),
+                          "step": "abq_pack_act_codes + abq_gemm"},
         "roofline": roof,
     }
     if args.cpu_seconds > 0:

@@ -141,6 +141,25 @@ int abq_gemm(int p, int q, int M, int N, int K,
              uint16_t* y_fp16, int32_t* acc_i32,
              void* workspace, size_t workspace_bytes, void* stream);
 
+/* Activation BitPacking fused into the matmul (Fig. 3b packs activations online on the way into
+ * the kernel; Sec. 3.4 keeps that overhead down by fusing it into an existing operator).  Same
+ * result, bit for bit, as abq_pack_act_codes followed by abq_gemm on the same arguments.
+ *   a_codes [M,K] uint8 row-major, values < 2^q;  a_scale [M] float;  a_zero [M] int32  (device)
+ *   packed_w, w_layout, y_fp16, acc_i32, stream: as for abq_gemm
+ *   workspace at least abq_gemm_act_codes_workspace_bytes(...) bytes.  That query returns 0 when
+ *             the call runs as ONE kernel: the decode shapes (M <= 16, or M <= 64 with few output
+ *             tiles) on field-packed weights with K a multiple of 16 — the codes are offset to
+ *             signed bytes and their row sums taken while the kernel stages them.  For every
+ *             other problem the packed activations are written to the workspace and the two
+ *             steps run back to back on the stream.
+ * Errors as abq_gemm (ABQ_ERR_NULL / ABQ_ERR_SIZE when a needed workspace is missing / too small). */
+size_t abq_gemm_act_codes_workspace_bytes(int p, int q, int M, int N, int K, int w_layout);
+int abq_gemm_act_codes(int p, int q, int M, int N, int K,
+                       const uint8_t* a_codes, const float* a_scale, const int32_t* a_zero,
+                       const void* packed_w, int w_layout,
+                       uint16_t* y_fp16, int32_t* acc_i32,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -35,6 +35,9 @@ _SIGNATURES = {
     "abq_gemm_workspace_bytes": (_c.c_size_t, [_c.c_int] * 5),
     "abq_gemm": (_c.c_int, [_c.c_int] * 5 + [_c.c_void_p, _c.c_int, _c.c_void_p, _c.c_int, _c.c_void_p, _c.c_void_p,
                                              _c.c_void_p, _c.c_size_t, _c.c_void_p]),
+    "abq_gemm_act_codes_workspace_bytes": (_c.c_size_t, [_c.c_int] * 6),
+    "abq_gemm_act_codes": (_c.c_int, [_c.c_int] * 5 + [_c.c_void_p] * 4 + [_c.c_int, _c.c_void_p, _c.c_void_p,
+                                                                          _c.c_void_p, _c.c_size_t, _c.c_void_p]),
 }
 
 _lib = None
@@ -175,4 +178,26 @@ def abq_gemm(p, q, M, N, K, packed_act, a_layout, packed_w, w_layout, y=None, ac
         workspace = torch.empty(need, dtype=torch.uint8, device=dev)
     _check(lib.abq_gemm(p, q, M, N, K, _ptr(packed_act), a_layout, _ptr(packed_w), w_layout, _ptr(y), _ptr(acc),
                         _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream()), "abq_gemm")
+    return y, acc
+
+
+def abq_gemm_act_codes_workspace_bytes(p, q, M, N, K, w_layout):
+    return load().abq_gemm_act_codes_workspace_bytes(p, q, M, N, K, w_layout)
+
+
+def abq_gemm_act_codes(p, q, M, N, K, a_codes, a_scale, a_zero, packed_w, w_layout, y=None, acc=None, want_acc=False,
+                       workspace=None):
+    """Activation packing fused into the matmul -> (y float16 [M,N], acc int32 [M,N] or None)."""
+    lib = load()
+    dev = packed_w.device
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.float16, device=dev)
+    if acc is None and want_acc:
+        acc = torch.empty((M, N), dtype=torch.int32, device=dev)
+    need = lib.abq_gemm_act_codes_workspace_bytes(p, q, M, N, K, w_layout)
+    if need and workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    _check(lib.abq_gemm_act_codes(p, q, M, N, K, _ptr(a_codes), _ptr(a_scale), _ptr(a_zero), _ptr(packed_w), w_layout,
+                                  _ptr(y), _ptr(acc), _ptr(workspace), 0 if workspace is None else workspace.numel(),
+                                  _stream()), "abq_gemm_act_codes")
     return y, acc

@@ -215,6 +215,16 @@ static bool choose_fields(bool can_fields, bool can_planes, int force, int p, in
 
 static const int kSkinnyMaxM = 16;   // one MFMA tile of activation rows: the streaming kernel; above it the tiled kernel
 
+// Streaming kernel or tiled kernel (both on field-packed operands).  Few output tiles and M <= 64:
+// the tiled kernel would occupy a fraction of the chip with long K loops; the streaming kernel
+// splits K over waves instead (one pass over W per 16 rows of A).
+static bool streaming_shape(int M, int N)
+{
+    if (M <= kSkinnyMaxM) return true;
+    const long tiled_wgs = (long)((M + 63) / 64) * ((N + 63) / 64);
+    return M <= 64 && tiled_wgs < 128;
+}
+
 size_t abq_gemm_workspace_bytes(int p, int q, int M, int N, int K)
 {
     if (check_gemm_shape(p, q, M, N, K) != ABQ_OK) return 0;
@@ -240,15 +250,64 @@ int abq_gemm(int p, int q, int M, int N, int K, const void* packed_act, int a_la
     const size_t need = abq_gemm_workspace_bytes(p, q, M, N, K);
     if (need > 0 && (!workspace || workspace_bytes < need)) return workspace ? ABQ_ERR_SIZE : ABQ_ERR_NULL;
 
-    GemmArgs g{p, q, M, N, K, (const uint8_t*)packed_act, (const uint8_t*)packed_w, y_fp16, acc_i32, workspace, workspace_bytes};
+    GemmArgs g{p, q, M, N, K, (const uint8_t*)packed_act, nullptr, nullptr, nullptr, (const uint8_t*)packed_w, y_fp16, acc_i32,
+               workspace, workspace_bytes};
     hipStream_t s = (hipStream_t)stream;
     if (!choose_fields(can_fields, can_planes, force, p, q, M, N)) return hip_status(launch_gemm_bitserial(g, A, W, s));
-    if (M <= kSkinnyMaxM) return hip_status(launch_gemm_skinny(g, A, W, s));
-    // Few output tiles and M <= 64: the tiled kernel would occupy a fraction of the chip with long K
-    // loops; the streaming kernel splits K over waves instead (one pass over W per 16 rows of A).
-    const long tiled_wgs = (long)((M + 63) / 64) * ((N + 63) / 64);
-    if (M <= 64 && tiled_wgs < 128) return hip_status(launch_gemm_skinny(g, A, W, s));
+    if (streaming_shape(M, N)) return hip_status(launch_gemm_skinny(g, A, W, s));
     return hip_status(launch_gemm_tiled(g, A, W, s));
+}
+
+// The fused call runs as one kernel when abq_gemm on the same problem would pick the streaming kernel
+// and the rows of A can be read as whole 16-byte vectors.
+static bool fused_act_direct(const WeightLayout& W, int force, int p, int q, int M, int N, int K)
+{
+    if (!W.has_fields || force == ABQ_USE_PLANES) return false;
+    if (!choose_fields(true, W.has_planes, force, p, q, M, N)) return false;
+    return streaming_shape(M, N) && K % 16 == 0;
+}
+
+size_t abq_gemm_act_codes_workspace_bytes(int p, int q, int M, int N, int K, int w_layout)
+{
+    if (check_gemm_shape(p, q, M, N, K) != ABQ_OK) return 0;
+    const int force = w_layout & (ABQ_USE_PLANES | ABQ_USE_FIELDS);
+    w_layout &= ~(ABQ_USE_PLANES | ABQ_USE_FIELDS);
+    WeightLayout W;
+    if (force == (ABQ_USE_PLANES | ABQ_USE_FIELDS) || !make_weight_layout(p, N, K, w_layout, &W)) return 0;
+    if (fused_act_direct(W, force, p, q, M, N, K)) return 0;
+    return abq_packed_act_bytes(q, M, K, w_layout) + abq_gemm_workspace_bytes(p, q, M, N, K);
+}
+
+int abq_gemm_act_codes(int p, int q, int M, int N, int K, const uint8_t* a_codes, const float* a_scale,
+                       const int32_t* a_zero, const void* packed_w, int w_layout, uint16_t* y_fp16, int32_t* acc_i32,
+                       void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!a_codes || !a_scale || !a_zero || !packed_w || !y_fp16) return ABQ_ERR_NULL;
+    if (int e = check_gemm_shape(p, q, M, N, K)) return e;
+    const int force = w_layout & (ABQ_USE_PLANES | ABQ_USE_FIELDS);
+    const int base_layout = w_layout & ~(ABQ_USE_PLANES | ABQ_USE_FIELDS);
+    if (force == (ABQ_USE_PLANES | ABQ_USE_FIELDS)) return ABQ_ERR_LAYOUT;
+    WeightLayout W;
+    if (!make_weight_layout(p, N, K, base_layout, &W)) return ABQ_ERR_LAYOUT;
+    if ((force == ABQ_USE_PLANES && !W.has_planes) || (force == ABQ_USE_FIELDS && !W.has_fields)) return ABQ_ERR_LAYOUT;
+    if (misaligned(a_codes) || misaligned(a_scale) || misaligned(a_zero) || misaligned(packed_w) || misaligned(y_fp16) ||
+        misaligned(acc_i32) || misaligned(workspace))
+        return ABQ_ERR_ALIGN;
+    hipStream_t s = (hipStream_t)stream;
+    if (fused_act_direct(W, force, p, q, M, N, K)) {
+        ActLayout A;
+        if (!make_act_layout(q, M, K, ABQ_LAYOUT_FIELDS, &A)) return ABQ_ERR_LAYOUT;
+        GemmArgs g{p, q, M, N, K, nullptr, a_codes, a_scale, a_zero, (const uint8_t*)packed_w, y_fp16, acc_i32, nullptr, 0};
+        return hip_status(launch_gemm_skinny(g, A, W, s));
+    }
+    // Otherwise the two steps run back to back, the packed activations living in the caller's workspace.
+    const size_t act_bytes = abq_packed_act_bytes(q, M, K, base_layout);
+    const size_t need = act_bytes + abq_gemm_workspace_bytes(p, q, M, N, K);
+    if (!workspace) return ABQ_ERR_NULL;
+    if (workspace_bytes < need) return ABQ_ERR_SIZE;
+    if (int e = abq_pack_act_codes(q, M, K, a_codes, a_scale, a_zero, base_layout, workspace, act_bytes, stream)) return e;
+    return abq_gemm(p, q, M, N, K, workspace, base_layout, packed_w, w_layout, y_fp16, acc_i32,
+                    (uint8_t*)workspace + act_bytes, workspace_bytes - act_bytes, stream);
 }
 
 }  // extern "C"

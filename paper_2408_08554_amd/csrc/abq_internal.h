@@ -72,7 +72,10 @@ hipError_t launch_unpack_act(const ActLayout& L, const uint8_t* blob, int which,
 
 struct GemmArgs {
     int p, q, M, N, K;
-    const uint8_t* act_blob;
+    const uint8_t* act_blob;   // packed activations, or null when a_raw is given (streaming kernel only)
+    const uint8_t* a_raw;      // unpacked codes [M][K] with a_scale[M], a_zero[M]: activation packing fused into the kernel
+    const float* a_scale;
+    const int32_t* a_zero;
     const uint8_t* w_blob;
     uint16_t* y;
     int32_t* acc;      // may be null

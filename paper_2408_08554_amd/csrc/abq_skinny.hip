@@ -37,8 +37,11 @@ __device__ unsigned long long g_phase_trace[1024 * 8 * 8];
 struct SkinnyParams {
     const u4v* fields[3];     // per plane group
     int chunks[3];
-    const int8_t* a_codes;    // [M][Kp]
+    const int8_t* a_codes;    // [M][Kp]  (packed activations)
     const RowParams* aparams;
+    const uint8_t* a_raw;     // [M][K] unpacked codes, with a_scale / a_zero: the fused-pack variant reads these instead
+    const float* a_scale;
+    const int32_t* a_zero;
     const RowParams* wparams;
     uint16_t* y;
     int32_t* acc;
@@ -52,6 +55,8 @@ struct SkinnyParams {
     int a_stride;             // bytes per staged row of A (Kp + 16: rows land 16 B apart in bank space)
     int par_off;              // byte offset in LDS of the staged per-row / per-channel parameters
     int red_off;              // byte offset in LDS of the two reduction buffers
+    int asum_off;             // byte offset in LDS of the per-wave partial row sums of A ([S][16] int32, fused-pack variant)
+    int zero_off;             // byte offset in LDS of 512 zero bytes
 };
 // Field t of a b-bit group as a signed-byte MFMA operand dword, and the power of two it is
 // scaled by.  The field that would touch the byte's sign bit is moved down one bit instead
@@ -128,6 +133,18 @@ __device__ __forceinline__ v4i group_combine(const v4i* acc)
     return r;
 }
 
+// Sum of v over the 64 lanes, returned in every lane: four DPP steps inside each row of 16
+// lanes, then the four row totals are read out as scalars.
+__device__ __forceinline__ int32_t wave_sum(int32_t v)
+{
+    v += __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xF, 0xF, false);    // quad_perm [1,0,3,2]
+    v += __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xF, 0xF, false);    // quad_perm [2,3,0,1]
+    v += __builtin_amdgcn_update_dpp(0, v, 0x141, 0xF, 0xF, false);   // row_half_mirror
+    v += __builtin_amdgcn_update_dpp(0, v, 0x140, 0xF, 0xF, false);   // row_mirror
+    return (__builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16)) +
+           (__builtin_amdgcn_readlane(v, 32) + __builtin_amdgcn_readlane(v, 48));
+}
+
 // One super-chunk of one tile: P wave loads of 1 KiB.  Every group stores whole super-chunks
 // (chunk count = b * Kp/512), so no load is conditional.
 template <int P>
@@ -145,15 +162,12 @@ __device__ __forceinline__ void load_super(const SkinnyParams& prm, int nsuper, 
 }
 
 template <int P>
-__device__ __forceinline__ void compute_super(const u4v* w, const uint8_t* lds_row, bool row_valid, v4i* acc)
+__device__ __forceinline__ void compute_super(const u4v* w, const uint8_t* lds_row, v4i* acc)
 {
     using GI = GroupInfo<P>;
     v4i aop[8];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        v4i v = *reinterpret_cast<const v4i*>(lds_row + j * 64);
-        aop[j] = row_valid ? v : v4i{0, 0, 0, 0};
-    }
+    for (int j = 0; j < 8; ++j) aop[j] = *reinterpret_cast<const v4i*>(lds_row + j * 64);
     group_mfma<GI::b(0)>(w + GI::load_base(0), aop, acc + GI::acc_base(0));
     if constexpr (GI::NG > 1) group_mfma<GI::b(1)>(w + GI::load_base(1), aop, acc + GI::acc_base(1));
     if constexpr (GI::NG > 2) group_mfma<GI::b(2)>(w + GI::load_base(2), aop, acc + GI::acc_base(2));
@@ -166,10 +180,11 @@ struct WaveState {
     int tile0, tstride;            // this workgroup's tiles: tile0 + i * tstride
     int p_ti, p_lsc;               // next item to prefetch
     int ti, lsc, parity;           // item being consumed
-    int lane, wave, tid, m0;
-    bool row_valid;
-    const uint8_t* lds_lane;       // this lane's A operand base in LDS
+    int lane, wave, tid, m0, mt;   // mt = rows of A this workgroup owns (<= 16)
+    const uint8_t* lds_lane;       // this lane's A operand base in LDS: its row of A, or a block of zeros for rows past mt
+    int k_mask;                    // ~0 for a row of A, 0 for the zero block (which has no k extent)
     const RowParams* par;          // LDS: [16] rows of A, then [nmy][16] channels
+    const int32_t* asum;           // LDS: [S][16] partial row sums of A (fused-pack variant)
     int32_t* red;
     v4i acc[GroupInfo<P>::NACC];
 #ifdef ABQ_PHASE_TRACE
@@ -186,7 +201,7 @@ __device__ __forceinline__ void prefetch_item(const SkinnyParams& prm, WaveState
 
 // End of a tile on this wave: bit reduction over the plane groups, sum over the S waves
 // through LDS (two buffers alternate, so one barrier per tile is enough), fused epilogue.
-template <int P, int EPT>
+template <int P, int EPT, bool RAW>
 __device__ __forceinline__ void finish_tile(const SkinnyParams& prm, WaveState<P>& st)
 {
     using GI = GroupInfo<P>;
@@ -212,12 +227,19 @@ __device__ __forceinline__ void finish_tile(const SkinnyParams& prm, WaveState<P
         const int e = st.tid + i * (int)blockDim.x;
         const int row = 4 * ((e & 63) >> 4) + (e >> 6);
         const int m = st.m0 + row;
-        if ((EPT > 1 || e < 256) && m < prm.M && n < prm.N) {
+        if ((EPT > 1 || e < 256) && row < st.mt && n < prm.N) {   // rows past mt belong to the next row group's workgroup
             int32_t part[8];
 #pragma unroll
             for (int ww = 0; ww < 8; ++ww) part[ww] = ww < st.S ? rb[ww * 256 + e] : 0;   // independent reads, one wait
             const int32_t s = ((part[0] + part[1]) + (part[2] + part[3])) + ((part[4] + part[5]) + (part[6] + part[7]));
-            epilogue_store(s, prm.oa, prm.ow, prm.K, st.par[row], pw, (size_t)m * prm.N + n, prm.y, prm.acc);
+            RowParams pa = st.par[row];
+            if constexpr (RAW) {   // the row sum of A was taken while staging, one part per wave
+                int32_t sp[8];
+#pragma unroll
+                for (int ww = 0; ww < 8; ++ww) sp[ww] = ww < st.S ? st.asum[ww * 16 + row] : 0;
+                pa.sum = ((sp[0] + sp[1]) + (sp[2] + sp[3])) + ((sp[4] + sp[5]) + (sp[6] + sp[7]));
+            }
+            epilogue_store(s, prm.oa, prm.ow, prm.K, pa, pw, (size_t)m * prm.N + n, prm.y, prm.acc);
         }
     }
     st.parity ^= 1;
@@ -225,18 +247,22 @@ __device__ __forceinline__ void finish_tile(const SkinnyParams& prm, WaveState<P
     ++st.ti;
 }
 
-template <int P, int EPT, bool REFILL>
+template <int P, int EPT, bool RAW, bool REFILL>
 __device__ __forceinline__ void item_step(const SkinnyParams& prm, WaveState<P>& st, u4v* slot, bool refill)
 {
-    compute_super<P>(slot, st.lds_lane + (st.wave + st.lsc * st.S) * kSuperK, st.row_valid, st.acc);
+    compute_super<P>(slot, st.lds_lane + (((st.wave + st.lsc * st.S) * kSuperK) & st.k_mask), st.acc);
     if (REFILL) prefetch_item<P>(prm, st, slot);
     else if (refill) prefetch_item<P>(prm, st, slot);
-    if (++st.lsc == st.nsw) finish_tile<P, EPT>(prm, st);
+    if (++st.lsc == st.nsw) finish_tile<P, EPT, RAW>(prm, st);
 }
 
 // D = super-chunks of weight loads each wave keeps in flight; EPT = C elements per thread in
-// the epilogue (1 for >= 4 waves, 2 for two waves, 4 for one).
-template <int P, int D, int EPT>
+// the epilogue (1 for >= 4 waves, 2 for two waves, 4 for one).  RAW: the activation BitPacking
+// step is fused in (Fig. 3b packs activations online; Sec. 3.4 folds that cost into existing
+// operators): A arrives as unpacked codes, is offset to signed bytes while it is staged, and
+// its row sums for the zero-point correction are taken on the way.
+// FULL: every wave of the launch has at least D items, so the ring prologue needs no conditions.
+template <int P, int D, int EPT, bool RAW, bool FULL>
 __global__ __launch_bounds__(512) void skinny_kernel(SkinnyParams prm)
 {
     using GI = GroupInfo<P>;
@@ -245,8 +271,8 @@ __global__ __launch_bounds__(512) void skinny_kernel(SkinnyParams prm)
     st.tid = threadIdx.x; st.lane = st.tid & 63; st.wave = st.tid >> 6; st.S = blockDim.x >> 6;
     st.m0 = blockIdx.y * prm.mrows;
     const int mt = min(prm.mrows, prm.M - st.m0);
+    st.mt = mt;
     const int r = st.lane & 15, G = st.lane >> 4;
-    st.row_valid = r < mt;
     st.nsuper = prm.nsuper;
     st.tile0 = blockIdx.x; st.tstride = gridDim.x;
     st.p_ti = 0; st.p_lsc = 0; st.ti = 0; st.lsc = 0; st.parity = 0;
@@ -256,48 +282,114 @@ __global__ __launch_bounds__(512) void skinny_kernel(SkinnyParams prm)
 #endif
     ABQ_TS(0);
 
-    // ---- the stream starts before anything else: first item = (tile0, super-chunk `wave`)
-    u4v w[D][P];
-    load_super<P>(prm, st.nsuper, st.tile0, st.wave, st.lane, w[0]);
     st.nsw = prm.sc_q + (st.wave < prm.sc_r ? 1 : 0);                       // this wave's super-chunks per tile (>= 1)
     const int nmy = prm.tl_q + ((int)blockIdx.x < prm.tl_r ? 1 : 0);         // this workgroup's tiles (>= 1)
     st.nitems = nmy * st.nsw;
-    if (++st.p_lsc == st.nsw) { st.p_lsc = 0; ++st.p_ti; }
-#pragma unroll
-    for (int d = 1; d < D; ++d)
-        if (d < st.nitems) prefetch_item<P>(prm, st, w[d]);
 
     // ---- epilogue parameters: entry i < 16 is row m0+i of A, entry 16 + 16*t + c is channel c of this
     // workgroup's t-th tile.  Loads use clamped indices so that none is conditional.
     RowParams* par = reinterpret_cast<RowParams*>(lds + prm.par_off);
     const int npar = 16 + nmy * 16;
     auto load_par = [&](int i) -> RowParams {
-        const RowParams* src = i < 16 ? prm.aparams + min(st.m0 + i, prm.M - 1)
-                                      : prm.wparams + min((st.tile0 + ((i - 16) >> 4) * st.tstride) * kTileN + (i & 15), prm.N - 1);
-        return *src;   // one unconditional load
+        if constexpr (RAW) {
+            const int m = min(st.m0 + min(i, 15), prm.M - 1);
+            const RowParams pa{0, prm.a_scale[m], prm.a_zero[m], 0};
+            const RowParams pw = prm.wparams[min((st.tile0 + (max(i - 16, 0) >> 4) * st.tstride) * kTileN + (i & 15), prm.N - 1)];
+            return i < 16 ? pa : pw;
+        } else {
+            const RowParams* src = i < 16 ? prm.aparams + min(st.m0 + i, prm.M - 1)
+                                          : prm.wparams + min((st.tile0 + ((i - 16) >> 4) * st.tstride) * kTileN + (i & 15), prm.N - 1);
+            return *src;   // one unconditional load
+        }
     };
     const RowParams par_first = load_par(min(st.tid, npar - 1));
 
-    // ---- stage this wave's part of A: columns of its own super-chunks, in every row (wave-private:
-    // only this wave reads what it writes, so no barrier is needed before the first MFMA).
-    // A load instruction covers two super-chunks of one row (2 x 32 vectors of 16 B).
-    const int8_t* a_base = prm.a_codes + (size_t)st.m0 * prm.Kp;
+    // ---- this wave's part of A: columns of its own super-chunks, in every row (wave-private: only this
+    // wave reads what it writes, so no barrier is needed before the first MFMA).  A load instruction
+    // covers two super-chunks of one row (2 x 32 vectors of 16 B); a batch is four rows of that.
+    // RAW: unpacked codes with K a multiple of 16, so a 16-byte vector is either all inside the row or
+    // all padding.  Valid bytes become a - oa (a xor 0x80 when q = 8), padding becomes 0, and lane `row`
+    // keeps that row's partial sum over this wave's super-chunks.
     const int half = st.lane >> 5, vec = st.lane & 31;
-    for (int pr = 0; pr < st.nsw; pr += 2) {
+    const uint8_t* a_base = RAW ? prm.a_raw + (size_t)st.m0 * prm.K : (const uint8_t*)prm.a_codes + (size_t)st.m0 * prm.Kp;
+    const int a_ld = RAW ? prm.K : prm.Kp;
+    const uint32_t flip = (RAW && prm.oa) ? 0x80808080u : 0u;
+    int32_t my_sum = 0;
+    auto batch_col = [&](int pr) { return (st.wave + min(pr + half, st.nsw - 1) * st.S) * kSuperK + vec * 16; };
+    auto batch_load = [&](int pr, int row0, uint4* areg) {
+        const int col = batch_col(pr);
+        const int colc = RAW ? min(col, prm.K - 16) : col;
+#pragma unroll
+        for (int u = 0; u < 4; ++u)   // row0 itself is always a row of A; the others are skipped when past mt (wave-uniform)
+            if (u == 0 || row0 + u < mt) areg[u] = *reinterpret_cast<const uint4*>(a_base + (size_t)(row0 + u) * a_ld + colc);
+    };
+    auto batch_store = [&](int pr, int row0, const uint4* areg) {
+        const int col = batch_col(pr);
         const bool lv = pr + half < st.nsw;
-        const int col = (st.wave + min(pr + half, st.nsw - 1) * st.S) * kSuperK + vec * 16;
-        for (int row0 = 0; row0 < mt; row0 += 4) {
-            uint4 areg[4];
+        const bool inside = !RAW || col < prm.K;
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
-                areg[u] = *reinterpret_cast<const uint4*>(a_base + (size_t)min(row0 + u, mt - 1) * prm.Kp + col);
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-                if (lv && row0 + u < mt) *reinterpret_cast<uint4*>(lds + (row0 + u) * prm.a_stride + col) = areg[u];
+        for (int u = 0; u < 4; ++u) {
+            if (u > 0 && row0 + u >= mt) break;   // wave-uniform
+            uint4 v = areg[u];
+            if constexpr (RAW) {
+                {
+                    uint32_t part = 0;
+                    part = __builtin_amdgcn_udot4(v.x, 0x01010101u, part, false);
+                    part = __builtin_amdgcn_udot4(v.y, 0x01010101u, part, false);
+                    part = __builtin_amdgcn_udot4(v.z, 0x01010101u, part, false);
+                    part = __builtin_amdgcn_udot4(v.w, 0x01010101u, part, false);
+                    const int32_t tot = wave_sum((lv && inside) ? (int32_t)part : 0);
+                    if (st.lane == row0 + u) my_sum += tot;
+                }
+                v = inside ? uint4{v.x ^ flip, v.y ^ flip, v.z ^ flip, v.w ^ flip} : uint4{0, 0, 0, 0};
+            }
+            if (lv) *reinterpret_cast<uint4*>(lds + (row0 + u) * prm.a_stride + col) = v;
         }
+    };
+    // The first two batches (rows 0..7 of the wave's first two super-chunks: all of A for M <= 8 and
+    // K <= 1024 * S) are loaded in straight-line code ahead of the weight stream, so that waiting for
+    // them does not wait for the stream behind them.
+    uint4 a0[4], a1[4];
+    batch_load(0, 0, a0);
+    const bool second = mt > 4;
+    if (second) batch_load(0, 4, a1);
+
+    // ---- the weight stream: first item = (tile0, super-chunk `wave`), then the rest of the ring
+    u4v w[D][P];
+    load_super<P>(prm, st.nsuper, st.tile0, st.wave, st.lane, w[0]);
+    if (++st.p_lsc == st.nsw) { st.p_lsc = 0; ++st.p_ti; }
+    if constexpr (FULL) {
+        // every wave has at least D items: the whole ring is issued unconditionally, the number of
+        // loads behind A is known, and the wait for A is exact
+#pragma unroll
+        for (int d = 1; d < D; ++d) prefetch_item<P>(prm, st, w[d]);
+        batch_store(0, 0, a0);
+        if (second) batch_store(0, 4, a1);
+    } else {
+        // short streams: A is staged behind the first item only (again an exact wait), the rest of
+        // the ring follows
+        batch_store(0, 0, a0);
+        if (second) batch_store(0, 4, a1);
+#pragma unroll
+        for (int d = 1; d < D; ++d)
+            if (d < st.nitems) prefetch_item<P>(prm, st, w[d]);
+    }
+    // whatever is left of A (more than 8 rows, or more than two super-chunks per wave)
+    for (int pr = 0; pr < st.nsw; pr += 2) {
+        for (int row0 = (pr == 0 ? 8 : 0); row0 < mt; row0 += 4) {
+            uint4 areg[4];
+            batch_load(pr, row0, areg);
+            batch_store(pr, row0, areg);
+        }
+    }
+    if constexpr (RAW) {
+        if (st.lane < 16) reinterpret_cast<int32_t*>(lds + prm.asum_off)[st.wave * 16 + st.lane] = my_sum;
     }
     if (st.tid < npar) par[st.tid] = par_first;
     for (int i = st.tid + blockDim.x; i < npar; i += blockDim.x) par[i] = load_par(i);
+    // MFMA rows past mt read a 512-byte block of zeros instead of A (every wave writes the same zeros,
+    // so this needs no barrier either)
+    if (st.lane < 32) *reinterpret_cast<uint4*>(lds + prm.zero_off + st.lane * 16) = uint4{0, 0, 0, 0};
     // same-wave LDS accesses execute in order; keep the compiler from moving the operand reads above
     // the staging writes (the parameters are read only after the first per-tile barrier)
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -309,9 +401,11 @@ __global__ __launch_bounds__(512) void skinny_kernel(SkinnyParams prm)
     ABQ_TS(2);
 #endif
 
-    st.lds_lane = lds + min(r, mt - 1) * prm.a_stride + G * 16;   // rows past mt re-read a valid row; their operand is zeroed
+    st.lds_lane = (r < mt ? lds + r * prm.a_stride : lds + prm.zero_off) + G * 16;
+    st.k_mask = r < mt ? ~0 : 0;
     st.par = par;
     st.red = reinterpret_cast<int32_t*>(lds + prm.red_off);
+    st.asum = reinterpret_cast<const int32_t*>(lds + prm.asum_off);
 #pragma unroll
     for (int i = 0; i < GI::NACC; ++i) st.acc[i] = v4i{0, 0, 0, 0};
 
@@ -322,7 +416,7 @@ __global__ __launch_bounds__(512) void skinny_kernel(SkinnyParams prm)
         for (; it + 2 * D <= st.nitems; it += D) {
 #pragma unroll
             for (int d = 0; d < D; ++d) {
-                compute_super<P>(w[d], st.lds_lane + (st.wave + st.lsc * st.S) * kSuperK, st.row_valid, st.acc);
+                compute_super<P>(w[d], st.lds_lane + (((st.wave + st.lsc * st.S) * kSuperK) & st.k_mask), st.acc);
                 prefetch_item<P>(prm, st, w[d]);
                 ++st.lsc;
             }
@@ -331,22 +425,22 @@ __global__ __launch_bounds__(512) void skinny_kernel(SkinnyParams prm)
 #pragma unroll
             for (int d = 0; d < D; ++d)
                 if (it + d < st.nitems) {
-                    compute_super<P>(w[d], st.lds_lane + (st.wave + st.lsc * st.S) * kSuperK, st.row_valid, st.acc);
+                    compute_super<P>(w[d], st.lds_lane + (((st.wave + st.lsc * st.S) * kSuperK) & st.k_mask), st.acc);
                     if (it + d + D < st.nitems) prefetch_item<P>(prm, st, w[d]);
                     ++st.lsc;
                 }
         }
-        finish_tile<P, EPT>(prm, st);
+        finish_tile<P, EPT, RAW>(prm, st);
     } else {
         // Several tiles per workgroup: the ring runs ahead across tile boundaries.
         for (; it + 2 * D <= st.nitems; it += D) {
 #pragma unroll
-            for (int d = 0; d < D; ++d) item_step<P, EPT, true>(prm, st, w[d], true);
+            for (int d = 0; d < D; ++d) item_step<P, EPT, RAW, true>(prm, st, w[d], true);
         }
         for (; it < st.nitems; it += D) {
 #pragma unroll
             for (int d = 0; d < D; ++d)
-                if (it + d < st.nitems) item_step<P, EPT, false>(prm, st, w[d], it + d + D < st.nitems);
+                if (it + d < st.nitems) item_step<P, EPT, RAW, false>(prm, st, w[d], it + d + D < st.nitems);
         }
     }
 #ifdef ABQ_PHASE_TRACE
@@ -375,6 +469,7 @@ static int num_cus()
 // The kernels use up to 256 VGPRs, i.e. two waves per SIMD, eight per CU.
 static const int kWavesPerCu = 8;
 static const size_t kLdsPerCu = 160 * 1024;
+static const size_t kAsumBytes = 8 * 16 * sizeof(int32_t) + 512;   // per-wave partial row sums of A and 512 zero bytes, kept at the end of the parameter area
 
 // Launch plan: S waves per workgroup (= K split of a tile) and gx workgroups walking the tiles.
 // What it trades off (the analogue of the paper's tile-shape search, Appendix D "Auto Kernel
@@ -392,7 +487,7 @@ static bool make_plan(int S, int M, int Kp, int ntiles, int cus, SkinnyPlan* out
     const size_t red_bytes = 2 * (size_t)S * 1024;
     int mrows = M < 16 ? M : 16;
     // first guess of the per-workgroup tile count (for the parameter area), refined once gx is known
-    size_t par_bytes = (size_t)(16 + 16) * sizeof(RowParams);
+    size_t par_bytes = (size_t)(16 + 16) * sizeof(RowParams) + kAsumBytes;
     for (int pass = 0; pass < 2; ++pass) {
         const size_t budget = kLdsPerCu - red_bytes - par_bytes - 64;
         if ((size_t)mrows * a_stride > budget) mrows = (int)(budget / a_stride);
@@ -403,7 +498,7 @@ static bool make_plan(int S, int M, int Kp, int ntiles, int cus, SkinnyPlan* out
         if (per_cu < 1) per_cu = 1;
         int gx = ntiles < cus * per_cu ? ntiles : cus * per_cu;
         const int rounds = (ntiles + gx - 1) / gx;
-        par_bytes = (size_t)(16 + rounds * 16) * sizeof(RowParams);
+        par_bytes = (size_t)(16 + rounds * 16) * sizeof(RowParams) + kAsumBytes;
         if (pass == 1) {
             out->waves = S; out->gx = gx; out->mrows = mrows;
             out->par_bytes = par_bytes; out->red_bytes = red_bytes;
@@ -456,17 +551,28 @@ static bool pick_plan(int M, int Kp, int ntiles, int cus, size_t stream_bytes, S
     return ok;
 }
 
-template <int P, int D, int EPT>
-static hipError_t launch_pde(const SkinnyParams& prm, dim3 grid, int waves, size_t lds_bytes, hipStream_t s)
+template <int P, int D, int EPT, bool RAW, bool FULL>
+static hipError_t launch_pderf(const SkinnyParams& prm, dim3 grid, int waves, size_t lds_bytes, hipStream_t s)
 {
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)skinny_kernel<P, D, EPT>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        hipError_t e = hipFuncSetAttribute((const void*)skinny_kernel<P, D, EPT, RAW, FULL>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    skinny_kernel<P, D, EPT><<<grid, waves * 64, lds_bytes, s>>>(prm);
+    skinny_kernel<P, D, EPT, RAW, FULL><<<grid, waves * 64, lds_bytes, s>>>(prm);
     return hipGetLastError();
+}
+
+template <int P, int D, int EPT>
+static hipError_t launch_pde(const SkinnyParams& prm, dim3 grid, int waves, size_t lds_bytes, hipStream_t s)
+{
+    const bool full = prm.tl_q * prm.sc_q >= D;   // the fewest items any wave has
+    if (prm.a_raw)
+        return full ? launch_pderf<P, D, EPT, true, true>(prm, grid, waves, lds_bytes, s)
+                    : launch_pderf<P, D, EPT, true, false>(prm, grid, waves, lds_bytes, s);
+    return full ? launch_pderf<P, D, EPT, false, true>(prm, grid, waves, lds_bytes, s)
+                : launch_pderf<P, D, EPT, false, false>(prm, grid, waves, lds_bytes, s);
 }
 
 template <int P, int D>
@@ -484,8 +590,14 @@ hipError_t launch_gemm_skinny(const GemmArgs& g, const ActLayout& A, const Weigh
         prm.fields[i] = (const u4v*)(g.w_blob + W.off_fields[i]);
         prm.chunks[i] = W.chunks[i];
     }
-    prm.a_codes = (const int8_t*)(g.act_blob + A.off_codes);
-    prm.aparams = (const RowParams*)(g.act_blob + A.off_params);
+    if (g.a_raw) {
+        prm.a_codes = nullptr; prm.aparams = nullptr;
+        prm.a_raw = g.a_raw; prm.a_scale = g.a_scale; prm.a_zero = g.a_zero;
+    } else {
+        prm.a_codes = (const int8_t*)(g.act_blob + A.off_codes);
+        prm.aparams = (const RowParams*)(g.act_blob + A.off_params);
+        prm.a_raw = nullptr; prm.a_scale = nullptr; prm.a_zero = nullptr;
+    }
     prm.wparams = (const RowParams*)(g.w_blob + W.off_params);
     prm.y = g.y;
     prm.acc = g.acc;
@@ -504,6 +616,8 @@ hipError_t launch_gemm_skinny(const GemmArgs& g, const ActLayout& A, const Weigh
     prm.mrows = mrows;
     prm.par_off = (int)align_up((size_t)mrows * prm.a_stride, 16);
     prm.red_off = prm.par_off + (int)pl.par_bytes;
+    prm.asum_off = prm.red_off - (int)kAsumBytes;
+    prm.zero_off = prm.red_off - 512;
     const size_t lds_bytes = pl.lds_bytes;
     prm.nsuper = nsuper;
     prm.sc_q = nsuper / waves; prm.sc_r = nsuper % waves;

@@ -31,6 +31,16 @@ def gpu_gemm(torch, abq, c, a_layout, w_layout, gemm_w_layout=None, want_acc=Tru
     return y.cpu().numpy(), (acc.cpu().numpy() if acc is not None else None)
 
 
+def gpu_gemm_fused(torch, abq, c, w_layout, gemm_w_layout=None, want_acc=True):
+    """pack the weights, then abq_gemm_act_codes on the unpacked activation codes."""
+    pw = abq.abq_pack_weights(c.p, to_dev(torch, c.W), to_dev(torch, c.w_scale), to_dev(torch, c.w_zero), w_layout)
+    y, acc = abq.abq_gemm_act_codes(c.p, c.q, c.M, c.N, c.K, to_dev(torch, c.A), to_dev(torch, c.a_scale),
+                                    to_dev(torch, c.a_zero), pw, w_layout if gemm_w_layout is None else gemm_w_layout,
+                                    want_acc=want_acc)
+    torch.cuda.synchronize()
+    return y.cpu().numpy(), (acc.cpu().numpy() if acc is not None else None)
+
+
 def check_against_oracle(c, y, acc, tight=True):
     ref_acc = oracle.acc(c.A, c.W)
     assert ref_acc.max() <= np.iinfo(np.int32).max

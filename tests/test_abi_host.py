@@ -103,6 +103,42 @@ def test_gemm_rejects():
     assert gemm(lib, acc=A16 + 4) == B.ABQ_ERR_ALIGN
 
 
+def gemm_fused(lib, p=4, q=8, M=1, N=16, K=64, a=A16, sc=A16, zp=A16, pw=A16, wl=0, y=A16, acc=None, ws=None, wsb=0):
+    return lib.abq_gemm_act_codes(p, q, M, N, K, a, sc, zp, pw, wl, y, acc, ws, wsb, None)
+
+
+def test_gemm_act_codes_rejects_and_workspace_query():
+    lib = B.load()
+    assert gemm_fused(lib, a=None) == B.ABQ_ERR_NULL
+    assert gemm_fused(lib, zp=None) == B.ABQ_ERR_NULL
+    assert gemm_fused(lib, y=None) == B.ABQ_ERR_NULL
+    assert gemm_fused(lib, p=9) == B.ABQ_ERR_BITS
+    assert gemm_fused(lib, N=0) == B.ABQ_ERR_SHAPE
+    assert gemm_fused(lib, p=8, q=8, K=33026) == B.ABQ_ERR_SHAPE
+    assert gemm_fused(lib, wl=7) == B.ABQ_ERR_LAYOUT
+    assert gemm_fused(lib, wl=B.ABQ_LAYOUT_FIELDS | B.ABQ_USE_PLANES) == B.ABQ_ERR_LAYOUT
+    assert gemm_fused(lib, a=A16 + 1) == B.ABQ_ERR_ALIGN
+    q = lib.abq_gemm_act_codes_workspace_bytes
+    # one kernel: decode shapes on field-packed weights with K a multiple of 16
+    assert q(4, 8, 1, 4096, 4096, B.ABQ_LAYOUT_FIELDS) == 0
+    assert q(2, 8, 8, 4096, 11008, B.ABQ_LAYOUT_AUTO) == 0
+    assert q(6, 6, 16, 64, 48, B.ABQ_LAYOUT_BOTH) == 0
+    # two kernels: the packed activations live in the workspace
+    for args in [(4, 8, 1, 4096, 4090, B.ABQ_LAYOUT_FIELDS),      # K not a multiple of 16
+                 (6, 6, 128, 11008, 4096, B.ABQ_LAYOUT_FIELDS),   # prefill shape
+                 (2, 8, 1, 4096, 4096, B.ABQ_LAYOUT_PLANES),      # bit-serial family
+                 (1, 1, 1, 13824, 5120, B.ABQ_LAYOUT_BOTH),       # auto dispatch picks bit-serial here
+                 (4, 8, 1, 4096, 4096, B.ABQ_LAYOUT_BOTH | B.ABQ_USE_PLANES)]:
+        p_, q_, M, N, K, wl = args
+        assert q(*args) == lib.abq_packed_act_bytes(q_, M, K, wl & 3) + lib.abq_gemm_workspace_bytes(p_, q_, M, N, K)
+        assert q(*args) > 0
+    assert q(0, 8, 1, 16, 64, 0) == 0 and q(4, 8, 1, 16, 64, 9) == 0
+    # a needed workspace that is missing or too small is an error before any HIP call
+    assert gemm_fused(lib, M=128, N=11008, K=4096) == B.ABQ_ERR_NULL
+    assert gemm_fused(lib, M=128, N=11008, K=4096, ws=A16, wsb=64) == B.ABQ_ERR_SIZE
+    assert gemm_fused(lib, K=40, ws=A16, wsb=64) == B.ABQ_ERR_SIZE
+
+
 def test_unpack_rejects():
     lib = B.load()
     assert lib.abq_unpack_weights(4, 16, 64, B.ABQ_LAYOUT_FIELDS, A16, B.ABQ_LAYOUT_PLANES, A16, None) == B.ABQ_ERR_LAYOUT

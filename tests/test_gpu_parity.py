@@ -7,7 +7,7 @@ import pytest
 
 import oracle
 from paper_2408_08554_amd import synth
-from helpers import check_against_oracle, check_sampled, gpu_gemm, to_dev
+from helpers import check_against_oracle, check_sampled, gpu_gemm, gpu_gemm_fused, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -81,7 +81,7 @@ def test_all_pq_small(abq, layout, p, q):
 
 
 SHAPES = [(1, 256, 512), (1, 17, 100), (2, 16, 32), (8, 100, 96), (16, 64, 2048), (5, 33, 1), (7, 1, 513),
-          (1, 48, 5120), (4, 31, 13824), (17, 20, 700), (33, 50, 1536), (64, 16, 640)]
+          (1, 48, 5120), (4, 31, 13824), (17, 20, 700), (33, 50, 1536), (64, 16, 640), (16, 70, 13824), (15, 33, 9000)]
 
 
 @pytest.mark.parametrize("layout", [FIELDS, PLANES], ids=["mfma", "bitserial"])
@@ -198,6 +198,75 @@ def test_output_overwrites_poison_and_is_deterministic(abq):
 
 
 # ---- the benchmark configurations at full size -------------------------------------------------
+
+# ---- activation packing fused into the matmul ------------------------------------------------------
+
+@pytest.mark.parametrize("p,q", list(itertools.product(range(1, 9), range(1, 9))))
+def test_fused_act_all_pq(abq, p, q):
+    say("fused pq", p, q)
+    c = synth.make_case(p, q, 3, 40, 1104, seed=synth.case_seed(7, p, q), name=f"fused W{p}A{q} 3x40x1104")
+    assert abq.abq_gemm_act_codes_workspace_bytes(p, q, c.M, c.N, c.K, FIELDS) == 0
+    y, acc = gpu_gemm_fused(torch, abq, c, FIELDS)
+    check_against_oracle(c, y, acc)
+
+
+FUSED_SHAPES = [(1, 256, 512), (1, 17, 112), (2, 16, 32), (8, 100, 96), (16, 64, 2048), (5, 33, 16), (7, 1, 528),
+                (1, 48, 5120), (4, 31, 13824), (13, 4096, 4096), (16, 300, 8192), (16, 70, 13824), (33, 50, 1536),
+                (64, 16, 640), (1, 13824, 5120)]
+
+
+@pytest.mark.parametrize("M,N,K", FUSED_SHAPES)
+@pytest.mark.parametrize("p,q", [(2, 8), (4, 8), (6, 6), (8, 8), (3, 5), (7, 7), (1, 1), (5, 2)])
+def test_fused_act_shapes(abq, M, N, K, p, q):
+    say("fused shape", M, N, K, p, q)
+    c = synth.make_case(p, q, M, N, K, seed=synth.case_seed(6, p, q) + M + N + K, name=f"fused W{p}A{q} {M}x{N}x{K}")
+    assert abq.abq_gemm_act_codes_workspace_bytes(p, q, M, N, K, FIELDS) == 0
+    y, acc = gpu_gemm_fused(torch, abq, c, FIELDS)
+    if M * N * K <= 1 << 28:
+        check_against_oracle(c, y, acc)
+    else:
+        check_sampled(c, y, acc)
+
+
+@pytest.mark.parametrize("M,N,K,layout,flag", [(1, 64, 1000, FIELDS, 0),        # K not a multiple of 16
+                                               (128, 130, 512, FIELDS, 0),      # prefill shape: tiled kernel
+                                               (3, 40, 640, PLANES, 0),         # bit-serial family
+                                               (2, 48, 512, BOTH, 0x10),        # planes forced on a blob with both
+                                               (2, 48, 512, BOTH, 0x20),        # fields forced: one kernel again
+                                               (1, 8192, 512, BOTH, 0)])        # auto dispatch -> bit-serial (p=2, q=4)
+def test_fused_act_two_step_paths(abq, M, N, K, layout, flag):
+    say("fused fallback", M, N, K, layout, flag)
+    p, q = (2, 4) if N == 8192 else (4, 8)
+    c = synth.make_case(p, q, M, N, K, seed=synth.case_seed(5, p, q) + M + N + K, name=f"fused2 W{p}A{q} {M}x{N}x{K}")
+    need = abq.abq_gemm_act_codes_workspace_bytes(p, q, M, N, K, layout | flag)
+    assert (need == 0) == (flag == 0x20)
+    y, acc = gpu_gemm_fused(torch, abq, c, layout, gemm_w_layout=layout | flag)
+    check_against_oracle(c, y, acc)
+
+
+def test_fused_act_equals_two_calls_bitwise(abq):
+    """The fused call and pack + gemm give the same bits (config-3 activations: rounded Gaussian codes)."""
+    for M in (1, 8):
+        c = synth.config3(M)
+        say("fused vs two calls", c.name)
+        y1, acc1 = gpu_gemm(torch, abq, c, FIELDS, FIELDS)
+        y2, acc2 = gpu_gemm_fused(torch, abq, c, FIELDS)
+        assert np.array_equal(acc1, acc2)
+        assert np.array_equal(y1.view(np.uint16), y2.view(np.uint16))
+        check_against_oracle(c, y2, acc2)
+
+
+def test_fused_act_extreme_codes(abq):
+    """All-maximum codes: the largest row sums and the q = 8 offset at its limit."""
+    for p, q, K in [(8, 8, 33024), (4, 8, 4096), (8, 4, 2048)]:
+        c = synth.make_case(p, q, 5, 48, K, seed=3, name=f"fused max W{p}A{q} K={K}")
+        c.A[:] = (1 << q) - 1
+        c.W[:] = (1 << p) - 1
+        c.A[1] = 0
+        say(c.name)
+        y, acc = gpu_gemm_fused(torch, abq, c, FIELDS)
+        check_against_oracle(c, y, acc)
+
 
 def test_config1_tiny(abq):
     c = synth.config1()
