@@ -57,7 +57,26 @@ struct SkinnyParams {
     int red_off;              // byte offset in LDS of the two reduction buffers
     int asum_off;             // byte offset in LDS of the per-wave partial row sums of A ([S][16] int32, fused-pack variant)
     int zero_off;             // byte offset in LDS of 512 zero bytes
+    // K groups (long K with up to 16 rows of A: all of A does not fit LDS at once).  A wave's nsw super-chunks
+    // are cut into kgroups runs [g*nsw/kgroups, (g+1)*nsw/kgroups); the workgroup walks its tiles once per
+    // run with only that run's columns of A staged, keeping per-tile partial sums in LDS in between.
+    int kgroups;              // 1: everything staged once
+    int col_w, col_s;         // LDS column of (wave, slot) = wave*col_w + slot*col_s  (slot = super-chunk index inside the run)
+    int part_off;             // byte offset in LDS of the partial sums [S][nmy_max][256] int32 (kgroups > 1)
+    int nmy_max;              // most tiles any workgroup owns
 };
+
+// g * n / G for the few group counts the host uses (constant divisors).
+__device__ __forceinline__ int group_bound(int g, int n, int G)
+{
+    const int x = g * n;
+    switch (G) {
+        case 1: return x;
+        case 2: return x >> 1;
+        case 3: return x / 3;
+        default: return x >> 2;
+    }
+}
 // Field t of a b-bit group as a signed-byte MFMA operand dword, and the power of two it is
 // scaled by.  The field that would touch the byte's sign bit is moved down one bit instead
 // (b = 2, 4) or taken as is with weight -128 (b = 1).
@@ -180,6 +199,10 @@ struct WaveState {
     int tile0, tstride;            // this workgroup's tiles: tile0 + i * tstride
     int p_ti, p_lsc;               // next item to prefetch
     int ti, lsc, parity;           // item being consumed
+    int nmy;                       // tiles this workgroup owns
+    int g, gs, ge;                 // K group being consumed and its run [gs, ge) of this wave's super-chunks
+    int p_g, p_gs, p_ge;           // the same for the prefetch side
+    int32_t* part;                 // LDS: this wave's partial sums [nmy_max][256] (kgroups > 1)
     int lane, wave, tid, m0, mt;   // mt = rows of A this workgroup owns (<= 16)
     const uint8_t* lds_lane;       // this lane's A operand base in LDS: its row of A, or a block of zeros for rows past mt
     int k_mask;                    // ~0 for a row of A, 0 for the zero block (which has no k extent)
@@ -192,16 +215,37 @@ struct WaveState {
 #endif
 };
 
-template <int P>
+// Item order: (K group,) tile, super-chunk.
+template <int P, bool KG = false>
 __device__ __forceinline__ void prefetch_item(const SkinnyParams& prm, WaveState<P>& st, u4v* slot)
 {
     load_super<P>(prm, st.nsuper, st.tile0 + st.p_ti * st.tstride, st.wave + st.p_lsc * st.S, st.lane, slot);
-    if (++st.p_lsc == st.nsw) { st.p_lsc = 0; ++st.p_ti; }
+    if constexpr (!KG) {
+        if (++st.p_lsc == st.nsw) { st.p_lsc = 0; ++st.p_ti; }
+    } else {
+        if (++st.p_lsc == st.p_ge) {
+            if (++st.p_ti == st.nmy) {
+                st.p_ti = 0;
+                ++st.p_g;
+                st.p_gs = st.p_ge;
+                st.p_ge = group_bound(st.p_g + 1, st.nsw, prm.kgroups);
+            }
+            st.p_lsc = st.p_gs;
+        }
+    }
+}
+
+// LDS address of this lane's A operand for the super-chunk being consumed.
+template <int P, bool KG>
+__device__ __forceinline__ const uint8_t* operand_row(const SkinnyParams& prm, const WaveState<P>& st)
+{
+    if constexpr (!KG) return st.lds_lane + (((st.wave + st.lsc * st.S) * kSuperK) & st.k_mask);
+    else return st.lds_lane + ((st.wave * prm.col_w + (st.lsc - st.gs) * prm.col_s) & st.k_mask);
 }
 
 // End of a tile on this wave: bit reduction over the plane groups, sum over the S waves
 // through LDS (two buffers alternate, so one barrier per tile is enough), fused epilogue.
-template <int P, int EPT, bool RAW>
+template <int P, int EPT, bool RAW, bool KG = false>
 __device__ __forceinline__ void finish_tile(const SkinnyParams& prm, WaveState<P>& st)
 {
     using GI = GroupInfo<P>;
@@ -211,6 +255,20 @@ __device__ __forceinline__ void finish_tile(const SkinnyParams& prm, WaveState<P
     if constexpr (GI::NG > 2) total += group_combine<GI::b(2)>(st.acc + GI::acc_base(2)) << GI::load_base(2);
 #pragma unroll
     for (int i = 0; i < GI::NACC; ++i) st.acc[i] = v4i{0, 0, 0, 0};
+    if constexpr (KG) {
+        // all but the last K group: the tile's sum so far stays in this wave's own part of LDS
+        int32_t* pp = st.part + st.ti * 256 + st.lane;
+        if (st.g > 0) {
+#pragma unroll
+            for (int reg = 0; reg < 4; ++reg) total[reg] += pp[reg * 64];
+        }
+        if (st.g < prm.kgroups - 1) {
+#pragma unroll
+            for (int reg = 0; reg < 4; ++reg) pp[reg * 64] = total[reg];
+            ++st.ti;
+            return;
+        }
+    }
     int32_t* rb = st.red + st.parity * (st.S * 256);
 #pragma unroll
     for (int reg = 0; reg < 4; ++reg) rb[(st.wave * 4 + reg) * 64 + st.lane] = total[reg];
@@ -243,17 +301,32 @@ __device__ __forceinline__ void finish_tile(const SkinnyParams& prm, WaveState<P
         }
     }
     st.parity ^= 1;
-    st.lsc = 0;
     ++st.ti;
 }
 
-template <int P, int EPT, bool RAW, bool REFILL>
-__device__ __forceinline__ void item_step(const SkinnyParams& prm, WaveState<P>& st, u4v* slot, bool refill)
+// One item: MFMAs, refill of its ring slot, end-of-tile work.  With K groups, the end of a group's last
+// tile moves on to the next run of super-chunks and stages its columns of A (next_group).
+template <int P, int EPT, bool RAW, bool KG, bool REFILL, typename F>
+__device__ __forceinline__ void item_step(const SkinnyParams& prm, WaveState<P>& st, u4v* slot, bool refill, F&& next_group)
 {
-    compute_super<P>(slot, st.lds_lane + (((st.wave + st.lsc * st.S) * kSuperK) & st.k_mask), st.acc);
-    if (REFILL) prefetch_item<P>(prm, st, slot);
-    else if (refill) prefetch_item<P>(prm, st, slot);
-    if (++st.lsc == st.nsw) finish_tile<P, EPT, RAW>(prm, st);
+    compute_super<P>(slot, operand_row<P, KG>(prm, st), st.acc);
+    if (REFILL) prefetch_item<P, KG>(prm, st, slot);
+    else if (refill) prefetch_item<P, KG>(prm, st, slot);
+    if constexpr (!KG) {
+        if (++st.lsc == st.nsw) { finish_tile<P, EPT, RAW>(prm, st); st.lsc = 0; }
+    } else {
+        if (++st.lsc == st.ge) {
+            finish_tile<P, EPT, RAW, true>(prm, st);
+            if (st.ti == st.nmy) {
+                st.ti = 0;
+                ++st.g;
+                st.gs = st.ge;
+                st.ge = group_bound(st.g + 1, st.nsw, prm.kgroups);
+                if (st.g < prm.kgroups) next_group();
+            }
+            st.lsc = st.gs;
+        }
+    }
 }
 
 // D = super-chunks of weight loads each wave keeps in flight; EPT = C elements per thread in
@@ -262,9 +335,11 @@ __device__ __forceinline__ void item_step(const SkinnyParams& prm, WaveState<P>&
 // operators): A arrives as unpacked codes, is offset to signed bytes while it is staged, and
 // its row sums for the zero-point correction are taken on the way.
 // FULL: every wave of the launch has at least D items, so the ring prologue needs no conditions.
-template <int P, int D, int EPT, bool RAW, bool FULL>
+// KG: K groups (see SkinnyParams); never together with FULL.
+template <int P, int D, int EPT, bool RAW, bool FULL, bool KG>
 __global__ __launch_bounds__(512) void skinny_kernel(SkinnyParams prm)
 {
+    static_assert(!(FULL && KG), "the K-group variant uses the conditional ring prologue");
     using GI = GroupInfo<P>;
     extern __shared__ __align__(16) uint8_t lds[];
     WaveState<P> st;
@@ -285,6 +360,9 @@ __global__ __launch_bounds__(512) void skinny_kernel(SkinnyParams prm)
     st.nsw = prm.sc_q + (st.wave < prm.sc_r ? 1 : 0);                       // this wave's super-chunks per tile (>= 1)
     const int nmy = prm.tl_q + ((int)blockIdx.x < prm.tl_r ? 1 : 0);         // this workgroup's tiles (>= 1)
     st.nitems = nmy * st.nsw;
+    st.nmy = nmy;
+    st.g = 0; st.gs = 0; st.ge = KG ? group_bound(1, st.nsw, prm.kgroups) : st.nsw;
+    st.p_g = 0; st.p_gs = 0; st.p_ge = st.ge;
 
     // ---- epilogue parameters: entry i < 16 is row m0+i of A, entry 16 + 16*t + c is channel c of this
     // workgroup's t-th tile.  Loads use clamped indices so that none is conditional.
@@ -315,7 +393,12 @@ __global__ __launch_bounds__(512) void skinny_kernel(SkinnyParams prm)
     const int a_ld = RAW ? prm.K : prm.Kp;
     const uint32_t flip = (RAW && prm.oa) ? 0x80808080u : 0u;
     int32_t my_sum = 0;
-    auto batch_col = [&](int pr) { return (st.wave + min(pr + half, st.nsw - 1) * st.S) * kSuperK + vec * 16; };
+    // column of A in global memory / in LDS for slot pr + half of the run [st.gs, st.ge) being staged
+    auto batch_col = [&](int pr) { return (st.wave + (st.gs + min(pr + half, st.ge - st.gs - 1)) * st.S) * kSuperK + vec * 16; };
+    auto batch_lds_col = [&](int pr) {
+        if constexpr (!KG) return batch_col(pr);
+        else return st.wave * prm.col_w + min(pr + half, st.ge - st.gs - 1) * prm.col_s + vec * 16;
+    };
     auto batch_load = [&](int pr, int row0, uint4* areg) {
         const int col = batch_col(pr);
         const int colc = RAW ? min(col, prm.K - 16) : col;
@@ -325,7 +408,8 @@ __global__ __launch_bounds__(512) void skinny_kernel(SkinnyParams prm)
     };
     auto batch_store = [&](int pr, int row0, const uint4* areg) {
         const int col = batch_col(pr);
-        const bool lv = pr + half < st.nsw;
+        const int lcol = batch_lds_col(pr);
+        const bool lv = pr + half < st.ge - st.gs;
         const bool inside = !RAW || col < prm.K;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
@@ -343,7 +427,7 @@ __global__ __launch_bounds__(512) void skinny_kernel(SkinnyParams prm)
                 }
                 v = inside ? uint4{v.x ^ flip, v.y ^ flip, v.z ^ flip, v.w ^ flip} : uint4{0, 0, 0, 0};
             }
-            if (lv) *reinterpret_cast<uint4*>(lds + (row0 + u) * prm.a_stride + col) = v;
+            if (lv) *reinterpret_cast<uint4*>(lds + (row0 + u) * prm.a_stride + lcol) = v;
         }
     };
     // The first two batches (rows 0..7 of the wave's first two super-chunks: all of A for M <= 8 and
@@ -356,13 +440,12 @@ __global__ __launch_bounds__(512) void skinny_kernel(SkinnyParams prm)
 
     // ---- the weight stream: first item = (tile0, super-chunk `wave`), then the rest of the ring
     u4v w[D][P];
-    load_super<P>(prm, st.nsuper, st.tile0, st.wave, st.lane, w[0]);
-    if (++st.p_lsc == st.nsw) { st.p_lsc = 0; ++st.p_ti; }
+    prefetch_item<P, KG>(prm, st, w[0]);
     if constexpr (FULL) {
         // every wave has at least D items: the whole ring is issued unconditionally, the number of
         // loads behind A is known, and the wait for A is exact
 #pragma unroll
-        for (int d = 1; d < D; ++d) prefetch_item<P>(prm, st, w[d]);
+        for (int d = 1; d < D; ++d) prefetch_item<P, KG>(prm, st, w[d]);
         batch_store(0, 0, a0);
         if (second) batch_store(0, 4, a1);
     } else {
@@ -372,19 +455,23 @@ __global__ __launch_bounds__(512) void skinny_kernel(SkinnyParams prm)
         if (second) batch_store(0, 4, a1);
 #pragma unroll
         for (int d = 1; d < D; ++d)
-            if (d < st.nitems) prefetch_item<P>(prm, st, w[d]);
+            if (d < st.nitems) prefetch_item<P, KG>(prm, st, w[d]);
     }
-    // whatever is left of A (more than 8 rows, or more than two super-chunks per wave)
-    for (int pr = 0; pr < st.nsw; pr += 2) {
-        for (int row0 = (pr == 0 ? 8 : 0); row0 < mt; row0 += 4) {
-            uint4 areg[4];
-            batch_load(pr, row0, areg);
-            batch_store(pr, row0, areg);
+    // whatever is left of A (more than 8 rows, or more than two super-chunks per wave); with K groups also
+    // every later run, staged over the columns of the run before it once that run's last tile is done
+    auto stage_rest = [&](int first_row0) {
+        for (int pr = 0; pr < st.ge - st.gs; pr += 2) {
+            for (int row0 = (pr == 0 ? first_row0 : 0); row0 < mt; row0 += 4) {
+                uint4 areg[4];
+                batch_load(pr, row0, areg);
+                batch_store(pr, row0, areg);
+            }
         }
-    }
-    if constexpr (RAW) {
-        if (st.lane < 16) reinterpret_cast<int32_t*>(lds + prm.asum_off)[st.wave * 16 + st.lane] = my_sum;
-    }
+        if constexpr (RAW) {
+            if (st.lane < 16) reinterpret_cast<int32_t*>(lds + prm.asum_off)[st.wave * 16 + st.lane] = my_sum;
+        }
+    };
+    stage_rest(8);
     if (st.tid < npar) par[st.tid] = par_first;
     for (int i = st.tid + blockDim.x; i < npar; i += blockDim.x) par[i] = load_par(i);
     // MFMA rows past mt read a 512-byte block of zeros instead of A (every wave writes the same zeros,
@@ -406,11 +493,18 @@ __global__ __launch_bounds__(512) void skinny_kernel(SkinnyParams prm)
     st.par = par;
     st.red = reinterpret_cast<int32_t*>(lds + prm.red_off);
     st.asum = reinterpret_cast<const int32_t*>(lds + prm.asum_off);
+    st.part = reinterpret_cast<int32_t*>(lds + prm.part_off) + st.wave * prm.nmy_max * 256;
+    auto next_group = [&]() {
+        stage_rest(0);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    };
 #pragma unroll
     for (int i = 0; i < GI::NACC; ++i) st.acc[i] = v4i{0, 0, 0, 0};
 
     int it = 0;
-    if (nmy == 1) {
+    if (!KG && nmy == 1) {
         // One tile per workgroup (the usual case): the K loop holds loads only, so the compiler's
         // waits are exact and P*(D-1) loads stay in flight; the tile is finished after the loop.
         for (; it + 2 * D <= st.nitems; it += D) {
@@ -435,12 +529,12 @@ __global__ __launch_bounds__(512) void skinny_kernel(SkinnyParams prm)
         // Several tiles per workgroup: the ring runs ahead across tile boundaries.
         for (; it + 2 * D <= st.nitems; it += D) {
 #pragma unroll
-            for (int d = 0; d < D; ++d) item_step<P, EPT, RAW, true>(prm, st, w[d], true);
+            for (int d = 0; d < D; ++d) item_step<P, EPT, RAW, KG, true>(prm, st, w[d], true, next_group);
         }
         for (; it < st.nitems; it += D) {
 #pragma unroll
             for (int d = 0; d < D; ++d)
-                if (it + d < st.nitems) item_step<P, EPT, RAW, false>(prm, st, w[d], it + d + D < st.nitems);
+                if (it + d < st.nitems) item_step<P, EPT, RAW, KG, false>(prm, st, w[d], it + d + D < st.nitems, next_group);
         }
     }
 #ifdef ABQ_PHASE_TRACE
@@ -477,102 +571,142 @@ static const size_t kAsumBytes = 8 * 16 * sizeof(int32_t) + 512;   // per-wave p
 //   - waves resident per CU (LDS for the staged rows of A and the 8-wave register limit bound it),
 //   - idle wave-slots in the last round over K when S does not divide the super-chunk count,
 //   - idle workgroup-slots in the last round over the tiles.
-struct SkinnyPlan { int waves, gx, mrows; size_t par_bytes, red_bytes, lds_bytes; };
+struct SkinnyPlan { int waves, gx, mrows, kgroups, cap, rounds; size_t a_stride, par_bytes, red_bytes, part_bytes, lds_bytes; };
 
-static bool make_plan(int S, int M, int Kp, int ntiles, int cus, SkinnyPlan* out, double* score)
+// G > 1 (K groups): only the columns of one run of super-chunks per wave are staged at a time, so up to 16
+// rows of A fit whatever K is and W is streamed once; the price is a drained ring at every group boundary
+// and S * rounds KiB of LDS for the partial sums.
+static bool make_plan(int S, int G, int M, int Kp, int ntiles, int cus, SkinnyPlan* out, double* score)
 {
     const int nsuper = Kp / kSuperK;
     if (S > nsuper) return false;
-    const size_t a_stride = (size_t)Kp + 16;
+    const int nsw_min = nsuper / S, nsw_max = (nsuper + S - 1) / S;
+    if (G > 1 && (S < 4 || nsw_min < G)) return false;   // every wave needs a super-chunk in every group
+    const int cap = (nsw_max + G - 1) / G;
+    const size_t a_stride = (G > 1 ? (size_t)S * cap * kSuperK : (size_t)Kp) + 16;
     const size_t red_bytes = 2 * (size_t)S * 1024;
-    int mrows = M < 16 ? M : 16;
-    // first guess of the per-workgroup tile count (for the parameter area), refined once gx is known
-    size_t par_bytes = (size_t)(16 + 16) * sizeof(RowParams) + kAsumBytes;
-    for (int pass = 0; pass < 2; ++pass) {
-        const size_t budget = kLdsPerCu - red_bytes - par_bytes - 64;
+    const int m16 = M < 16 ? M : 16;
+    int mrows = m16;
+    // the per-workgroup tile count (rounds) sizes the parameter and partial-sum areas, which bound how many
+    // workgroups fit a CU, which sets rounds: iterate to the fixed point (rounds only grows)
+    int rounds = 1;
+    for (int pass = 0; pass < 8; ++pass) {
+        const size_t par_bytes = (size_t)(16 + rounds * 16) * sizeof(RowParams) + kAsumBytes;
+        const size_t part_bytes = G > 1 ? (size_t)S * rounds * 1024 : 0;
+        if (red_bytes + par_bytes + part_bytes + 64 >= kLdsPerCu) return false;
+        const size_t budget = kLdsPerCu - red_bytes - par_bytes - part_bytes - 64;
         if ((size_t)mrows * a_stride > budget) mrows = (int)(budget / a_stride);
         if (mrows < 1) return false;
-        const size_t lds = align_up((size_t)mrows * a_stride, 16) + par_bytes + red_bytes;
+        const size_t lds = align_up((size_t)mrows * a_stride, 16) + par_bytes + red_bytes + part_bytes;
         int per_cu = (int)(kLdsPerCu / lds);
         if (per_cu > kWavesPerCu / S) per_cu = kWavesPerCu / S;
         if (per_cu < 1) per_cu = 1;
-        int gx = ntiles < cus * per_cu ? ntiles : cus * per_cu;
-        const int rounds = (ntiles + gx - 1) / gx;
-        par_bytes = (size_t)(16 + rounds * 16) * sizeof(RowParams) + kAsumBytes;
-        if (pass == 1) {
-            out->waves = S; out->gx = gx; out->mrows = mrows;
-            out->par_bytes = par_bytes; out->red_bytes = red_bytes;
-            out->lds_bytes = align_up((size_t)mrows * a_stride, 16) + par_bytes + red_bytes;
-            if (out->lds_bytes > kLdsPerCu) return false;
-            const double waves_cu = (double)per_cu * S < kWavesPerCu ? (double)per_cu * S : kWavesPerCu;
-            const double occupancy = (double)gx * S / cus < waves_cu ? (double)gx * S / cus : waves_cu;
-            const int krounds = (nsuper + S - 1) / S;
-            const double k_eff = (double)nsuper / (krounds * S);
-            const double t_eff = (double)ntiles / ((double)rounds * gx);
-            const double m_eff = (double)(M < 16 ? M : 16) / (((M < 16 ? M : 16) + mrows - 1) / mrows * mrows);
-            *score = (occupancy / kWavesPerCu) * k_eff * t_eff * m_eff;
-        }
+        const int gx = ntiles < cus * per_cu ? ntiles : cus * per_cu;
+        const int new_rounds = (ntiles + gx - 1) / gx;
+        if (new_rounds > rounds) { rounds = new_rounds; continue; }
+        out->waves = S; out->gx = gx; out->mrows = mrows; out->kgroups = G; out->cap = cap; out->rounds = rounds;
+        out->a_stride = a_stride; out->par_bytes = par_bytes; out->red_bytes = red_bytes; out->part_bytes = part_bytes;
+        out->lds_bytes = lds;
+        if (lds > kLdsPerCu) return false;
+        const double waves_cu = (double)per_cu * S < kWavesPerCu ? (double)per_cu * S : kWavesPerCu;
+        const double occupancy = (double)gx * S / cus < waves_cu ? (double)gx * S / cus : waves_cu;
+        const double k_eff = (double)nsuper / (nsw_max * S);
+        const double t_eff = (double)ntiles / ((double)rounds * gx);
+        const double m_eff = 1.0 / ((m16 + mrows - 1) / mrows);   // passes over W
+        const double g_eff = 1.0 / (1.0 + 0.1 * (G - 1));
+        *score = (occupancy / kWavesPerCu) * k_eff * t_eff * m_eff * g_eff;
+        return true;
     }
-    return true;
+    return false;
+}
+
+static int env_int(const char* name)
+{
+    const char* e = getenv(name);
+    return e ? atoi(e) : 0;
 }
 
 static bool pick_plan(int M, int Kp, int ntiles, int cus, size_t stream_bytes, SkinnyPlan* best)
 {
     static const int candidates[] = {8, 7, 6, 5, 4, 2, 1};
-    // tuning override: ABQ_SKINNY_WAVES=<S> forces the K split (read once)
-    static int forced = -1;
-    if (forced < 0) {
-        const char* e = getenv("ABQ_SKINNY_WAVES");
-        forced = e ? atoi(e) : 0;
-    }
-    double best_score = -1.0;
-    bool ok = false;
+    // tuning overrides (read once): ABQ_SKINNY_WAVES=<S> forces the K split, ABQ_SKINNY_KGROUPS=<G> the group count
+    static int forced = -1, forced_g = -1;
+    if (forced < 0) { forced = env_int("ABQ_SKINNY_WAVES"); forced_g = env_int("ABQ_SKINNY_KGROUPS"); }
+    const int m16 = M < 16 ? M : 16;
+    // K groups are used only where one group cannot hold all (up to 16) rows of A, and then as few as possible.
     // Long streams over many tiles (measured: >= 48 MB, >= 2 tiles per CU) run best as one resident
     // workgroup per CU that walks its tiles with 6..8 waves: the ring never drains between tiles and
     // A is staged once per workgroup.  Among 6..8 the split that wastes the fewest wave-slots over K.
-    if (forced <= 0 && stream_bytes >= ((size_t)48 << 20) && ntiles >= 2 * cus) {
+    if (forced <= 0 && forced_g <= 0 && stream_bytes >= ((size_t)48 << 20) && ntiles >= 2 * cus) {
         const int nsuper = Kp / kSuperK;
-        int pick = 0, waste = 1 << 30;
-        for (int S = 8; S >= 6; --S) {
-            const int w = (nsuper + S - 1) / S * S - nsuper;
-            if (S <= nsuper && w < waste) { waste = w; pick = S; }
+        int order[3] = {8, 7, 6};
+        for (int i = 0; i < 3; ++i)   // sort by wasted wave-slots, ties to the larger S
+            for (int j = i + 1; j < 3; ++j) {
+                const int wi = (nsuper + order[i] - 1) / order[i] * order[i] - nsuper;
+                const int wj = (nsuper + order[j] - 1) / order[j] * order[j] - nsuper;
+                if (wj < wi) { const int t = order[i]; order[i] = order[j]; order[j] = t; }
+            }
+        double sc;
+        for (int G = 1; G <= 4; ++G)
+            for (int S : order)
+                if (make_plan(S, G, M, Kp, ntiles, cus, best, &sc) && best->mrows == m16) return true;
+        for (int S : order)
+            if (make_plan(S, 1, M, Kp, ntiles, cus, best, &sc)) return true;
+    }
+    auto search = [&](int g_lo, int g_hi, bool all_rows, SkinnyPlan* out) {
+        double best_score = -1.0;
+        bool ok = false;
+        for (int G = g_lo; G <= g_hi; ++G) {
+            if (forced_g > 0 && G != forced_g) continue;
+            for (int S : candidates) {
+                if (forced > 0 && S != forced) continue;
+                SkinnyPlan pl;
+                double sc;
+                if (!make_plan(S, G, M, Kp, ntiles, cus, &pl, &sc)) continue;
+                if (all_rows && pl.mrows != m16) continue;
+                if (sc > best_score + 1e-9) { best_score = sc; *out = pl; ok = true; }
+            }
         }
-        double sc;
-        if (pick && make_plan(pick, M, Kp, ntiles, cus, best, &sc)) return true;
-    }
-    for (int S : candidates) {
-        if (forced > 0 && S != forced) continue;
-        SkinnyPlan pl;
-        double sc;
-        if (!make_plan(S, M, Kp, ntiles, cus, &pl, &sc)) continue;
-        if (sc > best_score + 1e-9) { best_score = sc; *best = pl; ok = true; }
-    }
-    if (!ok && forced > 0) { forced = 0; return pick_plan(M, Kp, ntiles, cus, stream_bytes, best); }
-    return ok;
+        return ok;
+    };
+    if (forced_g > 1 && search(forced_g, forced_g, false, best)) return true;
+    const bool one = search(1, 1, false, best);
+    if (one && best->mrows == m16) return true;
+    SkinnyPlan grouped;
+    if (forced_g <= 0 && search(2, 4, true, &grouped)) { *best = grouped; return true; }
+    if (one) return true;
+    if (forced > 0 || forced_g > 0) { forced = 0; forced_g = 0; return pick_plan(M, Kp, ntiles, cus, stream_bytes, best); }
+    return false;
 }
 
-template <int P, int D, int EPT, bool RAW, bool FULL>
-static hipError_t launch_pderf(const SkinnyParams& prm, dim3 grid, int waves, size_t lds_bytes, hipStream_t s)
+template <int P, int D, int EPT, bool RAW, bool FULL, bool KG>
+static hipError_t launch_variant(const SkinnyParams& prm, dim3 grid, int waves, size_t lds_bytes, hipStream_t s)
 {
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)skinny_kernel<P, D, EPT, RAW, FULL>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        hipError_t e = hipFuncSetAttribute((const void*)skinny_kernel<P, D, EPT, RAW, FULL, KG>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    skinny_kernel<P, D, EPT, RAW, FULL><<<grid, waves * 64, lds_bytes, s>>>(prm);
+    skinny_kernel<P, D, EPT, RAW, FULL, KG><<<grid, waves * 64, lds_bytes, s>>>(prm);
     return hipGetLastError();
 }
 
 template <int P, int D, int EPT>
 static hipError_t launch_pde(const SkinnyParams& prm, dim3 grid, int waves, size_t lds_bytes, hipStream_t s)
 {
+    if constexpr (EPT == 1) {   // K groups come with long K, hence with at least four waves
+        if (prm.kgroups > 1)
+            return prm.a_raw ? launch_variant<P, D, EPT, true, false, true>(prm, grid, waves, lds_bytes, s)
+                             : launch_variant<P, D, EPT, false, false, true>(prm, grid, waves, lds_bytes, s);
+    }
+    if (prm.kgroups > 1) return hipErrorInvalidValue;
     const bool full = prm.tl_q * prm.sc_q >= D;   // the fewest items any wave has
     if (prm.a_raw)
-        return full ? launch_pderf<P, D, EPT, true, true>(prm, grid, waves, lds_bytes, s)
-                    : launch_pderf<P, D, EPT, true, false>(prm, grid, waves, lds_bytes, s);
-    return full ? launch_pderf<P, D, EPT, false, true>(prm, grid, waves, lds_bytes, s)
-                : launch_pderf<P, D, EPT, false, false>(prm, grid, waves, lds_bytes, s);
+        return full ? launch_variant<P, D, EPT, true, true, false>(prm, grid, waves, lds_bytes, s)
+                    : launch_variant<P, D, EPT, true, false, false>(prm, grid, waves, lds_bytes, s);
+    return full ? launch_variant<P, D, EPT, false, true, false>(prm, grid, waves, lds_bytes, s)
+                : launch_variant<P, D, EPT, false, false, false>(prm, grid, waves, lds_bytes, s);
 }
 
 template <int P, int D>
@@ -611,13 +745,19 @@ hipError_t launch_gemm_skinny(const GemmArgs& g, const ActLayout& A, const Weigh
     const size_t stream_bytes = (size_t)g.p * W.NT * 16 * (size_t)A.Kp / 8;
     if (!pick_plan(g.M, A.Kp, W.NT, cus, stream_bytes, &pl)) return hipErrorInvalidValue;   // cannot happen for K <= ABQ_MAX_K
     const int waves = pl.waves, gx = pl.gx, mrows = pl.mrows;
-    // LDS: staged rows of A (all of K), the epilogue parameters, two reduction buffers of 1 KiB per wave
-    prm.a_stride = A.Kp + 16;
+    // LDS: staged rows of A (all of K, or one K group of it), the epilogue parameters, two reduction buffers
+    // of 1 KiB per wave, the partial sums of the K groups
+    prm.a_stride = (int)pl.a_stride;
     prm.mrows = mrows;
-    prm.par_off = (int)align_up((size_t)mrows * prm.a_stride, 16);
+    prm.par_off = (int)align_up((size_t)mrows * pl.a_stride, 16);
     prm.red_off = prm.par_off + (int)pl.par_bytes;
     prm.asum_off = prm.red_off - (int)kAsumBytes;
     prm.zero_off = prm.red_off - 512;
+    prm.part_off = prm.red_off + (int)pl.red_bytes;
+    prm.kgroups = pl.kgroups;
+    prm.col_w = pl.kgroups > 1 ? pl.cap * kSuperK : kSuperK;
+    prm.col_s = pl.kgroups > 1 ? kSuperK : waves * kSuperK;
+    prm.nmy_max = pl.rounds;
     const size_t lds_bytes = pl.lds_bytes;
     prm.nsuper = nsuper;
     prm.sc_q = nsuper / waves; prm.sc_r = nsuper % waves;

@@ -149,6 +149,27 @@ def test_longest_k(abq):
     check_against_oracle(c, y, acc)
 
 
+# Long K with up to 16 rows of A: the streaming kernel stages A one K group at a time and keeps per-tile
+# partial sums between the groups (several tiles per workgroup at the larger N).
+KGROUP_SHAPES = [(16, 70, 13824), (16, 4096, 11008), (12, 40, 20000), (9, 48, 16384), (16, 8200, 11008),
+                 (16, 5120, 13824), (8, 64, 28672), (16, 32, 28672), (13, 100, 33024), (16, 24, 131072)]
+
+
+@pytest.mark.parametrize("fused", [False, True], ids=["packed", "fused"])
+@pytest.mark.parametrize("M,N,K", KGROUP_SHAPES)
+def test_long_k_groups(abq, M, N, K, fused):
+    for p, q in [(4, 8), (8, 8), (1, 3), (7, 2), (3, 8)]:
+        if K * ((1 << p) - 1) * ((1 << q) - 1) > 2 ** 31 - 1:
+            p, q = min(p, 2), min(q, 4)
+        say("long K", M, N, K, p, q, "fused" if fused else "packed")
+        c = synth.make_case(p, q, M, N, K, seed=synth.case_seed(4, p, q) + M + N + K, name=f"longK W{p}A{q} {M}x{N}x{K}")
+        y, acc = gpu_gemm_fused(torch, abq, c, FIELDS) if fused else gpu_gemm(torch, abq, c, FIELDS, FIELDS)
+        if M * N * K <= 1 << 27:
+            check_against_oracle(c, y, acc)
+        else:
+            check_sampled(c, y, acc)
+
+
 def test_zero_and_constant_operands(abq):
     c = synth.make_case(4, 8, 3, 40, 1000, seed=6)
     c.A[:] = 0
