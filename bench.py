@@ -73,6 +73,103 @@ def cpu_baseline(c, budget_s):
             f"dequant + half rounding) in {el:.1f} s"}
 
 
+# The seven linear layers of one LLaMA-7B decoder block as (name, N, K): the shapes the paper's engine
+# replaces in a block (Sec. 3.4; Appendix D measures these layer shapes one by one).
+BLOCK_7B = [("q_proj", 4096, 4096), ("k_proj", 4096, 4096), ("v_proj", 4096, 4096), ("o_proj", 4096, 4096),
+            ("gate_proj", 11008, 4096), ("up_proj", 11008, 4096), ("down_proj", 4096, 11008)]
+
+
+def bench_grouped(p, q, M, steps, warmup, rotate_gib, check=True):
+    """One abq_gemm_grouped launch over the seven layer shapes of a decoder block (independent synthetic
+    problems: own weights, activation codes and outputs), against the same seven as single fused calls.
+    Weight sets rotate over >= rotate_gib GiB.  Returns a dict for the JSON line."""
+    import numpy as np
+    import torch
+    from paper_2408_08554_amd import binding as abq, metrics, synth
+    layout = abq.ABQ_LAYOUT_FIELDS
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    cases = [synth.make_case(p, q, M, N, K, seed=synth.case_seed(6, p, q, i, 0), name=f"{name} W{p}A{q} M={M} {K}->{N}")
+             for i, (name, N, K) in enumerate(BLOCK_7B)]
+    blobs0 = [abq.abq_pack_weights(p, dev(c.W), dev(c.w_scale), dev(c.w_zero), layout) for c in cases]
+    set_bytes = sum((b.numel() + 255) // 256 * 256 for b in blobs0)
+    R = max(2, int(np.ceil(rotate_gib * 2 ** 30 / set_bytes)))
+    pool = torch.empty(R * set_bytes, dtype=torch.uint8, device="cuda")
+    sets, off = [], 0
+    for r in range(R):
+        cur = []
+        for b in blobs0:
+            v = pool[off:off + b.numel()]
+            v.copy_(b)
+            cur.append(v)
+            off += (b.numel() + 255) // 256 * 256
+        sets.append(cur)
+    acts = [(dev(c.A), dev(c.a_scale), dev(c.a_zero)) for c in cases]
+    ys = [torch.empty((M, c.N), dtype=torch.float16, device="cuda") for c in cases]
+    accs = [torch.empty((M, c.N), dtype=torch.int32, device="cuda") for c in cases]
+
+    def problems(r, with_acc):
+        return [dict(N=c.N, K=c.K, packed_w=sets[r][i], a_codes=acts[i][0], a_scale=acts[i][1], a_zero=acts[i][2],
+                     y=ys[i], acc=accs[i] if with_acc else None) for i, c in enumerate(cases)]
+
+    descs = [abq.make_problems(problems(r, False)) for r in range(R)]
+    assert abq.abq_gemm_grouped_workspace_bytes(p, q, M, descs[0], layout, layout) == 0, "this group must run as one launch"
+
+    if check:
+        import oracle
+        rng = np.random.Generator(np.random.PCG64(11))
+        for r in (0, R - 1):
+            abq.abq_gemm_grouped(p, q, M, problems(r, True), layout, layout)
+            torch.cuda.synchronize()
+            for i, c in enumerate(cases):
+                ms = rng.integers(0, M, 1024).astype(np.int32)
+                ns = rng.integers(0, c.N, 1024).astype(np.int32)
+                got = accs[i].cpu().numpy()[ms, ns].astype(np.int64)
+                assert np.array_equal(got, oracle.acc_sampled(c.A, c.W, ms, ns)), f"int32 parity failure in {c.name}, set {r}"
+                accc = oracle.acc_centered_sampled(c.A, c.W, c.a_zero, c.w_zero, ms, ns)
+                yref = accc.astype(np.float64) * c.a_scale[ms].astype(np.float64) * c.w_scale[ns].astype(np.float64)
+                tol = np.maximum(np.maximum(1e-2 * np.abs(yref), 2.0 ** (np.floor(np.log2(np.maximum(np.abs(yref), 2.0 ** -14))) - 9)), 2.0 ** -24)
+                assert np.all(np.abs(ys[i].cpu().numpy()[ms, ns].astype(np.float64) - yref) <= tol), f"fp16 parity failure in {c.name}"
+
+    def grouped_step(i):
+        abq.abq_gemm_grouped(p, q, M, descs[i % R], layout, layout)
+
+    def single_step(i):
+        for j, c in enumerate(cases):
+            abq.abq_gemm_act_codes(p, q, M, c.N, c.K, acts[j][0], acts[j][1], acts[j][2], sets[i % R][j], layout, y=ys[j])
+
+    stream = torch.cuda.Stream()
+    times = {}
+    with torch.cuda.stream(stream):
+        for name, fn in (("grouped", grouped_step), ("single", single_step)):
+            for i in range(warmup):
+                fn(i)
+            stream.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=stream):
+                for i in range(steps):
+                    fn(i)
+            g.replay()
+            stream.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            g.replay()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            times[name] = e0.elapsed_time(e1) * 1e-3 / steps
+            del g
+    ops = sum(2.0 * M * c.N * c.K for c in cases)
+    alg = sum(metrics.gemm_algorithmic_bytes(p, q, M, c.N, c.K) for c in cases)
+    wbytes = sum(metrics.packed_weight_stream_bytes(p, c.N, c.K) for c in cases)
+    t = times["grouped"]
+    return {"workload": f"LLaMA-7B decoder block, 7 linear layers, W{p}A{q} M={M}, one abq_gemm_grouped launch",
+            "us_per_block": t * 1e6, "tops": ops / t / 1e12, "weight_gbs": wbytes / t / 1e9,
+            "roofline": {"bound": "hbm", "achieved": alg / t / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": alg / t / 1e9 / HBM_PEAK_GBS, "traffic": None, "algorithmic_bytes": alg,
+                         "kernel": "abq_gemm_grouped", "launches": steps},
+            "seven_single_launches_us": times["single"] * 1e6, "rotating_weight_sets": R, "rotating_bytes": R * set_bytes,
+            "steps": steps}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -87,6 +184,8 @@ def main():
     ap.add_argument("--rotate-gib", type=float, default=1.0, help="total size of the rotating weight buffers")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="time budget of the cpu_baseline leg (0 = skip)")
     ap.add_argument("--no-check", action="store_true")
+    ap.add_argument("--grouped-steps", type=int, default=200,
+                    help="launches of the grouped decoder-block leg reported beside the main workload (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
@@ -98,6 +197,11 @@ def main():
     torch.cuda.set_device(0)
     abq.load()
 
+    if args.workload.startswith("block:"):
+        # block:p,q,M — the grouped decoder-block launch as the timed workload, printed as its own JSON line
+        bp, bq, bm = (int(v) for v in args.workload.split(":")[1].split(","))
+        print(json.dumps(bench_grouped(bp, bq, bm, args.steps, args.warmup, args.rotate_gib, not args.no_check)), flush=True)
+        return
     c = build_case(args.workload)
     p, q, M, N, K = c.p, c.q, c.M, c.N, c.K
     layout = {"auto": abq.ABQ_LAYOUT_FIELDS, "mfma": abq.ABQ_LAYOUT_FIELDS, "bitserial": abq.ABQ_LAYOUT_PLANES}[args.family]
@@ -232,6 +336,10 @@ def main():
                           "step": "abq_pack_act_codes + abq_gemm"},
         "roofline": roof,
     }
+    if args.grouped_steps > 0 and M <= 16:
+        del pool, blobs
+        torch.cuda.empty_cache()
+        out["grouped_decoder_block"] = bench_grouped(p, q, M, args.grouped_steps, 20, args.rotate_gib, not args.no_check)
     if args.cpu_seconds > 0:
         out["cpu_baseline"] = cpu_baseline(c, args.cpu_seconds)
     print(json.dumps(out), flush=True)

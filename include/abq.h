@@ -160,6 +160,36 @@ int abq_gemm_act_codes(int p, int q, int M, int N, int K,
                        uint16_t* y_fp16, int32_t* acc_i32,
                        void* workspace, size_t workspace_bytes, void* stream);
 
+/* Grouped decode launch (Sec. 3.4: the engine replaces every linear layer of a decoder block; Table 4's
+ * matmuls take microseconds each, so launching them one by one leaves the memory system idle between
+ * them).  `count` independent problems that share p, q, M and the layouts, each with its own N, K,
+ * weights, activations and outputs, are served by ONE kernel launch per eight problems when every
+ * problem is decode-shaped: M <= 16, K >= 2048 (K a multiple of 16 for unpacked codes), up to 16 rows of
+ * A fitting LDS ((M * (K + 528) below ~120 KB), field-packed weights.  Otherwise the problems run one
+ * after the other exactly as abq_gemm / abq_gemm_act_codes would run them.  Results are bit-identical
+ * to the single calls either way.
+ *   host_problems: HOST array of `count` descriptors holding DEVICE pointers.  Each gives its activations
+ *                  either packed (packed_act, a_codes = NULL) or as unpacked codes (a_codes, a_scale, a_zero,
+ *                  packed_act = NULL); all problems of a call use the same form.  The array is read before the
+ *                  call returns.
+ *   workspace:     at least abq_gemm_grouped_workspace_bytes(...) bytes (0 whenever one launch serves the group
+ *                  or the activations are packed).
+ * Errors as abq_gemm; ABQ_ERR_SHAPE also for count < 1, ABQ_ERR_LAYOUT for mixed activation forms. */
+typedef struct abq_problem {
+    int N, K;
+    const void* packed_w;       /* abq_pack_weights(p, N, K, ..., w_layout) */
+    const void* packed_act;     /* abq_pack_act_codes / abq_quant_pack_act (q, M, K, ..., a_layout), or NULL */
+    const uint8_t* a_codes;     /* [M,K] uint8 codes < 2^q, or NULL */
+    const float* a_scale;       /* [M], with a_codes */
+    const int32_t* a_zero;      /* [M], with a_codes */
+    uint16_t* y_fp16;           /* [M,N], required */
+    int32_t* acc_i32;           /* [M,N] raw accumulator, may be NULL */
+} abq_problem;
+size_t abq_gemm_grouped_workspace_bytes(int p, int q, int M, int count, const abq_problem* host_problems,
+                                        int a_layout, int w_layout);
+int abq_gemm_grouped(int p, int q, int M, int count, const abq_problem* host_problems,
+                     int a_layout, int w_layout, void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

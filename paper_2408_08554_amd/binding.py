@@ -36,6 +36,8 @@ _SIGNATURES = {
     "abq_gemm": (_c.c_int, [_c.c_int] * 5 + [_c.c_void_p, _c.c_int, _c.c_void_p, _c.c_int, _c.c_void_p, _c.c_void_p,
                                              _c.c_void_p, _c.c_size_t, _c.c_void_p]),
     "abq_gemm_act_codes_workspace_bytes": (_c.c_size_t, [_c.c_int] * 6),
+    "abq_gemm_grouped_workspace_bytes": (_c.c_size_t, [_c.c_int] * 4 + [_c.c_void_p, _c.c_int, _c.c_int]),
+    "abq_gemm_grouped": (_c.c_int, [_c.c_int] * 4 + [_c.c_void_p, _c.c_int, _c.c_int, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
     "abq_gemm_act_codes": (_c.c_int, [_c.c_int] * 5 + [_c.c_void_p] * 4 + [_c.c_int, _c.c_void_p, _c.c_void_p,
                                                                           _c.c_void_p, _c.c_size_t, _c.c_void_p]),
 }
@@ -201,3 +203,43 @@ def abq_gemm_act_codes(p, q, M, N, K, a_codes, a_scale, a_zero, packed_w, w_layo
                                   _ptr(y), _ptr(acc), _ptr(workspace), 0 if workspace is None else workspace.numel(),
                                   _stream()), "abq_gemm_act_codes")
     return y, acc
+
+
+class AbqProblem(_c.Structure):
+    """struct abq_problem of include/abq.h (host descriptor holding device pointers)."""
+    _fields_ = [("N", _c.c_int), ("K", _c.c_int), ("packed_w", _c.c_void_p), ("packed_act", _c.c_void_p),
+                ("a_codes", _c.c_void_p), ("a_scale", _c.c_void_p), ("a_zero", _c.c_void_p), ("y_fp16", _c.c_void_p),
+                ("acc_i32", _c.c_void_p)]
+
+
+def make_problems(problems):
+    """problems: list of dicts with N, K, packed_w, y and either packed_act or a_codes/a_scale/a_zero (torch tensors),
+    optionally acc.  Returns the ctypes array (keep the tensors alive while it is in use)."""
+    arr = (AbqProblem * len(problems))()
+    for d, pr in zip(arr, problems):
+        d.N, d.K = pr["N"], pr["K"]
+        d.packed_w = _ptr(pr["packed_w"])
+        d.packed_act = _ptr(pr.get("packed_act"))
+        d.a_codes = _ptr(pr.get("a_codes"))
+        d.a_scale = _ptr(pr.get("a_scale"))
+        d.a_zero = _ptr(pr.get("a_zero"))
+        d.y_fp16 = _ptr(pr["y"])
+        d.acc_i32 = _ptr(pr.get("acc"))
+    return arr
+
+
+def abq_gemm_grouped_workspace_bytes(p, q, M, problems, a_layout, w_layout):
+    arr = problems if isinstance(problems, _c.Array) else make_problems(problems)
+    return load().abq_gemm_grouped_workspace_bytes(p, q, M, len(arr), _c.addressof(arr), a_layout, w_layout)
+
+
+def abq_gemm_grouped(p, q, M, problems, a_layout, w_layout, workspace=None):
+    """One call for a list of independent problems that share p, q, M (see make_problems); outputs are written to
+    the y / acc tensors of each problem."""
+    lib = load()
+    arr = problems if isinstance(problems, _c.Array) else make_problems(problems)
+    need = lib.abq_gemm_grouped_workspace_bytes(p, q, M, len(arr), _c.addressof(arr), a_layout, w_layout)
+    if need and workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device="cuda")
+    _check(lib.abq_gemm_grouped(p, q, M, len(arr), _c.addressof(arr), a_layout, w_layout, _ptr(workspace),
+                                0 if workspace is None else workspace.numel(), _stream()), "abq_gemm_grouped")

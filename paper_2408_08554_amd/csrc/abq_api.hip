@@ -5,6 +5,7 @@
 #include "../../include/abq.h"
 
 #include <limits.h>
+#include <vector>
 
 namespace abq {
 
@@ -308,6 +309,95 @@ int abq_gemm_act_codes(int p, int q, int M, int N, int K, const uint8_t* a_codes
     if (int e = abq_pack_act_codes(q, M, K, a_codes, a_scale, a_zero, base_layout, workspace, act_bytes, stream)) return e;
     return abq_gemm(p, q, M, N, K, workspace, base_layout, packed_w, w_layout, y_fp16, acc_i32,
                     (uint8_t*)workspace + act_bytes, workspace_bytes - act_bytes, stream);
+}
+
+// Validation and layouts of a group; fills the per-problem arrays (sized by the caller) and says whether one
+// launch can serve it.
+static int prepare_group(int p, int q, int M, int count, const abq_problem* pr, int a_layout, int w_layout,
+                         GemmArgs* args, ActLayout* A, WeightLayout* W, bool* raw, bool* fits, int* waves, size_t* lds)
+{
+    if (!pr) return ABQ_ERR_NULL;
+    if (count < 1 || count > 4096) return ABQ_ERR_SHAPE;
+    const int force = w_layout & (ABQ_USE_PLANES | ABQ_USE_FIELDS);
+    const int base_w = w_layout & ~(ABQ_USE_PLANES | ABQ_USE_FIELDS);
+    if (force == (ABQ_USE_PLANES | ABQ_USE_FIELDS)) return ABQ_ERR_LAYOUT;
+    *raw = pr[0].a_codes != nullptr;
+    for (int i = 0; i < count; ++i) {
+        const abq_problem& c = pr[i];
+        if (!c.packed_w || !c.y_fp16) return ABQ_ERR_NULL;
+        if ((c.a_codes != nullptr) != *raw) return ABQ_ERR_LAYOUT;
+        if (*raw ? (!c.a_scale || !c.a_zero || c.packed_act) : !c.packed_act) return *raw && c.packed_act ? ABQ_ERR_LAYOUT : ABQ_ERR_NULL;
+        if (int e = check_gemm_shape(p, q, M, c.N, c.K)) return e;
+        if (!make_weight_layout(p, c.N, c.K, base_w, &W[i])) return ABQ_ERR_LAYOUT;
+        if (!make_act_layout(q, M, c.K, *raw ? ABQ_LAYOUT_FIELDS : a_layout, &A[i])) return ABQ_ERR_LAYOUT;
+        if (misaligned(c.packed_w) || misaligned(c.packed_act) || misaligned(c.a_codes) || misaligned(c.a_scale) ||
+            misaligned(c.a_zero) || misaligned(c.y_fp16) || misaligned(c.acc_i32))
+            return ABQ_ERR_ALIGN;
+        args[i] = GemmArgs{p, q, M, c.N, c.K, (const uint8_t*)c.packed_act, c.a_codes, c.a_scale, c.a_zero,
+                           (const uint8_t*)c.packed_w, c.y_fp16, c.acc_i32, nullptr, 0};
+    }
+    // one launch only where every problem would go to the streaming kernel of the int8-MFMA family anyway
+    *fits = force != ABQ_USE_PLANES && M <= kSkinnyMaxM;
+    for (int i = 0; i < count && *fits; ++i)
+        *fits = choose_fields(W[i].has_fields && (*raw || A[i].has_fields), W[i].has_planes && !*raw && A[i].has_planes, force, p, q, M, pr[i].N);
+    if (*fits) *fits = gemm_grouped_fits(M, count, args, A, W, waves, lds);
+    return ABQ_OK;
+}
+
+size_t abq_gemm_grouped_workspace_bytes(int p, int q, int M, int count, const abq_problem* host_problems, int a_layout,
+                                        int w_layout)
+{
+    if (!host_problems || count < 1 || count > 4096) return 0;
+    std::vector<GemmArgs> args(count);
+    std::vector<ActLayout> A(count);
+    std::vector<WeightLayout> W(count);
+    bool raw = false, fits = false;
+    int waves = 0;
+    size_t lds = 0;
+    if (prepare_group(p, q, M, count, host_problems, a_layout, w_layout, args.data(), A.data(), W.data(), &raw, &fits, &waves, &lds) != ABQ_OK)
+        return 0;
+    if (fits || !raw) return 0;
+    size_t need = 0;
+    for (int i = 0; i < count; ++i) {
+        const size_t n = abq_gemm_act_codes_workspace_bytes(p, q, M, host_problems[i].N, host_problems[i].K, w_layout);
+        if (n > need) need = n;
+    }
+    return need;
+}
+
+int abq_gemm_grouped(int p, int q, int M, int count, const abq_problem* host_problems, int a_layout, int w_layout,
+                     void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!host_problems) return ABQ_ERR_NULL;
+    if (count < 1 || count > 4096) return ABQ_ERR_SHAPE;
+    std::vector<GemmArgs> args(count);
+    std::vector<ActLayout> A(count);
+    std::vector<WeightLayout> W(count);
+    bool raw = false, fits = false;
+    int waves = 0;
+    size_t lds = 0;
+    if (int e = prepare_group(p, q, M, count, host_problems, a_layout, w_layout, args.data(), A.data(), W.data(), &raw, &fits, &waves, &lds))
+        return e;
+    if (misaligned(workspace)) return ABQ_ERR_ALIGN;
+    if (fits) return hip_status(launch_gemm_grouped(p, M, count, args.data(), A.data(), W.data(), waves, lds, (hipStream_t)stream));
+    if (raw) {   // every problem's workspace need is checked before the first launch
+        size_t need = 0;
+        for (int i = 0; i < count; ++i) {
+            const size_t n = abq_gemm_act_codes_workspace_bytes(p, q, M, host_problems[i].N, host_problems[i].K, w_layout);
+            if (n > need) need = n;
+        }
+        if (need > 0 && !workspace) return ABQ_ERR_NULL;
+        if (workspace_bytes < need) return ABQ_ERR_SIZE;
+    }
+    for (int i = 0; i < count; ++i) {
+        const abq_problem& c = host_problems[i];
+        const int e = raw ? abq_gemm_act_codes(p, q, M, c.N, c.K, c.a_codes, c.a_scale, c.a_zero, c.packed_w, w_layout, c.y_fp16,
+                                               c.acc_i32, workspace, workspace_bytes, stream)
+                          : abq_gemm(p, q, M, c.N, c.K, c.packed_act, a_layout, c.packed_w, w_layout, c.y_fp16, c.acc_i32,
+                                     workspace, workspace_bytes, stream);
+        if (e != ABQ_OK) return e;
+    }
+    return ABQ_OK;
 }
 
 }  // extern "C"

@@ -149,7 +149,7 @@ __device__ __forceinline__ void load_tiles(const TiledParams& prm, int tile0, in
 // Up to two 16-row tiles of W per wave the kernel is held to 256 registers, so that two workgroups
 // share a CU and each hides the other's waits; the four-tile shape takes the whole register file.
 template <int P, int NTW, int MT>
-__global__ __launch_bounds__(256, (NTW <= 2 ? (MT == 4 ? 3 : 2) : 1)) void tiled_kernel(TiledParams prm)
+__global__ __launch_bounds__(256, (NTW <= 2 ? (MT == 4 ? 3 : 2) : (MT == 4 ? 2 : 1))) void tiled_kernel(TiledParams prm)
 {
     constexpr int kBM = MT * 16, kBN = 4 * NTW * kTileN;
     __shared__ __align__(16) uint8_t lds_a0[kBM * kARow];   // two separate objects: the loads that fill one must

@@ -336,20 +336,22 @@ __device__ __forceinline__ void item_step(const SkinnyParams& prm, WaveState<P>&
 // its row sums for the zero-point correction are taken on the way.
 // FULL: every wave of the launch has at least D items, so the ring prologue needs no conditions.
 // KG: K groups (see SkinnyParams); never together with FULL.
+// The body takes the workgroup's place in the launch as arguments (bx of gx workgroups along the tiles,
+// row group by) so that the grouped launch below can run it on one problem of several.
 template <int P, int D, int EPT, bool RAW, bool FULL, bool KG>
-__global__ __launch_bounds__(512) void skinny_kernel(SkinnyParams prm)
+__device__ __forceinline__ void skinny_body(const SkinnyParams& prm, const int bx, const int gx, const int by)
 {
     static_assert(!(FULL && KG), "the K-group variant uses the conditional ring prologue");
     using GI = GroupInfo<P>;
     extern __shared__ __align__(16) uint8_t lds[];
     WaveState<P> st;
     st.tid = threadIdx.x; st.lane = st.tid & 63; st.wave = st.tid >> 6; st.S = blockDim.x >> 6;
-    st.m0 = blockIdx.y * prm.mrows;
+    st.m0 = by * prm.mrows;
     const int mt = min(prm.mrows, prm.M - st.m0);
     st.mt = mt;
     const int r = st.lane & 15, G = st.lane >> 4;
     st.nsuper = prm.nsuper;
-    st.tile0 = blockIdx.x; st.tstride = gridDim.x;
+    st.tile0 = bx; st.tstride = gx;
     st.p_ti = 0; st.p_lsc = 0; st.ti = 0; st.lsc = 0; st.parity = 0;
 #ifdef ABQ_PHASE_TRACE
     unsigned long long ts[8] = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -358,7 +360,7 @@ __global__ __launch_bounds__(512) void skinny_kernel(SkinnyParams prm)
     ABQ_TS(0);
 
     st.nsw = prm.sc_q + (st.wave < prm.sc_r ? 1 : 0);                       // this wave's super-chunks per tile (>= 1)
-    const int nmy = prm.tl_q + ((int)blockIdx.x < prm.tl_r ? 1 : 0);         // this workgroup's tiles (>= 1)
+    const int nmy = prm.tl_q + (bx < prm.tl_r ? 1 : 0);         // this workgroup's tiles (>= 1)
     st.nitems = nmy * st.nsw;
     st.nmy = nmy;
     st.g = 0; st.gs = 0; st.ge = KG ? group_bound(1, st.nsw, prm.kgroups) : st.nsw;
@@ -539,9 +541,38 @@ __global__ __launch_bounds__(512) void skinny_kernel(SkinnyParams prm)
     }
 #ifdef ABQ_PHASE_TRACE
     ABQ_TS(6);
-    if (st.lane == 0 && blockIdx.x < 1024 && st.wave < 8)
-        for (int i = 0; i < 8; ++i) g_phase_trace[((size_t)blockIdx.x * 8 + st.wave) * 8 + i] = ts[i];
+    if (st.lane == 0 && bx < 1024 && st.wave < 8)
+        for (int i = 0; i < 8; ++i) g_phase_trace[((size_t)bx * 8 + st.wave) * 8 + i] = ts[i];
 #endif
+}
+
+template <int P, int D, int EPT, bool RAW, bool FULL, bool KG>
+__global__ __launch_bounds__(512) void skinny_kernel(SkinnyParams prm)
+{
+    skinny_body<P, D, EPT, RAW, FULL, KG>(prm, (int)blockIdx.x, (int)gridDim.x, (int)blockIdx.y);
+}
+
+// Grouped decode launch: up to kMaxGroup independent problems (same p, q and M <= 16; own A, W, Y, N, K)
+// in ONE launch.  Problem g gets workgroups first_wg[g] .. first_wg[g+1]-1, which walk its 16-row tiles
+// exactly as a launch of its own would (tile = bx + i * gx); the descriptor is read from the kernel arguments.  Microsecond-sized matmuls then share one
+// launch ramp and tail instead of paying one each (Sec. 3.4: the engine replaces all the linear
+// layers of a decoder block).
+constexpr int kMaxGroup = 8;
+struct GroupedParams {
+    int count;
+    int first_wg[kMaxGroup + 1];
+    SkinnyParams d[kMaxGroup];
+};
+
+template <int P, int D, int EPT, bool RAW>
+__global__ __launch_bounds__(512) void grouped_kernel(GroupedParams gp)
+{
+    const int b = (int)blockIdx.x;
+    int g = 0;
+#pragma unroll
+    for (int i = 1; i < kMaxGroup; ++i)
+        if (i < gp.count && b >= gp.first_wg[i]) g = i;
+    skinny_body<P, D, EPT, RAW, false, false>(gp.d[g], b - gp.first_wg[g], gp.first_wg[g + 1] - gp.first_wg[g], 0);
 }
 
 // ---- host side -------------------------------------------------------------------------------------
@@ -717,9 +748,9 @@ static hipError_t launch_pd(const SkinnyParams& prm, dim3 grid, int waves, size_
     return launch_pde<P, D, 4>(prm, grid, waves, lds_bytes, s);
 }
 
-hipError_t launch_gemm_skinny(const GemmArgs& g, const ActLayout& A, const WeightLayout& W, hipStream_t s)
+// Operand pointers and shape fields of the kernel arguments (everything but the launch plan).
+static void fill_operands(SkinnyParams& prm, const GemmArgs& g, const ActLayout& A, const WeightLayout& W)
 {
-    SkinnyParams prm;
     for (int i = 0; i < 3; ++i) {
         prm.fields[i] = (const u4v*)(g.w_blob + W.off_fields[i]);
         prm.chunks[i] = W.chunks[i];
@@ -739,6 +770,12 @@ hipError_t launch_gemm_skinny(const GemmArgs& g, const ActLayout& A, const Weigh
     prm.oa = (g.q == 8) ? 128 : 0;
     prm.ow = (g.p == 8) ? 128 : 0;
     prm.ntiles = W.NT;
+}
+
+hipError_t launch_gemm_skinny(const GemmArgs& g, const ActLayout& A, const WeightLayout& W, hipStream_t s)
+{
+    SkinnyParams prm;
+    fill_operands(prm, g, A, W);
     const int cus = num_cus();
     const int nsuper = A.Kp / kSuperK;
     SkinnyPlan pl;
@@ -773,6 +810,129 @@ hipError_t launch_gemm_skinny(const GemmArgs& g, const ActLayout& A, const Weigh
         case 7: return launch_pd<7, 2>(prm, grid, waves, lds_bytes, s);
         default: return launch_pd<8, 2>(prm, grid, waves, lds_bytes, s);
     }
+}
+
+// ---- grouped launch ----------------------------------------------------------------------------
+
+// One launch serves a group when every problem can run as "one workgroup of S waves per tile, all of
+// A staged at once": M <= 16, every K spans at least four super-chunks (S = 4..8 waves, the same for
+// all), the rows of A fit LDS, field-packed weights, and for unpacked codes K a multiple of 16.
+// Shape of a grouped launch, measured on the seven layer shapes of a LLaMA-7B block (W2/W4/W8, M = 1, 4, 8):
+// few rows of A -> many small workgroups (four waves, one or two tiles each: two or more share a CU and
+// hide each other's prologue and tail); more rows -> eight waves walking four tiles, so that the rows
+// of A are staged less often.  Tuning overrides, read once: ABQ_GROUP_TILES=<T>, ABQ_GROUP_WAVES=<S>.
+static int group_tiles_per_wg(int M)
+{
+    static int forced = -1;
+    if (forced < 0) forced = env_int("ABQ_GROUP_TILES");
+    if (forced > 0) return forced;
+    return M <= 2 ? 1 : (M <= 4 ? 2 : 4);
+}
+
+bool gemm_grouped_fits(int M, int count, const GemmArgs* probs, const ActLayout* A, const WeightLayout* W, int* waves, size_t* lds_bytes)
+{
+    if (M > 16 || count < 1) return false;
+    int S = M <= 4 ? 4 : 8;
+    for (int i = 0; i < count; ++i) {
+        if (!W[i].has_fields) return false;
+        if (probs[i].a_raw ? (probs[i].K % 16 != 0) : !A[i].has_fields) return false;
+        if ((probs[i].a_raw != nullptr) != (probs[0].a_raw != nullptr)) return false;
+        const int nsuper = A[i].Kp / kSuperK;
+        if (nsuper < 4) return false;
+        if (nsuper < S) S = nsuper;
+    }
+    {
+        static int forced = -1;
+        if (forced < 0) forced = env_int("ABQ_GROUP_WAVES");
+        if (forced >= 2 && forced <= 8 && forced != 3) {
+            S = forced;
+            for (int i = 0; i < count; ++i)
+                if (A[i].Kp / kSuperK < S) S = A[i].Kp / kSuperK;
+        }
+    }
+    size_t lds = 0;
+    for (int i = 0; i < count; ++i) {
+        const size_t need = align_up((size_t)M * ((size_t)A[i].Kp + 16), 16) + (16 + 16 * group_tiles_per_wg(M)) * sizeof(RowParams) +
+                            kAsumBytes + 2 * (size_t)S * 1024;
+        if (need > kLdsPerCu) return false;
+        if (need > lds) lds = need;
+    }
+    *waves = S;
+    *lds_bytes = lds;
+    return true;
+}
+
+template <int P, int D>
+static hipError_t launch_grouped_pd(const GroupedParams& gp, bool raw, unsigned grid, int waves, size_t lds_bytes, hipStream_t s)
+{
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)grouped_kernel<P, D, 1, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)grouped_kernel<P, D, 1, false>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)grouped_kernel<P, D, 2, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)grouped_kernel<P, D, 2, false>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    if (waves >= 4) {
+        if (raw) grouped_kernel<P, D, 1, true><<<grid, waves * 64, lds_bytes, s>>>(gp);
+        else grouped_kernel<P, D, 1, false><<<grid, waves * 64, lds_bytes, s>>>(gp);
+    } else {
+        if (raw) grouped_kernel<P, D, 2, true><<<grid, waves * 64, lds_bytes, s>>>(gp);
+        else grouped_kernel<P, D, 2, false><<<grid, waves * 64, lds_bytes, s>>>(gp);
+    }
+    return hipGetLastError();
+}
+
+// Callers check gemm_grouped_fits first; count may exceed kMaxGroup (then several launches follow each other).
+hipError_t launch_gemm_grouped(int p, int M, int count, const GemmArgs* probs, const ActLayout* A, const WeightLayout* W,
+                               int waves, size_t lds_bytes, hipStream_t s)
+{
+    for (int first = 0; first < count; first += kMaxGroup) {
+        const int n = count - first < kMaxGroup ? count - first : kMaxGroup;
+        GroupedParams gp;
+        gp.count = n;
+        int wgs = 0;
+        const int T = group_tiles_per_wg(M);
+        for (int i = 0; i < kMaxGroup; ++i) {
+            const int src = first + (i < n ? i : 0);   // unused slots repeat a valid descriptor
+            SkinnyParams& prm = gp.d[i];
+            fill_operands(prm, probs[src], A[src], W[src]);
+            const int nsuper = A[src].Kp / kSuperK;
+            prm.a_stride = A[src].Kp + 16;
+            prm.mrows = M;
+            prm.par_off = (int)align_up((size_t)M * prm.a_stride, 16);
+            prm.red_off = prm.par_off + (int)((16 + 16 * T) * sizeof(RowParams) + kAsumBytes);
+            prm.asum_off = prm.red_off - (int)kAsumBytes;
+            prm.zero_off = prm.red_off - 512;
+            prm.part_off = prm.red_off + 2 * waves * 1024;
+            prm.kgroups = 1;
+            prm.col_w = kSuperK;
+            prm.col_s = waves * kSuperK;
+            const int gx = (W[src].NT + T - 1) / T;          // every workgroup walks at most T tiles
+            prm.nmy_max = T;
+            prm.nsuper = nsuper;
+            prm.sc_q = nsuper / waves; prm.sc_r = nsuper % waves;
+            prm.tl_q = W[src].NT / gx; prm.tl_r = W[src].NT % gx;
+            gp.first_wg[i] = wgs;
+            if (i < n) wgs += gx;
+        }
+        gp.first_wg[kMaxGroup] = wgs;
+        hipError_t e;
+        const bool raw = probs[first].a_raw != nullptr;
+        switch (p) {
+            case 1: e = launch_grouped_pd<1, 8>(gp, raw, (unsigned)wgs, waves, lds_bytes, s); break;
+            case 2: e = launch_grouped_pd<2, 8>(gp, raw, (unsigned)wgs, waves, lds_bytes, s); break;
+            case 3: e = launch_grouped_pd<3, 4>(gp, raw, (unsigned)wgs, waves, lds_bytes, s); break;
+            case 4: e = launch_grouped_pd<4, 4>(gp, raw, (unsigned)wgs, waves, lds_bytes, s); break;
+            case 5: e = launch_grouped_pd<5, 2>(gp, raw, (unsigned)wgs, waves, lds_bytes, s); break;
+            case 6: e = launch_grouped_pd<6, 2>(gp, raw, (unsigned)wgs, waves, lds_bytes, s); break;
+            case 7: e = launch_grouped_pd<7, 2>(gp, raw, (unsigned)wgs, waves, lds_bytes, s); break;
+            default: e = launch_grouped_pd<8, 2>(gp, raw, (unsigned)wgs, waves, lds_bytes, s); break;
+        }
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 }  // namespace abq

@@ -139,6 +139,52 @@ def test_gemm_act_codes_rejects_and_workspace_query():
     assert gemm_fused(lib, K=40, ws=A16, wsb=64) == B.ABQ_ERR_SIZE
 
 
+def _problems(*items):
+    arr = (B.AbqProblem * len(items))()
+    for d, it in zip(arr, items):
+        for k, v in it.items():
+            setattr(d, k, v)
+    return arr
+
+
+def test_gemm_grouped_rejects_and_workspace_query():
+    import ctypes
+    lib = B.load()
+    packed = dict(N=64, K=4096, packed_w=A16, packed_act=A16, y_fp16=A16)
+    codes = dict(N=64, K=4096, packed_w=A16, a_codes=A16, a_scale=A16, a_zero=A16, y_fp16=A16)
+
+    def call(arr, p=4, q=8, M=1, count=None, al=0, wl=0, ws=None, wsb=0):
+        return lib.abq_gemm_grouped(p, q, M, len(arr) if count is None else count, ctypes.addressof(arr), al, wl, ws, wsb, None)
+
+    def query(arr, p=4, q=8, M=1, al=0, wl=0):
+        return lib.abq_gemm_grouped_workspace_bytes(p, q, M, len(arr), ctypes.addressof(arr), al, wl)
+
+    assert lib.abq_gemm_grouped(4, 8, 1, 1, None, 0, 0, None, 0, None) == B.ABQ_ERR_NULL
+    assert call(_problems(packed), count=0) == B.ABQ_ERR_SHAPE
+    assert call(_problems(dict(packed, packed_w=None))) == B.ABQ_ERR_NULL
+    assert call(_problems(dict(packed, y_fp16=None))) == B.ABQ_ERR_NULL
+    assert call(_problems(dict(packed, packed_act=None))) == B.ABQ_ERR_NULL
+    assert call(_problems(dict(codes, a_zero=None))) == B.ABQ_ERR_NULL
+    assert call(_problems(packed, codes)) == B.ABQ_ERR_LAYOUT                  # mixed activation forms
+    assert call(_problems(dict(codes, packed_act=A16))) == B.ABQ_ERR_LAYOUT    # both forms in one descriptor
+    assert call(_problems(packed), p=9) == B.ABQ_ERR_BITS
+    assert call(_problems(dict(packed, N=0))) == B.ABQ_ERR_SHAPE
+    assert call(_problems(packed, dict(packed, K=B.ABQ_MAX_K + 1))) == B.ABQ_ERR_SHAPE
+    assert call(_problems(dict(packed, y_fp16=A16 + 2))) == B.ABQ_ERR_ALIGN
+    assert call(_problems(packed), wl=B.ABQ_USE_PLANES | B.ABQ_USE_FIELDS) == B.ABQ_ERR_LAYOUT
+    assert call(_problems(packed), al=9) == B.ABQ_ERR_LAYOUT
+    # workspace: none when one launch serves the group, none for packed activations
+    assert query(_problems(codes, dict(codes, N=11008), dict(codes, K=11008))) == 0
+    assert query(_problems(packed, dict(packed, K=100))) == 0
+    # unpacked codes that cannot be grouped (a short K here) fall back to single calls: the largest of their needs
+    short = dict(codes, K=1000)
+    need = query(_problems(codes, short))
+    assert need == lib.abq_gemm_act_codes_workspace_bytes(4, 8, 1, 64, 1000, 0) and need > 0
+    assert call(_problems(codes, short)) == B.ABQ_ERR_NULL
+    assert call(_problems(codes, short), ws=A16, wsb=16) == B.ABQ_ERR_SIZE
+    assert query(_problems(codes), p=0) == 0
+
+
 def test_unpack_rejects():
     lib = B.load()
     assert lib.abq_unpack_weights(4, 16, 64, B.ABQ_LAYOUT_FIELDS, A16, B.ABQ_LAYOUT_PLANES, A16, None) == B.ABQ_ERR_LAYOUT

@@ -289,6 +289,72 @@ def test_fused_act_extreme_codes(abq):
         check_against_oracle(c, y, acc)
 
 
+# ---- grouped decode launch -------------------------------------------------------------------------
+
+def run_group(abq, p, q, M, shapes, fused, seed0, w_layout=FIELDS, a_layout=FIELDS, gemm_w_layout=None):
+    """shapes: list of (N, K).  Returns [(case, y, acc)] after one abq_gemm_grouped call."""
+    cases, problems, keep = [], [], []
+    for i, (N, K) in enumerate(shapes):
+        c = synth.make_case(p, q, M, N, K, seed=seed0 + 17 * i, name=f"group[{i}] W{p}A{q} {M}x{N}x{K}")
+        pw = abq.abq_pack_weights(p, to_dev(torch, c.W), to_dev(torch, c.w_scale), to_dev(torch, c.w_zero), w_layout)
+        y = torch.full((M, N), float("nan"), dtype=torch.float16, device="cuda")
+        acc = torch.full((M, N), -7, dtype=torch.int32, device="cuda")
+        pr = dict(N=N, K=K, packed_w=pw, y=y, acc=acc)
+        if fused:
+            pr.update(a_codes=to_dev(torch, c.A), a_scale=to_dev(torch, c.a_scale), a_zero=to_dev(torch, c.a_zero))
+        else:
+            pr.update(packed_act=abq.abq_pack_act_codes(q, to_dev(torch, c.A), to_dev(torch, c.a_scale), to_dev(torch, c.a_zero), a_layout))
+        cases.append(c)
+        problems.append(pr)
+    abq.abq_gemm_grouped(p, q, M, problems, a_layout, w_layout if gemm_w_layout is None else gemm_w_layout)
+    torch.cuda.synchronize()
+    return [(c, pr["y"].cpu().numpy(), pr["acc"].cpu().numpy()) for c, pr in zip(cases, problems)]
+
+
+GROUP_SHAPES = [(4096, 4096), (33, 2048), (1000, 11008), (16, 2560), (4097, 4096), (250, 5120), (64, 13824), (7, 2064),
+                (300, 4096), (48, 8192), (129, 2048)]
+
+
+@pytest.mark.parametrize("fused", [False, True], ids=["packed", "fused"])
+@pytest.mark.parametrize("p,q,M", [(4, 8, 1), (2, 8, 5), (8, 8, 2), (1, 1, 16), (7, 3, 3), (3, 4, 8), (6, 6, 1), (5, 8, 12)])
+def test_grouped_launch(abq, p, q, M, fused):
+    say("grouped", p, q, M, fused)
+    shapes = GROUP_SHAPES[: 11 if M <= 5 else 6]        # 11 problems: two launches (8 + 3)
+    for c, y, acc in run_group(abq, p, q, M, shapes, fused, synth.case_seed(3, p, q) + M):
+        if M * c.N * c.K <= 1 << 27:
+            check_against_oracle(c, y, acc)
+        else:
+            check_sampled(c, y, acc)
+
+
+def test_grouped_launch_equals_single_calls_bitwise(abq):
+    p, q, M = 4, 8, 3
+    shapes = [(4096, 4096), (200, 11008), (31, 2048)]
+    for fused in (False, True):
+        for c, y, acc in run_group(abq, p, q, M, shapes, fused, 77):
+            y1, acc1 = gpu_gemm_fused(torch, abq, c, FIELDS) if fused else gpu_gemm(torch, abq, c, FIELDS, FIELDS)
+            assert np.array_equal(acc, acc1)
+            assert np.array_equal(y.view(np.uint16), y1.view(np.uint16))
+
+
+@pytest.mark.parametrize("fused", [False, True], ids=["packed", "fused"])
+@pytest.mark.parametrize("kind", ["short_k", "many_rows", "planes", "ragged_k", "long_k16"])
+def test_grouped_falls_back_to_single_calls(abq, kind, fused):
+    """Groups that one launch cannot serve run problem by problem with the same results."""
+    say("grouped fallback", kind, fused)
+    p, q, M, shapes, wl, al = 4, 8, 2, [(64, 4096), (40, 512)], FIELDS, FIELDS
+    if kind == "many_rows":
+        M, shapes = 40, [(64, 2048), (130, 2560)]
+    elif kind == "planes":
+        wl = al = PLANES
+    elif kind == "ragged_k":
+        shapes = [(64, 4096), (40, 4100)]
+    elif kind == "long_k16":
+        M, shapes = 16, [(64, 4096), (48, 13824)]
+    for c, y, acc in run_group(abq, p, q, M, shapes, fused, 91, w_layout=wl, a_layout=al):
+        check_against_oracle(c, y, acc)
+
+
 def test_config1_tiny(abq):
     c = synth.config1()
     for layout in (FIELDS, PLANES):
