@@ -336,10 +336,10 @@ __device__ __forceinline__ void item_step(const SkinnyParams& prm, WaveState<P>&
 // its row sums for the zero-point correction are taken on the way.
 // FULL: every wave of the launch has at least D items, so the ring prologue needs no conditions.
 // KG: K groups (see SkinnyParams); never together with FULL.
-// The body takes the workgroup's place in the launch as arguments (bx of gx workgroups along the tiles,
-// row group by) so that the grouped launch below can run it on one problem of several.
+// The body takes the workgroup's share of the problem as arguments (tiles tile0 + i * tstride, i < nmy; row
+// group by) so that the grouped launch below can run it on one problem of several.
 template <int P, int D, int EPT, bool RAW, bool FULL, bool KG>
-__device__ __forceinline__ void skinny_body(const SkinnyParams& prm, const int bx, const int gx, const int by)
+__device__ __forceinline__ void skinny_body(const SkinnyParams& prm, const int tile0, const int tstride, const int nmy, const int by)
 {
     static_assert(!(FULL && KG), "the K-group variant uses the conditional ring prologue");
     using GI = GroupInfo<P>;
@@ -351,7 +351,7 @@ __device__ __forceinline__ void skinny_body(const SkinnyParams& prm, const int b
     st.mt = mt;
     const int r = st.lane & 15, G = st.lane >> 4;
     st.nsuper = prm.nsuper;
-    st.tile0 = bx; st.tstride = gx;
+    st.tile0 = tile0; st.tstride = tstride;
     st.p_ti = 0; st.p_lsc = 0; st.ti = 0; st.lsc = 0; st.parity = 0;
 #ifdef ABQ_PHASE_TRACE
     unsigned long long ts[8] = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -360,7 +360,6 @@ __device__ __forceinline__ void skinny_body(const SkinnyParams& prm, const int b
     ABQ_TS(0);
 
     st.nsw = prm.sc_q + (st.wave < prm.sc_r ? 1 : 0);                       // this wave's super-chunks per tile (>= 1)
-    const int nmy = prm.tl_q + (bx < prm.tl_r ? 1 : 0);         // this workgroup's tiles (>= 1)
     st.nitems = nmy * st.nsw;
     st.nmy = nmy;
     st.g = 0; st.gs = 0; st.ge = KG ? group_bound(1, st.nsw, prm.kgroups) : st.nsw;
@@ -541,26 +540,32 @@ __device__ __forceinline__ void skinny_body(const SkinnyParams& prm, const int b
     }
 #ifdef ABQ_PHASE_TRACE
     ABQ_TS(6);
-    if (st.lane == 0 && bx < 1024 && st.wave < 8)
-        for (int i = 0; i < 8; ++i) g_phase_trace[((size_t)bx * 8 + st.wave) * 8 + i] = ts[i];
+    if (st.lane == 0 && blockIdx.x < 1024 && st.wave < 8)
+        for (int i = 0; i < 8; ++i) g_phase_trace[((size_t)blockIdx.x * 8 + st.wave) * 8 + i] = ts[i];
 #endif
 }
 
 template <int P, int D, int EPT, bool RAW, bool FULL, bool KG>
 __global__ __launch_bounds__(512) void skinny_kernel(SkinnyParams prm)
 {
-    skinny_body<P, D, EPT, RAW, FULL, KG>(prm, (int)blockIdx.x, (int)gridDim.x, (int)blockIdx.y);
+    // workgroup b owns tl_q + (b < tl_r) tiles: b, b + gridDim.x, ...
+    skinny_body<P, D, EPT, RAW, FULL, KG>(prm, (int)blockIdx.x, (int)gridDim.x, prm.tl_q + ((int)blockIdx.x < prm.tl_r ? 1 : 0),
+                                          (int)blockIdx.y);
 }
 
 // Grouped decode launch: up to kMaxGroup independent problems (same p, q and M <= 16; own A, W, Y, N, K)
-// in ONE launch.  Problem g gets workgroups first_wg[g] .. first_wg[g+1]-1, which walk its 16-row tiles
-// exactly as a launch of its own would (tile = bx + i * gx); the descriptor is read from the kernel arguments.  Microsecond-sized matmuls then share one
-// launch ramp and tail instead of paying one each (Sec. 3.4: the engine replaces all the linear
-// layers of a decoder block).
+// in ONE launch.  The 16-row tiles of all problems form one list (problem after problem); a resident set
+// of workgroups cuts it into equal contiguous runs, and a workgroup streams its run problem by problem
+// with the load ring running across the tiles of a problem (a run mostly lies inside one problem; where
+// it crosses into the next, the workgroup drains, stages that problem's rows of A and goes on).
+// Microsecond-sized matmuls then share one launch ramp and tail instead of paying one each (Sec. 3.4:
+// the engine replaces all the linear layers of a decoder block).  Descriptors are read from the kernel
+// arguments.
 constexpr int kMaxGroup = 8;
 struct GroupedParams {
     int count;
-    int first_wg[kMaxGroup + 1];
+    int run_q, run_r;                 // workgroup b owns run_q + (b < run_r) tiles of the list
+    int first_tile[kMaxGroup + 1];    // where each problem's tiles start in the list
     SkinnyParams d[kMaxGroup];
 };
 
@@ -568,11 +573,17 @@ template <int P, int D, int EPT, bool RAW>
 __global__ __launch_bounds__(512) void grouped_kernel(GroupedParams gp)
 {
     const int b = (int)blockIdx.x;
-    int g = 0;
-#pragma unroll
-    for (int i = 1; i < kMaxGroup; ++i)
-        if (i < gp.count && b >= gp.first_wg[i]) g = i;
-    skinny_body<P, D, EPT, RAW, false, false>(gp.d[g], b - gp.first_wg[g], gp.first_wg[g + 1] - gp.first_wg[g], 0);
+    const int t0 = b * gp.run_q + min(b, gp.run_r);
+    const int t1 = t0 + gp.run_q + (b < gp.run_r ? 1 : 0);
+    bool first = true;
+#pragma nounroll
+    for (int g = 0; g < gp.count; ++g) {
+        const int lo = max(t0, gp.first_tile[g]), hi = min(t1, gp.first_tile[g + 1]);
+        if (lo >= hi) continue;   // the same for the whole workgroup
+        if (!first) __syncthreads();   // every wave is done with the LDS contents of the problem before
+        first = false;
+        skinny_body<P, D, EPT, RAW, false, false>(gp.d[g], lo - gp.first_tile[g], 1, hi - lo, 0);
+    }
 }
 
 // ---- host side -------------------------------------------------------------------------------------
@@ -817,22 +828,35 @@ hipError_t launch_gemm_skinny(const GemmArgs& g, const ActLayout& A, const Weigh
 // One launch serves a group when every problem can run as "one workgroup of S waves per tile, all of
 // A staged at once": M <= 16, every K spans at least four super-chunks (S = 4..8 waves, the same for
 // all), the rows of A fit LDS, field-packed weights, and for unpacked codes K a multiple of 16.
-// Shape of a grouped launch, measured on the seven layer shapes of a LLaMA-7B block (W2/W4/W8, M = 1, 4, 8):
-// few rows of A -> many small workgroups (four waves, one or two tiles each: two or more share a CU and
-// hide each other's prologue and tail); more rows -> eight waves walking four tiles, so that the rows
-// of A are staged less often.  Tuning overrides, read once: ABQ_GROUP_TILES=<T>, ABQ_GROUP_WAVES=<S>.
-static int group_tiles_per_wg(int M)
+// Shape of a grouped launch, measured on the seven layer shapes of a LLaMA-7B block (W1/W2/W4/W8, M = 1, 4, 8):
+// few rows of A -> small workgroups (two waves for M <= 2, four for M <= 4) and four of them per CU, so that
+// the prologue and tail of one run hide behind the streams of the others; more rows -> eight waves, one
+// workgroup per CU, so that the rows of A are staged as seldom as possible.  Tuning overrides, read once:
+// ABQ_GROUP_WAVES=<S>, ABQ_GROUP_WGS=<workgroup count>.  A run never exceeds kMaxRun tiles (the epilogue
+// parameters of a run live in LDS).
+constexpr int kMaxRun = 64;
+static int group_waves(int M) { return M <= 2 ? 2 : (M <= 4 ? 4 : 8); }
+static int group_workgroups(int tiles, int M, int cus)
 {
     static int forced = -1;
-    if (forced < 0) forced = env_int("ABQ_GROUP_TILES");
-    if (forced > 0) return forced;
-    return M <= 2 ? 1 : (M <= 4 ? 2 : 4);
+    if (forced < 0) forced = env_int("ABQ_GROUP_WGS");
+    int gx = forced > 0 ? forced : (M <= 4 ? 4 * cus : cus);
+    if (gx > tiles) gx = tiles;
+    if ((tiles + gx - 1) / gx > kMaxRun) gx = (tiles + kMaxRun - 1) / kMaxRun;
+    return gx;
 }
 
+static size_t group_par_bytes(int run_max) { return (size_t)(16 + 16 * run_max) * sizeof(RowParams) + kAsumBytes; }
+
+// One launch serves a group when every problem can run as "S waves per tile, all of A staged at once":
+// M <= 16, every K spans at least four super-chunks (and at least S of them: S is the same for all), the
+// rows of A fit LDS, field-packed weights, and for unpacked codes K a multiple of 16.
 bool gemm_grouped_fits(int M, int count, const GemmArgs* probs, const ActLayout* A, const WeightLayout* W, int* waves, size_t* lds_bytes)
 {
     if (M > 16 || count < 1) return false;
-    int S = M <= 4 ? 4 : 8;
+    static int forced = -1;
+    if (forced < 0) forced = env_int("ABQ_GROUP_WAVES");
+    int S = forced >= 1 && forced <= 8 && forced != 3 ? forced : group_waves(M);
     for (int i = 0; i < count; ++i) {
         if (!W[i].has_fields) return false;
         if (probs[i].a_raw ? (probs[i].K % 16 != 0) : !A[i].has_fields) return false;
@@ -841,21 +865,19 @@ bool gemm_grouped_fits(int M, int count, const GemmArgs* probs, const ActLayout*
         if (nsuper < 4) return false;
         if (nsuper < S) S = nsuper;
     }
-    {
-        static int forced = -1;
-        if (forced < 0) forced = env_int("ABQ_GROUP_WAVES");
-        if (forced >= 2 && forced <= 8 && forced != 3) {
-            S = forced;
-            for (int i = 0; i < count; ++i)
-                if (A[i].Kp / kSuperK < S) S = A[i].Kp / kSuperK;
-        }
-    }
+    const int cus = num_cus();
     size_t lds = 0;
-    for (int i = 0; i < count; ++i) {
-        const size_t need = align_up((size_t)M * ((size_t)A[i].Kp + 16), 16) + (16 + 16 * group_tiles_per_wg(M)) * sizeof(RowParams) +
-                            kAsumBytes + 2 * (size_t)S * 1024;
-        if (need > kLdsPerCu) return false;
-        if (need > lds) lds = need;
+    for (int first = 0; first < count; first += kMaxGroup) {
+        const int n = count - first < kMaxGroup ? count - first : kMaxGroup;
+        int tiles = 0;
+        for (int i = first; i < first + n; ++i) tiles += W[i].NT;
+        const int gx = group_workgroups(tiles, M, cus);
+        const int run_max = (tiles + gx - 1) / gx;
+        for (int i = first; i < first + n; ++i) {
+            const size_t need = align_up((size_t)M * ((size_t)A[i].Kp + 16), 16) + group_par_bytes(run_max) + 2 * (size_t)S * 1024;
+            if (need > kLdsPerCu) return false;
+            if (need > lds) lds = need;
+        }
     }
     *waves = S;
     *lds_bytes = lds;
@@ -871,15 +893,20 @@ static hipError_t launch_grouped_pd(const GroupedParams& gp, bool raw, unsigned 
         if (e == hipSuccess) e = hipFuncSetAttribute((const void*)grouped_kernel<P, D, 1, false>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e == hipSuccess) e = hipFuncSetAttribute((const void*)grouped_kernel<P, D, 2, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e == hipSuccess) e = hipFuncSetAttribute((const void*)grouped_kernel<P, D, 2, false>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)grouped_kernel<P, D, 4, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)grouped_kernel<P, D, 4, false>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     if (waves >= 4) {
         if (raw) grouped_kernel<P, D, 1, true><<<grid, waves * 64, lds_bytes, s>>>(gp);
         else grouped_kernel<P, D, 1, false><<<grid, waves * 64, lds_bytes, s>>>(gp);
-    } else {
+    } else if (waves == 2) {
         if (raw) grouped_kernel<P, D, 2, true><<<grid, waves * 64, lds_bytes, s>>>(gp);
         else grouped_kernel<P, D, 2, false><<<grid, waves * 64, lds_bytes, s>>>(gp);
+    } else {
+        if (raw) grouped_kernel<P, D, 4, true><<<grid, waves * 64, lds_bytes, s>>>(gp);
+        else grouped_kernel<P, D, 4, false><<<grid, waves * 64, lds_bytes, s>>>(gp);
     }
     return hipGetLastError();
 }
@@ -892,8 +919,12 @@ hipError_t launch_gemm_grouped(int p, int M, int count, const GemmArgs* probs, c
         const int n = count - first < kMaxGroup ? count - first : kMaxGroup;
         GroupedParams gp;
         gp.count = n;
-        int wgs = 0;
-        const int T = group_tiles_per_wg(M);
+        int tiles = 0;
+        for (int i = first; i < first + n; ++i) tiles += W[i].NT;
+        const int wgs = group_workgroups(tiles, M, num_cus());
+        const int run_max = (tiles + wgs - 1) / wgs;
+        gp.run_q = tiles / wgs; gp.run_r = tiles % wgs;
+        tiles = 0;
         for (int i = 0; i < kMaxGroup; ++i) {
             const int src = first + (i < n ? i : 0);   // unused slots repeat a valid descriptor
             SkinnyParams& prm = gp.d[i];
@@ -902,22 +933,21 @@ hipError_t launch_gemm_grouped(int p, int M, int count, const GemmArgs* probs, c
             prm.a_stride = A[src].Kp + 16;
             prm.mrows = M;
             prm.par_off = (int)align_up((size_t)M * prm.a_stride, 16);
-            prm.red_off = prm.par_off + (int)((16 + 16 * T) * sizeof(RowParams) + kAsumBytes);
+            prm.red_off = prm.par_off + (int)group_par_bytes(run_max);
             prm.asum_off = prm.red_off - (int)kAsumBytes;
             prm.zero_off = prm.red_off - 512;
             prm.part_off = prm.red_off + 2 * waves * 1024;
             prm.kgroups = 1;
             prm.col_w = kSuperK;
             prm.col_s = waves * kSuperK;
-            const int gx = (W[src].NT + T - 1) / T;          // every workgroup walks at most T tiles
-            prm.nmy_max = T;
+            prm.nmy_max = run_max;
             prm.nsuper = nsuper;
             prm.sc_q = nsuper / waves; prm.sc_r = nsuper % waves;
-            prm.tl_q = W[src].NT / gx; prm.tl_r = W[src].NT % gx;
-            gp.first_wg[i] = wgs;
-            if (i < n) wgs += gx;
+            prm.tl_q = 0; prm.tl_r = 0;   // (not used: the kernel hands each workgroup its run)
+            gp.first_tile[i] = tiles;
+            if (i < n) tiles += W[src].NT;
         }
-        gp.first_wg[kMaxGroup] = wgs;
+        gp.first_tile[kMaxGroup] = tiles;
         hipError_t e;
         const bool raw = probs[first].a_raw != nullptr;
         switch (p) {
