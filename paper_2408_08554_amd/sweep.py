@@ -1,5 +1,7 @@
-"""Timing sweep of abq_gemm over (p, q, M, shape): `python -m paper_2408_08554_amd.sweep`.
+"""Timing sweep of the matmul over (p, q, M, shape): `python -m paper_2408_08554_amd.sweep`.
 
+The timed call is abq_gemm_act_codes where that is one kernel (decode shapes: activation pack fused
+in) and abq_gemm on pre-packed activations elsewhere; `--entry gemm` times abq_gemm everywhere.
 Prints one markdown table row per case: kernel time from a HIP-graph replay over rotating weight
 blobs (>= 1 GiB in total, so the last-level cache cannot serve the weight stream), effective
 TOPS = 2*M*N*K/t, packed-weight GB/s, and the fraction of the bound that applies (HBM 8 TB/s on
@@ -17,7 +19,7 @@ SHAPES = {"13b_up": (5120, 13824), "13b_down": (13824, 5120), "7b_q": (4096, 409
           "7b_down": (11008, 4096)}
 
 
-def time_case(p, q, M, K, N, family, launches, rotate_bytes):
+def time_case(p, q, M, K, N, family, launches, rotate_bytes, entry="auto"):
     layout = abq.ABQ_LAYOUT_PLANES if family == "bitserial" else abq.ABQ_LAYOUT_FIELDS
     g = torch.Generator(device="cuda").manual_seed(1000 * p + 10 * q + M % 7)
     W = torch.randint(0, 1 << p, (N, K), dtype=torch.uint8, device="cuda", generator=g)
@@ -37,15 +39,23 @@ def time_case(p, q, M, K, N, family, launches, rotate_bytes):
         b.copy_(blob0)
     pa = abq.abq_pack_act_codes(q, A, a_s, az, layout)
     y = torch.empty((M, N), dtype=torch.float16, device="cuda")
+    fused = entry != "gemm" and family != "bitserial" and abq.abq_gemm_act_codes_workspace_bytes(p, q, M, N, K, layout) == 0
+
+    def call(i):
+        if fused:
+            abq.abq_gemm_act_codes(p, q, M, N, K, A, a_s, az, blobs[i % R], layout, y=y)
+        else:
+            abq.abq_gemm(p, q, M, N, K, pa, layout, blobs[i % R], layout, y=y)
+
     stream = torch.cuda.Stream()
     with torch.cuda.stream(stream):
         for i in range(3):
-            abq.abq_gemm(p, q, M, N, K, pa, layout, blobs[i % R], layout, y=y)
+            call(i)
         stream.synchronize()
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph, stream=stream):
             for i in range(launches):
-                abq.abq_gemm(p, q, M, N, K, pa, layout, blobs[i % R], layout, y=y)
+                call(i)
         graph.replay()
         stream.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -64,6 +74,7 @@ def main():
     ap.add_argument("--shapes", default="13b_up,13b_down")
     ap.add_argument("--family", default="mfma", choices=["mfma", "bitserial"])
     ap.add_argument("--rotate-gib", type=float, default=1.0)
+    ap.add_argument("--entry", default="auto", choices=["auto", "gemm"])
     args = ap.parse_args()
     abq.load()
     torch.cuda.set_device(0)
@@ -75,7 +86,7 @@ def main():
             for p in (int(v) for v in args.p.split(",")):
                 for q in (int(v) for v in args.q.split(",")):
                     launches = 200 if M <= 16 else (40 if M <= 256 else 12)
-                    t = time_case(p, q, M, K, N, args.family, launches, int(args.rotate_gib * 2 ** 30))
+                    t = time_case(p, q, M, K, N, args.family, launches, int(args.rotate_gib * 2 ** 30), args.entry)
                     tops = metrics.effective_tops(M, N, K, t)
                     if M <= 39 * p:
                         bound, frac = "hbm", metrics.gemm_algorithmic_bytes(p, q, M, N, K) / t / 8e12
