@@ -73,6 +73,46 @@ def cpu_baseline(c, budget_s):
             f"dequant + half rounding) in {el:.1f} s"}
 
 
+def measured_peaks(pool, workload_bytes, launches=200):
+    """What this machine delivers for the two kinds of work the kernels are priced against, with the library's
+    probe kernels, graph-launched like the workload: a plain streaming read (of the workload's own size and of
+    64 MiB, rotating through `pool` so that the last-level cache cannot serve it) and a dense int8 MFMA loop."""
+    import torch
+    from paper_2408_08554_amd import binding as abq
+    sink = torch.zeros(4096, dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.Stream()
+
+    def timed(fn, n):
+        with torch.cuda.stream(stream):
+            for i in range(3):
+                fn(i)
+            stream.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=stream):
+                for i in range(n):
+                    fn(i)
+            g.replay()
+            stream.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            g.replay()
+            e1.record(stream)
+            torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / n
+
+    out = {}
+    for key, nbytes in (("stream_read_workload_size", workload_bytes), ("stream_read_64MiB", 64 << 20)):
+        nbytes = max(4096, min(nbytes, pool.numel() // 2) // 256 * 256)
+        slots = pool.numel() // nbytes
+        t = timed(lambda i: abq.abq_probe_stream_read(pool[(i % slots) * nbytes:], nbytes, sink), launches)
+        out[key] = {"bytes": nbytes, "us": t * 1e6, "gbs": nbytes / t / 1e9}
+    iters = 2000
+    for key, pattern in (("mfma_i8_mostly_zero_operand_bytes", 0), ("mfma_i8_nonzero_operand_bytes", 1)):
+        t = timed(lambda i: abq.abq_probe_mfma_i8(iters, pattern, sink), 10)
+        out[key] = {"us": t * 1e6, "tops": abq.abq_probe_mfma_i8_ops(iters) / t / 1e12}
+    return out
+
+
 # The seven linear layers of one LLaMA-7B decoder block as (name, N, K): the shapes the paper's engine
 # replaces in a block (Sec. 3.4; Appendix D measures these layer shapes one by one).
 BLOCK_7B = [("q_proj", 4096, 4096), ("k_proj", 4096, 4096), ("v_proj", 4096, 4096), ("o_proj", 4096, 4096),
@@ -336,6 +376,12 @@ def main():
                           "step": "abq_pack_act_codes + abq_gemm"},
         "roofline": roof,
     }
+    peaks = measured_peaks(pool, alg_bytes)
+    out["measured_peaks"] = peaks
+    roof["measured_peak"] = peaks["stream_read_64MiB"]["gbs"] if hbm_bound else peaks["mfma_i8_nonzero_operand_bytes"]["tops"]
+    roof["frac_of_measured_peak"] = achieved / roof["measured_peak"]
+    if hbm_bound:   # a plain read of the same number of bytes in a launch of its own: the floor for this size
+        roof["frac_of_plain_read_same_size"] = peaks["stream_read_workload_size"]["us"] / (gemm_s * 1e6)
     if args.grouped_steps > 0 and M <= 16:
         del pool, blobs
         torch.cuda.empty_cache()

@@ -190,6 +190,25 @@ size_t abq_gemm_grouped_workspace_bytes(int p, int q, int M, int count, const ab
 int abq_gemm_grouped(int p, int q, int M, int count, const abq_problem* host_problems,
                      int a_layout, int w_layout, void* workspace, size_t workspace_bytes, void* stream);
 
+/* ------------------------------------------------------------------------------------------
+ * Measurement aids (no part of the method; for callers that price achieved figures against what
+ * the machine delivers, beside its published peaks).  Each enqueues ONE kernel; the caller times it.
+ * ------------------------------------------------------------------------------------------ */
+
+/* Streaming read of `bytes` bytes (a multiple of 16) at `buf` with 128-bit non-temporal loads, the access
+ * the decode kernel uses for its weights; nothing is written (`sink`: >= 2 KiB of device memory that
+ * stays untouched in practice). */
+int abq_probe_stream_read(const void* buf, size_t bytes, void* sink, void* stream);
+
+/* Dense int8 MFMA issue loop on every CU: `iters` rounds of eight independent 16x16x64 MFMAs per wave,
+ * 32 waves per CU.  pattern 0: three of four operand bytes zero; pattern 1: every operand byte non-zero
+ * and varying from lane to lane (the sustained rate depends on the data: the chip lowers its clock on
+ * the latter).  abq_probe_mfma_i8_ops(iters) is the
+ * number of integer operations (2 per MAC) one such launch performs on the current device (0 for
+ * iters < 1). */
+int abq_probe_mfma_i8(int iters, int pattern, void* sink, void* stream);
+double abq_probe_mfma_i8_ops(int iters);
+
 #ifdef __cplusplus
 }
 #endif

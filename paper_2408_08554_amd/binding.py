@@ -38,6 +38,9 @@ _SIGNATURES = {
     "abq_gemm_act_codes_workspace_bytes": (_c.c_size_t, [_c.c_int] * 6),
     "abq_gemm_grouped_workspace_bytes": (_c.c_size_t, [_c.c_int] * 4 + [_c.c_void_p, _c.c_int, _c.c_int]),
     "abq_gemm_grouped": (_c.c_int, [_c.c_int] * 4 + [_c.c_void_p, _c.c_int, _c.c_int, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
+    "abq_probe_stream_read": (_c.c_int, [_c.c_void_p, _c.c_size_t, _c.c_void_p, _c.c_void_p]),
+    "abq_probe_mfma_i8": (_c.c_int, [_c.c_int, _c.c_int, _c.c_void_p, _c.c_void_p]),
+    "abq_probe_mfma_i8_ops": (_c.c_double, [_c.c_int]),
     "abq_gemm_act_codes": (_c.c_int, [_c.c_int] * 5 + [_c.c_void_p] * 4 + [_c.c_int, _c.c_void_p, _c.c_void_p,
                                                                           _c.c_void_p, _c.c_size_t, _c.c_void_p]),
 }
@@ -243,3 +246,15 @@ def abq_gemm_grouped(p, q, M, problems, a_layout, w_layout, workspace=None):
         workspace = torch.empty(need, dtype=torch.uint8, device="cuda")
     _check(lib.abq_gemm_grouped(p, q, M, len(arr), _c.addressof(arr), a_layout, w_layout, _ptr(workspace),
                                 0 if workspace is None else workspace.numel(), _stream()), "abq_gemm_grouped")
+
+
+def abq_probe_stream_read(buf, nbytes, sink):
+    _check(load().abq_probe_stream_read(_ptr(buf), nbytes, _ptr(sink), _stream()), "abq_probe_stream_read")
+
+
+def abq_probe_mfma_i8(iters, pattern, sink):
+    _check(load().abq_probe_mfma_i8(iters, pattern, _ptr(sink), _stream()), "abq_probe_mfma_i8")
+
+
+def abq_probe_mfma_i8_ops(iters):
+    return load().abq_probe_mfma_i8_ops(iters)

@@ -1,0 +1,95 @@
+// Measurement aids, not part of the method: a plain streaming read and an int8 MFMA issue loop, so that
+// achieved figures can be priced against what this machine delivers for the same kind of work, beside
+// the published peaks (HBM 8 TB/s, dense int8 5 POP/s).  The caller times the launches.
+#include "abq_internal.h"
+#include "../../include/abq.h"
+
+namespace abq {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef unsigned int u4v __attribute__((ext_vector_type(4)));
+
+// Every thread reads U 16-byte vectors a workgroup-stride apart with non-temporal loads (what the decode
+// kernel issues for its weights) and folds them; the fold is stored only for a value that does not occur.
+template <int U>
+__global__ __launch_bounds__(512) void stream_read_kernel(const u4v* src, size_t nvec, uint32_t* sink)
+{
+    const size_t base = (size_t)blockIdx.x * (blockDim.x * U) + threadIdx.x;
+    u4v v[U];
+#pragma unroll
+    for (int i = 0; i < U; ++i) {
+        const size_t idx = base + (size_t)i * blockDim.x;
+        v[i] = __builtin_nontemporal_load(src + (idx < nvec ? idx : nvec - 1));   // clamped: no conditional load
+    }
+    uint32_t s = 0;
+#pragma unroll
+    for (int i = 0; i < U; ++i) s ^= v[i].x ^ v[i].y ^ v[i].z ^ v[i].w;
+    if (s == 0x9E3779B9u) sink[threadIdx.x] = s;
+}
+
+// Eight independent 16x16x64 int8 MFMA chains per wave, `iters` rounds.  pattern 0: three of four operand
+// bytes are zero; pattern 1: every operand byte is non-zero and differs from lane to lane.  The sustained
+// rate depends on the data: measured on MI355X, the chip holds its clock on the former (4.1-4.9 POP/s)
+// and lowers it on the latter (2.3-2.9 POP/s), which is the rate real operands see.
+__global__ void mfma_i8_kernel(int iters, int pattern, uint32_t* sink)   // (no launch bounds: with a 512-register budget the allocator moves the accumulators through AGPRs every round)
+{
+    v4i acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = v4i{0, 0, 0, 0};
+    const int t = (int)threadIdx.x;
+    const int h = (t * 0x9E3779B1) ^ (t << 13);
+    const v4i a = pattern ? v4i{h, h * 3 + 0x5A5A5A5A, ~h, h * 7 + 0x33CC33CC} : v4i{t, 1, 2, 3};
+    const v4i b = pattern ? v4i{h * 5, ~(h * 11), h * 13 + 0x0F0F0F0F, h * 17} : v4i{4, 5, 6, t};
+    for (int i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, acc[j], 0, 0, 0);
+    }
+    int s = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) s ^= acc[j].x ^ acc[j].y ^ acc[j].z ^ acc[j].w;
+    if (s == 0x12345 && iters < 0) sink[t] = (uint32_t)s;
+}
+
+static const int kProbeWaveMfmas = 8;          // per round
+static const int kProbeWgsPerCu = 8, kProbeWaves = 4;
+
+}  // namespace abq
+
+using namespace abq;
+
+extern "C" {
+
+int abq_probe_stream_read(const void* buf, size_t bytes, void* sink, void* stream)
+{
+    if (!buf || !sink) return ABQ_ERR_NULL;
+    if (bytes < 16 || bytes % 16 != 0) return ABQ_ERR_SHAPE;
+    if (((uintptr_t)buf & 15u) || ((uintptr_t)sink & 15u)) return ABQ_ERR_ALIGN;
+    constexpr int U = 8, threads = 512;
+    const size_t nvec = bytes / 16;
+    const size_t per_wg = (size_t)threads * U;
+    const size_t grid = (nvec + per_wg - 1) / per_wg;
+    if (grid > 0x7fffffffu) return ABQ_ERR_SHAPE;
+    stream_read_kernel<U><<<(unsigned)grid, threads, 0, (hipStream_t)stream>>>((const u4v*)buf, nvec, (uint32_t*)sink);
+    return hipGetLastError() == hipSuccess ? ABQ_OK : ABQ_ERR_HIP;
+}
+
+double abq_probe_mfma_i8_ops(int iters)
+{
+    if (iters < 1) return 0.0;
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+    return 2.0 * 16 * 16 * 64 * (double)kProbeWaveMfmas * iters * kProbeWaves * kProbeWgsPerCu * cus;
+}
+
+int abq_probe_mfma_i8(int iters, int pattern, void* sink, void* stream)
+{
+    if (!sink) return ABQ_ERR_NULL;
+    if (iters < 1 || iters > (1 << 20) || pattern < 0 || pattern > 1) return ABQ_ERR_SHAPE;
+    if ((uintptr_t)sink & 15u) return ABQ_ERR_ALIGN;
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+    mfma_i8_kernel<<<(unsigned)(cus * kProbeWgsPerCu), kProbeWaves * 64, 0, (hipStream_t)stream>>>(iters, pattern, (uint32_t*)sink);
+    return hipGetLastError() == hipSuccess ? ABQ_OK : ABQ_ERR_HIP;
+}
+
+}  // extern "C"

@@ -185,6 +185,19 @@ def test_gemm_grouped_rejects_and_workspace_query():
     assert query(_problems(codes), p=0) == 0
 
 
+def test_probe_rejects():
+    lib = B.load()
+    assert lib.abq_probe_stream_read(None, 4096, A16, None) == B.ABQ_ERR_NULL
+    assert lib.abq_probe_stream_read(A16, 4096, None, None) == B.ABQ_ERR_NULL
+    assert lib.abq_probe_stream_read(A16, 8, A16, None) == B.ABQ_ERR_SHAPE
+    assert lib.abq_probe_stream_read(A16, 4100, A16, None) == B.ABQ_ERR_SHAPE
+    assert lib.abq_probe_stream_read(A16 + 4, 4096, A16, None) == B.ABQ_ERR_ALIGN
+    assert lib.abq_probe_mfma_i8(10, 0, None, None) == B.ABQ_ERR_NULL
+    assert lib.abq_probe_mfma_i8(0, 0, A16, None) == B.ABQ_ERR_SHAPE
+    assert lib.abq_probe_mfma_i8(10, 2, A16, None) == B.ABQ_ERR_SHAPE
+    assert lib.abq_probe_mfma_i8_ops(0) == 0.0
+
+
 def test_unpack_rejects():
     lib = B.load()
     assert lib.abq_unpack_weights(4, 16, 64, B.ABQ_LAYOUT_FIELDS, A16, B.ABQ_LAYOUT_PLANES, A16, None) == B.ABQ_ERR_LAYOUT

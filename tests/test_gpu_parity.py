@@ -355,6 +355,19 @@ def test_grouped_falls_back_to_single_calls(abq, kind, fused):
         check_against_oracle(c, y, acc)
 
 
+def test_measurement_probes_run(abq):
+    """The two probe kernels launch, finish and leave their sink alone."""
+    buf = torch.ones(8 << 20, dtype=torch.uint8, device="cuda")
+    sink = torch.zeros(4096, dtype=torch.uint8, device="cuda")
+    abq.abq_probe_stream_read(buf, buf.numel(), sink)
+    abq.abq_probe_stream_read(buf[256:], 4096 + 16, sink)       # a ragged size: the last workgroup clamps its reads
+    abq.abq_probe_mfma_i8(100, 0, sink)
+    abq.abq_probe_mfma_i8(100, 1, sink)
+    torch.cuda.synchronize()
+    assert int(sink.sum()) == 0
+    assert abq.abq_probe_mfma_i8_ops(1) == 2.0 * 16 * 16 * 64 * 8 * 4 * 8 * torch.cuda.get_device_properties(0).multi_processor_count
+
+
 def test_config1_tiny(abq):
     c = synth.config1()
     for layout in (FIELDS, PLANES):
