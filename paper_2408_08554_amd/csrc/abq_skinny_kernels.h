@@ -1,0 +1,690 @@
+// Device code of the streaming decode kernel and the templates that launch its variants.  Included by the
+// host-side translation unit (abq_skinny.hip) for the argument structures and by one translation unit per
+// pair of weight widths (abq_skinny_p12.hip ...), which hold the kernel instantiations, so that they
+// compile in parallel.
+//
+// Decode-shaped matmul (M = 1 .. 64): the packed weight plane groups are streamed from HBM
+// exactly once with 128-bit coalesced non-temporal loads, expanded to signed bytes in
+// registers with one AND per dword, and contracted against the int8 activation codes on the
+// 16x16x64 int8 MFMA.  Bit reduction (Sec. 3.4 step 5 / Appendix B: the 2^(s+t) factors)
+// happens in registers: the activation side carries all q planes at once as the int8 code,
+// the weight side one plane group per accumulator, recombined with shifts after the K loop.
+// The dequant epilogue is fused (Fig. 3b).
+//
+// Work decomposition: a workgroup of S waves owns one 16-row tile of W at a time (and walks
+// several tiles when the grid is smaller than the tile count).  Its waves split K in units
+// of 512 (a "super-chunk": every plane group tiles 512 k-values with whole 1 KiB wave loads),
+// wave w taking super-chunks w, w+S, ...  Each wave keeps a ring of D super-chunks of weight
+// loads in flight, running ahead across tile boundaries, so the stream never drains between
+// tiles.  The rows of A a wave needs are staged once into its own part of LDS (no barrier on
+// the way to the first MFMA).  Per tile the S partial tiles are summed through LDS.
+#pragma once
+#include "abq_internal.h"
+#include "../../include/abq.h"
+
+#include <hip/hip_fp16.h>
+#include <stdlib.h>
+
+namespace abq {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef unsigned int u4v __attribute__((ext_vector_type(4)));
+
+// Phase timestamps for kernel tuning; compiled out unless a harness defines ABQ_PHASE_TRACE.
+#ifdef ABQ_PHASE_TRACE
+__device__ unsigned long long g_phase_trace[1024 * 8 * 8];
+#define ABQ_TS(i) ts[i] = wall_clock64()
+#define ABQ_TSS(i) st.ts[i] = wall_clock64()
+#else
+#define ABQ_TS(i)
+#define ABQ_TSS(i)
+#endif
+
+struct SkinnyParams {
+    const u4v* fields[3];     // per plane group
+    int chunks[3];
+    const int8_t* a_codes;    // [M][Kp]  (packed activations)
+    const RowParams* aparams;
+    const uint8_t* a_raw;     // [M][K] unpacked codes, with a_scale / a_zero: the fused-pack variant reads these instead
+    const float* a_scale;
+    const int32_t* a_zero;
+    const RowParams* wparams;
+    uint16_t* y;
+    int32_t* acc;
+    int M, N, K, Kp;
+    int oa, ow;
+    int ntiles;               // 16-row tiles of W
+    int nsuper;               // Kp / 512
+    int sc_q, sc_r;           // nsuper = sc_q * S + sc_r   (S = waves per workgroup): wave w owns sc_q + (w < sc_r) super-chunks
+    int tl_q, tl_r;           // ntiles = tl_q * gridDim.x + tl_r: workgroup b owns tl_q + (b < tl_r) tiles
+    int mrows;                // rows of A per workgroup (<= 16); blockIdx.y walks row groups
+    int a_stride;             // bytes per staged row of A (Kp + 16: rows land 16 B apart in bank space)
+    int par_off;              // byte offset in LDS of the staged per-row / per-channel parameters
+    int red_off;              // byte offset in LDS of the two reduction buffers
+    int asum_off;             // byte offset in LDS of the per-wave partial row sums of A ([S][16] int32, fused-pack variant)
+    int zero_off;             // byte offset in LDS of 512 zero bytes
+    // K groups (long K with up to 16 rows of A: all of A does not fit LDS at once).  A wave's nsw super-chunks
+    // are cut into kgroups runs [g*nsw/kgroups, (g+1)*nsw/kgroups); the workgroup walks its tiles once per
+    // run with only that run's columns of A staged, keeping per-tile partial sums in LDS in between.
+    int kgroups;              // 1: everything staged once
+    int col_w, col_s;         // LDS column of (wave, slot) = wave*col_w + slot*col_s  (slot = super-chunk index inside the run)
+    int part_off;             // byte offset in LDS of the partial sums [S][nmy_max][256] int32 (kgroups > 1)
+    int nmy_max;              // most tiles any workgroup owns
+};
+
+// g * n / G for the few group counts the host uses (constant divisors).
+__device__ __forceinline__ int group_bound(int g, int n, int G)
+{
+    const int x = g * n;
+    switch (G) {
+        case 1: return x;
+        case 2: return x >> 1;
+        case 3: return x / 3;
+        default: return x >> 2;
+    }
+}
+// Field t of a b-bit group as a signed-byte MFMA operand dword, and the power of two it is
+// scaled by.  The field that would touch the byte's sign bit is moved down one bit instead
+// (b = 2, 4) or taken as is with weight -128 (b = 1).
+template <int B, int T>
+__device__ __forceinline__ uint32_t field_bytes(uint32_t x)
+{
+    if constexpr (B == 8) return x;
+    else if constexpr (B == 4) return T == 0 ? (x & 0x0F0F0F0Fu) : ((x >> 1) & 0x78787878u);
+    else if constexpr (B == 2) return T == 3 ? ((x >> 1) & 0x60606060u) : (x & (0x03030303u << (2 * T)));
+    else return x & (0x01010101u << T);
+}
+template <int B, int T>
+__device__ __forceinline__ int32_t field_unscale(int32_t acc)
+{
+    if constexpr (B == 8) return acc;
+    else if constexpr (B == 4) return T == 0 ? acc : (acc >> 3);
+    else if constexpr (B == 2) return T == 3 ? (acc >> 5) : (acc >> (2 * T));
+    else return T == 7 ? -(acc >> 7) : (acc >> T);
+}
+
+template <int B, int T>
+__device__ __forceinline__ v4i field_operand(const u4v& w)
+{
+    v4i r;
+    r.x = (int)field_bytes<B, T>(w.x);
+    r.y = (int)field_bytes<B, T>(w.y);
+    r.z = (int)field_bytes<B, T>(w.z);
+    r.w = (int)field_bytes<B, T>(w.w);
+    return r;
+}
+
+// Per-group compile-time bookkeeping for weight width P.
+template <int P> struct GroupInfo {
+    static constexpr int NG = group_count(P);
+    static constexpr int loads = P;   // sum_g b_g chunks of 1 KiB per super-chunk
+    __host__ __device__ static constexpr int b(int g) { return group_width(P, g); }
+    __host__ __device__ static constexpr int load_base(int g) { return group_shift(P, g); }   // sum of widths below g
+    __host__ __device__ static constexpr int acc_base(int g)
+    {
+        return g == 0 ? 0 : (g == 1 ? 8 / b(0) : 8 / b(0) + 8 / b(1));
+    }
+    static constexpr int NACC = acc_base(NG - 1) + 8 / b(NG - 1);
+};
+
+// MFMAs of one chunk (index I inside the super-chunk) of group width B: slices I*T .. I*T+T-1.
+template <int B, int I, int T0 = 0>
+__device__ __forceinline__ void chunk_mfma(const u4v& w, const v4i* aop, v4i* acc)
+{
+    constexpr int T = 8 / B;
+    if constexpr (T0 < T) {
+        acc[T0] = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[I * T + T0], field_operand<B, T0>(w), acc[T0], 0, 0, 0);
+        chunk_mfma<B, I, T0 + 1>(w, aop, acc);
+    }
+}
+template <int B, int I = 0>
+__device__ __forceinline__ void group_mfma(const u4v* w, const v4i* aop, v4i* acc)
+{
+    if constexpr (I < B) {   // a b-bit group has b chunks per super-chunk
+        chunk_mfma<B, I>(w[I], aop, acc);
+        group_mfma<B, I + 1>(w, aop, acc);
+    }
+}
+template <int B, int T0 = 0>
+__device__ __forceinline__ v4i group_combine(const v4i* acc)
+{
+    constexpr int T = 8 / B;
+    v4i r;
+    r.x = field_unscale<B, T0>(acc[T0].x);
+    r.y = field_unscale<B, T0>(acc[T0].y);
+    r.z = field_unscale<B, T0>(acc[T0].z);
+    r.w = field_unscale<B, T0>(acc[T0].w);
+    if constexpr (T0 + 1 < T) r += group_combine<B, T0 + 1>(acc);
+    return r;
+}
+
+// Sum of v over the 64 lanes, returned in every lane: four DPP steps inside each row of 16
+// lanes, then the four row totals are read out as scalars.
+__device__ __forceinline__ int32_t wave_sum(int32_t v)
+{
+    v += __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xF, 0xF, false);    // quad_perm [1,0,3,2]
+    v += __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xF, 0xF, false);    // quad_perm [2,3,0,1]
+    v += __builtin_amdgcn_update_dpp(0, v, 0x141, 0xF, 0xF, false);   // row_half_mirror
+    v += __builtin_amdgcn_update_dpp(0, v, 0x140, 0xF, 0xF, false);   // row_mirror
+    return (__builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16)) +
+           (__builtin_amdgcn_readlane(v, 32) + __builtin_amdgcn_readlane(v, 48));
+}
+
+// One super-chunk of one tile: P wave loads of 1 KiB.  Every group stores whole super-chunks
+// (chunk count = b * Kp/512), so no load is conditional.
+template <int P>
+__device__ __forceinline__ void load_super(const SkinnyParams& prm, int nsuper, int tile, int sc, int lane, u4v* w)
+{
+    using GI = GroupInfo<P>;
+#pragma unroll
+    for (int g = 0; g < GI::NG; ++g) {
+        const int b = GI::b(g);
+        const u4v* base = prm.fields[g] + ((size_t)tile * nsuper + sc) * (b * 64) + lane;
+#pragma unroll
+        for (int i = 0; i < b; ++i)   // read once: non-temporal, so the stream does not displace A and the parameters in L2
+            w[GI::load_base(g) + i] = __builtin_nontemporal_load(base + i * 64);
+    }
+}
+
+template <int P>
+__device__ __forceinline__ void compute_super(const u4v* w, const uint8_t* lds_row, v4i* acc)
+{
+    using GI = GroupInfo<P>;
+    v4i aop[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) aop[j] = *reinterpret_cast<const v4i*>(lds_row + j * 64);
+    group_mfma<GI::b(0)>(w + GI::load_base(0), aop, acc + GI::acc_base(0));
+    if constexpr (GI::NG > 1) group_mfma<GI::b(1)>(w + GI::load_base(1), aop, acc + GI::acc_base(1));
+    if constexpr (GI::NG > 2) group_mfma<GI::b(2)>(w + GI::load_base(2), aop, acc + GI::acc_base(2));
+}
+
+// Per-wave streaming state (lives in registers once everything is inlined).
+template <int P>
+struct WaveState {
+    int nsuper, S, nsw, nitems;
+    int tile0, tstride;            // this workgroup's tiles: tile0 + i * tstride
+    int p_ti, p_lsc;               // next item to prefetch
+    int ti, lsc, parity;           // item being consumed
+    int nmy;                       // tiles this workgroup owns
+    int g, gs, ge;                 // K group being consumed and its run [gs, ge) of this wave's super-chunks
+    int p_g, p_gs, p_ge;           // the same for the prefetch side
+    int32_t* part;                 // LDS: this wave's partial sums [nmy_max][256] (kgroups > 1)
+    int lane, wave, tid, m0, mt;   // mt = rows of A this workgroup owns (<= 16)
+    const uint8_t* lds_lane;       // this lane's A operand base in LDS: its row of A, or a block of zeros for rows past mt
+    int k_mask;                    // ~0 for a row of A, 0 for the zero block (which has no k extent)
+    const RowParams* par;          // LDS: [16] rows of A, then [nmy][16] channels
+    const int32_t* asum;           // LDS: [S][16] partial row sums of A (fused-pack variant)
+    int32_t* red;
+    v4i acc[GroupInfo<P>::NACC];
+#ifdef ABQ_PHASE_TRACE
+    unsigned long long* ts;
+#endif
+};
+
+// Item order: (K group,) tile, super-chunk.
+template <int P, bool KG = false>
+__device__ __forceinline__ void prefetch_item(const SkinnyParams& prm, WaveState<P>& st, u4v* slot)
+{
+    load_super<P>(prm, st.nsuper, st.tile0 + st.p_ti * st.tstride, st.wave + st.p_lsc * st.S, st.lane, slot);
+    if constexpr (!KG) {
+        if (++st.p_lsc == st.nsw) { st.p_lsc = 0; ++st.p_ti; }
+    } else {
+        if (++st.p_lsc == st.p_ge) {
+            if (++st.p_ti == st.nmy) {
+                st.p_ti = 0;
+                ++st.p_g;
+                st.p_gs = st.p_ge;
+                st.p_ge = group_bound(st.p_g + 1, st.nsw, prm.kgroups);
+            }
+            st.p_lsc = st.p_gs;
+        }
+    }
+}
+
+// LDS address of this lane's A operand for the super-chunk being consumed.
+template <int P, bool KG>
+__device__ __forceinline__ const uint8_t* operand_row(const SkinnyParams& prm, const WaveState<P>& st)
+{
+    if constexpr (!KG) return st.lds_lane + (((st.wave + st.lsc * st.S) * kSuperK) & st.k_mask);
+    else return st.lds_lane + ((st.wave * prm.col_w + (st.lsc - st.gs) * prm.col_s) & st.k_mask);
+}
+
+// End of a tile on this wave: bit reduction over the plane groups, sum over the S waves
+// through LDS (two buffers alternate, so one barrier per tile is enough), fused epilogue.
+template <int P, int EPT, bool RAW, bool KG = false>
+__device__ __forceinline__ void finish_tile(const SkinnyParams& prm, WaveState<P>& st)
+{
+    using GI = GroupInfo<P>;
+    ABQ_TSS(3);
+    v4i total = group_combine<GI::b(0)>(st.acc + GI::acc_base(0));
+    if constexpr (GI::NG > 1) total += group_combine<GI::b(1)>(st.acc + GI::acc_base(1)) << GI::load_base(1);
+    if constexpr (GI::NG > 2) total += group_combine<GI::b(2)>(st.acc + GI::acc_base(2)) << GI::load_base(2);
+#pragma unroll
+    for (int i = 0; i < GI::NACC; ++i) st.acc[i] = v4i{0, 0, 0, 0};
+    if constexpr (KG) {
+        // all but the last K group: the tile's sum so far stays in this wave's own part of LDS
+        int32_t* pp = st.part + st.ti * 256 + st.lane;
+        if (st.g > 0) {
+#pragma unroll
+            for (int reg = 0; reg < 4; ++reg) total[reg] += pp[reg * 64];
+        }
+        if (st.g < prm.kgroups - 1) {
+#pragma unroll
+            for (int reg = 0; reg < 4; ++reg) pp[reg * 64] = total[reg];
+            ++st.ti;
+            return;
+        }
+    }
+    int32_t* rb = st.red + st.parity * (st.S * 256);
+#pragma unroll
+    for (int reg = 0; reg < 4; ++reg) rb[(st.wave * 4 + reg) * 64 + st.lane] = total[reg];
+    ABQ_TSS(4);
+    __syncthreads();
+    ABQ_TSS(5);
+    // thread t finishes C elements e = t + i*blockDim < 256; element e is register e/64 of lane e%64:
+    // row 4*((e%64)/16) + e/64 of A, column e%16 of the tile (the 16x16 MFMA accumulator layout)
+    const int tile = st.tile0 + st.ti * st.tstride;
+    const int n = tile * kTileN + (st.tid & 15);
+    const RowParams pw = st.par[16 + st.ti * 16 + (st.tid & 15)];
+#pragma unroll
+    for (int i = 0; i < EPT; ++i) {
+        const int e = st.tid + i * (int)blockDim.x;
+        const int row = 4 * ((e & 63) >> 4) + (e >> 6);
+        const int m = st.m0 + row;
+        if ((EPT > 1 || e < 256) && row < st.mt && n < prm.N) {   // rows past mt belong to the next row group's workgroup
+            int32_t part[8];
+#pragma unroll
+            for (int ww = 0; ww < 8; ++ww) part[ww] = ww < st.S ? rb[ww * 256 + e] : 0;   // independent reads, one wait
+            const int32_t s = ((part[0] + part[1]) + (part[2] + part[3])) + ((part[4] + part[5]) + (part[6] + part[7]));
+            RowParams pa = st.par[row];
+            if constexpr (RAW) {   // the row sum of A was taken while staging, one part per wave
+                int32_t sp[8];
+#pragma unroll
+                for (int ww = 0; ww < 8; ++ww) sp[ww] = ww < st.S ? st.asum[ww * 16 + row] : 0;
+                pa.sum = ((sp[0] + sp[1]) + (sp[2] + sp[3])) + ((sp[4] + sp[5]) + (sp[6] + sp[7]));
+            }
+            epilogue_store(s, prm.oa, prm.ow, prm.K, pa, pw, (size_t)m * prm.N + n, prm.y, prm.acc);
+        }
+    }
+    st.parity ^= 1;
+    ++st.ti;
+}
+
+// One item: MFMAs, refill of its ring slot, end-of-tile work.  With K groups, the end of a group's last
+// tile moves on to the next run of super-chunks and stages its columns of A (next_group).
+template <int P, int EPT, bool RAW, bool KG, bool REFILL, typename F>
+__device__ __forceinline__ void item_step(const SkinnyParams& prm, WaveState<P>& st, u4v* slot, bool refill, F&& next_group)
+{
+    compute_super<P>(slot, operand_row<P, KG>(prm, st), st.acc);
+    if (REFILL) prefetch_item<P, KG>(prm, st, slot);
+    else if (refill) prefetch_item<P, KG>(prm, st, slot);
+    if constexpr (!KG) {
+        if (++st.lsc == st.nsw) { finish_tile<P, EPT, RAW>(prm, st); st.lsc = 0; }
+    } else {
+        if (++st.lsc == st.ge) {
+            finish_tile<P, EPT, RAW, true>(prm, st);
+            if (st.ti == st.nmy) {
+                st.ti = 0;
+                ++st.g;
+                st.gs = st.ge;
+                st.ge = group_bound(st.g + 1, st.nsw, prm.kgroups);
+                if (st.g < prm.kgroups) next_group();
+            }
+            st.lsc = st.gs;
+        }
+    }
+}
+
+// D = super-chunks of weight loads each wave keeps in flight; EPT = C elements per thread in
+// the epilogue (1 for >= 4 waves, 2 for two waves, 4 for one).  RAW: the activation BitPacking
+// step is fused in (Fig. 3b packs activations online; Sec. 3.4 folds that cost into existing
+// operators): A arrives as unpacked codes, is offset to signed bytes while it is staged, and
+// its row sums for the zero-point correction are taken on the way.
+// FULL: every wave of the launch has at least D items, so the ring prologue needs no conditions.
+// KG: K groups (see SkinnyParams); never together with FULL.
+// The body takes the workgroup's share of the problem as arguments (tiles tile0 + i * tstride, i < nmy; row
+// group by) so that the grouped launch below can run it on one problem of several.
+template <int P, int D, int EPT, bool RAW, bool FULL, bool KG, bool R16>
+__device__ __forceinline__ void skinny_body(const SkinnyParams& prm, const int tile0, const int tstride, const int nmy, const int by)
+{
+    static_assert(!(FULL && KG), "the K-group variant uses the conditional ring prologue");
+    using GI = GroupInfo<P>;
+    extern __shared__ __align__(16) uint8_t lds[];
+    WaveState<P> st;
+    st.tid = threadIdx.x; st.lane = st.tid & 63; st.wave = st.tid >> 6; st.S = blockDim.x >> 6;
+    st.m0 = by * prm.mrows;
+    const int mt = min(prm.mrows, prm.M - st.m0);
+    st.mt = mt;
+    const int r = st.lane & 15, G = st.lane >> 4;
+    st.nsuper = prm.nsuper;
+    st.tile0 = tile0; st.tstride = tstride;
+    st.p_ti = 0; st.p_lsc = 0; st.ti = 0; st.lsc = 0; st.parity = 0;
+#ifdef ABQ_PHASE_TRACE
+    unsigned long long ts[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    st.ts = ts;
+#endif
+    ABQ_TS(0);
+
+    st.nsw = prm.sc_q + (st.wave < prm.sc_r ? 1 : 0);                       // this wave's super-chunks per tile (>= 1)
+    st.nitems = nmy * st.nsw;
+    st.nmy = nmy;
+    st.g = 0; st.gs = 0; st.ge = KG ? group_bound(1, st.nsw, prm.kgroups) : st.nsw;
+    st.p_g = 0; st.p_gs = 0; st.p_ge = st.ge;
+
+    // ---- epilogue parameters: entry i < 16 is row m0+i of A, entry 16 + 16*t + c is channel c of this
+    // workgroup's t-th tile.  Loads use clamped indices so that none is conditional.
+    RowParams* par = reinterpret_cast<RowParams*>(lds + prm.par_off);
+    const int npar = 16 + nmy * 16;
+    auto load_par = [&](int i) -> RowParams {
+        if constexpr (RAW) {
+            const int m = min(st.m0 + min(i, 15), prm.M - 1);
+            const RowParams pa{0, prm.a_scale[m], prm.a_zero[m], 0};
+            const RowParams pw = prm.wparams[min((st.tile0 + (max(i - 16, 0) >> 4) * st.tstride) * kTileN + (i & 15), prm.N - 1)];
+            return i < 16 ? pa : pw;
+        } else {
+            const RowParams* src = i < 16 ? prm.aparams + min(st.m0 + i, prm.M - 1)
+                                          : prm.wparams + min((st.tile0 + ((i - 16) >> 4) * st.tstride) * kTileN + (i & 15), prm.N - 1);
+            return *src;   // one unconditional load
+        }
+    };
+    const RowParams par_first = load_par(min(st.tid, npar - 1));
+
+    // ---- this wave's part of A: columns of its own super-chunks, in every row (wave-private: only this
+    // wave reads what it writes, so no barrier is needed before the first MFMA).  A load instruction
+    // covers two super-chunks of one row (2 x 32 vectors of 16 B); a batch is four rows of that.
+    // RAW: unpacked codes with K a multiple of 16, so a 16-byte vector is either all inside the row or
+    // all padding.  Valid bytes become a - oa (a xor 0x80 when q = 8), padding becomes 0, and lane `row`
+    // keeps that row's partial sum over this wave's super-chunks.
+    const int half = st.lane >> 5, vec = st.lane & 31;
+    const uint8_t* a_base = RAW ? prm.a_raw + (size_t)st.m0 * prm.K : (const uint8_t*)prm.a_codes + (size_t)st.m0 * prm.Kp;
+    const int a_ld = RAW ? prm.K : prm.Kp;
+    const uint32_t flip = (RAW && prm.oa) ? 0x80808080u : 0u;
+    int32_t my_sum = 0;
+    // column of A in global memory / in LDS for slot pr + half of the run [st.gs, st.ge) being staged
+    auto batch_col = [&](int pr) { return (st.wave + (st.gs + min(pr + half, st.ge - st.gs - 1)) * st.S) * kSuperK + vec * 16; };
+    auto batch_lds_col = [&](int pr) {
+        if constexpr (!KG) return batch_col(pr);
+        else return st.wave * prm.col_w + min(pr + half, st.ge - st.gs - 1) * prm.col_s + vec * 16;
+    };
+    auto batch_load = [&](int pr, int row0, uint4* areg) {
+        const int col = batch_col(pr);
+        const int colc = RAW ? min(col, prm.K - 16) : col;
+#pragma unroll
+        for (int u = 0; u < 4; ++u)   // row0 itself is always a row of A; the others are skipped when past mt (wave-uniform)
+            if (u == 0 || row0 + u < mt) areg[u] = *reinterpret_cast<const uint4*>(a_base + (size_t)(row0 + u) * a_ld + colc);
+    };
+    auto batch_store = [&](int pr, int row0, const uint4* areg) {
+        const int col = batch_col(pr);
+        const int lcol = batch_lds_col(pr);
+        const bool lv = pr + half < st.ge - st.gs;
+        const bool inside = !RAW || col < prm.K;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (u > 0 && row0 + u >= mt) break;   // wave-uniform
+            uint4 v = areg[u];
+            if constexpr (RAW) {
+                {
+                    uint32_t part = 0;
+                    part = __builtin_amdgcn_udot4(v.x, 0x01010101u, part, false);
+                    part = __builtin_amdgcn_udot4(v.y, 0x01010101u, part, false);
+                    part = __builtin_amdgcn_udot4(v.z, 0x01010101u, part, false);
+                    part = __builtin_amdgcn_udot4(v.w, 0x01010101u, part, false);
+                    const int32_t tot = wave_sum((lv && inside) ? (int32_t)part : 0);
+                    if (st.lane == row0 + u) my_sum += tot;
+                }
+                v = inside ? uint4{v.x ^ flip, v.y ^ flip, v.z ^ flip, v.w ^ flip} : uint4{0, 0, 0, 0};
+            }
+            if (lv) *reinterpret_cast<uint4*>(lds + (row0 + u) * prm.a_stride + lcol) = v;
+        }
+    };
+    // The first batches (rows 0..7, or all 16 with R16, of the wave's first two super-chunks: all of A for
+    // K <= 1024 * S) are loaded in straight-line code ahead of the weight stream, so that waiting for
+    // them does not wait for the stream behind them.  (R16 is a variant of its own: the extra code costs
+    // the single-token launches 2 %.)
+    uint4 a0[4], a1[4], a2[4], a3[4];
+    batch_load(0, 0, a0);
+    const bool second = mt > 4, third = R16 && mt > 8, fourth = R16 && mt > 12;
+    if (second) batch_load(0, 4, a1);
+    if constexpr (R16) {
+        if (third) batch_load(0, 8, a2);
+        if (fourth) batch_load(0, 12, a3);
+    }
+    auto store_first = [&]() {
+        batch_store(0, 0, a0);
+        if (second) batch_store(0, 4, a1);
+        if constexpr (R16) {
+            if (third) batch_store(0, 8, a2);
+            if (fourth) batch_store(0, 12, a3);
+        }
+    };
+
+    // ---- the weight stream: first item = (tile0, super-chunk `wave`), then the rest of the ring
+    u4v w[D][P];
+    prefetch_item<P, KG>(prm, st, w[0]);
+    if constexpr (FULL) {
+        // every wave has at least D items: the whole ring is issued unconditionally, the number of
+        // loads behind A is known, and the wait for A is exact
+#pragma unroll
+        for (int d = 1; d < D; ++d) prefetch_item<P, KG>(prm, st, w[d]);
+        store_first();
+    } else {
+        // short streams: A is staged behind the first item only (again an exact wait), the rest of
+        // the ring follows
+        store_first();
+#pragma unroll
+        for (int d = 1; d < D; ++d)
+            if (d < st.nitems) prefetch_item<P, KG>(prm, st, w[d]);
+    }
+    // whatever is left of A (more than two super-chunks per wave); with K groups also
+    // every later run, staged over the columns of the run before it once that run's last tile is done
+    auto stage_rest = [&](int first_row0) {
+        for (int pr = 0; pr < st.ge - st.gs; pr += 2) {
+            for (int row0 = (pr == 0 ? first_row0 : 0); row0 < mt; row0 += 4) {
+                uint4 areg[4];
+                batch_load(pr, row0, areg);
+                batch_store(pr, row0, areg);
+            }
+        }
+        if constexpr (RAW) {
+            if (st.lane < 16) reinterpret_cast<int32_t*>(lds + prm.asum_off)[st.wave * 16 + st.lane] = my_sum;
+        }
+    };
+    stage_rest(R16 ? 16 : 8);
+    if (st.tid < npar) par[st.tid] = par_first;
+    for (int i = st.tid + blockDim.x; i < npar; i += blockDim.x) par[i] = load_par(i);
+    // MFMA rows past mt read a 512-byte block of zeros instead of A (every wave writes the same zeros,
+    // so this needs no barrier either)
+    if (st.lane < 32) *reinterpret_cast<uint4*>(lds + prm.zero_off + st.lane * 16) = uint4{0, 0, 0, 0};
+    // same-wave LDS accesses execute in order; keep the compiler from moving the operand reads above
+    // the staging writes (the parameters are read only after the first per-tile barrier)
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    ABQ_TS(1);
+#ifdef ABQ_PHASE_TRACE
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    ABQ_TS(2);
+#endif
+
+    st.lds_lane = (r < mt ? lds + r * prm.a_stride : lds + prm.zero_off) + G * 16;
+    st.k_mask = r < mt ? ~0 : 0;
+    st.par = par;
+    st.red = reinterpret_cast<int32_t*>(lds + prm.red_off);
+    st.asum = reinterpret_cast<const int32_t*>(lds + prm.asum_off);
+    st.part = reinterpret_cast<int32_t*>(lds + prm.part_off) + st.wave * prm.nmy_max * 256;
+    auto next_group = [&]() {
+        stage_rest(0);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    };
+#pragma unroll
+    for (int i = 0; i < GI::NACC; ++i) st.acc[i] = v4i{0, 0, 0, 0};
+
+    int it = 0;
+    if (!KG && nmy == 1) {
+        // One tile per workgroup (the usual case): the K loop holds loads only, so the compiler's
+        // waits are exact and P*(D-1) loads stay in flight; the tile is finished after the loop.
+        for (; it + 2 * D <= st.nitems; it += D) {
+#pragma unroll
+            for (int d = 0; d < D; ++d) {
+                compute_super<P>(w[d], st.lds_lane + (((st.wave + st.lsc * st.S) * kSuperK) & st.k_mask), st.acc);
+                prefetch_item<P>(prm, st, w[d]);
+                ++st.lsc;
+            }
+        }
+        for (; it < st.nitems; it += D) {
+#pragma unroll
+            for (int d = 0; d < D; ++d)
+                if (it + d < st.nitems) {
+                    compute_super<P>(w[d], st.lds_lane + (((st.wave + st.lsc * st.S) * kSuperK) & st.k_mask), st.acc);
+                    if (it + d + D < st.nitems) prefetch_item<P>(prm, st, w[d]);
+                    ++st.lsc;
+                }
+        }
+        finish_tile<P, EPT, RAW>(prm, st);
+    } else {
+        // Several tiles per workgroup: the ring runs ahead across tile boundaries.
+        for (; it + 2 * D <= st.nitems; it += D) {
+#pragma unroll
+            for (int d = 0; d < D; ++d) item_step<P, EPT, RAW, KG, true>(prm, st, w[d], true, next_group);
+        }
+        for (; it < st.nitems; it += D) {
+#pragma unroll
+            for (int d = 0; d < D; ++d)
+                if (it + d < st.nitems) item_step<P, EPT, RAW, KG, false>(prm, st, w[d], it + d + D < st.nitems, next_group);
+        }
+    }
+#ifdef ABQ_PHASE_TRACE
+    ABQ_TS(6);
+    if (st.lane == 0 && blockIdx.x < 1024 && st.wave < 8)
+        for (int i = 0; i < 8; ++i) g_phase_trace[((size_t)blockIdx.x * 8 + st.wave) * 8 + i] = ts[i];
+#endif
+}
+
+template <int P, int D, int EPT, bool RAW, bool FULL, bool KG, bool R16>
+__global__ __launch_bounds__(512) void skinny_kernel(SkinnyParams prm)
+{
+    // workgroup b owns tl_q + (b < tl_r) tiles: b, b + gridDim.x, ...
+    skinny_body<P, D, EPT, RAW, FULL, KG, R16>(prm, (int)blockIdx.x, (int)gridDim.x, prm.tl_q + ((int)blockIdx.x < prm.tl_r ? 1 : 0),
+                                          (int)blockIdx.y);
+}
+
+// Grouped decode launch: up to kMaxGroup independent problems (same p, q and M <= 16; own A, W, Y, N, K)
+// in ONE launch.  The 16-row tiles of all problems form one list (problem after problem); a resident set
+// of workgroups cuts it into equal contiguous runs, and a workgroup streams its run problem by problem
+// with the load ring running across the tiles of a problem (a run mostly lies inside one problem; where
+// it crosses into the next, the workgroup drains, stages that problem's rows of A and goes on).
+// Microsecond-sized matmuls then share one launch ramp and tail instead of paying one each (Sec. 3.4:
+// the engine replaces all the linear layers of a decoder block).  Descriptors are read from the kernel
+// arguments.
+constexpr int kMaxGroup = 8;
+struct GroupedParams {
+    int count;
+    int run_q, run_r;                 // workgroup b owns run_q + (b < run_r) tiles of the list
+    int first_tile[kMaxGroup + 1];    // where each problem's tiles start in the list
+    SkinnyParams d[kMaxGroup];
+};
+
+template <int P, int D, int EPT, bool RAW>
+__global__ __launch_bounds__(512) void grouped_kernel(GroupedParams gp)
+{
+    const int b = (int)blockIdx.x;
+    const int t0 = b * gp.run_q + min(b, gp.run_r);
+    const int t1 = t0 + gp.run_q + (b < gp.run_r ? 1 : 0);
+    bool first = true;
+#pragma nounroll
+    for (int g = 0; g < gp.count; ++g) {
+        const int lo = max(t0, gp.first_tile[g]), hi = min(t1, gp.first_tile[g + 1]);
+        if (lo >= hi) continue;   // the same for the whole workgroup
+        if (!first) __syncthreads();   // every wave is done with the LDS contents of the problem before
+        first = false;
+        skinny_body<P, D, EPT, RAW, false, false, (EPT == 1)>(gp.d[g], lo - gp.first_tile[g], 1, hi - lo, 0);
+    }
+}
+
+template <int P, int D, int EPT, bool RAW, bool FULL, bool KG, bool R16>
+static hipError_t launch_variant_r(const SkinnyParams& prm, dim3 grid, int waves, size_t lds_bytes, hipStream_t s)
+{
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)skinny_kernel<P, D, EPT, RAW, FULL, KG, R16>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    skinny_kernel<P, D, EPT, RAW, FULL, KG, R16><<<grid, waves * 64, lds_bytes, s>>>(prm);
+    return hipGetLastError();
+}
+
+// More than 8 rows of A per workgroup (only with four or more waves): the variant that loads all 16 rows ahead of the ring.
+template <int P, int D, int EPT, bool RAW, bool FULL, bool KG>
+static hipError_t launch_variant(const SkinnyParams& prm, dim3 grid, int waves, size_t lds_bytes, hipStream_t s)
+{
+    if constexpr (EPT == 1) {
+        if (prm.mrows > 8) return launch_variant_r<P, D, EPT, RAW, FULL, KG, true>(prm, grid, waves, lds_bytes, s);
+    }
+    return launch_variant_r<P, D, EPT, RAW, FULL, KG, false>(prm, grid, waves, lds_bytes, s);
+}
+
+template <int P, int D, int EPT>
+static hipError_t launch_pde(const SkinnyParams& prm, dim3 grid, int waves, size_t lds_bytes, hipStream_t s)
+{
+    if constexpr (EPT == 1) {   // K groups come with long K, hence with at least four waves
+        if (prm.kgroups > 1)
+            return prm.a_raw ? launch_variant<P, D, EPT, true, false, true>(prm, grid, waves, lds_bytes, s)
+                             : launch_variant<P, D, EPT, false, false, true>(prm, grid, waves, lds_bytes, s);
+    }
+    if (prm.kgroups > 1) return hipErrorInvalidValue;
+    const bool full = prm.tl_q * prm.sc_q >= D;   // the fewest items any wave has
+    if (prm.a_raw)
+        return full ? launch_variant<P, D, EPT, true, true, false>(prm, grid, waves, lds_bytes, s)
+                    : launch_variant<P, D, EPT, true, false, false>(prm, grid, waves, lds_bytes, s);
+    return full ? launch_variant<P, D, EPT, false, true, false>(prm, grid, waves, lds_bytes, s)
+                : launch_variant<P, D, EPT, false, false, false>(prm, grid, waves, lds_bytes, s);
+}
+
+template <int P, int D>
+static hipError_t launch_pd(const SkinnyParams& prm, dim3 grid, int waves, size_t lds_bytes, hipStream_t s)
+{
+    if (waves >= 4) return launch_pde<P, D, 1>(prm, grid, waves, lds_bytes, s);
+    if (waves == 2) return launch_pde<P, D, 2>(prm, grid, waves, lds_bytes, s);
+    return launch_pde<P, D, 4>(prm, grid, waves, lds_bytes, s);
+}
+
+// Operand pointers and shape fields of the kernel arguments (everything but the launch plan).
+template <int P, int D>
+static hipError_t launch_grouped_pd(const GroupedParams& gp, bool raw, unsigned grid, int waves, size_t lds_bytes, hipStream_t s)
+{
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)grouped_kernel<P, D, 1, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)grouped_kernel<P, D, 1, false>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)grouped_kernel<P, D, 2, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)grouped_kernel<P, D, 2, false>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    if (waves >= 4) {
+        if (raw) grouped_kernel<P, D, 1, true><<<grid, waves * 64, lds_bytes, s>>>(gp);
+        else grouped_kernel<P, D, 1, false><<<grid, waves * 64, lds_bytes, s>>>(gp);
+    } else if (waves == 2) {
+        if (raw) grouped_kernel<P, D, 2, true><<<grid, waves * 64, lds_bytes, s>>>(gp);
+        else grouped_kernel<P, D, 2, false><<<grid, waves * 64, lds_bytes, s>>>(gp);
+    } else {
+        return hipErrorInvalidValue;   // (the plan never asks for one or three waves)
+    }
+    return hipGetLastError();
+}
+
+// Callers check gemm_grouped_fits first; count may exceed kMaxGroup (then several launches follow each other).
+// Entry points of the per-width translation units (P_LO..P_HI each).
+hipError_t skinny_launch_p12(int p, const SkinnyParams& prm, dim3 grid, int waves, size_t lds_bytes, hipStream_t s);
+hipError_t skinny_launch_p34(int p, const SkinnyParams& prm, dim3 grid, int waves, size_t lds_bytes, hipStream_t s);
+hipError_t skinny_launch_p56(int p, const SkinnyParams& prm, dim3 grid, int waves, size_t lds_bytes, hipStream_t s);
+hipError_t skinny_launch_p78(int p, const SkinnyParams& prm, dim3 grid, int waves, size_t lds_bytes, hipStream_t s);
+hipError_t grouped_launch_p12(int p, const GroupedParams& gp, bool raw, unsigned grid, int waves, size_t lds_bytes, hipStream_t s);
+hipError_t grouped_launch_p34(int p, const GroupedParams& gp, bool raw, unsigned grid, int waves, size_t lds_bytes, hipStream_t s);
+hipError_t grouped_launch_p56(int p, const GroupedParams& gp, bool raw, unsigned grid, int waves, size_t lds_bytes, hipStream_t s);
+hipError_t grouped_launch_p78(int p, const GroupedParams& gp, bool raw, unsigned grid, int waves, size_t lds_bytes, hipStream_t s);
+
+}  // namespace abq
