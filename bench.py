@@ -113,6 +113,9 @@ def measured_peaks(pool, workload_bytes, launches=200):
     return out
 
 
+# HBM bytes per abq_gemm_grouped launch over BLOCK_7B, measured the same way (profiles/grouped_kernel_*), by (p, q, M).
+MEASURED_GROUPED_TRAFFIC_BYTES = {(4, 8, 1): 103087465, (8, 8, 1): 204660282}
+
 # The seven linear layers of one LLaMA-7B decoder block as (name, N, K): the shapes the paper's engine
 # replaces in a block (Sec. 3.4; Appendix D measures these layer shapes one by one).
 BLOCK_7B = [("q_proj", 4096, 4096), ("k_proj", 4096, 4096), ("v_proj", 4096, 4096), ("o_proj", 4096, 4096),
@@ -204,7 +207,8 @@ def bench_grouped(p, q, M, steps, warmup, rotate_gib, check=True):
     return {"workload": f"LLaMA-7B decoder block, 7 linear layers, W{p}A{q} M={M}, one abq_gemm_grouped launch",
             "us_per_block": t * 1e6, "tops": ops / t / 1e12, "weight_gbs": wbytes / t / 1e9,
             "roofline": {"bound": "hbm", "achieved": alg / t / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                         "frac": alg / t / 1e9 / HBM_PEAK_GBS, "traffic": None, "algorithmic_bytes": alg,
+                         "frac": alg / t / 1e9 / HBM_PEAK_GBS, "traffic": MEASURED_GROUPED_TRAFFIC_BYTES.get((p, q, M)),
+                         "algorithmic_bytes": alg,
                          "kernel": "abq_gemm_grouped", "launches": steps},
             "seven_single_launches_us": times["single"] * 1e6, "rotating_weight_sets": R, "rotating_bytes": R * set_bytes,
             "steps": steps}

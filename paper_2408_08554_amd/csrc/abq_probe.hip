@@ -64,12 +64,21 @@ int abq_probe_stream_read(const void* buf, size_t bytes, void* sink, void* strea
     if (!buf || !sink) return ABQ_ERR_NULL;
     if (bytes < 16 || bytes % 16 != 0) return ABQ_ERR_SHAPE;
     if (((uintptr_t)buf & 15u) || ((uintptr_t)sink & 15u)) return ABQ_ERR_ALIGN;
-    constexpr int U = 8, threads = 512;
+    // 256 threads; the most loads per thread (8, 4, 2, 1) that still leaves four workgroups per CU
+    constexpr int threads = 256;
     const size_t nvec = bytes / 16;
+    int U = 8;
+    while (U > 1 && nvec / ((size_t)threads * U) < 1024) U >>= 1;
     const size_t per_wg = (size_t)threads * U;
     const size_t grid = (nvec + per_wg - 1) / per_wg;
     if (grid > 0x7fffffffu) return ABQ_ERR_SHAPE;
-    stream_read_kernel<U><<<(unsigned)grid, threads, 0, (hipStream_t)stream>>>((const u4v*)buf, nvec, (uint32_t*)sink);
+    hipStream_t s = (hipStream_t)stream;
+    switch (U) {
+        case 8: stream_read_kernel<8><<<(unsigned)grid, threads, 0, s>>>((const u4v*)buf, nvec, (uint32_t*)sink); break;
+        case 4: stream_read_kernel<4><<<(unsigned)grid, threads, 0, s>>>((const u4v*)buf, nvec, (uint32_t*)sink); break;
+        case 2: stream_read_kernel<2><<<(unsigned)grid, threads, 0, s>>>((const u4v*)buf, nvec, (uint32_t*)sink); break;
+        default: stream_read_kernel<1><<<(unsigned)grid, threads, 0, s>>>((const u4v*)buf, nvec, (uint32_t*)sink); break;
+    }
     return hipGetLastError() == hipSuccess ? ABQ_OK : ABQ_ERR_HIP;
 }
 
