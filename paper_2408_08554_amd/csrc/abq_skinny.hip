@@ -235,6 +235,45 @@ static int group_workgroups(int tiles, int M, int cus)
 
 static size_t group_par_bytes(int run_max) { return (size_t)(16 + 16 * run_max) * sizeof(RowParams) + kAsumBytes; }
 
+// Fills the tile list and the work-balanced partition of problems first .. first+n-1 and picks the workgroup
+// count; returns the most tiles any workgroup's run holds.
+static int group_partition(GroupedParams& gp, int first, int n, int M, const ActLayout* A, const WeightLayout* W, int cus, int* wgs_out)
+{
+    gp.count = n;
+    int tiles = 0;
+    double cost = 0;
+    // Measured on the LLaMA-7B block (same box, A/B): with many small workgroups per CU (M <= 4) equal tile
+    // counts, the longer runs first, beat every equal-work cut by 3-8 %; with one eight-wave workgroup per CU
+    // (M > 4) equal work (super-chunks + a fixed cost of 16 per tile) is 10 % faster than equal counts.
+    // Tuning override, read once: ABQ_GROUP_TILE_COST=<fixed cost> forces the equal-work cut with that cost.
+    static int overhead = -1;
+    if (overhead < 0) { const char* e = getenv("ABQ_GROUP_TILE_COST"); overhead = e ? atoi(e) : 0; }
+    gp.by_work = (overhead > 0 || M > 4) ? 1 : 0;
+    for (int i = 0; i < kMaxGroup; ++i) {
+        const int src = first + (i < n ? i : 0);
+        const int tile_cost = A[src].Kp / kSuperK + (overhead > 0 ? overhead : kTileOverheadCost);
+        gp.first_tile[i] = tiles;
+        gp.cost_first[i] = (float)cost;
+        gp.inv_tile_cost[i] = 1.0f / (float)tile_cost;
+        if (i < n) { tiles += W[src].NT; cost += (double)W[src].NT * tile_cost; }
+    }
+    gp.first_tile[kMaxGroup] = tiles;
+    gp.cost_first[kMaxGroup] = (float)cost;
+    int wgs = group_workgroups(tiles, M, cus);
+    for (;;) {
+        gp.cost_per_wg = (float)(cost / wgs);
+        gp.run_q = tiles / wgs; gp.run_r = tiles % wgs;
+        int run_max = 0, prev = grouped_run_start(gp, 0, wgs);
+        for (int b = 1; b <= wgs; ++b) {
+            const int next = grouped_run_start(gp, b, wgs);
+            if (next - prev > run_max) run_max = next - prev;
+            prev = next;
+        }
+        if (run_max <= kMaxRun || wgs >= tiles) { *wgs_out = wgs; return run_max + 1; }   // (+1: margin for the parameter area)
+        wgs = wgs * 2 < tiles ? wgs * 2 : tiles;
+    }
+}
+
 // One launch serves a group when every problem can run as "S waves per tile, all of A staged at once":
 // M <= 16, every K spans at least four super-chunks (and at least S of them: S is the same for all), the
 // rows of A fit LDS, field-packed weights, and for unpacked codes K a multiple of 16.
@@ -256,10 +295,10 @@ bool gemm_grouped_fits(int M, int count, const GemmArgs* probs, const ActLayout*
     size_t lds = 0;
     for (int first = 0; first < count; first += kMaxGroup) {
         const int n = count - first < kMaxGroup ? count - first : kMaxGroup;
-        int tiles = 0;
-        for (int i = first; i < first + n; ++i) tiles += W[i].NT;
-        const int gx = group_workgroups(tiles, M, cus);
-        const int run_max = (tiles + gx - 1) / gx;
+        GroupedParams gp;
+        int gx = 0;
+        const int run_max = group_partition(gp, first, n, M, A, W, cus, &gx);
+        if (run_max > kMaxRun + 1) return false;
         for (int i = first; i < first + n; ++i) {
             const size_t need = align_up((size_t)M * ((size_t)A[i].Kp + 16), 16) + group_par_bytes(run_max) + 2 * (size_t)S * 1024;
             if (need > kLdsPerCu) return false;
@@ -277,13 +316,8 @@ hipError_t launch_gemm_grouped(int p, int M, int count, const GemmArgs* probs, c
     for (int first = 0; first < count; first += kMaxGroup) {
         const int n = count - first < kMaxGroup ? count - first : kMaxGroup;
         GroupedParams gp;
-        gp.count = n;
-        int tiles = 0;
-        for (int i = first; i < first + n; ++i) tiles += W[i].NT;
-        const int wgs = group_workgroups(tiles, M, num_cus());
-        const int run_max = (tiles + wgs - 1) / wgs;
-        gp.run_q = tiles / wgs; gp.run_r = tiles % wgs;
-        tiles = 0;
+        int wgs = 0;
+        const int run_max = group_partition(gp, first, n, M, A, W, num_cus(), &wgs);
         for (int i = 0; i < kMaxGroup; ++i) {
             const int src = first + (i < n ? i : 0);   // unused slots repeat a valid descriptor
             SkinnyParams& prm = gp.d[i];
@@ -303,10 +337,7 @@ hipError_t launch_gemm_grouped(int p, int M, int count, const GemmArgs* probs, c
             prm.nsuper = nsuper;
             prm.sc_q = nsuper / waves; prm.sc_r = nsuper % waves;
             prm.tl_q = 0; prm.tl_r = 0;   // (not used: the kernel hands each workgroup its run)
-            gp.first_tile[i] = tiles;
-            if (i < n) tiles += W[src].NT;
         }
-        gp.first_tile[kMaxGroup] = tiles;
         hipError_t e;
         const bool raw = probs[first].a_raw != nullptr;
         if (p <= 2) e = grouped_launch_p12(p, gp, raw, (unsigned)wgs, waves, lds_bytes, s);

@@ -579,19 +579,50 @@ __global__ __launch_bounds__(512) void skinny_kernel(SkinnyParams prm)
 // the engine replaces all the linear layers of a decoder block).  Descriptors are read from the kernel
 // arguments.
 constexpr int kMaxGroup = 8;
+constexpr int kTileOverheadCost = 16;  // fixed work per tile (sum over waves, epilogue), in units of one super-chunk
 struct GroupedParams {
     int count;
-    int run_q, run_r;                 // workgroup b owns run_q + (b < run_r) tiles of the list
     int first_tile[kMaxGroup + 1];    // where each problem's tiles start in the list
+    // Two ways to cut the list into runs, as the host chooses.  by_work = 0: equal tile counts, workgroup b
+    // owning run_q + (b < run_r) tiles.  by_work = 1: equal work; a tile of problem g costs its super-chunks +
+    // a fixed overhead (a tile of a long-K problem is several tiles' worth of a short-K one), cost_first[g] is
+    // the cost of all tiles before problem g, and workgroup b starts at the first tile whose preceding cost
+    // reaches b * cost_per_wg.  Single precision is enough: neighbours evaluate the same expression for
+    // their common boundary, so the runs tile the list whatever the rounding.
+    int by_work, run_q, run_r;
+    float cost_per_wg;
+    float inv_tile_cost[kMaxGroup];
+    float cost_first[kMaxGroup + 1];
     SkinnyParams d[kMaxGroup];
 };
+
+// Index in the tile list where the run of workgroup b (of n) starts; b = n gives the end of the list.
+// (Select chains over constant indices instead of indexing by the problem found: the kernel arguments are
+// then fetched with a few wide scalar loads up front rather than one dependent load after another.)
+__host__ __device__ inline int grouped_run_start(const GroupedParams& gp, int b, int n)
+{
+    if (!gp.by_work) return b * gp.run_q + (b < gp.run_r ? b : gp.run_r);
+    const float target = (float)b * gp.cost_per_wg;
+    float cf = gp.cost_first[0], inv = gp.inv_tile_cost[0];
+    int ft = gp.first_tile[0], ft_next = gp.first_tile[1];
+#pragma unroll
+    for (int i = 1; i < kMaxGroup; ++i) {
+        const bool in = i < gp.count && target >= gp.cost_first[i];
+        cf = in ? gp.cost_first[i] : cf;
+        inv = in ? gp.inv_tile_cost[i] : inv;
+        ft = in ? gp.first_tile[i] : ft;
+        ft_next = in ? gp.first_tile[i + 1] : ft_next;
+    }
+    const int within = (int)ceilf((target - cf) * inv);
+    const int start = ft + (within < ft_next - ft ? within : ft_next - ft);
+    return b >= n ? gp.first_tile[kMaxGroup] : start;
+}
 
 template <int P, int D, int EPT, bool RAW>
 __global__ __launch_bounds__(512) void grouped_kernel(GroupedParams gp)
 {
     const int b = (int)blockIdx.x;
-    const int t0 = b * gp.run_q + min(b, gp.run_r);
-    const int t1 = t0 + gp.run_q + (b < gp.run_r ? 1 : 0);
+    const int t0 = grouped_run_start(gp, b, (int)gridDim.x), t1 = grouped_run_start(gp, b + 1, (int)gridDim.x);
     bool first = true;
 #pragma nounroll
     for (int g = 0; g < gp.count; ++g) {
