@@ -148,8 +148,12 @@ __device__ __forceinline__ void load_tiles(const TiledParams& prm, int tile0, in
 
 // Up to two 16-row tiles of W per wave the kernel is held to 256 registers, so that two workgroups
 // share a CU and each hides the other's waits; the four-tile shape takes the whole register file.
-template <int P, int NTW, int MT>
-__global__ __launch_bounds__(256, (NTW <= 2 ? (MT == 4 ? 3 : 2) : (MT == 4 ? 2 : 1))) void tiled_kernel(TiledParams prm)
+// WD = steps of operands in flight per wave: 2 (the next step is fetched while the current one is multiplied)
+// or 4 (weights and rows of A three steps ahead, both through registers: for the small tile shapes on
+// problems with few workgroups, where a step's MFMAs are much shorter than a load's latency and the K loop
+// would otherwise advance one load latency per step).
+template <int P, int NTW, int MT, int WD>
+__global__ __launch_bounds__(256, (WD == 4 ? 2 : (NTW <= 2 ? (MT == 4 ? 3 : 2) : (MT == 4 ? 2 : 1)))) void tiled_kernel(TiledParams prm)
 {
     constexpr int kBM = MT * 16, kBN = 4 * NTW * kTileN;
     __shared__ __align__(16) uint8_t lds_a0[kBM * kARow];   // two separate objects: the loads that fill one must
@@ -169,9 +173,19 @@ __global__ __launch_bounds__(256, (NTW <= 2 ? (MT == 4 ? 3 : 2) : (MT == 4 ? 2 :
     const int m0 = m_blk * kBM, n0 = n_blk * kBN;
     const int tile0 = n_blk * (kBN / kTileN) + wave * NTW;
 
-    // weights of the first phase
+    // weights of the first phase (WD = 2) or the first three (WD = 4)
     u4v wa[NTW][phase_regs(P)], wb[NTW][phase_regs(P)];
+    u4v wc[WD == 4 ? NTW : 1][phase_regs(P)], wd[WD == 4 ? NTW : 1][phase_regs(P)];
+    const int nsteps = prm.nsuper * 2;
+    auto load_phase = [&](int j, u4v (*w)[phase_regs(P)]) {   // phase j of the K loop, clamped to the last one
+        const int jc = min(j, nsteps - 1);
+        load_tiles<P, NTW>(prm, tile0, jc >> 1, jc & 1, lane, w);
+    };
     load_tiles<P, NTW>(prm, tile0, 0, 0, lane, wa);
+    if constexpr (WD == 4) {
+        load_phase(1, wb);
+        load_phase(2, wc);
+    }
 
     // epilogue parameters
     if (tid < kBM) par_a[tid] = prm.aparams[min(m0 + tid, prm.M - 1)];
@@ -206,7 +220,45 @@ __global__ __launch_bounds__(256, (NTW <= 2 ? (MT == 4 ? 3 : 2) : (MT == 4 ? 2 :
     a_prefetch(0, lds_a0);
     __syncthreads();   // (the compiler waits for the direct loads before the barrier)
 
-    const int nsteps = prm.nsuper * 2;
+    if constexpr (WD == 4) {
+        // two super-chunks per iteration, four steps; in every step the A tile of the next step is requested
+        // first and the weights of the step three ahead after it, so that the wait for A before the barrier
+        // leaves those weights in flight
+        // Here the A tiles travel through registers (global -> VGPR three steps ahead, VGPR -> LDS after the
+        // MFMAs of the step before their own) instead of straight into LDS: the compiler waits for direct loads
+        // with vmcnt(0) before a barrier, which would drain the rings every step, whereas for register loads
+        // its wait counts are exact and leave the younger loads in flight.
+        u4v ar0[MT], ar1[MT], ar2[MT], ar3[MT];
+#define ABQ_A_LOAD(STEP, AR)                                                                       \
+        {                                                                                          \
+            const int8_t* a_src = a_tile + (size_t)min((STEP), nsteps - 1) * kStepK;               \
+            _Pragma("unroll") for (int u = 0; u < MT; ++u)                                         \
+                AR[u] = *reinterpret_cast<const u4v*>(a_src + a_goff[u]);                          \
+        }
+        ABQ_A_LOAD(1, ar1)
+        ABQ_A_LOAD(2, ar2)
+#define ABQ_STEP(J, W_NEXT, W_CUR, PH, BUF_CUR, BUF_NEXT, AR_LOAD, AR_STORE)                   \
+        {                                                                                          \
+            ABQ_A_LOAD((J) + 3, AR_LOAD)                                                           \
+            load_phase((J) + 3, W_NEXT);                                                           \
+            __builtin_amdgcn_sched_barrier(0);                                                     \
+            step_mfma<P, NTW, MT, PH>(W_CUR, BUF_CUR, r, G, acc);                                  \
+            _Pragma("unroll") for (int u = 0; u < MT; ++u)                                         \
+                *reinterpret_cast<u4v*>(BUF_NEXT + (wave * MT + u) * 1024 + lane * 16) = AR_STORE[u]; \
+            __syncthreads();                                                                       \
+        }
+        for (int sc = 0; sc < prm.nsuper; sc += 2) {
+            const int j = 2 * sc;
+            ABQ_STEP(j, wd, wa, 0, lds_a0, lds_a1, ar3, ar1)
+            ABQ_STEP(j + 1, wa, wb, 1, lds_a1, lds_a0, ar0, ar2)
+            if (sc + 1 < prm.nsuper) {   // (the same for every thread)
+                ABQ_STEP(j + 2, wb, wc, 0, lds_a0, lds_a1, ar1, ar3)
+                ABQ_STEP(j + 3, wc, wd, 1, lds_a1, lds_a0, ar2, ar0)
+            }
+        }
+#undef ABQ_STEP
+#undef ABQ_A_LOAD
+    } else
     // one super-chunk per iteration: two steps (= phases) of four 64-k slices; the weights and the A
     // tile of the next step are fetched while the current one is multiplied.  Loads past the end are
     // clamped to the last step instead of being skipped, so that every load in the loop is unconditional.
@@ -279,23 +331,37 @@ __global__ __launch_bounds__(256, (NTW <= 2 ? (MT == 4 ? 3 : 2) : (MT == 4 ? 2 :
 }
 
 template <int P, int NTW, int MT>
-static hipError_t launch_shape(const TiledParams& prm, dim3 grid, hipStream_t s)
+static hipError_t launch_shape(const TiledParams& prm, dim3 grid, int cus, hipStream_t s)
 {
-    tiled_kernel<P, NTW, MT><<<grid, 256, 0, s>>>(prm);
+    // The deep rings exist for the small tile shapes (for two tiles of W per wave only up to p = 6: beyond, the
+    // registers run out) and run two workgroups per CU instead of three.  Measured: with at most one workgroup
+    // per CU (M = 64..128 on a 4096-wide layer) they are 20 % faster, with more workgroups (M = 128 on an
+    // 11008-wide layer and up) the traffic through L2, not the latency of a step, is the bound and they lose.
+    // Tuning override, read once: ABQ_TILED_WD=<2|4>.
+    constexpr bool has_deep = MT == 4 && (NTW == 1 || (NTW == 2 && P <= 6));
+    static int forced = -1;
+    if (forced < 0) { const char* e = getenv("ABQ_TILED_WD"); forced = e ? atoi(e) : 0; }
+    if constexpr (has_deep) {
+        if (forced == 4 || (forced != 2 && (long)grid.x <= (long)cus)) {
+            tiled_kernel<P, NTW, MT, 4><<<grid, 256, 0, s>>>(prm);
+            return hipGetLastError();
+        }
+    }
+    tiled_kernel<P, NTW, MT, 2><<<grid, 256, 0, s>>>(prm);
     return hipGetLastError();
 }
 
 template <int P>
-static hipError_t launch_p(const TiledParams& prm, int ntw, int mt, dim3 grid, hipStream_t s)
+static hipError_t launch_p(const TiledParams& prm, int ntw, int mt, dim3 grid, int cus, hipStream_t s)
 {
     if (mt == 4) {
-        if (ntw == 1) return launch_shape<P, 1, 4>(prm, grid, s);
-        if (ntw == 2) return launch_shape<P, 2, 4>(prm, grid, s);
-        return launch_shape<P, 4, 4>(prm, grid, s);
+        if (ntw == 1) return launch_shape<P, 1, 4>(prm, grid, cus, s);
+        if (ntw == 2) return launch_shape<P, 2, 4>(prm, grid, cus, s);
+        return launch_shape<P, 4, 4>(prm, grid, cus, s);
     }
-    if (ntw == 1) return launch_shape<P, 1, 8>(prm, grid, s);
-    if (ntw == 2) return launch_shape<P, 2, 8>(prm, grid, s);
-    return launch_shape<P, 4, 8>(prm, grid, s);
+    if (ntw == 1) return launch_shape<P, 1, 8>(prm, grid, cus, s);
+    if (ntw == 2) return launch_shape<P, 2, 8>(prm, grid, cus, s);
+    return launch_shape<P, 4, 8>(prm, grid, cus, s);
 }
 
 hipError_t launch_gemm_tiled(const GemmArgs& g, const ActLayout& A, const WeightLayout& W, hipStream_t s)
@@ -331,14 +397,14 @@ hipError_t launch_gemm_tiled(const GemmArgs& g, const ActLayout& A, const Weight
     prm.tiles_n = (g.N + 64 * ntw - 1) / (64 * ntw);
     dim3 grid((unsigned)(prm.tiles_m * prm.tiles_n));
     switch (g.p) {
-        case 1: return launch_p<1>(prm, ntw, mt, grid, s);
-        case 2: return launch_p<2>(prm, ntw, mt, grid, s);
-        case 3: return launch_p<3>(prm, ntw, mt, grid, s);
-        case 4: return launch_p<4>(prm, ntw, mt, grid, s);
-        case 5: return launch_p<5>(prm, ntw, mt, grid, s);
-        case 6: return launch_p<6>(prm, ntw, mt, grid, s);
-        case 7: return launch_p<7>(prm, ntw, mt, grid, s);
-        default: return launch_p<8>(prm, ntw, mt, grid, s);
+        case 1: return launch_p<1>(prm, ntw, mt, grid, cus, s);
+        case 2: return launch_p<2>(prm, ntw, mt, grid, cus, s);
+        case 3: return launch_p<3>(prm, ntw, mt, grid, cus, s);
+        case 4: return launch_p<4>(prm, ntw, mt, grid, cus, s);
+        case 5: return launch_p<5>(prm, ntw, mt, grid, cus, s);
+        case 6: return launch_p<6>(prm, ntw, mt, grid, cus, s);
+        case 7: return launch_p<7>(prm, ntw, mt, grid, cus, s);
+        default: return launch_p<8>(prm, ntw, mt, grid, cus, s);
     }
 }
 

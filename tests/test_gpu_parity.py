@@ -94,7 +94,8 @@ def test_shapes(abq, layout, M, N, K, p, q):
     check_against_oracle(c, y, acc)
 
 
-TILED_SHAPES = [(65, 40, 700), (128, 128, 512), (200, 150, 1100), (129, 257, 64), (300, 16, 2048), (257, 130, 1536)]
+TILED_SHAPES = [(65, 40, 700), (128, 128, 512), (200, 150, 1100), (129, 257, 64), (300, 16, 2048), (257, 130, 1536),
+                (128, 4096, 4096), (96, 300, 5632), (512, 11008, 1024), (70, 129, 3584)]
 
 
 @pytest.mark.parametrize("M,N,K", TILED_SHAPES)
@@ -103,7 +104,10 @@ def test_prefill_shapes(abq, M, N, K, p, q):
     say("prefill shape", M, N, K, p, q)
     c = synth.make_case(p, q, M, N, K, seed=synth.case_seed(7, p, q) + M + N + K, name=f"W{p}A{q} {M}x{N}x{K}")
     y, acc = gpu_gemm(torch, abq, c, FIELDS, FIELDS)
-    check_against_oracle(c, y, acc)
+    if M * N * K <= 1 << 28:
+        check_against_oracle(c, y, acc)
+    else:
+        check_sampled(c, y, acc)
 
 
 def test_prefill_bitserial(abq):
