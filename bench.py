@@ -30,9 +30,9 @@ INT8_MFMA_PEAK_TOPS = 5000.0    # MI355X published dense int8
 # scaled by what the same counter reads for a plain copy of known size in the same run (FETCH_SIZE
 # reads 0.5015x on this chip, WRITE_SIZE 1.000x); figures and commands are in profiles/.
 MEASURED_TRAFFIC_BYTES = {
-    "C2 W4A8 GEMV 4096x4096": int((4229.5 * 8256.25 / 4140.9 + 8.0) * 1024),
-    "C3 W2A8 GEMV M=1 11008->4096": int((5825.5 * 11328.25 / 5677.2 + 8.0) * 1024),
-    "C5 W8A8 M=1 K=5120 N=13824": int((34781.6 * 69336.2 / 34684.1 + 27.0) * 1024),
+    "C2 W4A8 GEMV 4096x4096": int((4232.0 * 8256.25 / 4140.9 + 8.0) * 1024),
+    "C3 W2A8 GEMV M=1 11008->4096": int((5821.5 * 11328.25 / 5677.3 + 8.0) * 1024),
+    "C5 W8A8 M=1 K=5120 N=13824": int((34785.6 * 69336.2 / 34687.3 + 27.0) * 1024),
 }
 
 
