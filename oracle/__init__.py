@@ -174,3 +174,18 @@ def quant_act(x_half, q):
     zp = np.empty(M, dtype=np.int32)
     _load().abq_oracle_quant_act(q, M, K, _p(x_half.view(np.uint16)), _p(codes), _p(sc), _p(zp))
     return codes, sc, zp
+
+
+def rmsnorm_half(x_half, gamma_half, eps):
+    """RMSNorm of binary16 rows to binary16 (exact sum of squares, roundings as stated in the C source)."""
+    x_half = np.ascontiguousarray(x_half)
+    gamma_half = np.ascontiguousarray(gamma_half)
+    assert x_half.dtype == np.float16 and gamma_half.dtype == np.float16
+    M, K = x_half.shape
+    assert gamma_half.shape == (K,)
+    y = np.empty((M, K), dtype=np.float16)
+    fn = _load().abq_oracle_rmsnorm_half
+    fn.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float, ctypes.c_void_p]
+    fn.restype = None
+    fn(M, K, _p(x_half.view(np.uint16)), _p(gamma_half.view(np.uint16)), float(eps), _p(y.view(np.uint16)))
+    return y

@@ -24,7 +24,9 @@
  * Parity status: accumulator, centered accumulator, dequant, half rounding, plane packing are
  * pinned by tests (brute force, library matmul, closed forms, long-double dequantise-then-
  * multiply, numpy's float16 conversion).  abq_oracle_quant_act: PARITY UNPINNED by the paper
- * (it only says "per-token"); pinned by invariants only.
+ * (it only says "per-token"); pinned by invariants only.  abq_oracle_rmsnorm_half (the producer
+ * the quantizer is fused into): the paper prints no formula; pinned against a float64 numpy
+ * evaluation of the standard definition, closed forms and invariances.
  */
 #include <stdint.h>
 #include <stddef.h>
@@ -251,6 +253,39 @@ void abq_oracle_quant_act(int q, int M, int K, const uint16_t* x_half, uint8_t* 
             /* r is integral and |r| <= 2^q-1 here, so the int sum is exact */
             int c = (int)r + z;
             codes[(size_t)m * K + k] = (uint8_t)(c < 0 ? 0 : (c > qmax ? qmax : c));
+        }
+    }
+}
+
+/* RMSNorm to binary16, the producer that Sec. 3.4 / Fig. 3b fuse the activation quantizer into
+ * (the paper quantizes the input of every linear layer of LLaMA, whose normalization is RMSNorm;
+ * the paper prints no formula for it, so this is the standard definition):
+ *     y[k] = x[k] / sqrt(mean_k(x[k]^2) + eps) * gamma[k]
+ * The results feed a quantizer, i.e. they decide integer codes, so every rounding is spelled out:
+ *   - sum_k x[k]^2 is taken EXACTLY (x is binary16, so 2^48 * x^2 is an integer below 2^81; the sum
+ *     is an integer in 128 bits and does not depend on the order of summation),
+ *   - ss   = double(high 64 bits) * 2^64 + double(low 64 bits), scaled by 2^-48   (one rounding at most)
+ *   - mean = ss / K;  r = (float)(1.0 / sqrt(mean + (double)eps))                (double ops, then one rounding)
+ *   - y[k] = half_rne( (float(x[k]) * r) * float(gamma[k]) )                    (two float products)
+ * NaN/Inf inputs are undefined. */
+void abq_oracle_rmsnorm_half(int M, int K, const uint16_t* x_half, const uint16_t* gamma_half, float eps,
+                             uint16_t* y_half)
+{
+    for (int m = 0; m < M; ++m) {
+        unsigned __int128 sum = 0;
+        for (int k = 0; k < K; ++k) {
+            const double x = (double)half_to_float(x_half[(size_t)m * K + k]);
+            const double scaled = x * x * 281474976710656.0;      /* 2^48: exact, an integer */
+            sum += (unsigned __int128)scaled;
+        }
+        const uint64_t hi = (uint64_t)(sum >> 64), lo = (uint64_t)sum;
+        const double ss = ((double)hi * 18446744073709551616.0 + (double)lo) * (1.0 / 281474976710656.0);
+        const double mean = ss / (double)K;
+        volatile float r = (float)(1.0 / sqrt(mean + (double)eps));
+        for (int k = 0; k < K; ++k) {
+            volatile float t = half_to_float(x_half[(size_t)m * K + k]) * r;
+            volatile float u = t * half_to_float(gamma_half[k]);
+            y_half[(size_t)m * K + k] = abq_oracle_half_bits((double)u);
         }
     }
 }

@@ -42,6 +42,14 @@ MUTATIONS = {
         ("z = zf < 0.0f ? 0 : (zf > (float)qmax ? qmax : (int)zf);", "z = (int)zf + 1;"),
     "quantizer: truncation instead of rint":
         ("float r = nearbyintf(t);", "float r = truncf(t);"),
+    "rmsnorm: sum instead of mean of the squares":
+        ("const double mean = ss / (double)K;", "const double mean = ss;"),
+    "rmsnorm: eps dropped":
+        ("(float)(1.0 / sqrt(mean + (double)eps));", "(float)(1.0 / sqrt(mean));"),
+    "rmsnorm: gain of channel 0 for every channel":
+        ("volatile float u = t * half_to_float(gamma_half[k]);", "volatile float u = t * half_to_float(gamma_half[0]);"),
+    "rmsnorm: low half of the exact sum dropped":
+        ("((double)hi * 18446744073709551616.0 + (double)lo) *", "((double)hi * 18446744073709551616.0) *"),
 }
 
 CHECKS = [
@@ -59,6 +67,9 @@ CHECKS = [
     lambda: pins.test_pack_unpack_planes(5, 2, 100),
     lambda: pins.test_quant_act_invariants(4),
     lambda: pins.test_quant_act_invariants(8),
+    lambda: pins.test_rmsnorm_matches_float64_definition(3, 1000, 1e-6),
+    lambda: pins.test_rmsnorm_closed_forms(),
+    lambda: pins.test_rmsnorm_invariances_are_bit_exact(),
 ]
 
 

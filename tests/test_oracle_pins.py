@@ -285,3 +285,70 @@ def test_synth_cases():
     assert (g.a_zero == 128).all() and 100 < g.A.mean() < 156
     y, _ = oracle.dequant(oracle.acc_centered(c.A, c.W, c.a_zero, c.w_zero), c.a_scale, c.w_scale)
     assert np.abs(y).max() < 410
+
+
+# ---- RMSNorm (the producer the activation quantizer is fused into) ---------------------------
+# No printed formula or worked example in the paper: pinned against a float64 evaluation of the standard
+# definition, closed forms, and invariances that the exact sum of squares gives bit for bit.
+
+def _ulp16(v):
+    return 2.0 ** (np.floor(np.log2(np.maximum(np.abs(v), 2.0 ** -14))) - 10)
+
+
+@pytest.mark.parametrize("M,K,eps", [(1, 512, 1e-5), (3, 1000, 1e-6), (2, 4096, 1e-5), (5, 37, 0.0), (1, 11008, 1e-5)])
+def test_rmsnorm_matches_float64_definition(M, K, eps):
+    rng = np.random.Generator(np.random.PCG64(1000 + K))
+    x = (rng.standard_normal((M, K)) * rng.uniform(0.05, 8.0, (M, 1))).astype(np.float16)
+    x[:, rng.integers(0, K, 3)] *= np.float16(20.0)                      # outlier channels
+    g = (1.0 + 0.2 * rng.standard_normal(K)).astype(np.float16)
+    y = oracle.rmsnorm_half(x, g, eps)
+    xr = x.astype(np.float64)
+    ref = xr / np.sqrt((xr ** 2).mean(axis=1, keepdims=True) + np.float64(np.float32(eps))) * g.astype(np.float64)
+    # one rounding to binary16 (half an ulp) plus three binary32 roundings before it (2^-13 of an ulp16 each)
+    assert np.all(np.abs(y.astype(np.float64) - ref) <= 0.501 * _ulp16(ref))
+
+
+def test_rmsnorm_closed_forms():
+    K = 1024
+    # constant row, unit gain, no eps: every output is exactly +-1
+    for c in (3.0, -0.37, 1000.0, 6e-5):
+        x = np.full((1, K), c, dtype=np.float16)
+        y = oracle.rmsnorm_half(x, np.ones(K, dtype=np.float16), 0.0)
+        assert np.all(y == np.float16(np.sign(c)))
+    # one-hot row: mean = a^2/K, so the hot output is sqrt(K) * gamma * sign(a) and the rest stay zero
+    x = np.zeros((1, K), dtype=np.float16)
+    x[0, 17] = -2.5
+    g = np.full(K, 0.75, dtype=np.float16)
+    y = oracle.rmsnorm_half(x, g, 0.0)
+    assert y[0, 17] == np.float16(-32.0 * 0.75) and np.count_nonzero(y) == 1
+    # all-zero row with eps: zeros (0 * finite)
+    y = oracle.rmsnorm_half(np.zeros((2, 64), dtype=np.float16), np.ones(64, dtype=np.float16), 1e-5)
+    assert not y.any()
+    # eps dominates: x = 2^-10 everywhere, eps = 1 -> y = x / sqrt(2^-20 + 1) rounds to x itself
+    x = np.full((1, 256), 2.0 ** -10, dtype=np.float16)
+    assert np.all(oracle.rmsnorm_half(x, np.ones(256, dtype=np.float16), 1.0) == np.float16(2.0 ** -10))
+
+
+def test_rmsnorm_invariances_are_bit_exact():
+    rng = np.random.Generator(np.random.PCG64(77))
+    K = 777
+    x = rng.standard_normal((4, K)).astype(np.float16)
+    g = rng.uniform(0.5, 1.5, K).astype(np.float16)
+    y = oracle.rmsnorm_half(x, g, 0.0)
+    # a power-of-two gain on the input cancels exactly when eps = 0 (every step scales exactly)
+    for s in (0.25, 4.0):
+        assert np.array_equal(oracle.rmsnorm_half((x * np.float16(s)).astype(np.float16), g, 0.0).view(np.uint16), y.view(np.uint16))
+    # permuting the channels (of x and gamma alike) permutes the outputs: the sum of squares is exact, so
+    # it cannot depend on the order of the terms
+    perm = rng.permutation(K)
+    yp = oracle.rmsnorm_half(np.ascontiguousarray(x[:, perm]), np.ascontiguousarray(g[perm]), 1e-5)
+    assert np.array_equal(yp.view(np.uint16), oracle.rmsnorm_half(x, g, 1e-5)[:, perm].view(np.uint16))
+    # rows are independent, and flipping the sign of a row flips its outputs
+    assert np.array_equal(oracle.rmsnorm_half(x[1:2], g, 1e-5), oracle.rmsnorm_half(x, g, 1e-5)[1:2])
+    assert np.array_equal(oracle.rmsnorm_half(-x, g, 1e-5), -oracle.rmsnorm_half(x, g, 1e-5))
+    # the exact sum copes with terms 2^60 apart (a float or double running sum would drop the small ones):
+    # one huge element and 4095 tiny ones whose squares together shift the mean by less than one part in 2^53
+    x = np.full((1, 4096), 6e-5, dtype=np.float16)
+    x[0, 0] = 60000.0
+    y = oracle.rmsnorm_half(x, np.ones(4096, dtype=np.float16), 0.0)
+    assert y[0, 0] == np.float16(64.0) and np.all(y[0, 1:] == np.float16(np.float64(x[0, 1]) * 64.0 / 60000.0))
