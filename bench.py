@@ -214,6 +214,57 @@ def bench_grouped(p, q, M, steps, warmup, rotate_gib, check=True):
             "steps": steps}
 
 
+def bench_rmsnorm_quant(q, M, K, steps, warmup, check=True):
+    """abq_rmsnorm_quant_act alone (fp16 hidden state -> codes, scale, zero-point in one kernel)."""
+    import numpy as np
+    import torch
+    from paper_2408_08554_amd import binding as abq
+    rng = np.random.Generator(np.random.PCG64(5))
+    x = (rng.standard_normal((M, K)) * rng.uniform(0.05, 8.0, (M, 1))).astype(np.float16)
+    g = (1.0 + 0.2 * rng.standard_normal(K)).astype(np.float16)
+    R = max(2, min(64, (1 << 30) // max(1, 2 * M * K)))      # rotate the inputs past the last-level cache when they are large
+    xs = [torch.from_numpy(x).cuda() for _ in range(R)]
+    gd = torch.from_numpy(g).cuda()
+    lib = abq.load()
+    codes = torch.empty((M, K), dtype=torch.uint8, device="cuda")
+    scale = torch.empty(M, dtype=torch.float32, device="cuda")
+    zero = torch.empty(M, dtype=torch.int32, device="cuda")
+    if check:
+        import oracle
+        rows = min(M, 4)
+        c, sc, zp, _ = abq.abq_rmsnorm_quant_act(q, xs[0][:rows].contiguous(), gd, 1e-5)
+        rc, rs, rz = oracle.quant_act(oracle.rmsnorm_half(x[:rows], g, 1e-5), q)
+        assert np.array_equal(c.cpu().numpy(), rc) and np.array_equal(sc.cpu().numpy(), rs) and np.array_equal(zp.cpu().numpy(), rz)
+    stream = torch.cuda.Stream()
+
+    def call(i):
+        st = lib.abq_rmsnorm_quant_act(q, M, K, xs[i % R].data_ptr(), gd.data_ptr(), 1e-5, codes.data_ptr(), scale.data_ptr(),
+                                       zero.data_ptr(), None, torch.cuda.current_stream().cuda_stream)
+        assert st == 0
+
+    with torch.cuda.stream(stream):
+        for i in range(warmup):
+            call(i)
+        stream.synchronize()
+        gph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gph, stream=stream):
+            for i in range(steps):
+                call(i)
+        gph.replay()
+        stream.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        gph.replay()
+        e1.record(stream)
+        torch.cuda.synchronize()
+    t = e0.elapsed_time(e1) * 1e-3 / steps
+    alg = 2 * M * K + 2 * K + M * K + 8 * M
+    return {"workload": f"abq_rmsnorm_quant_act q={q} M={M} K={K}", "us": t * 1e6, "tokens_per_s": M / t,
+            "roofline": {"bound": "hbm", "achieved": alg / t / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": alg / t / 1e9 / HBM_PEAK_GBS, "traffic": None, "algorithmic_bytes": alg,
+                         "kernel": "rmsnorm_quant_kernel", "launches": steps}, "steps": steps}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -245,6 +296,11 @@ def main():
         # block:p,q,M — the grouped decoder-block launch as the timed workload, printed as its own JSON line
         bp, bq, bm = (int(v) for v in args.workload.split(":")[1].split(","))
         print(json.dumps(bench_grouped(bp, bq, bm, args.steps, args.warmup, args.rotate_gib, not args.no_check)), flush=True)
+        return
+    if args.workload.startswith("norm:"):
+        # norm:q,M,K — the fused RMSNorm + quantizer kernel alone, printed as its own JSON line
+        nq, nm, nk = (int(v) for v in args.workload.split(":")[1].split(","))
+        print(json.dumps(bench_rmsnorm_quant(nq, nm, nk, args.steps, args.warmup, not args.no_check)), flush=True)
         return
     c = build_case(args.workload)
     p, q, M, N, K = c.p, c.q, c.M, c.N, c.K

@@ -113,6 +113,19 @@ int abq_pack_act_codes(int q, int M, int K,
                        const uint8_t* a_codes, const float* a_scale, const int32_t* a_zero,
                        int layout, void* packed_out, size_t packed_bytes, void* stream);
 
+/* RMSNorm with the quantizer fused in (Sec. 3.4 / Fig. 3b: the online quantization of a linear layer's input
+ * is folded into the operator in front of it; for the LLaMA models of the paper that operator is RMSNorm,
+ * y = x / sqrt(mean(x^2) + eps) * gamma, whose formula the paper does not print).  Per token m:
+ *   y[m,:] in binary16 (sum of squares exact, 1/sqrt in double rounded once to float, two float products,
+ *   one rounding to binary16), then the quantizer of abq_quant_pack_act on y[m,:].
+ *   x_fp16 [M,K], gamma_fp16 [K]: binary16 bit patterns;  eps >= 0
+ *   a_codes_out [M,K] uint8, a_scale_out [M] float, a_zero_out [M] int32: the inputs of abq_gemm_act_codes
+ *   y_fp16_out  [M,K] binary16, optional (NULL to skip): the normalized row before quantization
+ * NaN/Inf inputs are undefined. */
+int abq_rmsnorm_quant_act(int q, int M, int K, const uint16_t* x_fp16, const uint16_t* gamma_fp16, float eps,
+                          uint8_t* a_codes_out, float* a_scale_out, int32_t* a_zero_out,
+                          uint16_t* y_fp16_out, void* stream);
+
 /* Test hook: decodes an activation blob.  Any output pointer may be NULL.
  *   a_codes_out [M,K] uint8, a_scale_out [M] float, a_zero_out [M] int32, a_sum_out [M] int32. */
 int abq_unpack_act(int q, int M, int K, int layout, const void* packed, int which,

@@ -70,6 +70,9 @@ hipError_t launch_quant_pack_act(const ActLayout& L, const uint16_t* x, uint8_t*
 hipError_t launch_unpack_act(const ActLayout& L, const uint8_t* blob, int which, uint8_t* codes, float* scale,
                              int32_t* zero, int32_t* sum, hipStream_t s);
 
+hipError_t launch_rmsnorm_quant(int q, int M, int K, const uint16_t* x, const uint16_t* gamma, float eps, uint8_t* codes,
+                                float* scale, int32_t* zero, uint16_t* y_out, hipStream_t s);
+
 struct GemmArgs {
     int p, q, M, N, K;
     const uint8_t* act_blob;   // packed activations, or null when a_raw is given (streaming kernel only)

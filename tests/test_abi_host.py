@@ -198,6 +198,24 @@ def test_probe_rejects():
     assert lib.abq_probe_mfma_i8_ops(0) == 0.0
 
 
+def test_rmsnorm_quant_act_rejects():
+    lib = B.load()
+
+    def call(q=8, M=1, K=64, x=A16, g=A16, eps=1e-5, c=A16, s=A16, z=A16, y=None):
+        return lib.abq_rmsnorm_quant_act(q, M, K, x, g, eps, c, s, z, y, None)
+
+    assert call(x=None) == B.ABQ_ERR_NULL
+    assert call(g=None) == B.ABQ_ERR_NULL
+    assert call(z=None) == B.ABQ_ERR_NULL
+    assert call(q=0) == B.ABQ_ERR_BITS
+    assert call(M=0) == B.ABQ_ERR_SHAPE
+    assert call(K=B.ABQ_MAX_K + 1) == B.ABQ_ERR_SHAPE
+    assert call(eps=-1.0) == B.ABQ_ERR_SHAPE
+    assert call(eps=float("nan")) == B.ABQ_ERR_SHAPE
+    assert call(y=A16 + 2) == B.ABQ_ERR_ALIGN
+    assert call(c=A16 + 1) == B.ABQ_ERR_ALIGN
+
+
 def test_unpack_rejects():
     lib = B.load()
     assert lib.abq_unpack_weights(4, 16, 64, B.ABQ_LAYOUT_FIELDS, A16, B.ABQ_LAYOUT_PLANES, A16, None) == B.ABQ_ERR_LAYOUT

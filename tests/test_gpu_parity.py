@@ -359,6 +359,59 @@ def test_grouped_falls_back_to_single_calls(abq, kind, fused):
         check_against_oracle(c, y, acc)
 
 
+# ---- RMSNorm with the quantizer fused in -----------------------------------------------------------
+
+def _norm_inputs(M, K, seed, kind="normal"):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    x = (rng.standard_normal((M, K)) * rng.uniform(0.05, 8.0, (M, 1))).astype(np.float16)
+    x[:, rng.integers(0, K, 4)] *= np.float16(20.0)
+    if kind == "extremes":      # huge and tiny magnitudes, subnormals, zeros, an all-zero row, a constant row
+        x[0, : K // 2] = np.float16(6e-5)
+        x[0, 0] = np.float16(60000.0)
+        x[0, 1] = np.float16(5.96e-8)
+        if M > 1:
+            x[1] = 0
+        if M > 2:
+            x[2] = np.float16(-3.0)
+    g = (1.0 + 0.2 * rng.standard_normal(K)).astype(np.float16)
+    return x, g
+
+
+@pytest.mark.parametrize("q", [1, 4, 6, 8])
+@pytest.mark.parametrize("M,K,eps,kind", [(1, 4096, 1e-5, "normal"), (5, 1000, 1e-6, "normal"), (3, 37, 0.0, "normal"),
+                                          (2, 11008, 1e-5, "normal"), (16, 5120, 1e-5, "normal"), (4, 4096, 1e-5, "extremes"),
+                                          (3, 1, 1e-5, "normal"), (2, 131072, 1e-6, "normal")])
+def test_rmsnorm_quant_act_matches_oracle(abq, q, M, K, eps, kind):
+    say("rmsnorm quant", q, M, K, eps, kind)
+    x, g = _norm_inputs(M, K, 4000 + 13 * q + K + M, kind)
+    y_ref = oracle.rmsnorm_half(x, g, eps)
+    codes_ref, scale_ref, zero_ref = oracle.quant_act(y_ref, q)
+    codes, scale, zero, y = abq.abq_rmsnorm_quant_act(q, to_dev(torch, x), to_dev(torch, g), eps, want_y=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(y.cpu().numpy().view(np.uint16), y_ref.view(np.uint16))
+    assert np.array_equal(scale.cpu().numpy(), scale_ref)
+    assert np.array_equal(zero.cpu().numpy(), zero_ref)
+    assert np.array_equal(codes.cpu().numpy(), codes_ref)
+    # without the optional output the codes are the same
+    codes2, _, _, none = abq.abq_rmsnorm_quant_act(q, to_dev(torch, x), to_dev(torch, g), eps)
+    assert none is None and np.array_equal(codes2.cpu().numpy(), codes_ref)
+
+
+def test_rmsnorm_quant_then_fused_gemm_end_to_end(abq):
+    """fp16 hidden state -> RMSNorm + quantizer (one kernel) -> fused decode matmul (one kernel), against the
+    oracle chain rmsnorm -> quantizer -> centered product sum -> dequant."""
+    p, q, M, N, K = 4, 8, 3, 200, 4096
+    x, g = _norm_inputs(M, K, 99)
+    c = synth.make_case(p, q, M, N, K, seed=98)
+    codes_ref, scale_ref, zero_ref = oracle.quant_act(oracle.rmsnorm_half(x, g, 1e-5), q)
+    pw = abq.abq_pack_weights(p, to_dev(torch, c.W), to_dev(torch, c.w_scale), to_dev(torch, c.w_zero), FIELDS)
+    codes, scale, zero, _ = abq.abq_rmsnorm_quant_act(q, to_dev(torch, x), to_dev(torch, g), 1e-5)
+    y, acc = abq.abq_gemm_act_codes(p, q, M, N, K, codes, scale, zero, pw, FIELDS, want_acc=True)
+    torch.cuda.synchronize()
+    c.A, c.a_scale, c.a_zero = codes_ref, scale_ref, zero_ref
+    check_against_oracle(c, y.cpu().numpy(), acc.cpu().numpy())
+
+
 def test_measurement_probes_run(abq):
     """The two probe kernels launch, finish and leave their sink alone."""
     buf = torch.ones(8 << 20, dtype=torch.uint8, device="cuda")
