@@ -412,6 +412,60 @@ def test_rmsnorm_quant_then_fused_gemm_end_to_end(abq):
     check_against_oracle(c, y.cpu().numpy(), acc.cpu().numpy())
 
 
+def test_graph_replays_match_eager(abq):
+    """The decode entry points captured in one HIP graph (no allocation, no memset inside) and replayed several
+    times with new inputs, eager work and synchronizations in between: every replay equals the eager result."""
+    p, q, M, K = 4, 8, 2, 4096
+    shapes = [(4096, 4096), (300, 4096)]
+    rng = np.random.Generator(np.random.PCG64(321))
+    cases = [synth.make_case(p, q, M, N, K2, seed=500 + i) for i, (N, K2) in enumerate(shapes)]
+    pws = [abq.abq_pack_weights(p, to_dev(torch, c.W), to_dev(torch, c.w_scale), to_dev(torch, c.w_zero), FIELDS) for c in cases]
+    g = to_dev(torch, (1.0 + 0.1 * rng.standard_normal(K)).astype(np.float16))
+    x = torch.zeros((M, K), dtype=torch.float16, device="cuda")
+    codes = torch.empty((M, K), dtype=torch.uint8, device="cuda")
+    scale = torch.empty(M, dtype=torch.float32, device="cuda")
+    zero = torch.empty(M, dtype=torch.int32, device="cuda")
+    y1 = torch.empty((M, shapes[0][0]), dtype=torch.float16, device="cuda")
+    ys = [torch.empty((M, N), dtype=torch.float16, device="cuda") for N, _ in shapes]
+    lib = abq.load()
+    problems = abq.make_problems([dict(N=c.N, K=c.K, packed_w=pw, a_codes=codes, a_scale=scale, a_zero=zero, y=y)
+                                  for c, pw, y in zip(cases, pws, ys)])
+
+    def run():
+        st = torch.cuda.current_stream().cuda_stream
+        assert lib.abq_rmsnorm_quant_act(q, M, K, x.data_ptr(), g.data_ptr(), 1e-5, codes.data_ptr(), scale.data_ptr(),
+                                         zero.data_ptr(), None, st) == 0
+        abq.abq_gemm_act_codes(p, q, M, shapes[0][0], K, codes, scale, zero, pws[0], FIELDS, y=y1)
+        abq.abq_gemm_grouped(p, q, M, problems, FIELDS, FIELDS)
+
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        run()
+        stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            run()
+        for rep in range(4):
+            xin = (rng.standard_normal((M, K)) * (rep + 1)).astype(np.float16)
+            x.copy_(torch.from_numpy(xin).cuda())
+            for t in (y1, *ys):
+                t.fill_(float("nan"))
+            graph.replay()
+            stream.synchronize()
+            got = [y1.clone()] + [t.clone() for t in ys]
+            for t in (y1, *ys):
+                t.fill_(float("nan"))
+            run()                               # eager, same inputs
+            stream.synchronize()
+            for a, b in zip(got, [y1, *ys]):
+                assert torch.equal(a.view(torch.int16), b.view(torch.int16)), f"replay {rep} differs from the eager run"
+            # and the eager run is right: first problem against the oracle chain
+            cr, sr, zr = oracle.quant_act(oracle.rmsnorm_half(xin, g.cpu().numpy(), 1e-5), q)
+            c0 = cases[0]
+            c0.A, c0.a_scale, c0.a_zero = cr, sr, zr
+            check_against_oracle(c0, y1.cpu().numpy(), None)
+
+
 def test_measurement_probes_run(abq):
     """The two probe kernels launch, finish and leave their sink alone."""
     buf = torch.ones(8 << 20, dtype=torch.uint8, device="cuda")
