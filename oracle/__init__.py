@@ -189,3 +189,17 @@ def rmsnorm_half(x_half, gamma_half, eps):
     fn.restype = None
     fn(M, K, _p(x_half.view(np.uint16)), _p(gamma_half.view(np.uint16)), float(eps), _p(y.view(np.uint16)))
     return y
+
+
+def silu_mul_half(gate_half, up_half):
+    """silu(gate) * up in binary16 (exp as the stated sequence of binary32 operations; see the C source)."""
+    gate_half = np.ascontiguousarray(gate_half)
+    up_half = np.ascontiguousarray(up_half)
+    assert gate_half.dtype == np.float16 and up_half.dtype == np.float16 and gate_half.shape == up_half.shape
+    M, K = gate_half.shape
+    h = np.empty((M, K), dtype=np.float16)
+    fn = _load().abq_oracle_silu_mul_half
+    fn.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+    fn.restype = None
+    fn(M, K, _p(gate_half.view(np.uint16)), _p(up_half.view(np.uint16)), _p(h.view(np.uint16)))
+    return h

@@ -26,7 +26,8 @@
  * multiply, numpy's float16 conversion).  abq_oracle_quant_act: PARITY UNPINNED by the paper
  * (it only says "per-token"); pinned by invariants only.  abq_oracle_rmsnorm_half (the producer
  * the quantizer is fused into): the paper prints no formula; pinned against a float64 numpy
- * evaluation of the standard definition, closed forms and invariances.
+ * evaluation of the standard definition, closed forms and invariances.  abq_oracle_silu_mul_half
+ * (the second producer): pinned against a float64 evaluation with the library exp and closed forms.
  */
 #include <stdint.h>
 #include <stddef.h>
@@ -287,5 +288,45 @@ void abq_oracle_rmsnorm_half(int M, int K, const uint16_t* x_half, const uint16_
             volatile float u = t * half_to_float(gamma_half[k]);
             y_half[(size_t)m * K + k] = abq_oracle_half_bits((double)u);
         }
+    }
+}
+
+/* SiLU(gate) * up to binary16: the producer in front of down_proj in the LLaMA MLP, the other operator
+ * Sec. 3.4 / Fig. 3b fuse the activation quantizer into.  silu(g) = g / (1 + exp(-g)).  The result
+ * decides integer codes, so exp is not left to a math library (two libraries differ in the last bits);
+ * it is the following sequence of single IEEE binary32 operations, the same on every machine:
+ *   t = clamp(-g * log2(e), -126, 126);  n = rint(t);  f = t - n      (f in [-1/2, 1/2], exact)
+ *   2^f = 1 + f*(c1 + f*(c2 + f*(c3 + f*(c4 + f*(c5 + f*c6)))))        (c_k = ln(2)^k / k!, Horner, no fma)
+ *   e = 2^f * 2^n;   h = half_rne( (g / (1 + e)) * up )
+ * Its distance from the real exp is below 2 * 10^-7 relative, far inside half an ulp of binary16.
+ * NaN/Inf inputs are undefined. */
+static float oracle_exp2_poly(float f)
+{
+    static const float c1 = 0x1.62e430p-1f, c2 = 0x1.ebfbe0p-3f, c3 = 0x1.c6b08ep-5f, c4 = 0x1.3b2ab6p-7f,
+                       c5 = 0x1.5d87fep-10f, c6 = 0x1.430912p-13f;
+    volatile float p = f * c6;
+    p = p + c5; p = p * f;
+    p = p + c4; p = p * f;
+    p = p + c3; p = p * f;
+    p = p + c2; p = p * f;
+    p = p + c1; p = p * f;
+    p = p + 1.0f;
+    return p;
+}
+
+void abq_oracle_silu_mul_half(int M, int K, const uint16_t* gate_half, const uint16_t* up_half, uint16_t* h_half)
+{
+    for (size_t i = 0; i < (size_t)M * K; ++i) {
+        const float g = half_to_float(gate_half[i]), u = half_to_float(up_half[i]);
+        volatile float t = -g * 0x1.715476p+0f;
+        if (t < -126.0f) t = -126.0f;
+        if (t > 126.0f) t = 126.0f;
+        const float n = nearbyintf(t);
+        volatile float f = t - n;
+        volatile float e = ldexpf(oracle_exp2_poly(f), (int)n);
+        volatile float s = 1.0f + e;
+        volatile float sg = g / s;
+        volatile float h = sg * u;
+        h_half[i] = abq_oracle_half_bits((double)h);
     }
 }

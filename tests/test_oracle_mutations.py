@@ -48,6 +48,14 @@ MUTATIONS = {
         ("(float)(1.0 / sqrt(mean + (double)eps));", "(float)(1.0 / sqrt(mean));"),
     "rmsnorm: gain of channel 0 for every channel":
         ("volatile float u = t * half_to_float(gamma_half[k]);", "volatile float u = t * half_to_float(gamma_half[0]);"),
+    "silu: sign of the exponent":
+        ("volatile float t = -g * 0x1.715476p+0f;", "volatile float t = g * 0x1.715476p+0f;"),
+    "silu: natural instead of binary exponent scaling":
+        ("volatile float t = -g * 0x1.715476p+0f;", "volatile float t = -g;"),
+    "silu: polynomial term dropped":
+        ("    p = p + c2; p = p * f;\n", "    p = p * f;\n"),
+    "silu: second operand not applied":
+        ("volatile float h = sg * u;", "volatile float h = sg;"),
     "rmsnorm: low half of the exact sum dropped":
         ("((double)hi * 18446744073709551616.0 + (double)lo) *", "((double)hi * 18446744073709551616.0) *"),
 }
@@ -70,6 +78,8 @@ CHECKS = [
     lambda: pins.test_rmsnorm_matches_float64_definition(3, 1000, 1e-6),
     lambda: pins.test_rmsnorm_closed_forms(),
     lambda: pins.test_rmsnorm_invariances_are_bit_exact(),
+    lambda: pins.test_silu_mul_matches_float64_definition(),
+    lambda: pins.test_silu_mul_closed_forms_and_limits(),
 ]
 
 

@@ -352,3 +352,40 @@ def test_rmsnorm_invariances_are_bit_exact():
     x[0, 0] = 60000.0
     y = oracle.rmsnorm_half(x, np.ones(4096, dtype=np.float16), 0.0)
     assert y[0, 0] == np.float16(64.0) and np.all(y[0, 1:] == np.float16(np.float64(x[0, 1]) * 64.0 / 60000.0))
+
+
+# ---- SiLU(gate) * up (the second producer the quantizer is fused into) ------------------------------
+
+def test_silu_mul_matches_float64_definition():
+    rng = np.random.Generator(np.random.PCG64(2024))
+    g = (rng.standard_normal((6, 3000)) * rng.uniform(0.1, 12.0, (6, 1))).astype(np.float16)
+    u = (rng.standard_normal((6, 3000)) * 3.0).astype(np.float16)
+    h = oracle.silu_mul_half(g, u)
+    gd = g.astype(np.float64)
+    ref = gd / (1.0 + np.exp(-gd)) * u.astype(np.float64)
+    # half an ulp of binary16 for the final rounding; the binary32 steps before it (polynomial exp within
+    # 2e-7, one add, one division, one product) add less than a thousandth of that
+    assert np.all(np.abs(h.astype(np.float64) - ref) <= 0.501 * _ulp16(ref))
+
+
+def test_silu_mul_closed_forms_and_limits():
+    one = np.ones((1, 8), dtype=np.float16)
+    g = np.array([[0.0, -0.0, 100.0, -100.0, 60000.0, -60000.0, 1e-4, -1e-4]], dtype=np.float16)
+    h = oracle.silu_mul_half(g, one)
+    assert h[0, 0] == 0 and h[0, 1] == 0                        # silu(0) = 0
+    assert h[0, 2] == np.float16(100.0) and h[0, 4] == np.float16(60000.0)     # exp(-g) vanishes: silu(g) = g
+    assert h[0, 3] == 0 and h[0, 5] == 0                        # g * exp(g) underflows binary16
+    assert h[0, 6] == np.float16(np.float64(g[0, 6]) / 2) and h[0, 7] == np.float16(np.float64(g[0, 7]) / 2)   # silu(g) ~ g/2 near 0
+    # the second operand multiplies: zero, sign, and a power of two pass through exactly
+    g = np.linspace(-8, 8, 64, dtype=np.float16).reshape(1, 64)
+    base = oracle.silu_mul_half(g, np.ones_like(g))
+    assert not oracle.silu_mul_half(g, np.zeros_like(g)).any()
+    assert np.array_equal(oracle.silu_mul_half(g, -np.ones_like(g)), -base)
+    assert np.array_equal(oracle.silu_mul_half(g, np.full_like(g, 4.0)).astype(np.float64), base.astype(np.float64) * 4.0)
+    # silu(g) - silu(-g) = g: holds to rounding
+    b64 = base.astype(np.float64)[0]
+    assert np.all(np.abs(b64 - b64[::-1] - g.astype(np.float64)[0]) <= 2 * _ulp16(g.astype(np.float64)[0]))
+    # silu has its minimum -0.2785 at g = -1.2785 and increases from there on
+    gpos = np.linspace(-1.25, 12.0, 500, dtype=np.float16).reshape(1, 500)
+    hp = oracle.silu_mul_half(gpos, np.ones_like(gpos)).astype(np.float64)[0]
+    assert np.all(np.diff(hp) >= 0) and abs(oracle.silu_mul_half(np.array([[-1.2785]], dtype=np.float16), np.ones((1, 1), dtype=np.float16))[0, 0] + 0.2785) < 3e-4
