@@ -126,6 +126,15 @@ int abq_rmsnorm_quant_act(int q, int M, int K, const uint16_t* x_fp16, const uin
                           uint8_t* a_codes_out, float* a_scale_out, int32_t* a_zero_out,
                           uint16_t* y_fp16_out, void* stream);
 
+/* SiLU(gate) * up with the quantizer fused in: the producer in front of down_proj in the LLaMA MLP (same passage).
+ * Per element h = half_rne((g / (1 + exp(-g))) * up), exp taken as a fixed sequence of binary32 operations
+ * (t = clamp(-g * log2 e, -126, 126), n = rint(t), 2^(t-n) by a degree-6 polynomial, scaled by 2^n: within
+ * 2e-7 of exp, the same bits on every machine), then the quantizer of abq_quant_pack_act on h[m,:].
+ *   gate_fp16, up_fp16 [M,K] binary16;  outputs as for abq_rmsnorm_quant_act (h_fp16_out optional). */
+int abq_silu_mul_quant_act(int q, int M, int K, const uint16_t* gate_fp16, const uint16_t* up_fp16,
+                           uint8_t* a_codes_out, float* a_scale_out, int32_t* a_zero_out,
+                           uint16_t* h_fp16_out, void* stream);
+
 /* Test hook: decodes an activation blob.  Any output pointer may be NULL.
  *   a_codes_out [M,K] uint8, a_scale_out [M] float, a_zero_out [M] int32, a_sum_out [M] int32. */
 int abq_unpack_act(int q, int M, int K, int layout, const void* packed, int which,

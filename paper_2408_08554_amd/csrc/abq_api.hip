@@ -205,6 +205,18 @@ int abq_rmsnorm_quant_act(int q, int M, int K, const uint16_t* x_fp16, const uin
                                            (hipStream_t)stream));
 }
 
+int abq_silu_mul_quant_act(int q, int M, int K, const uint16_t* gate_fp16, const uint16_t* up_fp16, uint8_t* a_codes_out,
+                           float* a_scale_out, int32_t* a_zero_out, uint16_t* h_fp16_out, void* stream)
+{
+    if (!gate_fp16 || !up_fp16 || !a_codes_out || !a_scale_out || !a_zero_out) return ABQ_ERR_NULL;
+    if (int e = check_bits_shape(q, M, K)) return e;
+    if (misaligned(gate_fp16) || misaligned(up_fp16) || misaligned(a_codes_out) || misaligned(a_scale_out) ||
+        misaligned(a_zero_out) || misaligned(h_fp16_out))
+        return ABQ_ERR_ALIGN;
+    return hip_status(launch_silu_mul_quant(q, M, K, gate_fp16, up_fp16, a_codes_out, a_scale_out, a_zero_out, h_fp16_out,
+                                            (hipStream_t)stream));
+}
+
 static int check_gemm_shape(int p, int q, int M, int N, int K)
 {
     if (p < 1 || p > 8 || q < 1 || q > 8) return ABQ_ERR_BITS;

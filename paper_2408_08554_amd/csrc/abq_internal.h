@@ -73,6 +73,9 @@ hipError_t launch_unpack_act(const ActLayout& L, const uint8_t* blob, int which,
 hipError_t launch_rmsnorm_quant(int q, int M, int K, const uint16_t* x, const uint16_t* gamma, float eps, uint8_t* codes,
                                 float* scale, int32_t* zero, uint16_t* y_out, hipStream_t s);
 
+hipError_t launch_silu_mul_quant(int q, int M, int K, const uint16_t* gate, const uint16_t* up, uint8_t* codes, float* scale,
+                                 int32_t* zero, uint16_t* h_out, hipStream_t s);
+
 struct GemmArgs {
     int p, q, M, N, K;
     const uint8_t* act_blob;   // packed activations, or null when a_raw is given (streaming kernel only)

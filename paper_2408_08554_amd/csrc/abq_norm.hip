@@ -1,8 +1,10 @@
-// RMSNorm with the activation quantizer fused in: the producer-side fusion of Sec. 3.4 / Fig. 3b (the
+// The activation quantizer fused into its producers: the producer-side fusion of Sec. 3.4 / Fig. 3b (the
 // online quantization of a linear layer's input is folded into the operator in front of it, which in
-// the LLaMA models the paper evaluates is RMSNorm).  One kernel takes a token's fp16 hidden state to
-// q-bit codes with their per-token scale and zero-point, ready for abq_gemm_act_codes.
+// the LLaMA models the paper evaluates is RMSNorm for the attention and gate/up projections and
+// SiLU(gate) * up for down_proj).  One kernel takes a token's fp16 row to q-bit codes with their
+// per-token scale and zero-point, ready for abq_gemm_act_codes.
 //
+// RMSNorm (KIND 0).
 // Every step that decides a code is a single, stated IEEE operation, so the codes are reproducible
 // bit for bit whatever the order of the parallel reductions:
 //   sum_k x^2 exactly (x is binary16: 2^48 x^2 is an integer below 2^81, summed in 128 bits),
@@ -10,6 +12,9 @@
 //   y = half_rne((float(x) * r) * float(gamma)),
 //   then the per-token quantizer of abq_quant_pack_act on y (lo/hi include 0, Delta = (hi - lo) / (2^q - 1),
 //   z = clamp(rint(-lo / Delta)), code = clamp(rint(y / Delta) + z)).
+// SiLU * up (KIND 1): h = half_rne((g / (1 + e)) * up) with e = exp(-g) as a fixed sequence of binary32
+// operations (no math library, no fused multiply-add): t = clamp(-g * log2(e), -126, 126), n = rint(t),
+// f = t - n, 2^f by a degree-6 Horner polynomial with coefficients ln(2)^k / k!, e = ldexp(2^f, n).
 #include "abq_internal.h"
 #include "../../include/abq.h"
 
@@ -70,10 +75,41 @@ __device__ __forceinline__ uint16_t normalized_half(uint16_t xb, uint16_t gb, fl
     return (uint16_t)hb;
 }
 
+// silu(g) * u as binary16 bits (see the head of the file for the definition of exp).
+__device__ __forceinline__ uint16_t silu_mul_half(uint16_t gb, uint16_t ub)
+{
+    const float g = half_to_f32(gb), u = half_to_f32(ub);
+    float t = __fmul_rn(-g, 0x1.715476p+0f);
+    t = t < -126.0f ? -126.0f : (t > 126.0f ? 126.0f : t);
+    const float n = rintf(t);
+    const float f = __fsub_rn(t, n);
+    float p = __fmul_rn(f, 0x1.430912p-13f);
+    p = __fmul_rn(__fadd_rn(p, 0x1.5d87fep-10f), f);
+    p = __fmul_rn(__fadd_rn(p, 0x1.3b2ab6p-7f), f);
+    p = __fmul_rn(__fadd_rn(p, 0x1.c6b08ep-5f), f);
+    p = __fmul_rn(__fadd_rn(p, 0x1.ebfbe0p-3f), f);
+    p = __fmul_rn(__fadd_rn(p, 0x1.62e430p-1f), f);
+    p = __fadd_rn(p, 1.0f);
+    const float e = ldexpf(p, (int)n);
+    const float sg = __fdiv_rn(g, __fadd_rn(1.0f, e));
+    const float h = __fmul_rn(sg, u);
+    uint32_t hb;
+    asm("v_cvt_f16_f32 %0, %1" : "=v"(hb) : "v"(h));   // (kept apart from the product, as above)
+    return (uint16_t)hb;
+}
+
+// KIND 0: RMSNorm, operand b = gamma [K];  KIND 1: SiLU(a) * b, operand b = up [M,K].
+template <int KIND>
+__device__ __forceinline__ uint16_t produce_half(uint16_t ab, uint16_t bb, float r)
+{
+    if constexpr (KIND == 0) return normalized_half(ab, bb, r);
+    else return silu_mul_half(ab, bb);
+}
+
 // Fast path: K a multiple of 8 and at most 8 * BLOCK * VPT.  A thread keeps its VPT 16-byte vectors of x and
 // of gamma in registers across the three passes (sum of squares, range, codes): the row is read once.
-template <int VPT, int BLOCK>
-__global__ __launch_bounds__(BLOCK) void rmsnorm_quant_rows_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ gamma,
+template <int KIND, int VPT, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void producer_quant_rows_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ gamma,
                                                                  float eps, int q, int K, uint8_t* __restrict__ codes,
                                                                  float* __restrict__ scale, int32_t* __restrict__ zero,
                                                                  uint16_t* __restrict__ y_out)
@@ -84,7 +120,7 @@ __global__ __launch_bounds__(BLOCK) void rmsnorm_quant_rows_kernel(const uint16_
     const int m = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nvec = K >> 3, qmax = (1 << q) - 1;
     const uint4* xrow = reinterpret_cast<const uint4*>(x + (size_t)m * K);
-    const uint4* grow = reinterpret_cast<const uint4*>(gamma);
+    const uint4* grow = reinterpret_cast<const uint4*>(KIND == 0 ? gamma : gamma + (size_t)m * K);
     uint32_t xv[VPT][4], gv[VPT][4];
 #pragma unroll
     for (int i = 0; i < VPT; ++i) {
@@ -94,36 +130,39 @@ __global__ __launch_bounds__(BLOCK) void rmsnorm_quant_rows_kernel(const uint16_
         xv[i][0] = in ? a.x : 0u; xv[i][1] = in ? a.y : 0u; xv[i][2] = in ? a.z : 0u; xv[i][3] = in ? a.w : 0u;
         gv[i][0] = b.x; gv[i][1] = b.y; gv[i][2] = b.z; gv[i][3] = b.w;
     }
-    SquareSum acc;
+    float r = 0.0f;
+    if constexpr (KIND == 0) {
+        SquareSum acc;
 #pragma unroll
-    for (int i = 0; i < VPT; ++i)
+        for (int i = 0; i < VPT; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) { acc.add((uint16_t)(xv[i][j] & 0xFFFFu)); acc.add((uint16_t)(xv[i][j] >> 16)); }
-    uint64_t lo, hi;
-    acc.fold(lo, hi);
-    for (int off = 32; off > 0; off >>= 1) {
-        const uint64_t l = (uint64_t)__shfl_xor((unsigned long long)lo, off, 64);
-        const uint64_t h = (uint64_t)__shfl_xor((unsigned long long)hi, off, 64);
-        add128(lo, hi, l, h);
+            for (int j = 0; j < 4; ++j) { acc.add((uint16_t)(xv[i][j] & 0xFFFFu)); acc.add((uint16_t)(xv[i][j] >> 16)); }
+        uint64_t lo, hi;
+        acc.fold(lo, hi);
+        for (int off = 32; off > 0; off >>= 1) {
+            const uint64_t l = (uint64_t)__shfl_xor((unsigned long long)lo, off, 64);
+            const uint64_t h = (uint64_t)__shfl_xor((unsigned long long)hi, off, 64);
+            add128(lo, hi, l, h);
+        }
+        if (lane == 0) { s_lo64[wave] = lo; s_hi64[wave] = hi; }
+        __syncthreads();
+        if (tid == 0) {
+            uint64_t tl = 0, th = 0;
+            for (int w = 0; w < W; ++w) add128(tl, th, s_lo64[w], s_hi64[w]);
+            s_r = inv_rms(tl, th, K, eps);
+        }
+        __syncthreads();
+        r = s_r;
     }
-    if (lane == 0) { s_lo64[wave] = lo; s_hi64[wave] = hi; }
-    __syncthreads();
-    if (tid == 0) {
-        uint64_t tl = 0, th = 0;
-        for (int w = 0; w < W; ++w) add128(tl, th, s_lo64[w], s_hi64[w]);
-        s_r = inv_rms(tl, th, K, eps);
-    }
-    __syncthreads();
-    const float r = s_r;
 
-    // normalized row (kept as binary16 bits in place of x) and its range, 0 included; padding lanes hold zeros
+    // produced row (kept as binary16 bits in place of x) and its range, 0 included; padding lanes hold zeros
     float vmin = 0.0f, vmax = 0.0f;
 #pragma unroll
     for (int i = 0; i < VPT; ++i) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const uint16_t y0 = normalized_half((uint16_t)(xv[i][j] & 0xFFFFu), (uint16_t)(gv[i][j] & 0xFFFFu), r);
-            const uint16_t y1 = normalized_half((uint16_t)(xv[i][j] >> 16), (uint16_t)(gv[i][j] >> 16), r);
+            const uint16_t y0 = produce_half<KIND>((uint16_t)(xv[i][j] & 0xFFFFu), (uint16_t)(gv[i][j] & 0xFFFFu), r);
+            const uint16_t y1 = produce_half<KIND>((uint16_t)(xv[i][j] >> 16), (uint16_t)(gv[i][j] >> 16), r);
             xv[i][j] = (uint32_t)y0 | ((uint32_t)y1 << 16);
             const float f0 = half_to_f32(y0), f1 = half_to_f32(y1);
             vmin = fminf(vmin, fminf(f0, f1));
@@ -168,8 +207,8 @@ __global__ __launch_bounds__(BLOCK) void rmsnorm_quant_rows_kernel(const uint16_
     }
 }
 
-template <int BLOCK>
-__global__ __launch_bounds__(BLOCK) void rmsnorm_quant_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ gamma,
+template <int KIND, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void producer_quant_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ gamma,
                                                               float eps, int q, int K, uint8_t* __restrict__ codes,
                                                               float* __restrict__ scale, int32_t* __restrict__ zero,
                                                               uint16_t* __restrict__ y_out)
@@ -181,27 +220,31 @@ __global__ __launch_bounds__(BLOCK) void rmsnorm_quant_kernel(const uint16_t* __
     const uint16_t* row = x + (size_t)m * K;
     const int qmax = (1 << q) - 1;
 
-    // exact sum of squares (at most K / BLOCK <= 512 terms per thread)
-    SquareSum acc;
-    for (int k = tid; k < K; k += BLOCK) acc.add(row[k]);
-    uint64_t lo, hi;
-    acc.fold(lo, hi);
-    for (int off = 32; off > 0; off >>= 1) {
-        const uint64_t l = (uint64_t)__shfl_xor((unsigned long long)lo, off, 64);
-        const uint64_t h = (uint64_t)__shfl_xor((unsigned long long)hi, off, 64);
-        add128(lo, hi, l, h);
+    const uint16_t* brow = KIND == 0 ? gamma : gamma + (size_t)m * K;
+    float r = 0.0f;
+    if constexpr (KIND == 0) {
+        // exact sum of squares (at most K / BLOCK <= 512 terms per thread)
+        SquareSum acc;
+        for (int k = tid; k < K; k += BLOCK) acc.add(row[k]);
+        uint64_t lo, hi;
+        acc.fold(lo, hi);
+        for (int off = 32; off > 0; off >>= 1) {
+            const uint64_t l = (uint64_t)__shfl_xor((unsigned long long)lo, off, 64);
+            const uint64_t h = (uint64_t)__shfl_xor((unsigned long long)hi, off, 64);
+            add128(lo, hi, l, h);
+        }
+        if (lane == 0) { s_lo64[wave] = lo; s_hi64[wave] = hi; }
+        __syncthreads();
+        if (tid == 0) {
+            uint64_t tl = 0, th = 0;
+            for (int w = 0; w < W; ++w) add128(tl, th, s_lo64[w], s_hi64[w]);
+            s_r = inv_rms(tl, th, K, eps);
+        }
+        __syncthreads();
+        r = s_r;
     }
-    if (lane == 0) { s_lo64[wave] = lo; s_hi64[wave] = hi; }
-    __syncthreads();
-    if (tid == 0) {
-        uint64_t tl = 0, th = 0;
-        for (int w = 0; w < W; ++w) add128(tl, th, s_lo64[w], s_hi64[w]);
-        s_r = inv_rms(tl, th, K, eps);
-    }
-    __syncthreads();
-    const float r = s_r;
 
-    auto normalized = [&](int k) -> uint16_t { return normalized_half(row[k], gamma[k], r); };
+    auto normalized = [&](int k) -> uint16_t { return produce_half<KIND>(row[k], brow[k], r); };
 
     // range of the normalized row (0 included)
     float vmin = 0.0f, vmax = 0.0f;
@@ -238,17 +281,31 @@ __global__ __launch_bounds__(BLOCK) void rmsnorm_quant_kernel(const uint16_t* __
     }
 }
 
-hipError_t launch_rmsnorm_quant(int q, int M, int K, const uint16_t* x, const uint16_t* gamma, float eps, uint8_t* codes,
-                                float* scale, int32_t* zero, uint16_t* y_out, hipStream_t s)
+// KIND 0: b = gamma [K], eps used;  KIND 1: b = up [M,K], eps ignored.
+template <int KIND>
+static hipError_t launch_producer_quant(int q, int M, int K, const uint16_t* a, const uint16_t* b, float eps, uint8_t* codes,
+                                        float* scale, int32_t* zero, uint16_t* y_out, hipStream_t s)
 {
     // rows of whole, 16-byte aligned vectors that fit a workgroup's registers take the fast path
     const bool vec_ok = K % 8 == 0 && K <= 16384 && ((uintptr_t)y_out & 15u) == 0;
-    if (vec_ok && K <= 2048) rmsnorm_quant_rows_kernel<1, 256><<<M, 256, 0, s>>>(x, gamma, eps, q, K, codes, scale, zero, y_out);
-    else if (vec_ok && K <= 4096) rmsnorm_quant_rows_kernel<1, 512><<<M, 512, 0, s>>>(x, gamma, eps, q, K, codes, scale, zero, y_out);
-    else if (vec_ok && K <= 8192) rmsnorm_quant_rows_kernel<2, 512><<<M, 512, 0, s>>>(x, gamma, eps, q, K, codes, scale, zero, y_out);
-    else if (vec_ok) rmsnorm_quant_rows_kernel<4, 512><<<M, 512, 0, s>>>(x, gamma, eps, q, K, codes, scale, zero, y_out);
-    else rmsnorm_quant_kernel<256><<<M, 256, 0, s>>>(x, gamma, eps, q, K, codes, scale, zero, y_out);
+    if (vec_ok && K <= 2048) producer_quant_rows_kernel<KIND, 1, 256><<<M, 256, 0, s>>>(a, b, eps, q, K, codes, scale, zero, y_out);
+    else if (vec_ok && K <= 4096) producer_quant_rows_kernel<KIND, 1, 512><<<M, 512, 0, s>>>(a, b, eps, q, K, codes, scale, zero, y_out);
+    else if (vec_ok && K <= 8192) producer_quant_rows_kernel<KIND, 2, 512><<<M, 512, 0, s>>>(a, b, eps, q, K, codes, scale, zero, y_out);
+    else if (vec_ok) producer_quant_rows_kernel<KIND, 4, 512><<<M, 512, 0, s>>>(a, b, eps, q, K, codes, scale, zero, y_out);
+    else producer_quant_kernel<KIND, 256><<<M, 256, 0, s>>>(a, b, eps, q, K, codes, scale, zero, y_out);
     return hipGetLastError();
+}
+
+hipError_t launch_rmsnorm_quant(int q, int M, int K, const uint16_t* x, const uint16_t* gamma, float eps, uint8_t* codes,
+                                float* scale, int32_t* zero, uint16_t* y_out, hipStream_t s)
+{
+    return launch_producer_quant<0>(q, M, K, x, gamma, eps, codes, scale, zero, y_out, s);
+}
+
+hipError_t launch_silu_mul_quant(int q, int M, int K, const uint16_t* gate, const uint16_t* up, uint8_t* codes, float* scale,
+                                 int32_t* zero, uint16_t* h_out, hipStream_t s)
+{
+    return launch_producer_quant<1>(q, M, K, gate, up, 0.0f, codes, scale, zero, h_out, s);
 }
 
 }  // namespace abq

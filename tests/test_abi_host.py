@@ -216,6 +216,21 @@ def test_rmsnorm_quant_act_rejects():
     assert call(c=A16 + 1) == B.ABQ_ERR_ALIGN
 
 
+def test_silu_mul_quant_act_rejects():
+    lib = B.load()
+
+    def call(q=8, M=1, K=64, g=A16, u=A16, c=A16, s=A16, z=A16, h=None):
+        return lib.abq_silu_mul_quant_act(q, M, K, g, u, c, s, z, h, None)
+
+    assert call(g=None) == B.ABQ_ERR_NULL
+    assert call(u=None) == B.ABQ_ERR_NULL
+    assert call(s=None) == B.ABQ_ERR_NULL
+    assert call(q=9) == B.ABQ_ERR_BITS
+    assert call(K=0) == B.ABQ_ERR_SHAPE
+    assert call(u=A16 + 2) == B.ABQ_ERR_ALIGN
+    assert call(h=A16 + 6) == B.ABQ_ERR_ALIGN
+
+
 def test_unpack_rejects():
     lib = B.load()
     assert lib.abq_unpack_weights(4, 16, 64, B.ABQ_LAYOUT_FIELDS, A16, B.ABQ_LAYOUT_PLANES, A16, None) == B.ABQ_ERR_LAYOUT

@@ -412,6 +412,44 @@ def test_rmsnorm_quant_then_fused_gemm_end_to_end(abq):
     check_against_oracle(c, y.cpu().numpy(), acc.cpu().numpy())
 
 
+@pytest.mark.parametrize("q", [2, 4, 8])
+@pytest.mark.parametrize("M,K", [(1, 11008), (5, 1000), (3, 37), (16, 4096), (2, 13824), (4, 16392), (2, 131072), (3, 8)])
+def test_silu_mul_quant_act_matches_oracle(abq, q, M, K):
+    say("silu quant", q, M, K)
+    rng = np.random.Generator(np.random.PCG64(7000 + 11 * q + K + M))
+    g = (rng.standard_normal((M, K)) * rng.uniform(0.1, 12.0, (M, 1))).astype(np.float16)
+    u = (rng.standard_normal((M, K)) * 3.0).astype(np.float16)
+    g[0, :8] = np.array([0.0, -0.0, 100.0, -100.0, 60000.0, -60000.0, 1e-4, -1e-4], dtype=np.float16)[: min(8, K)]
+    u[0, :8] = np.float16(1.0)                         # (keeps the products of the extreme gates finite)
+    if M > 1:
+        u[1] = 0                                      # a row of zeros: Delta = 1, z = 0
+    h_ref = oracle.silu_mul_half(g, u)
+    codes_ref, scale_ref, zero_ref = oracle.quant_act(h_ref, q)
+    codes, scale, zero, h = abq.abq_silu_mul_quant_act(q, to_dev(torch, g), to_dev(torch, u), want_h=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(h.cpu().numpy().view(np.uint16), h_ref.view(np.uint16))
+    assert np.array_equal(scale.cpu().numpy(), scale_ref)
+    assert np.array_equal(zero.cpu().numpy(), zero_ref)
+    assert np.array_equal(codes.cpu().numpy(), codes_ref)
+    codes2, _, _, none = abq.abq_silu_mul_quant_act(q, to_dev(torch, g), to_dev(torch, u))
+    assert none is None and np.array_equal(codes2.cpu().numpy(), codes_ref)
+
+
+def test_silu_mul_quant_then_down_proj_end_to_end(abq):
+    """gate, up fp16 -> SiLU * up + quantizer (one kernel) -> fused decode matmul on a down_proj shape."""
+    p, q, M, N, K = 2, 8, 2, 300, 11008
+    rng = np.random.Generator(np.random.PCG64(55))
+    g = (rng.standard_normal((M, K)) * 2.0).astype(np.float16)
+    u = (rng.standard_normal((M, K)) * 1.5).astype(np.float16)
+    c = synth.make_case(p, q, M, N, K, seed=56)
+    c.A, c.a_scale, c.a_zero = oracle.quant_act(oracle.silu_mul_half(g, u), q)
+    pw = abq.abq_pack_weights(p, to_dev(torch, c.W), to_dev(torch, c.w_scale), to_dev(torch, c.w_zero), FIELDS)
+    codes, scale, zero, _ = abq.abq_silu_mul_quant_act(q, to_dev(torch, g), to_dev(torch, u))
+    y, acc = abq.abq_gemm_act_codes(p, q, M, N, K, codes, scale, zero, pw, FIELDS, want_acc=True)
+    torch.cuda.synchronize()
+    check_against_oracle(c, y.cpu().numpy(), acc.cpu().numpy())
+
+
 def test_graph_replays_match_eager(abq):
     """The decode entry points captured in one HIP graph (no allocation, no memset inside) and replayed several
     times with new inputs, eager work and synchronizations in between: every replay equals the eager result."""
