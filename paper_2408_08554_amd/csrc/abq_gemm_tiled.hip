@@ -27,6 +27,7 @@ typedef unsigned int u4v __attribute__((ext_vector_type(4)));
 constexpr int kStepK = 256;          // one step = one phase = four 64-k slices
 constexpr int kARow = kStepK;        // LDS row stride (unpadded; the 16-B vectors of a row are XOR-swizzled by the row index)
 
+
 struct TiledParams {
     const u4v* fields[3];
     const int8_t* a_codes;
@@ -37,6 +38,7 @@ struct TiledParams {
     int M, N, K, Kp, nsuper, ntiles;
     int oa, ow;
     int tiles_m, tiles_n;     // workgroup tiles along M and N (1-D grid of tiles_m * tiles_n workgroups)
+    int band_m;               // row blocks per band of the tile order (see the kernel's tile mapping)
 };
 
 // Weights are held one phase (half a super-chunk, 256 k, four 64-k slices) at a time.  A b-bit
@@ -163,13 +165,17 @@ __global__ __launch_bounds__(256, (WD == 4 ? 2 : (NTW <= 2 ? (MT == 4 ? 3 : 2) :
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps the weight addresses scalar
     const int r = lane & 15, G = lane >> 4;
     // Workgroup b runs on XCD b % 8 (round-robin dispatch) and each XCD has its own L2.  Give every
-    // XCD a contiguous run of the tile order, M fastest: the workgroups resident on one XCD then share
-    // a few column blocks of W and all row blocks of A through that L2 instead of each fetching its own.
+    // XCD a contiguous run of the tile order.  The order goes band by band (band_m row blocks of A), and
+    // inside a band column block by column block with M fastest: the workgroups resident on one XCD then
+    // cover band_m row blocks of A times a few column blocks of W and share both through that L2.  A band
+    // of all row blocks would make every XCD stream the whole of A once per handful of column blocks.
     const int nwg = prm.tiles_m * prm.tiles_n;
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     const int per = nwg >> 3, rem = nwg & 7;                     // XCD x owns per + (x < rem) workgroups
     const int vid = xcd * per + min(xcd, rem) + slot;
-    const int m_blk = vid % prm.tiles_m, n_blk = vid / prm.tiles_m;
+    const int band = vid / (prm.band_m * prm.tiles_n), in_band = vid - band * prm.band_m * prm.tiles_n;
+    const int band_rows = min(prm.band_m, prm.tiles_m - band * prm.band_m);
+    const int m_blk = band * prm.band_m + in_band % band_rows, n_blk = in_band / band_rows;
     const int m0 = m_blk * kBM, n0 = n_blk * kBN;
     const int tile0 = n_blk * (kBN / kTileN) + wave * NTW;
 
@@ -395,6 +401,17 @@ hipError_t launch_gemm_tiled(const GemmArgs& g, const ActLayout& A, const Weight
     }
     prm.tiles_m = (g.M + mt * 16 - 1) / (mt * 16);
     prm.tiles_n = (g.N + 64 * ntw - 1) / (64 * ntw);
+    // Bands of equal height.  The workgroups resident on one XCD (about 64) form a band_m x (64 / band_m)
+    // patch of tiles whose L2 fills cost band_m row blocks of A (one byte per element) plus 64 / band_m
+    // column blocks of W (p/8 byte per element): least near band_m = sqrt(8p), and measured so on M = 2048
+    // and 8192 (4 row blocks for p <= 4, 8 above).
+    {
+        static int forced_band = -1;   // tuning override, read once: ABQ_TILED_BAND=<row blocks per band>
+        if (forced_band < 0) { const char* e = getenv("ABQ_TILED_BAND"); forced_band = e ? atoi(e) : 0; }
+        const int cap = forced_band > 0 ? forced_band : (g.p <= 4 ? 4 : 8);
+        const int bands = (prm.tiles_m + cap - 1) / cap;
+        prm.band_m = (prm.tiles_m + bands - 1) / bands;
+    }
     dim3 grid((unsigned)(prm.tiles_m * prm.tiles_n));
     switch (g.p) {
         case 1: return launch_p<1>(prm, ntw, mt, grid, cus, s);
