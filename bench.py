@@ -44,6 +44,8 @@ def build_case(name):
         return synth.config1()
     if name == "c2":
         return synth.config2()
+    if name.startswith("w2star"):   # w2star or w2starm<M>: config 3's shape with bit-balance weights (p = 3 codes, zero-point 2)
+        return synth.config3_bit_balance(int(name.split("m")[1]) if "m" in name else 1)
     if name.startswith("c3"):
         return synth.config3(int(name.split("m")[1]) if "m" in name else 1)
     if name.startswith("c4"):
@@ -272,7 +274,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
-    ap.add_argument("--workload", default="c2", help="c1 | c2 | c3m<M> | c4m<M> | c5:p,q,shape,m | custom:p,q,M,N,K")
+    ap.add_argument("--workload", default="c2", help="c1 | c2 | c3m<M> | w2starm<M> | c4m<M> | c5:p,q,shape,m | custom:p,q,M,N,K")
     ap.add_argument("--mode", default="graph", choices=["graph", "eager"],
                     help="graph: the timed steps are replayed from one captured HIP graph; eager: launched one by one")
     ap.add_argument("--family", default="auto", choices=["auto", "mfma", "bitserial"])

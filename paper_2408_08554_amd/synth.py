@@ -93,6 +93,23 @@ def config5(p: int, q: int, shape_idx: int, m_idx: int) -> Case:
                      name=f"C5 W{p}A{q} M={M} K={K} N={N}")
 
 
+def bit_balance_case(q: int, M: int, N: int, K: int, seed: int, name: str = "") -> Case:
+    """W2* (bit balance, Sec. 3.3): weights on the five levels {-2,-1,0,1,2}.  Five levels need three
+    bits; they are carried as p = 3 codes level + 2 with zero-point 2 in every channel.  Levels are a
+    rounded Gaussian (sigma 0.9) clipped to +-2: symmetric, like the near-normal weights the section
+    describes.  Everything else as in make_case (same draw order)."""
+    c = make_case(3, q, M, N, K, seed, act="gauss" if q == 8 else "uniform", name=name or f"W2*A{q} M={M} {K}->{N}")
+    rng = np.random.Generator(np.random.PCG64(seed + 7))
+    levels = np.clip(np.rint(rng.normal(0.0, 0.9, size=(N, K))), -2, 2).astype(np.int8)
+    c.W = (levels + 2).astype(np.uint8)
+    c.w_zero = np.full(N, 2, dtype=np.int32)
+    return c
+
+
+def config3_bit_balance(M: int) -> Case:
+    return bit_balance_case(8, M, 4096, 11008, case_seed(3, 3, 8, 1, M - 1), name=f"W2*A8 GEMV M={M} 11008->4096")
+
+
 def act_fp16(seed: int, M: int, K: int, outliers: bool = True) -> np.ndarray:
     """fp16 activations for the online quantizer: N(0,1) rows with a per-row gain and a few
     large-magnitude channels (the outlier structure LLM activations are known for)."""

@@ -545,6 +545,18 @@ def test_config3_bitserial(abq):
     check_against_oracle(c, y, acc)
 
 
+@pytest.mark.parametrize("M,N,K,fused", [(1, 4096, 11008, True), (1, 4096, 11008, False), (8, 4096, 11008, True),
+                                          (5, 70, 1000, True), (16, 33, 9000, False), (128, 1000, 2048, False)])
+def test_bit_balance_five_level_weights(abq, M, N, K, fused):
+    # W2* (Sec. 3.3): levels {-2..2} as p = 3 codes with zero-point 2, on the decode and the tiled path
+    c = synth.bit_balance_case(8, M, N, K, seed=777 + M)
+    y, acc = (gpu_gemm_fused(torch, abq, c, FIELDS) if fused else gpu_gemm(torch, abq, c, FIELDS, FIELDS))
+    yref = check_against_oracle(c, y, acc)
+    levels = c.W.astype(np.float64) - 2.0
+    real = ((c.A.astype(np.float64) - c.a_zero[:, None]) * c.a_scale[:, None]) @ (levels * c.w_scale[:, None].astype(np.float64)).T
+    assert np.allclose(yref, real, rtol=1e-12, atol=0)
+
+
 def test_quantize_then_gemm_end_to_end(abq):
     # fp16 activations -> online quantizer -> matmul; the oracle follows the same two steps
     p, q, M, N, K = 4, 8, 4, 64, 2048

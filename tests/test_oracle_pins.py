@@ -389,3 +389,24 @@ def test_silu_mul_closed_forms_and_limits():
     gpos = np.linspace(-1.25, 12.0, 500, dtype=np.float16).reshape(1, 500)
     hp = oracle.silu_mul_half(gpos, np.ones_like(gpos)).astype(np.float64)[0]
     assert np.all(np.diff(hp) >= 0) and abs(oracle.silu_mul_half(np.array([[-1.2785]], dtype=np.float16), np.ones((1, 1), dtype=np.float16))[0, 0] + 0.2785) < 3e-4
+
+
+# ---- bit balance (Sec. 3.3): five weight levels carried as three-bit codes ------------------
+
+def test_bit_balance_levels_equal_three_bit_codes_with_zero_point_two():
+    """W2* weights take the levels {-2..2}.  The engine has no level type: the levels ride as p = 3 codes
+    level + 2 with zero-point 2.  The centered sum over codes must equal the plain integer product with
+    the signed levels, and the dequantised value the real-valued product s_a (A - z_a) . s_w level."""
+    c = synth.bit_balance_case(8, 3, 7, 300, seed=99)
+    levels = c.W.astype(np.int64) - 2
+    assert levels.min() == -2 and levels.max() == 2 and set(np.unique(c.W)) <= {0, 1, 2, 3, 4}
+    assert abs(float(levels.mean())) < 0.1                      # symmetric level histogram
+    direct = (c.A.astype(np.int64) - c.a_zero[:, None]) @ levels.T
+    accc = oracle.acc_centered(c.A, c.W, c.a_zero, c.w_zero)
+    assert np.array_equal(accc, direct)
+    planes = oracle.acc_bitplane(oracle.pack_planes(c.A, 8), oracle.pack_planes(c.W, 3))
+    assert np.array_equal(planes, c.A.astype(np.int64) @ c.W.astype(np.int64).T)
+    y, _ = oracle.dequant(accc, c.a_scale, c.w_scale)
+    real = ((c.A.astype(np.float64) - c.a_zero[:, None]) * c.a_scale[:, None].astype(np.float64)) @ \
+           (levels.astype(np.float64) * c.w_scale[:, None].astype(np.float64)).T
+    assert np.allclose(y, real, rtol=1e-12, atol=0)
