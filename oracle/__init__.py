@@ -106,6 +106,27 @@ def dequant(accc, a_scale, w_scale):
     return y, y16
 
 
+def dequant_grouped(A, W, a_zero, a_scale, w_zero, w_scale_half, gs=128, want_mag=False):
+    """Per-group weight scales / zero-points [N][ceil(K/gs)] (scales as binary16 bit patterns):
+    (double Y, uint16 half bits[, double size of the summed terms])."""
+    A = np.ascontiguousarray(A, dtype=np.uint8)
+    W = np.ascontiguousarray(W, dtype=np.uint8)
+    (M, K), (N, K2) = A.shape, W.shape
+    assert K == K2 and gs >= 1
+    G = (K + gs - 1) // gs
+    a_zero = np.ascontiguousarray(a_zero, dtype=np.int32)
+    a_scale = np.ascontiguousarray(a_scale, dtype=np.float32)
+    w_zero = np.ascontiguousarray(w_zero, dtype=np.int32)
+    w_scale_half = np.ascontiguousarray(w_scale_half, dtype=np.uint16)
+    assert a_zero.shape == (M,) and a_scale.shape == (M,) and w_zero.shape == (N, G) and w_scale_half.shape == (N, G)
+    y = np.empty((M, N), dtype=np.float64)
+    y16 = np.empty((M, N), dtype=np.uint16)
+    mag = np.empty((M, N), dtype=np.float64) if want_mag else None
+    _load().abq_oracle_dequant_grouped(M, N, K, gs, _p(A), _p(W), _p(a_zero), _p(a_scale), _p(w_zero), _p(w_scale_half),
+                                       _p(y), _p(y16), _p(mag) if want_mag else None)
+    return (y, y16, mag) if want_mag else (y, y16)
+
+
 def dequant_flat(accc, a_scale_per_elem, w_scale_per_elem):
     """Same as dequant for a flat list of sampled elements with their own scales."""
     accc = np.ascontiguousarray(accc, dtype=np.int64).reshape(-1)

@@ -154,6 +154,41 @@ void abq_oracle_dequant(int M, int N, const int64_t* accc, const float* a_scale,
     }
 }
 
+/* Per-group weight quantization (Appendix C: the weight row is cut along K into groups of gs
+ * values, e.g. 128, each with its own scale and zero-point; activations stay per token):
+ *   Y[m][n] = a_scale[m] * sum_g w_scale[n][g] * sum_{k in group g} (A[m][k] - az[m]) * (W[n][k] - wz[n][g])
+ * with group g = k / gs (the last group may be short), G = ceil(K / gs) groups per row.  The inner
+ * sums are exact integers; the sum over groups is taken in double in the order g = 0, 1, ...
+ * Group scales are binary16 values (given as bit patterns), the way deployed group formats store them.
+ * y, y16 and mag may be NULL; mag[m][n] = a_scale[m] * sum_g |w_scale[n][g] * inner_g| is the size of
+ * the terms the sum is made of (what a single-precision evaluation's rounding error scales with). */
+static float half_to_float(uint16_t h);
+void abq_oracle_dequant_grouped(int M, int N, int K, int gs, const uint8_t* A, const uint8_t* W,
+                                const int32_t* az, const float* a_scale, const int32_t* wz,
+                                const uint16_t* w_scale_half, double* y, uint16_t* y16, double* mag)
+{
+    const int G = (K + gs - 1) / gs;
+#pragma omp parallel for schedule(static)
+    for (int m = 0; m < M; ++m) {
+        for (int n = 0; n < N; ++n) {
+            double total = 0.0, size = 0.0;
+            for (int g = 0; g < G; ++g) {
+                const int k_end = (g + 1) * gs < K ? (g + 1) * gs : K;
+                int64_t inner = 0;
+                for (int k = g * gs; k < k_end; ++k)
+                    inner += ((int64_t)A[(size_t)m * K + k] - az[m]) * ((int64_t)W[(size_t)n * K + k] - wz[(size_t)n * G + g]);
+                const double term = (double)half_to_float(w_scale_half[(size_t)n * G + g]) * (double)inner;
+                total += term;
+                size += fabs(term);
+            }
+            const double v = (double)a_scale[m] * total;
+            if (y) y[(size_t)m * N + n] = v;
+            if (y16) y16[(size_t)m * N + n] = abq_oracle_half_bits(v);
+            if (mag) mag[(size_t)m * N + n] = fabs((double)a_scale[m]) * size;
+        }
+    }
+}
+
 /* BitPacking (Sec. 3.4 step 1): bit view [R,K,bits] -> [bits,R,K]; plane s holds
  * (code >> s) & 1 (Appendix B).  Each plane row is stored as 32-bit words, bit (k mod 32) of
  * word k/32, zero padded to Kw words (the word order inside a plane is this build's choice,

@@ -110,6 +110,16 @@ def config3_bit_balance(M: int) -> Case:
     return bit_balance_case(8, M, 4096, 11008, case_seed(3, 3, 8, 1, M - 1), name=f"W2*A8 GEMV M={M} 11008->4096")
 
 
+def group_quant_params(c: Case, gs: int = 128):
+    """Per-group weight parameters for case c (Appendix C, group size gs along K): binary16 scales
+    ~ U[0.01, 0.1] as bit patterns [N][G] and zero-points uniform in the code range [N][G], G = ceil(K/gs)."""
+    rng = np.random.Generator(np.random.PCG64(c.seed + 13))
+    G = (c.K + gs - 1) // gs
+    scale = rng.uniform(0.01, 0.1, size=(c.N, G)).astype(np.float16)
+    zero = rng.integers(0, 1 << c.p, size=(c.N, G)).astype(np.int32)
+    return scale.view(np.uint16).copy(), zero
+
+
 def act_fp16(seed: int, M: int, K: int, outliers: bool = True) -> np.ndarray:
     """fp16 activations for the online quantizer: N(0,1) rows with a per-row gain and a few
     large-magnitude channels (the outlier structure LLM activations are known for)."""

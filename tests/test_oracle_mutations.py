@@ -58,6 +58,17 @@ MUTATIONS = {
         ("volatile float h = sg * u;", "volatile float h = sg;"),
     "rmsnorm: low half of the exact sum dropped":
         ("((double)hi * 18446744073709551616.0 + (double)lo) *", "((double)hi * 18446744073709551616.0) *"),
+    "grouped: zero-point of group 0 for every group":
+        ("((int64_t)W[(size_t)n * K + k] - wz[(size_t)n * G + g]);", "((int64_t)W[(size_t)n * K + k] - wz[(size_t)n * G]);"),
+    "grouped: scale of group 0 for every group":
+        ("(double)half_to_float(w_scale_half[(size_t)n * G + g]) * (double)inner;", "(double)half_to_float(w_scale_half[(size_t)n * G]) * (double)inner;"),
+    "grouped: short last group dropped":
+        ("    const int G = (K + gs - 1) / gs;\n#pragma omp parallel for schedule(static)\n    for (int m = 0; m < M; ++m) {\n        for (int n = 0; n < N; ++n) {\n            double total = 0.0, size = 0.0;\n            for (int g = 0; g < G; ++g) {",
+         "    const int G = (K + gs - 1) / gs;\n#pragma omp parallel for schedule(static)\n    for (int m = 0; m < M; ++m) {\n        for (int n = 0; n < N; ++n) {\n            double total = 0.0, size = 0.0;\n            for (int g = 0; g < K / gs; ++g) {"),
+    "grouped: sign of the activation zero-point":
+        ("inner += ((int64_t)A[(size_t)m * K + k] - az[m]) *", "inner += ((int64_t)A[(size_t)m * K + k] + az[m]) *"),
+    "grouped: activation scale of row 0 for every row":
+        ("const double v = (double)a_scale[m] * total;", "const double v = (double)a_scale[0] * total;"),
 }
 
 CHECKS = [
@@ -80,6 +91,9 @@ CHECKS = [
     lambda: pins.test_rmsnorm_invariances_are_bit_exact(),
     lambda: pins.test_silu_mul_matches_float64_definition(),
     lambda: pins.test_silu_mul_closed_forms_and_limits(),
+    lambda: pins.test_grouped_one_group_is_the_per_channel_result(),
+    lambda: pins.test_grouped_equals_dequantise_then_multiply(4, 8, 3, 5, 300, 128),
+    lambda: pins.test_grouped_single_live_group_uses_that_groups_scale_and_zero(),
 ]
 
 

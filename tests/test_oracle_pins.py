@@ -410,3 +410,62 @@ def test_bit_balance_levels_equal_three_bit_codes_with_zero_point_two():
     real = ((c.A.astype(np.float64) - c.a_zero[:, None]) * c.a_scale[:, None].astype(np.float64)) @ \
            (levels.astype(np.float64) * c.w_scale[:, None].astype(np.float64)).T
     assert np.allclose(y, real, rtol=1e-12, atol=0)
+
+
+# ---- per-group weight scales and zero-points (Appendix C) ------------------------------------
+
+def _grouped_case(p, q, M, N, K, seed, gs):
+    c = synth.make_case(p, q, M, N, K, seed=seed)
+    sh, zg = synth.group_quant_params(c, gs)
+    return c, sh, zg
+
+
+def test_grouped_one_group_is_the_per_channel_result():
+    c, sh, zg = _grouped_case(4, 8, 3, 9, 200, 501, gs=256)          # gs >= K: one group per row
+    assert sh.shape == (9, 1)
+    y, y16 = oracle.dequant_grouped(c.A, c.W, c.a_zero, c.a_scale, zg, sh, gs=256)
+    accc = oracle.acc_centered(c.A, c.W, c.a_zero, zg[:, 0])
+    yc, yc16 = oracle.dequant(accc, c.a_scale, sh.view(np.float16)[:, 0].astype(np.float32))
+    assert np.array_equal(y16, yc16) and np.allclose(y, yc, rtol=1e-15, atol=0)
+
+
+def test_grouped_equal_parameters_in_every_group_is_the_per_channel_result():
+    c, sh, zg = _grouped_case(3, 5, 2, 6, 700, 502, gs=128)
+    sh[:] = sh[:, :1]
+    zg[:] = zg[:, :1]
+    y, _ = oracle.dequant_grouped(c.A, c.W, c.a_zero, c.a_scale, zg, sh, gs=128)
+    yc, _ = oracle.dequant(oracle.acc_centered(c.A, c.W, c.a_zero, zg[:, 0]), c.a_scale,
+                           sh.view(np.float16)[:, 0].astype(np.float32))
+    assert np.allclose(y, yc, rtol=1e-13, atol=0)
+
+
+@pytest.mark.parametrize("p,q,M,N,K,gs", [(4, 8, 3, 5, 300, 128), (2, 8, 1, 7, 1024, 128), (8, 8, 2, 3, 129, 128),
+                                          (6, 6, 4, 4, 1000, 64), (1, 1, 2, 2, 513, 128)])
+def test_grouped_equals_dequantise_then_multiply(p, q, M, N, K, gs):
+    """The definition taken the other way round: dequantise every weight with the parameters of ITS group
+    (group of k is k // gs, the last one short), dequantise the activations, multiply as real matrices."""
+    c, sh, zg = _grouped_case(p, q, M, N, K, 503 + K, gs)
+    y, y16, mag = oracle.dequant_grouped(c.A, c.W, c.a_zero, c.a_scale, zg, sh, gs=gs, want_mag=True)
+    gk = np.arange(K) // gs
+    s_real = sh.view(np.float16).astype(np.longdouble)[:, gk]                       # [N][K]
+    w_real = s_real * (c.W.astype(np.longdouble) - zg[:, gk].astype(np.longdouble))
+    a_real = c.a_scale[:, None].astype(np.longdouble) * (c.A.astype(np.longdouble) - c.a_zero[:, None])
+    real = a_real @ w_real.T
+    assert np.all(np.abs(y - real.astype(np.float64)) <= 1e-12 * mag + 1e-300)
+    assert np.all(mag >= np.abs(y) * (1 - 1e-12))
+    assert np.array_equal(y16, np.array([[oracle.half_bits(v) for v in row] for row in y], dtype=np.uint16))
+
+
+def test_grouped_single_live_group_uses_that_groups_scale_and_zero():
+    """Weights equal to their group's zero-point contribute nothing; leave one group live and the result is
+    that group's scale times its integer sum, for a middle group and for the short last one."""
+    c, sh, zg = _grouped_case(4, 8, 2, 5, 300, 504, gs=128)          # groups: 128, 128, 44
+    G = 3
+    for live in range(G):
+        W = np.repeat(zg, 128, axis=1)[:, :300].astype(np.uint8)
+        lo, hi = live * 128, min(live * 128 + 128, 300)
+        W[:, lo:hi] = c.W[:, lo:hi]
+        y, _ = oracle.dequant_grouped(c.A, W, c.a_zero, c.a_scale, zg, sh, gs=128)
+        inner = (c.A[:, lo:hi].astype(np.int64) - c.a_zero[:, None]) @ (W[:, lo:hi].astype(np.int64) - zg[:, live:live + 1]).T
+        expect = c.a_scale[:, None].astype(np.float64) * sh.view(np.float16)[:, live].astype(np.float64)[None, :] * inner
+        assert np.allclose(y, expect, rtol=1e-15, atol=0)
