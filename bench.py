@@ -60,14 +60,17 @@ def build_case(name):
     raise SystemExit(f"unknown workload {name}")
 
 
-def cpu_baseline(c, budget_s):
+def cpu_baseline(c, budget_s, group_params=None):
     """The oracle as it stands, on the host cores, repeated over the same workload."""
     import oracle
     from paper_2408_08554_amd import metrics
     reps, t0 = 0, time.perf_counter()
     while True:
-        accc = oracle.acc_centered(c.A, c.W, c.a_zero, c.w_zero)
-        oracle.dequant(accc, c.a_scale, c.w_scale)
+        if group_params is not None:
+            oracle.dequant_grouped(c.A, c.W, c.a_zero, c.a_scale, group_params[1], group_params[0], gs=128)
+        else:
+            accc = oracle.acc_centered(c.A, c.W, c.a_zero, c.w_zero)
+            oracle.dequant(accc, c.a_scale, c.w_scale)
         reps += 1
         el = time.perf_counter() - t0
         if el >= budget_s or reps >= 100000:
@@ -283,6 +286,8 @@ def main():
     ap.add_argument("--rotate-gib", type=float, default=1.0, help="total size of the rotating weight buffers")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="time budget of the cpu_baseline leg (0 = skip)")
     ap.add_argument("--no-check", action="store_true")
+    ap.add_argument("--g128", action="store_true",
+                    help="per-group weight scales and zero-points (groups of 128 along K, Appendix C) on the workload's shape")
     ap.add_argument("--grouped-steps", type=int, default=200,
                     help="launches of the grouped decoder-block leg reported beside the main workload (0 = skip)")
     args = ap.parse_args()
@@ -309,11 +314,20 @@ def main():
     c = build_case(args.workload)
     p, q, M, N, K = c.p, c.q, c.M, c.N, c.K
     layout = {"auto": abq.ABQ_LAYOUT_FIELDS, "mfma": abq.ABQ_LAYOUT_FIELDS, "bitserial": abq.ABQ_LAYOUT_PLANES}[args.family]
+    wl = layout   # layout value of the weight blob
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
     # offline: pack the weights once, then replicate the blob into the rotation set
     w_codes, w_scale, w_zero = dev(c.W), dev(c.w_scale), dev(c.w_zero)
-    blob0 = abq.abq_pack_weights(p, w_codes, w_scale, w_zero, layout)
+    if args.g128:
+        from paper_2408_08554_amd import synth
+        assert layout == abq.ABQ_LAYOUT_FIELDS, "--g128 runs on the int8-MFMA family"
+        g_scale_half, g_zero = synth.group_quant_params(c)
+        wl = abq.ABQ_LAYOUT_FIELDS_G128
+        blob0 = abq.abq_pack_weights_g128(p, w_codes, dev(g_scale_half.view(np.float16)), dev(g_zero))
+        c.name += " g128"
+    else:
+        blob0 = abq.abq_pack_weights(p, w_codes, w_scale, w_zero, layout)
     blob_bytes = blob0.numel()
     R = max(2, int(np.ceil(args.rotate_gib * 2 ** 30 / blob_bytes)))
     R = min(R, max(2, args.steps))
@@ -330,26 +344,53 @@ def main():
     ws_bytes = abq.abq_gemm_workspace_bytes(p, q, M, N, K)
     ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
 
-    fused_ws_bytes = abq.abq_gemm_act_codes_workspace_bytes(p, q, M, N, K, layout)
+    fused_ws_bytes = abq.abq_gemm_act_codes_workspace_bytes(p, q, M, N, K, wl)
     fused = args.step == "fused" or (args.step == "auto" and fused_ws_bytes == 0)
     fws = torch.empty(max(fused_ws_bytes, 16), dtype=torch.uint8, device="cuda")
 
     def two_step(i):
         abq.abq_pack_act_codes(q, a_codes, a_scale, a_zero, layout, out=pa)
-        abq.abq_gemm(p, q, M, N, K, pa, layout, blobs[i % R], layout, y=y, workspace=ws)
+        abq.abq_gemm(p, q, M, N, K, pa, layout, blobs[i % R], wl, y=y, workspace=ws)
 
     def fused_step(i):
-        abq.abq_gemm_act_codes(p, q, M, N, K, a_codes, a_scale, a_zero, blobs[i % R], layout, y=y, workspace=fws)
+        abq.abq_gemm_act_codes(p, q, M, N, K, a_codes, a_scale, a_zero, blobs[i % R], wl, y=y, workspace=fws)
 
     def gemm_alone(i):
-        abq.abq_gemm(p, q, M, N, K, pa, layout, blobs[i % R], layout, y=y, workspace=ws)
+        abq.abq_gemm(p, q, M, N, K, pa, layout, blobs[i % R], wl, y=y, workspace=ws)
 
     step = fused_step if fused else two_step
     # the kernel the roofline prices: the one launch of the fused step, else the matmul of the two-call step
     gemm_only = fused_step if fused and fused_ws_bytes == 0 else gemm_alone
 
     # parity on the buffers that are timed (first and last rotation slot)
-    if not args.no_check:
+    if not args.no_check and args.g128:
+        # group-scaled weights: sampled channels (all rows up to 16) against the oracle's definition; the bound is the
+        # binary32 accumulation over G groups (see the parity tests) on top of the fp16 tolerance
+        import oracle
+        abq.abq_pack_act_codes(q, a_codes, a_scale, a_zero, layout, out=pa)
+        rng = np.random.Generator(np.random.PCG64(7))
+        ns = np.unique(rng.integers(0, N, 256))
+        ms = np.arange(M) if M <= 16 else np.unique(rng.integers(0, M, 16))
+        G = (K + 127) // 128
+        yref, _, mag = oracle.dequant_grouped(c.A[ms], c.W[ns], c.a_zero[ms], c.a_scale[ms], g_zero[ns], g_scale_half[ns],
+                                              gs=128, want_mag=True)
+        pad = np.zeros((len(ns), G * 128), dtype=np.int64)
+        pad[:, :K] = c.W[ns].astype(np.int64) - np.repeat(g_zero[ns], 128, axis=1)[:, :K]
+        t_abs = np.abs(g_scale_half[ns].view(np.float16).astype(np.float64) * pad.reshape(len(ns), G, 128).sum(axis=2)).sum(axis=1)
+        za = np.maximum(np.abs(c.a_zero[ms]), np.abs(c.a_zero[ms] - 128)).astype(np.float64)
+        size = mag + 2 * np.abs(c.a_scale[ms].astype(np.float64))[:, None] * za[:, None] * t_abs[None, :] + np.abs(yref)
+        ytol = np.maximum(np.maximum(1e-2 * np.abs(yref), 2.0 ** (np.floor(np.log2(np.maximum(np.abs(yref), 2.0 ** -14))) - 9)),
+                          2.0 ** -24) + (G + 12) * 2.0 ** -24 * size
+        for slot in (0, R - 1):
+            for name in ("two calls", "fused"):
+                if name == "fused":
+                    abq.abq_gemm_act_codes(p, q, M, N, K, a_codes, a_scale, a_zero, blobs[slot], wl, y=y, workspace=fws)
+                else:
+                    abq.abq_gemm(p, q, M, N, K, pa, layout, blobs[slot], wl, y=y, workspace=ws)
+                torch.cuda.synchronize()
+                yerr = np.abs(y.cpu().numpy()[np.ix_(ms, ns)].astype(np.float64) - yref)
+                assert np.all(yerr <= ytol), f"fp16 parity failure ({name}, g128) on rotation slot {slot}"
+    elif not args.no_check:
         import oracle
         acc = torch.empty((M, N), dtype=torch.int32, device="cuda")
         abq.abq_pack_act_codes(q, a_codes, a_scale, a_zero, layout, out=pa)
@@ -411,6 +452,8 @@ def main():
     sec_per_step = wall / args.steps
     gemm_s = ev_gemm / args.steps
     alg_bytes = metrics.gemm_algorithmic_bytes(p, q, M, N, K)
+    if args.g128:
+        alg_bytes += 3 * N * ((K + 127) // 128)   # a binary16 scale and a one-byte zero-point per channel and group
     hbm_bound = M <= 39 * p
     if hbm_bound:
         achieved = alg_bytes / gemm_s / 1e9
@@ -446,12 +489,12 @@ def main():
     roof["frac_of_measured_peak"] = achieved / roof["measured_peak"]
     if hbm_bound:   # a plain read of the same number of bytes in a launch of its own: the floor for this size
         roof["frac_of_plain_read_same_size"] = peaks["stream_read_workload_size"]["us"] / (gemm_s * 1e6)
-    if args.grouped_steps > 0 and M <= 16:
+    if args.grouped_steps > 0 and M <= 16 and not args.g128:
         del pool, blobs
         torch.cuda.empty_cache()
         out["grouped_decoder_block"] = bench_grouped(p, q, M, args.grouped_steps, 20, args.rotate_gib, not args.no_check)
     if args.cpu_seconds > 0:
-        out["cpu_baseline"] = cpu_baseline(c, args.cpu_seconds)
+        out["cpu_baseline"] = cpu_baseline(c, args.cpu_seconds, (g_scale_half, g_zero) if args.g128 else None)
     print(json.dumps(out), flush=True)
 
 

@@ -58,6 +58,7 @@ extern "C" {
 #define ABQ_LAYOUT_PLANES  1
 #define ABQ_LAYOUT_FIELDS  2
 #define ABQ_LAYOUT_BOTH    3
+#define ABQ_LAYOUT_FIELDS_G128 4   /* field-packed weights with a scale and zero-point per 128 values of K (abq_pack_weights_g128) */
 /* abq_gemm only: OR one of these onto a BOTH layout to force a kernel family (A/B timing). */
 #define ABQ_USE_PLANES     0x10
 #define ABQ_USE_FIELDS     0x20
@@ -85,6 +86,26 @@ size_t abq_packed_weight_bytes(int p, int N, int K, int layout);
 int abq_pack_weights(int p, int N, int K,
                      const uint8_t* w_codes, const float* w_scale, const int32_t* w_zero,
                      int layout, void* packed_out, size_t packed_bytes, void* stream);
+
+/* Per-group weight quantization (Appendix C: the method is orthogonal to group-wise weight scales; the
+ * group runs along K and holds 128 values, "g128").  The blob is field-packed like ABQ_LAYOUT_FIELDS and
+ * carries, per output channel and group, a binary16 scale and an integer zero-point:
+ *   Y[m,n] = half_rne( a_scale[m] · sum_g w_scale[n,g] · sum_{k in group g} (A[m,k] − az[m])·(W[n,k] − wz[n,g]) )
+ * with G = ceil(K/128) groups per channel, the last one short when 128 does not divide K.  The inner
+ * sums are exact integers; the sum over groups is accumulated in binary32 (one rounding per group), so
+ * the result carries a relative error of about G·2^-24 of the summed terms' size before the final
+ * rounding to binary16.
+ *   w_codes      [N,K] uint8, values < 2^p
+ *   w_scale_fp16 [N,G] binary16 bit patterns (the precision deployed group formats store)
+ *   w_zero       [N,G] int32 in 0..2^p−1
+ *   packed_out / packed_bytes: at least abq_packed_weight_bytes(p, N, K, ABQ_LAYOUT_FIELDS_G128) bytes.
+ * abq_gemm, abq_gemm_act_codes and abq_gemm_grouped take such a blob with w_layout =
+ * ABQ_LAYOUT_FIELDS_G128.  They run it on the streaming (decode) kernel for every M, one pass over the
+ * weights per 16 rows of A, and cannot return the raw integer accumulator: acc_i32 must be NULL
+ * (ABQ_ERR_LAYOUT otherwise).  abq_pack_weights rejects this layout value (ABQ_ERR_LAYOUT). */
+int abq_pack_weights_g128(int p, int N, int K,
+                          const uint8_t* w_codes, const uint16_t* w_scale_fp16, const int32_t* w_zero,
+                          void* packed_out, size_t packed_bytes, void* stream);
 
 /* Test hook: recovers the codes from a blob.  `which` is ABQ_LAYOUT_PLANES or ABQ_LAYOUT_FIELDS
  * and selects the representation to decode (it must be present in the blob).

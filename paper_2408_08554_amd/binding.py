@@ -16,6 +16,7 @@ ABQ_OK = 0
 ABQ_ERR_NULL, ABQ_ERR_BITS, ABQ_ERR_SHAPE, ABQ_ERR_ALIGN = -1, -2, -3, -4
 ABQ_ERR_SIZE, ABQ_ERR_LAYOUT, ABQ_ERR_HIP = -5, -6, -7
 ABQ_LAYOUT_AUTO, ABQ_LAYOUT_PLANES, ABQ_LAYOUT_FIELDS, ABQ_LAYOUT_BOTH = 0, 1, 2, 3
+ABQ_LAYOUT_FIELDS_G128 = 4
 ABQ_USE_PLANES, ABQ_USE_FIELDS = 0x10, 0x20
 ABQ_MAX_K = 131072
 
@@ -27,6 +28,7 @@ _SIGNATURES = {
     "abq_last_hip_error": (_c.c_int, []),
     "abq_packed_weight_bytes": (_c.c_size_t, [_c.c_int] * 4),
     "abq_pack_weights": (_c.c_int, [_c.c_int] * 3 + [_c.c_void_p] * 3 + [_c.c_int, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
+    "abq_pack_weights_g128": (_c.c_int, [_c.c_int] * 3 + [_c.c_void_p] * 3 + [_c.c_void_p, _c.c_size_t, _c.c_void_p]),
     "abq_unpack_weights": (_c.c_int, [_c.c_int] * 4 + [_c.c_void_p, _c.c_int, _c.c_void_p, _c.c_void_p]),
     "abq_packed_act_bytes": (_c.c_size_t, [_c.c_int] * 4),
     "abq_quant_pack_act": (_c.c_int, [_c.c_int] * 3 + [_c.c_void_p, _c.c_int, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
@@ -125,6 +127,21 @@ def abq_pack_weights(p, w_codes, w_scale, w_zero, layout=ABQ_LAYOUT_AUTO, out=No
         out = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=w_codes.device)
     _check(lib.abq_pack_weights(p, N, K, _ptr(w_codes), _ptr(w_scale), _ptr(w_zero), layout, _ptr(out), out.numel(),
                                 _stream()), "abq_pack_weights")
+    return out
+
+
+def abq_pack_weights_g128(p, w_codes, w_scale_fp16, w_zero, out=None):
+    """w_codes uint8 [N,K], w_scale_fp16 float16 [N,G], w_zero int32 [N,G] (device), G = ceil(K/128) -> packed blob
+    for w_layout = ABQ_LAYOUT_FIELDS_G128."""
+    lib = load()
+    N, K = w_codes.shape
+    G = (K + 127) // 128
+    _dev(w_codes, torch.uint8), _dev(w_scale_fp16, torch.float16, (N, G)), _dev(w_zero, torch.int32, (N, G))
+    nbytes = lib.abq_packed_weight_bytes(p, N, K, ABQ_LAYOUT_FIELDS_G128)
+    if out is None:
+        out = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=w_codes.device)
+    _check(lib.abq_pack_weights_g128(p, N, K, _ptr(w_codes), _ptr(w_scale_fp16), _ptr(w_zero), _ptr(out), out.numel(),
+                                     _stream()), "abq_pack_weights_g128")
     return out
 
 

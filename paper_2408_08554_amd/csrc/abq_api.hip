@@ -25,6 +25,7 @@ static bool layout_bits(int layout, bool* planes, bool* fields)
         case ABQ_LAYOUT_FIELDS: *planes = false; *fields = true; return true;
         case ABQ_LAYOUT_PLANES: *planes = true; *fields = false; return true;
         case ABQ_LAYOUT_BOTH: *planes = true; *fields = true; return true;
+        case ABQ_LAYOUT_FIELDS_G128: *planes = false; *fields = true; return true;
         default: return false;
     }
 }
@@ -34,6 +35,7 @@ bool make_weight_layout(int p, int N, int K, int layout, WeightLayout* L)
     if (p < 1 || p > 8 || N < 1 || K < 1 || K > ABQ_MAX_K) return false;
     if (!layout_bits(layout, &L->has_planes, &L->has_fields)) return false;
     L->p = p; L->N = N; L->K = K; L->layout = layout;
+    L->g128 = layout == ABQ_LAYOUT_FIELDS_G128;
     L->NT = (N + kTileN - 1) / kTileN;
     L->Kw = (K + 127) / 128 * 4;
     L->ngroups = group_count(p);
@@ -55,6 +57,11 @@ bool make_weight_layout(int p, int N, int K, int layout, WeightLayout* L)
             off = align_up(off + (size_t)L->NT * L->chunks[g] * 1024, 256);
         }
     }
+    L->off_gparams = 0;
+    if (L->g128) {
+        L->off_gparams = off;
+        off = align_up(off + (size_t)L->NT * ((K + kSuperK - 1) / kSuperK) * 256, 256);
+    }
     L->total = off;
     return true;
 }
@@ -62,7 +69,7 @@ bool make_weight_layout(int p, int N, int K, int layout, WeightLayout* L)
 bool make_act_layout(int q, int M, int K, int layout, ActLayout* L)
 {
     if (q < 1 || q > 8 || M < 1 || K < 1 || K > ABQ_MAX_K) return false;
-    if (!layout_bits(layout, &L->has_planes, &L->has_fields)) return false;
+    if (layout == ABQ_LAYOUT_FIELDS_G128 || !layout_bits(layout, &L->has_planes, &L->has_fields)) return false;
     L->q = q; L->M = M; L->K = K; L->layout = layout;
     L->Kp = (K + kSuperK - 1) / kSuperK * kSuperK;
     L->Kw = (K + 127) / 128 * 4;
@@ -135,10 +142,22 @@ int abq_pack_weights(int p, int N, int K, const uint8_t* w_codes, const float* w
     if (!w_codes || !w_scale || !w_zero || !packed_out) return ABQ_ERR_NULL;
     if (int e = check_bits_shape(p, N, K)) return e;
     WeightLayout L;
-    if (!make_weight_layout(p, N, K, layout, &L)) return ABQ_ERR_LAYOUT;
+    if (!make_weight_layout(p, N, K, layout, &L) || L.g128) return ABQ_ERR_LAYOUT;
     if (misaligned(w_codes) || misaligned(w_scale) || misaligned(w_zero) || misaligned(packed_out)) return ABQ_ERR_ALIGN;
     if (packed_bytes < L.total) return ABQ_ERR_SIZE;
     return hip_status(launch_pack_weights(L, w_codes, w_scale, w_zero, (uint8_t*)packed_out, (hipStream_t)stream));
+}
+
+int abq_pack_weights_g128(int p, int N, int K, const uint8_t* w_codes, const uint16_t* w_scale_fp16, const int32_t* w_zero,
+                          void* packed_out, size_t packed_bytes, void* stream)
+{
+    if (!w_codes || !w_scale_fp16 || !w_zero || !packed_out) return ABQ_ERR_NULL;
+    if (int e = check_bits_shape(p, N, K)) return e;
+    WeightLayout L;
+    if (!make_weight_layout(p, N, K, ABQ_LAYOUT_FIELDS_G128, &L)) return ABQ_ERR_LAYOUT;
+    if (misaligned(w_codes) || misaligned(w_scale_fp16) || misaligned(w_zero) || misaligned(packed_out)) return ABQ_ERR_ALIGN;
+    if (packed_bytes < L.total) return ABQ_ERR_SIZE;
+    return hip_status(launch_pack_weights_g128(L, w_codes, w_scale_fp16, w_zero, (uint8_t*)packed_out, (hipStream_t)stream));
 }
 
 int abq_unpack_weights(int p, int N, int K, int layout, const void* packed, int which, uint8_t* w_codes_out, void* stream)
@@ -275,10 +294,12 @@ int abq_gemm(int p, int q, int M, int N, int K, const void* packed_act, int a_la
         return ABQ_ERR_ALIGN;
     const size_t need = abq_gemm_workspace_bytes(p, q, M, N, K);
     if (need > 0 && (!workspace || workspace_bytes < need)) return workspace ? ABQ_ERR_SIZE : ABQ_ERR_NULL;
+    if (W.g128 && (acc_i32 || force == ABQ_USE_PLANES)) return ABQ_ERR_LAYOUT;
 
     GemmArgs g{p, q, M, N, K, (const uint8_t*)packed_act, nullptr, nullptr, nullptr, (const uint8_t*)packed_w, y_fp16, acc_i32,
                workspace, workspace_bytes};
     hipStream_t s = (hipStream_t)stream;
+    if (W.g128) return hip_status(launch_gemm_skinny(g, A, W, s));   // every M: one pass over W per 16 rows
     if (!choose_fields(can_fields, can_planes, force, p, q, M, N)) return hip_status(launch_gemm_bitserial(g, A, W, s));
     if (streaming_shape(M, N)) return hip_status(launch_gemm_skinny(g, A, W, s));
     return hip_status(launch_gemm_tiled(g, A, W, s));
@@ -289,6 +310,7 @@ int abq_gemm(int p, int q, int M, int N, int K, const void* packed_act, int a_la
 static bool fused_act_direct(const WeightLayout& W, int force, int p, int q, int M, int N, int K)
 {
     if (!W.has_fields || force == ABQ_USE_PLANES) return false;
+    if (W.g128) return K % 16 == 0;
     if (!choose_fields(true, W.has_planes, force, p, q, M, N)) return false;
     return streaming_shape(M, N) && K % 16 == 0;
 }
@@ -301,7 +323,7 @@ size_t abq_gemm_act_codes_workspace_bytes(int p, int q, int M, int N, int K, int
     WeightLayout W;
     if (force == (ABQ_USE_PLANES | ABQ_USE_FIELDS) || !make_weight_layout(p, N, K, w_layout, &W)) return 0;
     if (fused_act_direct(W, force, p, q, M, N, K)) return 0;
-    return abq_packed_act_bytes(q, M, K, w_layout) + abq_gemm_workspace_bytes(p, q, M, N, K);
+    return abq_packed_act_bytes(q, M, K, W.g128 ? ABQ_LAYOUT_FIELDS : w_layout) + abq_gemm_workspace_bytes(p, q, M, N, K);
 }
 
 int abq_gemm_act_codes(int p, int q, int M, int N, int K, const uint8_t* a_codes, const float* a_scale,
@@ -319,6 +341,7 @@ int abq_gemm_act_codes(int p, int q, int M, int N, int K, const uint8_t* a_codes
     if (misaligned(a_codes) || misaligned(a_scale) || misaligned(a_zero) || misaligned(packed_w) || misaligned(y_fp16) ||
         misaligned(acc_i32) || misaligned(workspace))
         return ABQ_ERR_ALIGN;
+    if (W.g128 && acc_i32) return ABQ_ERR_LAYOUT;
     hipStream_t s = (hipStream_t)stream;
     if (fused_act_direct(W, force, p, q, M, N, K)) {
         ActLayout A;
@@ -327,12 +350,13 @@ int abq_gemm_act_codes(int p, int q, int M, int N, int K, const uint8_t* a_codes
         return hip_status(launch_gemm_skinny(g, A, W, s));
     }
     // Otherwise the two steps run back to back, the packed activations living in the caller's workspace.
-    const size_t act_bytes = abq_packed_act_bytes(q, M, K, base_layout);
+    const int act_layout = W.g128 ? ABQ_LAYOUT_FIELDS : base_layout;
+    const size_t act_bytes = abq_packed_act_bytes(q, M, K, act_layout);
     const size_t need = act_bytes + abq_gemm_workspace_bytes(p, q, M, N, K);
     if (!workspace) return ABQ_ERR_NULL;
     if (workspace_bytes < need) return ABQ_ERR_SIZE;
-    if (int e = abq_pack_act_codes(q, M, K, a_codes, a_scale, a_zero, base_layout, workspace, act_bytes, stream)) return e;
-    return abq_gemm(p, q, M, N, K, workspace, base_layout, packed_w, w_layout, y_fp16, acc_i32,
+    if (int e = abq_pack_act_codes(q, M, K, a_codes, a_scale, a_zero, act_layout, workspace, act_bytes, stream)) return e;
+    return abq_gemm(p, q, M, N, K, workspace, act_layout, packed_w, w_layout, y_fp16, acc_i32,
                     (uint8_t*)workspace + act_bytes, workspace_bytes - act_bytes, stream);
 }
 
@@ -364,7 +388,7 @@ static int prepare_group(int p, int q, int M, int count, const abq_problem* pr, 
     // one launch only where every problem would go to the streaming kernel of the int8-MFMA family anyway
     *fits = force != ABQ_USE_PLANES && M <= kSkinnyMaxM;
     for (int i = 0; i < count && *fits; ++i)
-        *fits = choose_fields(W[i].has_fields && (*raw || A[i].has_fields), W[i].has_planes && !*raw && A[i].has_planes, force, p, q, M, pr[i].N);
+        *fits = !W[i].g128 && choose_fields(W[i].has_fields && (*raw || A[i].has_fields), W[i].has_planes && !*raw && A[i].has_planes, force, p, q, M, pr[i].N);
     if (*fits) *fits = gemm_grouped_fits(M, count, args, A, W, waves, lds);
     return ABQ_OK;
 }

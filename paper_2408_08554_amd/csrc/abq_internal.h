@@ -38,12 +38,16 @@ static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; 
 //   [header 256 B][wparams N x {int32 wsum, float scale, int32 zero, int32 0}]
 //   [planes  uint32 [p][N][Kw]]                               if PLANES/BOTH   (Kw = ceil(K/128)*4)
 //   [group g: uint4 [NT][C_g][64 lanes]] for each group       if FIELDS/BOTH   (NT = ceil(N/16), C_g = b_g*ceil(K/512))
+//   [uint4 [NT][ceil(K/512)][16 channels]]                    if FIELDS_G128: per channel of a tile and super-chunk of 512 k
+//                                                             the four 128-k groups' binary16 scales (8 B), their zero-points
+//                                                             as int8 (zero - 128 when p == 8; 4 B), 4 B unused.  wparams then
+//                                                             holds {0, t[n], 0, 0} with t[n] = sum_g scale*(sum_k (w - zero)).
 struct WeightLayout {
     int p, N, K, layout;
-    bool has_planes, has_fields;
+    bool has_planes, has_fields, g128;
     int ngroups, gb[3], gs[3], chunks[3];
     int NT, Kw;
-    size_t off_params, off_planes, off_fields[3], total;
+    size_t off_params, off_planes, off_fields[3], off_gparams, total;
 };
 
 // Packed-activation blob:
@@ -63,6 +67,8 @@ bool make_act_layout(int q, int M, int K, int layout, ActLayout* out);
 // ---- kernel launchers (each returns the hipError_t of the launch) --------------------------
 hipError_t launch_pack_weights(const WeightLayout& L, const uint8_t* w_codes, const float* w_scale,
                                const int32_t* w_zero, uint8_t* blob, hipStream_t s);
+hipError_t launch_pack_weights_g128(const WeightLayout& L, const uint8_t* w_codes, const uint16_t* w_scale_half,
+                                    const int32_t* w_zero, uint8_t* blob, hipStream_t s);
 hipError_t launch_unpack_weights(const WeightLayout& L, const uint8_t* blob, int which, uint8_t* out, hipStream_t s);
 hipError_t launch_pack_act_codes(const ActLayout& L, const uint8_t* codes, const float* a_scale,
                                  const int32_t* a_zero, uint8_t* blob, hipStream_t s);

@@ -121,6 +121,48 @@ __global__ void row_params_kernel(const uint8_t* __restrict__ codes, int bits, i
     if (lane == 0) out[row] = RowParams{s, scale[row], zero[row], 0};
 }
 
+// ---- per-group weight parameters (groups of 128 along K, Appendix C) ------------------------------
+// One thread per (tile, super-chunk, channel): the 16-byte record the streaming kernel loads with the
+// super-chunk's weights.  Groups past ceil(K/128) and channels past N get scale 0 and zero-point 0.
+__global__ void group_params_kernel(const uint16_t* __restrict__ scale_half, const int32_t* __restrict__ zero, int N, int G,
+                                    int nsuper, int NT, int ow, uint4* __restrict__ out)
+{
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (size_t)NT * nsuper * 16) return;
+    const int c = (int)(idx & 15), sc = (int)((idx >> 4) % nsuper), nt = (int)((idx >> 4) / nsuper);
+    const int n = nt * kTileN + c;
+    uint32_t sh[4], zz = 0;
+    for (int j = 0; j < 4; ++j) {
+        const int g = sc * 4 + j;
+        const bool live = n < N && g < G;
+        sh[j] = live ? scale_half[(size_t)n * G + g] : 0u;
+        const int z = live ? zero[(size_t)n * G + g] - ow : 0;
+        zz |= ((uint32_t)z & 0xFFu) << (8 * j);
+    }
+    out[idx] = uint4{sh[0] | (sh[1] << 16), sh[2] | (sh[3] << 16), zz, 0u};
+}
+
+// t[n] = sum_g scale[n][g] * sum_{k in group g} (w[n][k] - zero[n][g]): what the activation zero-point multiplies
+// in the epilogue.  One wave per channel, lanes over groups, the sum in double in a fixed butterfly order.
+__global__ void group_tail_kernel(const uint8_t* __restrict__ codes, int bits, int N, int K, int G,
+                                  const uint16_t* __restrict__ scale_half, const int32_t* __restrict__ zero,
+                                  RowParams* __restrict__ out)
+{
+    const int row = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (row >= N) return;
+    const uint32_t mask = (1u << bits) - 1u;
+    double acc = 0.0;
+    for (int g = lane; g < G; g += 64) {
+        const int k_end = min(g * 128 + 128, K), z = zero[(size_t)row * G + g];
+        int32_t s = 0;
+        for (int k = g * 128; k < k_end; ++k) s += (int32_t)(codes[(size_t)row * K + k] & mask) - z;
+        acc += (double)__half2float(__ushort_as_half(scale_half[(size_t)row * G + g])) * (double)s;
+    }
+    for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
+    if (lane == 0) out[row] = RowParams{0, (float)acc, 0, 0};
+}
+
 // ---- activation rows: codes (given, or quantized here) -> int8 rows + 1-bit planes ---------------
 // One workgroup per token m.  Thread units of 32 consecutive k: 32 codes -> two uint4 of int8
 // (a - oa, oa = 128 when q == 8 so that the value fits the signed MFMA operand; zero beyond K
@@ -382,6 +424,23 @@ hipError_t launch_pack_weights(const WeightLayout& L, const uint8_t* w, const fl
                                                                       (uint32_t*)(blob + L.off_fields[g]));
         }
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_pack_weights_g128(const WeightLayout& L, const uint8_t* w, const uint16_t* w_scale_half, const int32_t* w_zero,
+                                    uint8_t* blob, hipStream_t s)
+{
+    const int G = (L.K + 127) / 128, nsuper = (L.K + kSuperK - 1) / kSuperK;
+    write_header_kernel<<<1, 64, 0, s>>>((uint32_t*)blob, kMagicW, L.p, L.N, L.K, L.layout);
+    group_tail_kernel<<<blocks_for(L.N, 4), 256, 0, s>>>(w, L.p, L.N, L.K, G, w_scale_half, w_zero, (RowParams*)(blob + L.off_params));
+    for (int g = 0; g < L.ngroups; ++g) {
+        const size_t dwords = (size_t)L.NT * L.chunks[g] * 256;
+        pack_fields_kernel<<<blocks_for(dwords, 256), 256, 0, s>>>(w, L.N, L.K, L.gb[g], L.gs[g], L.chunks[g], dwords,
+                                                                  (uint32_t*)(blob + L.off_fields[g]));
+    }
+    const size_t records = (size_t)L.NT * nsuper * 16;
+    group_params_kernel<<<blocks_for(records, 256), 256, 0, s>>>(w_scale_half, w_zero, L.N, G, nsuper, L.NT, L.p == 8 ? 128 : 0,
+                                                                (uint4*)(blob + L.off_gparams));
     return hipGetLastError();
 }
 

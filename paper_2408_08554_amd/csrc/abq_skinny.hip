@@ -99,7 +99,8 @@ static int env_int(const char* name)
     return e ? atoi(e) : 0;
 }
 
-static bool pick_plan(int M, int Kp, int ntiles, int cus, size_t stream_bytes, SkinnyPlan* best)
+// one_group: the kernel variant at hand has no K groups (then long K with many rows takes more passes over W).
+static bool pick_plan(int M, int Kp, int ntiles, int cus, size_t stream_bytes, bool one_group, SkinnyPlan* best)
 {
     static const int candidates[] = {8, 7, 6, 5, 4, 2, 1};
     // tuning overrides (read once): ABQ_SKINNY_WAVES=<S> forces the K split, ABQ_SKINNY_KGROUPS=<G> the group count
@@ -120,7 +121,7 @@ static bool pick_plan(int M, int Kp, int ntiles, int cus, size_t stream_bytes, S
                 if (wj < wi) { const int t = order[i]; order[i] = order[j]; order[j] = t; }
             }
         double sc;
-        for (int G = 1; G <= 4; ++G)
+        for (int G = 1; G <= (one_group ? 1 : 4); ++G)
             for (int S : order)
                 if (make_plan(S, G, M, Kp, ntiles, cus, best, &sc) && best->mrows == m16) return true;
         for (int S : order)
@@ -142,13 +143,17 @@ static bool pick_plan(int M, int Kp, int ntiles, int cus, size_t stream_bytes, S
         }
         return ok;
     };
-    if (forced_g > 1 && search(forced_g, forced_g, false, best)) return true;
-    const bool one = search(1, 1, false, best);
-    if (one && best->mrows == m16) return true;
-    SkinnyPlan grouped;
-    if (forced_g <= 0 && search(2, 4, true, &grouped)) { *best = grouped; return true; }
-    if (one) return true;
-    if (forced > 0 || forced_g > 0) { forced = 0; forced_g = 0; return pick_plan(M, Kp, ntiles, cus, stream_bytes, best); }
+    if (one_group) {
+        if (search(1, 1, false, best)) return true;
+    } else {
+        if (forced_g > 1 && search(forced_g, forced_g, false, best)) return true;
+        const bool one = search(1, 1, false, best);
+        if (one && best->mrows == m16) return true;
+        SkinnyPlan grouped;
+        if (forced_g <= 0 && search(2, 4, true, &grouped)) { *best = grouped; return true; }
+        if (one) return true;
+    }
+    if (forced > 0 || forced_g > 0) { forced = 0; forced_g = 0; return pick_plan(M, Kp, ntiles, cus, stream_bytes, one_group, best); }
     return false;
 }
 
@@ -167,6 +172,7 @@ static void fill_operands(SkinnyParams& prm, const GemmArgs& g, const ActLayout&
         prm.a_raw = nullptr; prm.a_scale = nullptr; prm.a_zero = nullptr;
     }
     prm.wparams = (const RowParams*)(g.w_blob + W.off_params);
+    prm.gparams = W.g128 ? (const u4v*)(g.w_blob + W.off_gparams) : nullptr;
     prm.y = g.y;
     prm.acc = g.acc;
     prm.M = g.M; prm.N = g.N; prm.K = g.K; prm.Kp = A.Kp;
@@ -183,7 +189,7 @@ hipError_t launch_gemm_skinny(const GemmArgs& g, const ActLayout& A, const Weigh
     const int nsuper = A.Kp / kSuperK;
     SkinnyPlan pl;
     const size_t stream_bytes = (size_t)g.p * W.NT * 16 * (size_t)A.Kp / 8;
-    if (!pick_plan(g.M, A.Kp, W.NT, cus, stream_bytes, &pl)) return hipErrorInvalidValue;   // cannot happen for K <= ABQ_MAX_K
+    if (!pick_plan(g.M, A.Kp, W.NT, cus, stream_bytes, W.g128, &pl)) return hipErrorInvalidValue;   // cannot happen for K <= ABQ_MAX_K
     const int waves = pl.waves, gx = pl.gx, mrows = pl.mrows;
     // LDS: staged rows of A (all of K, or one K group of it), the epilogue parameters, two reduction buffers
     // of 1 KiB per wave, the partial sums of the K groups

@@ -70,6 +70,9 @@ struct SkinnyParams {
     int col_w, col_s;         // LDS column of (wave, slot) = wave*col_w + slot*col_s  (slot = super-chunk index inside the run)
     int part_off;             // byte offset in LDS of the partial sums [S][nmy_max][256] int32 (kgroups > 1)
     int nmy_max;              // most tiles any workgroup owns
+    // Per-group weight parameters (groups of 128 k; null for per-channel weights): [ntiles][nsuper][16 channels]
+    // records of 16 B = four binary16 scales, four int8 zero-points (already less ow), 4 B unused.
+    const u4v* gparams;
 };
 
 // g * n / G for the few group counts the host uses (constant divisors).
@@ -172,10 +175,12 @@ __device__ __forceinline__ int32_t wave_sum(int32_t v)
 
 // One super-chunk of one tile: P wave loads of 1 KiB.  Every group stores whole super-chunks
 // (chunk count = b * Kp/512), so no load is conditional.
-template <int P>
+template <int P, bool GQ = false>
 __device__ __forceinline__ void load_super(const SkinnyParams& prm, int nsuper, int tile, int sc, int lane, u4v* w)
 {
     using GI = GroupInfo<P>;
+    if constexpr (GQ)   // the super-chunk's group parameters of this lane's channel ride in the ring slot's last entry
+        w[P] = __builtin_nontemporal_load(prm.gparams + ((size_t)tile * nsuper + sc) * 16 + (lane & 15));
 #pragma unroll
     for (int g = 0; g < GI::NG; ++g) {
         const int b = GI::b(g);
@@ -198,6 +203,71 @@ __device__ __forceinline__ void compute_super(const u4v* w, const uint8_t* lds_r
     if constexpr (GI::NG > 2) group_mfma<GI::b(2)>(w + GI::load_base(2), aop, acc + GI::acc_base(2));
 }
 
+// ---- per-group weight parameters: one super-chunk = four groups of 128 k = four pairs of 64-k slices --------
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+template <int B, int T>
+__device__ __forceinline__ v4i unscale4(v4i a)
+{
+    return v4i{field_unscale<B, T>(a.x), field_unscale<B, T>(a.y), field_unscale<B, T>(a.z), field_unscale<B, T>(a.w)};
+}
+// sum_k a*field over the 128 k of pair J for one plane group of width B (fresh accumulators: the sum belongs to
+// this group of 128 alone).  Slice SL lives in chunk SL / T at field position SL % T (T = 8 / B).
+template <int B, int J>
+__device__ __forceinline__ v4i pair_sum(const u4v* w, const v4i* aop)
+{
+    constexpr int T = 8 / B, S0 = 2 * J, S1 = 2 * J + 1;
+    const v4i zero{0, 0, 0, 0};
+    if constexpr (B == 8) {
+        const v4i t = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[S0], field_operand<8, 0>(w[S0]), zero, 0, 0, 0);
+        return __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[S1], field_operand<8, 0>(w[S1]), t, 0, 0, 0);
+    } else {
+        const v4i t0 = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[S0], field_operand<B, S0 % T>(w[S0 / T]), zero, 0, 0, 0);
+        const v4i t1 = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[S1], field_operand<B, S1 % T>(w[S1 / T]), zero, 0, 0, 0);
+        return unscale4<B, S0 % T>(t0) + unscale4<B, S1 % T>(t1);
+    }
+}
+// Group J of the super-chunk: S = sum a'w' over its 128 k (all plane groups, bit reduction by shifts), the
+// activation sum over the same k from one more MFMA pair against a B operand of ones (it lands in the
+// accumulator layout, the same in every column), the zero-point correction in integers, then one
+// conversion and one multiply-add per element into the single-precision sum over groups.
+template <int P, int J>
+__device__ __forceinline__ void group_step(const u4v* w, const v4i* aop, const u4v gp, v4f& facc)
+{
+    using GI = GroupInfo<P>;
+    const v4i zero{0, 0, 0, 0}, ones{0x01010101, 0x01010101, 0x01010101, 0x01010101};
+    v4i S = pair_sum<GI::b(0), J>(w + GI::load_base(0), aop);
+    if constexpr (GI::NG > 1) S += pair_sum<GI::b(1), J>(w + GI::load_base(1), aop) << GI::load_base(1);
+    if constexpr (GI::NG > 2) S += pair_sum<GI::b(2), J>(w + GI::load_base(2), aop) << GI::load_base(2);
+    const v4i asum = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[2 * J + 1], ones,
+                         __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[2 * J], ones, zero, 0, 0, 0), 0, 0, 0);
+    const int z = ((int)(gp.z << (24 - 8 * J))) >> 24;
+    const uint32_t sbits = (J < 2 ? gp.x : gp.y) >> (16 * (J & 1));
+    const float sc = __half2float(__ushort_as_half((unsigned short)(sbits & 0xFFFFu)));
+    facc.x = fmaf((float)(S.x - __mul24(z, asum.x)), sc, facc.x);
+    facc.y = fmaf((float)(S.y - __mul24(z, asum.y)), sc, facc.y);
+    facc.z = fmaf((float)(S.z - __mul24(z, asum.z)), sc, facc.z);
+    facc.w = fmaf((float)(S.w - __mul24(z, asum.w)), sc, facc.w);
+}
+template <int P>
+__device__ __forceinline__ void compute_super_gq(const u4v* w, const uint8_t* lds_row, v4f& facc)
+{
+    v4i aop[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) aop[j] = *reinterpret_cast<const v4i*>(lds_row + j * 64);
+    const u4v gp = w[P];
+    // one group after the other: scheduled freely, the MFMA results of all four groups are live at once
+    // (up to 80 registers) and the wider variants spill
+    group_step<P, 0>(w, aop, gp, facc);
+    __builtin_amdgcn_sched_barrier(0);
+    group_step<P, 1>(w, aop, gp, facc);
+    __builtin_amdgcn_sched_barrier(0);
+    group_step<P, 2>(w, aop, gp, facc);
+    __builtin_amdgcn_sched_barrier(0);
+    group_step<P, 3>(w, aop, gp, facc);
+    __builtin_amdgcn_sched_barrier(0);
+}
+
 // Per-wave streaming state (lives in registers once everything is inlined).
 template <int P>
 struct WaveState {
@@ -216,16 +286,17 @@ struct WaveState {
     const int32_t* asum;           // LDS: [S][16] partial row sums of A (fused-pack variant)
     int32_t* red;
     v4i acc[GroupInfo<P>::NACC];
+    v4f facc;                      // per-group weight parameters: this wave's single-precision sum over its groups
 #ifdef ABQ_PHASE_TRACE
     unsigned long long* ts;
 #endif
 };
 
 // Item order: (K group,) tile, super-chunk.
-template <int P, bool KG = false>
+template <int P, bool KG = false, bool GQ = false>
 __device__ __forceinline__ void prefetch_item(const SkinnyParams& prm, WaveState<P>& st, u4v* slot)
 {
-    load_super<P>(prm, st.nsuper, st.tile0 + st.p_ti * st.tstride, st.wave + st.p_lsc * st.S, st.lane, slot);
+    load_super<P, GQ>(prm, st.nsuper, st.tile0 + st.p_ti * st.tstride, st.wave + st.p_lsc * st.S, st.lane, slot);
     if constexpr (!KG) {
         if (++st.p_lsc == st.nsw) { st.p_lsc = 0; ++st.p_ti; }
     } else {
@@ -251,16 +322,24 @@ __device__ __forceinline__ const uint8_t* operand_row(const SkinnyParams& prm, c
 
 // End of a tile on this wave: bit reduction over the plane groups, sum over the S waves
 // through LDS (two buffers alternate, so one barrier per tile is enough), fused epilogue.
-template <int P, int EPT, bool RAW, bool KG = false>
+template <int P, int EPT, bool RAW, bool KG = false, bool GQ = false>
 __device__ __forceinline__ void finish_tile(const SkinnyParams& prm, WaveState<P>& st)
 {
     using GI = GroupInfo<P>;
+    static_assert(!(GQ && KG), "per-group weight parameters are not combined with K groups");
     ABQ_TSS(3);
-    v4i total = group_combine<GI::b(0)>(st.acc + GI::acc_base(0));
-    if constexpr (GI::NG > 1) total += group_combine<GI::b(1)>(st.acc + GI::acc_base(1)) << GI::load_base(1);
-    if constexpr (GI::NG > 2) total += group_combine<GI::b(2)>(st.acc + GI::acc_base(2)) << GI::load_base(2);
+    v4i total;
+    if constexpr (GQ) {
+        // the wave's partial result is a single-precision sum; it travels through LDS as its bit pattern
+        total = v4i{__float_as_int(st.facc.x), __float_as_int(st.facc.y), __float_as_int(st.facc.z), __float_as_int(st.facc.w)};
+        st.facc = v4f{0.f, 0.f, 0.f, 0.f};
+    } else {
+        total = group_combine<GI::b(0)>(st.acc + GI::acc_base(0));
+        if constexpr (GI::NG > 1) total += group_combine<GI::b(1)>(st.acc + GI::acc_base(1)) << GI::load_base(1);
+        if constexpr (GI::NG > 2) total += group_combine<GI::b(2)>(st.acc + GI::acc_base(2)) << GI::load_base(2);
 #pragma unroll
-    for (int i = 0; i < GI::NACC; ++i) st.acc[i] = v4i{0, 0, 0, 0};
+        for (int i = 0; i < GI::NACC; ++i) st.acc[i] = v4i{0, 0, 0, 0};
+    }
     if constexpr (KG) {
         // all but the last K group: the tile's sum so far stays in this wave's own part of LDS
         int32_t* pp = st.part + st.ti * 256 + st.lane;
@@ -286,6 +365,25 @@ __device__ __forceinline__ void finish_tile(const SkinnyParams& prm, WaveState<P
     const int tile = st.tile0 + st.ti * st.tstride;
     const int n = tile * kTileN + (st.tid & 15);
     const RowParams pw = st.par[16 + st.ti * 16 + (st.tid & 15)];
+    if constexpr (GQ) {
+        // Y = a_scale * (sum over waves and groups - (az - oa) * t[n]), t[n] in pw.scale; the waves' sums are
+        // added in a fixed order.  Any workgroup size: thread t takes elements t, t + blockDim, ...
+        for (int e = st.tid; e < 256; e += (int)blockDim.x) {
+            const int row = 4 * ((e & 63) >> 4) + (e >> 6);
+            if (row < st.mt && n < prm.N) {
+                float part[8];
+#pragma unroll
+                for (int ww = 0; ww < 8; ++ww) part[ww] = ww < st.S ? __int_as_float(rb[ww * 256 + e]) : 0.f;
+                const float sum = ((part[0] + part[1]) + (part[2] + part[3])) + ((part[4] + part[5]) + (part[6] + part[7]));
+                const RowParams pa = st.par[row];
+                const float v = pa.scale * (sum - (float)(pa.zero - prm.oa) * pw.scale);
+                prm.y[(size_t)(st.m0 + row) * prm.N + n] = __half_as_ushort(__float2half_rn(v));
+            }
+        }
+        st.parity ^= 1;
+        ++st.ti;
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < EPT; ++i) {
         const int e = st.tid + i * (int)blockDim.x;
@@ -312,14 +410,15 @@ __device__ __forceinline__ void finish_tile(const SkinnyParams& prm, WaveState<P
 
 // One item: MFMAs, refill of its ring slot, end-of-tile work.  With K groups, the end of a group's last
 // tile moves on to the next run of super-chunks and stages its columns of A (next_group).
-template <int P, int EPT, bool RAW, bool KG, bool REFILL, typename F>
+template <int P, int EPT, bool RAW, bool KG, bool REFILL, bool GQ, typename F>
 __device__ __forceinline__ void item_step(const SkinnyParams& prm, WaveState<P>& st, u4v* slot, bool refill, F&& next_group)
 {
-    compute_super<P>(slot, operand_row<P, KG>(prm, st), st.acc);
-    if (REFILL) prefetch_item<P, KG>(prm, st, slot);
-    else if (refill) prefetch_item<P, KG>(prm, st, slot);
+    if constexpr (GQ) compute_super_gq<P>(slot, operand_row<P, KG>(prm, st), st.facc);
+    else compute_super<P>(slot, operand_row<P, KG>(prm, st), st.acc);
+    if (REFILL) prefetch_item<P, KG, GQ>(prm, st, slot);
+    else if (refill) prefetch_item<P, KG, GQ>(prm, st, slot);
     if constexpr (!KG) {
-        if (++st.lsc == st.nsw) { finish_tile<P, EPT, RAW>(prm, st); st.lsc = 0; }
+        if (++st.lsc == st.nsw) { finish_tile<P, EPT, RAW, false, GQ>(prm, st); st.lsc = 0; }
     } else {
         if (++st.lsc == st.ge) {
             finish_tile<P, EPT, RAW, true>(prm, st);
@@ -344,10 +443,11 @@ __device__ __forceinline__ void item_step(const SkinnyParams& prm, WaveState<P>&
 // KG: K groups (see SkinnyParams); never together with FULL.
 // The body takes the workgroup's share of the problem as arguments (tiles tile0 + i * tstride, i < nmy; row
 // group by) so that the grouped launch below can run it on one problem of several.
-template <int P, int D, int EPT, bool RAW, bool FULL, bool KG, bool R16>
+template <int P, int D, int EPT, bool RAW, bool FULL, bool KG, bool R16, bool GQ = false>
 __device__ __forceinline__ void skinny_body(const SkinnyParams& prm, const int tile0, const int tstride, const int nmy, const int by)
 {
     static_assert(!(FULL && KG), "the K-group variant uses the conditional ring prologue");
+    static_assert(!(GQ && (KG || R16)), "per-group weight parameters: plain and FULL variants only");
     using GI = GroupInfo<P>;
     extern __shared__ __align__(16) uint8_t lds[];
     WaveState<P> st;
@@ -459,13 +559,13 @@ __device__ __forceinline__ void skinny_body(const SkinnyParams& prm, const int t
     };
 
     // ---- the weight stream: first item = (tile0, super-chunk `wave`), then the rest of the ring
-    u4v w[D][P];
-    prefetch_item<P, KG>(prm, st, w[0]);
+    u4v w[D][P + (GQ ? 1 : 0)];
+    prefetch_item<P, KG, GQ>(prm, st, w[0]);
     if constexpr (FULL) {
         // every wave has at least D items: the whole ring is issued unconditionally, the number of
         // loads behind A is known, and the wait for A is exact
 #pragma unroll
-        for (int d = 1; d < D; ++d) prefetch_item<P, KG>(prm, st, w[d]);
+        for (int d = 1; d < D; ++d) prefetch_item<P, KG, GQ>(prm, st, w[d]);
         store_first();
     } else {
         // short streams: A is staged behind the first item only (again an exact wait), the rest of
@@ -473,7 +573,7 @@ __device__ __forceinline__ void skinny_body(const SkinnyParams& prm, const int t
         store_first();
 #pragma unroll
         for (int d = 1; d < D; ++d)
-            if (d < st.nitems) prefetch_item<P, KG>(prm, st, w[d]);
+            if (d < st.nitems) prefetch_item<P, KG, GQ>(prm, st, w[d]);
     }
     // whatever is left of A (more than two super-chunks per wave); with K groups also
     // every later run, staged over the columns of the run before it once that run's last tile is done
@@ -520,6 +620,11 @@ __device__ __forceinline__ void skinny_body(const SkinnyParams& prm, const int t
     };
 #pragma unroll
     for (int i = 0; i < GI::NACC; ++i) st.acc[i] = v4i{0, 0, 0, 0};
+    st.facc = v4f{0.f, 0.f, 0.f, 0.f};
+    auto compute = [&](const u4v* slot, const uint8_t* row) {
+        if constexpr (GQ) compute_super_gq<P>(slot, row, st.facc);
+        else compute_super<P>(slot, row, st.acc);
+    };
 
     int it = 0;
     if (!KG && nmy == 1) {
@@ -528,8 +633,8 @@ __device__ __forceinline__ void skinny_body(const SkinnyParams& prm, const int t
         for (; it + 2 * D <= st.nitems; it += D) {
 #pragma unroll
             for (int d = 0; d < D; ++d) {
-                compute_super<P>(w[d], st.lds_lane + (((st.wave + st.lsc * st.S) * kSuperK) & st.k_mask), st.acc);
-                prefetch_item<P>(prm, st, w[d]);
+                compute(w[d], st.lds_lane + (((st.wave + st.lsc * st.S) * kSuperK) & st.k_mask));
+                prefetch_item<P, false, GQ>(prm, st, w[d]);
                 ++st.lsc;
             }
         }
@@ -537,22 +642,22 @@ __device__ __forceinline__ void skinny_body(const SkinnyParams& prm, const int t
 #pragma unroll
             for (int d = 0; d < D; ++d)
                 if (it + d < st.nitems) {
-                    compute_super<P>(w[d], st.lds_lane + (((st.wave + st.lsc * st.S) * kSuperK) & st.k_mask), st.acc);
-                    if (it + d + D < st.nitems) prefetch_item<P>(prm, st, w[d]);
+                    compute(w[d], st.lds_lane + (((st.wave + st.lsc * st.S) * kSuperK) & st.k_mask));
+                    if (it + d + D < st.nitems) prefetch_item<P, false, GQ>(prm, st, w[d]);
                     ++st.lsc;
                 }
         }
-        finish_tile<P, EPT, RAW>(prm, st);
+        finish_tile<P, EPT, RAW, false, GQ>(prm, st);
     } else {
         // Several tiles per workgroup: the ring runs ahead across tile boundaries.
         for (; it + 2 * D <= st.nitems; it += D) {
 #pragma unroll
-            for (int d = 0; d < D; ++d) item_step<P, EPT, RAW, KG, true>(prm, st, w[d], true, next_group);
+            for (int d = 0; d < D; ++d) item_step<P, EPT, RAW, KG, true, GQ>(prm, st, w[d], true, next_group);
         }
         for (; it < st.nitems; it += D) {
 #pragma unroll
             for (int d = 0; d < D; ++d)
-                if (it + d < st.nitems) item_step<P, EPT, RAW, KG, false>(prm, st, w[d], it + d + D < st.nitems, next_group);
+                if (it + d < st.nitems) item_step<P, EPT, RAW, KG, false, GQ>(prm, st, w[d], it + d + D < st.nitems, next_group);
         }
     }
 #ifdef ABQ_PHASE_TRACE
@@ -562,11 +667,11 @@ __device__ __forceinline__ void skinny_body(const SkinnyParams& prm, const int t
 #endif
 }
 
-template <int P, int D, int EPT, bool RAW, bool FULL, bool KG, bool R16>
+template <int P, int D, int EPT, bool RAW, bool FULL, bool KG, bool R16, bool GQ = false>
 __global__ __launch_bounds__(512) void skinny_kernel(SkinnyParams prm)
 {
     // workgroup b owns tl_q + (b < tl_r) tiles: b, b + gridDim.x, ...
-    skinny_body<P, D, EPT, RAW, FULL, KG, R16>(prm, (int)blockIdx.x, (int)gridDim.x, prm.tl_q + ((int)blockIdx.x < prm.tl_r ? 1 : 0),
+    skinny_body<P, D, EPT, RAW, FULL, KG, R16, GQ>(prm, (int)blockIdx.x, (int)gridDim.x, prm.tl_q + ((int)blockIdx.x < prm.tl_r ? 1 : 0),
                                           (int)blockIdx.y);
 }
 
@@ -634,16 +739,16 @@ __global__ __launch_bounds__(512) void grouped_kernel(GroupedParams gp)
     }
 }
 
-template <int P, int D, int EPT, bool RAW, bool FULL, bool KG, bool R16>
+template <int P, int D, int EPT, bool RAW, bool FULL, bool KG, bool R16, bool GQ = false>
 static hipError_t launch_variant_r(const SkinnyParams& prm, dim3 grid, int waves, size_t lds_bytes, hipStream_t s)
 {
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)skinny_kernel<P, D, EPT, RAW, FULL, KG, R16>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        hipError_t e = hipFuncSetAttribute((const void*)skinny_kernel<P, D, EPT, RAW, FULL, KG, R16, GQ>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    skinny_kernel<P, D, EPT, RAW, FULL, KG, R16><<<grid, waves * 64, lds_bytes, s>>>(prm);
+    skinny_kernel<P, D, EPT, RAW, FULL, KG, R16, GQ><<<grid, waves * 64, lds_bytes, s>>>(prm);
     return hipGetLastError();
 }
 
@@ -674,9 +779,26 @@ static hipError_t launch_pde(const SkinnyParams& prm, dim3 grid, int waves, size
                 : launch_variant<P, D, EPT, false, false, false>(prm, grid, waves, lds_bytes, s);
 }
 
+// Per-group weight parameters: one epilogue serves every workgroup size (instantiated as EPT = 1), no K groups.
+// The ring is half as deep as the per-channel kernel's (one super-chunk only at p = 7): the group arithmetic
+// needs the registers, and deeper rings spill.
+__host__ __device__ constexpr int gq_depth(int p, int d) { return p == 7 ? 1 : (d > 2 ? d / 2 : d); }
+template <int P, int D>
+static hipError_t launch_gq(const SkinnyParams& prm, dim3 grid, int waves, size_t lds_bytes, hipStream_t s)
+{
+    if (prm.kgroups > 1) return hipErrorInvalidValue;
+    const bool full = prm.tl_q * prm.sc_q >= D;
+    if (prm.a_raw)
+        return full ? launch_variant_r<P, D, 1, true, true, false, false, true>(prm, grid, waves, lds_bytes, s)
+                    : launch_variant_r<P, D, 1, true, false, false, false, true>(prm, grid, waves, lds_bytes, s);
+    return full ? launch_variant_r<P, D, 1, false, true, false, false, true>(prm, grid, waves, lds_bytes, s)
+                : launch_variant_r<P, D, 1, false, false, false, false, true>(prm, grid, waves, lds_bytes, s);
+}
+
 template <int P, int D>
 static hipError_t launch_pd(const SkinnyParams& prm, dim3 grid, int waves, size_t lds_bytes, hipStream_t s)
 {
+    if (prm.gparams) return launch_gq<P, gq_depth(P, D)>(prm, grid, waves, lds_bytes, s);
     if (waves >= 4) return launch_pde<P, D, 1>(prm, grid, waves, lds_bytes, s);
     if (waves == 2) return launch_pde<P, D, 2>(prm, grid, waves, lds_bytes, s);
     return launch_pde<P, D, 4>(prm, grid, waves, lds_bytes, s);

@@ -72,6 +72,30 @@ def test_quant_pack_act_rejects(args, want):
     assert B.load().abq_quant_pack_act(*args) == want
 
 
+def test_g128_pack_rejects_and_size_query():
+    lib = B.load()
+    G128 = B.ABQ_LAYOUT_FIELDS_G128
+    # the field-packed blob plus one 256-byte record block per (16-channel tile, 512-k super-chunk)
+    assert lib.abq_packed_weight_bytes(4, 4096, 4096, G128) == lib.abq_packed_weight_bytes(4, 4096, 4096, B.ABQ_LAYOUT_FIELDS) + 256 * 8 * 256
+    assert lib.abq_packed_weight_bytes(2, 17, 100, G128) == lib.abq_packed_weight_bytes(2, 17, 100, B.ABQ_LAYOUT_FIELDS) + 2 * 256
+    assert lib.abq_packed_act_bytes(8, 1, 4096, G128) == 0          # a weight-side layout only
+    f = lib.abq_pack_weights_g128
+    assert f(4, 16, 256, A16, A16, None, A16, 1 << 20, None) == B.ABQ_ERR_NULL
+    assert f(4, 16, 256, A16, None, A16, A16, 1 << 20, None) == B.ABQ_ERR_NULL
+    assert f(9, 16, 256, A16, A16, A16, A16, 1 << 20, None) == B.ABQ_ERR_BITS
+    assert f(4, 16, 0, A16, A16, A16, A16, 1 << 20, None) == B.ABQ_ERR_SHAPE
+    assert f(4, 16, 256, A16, A16 + 2, A16, A16, 1 << 20, None) == B.ABQ_ERR_ALIGN
+    assert f(4, 16, 256, A16, A16, A16, A16, 1000, None) == B.ABQ_ERR_SIZE
+    # the per-channel packer does not write this layout; the matmuls cannot return the raw accumulator from it
+    assert lib.abq_pack_weights(4, 16, 256, A16, A16, A16, G128, A16, 1 << 20, None) == B.ABQ_ERR_LAYOUT
+    assert gemm(lib, al=B.ABQ_LAYOUT_FIELDS, wl=G128, acc=A16) == B.ABQ_ERR_LAYOUT
+    assert gemm(lib, al=B.ABQ_LAYOUT_PLANES, wl=G128) == B.ABQ_ERR_LAYOUT
+    assert gemm_fused(lib, wl=G128, acc=A16) == B.ABQ_ERR_LAYOUT
+    q = lib.abq_gemm_act_codes_workspace_bytes
+    assert q(4, 8, 1, 4096, 4096, G128) == 0 and q(4, 8, 300, 4096, 4096, G128) == 0      # one launch for every M
+    assert q(4, 8, 2, 64, 1000, G128) == lib.abq_packed_act_bytes(8, 2, 1000, B.ABQ_LAYOUT_FIELDS)   # K not a multiple of 16
+
+
 def test_pack_act_codes_rejects():
     lib = B.load()
     assert lib.abq_pack_act_codes(8, 1, 64, A16, None, A16, 0, A16, 1 << 20, None) == B.ABQ_ERR_NULL
@@ -99,7 +123,8 @@ def test_gemm_rejects():
     assert gemm(lib, al=B.ABQ_LAYOUT_PLANES, wl=B.ABQ_LAYOUT_FIELDS) == B.ABQ_ERR_LAYOUT
     assert gemm(lib, al=B.ABQ_LAYOUT_FIELDS, wl=B.ABQ_LAYOUT_FIELDS | B.ABQ_USE_PLANES) == B.ABQ_ERR_LAYOUT
     assert gemm(lib, al=B.ABQ_LAYOUT_BOTH, wl=B.ABQ_LAYOUT_BOTH | B.ABQ_USE_PLANES | B.ABQ_USE_FIELDS) == B.ABQ_ERR_LAYOUT
-    assert gemm(lib, al=4) == B.ABQ_ERR_LAYOUT
+    assert gemm(lib, al=4) == B.ABQ_ERR_LAYOUT    # the group layout exists for weights only
+    assert gemm(lib, al=5) == B.ABQ_ERR_LAYOUT
     assert gemm(lib, acc=A16 + 4) == B.ABQ_ERR_ALIGN
 
 

@@ -7,7 +7,7 @@ import pytest
 
 import oracle
 from paper_2408_08554_amd import synth
-from helpers import check_against_oracle, check_sampled, gpu_gemm, gpu_gemm_fused, to_dev
+from helpers import check_against_oracle, check_g128, check_sampled, gpu_gemm, gpu_gemm_fused, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -555,6 +555,85 @@ def test_bit_balance_five_level_weights(abq, M, N, K, fused):
     levels = c.W.astype(np.float64) - 2.0
     real = ((c.A.astype(np.float64) - c.a_zero[:, None]) * c.a_scale[:, None]) @ (levels * c.w_scale[:, None].astype(np.float64)).T
     assert np.allclose(yref, real, rtol=1e-12, atol=0)
+
+
+# ---- per-group weight scales and zero-points, groups of 128 along K (Appendix C) -------------------------
+
+G128 = 4   # ABQ_LAYOUT_FIELDS_G128
+
+
+def run_g128(abq, c, sh, zg, fused):
+    pw = abq.abq_pack_weights_g128(c.p, to_dev(torch, c.W), to_dev(torch, sh.view(np.float16)), to_dev(torch, zg))
+    if fused:
+        y, _ = abq.abq_gemm_act_codes(c.p, c.q, c.M, c.N, c.K, to_dev(torch, c.A), to_dev(torch, c.a_scale),
+                                      to_dev(torch, c.a_zero), pw, G128, want_acc=False)
+    else:
+        pa = abq.abq_pack_act_codes(c.q, to_dev(torch, c.A), to_dev(torch, c.a_scale), to_dev(torch, c.a_zero), FIELDS)
+        y, _ = abq.abq_gemm(c.p, c.q, c.M, c.N, c.K, pa, FIELDS, pw, G128, want_acc=False)
+    torch.cuda.synchronize()
+    return y.cpu().numpy()
+
+
+@pytest.mark.parametrize("fused", [False, True], ids=["packed", "fused"])
+@pytest.mark.parametrize("p,q", list(itertools.product(range(1, 9), [1, 4, 8])))
+def test_g128_all_widths(abq, p, q, fused):
+    say(f"g128 p={p} q={q} fused={fused}")
+    c = synth.make_case(p, q, 3, 40, 1536, seed=9000 + 10 * p + q)
+    sh, zg = synth.group_quant_params(c)
+    check_g128(c, sh, zg, run_g128(abq, c, sh, zg, fused))
+
+
+G128_SHAPES = [(1, 4096, 4096), (1, 4096, 11008), (8, 4096, 11008), (16, 70, 13824), (5, 33, 1000), (2, 17, 128),
+               (3, 16, 80), (16, 256, 4096), (40, 100, 2048), (1, 13824, 5120)]
+
+
+@pytest.mark.parametrize("fused", [False, True], ids=["packed", "fused"])
+@pytest.mark.parametrize("M,N,K", G128_SHAPES)
+@pytest.mark.parametrize("p,q", [(2, 8), (4, 8), (3, 8), (8, 8), (4, 4)])
+def test_g128_shapes(abq, M, N, K, p, q, fused):
+    say(f"g128 shape M={M} N={N} K={K} p={p} q={q} fused={fused}")
+    c = synth.make_case(p, q, M, N, K, seed=9100 + M + N + K + p)
+    sh, zg = synth.group_quant_params(c)
+    check_g128(c, sh, zg, run_g128(abq, c, sh, zg, fused))
+
+
+def test_g128_exact_when_the_float_sum_is_exact(abq):
+    # power-of-two scales and small codes: every product and partial sum is an integer multiple of 2^-10 below
+    # 2^24 ulps, so binary32 accumulates without rounding and the output must equal the oracle's bit for bit
+    c = synth.make_case(3, 4, 4, 48, 2048, seed=9200)
+    sh, zg = synth.group_quant_params(c)
+    rng = np.random.Generator(np.random.PCG64(9201))
+    sh = np.float16(2.0) ** rng.integers(-6, -2, size=sh.shape).astype(np.float16)
+    sh = sh.astype(np.float16).view(np.uint16)
+    c.a_scale = (np.float32(2.0) ** rng.integers(-8, -5, size=c.M)).astype(np.float32)
+    for fused in (False, True):
+        y = run_g128(abq, c, sh, zg, fused)
+        _, y16 = oracle.dequant_grouped(c.A, c.W, c.a_zero, c.a_scale, zg, sh, gs=128)
+        assert np.array_equal(y.view(np.uint16), y16)
+
+
+def test_g128_one_parameter_set_per_channel_matches_the_per_channel_kernel(abq):
+    # equal parameters in every group: the same problem as the per-channel path
+    c = synth.make_case(4, 8, 2, 64, 4096, seed=9300)
+    G = c.K // 128
+    sh = np.repeat(c.w_scale.astype(np.float16).view(np.uint16)[:, None], G, axis=1).copy()
+    zg = np.repeat(c.w_zero[:, None], G, axis=1).astype(np.int32).copy()
+    y = run_g128(abq, c, sh, zg, True)
+    y_pc, _ = gpu_gemm_fused(torch, abq, c, FIELDS)
+    yref = check_against_oracle(c, y_pc, None)
+    check_g128(c, sh, zg, y)
+    assert np.all(np.abs(y.astype(np.float64) - y_pc.astype(np.float64)) <= 2 * (2.0 ** (np.floor(np.log2(np.maximum(np.abs(yref), 2.0 ** -14))) - 10)))
+
+
+def test_g128_rejects_what_it_cannot_do(abq):
+    c = synth.make_case(4, 8, 1, 32, 1024, seed=9400)
+    sh, zg = synth.group_quant_params(c)
+    pw = abq.abq_pack_weights_g128(4, to_dev(torch, c.W), to_dev(torch, sh.view(np.float16)), to_dev(torch, zg))
+    with pytest.raises(abq.AbqError):   # no raw integer accumulator on this path
+        abq.abq_gemm_act_codes(4, 8, 1, 32, 1024, to_dev(torch, c.A), to_dev(torch, c.a_scale), to_dev(torch, c.a_zero), pw, G128,
+                               want_acc=True)
+    codes = abq.abq_unpack_weights(4, 32, 1024, G128, pw, FIELDS)
+    assert np.array_equal(codes.cpu().numpy(), c.W)
 
 
 def test_quantize_then_gemm_end_to_end(abq):
