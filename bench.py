@@ -33,6 +33,8 @@ MEASURED_TRAFFIC_BYTES = {
     "C2 W4A8 GEMV 4096x4096": int((4232.0 * 8256.25 / 4140.9 + 8.0) * 1024),
     "C3 W2A8 GEMV M=1 11008->4096": int((5821.5 * 11328.25 / 5677.3 + 8.0) * 1024),
     "C5 W8A8 M=1 K=5120 N=13824": int((34785.6 * 69336.2 / 34687.3 + 27.0) * 1024),
+    "C2 W4A8 GEMV 4096x4096 g128": int((4491.5 * 8768.2 / 4396.6 + 8.0) * 1024),
+    "C5 W4A8 M=1 K=5120 N=13824 g128": int((18589.0 * 36936.2 / 18483.4 + 27.0) * 1024),
     "C4 W6A6 GEMM M=512 4096->11008": int((26750.5 * 33196.2 / 16612.3 + 11008.1) * 1024),
     "C5 W4A4 M=2048 K=5120 N=13824": int((122141.9 * 34776.2 / 17402.2 + 55299.1) * 1024),
 }
