@@ -33,8 +33,8 @@ MEASURED_TRAFFIC_BYTES = {
     "C2 W4A8 GEMV 4096x4096": int((4232.0 * 8256.25 / 4140.9 + 8.0) * 1024),
     "C3 W2A8 GEMV M=1 11008->4096": int((5821.5 * 11328.25 / 5677.3 + 8.0) * 1024),
     "C5 W8A8 M=1 K=5120 N=13824": int((34785.6 * 69336.2 / 34687.3 + 27.0) * 1024),
-    "C2 W4A8 GEMV 4096x4096 g128": int((4491.5 * 8768.2 / 4396.6 + 8.0) * 1024),
-    "C5 W4A8 M=1 K=5120 N=13824 g128": int((18589.0 * 36936.2 / 18483.4 + 27.0) * 1024),
+    "C2 W4A8 GEMV 4096x4096 g128": int((4482.0 * 8768.2 / 4396.6 + 8.0) * 1024),
+    "C5 W4A8 M=1 K=5120 N=13824 g128": int((18575.5 * 36936.2 / 18483.2 + 27.0) * 1024),
     "C4 W6A6 GEMM M=512 4096->11008": int((26750.5 * 33196.2 / 16612.3 + 11008.1) * 1024),
     "C5 W4A4 M=2048 K=5120 N=13824": int((122141.9 * 34776.2 / 17402.2 + 55299.1) * 1024),
 }
@@ -131,7 +131,7 @@ BLOCK_7B = [("q_proj", 4096, 4096), ("k_proj", 4096, 4096), ("v_proj", 4096, 409
             ("gate_proj", 11008, 4096), ("up_proj", 11008, 4096), ("down_proj", 4096, 11008)]
 
 
-def bench_grouped(p, q, M, steps, warmup, rotate_gib, check=True):
+def bench_grouped(p, q, M, steps, warmup, rotate_gib, check=True, g128=False):
     """One abq_gemm_grouped launch over the seven layer shapes of a decoder block (independent synthetic
     problems: own weights, activation codes and outputs), against the same seven as single fused calls.
     Weight sets rotate over >= rotate_gib GiB.  Returns a dict for the JSON line."""
@@ -139,10 +139,15 @@ def bench_grouped(p, q, M, steps, warmup, rotate_gib, check=True):
     import torch
     from paper_2408_08554_amd import binding as abq, metrics, synth
     layout = abq.ABQ_LAYOUT_FIELDS
+    wl = abq.ABQ_LAYOUT_FIELDS_G128 if g128 else layout
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
     cases = [synth.make_case(p, q, M, N, K, seed=synth.case_seed(6, p, q, i, 0), name=f"{name} W{p}A{q} M={M} {K}->{N}")
              for i, (name, N, K) in enumerate(BLOCK_7B)]
-    blobs0 = [abq.abq_pack_weights(p, dev(c.W), dev(c.w_scale), dev(c.w_zero), layout) for c in cases]
+    if g128:
+        gpar = [synth.group_quant_params(c) for c in cases]
+        blobs0 = [abq.abq_pack_weights_g128(p, dev(c.W), dev(sh.view(np.float16)), dev(zg)) for c, (sh, zg) in zip(cases, gpar)]
+    else:
+        blobs0 = [abq.abq_pack_weights(p, dev(c.W), dev(c.w_scale), dev(c.w_zero), layout) for c in cases]
     set_bytes = sum((b.numel() + 255) // 256 * 256 for b in blobs0)
     R = max(2, int(np.ceil(rotate_gib * 2 ** 30 / set_bytes)))
     pool = torch.empty(R * set_bytes, dtype=torch.uint8, device="cuda")
@@ -164,13 +169,32 @@ def bench_grouped(p, q, M, steps, warmup, rotate_gib, check=True):
                      y=ys[i], acc=accs[i] if with_acc else None) for i, c in enumerate(cases)]
 
     descs = [abq.make_problems(problems(r, False)) for r in range(R)]
-    assert abq.abq_gemm_grouped_workspace_bytes(p, q, M, descs[0], layout, layout) == 0, "this group must run as one launch"
+    assert abq.abq_gemm_grouped_workspace_bytes(p, q, M, descs[0], layout, wl) == 0, "this group must run as one launch"
 
-    if check:
+    if check and g128:
         import oracle
         rng = np.random.Generator(np.random.PCG64(11))
         for r in (0, R - 1):
-            abq.abq_gemm_grouped(p, q, M, problems(r, True), layout, layout)
+            abq.abq_gemm_grouped(p, q, M, problems(r, False), layout, wl)
+            torch.cuda.synchronize()
+            for i, c in enumerate(cases):
+                sh, zg = gpar[i]
+                ns = np.unique(rng.integers(0, c.N, 128))
+                G = (c.K + 127) // 128
+                yref, _, mag = oracle.dequant_grouped(c.A, c.W[ns], c.a_zero, c.a_scale, zg[ns], sh[ns], gs=128, want_mag=True)
+                pad = np.zeros((len(ns), G * 128), dtype=np.int64)
+                pad[:, :c.K] = c.W[ns].astype(np.int64) - np.repeat(zg[ns], 128, axis=1)[:, :c.K]
+                t_abs = np.abs(sh[ns].view(np.float16).astype(np.float64) * pad.reshape(len(ns), G, 128).sum(axis=2)).sum(axis=1)
+                za = np.maximum(np.abs(c.a_zero), np.abs(c.a_zero - 128)).astype(np.float64)
+                size = mag + 2 * np.abs(c.a_scale.astype(np.float64))[:, None] * za[:, None] * t_abs[None, :] + np.abs(yref)
+                tol = np.maximum(np.maximum(1e-2 * np.abs(yref), 2.0 ** (np.floor(np.log2(np.maximum(np.abs(yref), 2.0 ** -14))) - 9)),
+                                 2.0 ** -24) + (G + 12) * 2.0 ** -24 * size
+                assert np.all(np.abs(ys[i].cpu().numpy()[:, ns].astype(np.float64) - yref) <= tol), f"fp16 parity failure in {c.name} (g128)"
+    elif check:
+        import oracle
+        rng = np.random.Generator(np.random.PCG64(11))
+        for r in (0, R - 1):
+            abq.abq_gemm_grouped(p, q, M, problems(r, True), layout, wl)
             torch.cuda.synchronize()
             for i, c in enumerate(cases):
                 ms = rng.integers(0, M, 1024).astype(np.int32)
@@ -183,11 +207,11 @@ def bench_grouped(p, q, M, steps, warmup, rotate_gib, check=True):
                 assert np.all(np.abs(ys[i].cpu().numpy()[ms, ns].astype(np.float64) - yref) <= tol), f"fp16 parity failure in {c.name}"
 
     def grouped_step(i):
-        abq.abq_gemm_grouped(p, q, M, descs[i % R], layout, layout)
+        abq.abq_gemm_grouped(p, q, M, descs[i % R], layout, wl)
 
     def single_step(i):
         for j, c in enumerate(cases):
-            abq.abq_gemm_act_codes(p, q, M, c.N, c.K, acts[j][0], acts[j][1], acts[j][2], sets[i % R][j], layout, y=ys[j])
+            abq.abq_gemm_act_codes(p, q, M, c.N, c.K, acts[j][0], acts[j][1], acts[j][2], sets[i % R][j], wl, y=ys[j])
 
     stream = torch.cuda.Stream()
     times = {}
@@ -210,13 +234,13 @@ def bench_grouped(p, q, M, steps, warmup, rotate_gib, check=True):
             times[name] = e0.elapsed_time(e1) * 1e-3 / steps
             del g
     ops = sum(2.0 * M * c.N * c.K for c in cases)
-    alg = sum(metrics.gemm_algorithmic_bytes(p, q, M, c.N, c.K) for c in cases)
+    alg = sum(metrics.gemm_algorithmic_bytes(p, q, M, c.N, c.K) + (3 * c.N * ((c.K + 127) // 128) if g128 else 0) for c in cases)
     wbytes = sum(metrics.packed_weight_stream_bytes(p, c.N, c.K) for c in cases)
     t = times["grouped"]
-    return {"workload": f"LLaMA-7B decoder block, 7 linear layers, W{p}A{q} M={M}, one abq_gemm_grouped launch",
+    return {"workload": f"LLaMA-7B decoder block, 7 linear layers, W{p}A{q}{' g128' if g128 else ''} M={M}, one abq_gemm_grouped launch",
             "us_per_block": t * 1e6, "tops": ops / t / 1e12, "weight_gbs": wbytes / t / 1e9,
             "roofline": {"bound": "hbm", "achieved": alg / t / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                         "frac": alg / t / 1e9 / HBM_PEAK_GBS, "traffic": MEASURED_GROUPED_TRAFFIC_BYTES.get((p, q, M)),
+                         "frac": alg / t / 1e9 / HBM_PEAK_GBS, "traffic": None if g128 else MEASURED_GROUPED_TRAFFIC_BYTES.get((p, q, M)),
                          "algorithmic_bytes": alg,
                          "kernel": "abq_gemm_grouped", "launches": steps},
             "seven_single_launches_us": times["single"] * 1e6, "rotating_weight_sets": R, "rotating_bytes": R * set_bytes,
@@ -306,7 +330,7 @@ def main():
     if args.workload.startswith("block:"):
         # block:p,q,M — the grouped decoder-block launch as the timed workload, printed as its own JSON line
         bp, bq, bm = (int(v) for v in args.workload.split(":")[1].split(","))
-        print(json.dumps(bench_grouped(bp, bq, bm, args.steps, args.warmup, args.rotate_gib, not args.no_check)), flush=True)
+        print(json.dumps(bench_grouped(bp, bq, bm, args.steps, args.warmup, args.rotate_gib, not args.no_check, args.g128)), flush=True)
         return
     if args.workload.startswith("norm:"):
         # norm:q,M,K — the fused RMSNorm + quantizer kernel alone, printed as its own JSON line
@@ -491,10 +515,10 @@ def main():
     roof["frac_of_measured_peak"] = achieved / roof["measured_peak"]
     if hbm_bound:   # a plain read of the same number of bytes in a launch of its own: the floor for this size
         roof["frac_of_plain_read_same_size"] = peaks["stream_read_workload_size"]["us"] / (gemm_s * 1e6)
-    if args.grouped_steps > 0 and M <= 16 and not args.g128:
+    if args.grouped_steps > 0 and M <= 16:
         del pool, blobs
         torch.cuda.empty_cache()
-        out["grouped_decoder_block"] = bench_grouped(p, q, M, args.grouped_steps, 20, args.rotate_gib, not args.no_check)
+        out["grouped_decoder_block"] = bench_grouped(p, q, M, args.grouped_steps, 20, args.rotate_gib, not args.no_check, args.g128)
     if args.cpu_seconds > 0:
         out["cpu_baseline"] = cpu_baseline(c, args.cpu_seconds, (g_scale_half, g_zero) if args.g128 else None)
     print(json.dumps(out), flush=True)

@@ -99,6 +99,8 @@ int abq_pack_weights(int p, int N, int K,
  *   w_scale_fp16 [N,G] binary16 bit patterns (the precision deployed group formats store)
  *   w_zero       [N,G] int32 in 0..2^p−1
  *   packed_out / packed_bytes: at least abq_packed_weight_bytes(p, N, K, ABQ_LAYOUT_FIELDS_G128) bytes.
+ * The order of that binary32 sum follows the launch plan (how K is split over waves), so the same problem
+ * through different entry points agrees to this bound, not to the bit.
  * abq_gemm, abq_gemm_act_codes and abq_gemm_grouped take such a blob with w_layout =
  * ABQ_LAYOUT_FIELDS_G128.  They run it on the streaming (decode) kernel for every M, one pass over the
  * weights per 16 rows of A, and cannot return the raw integer accumulator: acc_i32 must be NULL

@@ -378,6 +378,7 @@ static int prepare_group(int p, int q, int M, int count, const abq_problem* pr, 
         if (*raw ? (!c.a_scale || !c.a_zero || c.packed_act) : !c.packed_act) return *raw && c.packed_act ? ABQ_ERR_LAYOUT : ABQ_ERR_NULL;
         if (int e = check_gemm_shape(p, q, M, c.N, c.K)) return e;
         if (!make_weight_layout(p, c.N, c.K, base_w, &W[i])) return ABQ_ERR_LAYOUT;
+        if (W[i].g128 && (c.acc_i32 || force == ABQ_USE_PLANES)) return ABQ_ERR_LAYOUT;
         if (!make_act_layout(q, M, c.K, *raw ? ABQ_LAYOUT_FIELDS : a_layout, &A[i])) return ABQ_ERR_LAYOUT;
         if (misaligned(c.packed_w) || misaligned(c.packed_act) || misaligned(c.a_codes) || misaligned(c.a_scale) ||
             misaligned(c.a_zero) || misaligned(c.y_fp16) || misaligned(c.acc_i32))
@@ -388,7 +389,7 @@ static int prepare_group(int p, int q, int M, int count, const abq_problem* pr, 
     // one launch only where every problem would go to the streaming kernel of the int8-MFMA family anyway
     *fits = force != ABQ_USE_PLANES && M <= kSkinnyMaxM;
     for (int i = 0; i < count && *fits; ++i)
-        *fits = !W[i].g128 && choose_fields(W[i].has_fields && (*raw || A[i].has_fields), W[i].has_planes && !*raw && A[i].has_planes, force, p, q, M, pr[i].N);
+        *fits = W[i].g128 || choose_fields(W[i].has_fields && (*raw || A[i].has_fields), W[i].has_planes && !*raw && A[i].has_planes, force, p, q, M, pr[i].N);
     if (*fits) *fits = gemm_grouped_fits(M, count, args, A, W, waves, lds);
     return ABQ_OK;
 }

@@ -206,48 +206,69 @@ __device__ __forceinline__ void compute_super(const u4v* w, const uint8_t* lds_r
 // ---- per-group weight parameters: one super-chunk = four groups of 128 k = four pairs of 64-k slices --------
 typedef float v4f __attribute__((ext_vector_type(4)));
 
-template <int B, int T>
-__device__ __forceinline__ v4i unscale4(v4i a)
+// Field T0 of a b-bit plane group placed at bit position SH of the operand byte (the plane group's shift inside
+// the weight): the bit reduction over plane groups then happens inside the MFMA, every group adding into one
+// accumulator.  p <= 7 keeps the byte below 128; an 8-bit group is the stored signed byte itself.
+template <int B, int T0, int SH>
+__device__ __forceinline__ uint32_t placed_bytes(uint32_t x)
 {
-    return v4i{field_unscale<B, T>(a.x), field_unscale<B, T>(a.y), field_unscale<B, T>(a.z), field_unscale<B, T>(a.w)};
-}
-// sum_k a*field over the 128 k of pair J for one plane group of width B (fresh accumulators: the sum belongs to
-// this group of 128 alone).  Slice SL lives in chunk SL / T at field position SL % T (T = 8 / B).
-template <int B, int J>
-__device__ __forceinline__ v4i pair_sum(const u4v* w, const v4i* aop)
-{
-    constexpr int T = 8 / B, S0 = 2 * J, S1 = 2 * J + 1;
-    const v4i zero{0, 0, 0, 0};
-    if constexpr (B == 8) {
-        const v4i t = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[S0], field_operand<8, 0>(w[S0]), zero, 0, 0, 0);
-        return __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[S1], field_operand<8, 0>(w[S1]), t, 0, 0, 0);
-    } else {
-        const v4i t0 = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[S0], field_operand<B, S0 % T>(w[S0 / T]), zero, 0, 0, 0);
-        const v4i t1 = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[S1], field_operand<B, S1 % T>(w[S1 / T]), zero, 0, 0, 0);
-        return unscale4<B, S0 % T>(t0) + unscale4<B, S1 % T>(t1);
+    if constexpr (B == 8) return x;
+    else {
+        constexpr uint32_t mask = (0x01010101u * ((1u << B) - 1u)) << SH;
+        constexpr int from = B * T0;
+        if constexpr (from == SH) return x & mask;
+        else if constexpr (from > SH) return (x >> (from - SH)) & mask;
+        else return (x << (SH - from)) & mask;
     }
 }
-// Group J of the super-chunk: S = sum a'w' over its 128 k (all plane groups, bit reduction by shifts), the
-// activation sum over the same k from one more MFMA pair against a B operand of ones (it lands in the
-// accumulator layout, the same in every column), the zero-point correction in integers, then one
-// conversion and one multiply-add per element into the single-precision sum over groups.
+template <int B, int T0, int SH>
+__device__ __forceinline__ v4i placed_operand(const u4v& w)
+{
+    return v4i{(int)placed_bytes<B, T0, SH>(w.x), (int)placed_bytes<B, T0, SH>(w.y), (int)placed_bytes<B, T0, SH>(w.z),
+               (int)placed_bytes<B, T0, SH>(w.w)};
+}
+// acc += sum_k a * (field << SH) over the 128 k of pair J for one plane group of width B.  Slice SL lives in chunk
+// SL / T at field position SL % T (T = 8 / B).
+template <int B, int SH, int J>
+__device__ __forceinline__ v4i pair_add(const u4v* w, const v4i* aop, v4i acc)
+{
+    constexpr int T = 8 / B, S0 = 2 * J, S1 = 2 * J + 1;
+    acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[S0], placed_operand<B, S0 % T, SH>(w[S0 / T]), acc, 0, 0, 0);
+    return __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[S1], placed_operand<B, S1 % T, SH>(w[S1 / T]), acc, 0, 0, 0);
+}
+// Group J of the super-chunk.  One accumulator, fresh for this group of 128 k, takes every plane group (fields
+// placed at their bit positions) and then the zero-point: sum_k a' (w' - z) = sum_k a' w' + sum_k a' (-z), the second
+// sum being one more MFMA pair against a B operand whose bytes all hold -z of the lane's channel (p <= 7: -z
+// fits a signed byte).  At p = 8 (z down to -128) the activation sum over the group comes from an MFMA pair against
+// ones instead and the product is subtracted in integers.  Either way the correction is exact and precedes any
+// float, so the large raw products never cancel in floating point.  Then one conversion and one multiply-add per
+// element into the single-precision sum over groups.
 template <int P, int J>
 __device__ __forceinline__ void group_step(const u4v* w, const v4i* aop, const u4v gp, v4f& facc)
 {
     using GI = GroupInfo<P>;
-    const v4i zero{0, 0, 0, 0}, ones{0x01010101, 0x01010101, 0x01010101, 0x01010101};
-    v4i S = pair_sum<GI::b(0), J>(w + GI::load_base(0), aop);
-    if constexpr (GI::NG > 1) S += pair_sum<GI::b(1), J>(w + GI::load_base(1), aop) << GI::load_base(1);
-    if constexpr (GI::NG > 2) S += pair_sum<GI::b(2), J>(w + GI::load_base(2), aop) << GI::load_base(2);
-    const v4i asum = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[2 * J + 1], ones,
-                         __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[2 * J], ones, zero, 0, 0, 0), 0, 0, 0);
+    v4i c{0, 0, 0, 0};
+    c = pair_add<GI::b(0), 0, J>(w + GI::load_base(0), aop, c);
+    if constexpr (GI::NG > 1) c = pair_add<GI::b(1), GI::load_base(1), J>(w + GI::load_base(1), aop, c);
+    if constexpr (GI::NG > 2) c = pair_add<GI::b(2), GI::load_base(2), J>(w + GI::load_base(2), aop, c);
     const int z = ((int)(gp.z << (24 - 8 * J))) >> 24;
+    if constexpr (P < 8) {
+        const int zb = (int)(((uint32_t)(-z) & 0xFFu) * 0x01010101u);
+        const v4i zop{zb, zb, zb, zb};
+        c = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[2 * J], zop, c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[2 * J + 1], zop, c, 0, 0, 0);
+    } else {
+        const v4i zero{0, 0, 0, 0}, ones{0x01010101, 0x01010101, 0x01010101, 0x01010101};
+        const v4i asum = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[2 * J + 1], ones,
+                             __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[2 * J], ones, zero, 0, 0, 0), 0, 0, 0);
+        c = v4i{c.x - __mul24(z, asum.x), c.y - __mul24(z, asum.y), c.z - __mul24(z, asum.z), c.w - __mul24(z, asum.w)};
+    }
     const uint32_t sbits = (J < 2 ? gp.x : gp.y) >> (16 * (J & 1));
     const float sc = __half2float(__ushort_as_half((unsigned short)(sbits & 0xFFFFu)));
-    facc.x = fmaf((float)(S.x - __mul24(z, asum.x)), sc, facc.x);
-    facc.y = fmaf((float)(S.y - __mul24(z, asum.y)), sc, facc.y);
-    facc.z = fmaf((float)(S.z - __mul24(z, asum.z)), sc, facc.z);
-    facc.w = fmaf((float)(S.w - __mul24(z, asum.w)), sc, facc.w);
+    facc.x = fmaf((float)c.x, sc, facc.x);
+    facc.y = fmaf((float)c.y, sc, facc.y);
+    facc.z = fmaf((float)c.z, sc, facc.z);
+    facc.w = fmaf((float)c.w, sc, facc.w);
 }
 template <int P>
 __device__ __forceinline__ void compute_super_gq(const u4v* w, const uint8_t* lds_row, v4f& facc)
@@ -256,16 +277,10 @@ __device__ __forceinline__ void compute_super_gq(const u4v* w, const uint8_t* ld
 #pragma unroll
     for (int j = 0; j < 8; ++j) aop[j] = *reinterpret_cast<const v4i*>(lds_row + j * 64);
     const u4v gp = w[P];
-    // one group after the other: scheduled freely, the MFMA results of all four groups are live at once
-    // (up to 80 registers) and the wider variants spill
     group_step<P, 0>(w, aop, gp, facc);
-    __builtin_amdgcn_sched_barrier(0);
     group_step<P, 1>(w, aop, gp, facc);
-    __builtin_amdgcn_sched_barrier(0);
     group_step<P, 2>(w, aop, gp, facc);
-    __builtin_amdgcn_sched_barrier(0);
     group_step<P, 3>(w, aop, gp, facc);
-    __builtin_amdgcn_sched_barrier(0);
 }
 
 // Per-wave streaming state (lives in registers once everything is inlined).
@@ -723,7 +738,7 @@ __host__ __device__ inline int grouped_run_start(const GroupedParams& gp, int b,
     return b >= n ? gp.first_tile[kMaxGroup] : start;
 }
 
-template <int P, int D, int EPT, bool RAW>
+template <int P, int D, int EPT, bool RAW, bool GQ = false>
 __global__ __launch_bounds__(512) void grouped_kernel(GroupedParams gp)
 {
     const int b = (int)blockIdx.x;
@@ -735,7 +750,7 @@ __global__ __launch_bounds__(512) void grouped_kernel(GroupedParams gp)
         if (lo >= hi) continue;   // the same for the whole workgroup
         if (!first) __syncthreads();   // every wave is done with the LDS contents of the problem before
         first = false;
-        skinny_body<P, D, EPT, RAW, false, false, (EPT == 1)>(gp.d[g], lo - gp.first_tile[g], 1, hi - lo, 0);
+        skinny_body<P, D, EPT, RAW, false, false, (EPT == 1 && !GQ), GQ>(gp.d[g], lo - gp.first_tile[g], 1, hi - lo, 0);
     }
 }
 
@@ -780,9 +795,10 @@ static hipError_t launch_pde(const SkinnyParams& prm, dim3 grid, int waves, size
 }
 
 // Per-group weight parameters: one epilogue serves every workgroup size (instantiated as EPT = 1), no K groups.
-// The ring is half as deep as the per-channel kernel's (one super-chunk only at p = 7): the group arithmetic
-// needs the registers, and deeper rings spill.
-__host__ __device__ constexpr int gq_depth(int p, int d) { return p == 7 ? 1 : (d > 2 ? d / 2 : d); }
+// Ring depth, measured against deeper and shallower rings on one box (5120->13824, 11008<->4096, the LLaMA-7B
+// block): four super-chunks at p <= 2 (eight spill), two above (at p = 3, 4 two beat four by 4-11 % in single
+// launches and tie in the grouped launch).
+__host__ __device__ constexpr int gq_depth(int p, int d) { return p <= 2 ? (d > 4 ? 4 : d) : (d > 2 ? 2 : d); }
 template <int P, int D>
 static hipError_t launch_gq(const SkinnyParams& prm, dim3 grid, int waves, size_t lds_bytes, hipStream_t s)
 {
@@ -804,10 +820,27 @@ static hipError_t launch_pd(const SkinnyParams& prm, dim3 grid, int waves, size_
     return launch_pde<P, D, 4>(prm, grid, waves, lds_bytes, s);
 }
 
-// Operand pointers and shape fields of the kernel arguments (everything but the launch plan).
+// Grouped launch on blobs with per-group weight parameters (all problems of a launch alike): one variant per
+// activation form, any workgroup size.
+template <int P, int D>
+static hipError_t launch_grouped_gq(const GroupedParams& gp, bool raw, unsigned grid, int waves, size_t lds_bytes, hipStream_t s)
+{
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)grouped_kernel<P, D, 1, true, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)grouped_kernel<P, D, 1, false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    if (raw) grouped_kernel<P, D, 1, true, true><<<grid, waves * 64, lds_bytes, s>>>(gp);
+    else grouped_kernel<P, D, 1, false, true><<<grid, waves * 64, lds_bytes, s>>>(gp);
+    return hipGetLastError();
+}
+
 template <int P, int D>
 static hipError_t launch_grouped_pd(const GroupedParams& gp, bool raw, unsigned grid, int waves, size_t lds_bytes, hipStream_t s)
 {
+    if (gp.d[0].gparams) return launch_grouped_gq<P, gq_depth(P, D)>(gp, raw, grid, waves, lds_bytes, s);
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)grouped_kernel<P, D, 1, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
