@@ -205,6 +205,29 @@ int abq_gemm_act_codes(int p, int q, int M, int N, int K,
                        uint16_t* y_fp16, int32_t* acc_i32,
                        void* workspace, size_t workspace_bytes, void* stream);
 
+/* Launch-plan table (Appendix D, "auto kernel search": the engine picks, per problem size, the fastest of a
+ * set of kernel configurations found by timing them).  The library chooses every launch plan from closed-form
+ * rules; this table lets a tuner (paper_2408_08554_amd/tune.py times the candidates on the device) replace the
+ * rule for exact problem sizes.  A field left 0 keeps the rule for that knob; a plan that does not fit the
+ * problem (say, more waves than K has 512-blocks) is ignored and the rule applies.  Results never depend on
+ * the plan (per-group weight scales: to their stated bound).  Process-wide, thread-safe; entries hold no
+ * device state.
+ *   skinny_waves    waves per workgroup of the decode kernel = K split of a tile: 1, 2, 4..8
+ *   skinny_kgroups  K groups of the decode kernel: 1..4
+ *   tiled_mt        rows of A per workgroup tile of the prefill kernel / 16: 4 or 8
+ *   tiled_ntw       16-channel tiles of W per wave: 1, 2 or 4
+ *   tiled_wd        operand steps in flight: 2 or 4 (4 exists for tiled_mt = 4 with tiled_ntw <= 2)
+ *   tiled_band      row blocks of A per band of the tile order: >= 1
+ * abq_plan_set: plan == NULL removes the entry.  ABQ_ERR_BITS / ABQ_ERR_SHAPE as abq_gemm; ABQ_ERR_LAYOUT for a
+ * value outside the lists above.  abq_plan_get fills *out (all zero when there is no entry). */
+typedef struct abq_plan {
+    int skinny_waves, skinny_kgroups;
+    int tiled_mt, tiled_ntw, tiled_wd, tiled_band;
+} abq_plan;
+int  abq_plan_set(int p, int q, int M, int N, int K, const abq_plan* plan);
+int  abq_plan_get(int p, int q, int M, int N, int K, abq_plan* out);
+void abq_plan_clear(void);
+
 /* Grouped decode launch (Sec. 3.4: the engine replaces every linear layer of a decoder block; Table 4's
  * matmuls take microseconds each, so launching them one by one leaves the memory system idle between
  * them).  `count` independent problems that share p, q, M and the layouts, each with its own N, K,

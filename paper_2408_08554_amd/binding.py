@@ -29,6 +29,9 @@ _SIGNATURES = {
     "abq_packed_weight_bytes": (_c.c_size_t, [_c.c_int] * 4),
     "abq_pack_weights": (_c.c_int, [_c.c_int] * 3 + [_c.c_void_p] * 3 + [_c.c_int, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
     "abq_pack_weights_g128": (_c.c_int, [_c.c_int] * 3 + [_c.c_void_p] * 3 + [_c.c_void_p, _c.c_size_t, _c.c_void_p]),
+    "abq_plan_set": (_c.c_int, [_c.c_int] * 5 + [_c.c_void_p]),
+    "abq_plan_get": (_c.c_int, [_c.c_int] * 5 + [_c.c_void_p]),
+    "abq_plan_clear": (None, []),
     "abq_unpack_weights": (_c.c_int, [_c.c_int] * 4 + [_c.c_void_p, _c.c_int, _c.c_void_p, _c.c_void_p]),
     "abq_packed_act_bytes": (_c.c_size_t, [_c.c_int] * 4),
     "abq_quant_pack_act": (_c.c_int, [_c.c_int] * 3 + [_c.c_void_p, _c.c_int, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
@@ -265,6 +268,28 @@ def abq_gemm_grouped(p, q, M, problems, a_layout, w_layout, workspace=None):
         workspace = torch.empty(need, dtype=torch.uint8, device="cuda")
     _check(lib.abq_gemm_grouped(p, q, M, len(arr), _c.addressof(arr), a_layout, w_layout, _ptr(workspace),
                                 0 if workspace is None else workspace.numel(), _stream()), "abq_gemm_grouped")
+
+
+class AbqPlan(_c.Structure):
+    """struct abq_plan of include/abq.h (0 = keep the library's rule for that knob)."""
+    _fields_ = [(n, _c.c_int) for n in ("skinny_waves", "skinny_kgroups", "tiled_mt", "tiled_ntw", "tiled_wd", "tiled_band")]
+
+
+def abq_plan_set(p, q, M, N, K, plan=None, **knobs):
+    """plan: an AbqPlan, or knobs as keywords; neither removes the entry."""
+    if plan is None and knobs:
+        plan = AbqPlan(**knobs)
+    _check(load().abq_plan_set(p, q, M, N, K, None if plan is None else _c.addressof(plan)), "abq_plan_set")
+
+
+def abq_plan_get(p, q, M, N, K):
+    out = AbqPlan()
+    _check(load().abq_plan_get(p, q, M, N, K, _c.addressof(out)), "abq_plan_get")
+    return {n: getattr(out, n) for n, _ in AbqPlan._fields_}
+
+
+def abq_plan_clear():
+    load().abq_plan_clear()
 
 
 def abq_probe_stream_read(buf, nbytes, sink):

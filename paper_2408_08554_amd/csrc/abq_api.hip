@@ -5,6 +5,10 @@
 #include "../../include/abq.h"
 
 #include <limits.h>
+#include <array>
+#include <atomic>
+#include <map>
+#include <mutex>
 #include <vector>
 
 namespace abq {
@@ -87,6 +91,22 @@ bool make_act_layout(int q, int M, int K, int layout, ActLayout* L)
         off = align_up(off + (size_t)M * L->Kp, 256);
     }
     L->total = off;
+    return true;
+}
+
+// ---- launch-plan table --------------------------------------------------------------------------
+static std::mutex g_plan_mutex;
+static std::map<std::array<int, 5>, PlanOverride> g_plans;
+static std::atomic<int> g_plan_count{0};   // launches skip the lock while the table is empty
+
+bool lookup_plan(int p, int q, int M, int N, int K, PlanOverride* out)
+{
+    *out = PlanOverride{0, 0, 0, 0, 0, 0};
+    if (g_plan_count.load(std::memory_order_relaxed) == 0) return false;
+    std::lock_guard<std::mutex> lock(g_plan_mutex);
+    auto it = g_plans.find({p, q, M, N, K});
+    if (it == g_plans.end()) return false;
+    *out = it->second;
     return true;
 }
 
@@ -268,6 +288,40 @@ static bool streaming_shape(int M, int N)
     if (M <= kSkinnyMaxM) return true;
     const long tiled_wgs = (long)((M + 63) / 64) * ((N + 63) / 64);
     return M <= 64 && tiled_wgs < 128;
+}
+
+int abq_plan_set(int p, int q, int M, int N, int K, const abq_plan* plan)
+{
+    if (int e = check_gemm_shape(p, q, M, N, K)) return e;
+    std::lock_guard<std::mutex> lock(g_plan_mutex);
+    if (!plan) {
+        g_plans.erase({p, q, M, N, K});
+    } else {
+        const int w = plan->skinny_waves, g = plan->skinny_kgroups, mt = plan->tiled_mt, nt = plan->tiled_ntw, wd = plan->tiled_wd;
+        const bool ok = (w == 0 || w == 1 || w == 2 || (w >= 4 && w <= 8)) && g >= 0 && g <= 4 && (mt == 0 || mt == 4 || mt == 8) &&
+                        (nt == 0 || nt == 1 || nt == 2 || nt == 4) && (wd == 0 || wd == 2 || wd == 4) && plan->tiled_band >= 0;
+        if (!ok) return ABQ_ERR_LAYOUT;
+        g_plans[{p, q, M, N, K}] = PlanOverride{w, g, mt, nt, wd, plan->tiled_band};
+    }
+    g_plan_count.store((int)g_plans.size(), std::memory_order_relaxed);
+    return ABQ_OK;
+}
+
+int abq_plan_get(int p, int q, int M, int N, int K, abq_plan* out)
+{
+    if (!out) return ABQ_ERR_NULL;
+    if (int e = check_gemm_shape(p, q, M, N, K)) return e;
+    PlanOverride o;
+    lookup_plan(p, q, M, N, K, &o);
+    *out = abq_plan{o.skinny_waves, o.skinny_kgroups, o.tiled_mt, o.tiled_ntw, o.tiled_wd, o.tiled_band};
+    return ABQ_OK;
+}
+
+void abq_plan_clear(void)
+{
+    std::lock_guard<std::mutex> lock(g_plan_mutex);
+    g_plans.clear();
+    g_plan_count.store(0, std::memory_order_relaxed);
 }
 
 size_t abq_gemm_workspace_bytes(int p, int q, int M, int N, int K)

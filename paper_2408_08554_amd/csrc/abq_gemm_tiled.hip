@@ -337,16 +337,17 @@ __global__ __launch_bounds__(256, (WD == 4 ? 2 : (NTW <= 2 ? (MT == 4 ? 3 : 2) :
 }
 
 template <int P, int NTW, int MT>
-static hipError_t launch_shape(const TiledParams& prm, dim3 grid, int cus, hipStream_t s)
+static hipError_t launch_shape(const TiledParams& prm, dim3 grid, int cus, int plan_wd, hipStream_t s)
 {
     // The deep rings exist for the small tile shapes (for two tiles of W per wave only up to p = 6: beyond, the
     // registers run out) and run two workgroups per CU instead of three.  Measured: with at most one workgroup
     // per CU (M = 64..128 on a 4096-wide layer) they are 20 % faster, with more workgroups (M = 128 on an
     // 11008-wide layer and up) the traffic through L2, not the latency of a step, is the bound and they lose.
-    // Tuning override, read once: ABQ_TILED_WD=<2|4>.
+    // Overrides: the plan table (plan_wd), else ABQ_TILED_WD=<2|4> (read once).
     constexpr bool has_deep = MT == 4 && (NTW == 1 || (NTW == 2 && P <= 6));
-    static int forced = -1;
-    if (forced < 0) { const char* e = getenv("ABQ_TILED_WD"); forced = e ? atoi(e) : 0; }
+    static int env_forced = -1;
+    if (env_forced < 0) { const char* e = getenv("ABQ_TILED_WD"); env_forced = e ? atoi(e) : 0; }
+    const int forced = plan_wd > 0 ? plan_wd : env_forced;
     if constexpr (has_deep) {
         if (forced == 4 || (forced != 2 && (long)grid.x <= (long)cus)) {
             tiled_kernel<P, NTW, MT, 4><<<grid, 256, 0, s>>>(prm);
@@ -358,16 +359,16 @@ static hipError_t launch_shape(const TiledParams& prm, dim3 grid, int cus, hipSt
 }
 
 template <int P>
-static hipError_t launch_p(const TiledParams& prm, int ntw, int mt, dim3 grid, int cus, hipStream_t s)
+static hipError_t launch_p(const TiledParams& prm, int ntw, int mt, dim3 grid, int cus, int plan_wd, hipStream_t s)
 {
     if (mt == 4) {
-        if (ntw == 1) return launch_shape<P, 1, 4>(prm, grid, cus, s);
-        if (ntw == 2) return launch_shape<P, 2, 4>(prm, grid, cus, s);
-        return launch_shape<P, 4, 4>(prm, grid, cus, s);
+        if (ntw == 1) return launch_shape<P, 1, 4>(prm, grid, cus, plan_wd, s);
+        if (ntw == 2) return launch_shape<P, 2, 4>(prm, grid, cus, plan_wd, s);
+        return launch_shape<P, 4, 4>(prm, grid, cus, plan_wd, s);
     }
-    if (ntw == 1) return launch_shape<P, 1, 8>(prm, grid, cus, s);
-    if (ntw == 2) return launch_shape<P, 2, 8>(prm, grid, cus, s);
-    return launch_shape<P, 4, 8>(prm, grid, cus, s);
+    if (ntw == 1) return launch_shape<P, 1, 8>(prm, grid, cus, plan_wd, s);
+    if (ntw == 2) return launch_shape<P, 2, 8>(prm, grid, cus, plan_wd, s);
+    return launch_shape<P, 4, 8>(prm, grid, cus, plan_wd, s);
 }
 
 hipError_t launch_gemm_tiled(const GemmArgs& g, const ActLayout& A, const WeightLayout& W, hipStream_t s)
@@ -386,12 +387,17 @@ hipError_t launch_gemm_tiled(const GemmArgs& g, const ActLayout& A, const Weight
     prm.ow = (g.p == 8) ? 128 : 0;
     // Tile shape (rows of A x rows of W per workgroup), measured on LLaMA-7B/13B prefill shapes: 128x128
     // while it yields at least 1.5 workgroups per CU (two or three share a CU), else 64x128, else 64x64.
+    // Narrow weights (p <= 4) with M >= 1024 do better with 64 rows of A against 256 (or 128) rows of W: the
+    // launch-plan search on M = 1024..8192 found 64x256 3-19 % ahead of 128x128 at p = 2, 4 where it still
+    // yields three workgroups per CU, and 64x128 ahead of both where it does not (N = 5120: 124 vs 144 us);
+    // at M = 512 and at p = 8 128x128 stays ahead.
     int cus = 256, dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
     auto wgs = [&](int mt_, int ntw_) { return (long)((g.M + mt_ * 16 - 1) / (mt_ * 16)) * ((g.N + 64 * ntw_ - 1) / (64 * ntw_)); };
     int mt = 8, ntw = 2;
     if (g.M <= 64 || 2 * wgs(8, 2) < 3L * cus) { mt = 4; ntw = 2; }
-    if (mt == 4 && 2 * wgs(4, 2) < 3L * cus) ntw = 1;
+    else if (g.p <= 4 && g.M >= 1024) { mt = 4; ntw = wgs(4, 4) >= 3L * cus ? 4 : 2; }
+    if (mt == 4 && ntw == 2 && 2 * wgs(4, 2) < 3L * cus) ntw = 1;
     {
         static int forced_mt = -1, forced_ntw = -1;   // tuning overrides, read once: ABQ_TILED_MT=<4|8>, ABQ_TILED_NTW=<1|2|4>
         if (forced_mt < 0) { const char* e = getenv("ABQ_TILED_MT"); forced_mt = e ? atoi(e) : 0; }
@@ -399,29 +405,33 @@ hipError_t launch_gemm_tiled(const GemmArgs& g, const ActLayout& A, const Weight
         if (forced_mt == 4 || forced_mt == 8) mt = forced_mt;
         if (forced_ntw == 1 || forced_ntw == 2 || forced_ntw == 4) ntw = forced_ntw;
     }
+    PlanOverride ov;   // the plan table entry of this exact problem goes before the environment
+    lookup_plan(g.p, g.q, g.M, g.N, g.K, &ov);
+    if (ov.tiled_mt > 0) mt = ov.tiled_mt;
+    if (ov.tiled_ntw > 0) ntw = ov.tiled_ntw;
     prm.tiles_m = (g.M + mt * 16 - 1) / (mt * 16);
     prm.tiles_n = (g.N + 64 * ntw - 1) / (64 * ntw);
     // Bands of equal height.  The workgroups resident on one XCD (about 64) form a band_m x (64 / band_m)
     // patch of tiles whose L2 fills cost band_m row blocks of A (one byte per element) plus 64 / band_m
-    // column blocks of W (p/8 byte per element): least near band_m = sqrt(8p), and measured so on M = 2048
-    // and 8192 (4 row blocks for p <= 4, 8 above).
+    // column blocks of W (p/8 byte per element): least near band_m = sqrt(8p) blocks of 128 rows, and measured
+    // so on M = 2048 and 8192: bands of 512 rows of A for p <= 4, 1024 above.
     {
         static int forced_band = -1;   // tuning override, read once: ABQ_TILED_BAND=<row blocks per band>
         if (forced_band < 0) { const char* e = getenv("ABQ_TILED_BAND"); forced_band = e ? atoi(e) : 0; }
-        const int cap = forced_band > 0 ? forced_band : (g.p <= 4 ? 4 : 8);
+        const int cap = ov.tiled_band > 0 ? ov.tiled_band : (forced_band > 0 ? forced_band : (g.p <= 4 ? 512 : 1024) / (mt * 16));
         const int bands = (prm.tiles_m + cap - 1) / cap;
         prm.band_m = (prm.tiles_m + bands - 1) / bands;
     }
     dim3 grid((unsigned)(prm.tiles_m * prm.tiles_n));
     switch (g.p) {
-        case 1: return launch_p<1>(prm, ntw, mt, grid, cus, s);
-        case 2: return launch_p<2>(prm, ntw, mt, grid, cus, s);
-        case 3: return launch_p<3>(prm, ntw, mt, grid, cus, s);
-        case 4: return launch_p<4>(prm, ntw, mt, grid, cus, s);
-        case 5: return launch_p<5>(prm, ntw, mt, grid, cus, s);
-        case 6: return launch_p<6>(prm, ntw, mt, grid, cus, s);
-        case 7: return launch_p<7>(prm, ntw, mt, grid, cus, s);
-        default: return launch_p<8>(prm, ntw, mt, grid, cus, s);
+        case 1: return launch_p<1>(prm, ntw, mt, grid, cus, ov.tiled_wd, s);
+        case 2: return launch_p<2>(prm, ntw, mt, grid, cus, ov.tiled_wd, s);
+        case 3: return launch_p<3>(prm, ntw, mt, grid, cus, ov.tiled_wd, s);
+        case 4: return launch_p<4>(prm, ntw, mt, grid, cus, ov.tiled_wd, s);
+        case 5: return launch_p<5>(prm, ntw, mt, grid, cus, ov.tiled_wd, s);
+        case 6: return launch_p<6>(prm, ntw, mt, grid, cus, ov.tiled_wd, s);
+        case 7: return launch_p<7>(prm, ntw, mt, grid, cus, ov.tiled_wd, s);
+        default: return launch_p<8>(prm, ntw, mt, grid, cus, ov.tiled_wd, s);
     }
 }
 

@@ -82,6 +82,10 @@ hipError_t launch_rmsnorm_quant(int q, int M, int K, const uint16_t* x, const ui
 hipError_t launch_silu_mul_quant(int q, int M, int K, const uint16_t* gate, const uint16_t* up, uint8_t* codes, float* scale,
                                  int32_t* zero, uint16_t* h_out, hipStream_t s);
 
+// Launch-plan override for one exact problem size (0 = keep the library's rule); see abq_plan in the ABI header.
+struct PlanOverride { int skinny_waves, skinny_kgroups, tiled_mt, tiled_ntw, tiled_wd, tiled_band; };
+bool lookup_plan(int p, int q, int M, int N, int K, PlanOverride* out);   // false (and *out all zero) when none is set
+
 struct GemmArgs {
     int p, q, M, N, K;
     const uint8_t* act_blob;   // packed activations, or null when a_raw is given (streaming kernel only)

@@ -100,12 +100,11 @@ static int env_int(const char* name)
 }
 
 // one_group: the kernel variant at hand has no K groups (then long K with many rows takes more passes over W).
-static bool pick_plan(int M, int Kp, int ntiles, int cus, size_t stream_bytes, bool one_group, SkinnyPlan* best)
+// forced / forced_g > 0: the K split / group count to use if it fits (from the plan table or the environment).
+static bool pick_plan(int M, int Kp, int ntiles, int cus, size_t stream_bytes, bool one_group, int forced, int forced_g,
+                      SkinnyPlan* best)
 {
     static const int candidates[] = {8, 7, 6, 5, 4, 2, 1};
-    // tuning overrides (read once): ABQ_SKINNY_WAVES=<S> forces the K split, ABQ_SKINNY_KGROUPS=<G> the group count
-    static int forced = -1, forced_g = -1;
-    if (forced < 0) { forced = env_int("ABQ_SKINNY_WAVES"); forced_g = env_int("ABQ_SKINNY_KGROUPS"); }
     const int m16 = M < 16 ? M : 16;
     // K groups are used only where one group cannot hold all (up to 16) rows of A, and then as few as possible.
     // Long streams over many tiles (measured: >= 48 MB, >= 2 tiles per CU) run best as one resident
@@ -153,7 +152,7 @@ static bool pick_plan(int M, int Kp, int ntiles, int cus, size_t stream_bytes, b
         if (forced_g <= 0 && search(2, 4, true, &grouped)) { *best = grouped; return true; }
         if (one) return true;
     }
-    if (forced > 0 || forced_g > 0) { forced = 0; forced_g = 0; return pick_plan(M, Kp, ntiles, cus, stream_bytes, one_group, best); }
+    if (forced > 0 || forced_g > 0) return pick_plan(M, Kp, ntiles, cus, stream_bytes, one_group, 0, 0, best);   // does not fit: the rule
     return false;
 }
 
@@ -189,7 +188,15 @@ hipError_t launch_gemm_skinny(const GemmArgs& g, const ActLayout& A, const Weigh
     const int nsuper = A.Kp / kSuperK;
     SkinnyPlan pl;
     const size_t stream_bytes = (size_t)g.p * W.NT * 16 * (size_t)A.Kp / 8;
-    if (!pick_plan(g.M, A.Kp, W.NT, cus, stream_bytes, W.g128, &pl)) return hipErrorInvalidValue;   // cannot happen for K <= ABQ_MAX_K
+    // overrides: the plan table entry of this exact problem, else the environment (read once):
+    // ABQ_SKINNY_WAVES=<S> forces the K split, ABQ_SKINNY_KGROUPS=<G> the group count
+    static int env_waves = -1, env_groups = -1;
+    if (env_waves < 0) { env_waves = env_int("ABQ_SKINNY_WAVES"); env_groups = env_int("ABQ_SKINNY_KGROUPS"); }
+    PlanOverride ov;
+    lookup_plan(g.p, g.q, g.M, g.N, g.K, &ov);
+    const int forced = ov.skinny_waves > 0 ? ov.skinny_waves : env_waves;
+    const int forced_g = ov.skinny_kgroups > 0 ? ov.skinny_kgroups : env_groups;
+    if (!pick_plan(g.M, A.Kp, W.NT, cus, stream_bytes, W.g128, forced, forced_g, &pl)) return hipErrorInvalidValue;   // cannot happen for K <= ABQ_MAX_K
     const int waves = pl.waves, gx = pl.gx, mrows = pl.mrows;
     // LDS: staged rows of A (all of K, or one K group of it), the epilogue parameters, two reduction buffers
     // of 1 KiB per wave, the partial sums of the K groups

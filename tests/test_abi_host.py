@@ -96,6 +96,33 @@ def test_g128_pack_rejects_and_size_query():
     assert q(4, 8, 2, 64, 1000, G128) == lib.abq_packed_act_bytes(8, 2, 1000, B.ABQ_LAYOUT_FIELDS)   # K not a multiple of 16
 
 
+def test_plan_table_set_get_clear_and_rejects():
+    B.load()
+    B.abq_plan_clear()
+    zero = dict(skinny_waves=0, skinny_kgroups=0, tiled_mt=0, tiled_ntw=0, tiled_wd=0, tiled_band=0)
+    assert B.abq_plan_get(4, 8, 1, 4096, 4096) == zero
+    B.abq_plan_set(4, 8, 1, 4096, 4096, skinny_waves=6)
+    B.abq_plan_set(6, 6, 512, 11008, 4096, tiled_mt=4, tiled_ntw=2, tiled_wd=4, tiled_band=8)
+    assert B.abq_plan_get(4, 8, 1, 4096, 4096) == dict(zero, skinny_waves=6)
+    assert B.abq_plan_get(6, 6, 512, 11008, 4096) == dict(zero, tiled_mt=4, tiled_ntw=2, tiled_wd=4, tiled_band=8)
+    assert B.abq_plan_get(4, 8, 2, 4096, 4096) == zero                      # exact problem sizes only
+    B.abq_plan_set(4, 8, 1, 4096, 4096)                                     # no plan: removes the entry
+    assert B.abq_plan_get(4, 8, 1, 4096, 4096) == zero
+    assert B.abq_plan_get(6, 6, 512, 11008, 4096)["tiled_mt"] == 4
+    B.abq_plan_clear()
+    assert B.abq_plan_get(6, 6, 512, 11008, 4096) == zero
+    lib = B.load()
+    for bad in (dict(skinny_waves=3), dict(skinny_waves=9), dict(skinny_kgroups=5), dict(tiled_mt=6), dict(tiled_ntw=3),
+                dict(tiled_wd=3), dict(tiled_band=-1)):
+        plan = B.AbqPlan(**bad)
+        assert lib.abq_plan_set(4, 8, 1, 64, 64, ctypes.addressof(plan)) == B.ABQ_ERR_LAYOUT, bad
+    plan = B.AbqPlan(skinny_waves=4)
+    assert lib.abq_plan_set(9, 8, 1, 64, 64, ctypes.addressof(plan)) == B.ABQ_ERR_BITS
+    assert lib.abq_plan_set(4, 8, 0, 64, 64, ctypes.addressof(plan)) == B.ABQ_ERR_SHAPE
+    assert lib.abq_plan_get(4, 8, 1, 64, 64, None) == B.ABQ_ERR_NULL
+    assert B.abq_plan_get(4, 8, 1, 64, 64) == zero                          # rejected plans left nothing behind
+
+
 def test_pack_act_codes_rejects():
     lib = B.load()
     assert lib.abq_pack_act_codes(8, 1, 64, A16, None, A16, 0, A16, 1 << 20, None) == B.ABQ_ERR_NULL

@@ -557,6 +557,39 @@ def test_bit_balance_five_level_weights(abq, M, N, K, fused):
     assert np.allclose(yref, real, rtol=1e-12, atol=0)
 
 
+# ---- launch-plan table: every candidate plan of the tuner returns the oracle's result -------------------------
+
+@pytest.mark.parametrize("p,q,M,N,K", [(4, 8, 1, 256, 4096), (2, 8, 5, 70, 1000), (8, 8, 16, 70, 13824), (6, 6, 128, 300, 2048),
+                                       (3, 5, 40, 100, 1536), (4, 4, 300, 520, 1024)])
+def test_every_candidate_plan_gives_the_same_result(abq, p, q, M, N, K):
+    from paper_2408_08554_amd import tune
+    c = synth.make_case(p, q, M, N, K, seed=9600 + M)
+    plans = tune.candidates(p, q, M, N, K)
+    assert len(plans) >= 3 and plans[0] == {}
+    try:
+        for plan in plans:
+            say(f"plan {plan} on {p, q, M, N, K}")
+            abq.abq_plan_set(p, q, M, N, K, **plan)
+            assert {k: v for k, v in abq.abq_plan_get(p, q, M, N, K).items() if v} == plan
+            y, acc = gpu_gemm(torch, abq, c, FIELDS, FIELDS)
+            check_against_oracle(c, y, acc)
+            if K % 16 == 0:
+                y, acc = gpu_gemm_fused(torch, abq, c, FIELDS)
+                check_against_oracle(c, y, acc)
+    finally:
+        abq.abq_plan_clear()
+
+
+def test_tuner_search_reports_the_rule_and_restores_the_table(abq):
+    from paper_2408_08554_amd import tune
+    abq.abq_plan_set(4, 8, 1, 512, 2048, skinny_waves=2)
+    rows = tune.search(4, 8, 1, 512, 2048, launches=20, rotate_bytes=1 << 24)
+    assert any(not plan for _, plan in rows) and all(t > 0 for t, _ in rows)
+    assert rows == sorted(rows, key=lambda r: r[0])
+    assert abq.abq_plan_get(4, 8, 1, 512, 2048)["skinny_waves"] == 2
+    abq.abq_plan_clear()
+
+
 # ---- per-group weight scales and zero-points, groups of 128 along K (Appendix C) -------------------------
 
 G128 = 4   # ABQ_LAYOUT_FIELDS_G128
