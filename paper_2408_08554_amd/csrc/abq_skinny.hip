@@ -15,6 +15,8 @@
 // the way to the first MFMA).  Per tile the S partial tiles are summed through LDS.
 #include "abq_skinny_kernels.h"
 
+#include <math.h>
+
 namespace abq {
 
 // ---- host side -------------------------------------------------------------------------------------
@@ -36,6 +38,7 @@ static int num_cus()
 // The kernels use up to 256 VGPRs, i.e. two waves per SIMD, eight per CU.
 static const int kWavesPerCu = 8;
 static const size_t kLdsPerCu = 160 * 1024;
+static const int kMaxWalk = 64;   // most tiles one workgroup walks (their epilogue parameters live in LDS)
 static const size_t kAsumBytes = 8 * 16 * sizeof(int32_t) + 512;   // per-wave partial row sums of A and 512 zero bytes, kept at the end of the parameter area
 
 // Launch plan: S waves per workgroup (= K split of a tile) and gx workgroups walking the tiles.
@@ -74,7 +77,14 @@ static bool make_plan(int S, int G, int M, int Kp, int ntiles, int cus, SkinnyPl
         int per_cu = (int)(kLdsPerCu / lds);
         if (per_cu > kWavesPerCu / S) per_cu = kWavesPerCu / S;
         if (per_cu < 1) per_cu = 1;
-        const int gx = ntiles < cus * per_cu ? ntiles : cus * per_cu;
+        // M > mrows: the launch has one set of gx workgroups per group of mrows rows.  All sets together should be
+        // resident at once, each workgroup walking more tiles (A staged once per workgroup, the ring running
+        // across its tiles), rather than several rounds of workgroups that each stage their rows of A afresh.
+        const int row_groups = (M + mrows - 1) / mrows;
+        int slots = cus * per_cu / row_groups;
+        if (slots < 1) slots = 1;
+        int gx = ntiles < slots ? ntiles : slots;
+        if ((ntiles + gx - 1) / gx > kMaxWalk) gx = (ntiles + kMaxWalk - 1) / kMaxWalk;   // (many row groups: several rounds after all)
         const int new_rounds = (ntiles + gx - 1) / gx;
         if (new_rounds > rounds) { rounds = new_rounds; continue; }
         out->waves = S; out->gx = gx; out->mrows = mrows; out->kgroups = G; out->cap = cap; out->rounds = rounds;
@@ -82,12 +92,24 @@ static bool make_plan(int S, int G, int M, int Kp, int ntiles, int cus, SkinnyPl
         out->lds_bytes = lds;
         if (lds > kLdsPerCu) return false;
         const double waves_cu = (double)per_cu * S < kWavesPerCu ? (double)per_cu * S : kWavesPerCu;
-        const double occupancy = (double)gx * S / cus < waves_cu ? (double)gx * S / cus : waves_cu;
+        const double occupancy = (double)gx * row_groups * S / cus < waves_cu ? (double)gx * row_groups * S / cus : waves_cu;
         const double k_eff = (double)nsuper / (nsw_max * S);
-        const double t_eff = (double)ntiles / ((double)rounds * gx);
-        const double m_eff = 1.0 / ((m16 + mrows - 1) / mrows);   // passes over W
+        // tiles the busiest CU works through (its workgroups, each walking `rounds` tiles) against an even spread
+        const long wgs_busiest = ((long)gx * row_groups + cus - 1) / cus;
+        const double t_eff = ((double)ntiles * row_groups / cus) / ((double)wgs_busiest * rounds) < 1.0
+                                 ? ((double)ntiles * row_groups / cus) / ((double)wgs_busiest * rounds) : 1.0;
+        const double m_eff = (double)((M + 15) / 16) / row_groups;   // passes over W against the fewest possible
         const double g_eff = 1.0 / (1.0 + 0.1 * (G - 1));
-        *score = (occupancy / kWavesPerCu) * k_eff * t_eff * m_eff * g_eff;
+        // Staging A: one load instruction covers a row over TWO of the wave's super-chunks, so a wave with an odd
+        // count wastes half an instruction per row, all of it when it owns a single super-chunk; it matters as
+        // the rows grow (measured with the plan search at K = 4096: from four rows on, four waves with two
+        // super-chunks each beat eight waves with one by 13-20 %; at one or two rows eight stay ahead).  For the
+        // same reason half-filled CUs cost less than their share of idle wave slots (the exponent below).
+        const int run = (nsw_max + G - 1) / G;
+        const double stage_eff = (double)run / (2 * ((run + 1) / 2));
+        const double row_weight = mrows >= 4 ? 1.0 : (mrows - 1) / 3.0;
+        const double s_eff = 1.0 - row_weight * (1.0 - stage_eff);
+        *score = pow(occupancy / kWavesPerCu, 0.75) * k_eff * t_eff * m_eff * g_eff * s_eff;
         return true;
     }
     return false;
@@ -147,7 +169,8 @@ static bool pick_plan(int M, int Kp, int ntiles, int cus, size_t stream_bytes, b
     } else {
         if (forced_g > 1 && search(forced_g, forced_g, false, best)) return true;
         const bool one = search(1, 1, false, best);
-        if (one && best->mrows == m16) return true;
+        // (no K groups where they save no pass over W: all rows fit, or M > 16 needs as many passes anyway)
+        if (one && (best->mrows == m16 || (M + best->mrows - 1) / best->mrows == (M + 15) / 16)) return true;
         SkinnyPlan grouped;
         if (forced_g <= 0 && search(2, 4, true, &grouped)) { *best = grouped; return true; }
         if (one) return true;
