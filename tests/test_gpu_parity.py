@@ -630,6 +630,55 @@ def test_g128_shapes(abq, M, N, K, p, q, fused):
     check_g128(c, sh, zg, run_g128(abq, c, sh, zg, fused))
 
 
+@pytest.mark.parametrize("p", [1, 2, 4, 7, 8])
+@pytest.mark.parametrize("kind", ["zero_points_at_both_ends", "all_codes_maximal", "all_codes_zero", "zero_scales"])
+def test_g128_extremes(abq, p, kind):
+    # the zero-point rides an MFMA operand byte as -z (p <= 7: down to -127) or is subtracted in integers (p = 8:
+    # z - 128 spans -128..127); the ends of those ranges, saturated operands and dead groups
+    q, M, N, K = 8, 5, 40, 1300                      # 11 groups, the last of 20 values
+    c = synth.make_case(p, q, M, N, K, seed=9700 + p)
+    sh, zg = synth.group_quant_params(c)
+    top = (1 << p) - 1
+    if kind == "zero_points_at_both_ends":
+        zg[:, 0::2] = 0
+        zg[:, 1::2] = top
+        c.a_zero[:] = [0, 255, 128, 1, 254]
+    elif kind == "all_codes_maximal":
+        c.W[:] = top
+        c.A[:] = 255
+        zg[:] = 0
+        c.a_zero[:] = 0
+        c.a_scale[:] = np.float32(1e-4)
+    elif kind == "all_codes_zero":
+        c.W[:] = 0
+        c.A[:] = 0
+        zg[:] = top
+        c.a_zero[:] = 255
+        c.a_scale[:] = np.float32(1e-4)
+    else:
+        sh[:, 3:7] = 0                               # binary16 +0: groups that contribute nothing
+        sh[:, 8] = 0x8000                            # and -0
+    for fused in (False, True):
+        if fused and K % 16:
+            continue
+        check_g128(c, sh, zg, run_g128(abq, c, sh, zg, fused))
+    c2 = synth.make_case(p, q, 3, 17, 1296, seed=9750 + p)      # K a multiple of 16: the fused entry point as well
+    sh2, zg2 = synth.group_quant_params(c2)
+    if kind == "zero_points_at_both_ends":
+        zg2[:, 0::2] = top
+        zg2[:, 1::2] = 0
+    check_g128(c2, sh2, zg2, run_g128(abq, c2, sh2, zg2, True))
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 1, 1), (1, 16, 127), (2, 3, 129), (64, 48, 1024), (100, 20, 640), (16, 1, 8192)])
+def test_g128_degenerate_and_many_rows(abq, M, N, K):
+    c = synth.make_case(4, 8, M, N, K, seed=9800 + M + K)
+    sh, zg = synth.group_quant_params(c)
+    check_g128(c, sh, zg, run_g128(abq, c, sh, zg, False))
+    if K % 16 == 0:
+        check_g128(c, sh, zg, run_g128(abq, c, sh, zg, True))
+
+
 def test_g128_exact_when_the_float_sum_is_exact(abq):
     # power-of-two scales and small codes: every product and partial sum is an integer multiple of 2^-10 below
     # 2^24 ulps, so binary32 accumulates without rounding and the output must equal the oracle's bit for bit
