@@ -36,7 +36,8 @@ MEASURED_TRAFFIC_BYTES = {
     "C2 W4A8 GEMV 4096x4096 g128": int((4482.0 * 8768.2 / 4396.6 + 8.0) * 1024),
     "C5 W4A8 M=1 K=5120 N=13824 g128": int((18575.5 * 36936.2 / 18483.2 + 27.0) * 1024),
     "C4 W6A6 GEMM M=512 4096->11008": int((26750.5 * 33196.2 / 16612.3 + 11008.1) * 1024),
-    "C5 W4A4 M=2048 K=5120 N=13824": int((122141.9 * 34776.2 / 17402.2 + 55299.1) * 1024),
+    "C5 W4A4 M=2048 K=5120 N=13824": int((125201.5 * 34776.2 / 17402.1 + 55296.0) * 1024),
+    "C5 W2A8 M=2048 K=5120 N=13824": int((70795.0 * 17496.2 / 8762.0 + 55296.0) * 1024),
 }
 
 
