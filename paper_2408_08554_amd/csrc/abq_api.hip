@@ -5,6 +5,7 @@
 #include "../../include/abq.h"
 
 #include <limits.h>
+#include <stdlib.h>
 #include <array>
 #include <atomic>
 #include <map>
@@ -286,8 +287,15 @@ static const int kSkinnyMaxM = 16;   // one MFMA tile of activation rows: the st
 static bool streaming_shape(int M, int N)
 {
     if (M <= kSkinnyMaxM) return true;
+    static int max_m = -1, max_wgs = -1;   // tuning overrides, read once: ABQ_STREAM_MAX_M, ABQ_STREAM_MAX_WGS
+    if (max_m < 0) {
+        const char* e = getenv("ABQ_STREAM_MAX_M");
+        max_m = e ? atoi(e) : 64;
+        e = getenv("ABQ_STREAM_MAX_WGS");
+        max_wgs = e ? atoi(e) : 128;
+    }
     const long tiled_wgs = (long)((M + 63) / 64) * ((N + 63) / 64);
-    return M <= 64 && tiled_wgs < 128;
+    return M <= max_m && tiled_wgs < max_wgs;
 }
 
 int abq_plan_set(int p, int q, int M, int N, int K, const abq_plan* plan)
