@@ -288,3 +288,19 @@ def test_unpack_rejects():
     assert lib.abq_unpack_weights(4, 16, 64, B.ABQ_LAYOUT_FIELDS, A16, B.ABQ_LAYOUT_PLANES, A16, None) == B.ABQ_ERR_LAYOUT
     assert lib.abq_unpack_weights(4, 16, 64, B.ABQ_LAYOUT_FIELDS, None, B.ABQ_LAYOUT_FIELDS, A16, None) == B.ABQ_ERR_NULL
     assert lib.abq_unpack_act(8, 1, 64, B.ABQ_LAYOUT_PLANES, A16, B.ABQ_LAYOUT_FIELDS, A16, None, None, None, None) == B.ABQ_ERR_LAYOUT
+
+
+def test_tuner_candidate_plans_are_valid_plan_table_entries():
+    """Every plan the search would try must be one the table accepts (no GPU needed: the table is host state)."""
+    from paper_2408_08554_amd import tune
+    B.load()
+    B.abq_plan_clear()
+    for shape in [(4, 8, 1, 4096, 4096), (8, 8, 16, 5120, 13824), (2, 8, 40, 100, 1536), (6, 6, 128, 11008, 4096),
+                  (4, 4, 2048, 13824, 5120), (1, 1, 1, 16, 100)]:
+        plans = tune.candidates(*shape)
+        assert plans[0] == {} and len({tuple(sorted(pl.items())) for pl in plans}) == len(plans)      # the rule first, no duplicates
+        for plan in plans:
+            assert set(plan) <= set(tune.KNOBS)
+            B.abq_plan_set(*shape, **plan) if plan else B.abq_plan_set(*shape)
+            assert {k: v for k, v in B.abq_plan_get(*shape).items() if v} == plan
+    B.abq_plan_clear()
