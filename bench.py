@@ -30,9 +30,9 @@ INT8_MFMA_PEAK_TOPS = 5000.0    # MI355X published dense int8
 # scaled by what the same counter reads for a plain copy of known size in the same run (FETCH_SIZE
 # reads 0.5015x on this chip, WRITE_SIZE 1.000x); figures and commands are in profiles/.
 MEASURED_TRAFFIC_BYTES = {
-    "C2 W4A8 GEMV 4096x4096": int((4232.0 * 8256.25 / 4140.9 + 8.0) * 1024),
-    "C3 W2A8 GEMV M=1 11008->4096": int((5821.5 * 11328.25 / 5677.3 + 8.0) * 1024),
-    "C5 W8A8 M=1 K=5120 N=13824": int((34785.6 * 69336.2 / 34687.3 + 27.0) * 1024),
+    "C2 W4A8 GEMV 4096x4096": int((4233.0 * 8256.25 / 4141.0 + 8.0) * 1024),
+    "C3 W2A8 GEMV M=1 11008->4096": int((5822.0 * 11328.25 / 5677.5 + 8.0) * 1024),
+    "C5 W8A8 M=1 K=5120 N=13824": int((34782.1 * 69336.25 / 34687.75 + 27.0) * 1024),
     "C2 W4A8 GEMV 4096x4096 g128": int((4482.0 * 8768.2 / 4396.6 + 8.0) * 1024),
     "C5 W4A8 M=1 K=5120 N=13824 g128": int((18575.5 * 36936.2 / 18483.2 + 27.0) * 1024),
     "C4 W6A6 GEMM M=512 4096->11008": int((26750.5 * 33196.2 / 16612.3 + 11008.1) * 1024),
@@ -124,7 +124,7 @@ def measured_peaks(pool, workload_bytes, launches=200):
 
 
 # HBM bytes per abq_gemm_grouped launch over BLOCK_7B, measured the same way (profiles/grouped_kernel_*), by (p, q, M).
-MEASURED_GROUPED_TRAFFIC_BYTES = {(4, 8, 1): 103087465, (8, 8, 1): 204660282}
+MEASURED_GROUPED_TRAFFIC_BYTES = {(4, 8, 1): 103116232, (8, 8, 1): 204653570}
 
 # The seven linear layers of one LLaMA-7B decoder block as (name, N, K): the shapes the paper's engine
 # replaces in a block (Sec. 3.4; Appendix D measures these layer shapes one by one).
