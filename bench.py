@@ -83,6 +83,20 @@ def cpu_baseline(c, budget_s, group_params=None):
             f"dequant + half rounding) in {el:.1f} s"}
 
 
+def child_summary(flags):
+    """Runs this script once more with `flags` (no cpu baseline, no grouped leg, no further children) and returns
+    the few figures of its JSON line that the parent reports; None fields when the child fails."""
+    import subprocess
+    cmd = [sys.executable, os.path.abspath(__file__), *flags, "--cpu-seconds", "0", "--grouped-steps", "0"]
+    try:
+        r = subprocess.run(cmd, capture_output=True, text=True, timeout=300)
+        d = json.loads([l for l in r.stdout.splitlines() if l.startswith("{")][-1])
+        return {"workload": d["config"]["workload"], "step": d["config"]["step"], "kernel_us": d["roofline"]["kernel_us_hip_events"],
+                "value": d["value"], "unit": d["unit"], "roofline": {k: d["roofline"][k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")}}
+    except Exception as e:   # the main figures stand on their own
+        return {"error": f"{type(e).__name__}: {e}"}
+
+
 def measured_peaks(pool, workload_bytes, launches=200):
     """What this machine delivers for the two kinds of work the kernels are priced against, with the library's
     probe kernels, graph-launched like the workload: a plain streaming read (of the workload's own size and of
@@ -315,6 +329,8 @@ def main():
     ap.add_argument("--no-check", action="store_true")
     ap.add_argument("--g128", action="store_true",
                     help="per-group weight scales and zero-points (groups of 128 along K, Appendix C) on the workload's shape")
+    ap.add_argument("--no-other-paths", dest="other_paths", action="store_false",
+                    help="skip the two short child runs (g128 decode, prefill) that the default run reports beside the main workload")
     ap.add_argument("--grouped-steps", type=int, default=200,
                     help="launches of the grouped decoder-block leg reported beside the main workload (0 = skip)")
     args = ap.parse_args()
@@ -522,6 +538,13 @@ def main():
         out["grouped_decoder_block"] = bench_grouped(p, q, M, args.grouped_steps, 20, args.rotate_gib, not args.no_check, args.g128)
     if args.cpu_seconds > 0:
         out["cpu_baseline"] = cpu_baseline(c, args.cpu_seconds, (g_scale_half, g_zero) if args.g128 else None)
+    if args.other_paths and not args.g128 and args.workload == "c2" and args.grouped_steps > 0:
+        # the other kernels of the path, each as a short run of this script in a child process (own parity check):
+        # the same decode step on per-group (g128) weight parameters, and a prefill matmul on the tiled kernel
+        out["other_paths"] = {
+            "decode_g128_weights": child_summary(["--workload", "c2", "--g128", "--steps", "500", "--warmup", "50"]),
+            "prefill_w4a4_m2048": child_summary(["--workload", "c5:4,4,0,3", "--step", "two", "--steps", "30", "--warmup", "5"]),
+        }
     print(json.dumps(out), flush=True)
 
 
