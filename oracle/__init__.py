@@ -197,6 +197,19 @@ def quant_act(x_half, q):
     return codes, sc, zp
 
 
+def add_half(a_half, b_half):
+    """Element-wise binary16 sum: one binary32 addition, one rounding to binary16 (the residual add in front of RMSNorm)."""
+    a_half = np.ascontiguousarray(a_half)
+    b_half = np.ascontiguousarray(b_half)
+    assert a_half.dtype == np.float16 and b_half.dtype == np.float16 and a_half.shape == b_half.shape
+    h = np.empty(a_half.shape, dtype=np.float16)
+    fn = _load().abq_oracle_add_half
+    fn.argtypes = [ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+    fn.restype = None
+    fn(a_half.size, _p(a_half.view(np.uint16)), _p(b_half.view(np.uint16)), _p(h.view(np.uint16)))
+    return h
+
+
 def rmsnorm_half(x_half, gamma_half, eps):
     """RMSNorm of binary16 rows to binary16 (exact sum of squares, roundings as stated in the C source)."""
     x_half = np.ascontiguousarray(x_half)

@@ -293,6 +293,19 @@ void abq_oracle_quant_act(int q, int M, int K, const uint16_t* x_half, uint8_t* 
     }
 }
 
+/* Residual add in front of the normalization (the LLaMA block adds a sub-layer's output to the hidden state and
+ * normalizes the sum; the sum is also the next residual, so it is materialised in binary16):
+ *     h[i] = half_rne( float(a[i]) + float(b[i]) )          one binary32 addition, then one rounding to binary16
+ * (two binary16 values can be 40 binades apart, so the binary32 sum is not always exact: the two roundings are
+ * part of the definition). */
+void abq_oracle_add_half(size_t n, const uint16_t* a_half, const uint16_t* b_half, uint16_t* h_half)
+{
+    for (size_t i = 0; i < n; ++i) {
+        volatile float s = half_to_float(a_half[i]) + half_to_float(b_half[i]);
+        h_half[i] = abq_oracle_half_bits((double)s);
+    }
+}
+
 /* RMSNorm to binary16, the producer that Sec. 3.4 / Fig. 3b fuse the activation quantizer into
  * (the paper quantizes the input of every linear layer of LLaMA, whose normalization is RMSNorm;
  * the paper prints no formula for it, so this is the standard definition):

@@ -69,6 +69,10 @@ MUTATIONS = {
         ("inner += ((int64_t)A[(size_t)m * K + k] - az[m]) *", "inner += ((int64_t)A[(size_t)m * K + k] + az[m]) *"),
     "grouped: activation scale of row 0 for every row":
         ("const double v = (double)a_scale[m] * total;", "const double v = (double)a_scale[0] * total;"),
+    "add: difference instead of sum":
+        ("volatile float s = half_to_float(a_half[i]) + half_to_float(b_half[i]);", "volatile float s = half_to_float(a_half[i]) - half_to_float(b_half[i]);"),
+    "add: second operand taken from the first":
+        ("volatile float s = half_to_float(a_half[i]) + half_to_float(b_half[i]);", "volatile float s = half_to_float(a_half[i]) + half_to_float(a_half[i]);"),
 }
 
 CHECKS = [
@@ -91,6 +95,7 @@ CHECKS = [
     lambda: pins.test_rmsnorm_invariances_are_bit_exact(),
     lambda: pins.test_silu_mul_matches_float64_definition(),
     lambda: pins.test_silu_mul_closed_forms_and_limits(),
+    lambda: pins.test_add_half_matches_numpy_two_step_rounding_and_identities(),
     lambda: pins.test_grouped_one_group_is_the_per_channel_result(),
     lambda: pins.test_grouped_equals_dequantise_then_multiply(4, 8, 3, 5, 300, 128),
     lambda: pins.test_grouped_single_live_group_uses_that_groups_scale_and_zero(),

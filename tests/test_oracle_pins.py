@@ -469,3 +469,21 @@ def test_grouped_single_live_group_uses_that_groups_scale_and_zero():
         inner = (c.A[:, lo:hi].astype(np.int64) - c.a_zero[:, None]) @ (W[:, lo:hi].astype(np.int64) - zg[:, live:live + 1]).T
         expect = c.a_scale[:, None].astype(np.float64) * sh.view(np.float16)[:, live].astype(np.float64)[None, :] * inner
         assert np.allclose(y, expect, rtol=1e-15, atol=0)
+
+
+# ---- residual add in front of the normalization ------------------------------------------------
+
+def test_add_half_matches_numpy_two_step_rounding_and_identities():
+    rng = np.random.Generator(np.random.PCG64(77))
+    a = (rng.standard_normal(20000) * rng.choice([1e-4, 1.0, 300.0, 3e4], 20000)).astype(np.float16)
+    b = (rng.standard_normal(20000) * rng.choice([1e-6, 1.0, 300.0, 3e4], 20000)).astype(np.float16)
+    got = oracle.add_half(a, b)
+    with np.errstate(over="ignore"):
+        lib = (a.astype(np.float32) + b.astype(np.float32)).astype(np.float16)        # numpy: IEEE add, RNE conversion
+    assert np.array_equal(got.view(np.uint16), lib.view(np.uint16))
+    assert np.array_equal(oracle.add_half(b, a).view(np.uint16), got.view(np.uint16))                 # commutative
+    assert np.array_equal(oracle.add_half(a, np.zeros_like(a)).view(np.uint16), (a + np.float16(0)).view(np.uint16))
+    fin = np.isfinite(a)
+    assert np.all(oracle.add_half(a[fin], -a[fin]) == 0)
+    ties = oracle.add_half(np.array([2048, 2048, 1, 60000], np.float16), np.array([1, 3, 2.0 ** -24, 60000], np.float16))
+    assert ties.tolist()[:3] == [2048.0, 2052.0, 1.0] and np.isinf(ties[3])         # ties to even; overflow to infinity
