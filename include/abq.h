@@ -149,6 +149,16 @@ int abq_rmsnorm_quant_act(int q, int M, int K, const uint16_t* x_fp16, const uin
                           uint8_t* a_codes_out, float* a_scale_out, int32_t* a_zero_out,
                           uint16_t* y_fp16_out, void* stream);
 
+/* The same with the residual add in front (the LLaMA block adds a sub-layer's output to the hidden state and
+ * normalizes the sum): h = half_rne(float(x) + float(residual)) — one binary32 addition, one rounding to binary16 —
+ * then abq_rmsnorm_quant_act on h, all in one kernel.
+ *   x_fp16, residual_fp16 [M,K] binary16;  sum_fp16_out [M,K] binary16, required: h, the next residual (it may be the
+ *   buffer residual_fp16 itself, not x_fp16);  the other arguments as above. */
+int abq_add_rmsnorm_quant_act(int q, int M, int K, const uint16_t* x_fp16, const uint16_t* residual_fp16,
+                              const uint16_t* gamma_fp16, float eps,
+                              uint8_t* a_codes_out, float* a_scale_out, int32_t* a_zero_out,
+                              uint16_t* sum_fp16_out, uint16_t* y_fp16_out, void* stream);
+
 /* SiLU(gate) * up with the quantizer fused in: the producer in front of down_proj in the LLaMA MLP (same passage).
  * Per element h = half_rne((g / (1 + exp(-g))) * up), exp taken as a fixed sequence of binary32 operations
  * (t = clamp(-g * log2 e, -126, 126), n = rint(t), 2^(t-n) by a degree-6 polynomial, scaled by 2^n: within

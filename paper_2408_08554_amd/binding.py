@@ -47,6 +47,7 @@ _SIGNATURES = {
     "abq_probe_mfma_i8": (_c.c_int, [_c.c_int, _c.c_int, _c.c_void_p, _c.c_void_p]),
     "abq_probe_mfma_i8_ops": (_c.c_double, [_c.c_int]),
     "abq_rmsnorm_quant_act": (_c.c_int, [_c.c_int] * 3 + [_c.c_void_p, _c.c_void_p, _c.c_float] + [_c.c_void_p] * 5),
+    "abq_add_rmsnorm_quant_act": (_c.c_int, [_c.c_int] * 3 + [_c.c_void_p] * 3 + [_c.c_float] + [_c.c_void_p] * 6),
     "abq_silu_mul_quant_act": (_c.c_int, [_c.c_int] * 3 + [_c.c_void_p] * 7),
     "abq_gemm_act_codes": (_c.c_int, [_c.c_int] * 5 + [_c.c_void_p] * 4 + [_c.c_int, _c.c_void_p, _c.c_void_p,
                                                                           _c.c_void_p, _c.c_size_t, _c.c_void_p]),
@@ -315,6 +316,20 @@ def abq_rmsnorm_quant_act(q, x_fp16, gamma_fp16, eps, want_y=False):
     _check(load().abq_rmsnorm_quant_act(q, M, K, _ptr(x_fp16), _ptr(gamma_fp16), float(eps), _ptr(codes), _ptr(scale),
                                         _ptr(zero), _ptr(y), _stream()), "abq_rmsnorm_quant_act")
     return codes, scale, zero, y
+
+
+def abq_add_rmsnorm_quant_act(q, x_fp16, residual_fp16, gamma_fp16, eps, want_y=False, sum_out=None):
+    """-> (codes, a_scale, a_zero, h = x + residual as float16 [M,K], y float16 [M,K] or None)."""
+    M, K = x_fp16.shape
+    dev = x_fp16.device
+    codes = torch.empty((M, K), dtype=torch.uint8, device=dev)
+    scale = torch.empty(M, dtype=torch.float32, device=dev)
+    zero = torch.empty(M, dtype=torch.int32, device=dev)
+    h = torch.empty((M, K), dtype=torch.float16, device=dev) if sum_out is None else sum_out
+    y = torch.empty((M, K), dtype=torch.float16, device=dev) if want_y else None
+    _check(load().abq_add_rmsnorm_quant_act(q, M, K, _ptr(x_fp16), _ptr(residual_fp16), _ptr(gamma_fp16), float(eps), _ptr(codes),
+                                            _ptr(scale), _ptr(zero), _ptr(h), _ptr(y), _stream()), "abq_add_rmsnorm_quant_act")
+    return codes, scale, zero, h, y
 
 
 def abq_silu_mul_quant_act(q, gate_fp16, up_fp16, want_h=False):

@@ -245,6 +245,20 @@ int abq_rmsnorm_quant_act(int q, int M, int K, const uint16_t* x_fp16, const uin
                                            (hipStream_t)stream));
 }
 
+int abq_add_rmsnorm_quant_act(int q, int M, int K, const uint16_t* x_fp16, const uint16_t* residual_fp16, const uint16_t* gamma_fp16,
+                              float eps, uint8_t* a_codes_out, float* a_scale_out, int32_t* a_zero_out, uint16_t* sum_fp16_out,
+                              uint16_t* y_fp16_out, void* stream)
+{
+    if (!x_fp16 || !residual_fp16 || !gamma_fp16 || !a_codes_out || !a_scale_out || !a_zero_out || !sum_fp16_out) return ABQ_ERR_NULL;
+    if (int e = check_bits_shape(q, M, K)) return e;
+    if (!(eps >= 0.0f)) return ABQ_ERR_SHAPE;
+    if (misaligned(x_fp16) || misaligned(residual_fp16) || misaligned(gamma_fp16) || misaligned(a_codes_out) ||
+        misaligned(a_scale_out) || misaligned(a_zero_out) || misaligned(sum_fp16_out) || misaligned(y_fp16_out))
+        return ABQ_ERR_ALIGN;
+    return hip_status(launch_add_rmsnorm_quant(q, M, K, x_fp16, residual_fp16, gamma_fp16, eps, a_codes_out, a_scale_out, a_zero_out,
+                                               sum_fp16_out, y_fp16_out, (hipStream_t)stream));
+}
+
 int abq_silu_mul_quant_act(int q, int M, int K, const uint16_t* gate_fp16, const uint16_t* up_fp16, uint8_t* a_codes_out,
                            float* a_scale_out, int32_t* a_zero_out, uint16_t* h_fp16_out, void* stream)
 {

@@ -79,6 +79,10 @@ hipError_t launch_unpack_act(const ActLayout& L, const uint8_t* blob, int which,
 hipError_t launch_rmsnorm_quant(int q, int M, int K, const uint16_t* x, const uint16_t* gamma, float eps, uint8_t* codes,
                                 float* scale, int32_t* zero, uint16_t* y_out, hipStream_t s);
 
+hipError_t launch_add_rmsnorm_quant(int q, int M, int K, const uint16_t* x, const uint16_t* residual, const uint16_t* gamma,
+                                    float eps, uint8_t* codes, float* scale, int32_t* zero, uint16_t* sum_out, uint16_t* y_out,
+                                    hipStream_t s);
+
 hipError_t launch_silu_mul_quant(int q, int M, int K, const uint16_t* gate, const uint16_t* up, uint8_t* codes, float* scale,
                                  int32_t* zero, uint16_t* h_out, hipStream_t s);
 

@@ -98,6 +98,21 @@ __device__ __forceinline__ uint16_t silu_mul_half(uint16_t gb, uint16_t ub)
     return (uint16_t)hb;
 }
 
+// h = half_rne(float(a) + float(b)): the residual add in front of the normalization (one binary32 addition, then the
+// conversion as its own instruction, for the reason given above).
+__device__ __forceinline__ uint16_t add_half(uint16_t ab, uint16_t bb)
+{
+    const float s = __fadd_rn(half_to_f32(ab), half_to_f32(bb));
+    uint32_t hb;
+    asm("v_cvt_f16_f32 %0, %1" : "=v"(hb) : "v"(s));
+    return (uint16_t)hb;
+}
+__device__ __forceinline__ uint32_t add_half2(uint32_t a, uint32_t b)
+{
+    return (uint32_t)add_half((uint16_t)(a & 0xFFFFu), (uint16_t)(b & 0xFFFFu)) |
+           ((uint32_t)add_half((uint16_t)(a >> 16), (uint16_t)(b >> 16)) << 16);
+}
+
 // KIND 0: RMSNorm, operand b = gamma [K];  KIND 1: SiLU(a) * b, operand b = up [M,K].
 template <int KIND>
 __device__ __forceinline__ uint16_t produce_half(uint16_t ab, uint16_t bb, float r)
@@ -112,7 +127,8 @@ template <int KIND, int VPT, int BLOCK>
 __global__ __launch_bounds__(BLOCK) void producer_quant_rows_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ gamma,
                                                                  float eps, int q, int K, uint8_t* __restrict__ codes,
                                                                  float* __restrict__ scale, int32_t* __restrict__ zero,
-                                                                 uint16_t* __restrict__ y_out)
+                                                                 uint16_t* __restrict__ y_out,
+                                                                 const uint16_t* residual, uint16_t* sum_out)   /* may be one buffer */
 {
     constexpr int W = BLOCK / 64;
     __shared__ uint64_t s_lo64[W], s_hi64[W];
@@ -129,6 +145,20 @@ __global__ __launch_bounds__(BLOCK) void producer_quant_rows_kernel(const uint16
         const bool in = v < nvec;
         xv[i][0] = in ? a.x : 0u; xv[i][1] = in ? a.y : 0u; xv[i][2] = in ? a.z : 0u; xv[i][3] = in ? a.w : 0u;
         gv[i][0] = b.x; gv[i][1] = b.y; gv[i][2] = b.z; gv[i][3] = b.w;
+    }
+    if constexpr (KIND == 0) {
+        if (residual) {   // x + residual first; the sum is the row that is normalized and the next residual
+            const uint4* rrow = reinterpret_cast<const uint4*>(residual + (size_t)m * K);
+#pragma unroll
+            for (int i = 0; i < VPT; ++i) {
+                const int v = tid + i * BLOCK;
+                const uint4 c = rrow[v < nvec ? v : nvec - 1];
+                xv[i][0] = add_half2(xv[i][0], c.x); xv[i][1] = add_half2(xv[i][1], c.y);
+                xv[i][2] = add_half2(xv[i][2], c.z); xv[i][3] = add_half2(xv[i][3], c.w);
+                if (v < nvec) reinterpret_cast<uint4*>(sum_out + (size_t)m * K)[v] = uint4{xv[i][0], xv[i][1], xv[i][2], xv[i][3]};
+                else { xv[i][0] = 0u; xv[i][1] = 0u; xv[i][2] = 0u; xv[i][3] = 0u; }
+            }
+        }
     }
     float r = 0.0f;
     if constexpr (KIND == 0) {
@@ -211,7 +241,8 @@ template <int KIND, int BLOCK>
 __global__ __launch_bounds__(BLOCK) void producer_quant_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ gamma,
                                                               float eps, int q, int K, uint8_t* __restrict__ codes,
                                                               float* __restrict__ scale, int32_t* __restrict__ zero,
-                                                              uint16_t* __restrict__ y_out)
+                                                              uint16_t* __restrict__ y_out,
+                                                              const uint16_t* residual, uint16_t* sum_out)   /* may be one buffer */
 {
     constexpr int W = BLOCK / 64;
     __shared__ uint64_t s_lo64[W], s_hi64[W];
@@ -219,6 +250,12 @@ __global__ __launch_bounds__(BLOCK) void producer_quant_kernel(const uint16_t* _
     const int m = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint16_t* row = x + (size_t)m * K;
     const int qmax = (1 << q) - 1;
+    if constexpr (KIND == 0) {
+        if (residual) {   // x + residual first; every later pass reads the sum (each thread re-reads only what it wrote)
+            for (int k = tid; k < K; k += BLOCK) sum_out[(size_t)m * K + k] = add_half(row[k], residual[(size_t)m * K + k]);
+            row = sum_out + (size_t)m * K;
+        }
+    }
 
     const uint16_t* brow = KIND == 0 ? gamma : gamma + (size_t)m * K;
     float r = 0.0f;
@@ -284,15 +321,16 @@ __global__ __launch_bounds__(BLOCK) void producer_quant_kernel(const uint16_t* _
 // KIND 0: b = gamma [K], eps used;  KIND 1: b = up [M,K], eps ignored.
 template <int KIND>
 static hipError_t launch_producer_quant(int q, int M, int K, const uint16_t* a, const uint16_t* b, float eps, uint8_t* codes,
-                                        float* scale, int32_t* zero, uint16_t* y_out, hipStream_t s)
+                                        float* scale, int32_t* zero, uint16_t* y_out, hipStream_t s,
+                                        const uint16_t* residual = nullptr, uint16_t* sum_out = nullptr)
 {
     // rows of whole, 16-byte aligned vectors that fit a workgroup's registers take the fast path
     const bool vec_ok = K % 8 == 0 && K <= 16384 && ((uintptr_t)y_out & 15u) == 0;
-    if (vec_ok && K <= 2048) producer_quant_rows_kernel<KIND, 1, 256><<<M, 256, 0, s>>>(a, b, eps, q, K, codes, scale, zero, y_out);
-    else if (vec_ok && K <= 4096) producer_quant_rows_kernel<KIND, 1, 512><<<M, 512, 0, s>>>(a, b, eps, q, K, codes, scale, zero, y_out);
-    else if (vec_ok && K <= 8192) producer_quant_rows_kernel<KIND, 2, 512><<<M, 512, 0, s>>>(a, b, eps, q, K, codes, scale, zero, y_out);
-    else if (vec_ok) producer_quant_rows_kernel<KIND, 4, 512><<<M, 512, 0, s>>>(a, b, eps, q, K, codes, scale, zero, y_out);
-    else producer_quant_kernel<KIND, 256><<<M, 256, 0, s>>>(a, b, eps, q, K, codes, scale, zero, y_out);
+    if (vec_ok && K <= 2048) producer_quant_rows_kernel<KIND, 1, 256><<<M, 256, 0, s>>>(a, b, eps, q, K, codes, scale, zero, y_out, residual, sum_out);
+    else if (vec_ok && K <= 4096) producer_quant_rows_kernel<KIND, 1, 512><<<M, 512, 0, s>>>(a, b, eps, q, K, codes, scale, zero, y_out, residual, sum_out);
+    else if (vec_ok && K <= 8192) producer_quant_rows_kernel<KIND, 2, 512><<<M, 512, 0, s>>>(a, b, eps, q, K, codes, scale, zero, y_out, residual, sum_out);
+    else if (vec_ok) producer_quant_rows_kernel<KIND, 4, 512><<<M, 512, 0, s>>>(a, b, eps, q, K, codes, scale, zero, y_out, residual, sum_out);
+    else producer_quant_kernel<KIND, 256><<<M, 256, 0, s>>>(a, b, eps, q, K, codes, scale, zero, y_out, residual, sum_out);
     return hipGetLastError();
 }
 
@@ -300,6 +338,12 @@ hipError_t launch_rmsnorm_quant(int q, int M, int K, const uint16_t* x, const ui
                                 float* scale, int32_t* zero, uint16_t* y_out, hipStream_t s)
 {
     return launch_producer_quant<0>(q, M, K, x, gamma, eps, codes, scale, zero, y_out, s);
+}
+
+hipError_t launch_add_rmsnorm_quant(int q, int M, int K, const uint16_t* x, const uint16_t* residual, const uint16_t* gamma, float eps,
+                                    uint8_t* codes, float* scale, int32_t* zero, uint16_t* sum_out, uint16_t* y_out, hipStream_t s)
+{
+    return launch_producer_quant<0>(q, M, K, x, gamma, eps, codes, scale, zero, y_out, s, residual, sum_out);
 }
 
 hipError_t launch_silu_mul_quant(int q, int M, int K, const uint16_t* gate, const uint16_t* up, uint8_t* codes, float* scale,

@@ -268,6 +268,23 @@ def test_rmsnorm_quant_act_rejects():
     assert call(c=A16 + 1) == B.ABQ_ERR_ALIGN
 
 
+def test_add_rmsnorm_quant_act_rejects():
+    f = B.load().abq_add_rmsnorm_quant_act
+    ok = dict(q=8, M=2, K=64, x=A16, r=A16, g=A16, eps=1e-5, c=A16, s=A16, z=A16, h=A16, y=None)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return f(a["q"], a["M"], a["K"], a["x"], a["r"], a["g"], a["eps"], a["c"], a["s"], a["z"], a["h"], a["y"], None)
+
+    assert call(r=None) == B.ABQ_ERR_NULL
+    assert call(h=None) == B.ABQ_ERR_NULL          # the sum is the next residual: always written
+    assert call(q=0) == B.ABQ_ERR_BITS
+    assert call(K=0) == B.ABQ_ERR_SHAPE
+    assert call(eps=-1.0) == B.ABQ_ERR_SHAPE
+    assert call(r=A16 + 2) == B.ABQ_ERR_ALIGN
+    assert call(y=A16 + 8) == B.ABQ_ERR_ALIGN
+
+
 def test_silu_mul_quant_act_rejects():
     lib = B.load()
 

@@ -397,6 +397,30 @@ def test_rmsnorm_quant_act_matches_oracle(abq, q, M, K, eps, kind):
     assert none is None and np.array_equal(codes2.cpu().numpy(), codes_ref)
 
 
+@pytest.mark.parametrize("q", [4, 8])
+@pytest.mark.parametrize("M,K", [(1, 4096), (5, 1000), (3, 37), (16, 11008), (2, 16392), (4, 8)])
+def test_add_rmsnorm_quant_act_matches_oracle(abq, q, M, K):
+    say(f"add+rmsnorm q={q} M={M} K={K}")
+    x, gamma = _norm_inputs(M, K, 3100 + K)
+    res, _ = _norm_inputs(M, K, 3200 + K)
+    res[0, : min(K, 8)] = -x[0, : min(K, 8)]                    # exact cancellation inside a row
+    h_ref = oracle.add_half(x, res)
+    y_ref = oracle.rmsnorm_half(h_ref, gamma, 1e-5)
+    c_ref, s_ref, z_ref = oracle.quant_act(y_ref, q)
+    codes, sc, zp, h, y = abq.abq_add_rmsnorm_quant_act(q, to_dev(torch, x), to_dev(torch, res), to_dev(torch, gamma), 1e-5, want_y=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(h.cpu().numpy().view(np.uint16), h_ref.view(np.uint16))
+    assert np.array_equal(y.cpu().numpy().view(np.uint16), y_ref.view(np.uint16))
+    assert np.array_equal(codes.cpu().numpy(), c_ref) and np.array_equal(zp.cpu().numpy(), z_ref)
+    assert np.array_equal(sc.cpu().numpy().view(np.uint32), s_ref.view(np.uint32))
+    # the sum written over the residual buffer itself
+    r_dev = to_dev(torch, res)
+    codes2, _, _, h2, _ = abq.abq_add_rmsnorm_quant_act(q, to_dev(torch, x), r_dev, to_dev(torch, gamma), 1e-5, sum_out=r_dev)
+    torch.cuda.synchronize()
+    assert h2.data_ptr() == r_dev.data_ptr() and np.array_equal(r_dev.cpu().numpy().view(np.uint16), h_ref.view(np.uint16))
+    assert np.array_equal(codes2.cpu().numpy(), c_ref)
+
+
 def test_rmsnorm_quant_then_fused_gemm_end_to_end(abq):
     """fp16 hidden state -> RMSNorm + quantizer (one kernel) -> fused decode matmul (one kernel), against the
     oracle chain rmsnorm -> quantizer -> centered product sum -> dequant."""
