@@ -343,14 +343,15 @@ static hipError_t launch_shape(const TiledParams& prm, dim3 grid, int cus, int p
     // registers run out) and run two workgroups per CU instead of three.  Measured: with at most one workgroup
     // per CU (M = 64..128 on a 4096-wide layer) they are 20 % faster, with more workgroups (M = 128 on an
     // 11008-wide layer and up) the traffic through L2, not the latency of a step, is the bound and they lose.
-    // With long K (13824) the plan search found them 6-7 % ahead up to 1.25 workgroups per CU as well.
+    // With long K (13824) the plan search found them 6-7 % ahead up to 1.25 workgroups per CU as well, and at
+    // p = 8 up to 2.5 per CU (M = 512, 5120 channels: 75 vs 84 us); narrower weights lose there (W2A8: 53 vs 44 us).
     // Overrides: the plan table (plan_wd), else ABQ_TILED_WD=<2|4> (read once).
     constexpr bool has_deep = MT == 4 && (NTW == 1 || (NTW == 2 && P <= 6));
     static int env_forced = -1;
     if (env_forced < 0) { const char* e = getenv("ABQ_TILED_WD"); env_forced = e ? atoi(e) : 0; }
     const int forced = plan_wd > 0 ? plan_wd : env_forced;
     if constexpr (has_deep) {
-        if (forced == 4 || (forced != 2 && ((long)grid.x <= (long)cus || ((long)grid.x <= 2L * cus && prm.K >= 8192)))) {
+        if (forced == 4 || (forced != 2 && ((long)grid.x <= (long)cus || ((long)grid.x <= (P == 8 ? 3L : 2L) * cus && prm.K >= 8192)))) {
             tiled_kernel<P, NTW, MT, 4><<<grid, 256, 0, s>>>(prm);
             return hipGetLastError();
         }
