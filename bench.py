@@ -329,6 +329,9 @@ def main():
     ap.add_argument("--no-check", action="store_true")
     ap.add_argument("--g128", action="store_true",
                     help="per-group weight scales and zero-points (groups of 128 along K, Appendix C) on the workload's shape")
+    ap.add_argument("--plans", nargs="?", const="shipped", default=None,
+                    help="install searched launch plans before timing: a JSON file written by tune.py --save, or no value "
+                         "for the table shipped with the package (default: the library's own rules only)")
     ap.add_argument("--no-other-paths", dest="other_paths", action="store_false",
                     help="skip the two short child runs (g128 decode, prefill) that the default run reports beside the main workload")
     ap.add_argument("--grouped-steps", type=int, default=200,
@@ -343,6 +346,10 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     abq.load()
+    plans_loaded = 0
+    if args.plans:
+        from paper_2408_08554_amd import tune
+        plans_loaded = tune.load_plans() if args.plans == "shipped" else tune.load_plans(args.plans)
 
     if args.workload.startswith("block:"):
         # block:p,q,M — the grouped decoder-block launch as the timed workload, printed as its own JSON line
@@ -515,7 +522,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": sec_per_step * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
         "config": {"workload": c.name, "p": p, "q": q, "M": M, "N": N, "K": K, "mode": args.mode,
-                   "family": args.family, "rotating_weight_buffers": R, "rotating_bytes": R * stride,
+                   "family": args.family, "launch_plans_loaded": plans_loaded, "rotating_weight_buffers": R, "rotating_bytes": R * stride,
                    "step": "abq_gemm_act_codes" + ("" if fused_ws_bytes == 0 else " (two kernels)") if fused
                            else "abq_pack_act_codes + abq_gemm"},
         "weight_gbs": metrics.weight_gbs(p, N, K, sec_per_step),

@@ -321,3 +321,17 @@ def test_tuner_candidate_plans_are_valid_plan_table_entries():
             B.abq_plan_set(*shape, **plan) if plan else B.abq_plan_set(*shape)
             assert {k: v for k, v in B.abq_plan_get(*shape).items() if v} == plan
     B.abq_plan_clear()
+
+
+def test_shipped_plan_table_is_well_formed():
+    import json
+    from paper_2408_08554_amd import tune
+    table = json.load(open(tune.DEFAULT_PLANS))
+    B.load()
+    B.abq_plan_clear()
+    assert tune.load_plans() == len(table)
+    for key, plan in table.items():
+        shape = tuple(int(v) for v in key.split(","))
+        assert len(shape) == 5 and set(plan) <= set(tune.KNOBS)
+        assert {k: v for k, v in B.abq_plan_get(*shape).items() if v} == plan
+    B.abq_plan_clear()

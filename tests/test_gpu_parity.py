@@ -604,6 +604,27 @@ def test_every_candidate_plan_gives_the_same_result(abq, p, q, M, N, K):
         abq.abq_plan_clear()
 
 
+def test_shipped_plan_table_loads_and_keeps_results(abq):
+    from paper_2408_08554_amd import tune
+    import json
+    table = json.load(open(tune.DEFAULT_PLANS))
+    try:
+        assert tune.load_plans() == len(table) > 0
+        checked = 0
+        for key in sorted(table):
+            p, q, M, N, K = (int(v) for v in key.split(","))
+            assert {k: v for k, v in abq.abq_plan_get(p, q, M, N, K).items() if v} == table[key]
+            if M * N * K > 16 * 11008 * 4096:       # the oracle takes the small ones in full
+                continue
+            c = synth.make_case(p, q, M, N, K, seed=9650 + checked)
+            y, acc = gpu_gemm_fused(torch, abq, c, FIELDS)
+            check_against_oracle(c, y, acc)
+            checked += 1
+        assert checked >= 3
+    finally:
+        abq.abq_plan_clear()
+
+
 def test_tuner_search_reports_the_rule_and_restores_the_table(abq):
     from paper_2408_08554_amd import tune
     abq.abq_plan_set(4, 8, 1, 512, 2048, skinny_waves=2)
