@@ -149,8 +149,9 @@ int abq_rmsnorm_quant_act(int q, int M, int K, const uint16_t* x_fp16, const uin
                           uint8_t* a_codes_out, float* a_scale_out, int32_t* a_zero_out,
                           uint16_t* y_fp16_out, void* stream);
 
-/* The same with the residual add in front (the LLaMA block adds a sub-layer's output to the hidden state and
- * normalizes the sum): h = half_rne(float(x) + float(residual)) — one binary32 addition, one rounding to binary16 —
+/* The same with the residual add in front (Sec. 3.4 / Fig. 3b again: the quantizer rides on the operator that
+ * produces the linear layer's input; in the LLaMA block that operator adds a sub-layer's output to the hidden
+ * state and normalizes the sum): h = half_rne(float(x) + float(residual)) — one binary32 addition, one rounding to binary16 —
  * then abq_rmsnorm_quant_act on h, all in one kernel.
  *   x_fp16, residual_fp16 [M,K] binary16;  sum_fp16_out [M,K] binary16, required: h, the next residual (it may be the
  *   buffer residual_fp16 itself, not x_fp16);  the other arguments as above. */
