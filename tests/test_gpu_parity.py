@@ -110,6 +110,22 @@ def test_prefill_shapes(abq, M, N, K, p, q):
         check_sampled(c, y, acc)
 
 
+@pytest.mark.parametrize("p,q,M,N,K", [(4, 4, 2050, 6000, 200),     # 64x256 workgroup tiles by the rule, ragged on every side
+                                       (2, 8, 1030, 5500, 300),     # 64x128 tiles by the rule
+                                       (3, 8, 1024, 13824, 128),    # K of half a super-chunk
+                                       (8, 8, 520, 5100, 8200)])    # p = 8, long K: deep rings past one workgroup per CU
+def test_prefill_large_ragged_rule_paths(abq, p, q, M, N, K):
+    say("prefill rule path", p, q, M, N, K)
+    c = synth.make_case(p, q, M, N, K, seed=synth.case_seed(7, p, q) + M + N + K, name=f"W{p}A{q} {M}x{N}x{K}")
+    y, acc = gpu_gemm(torch, abq, c, FIELDS, FIELDS)
+    check_sampled(c, y, acc, count=8192)
+    # the last row and column blocks in full (partial tiles at both edges)
+    ms = np.arange(M - 70, M)
+    ns = np.arange(N - 300, N)
+    sub = synth.Case(p, q, len(ms), len(ns), K, c.W[ns], c.A[ms], c.w_scale[ns], c.w_zero[ns], c.a_scale[ms], c.a_zero[ms], c.seed, c.name)
+    check_against_oracle(sub, y[np.ix_(ms, ns)], acc[np.ix_(ms, ns)])
+
+
 def test_prefill_bitserial(abq):
     c = synth.make_case(3, 5, 70, 50, 600, seed=123)
     y, acc = gpu_gemm(torch, abq, c, PLANES, PLANES)
