@@ -28,6 +28,11 @@
  * the quantizer is fused into): the paper prints no formula; pinned against a float64 numpy
  * evaluation of the standard definition, closed forms and invariances.  abq_oracle_silu_mul_half
  * (the second producer): pinned against a float64 evaluation with the library exp and closed forms.
+ * abq_oracle_add_half (the residual add in front of the normalization): pinned against numpy's float32
+ * addition and float16 conversion, identities, ties and overflow.  abq_oracle_dequant_grouped (per-group
+ * weight scales and zero-points, Appendix C): pinned by its reductions to the per-channel result (one group;
+ * equal parameters in every group), a long-double dequantise-then-multiply with every weight under its own
+ * group's parameters, and single-live-group closed forms including the short last group.
  */
 #include <stdint.h>
 #include <stddef.h>
