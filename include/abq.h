@@ -216,6 +216,22 @@ int abq_gemm_act_codes(int p, int q, int M, int N, int K,
                        uint16_t* y_fp16, int32_t* acc_i32,
                        void* workspace, size_t workspace_bytes, void* stream);
 
+/* abq_gemm_act_codes for callers that cannot allocate device memory or bring a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the same call with no workspace argument.
+ * Where abq_gemm_act_codes needs a workspace (the packed activations of its two-kernel path) this variant keeps
+ * it in a buffer of ABQ_STATIC_SCRATCH_BYTES bytes that is part of the library's device image (every GPU the
+ * library runs on holds it until the process ends).  It allocates nothing and frees nothing.
+ * Same arguments, results (bit for bit) and errors as abq_gemm_act_codes; in addition ABQ_ERR_SIZE when
+ * abq_gemm_act_codes_workspace_bytes(...) for the problem exceeds ABQ_STATIC_SCRATCH_BYTES (checked before
+ * the first HIP call).  All calls on one GPU share that GPU's buffer: calls that may overlap on one GPU
+ * (different streams, different host threads) race on it and must be serialized by the caller; calls on one
+ * stream are safe.  The buffer needs no clearing between calls (each call writes what it reads). */
+#define ABQ_STATIC_SCRATCH_BYTES (32u << 20)
+int abq_gemm_act_codes_static(int p, int q, int M, int N, int K,
+                              const uint8_t* a_codes, const float* a_scale, const int32_t* a_zero,
+                              const void* packed_w, int w_layout,
+                              uint16_t* y_fp16, int32_t* acc_i32, void* stream);
+
 /* Launch-plan table (Appendix D, "auto kernel search": the engine picks, per problem size, the fastest of a
  * set of kernel configurations found by timing them).  The library chooses every launch plan from closed-form
  * rules; this table lets a tuner (paper_2408_08554_amd/tune.py times the candidates on the device) replace the

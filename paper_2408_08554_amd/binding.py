@@ -19,6 +19,7 @@ ABQ_LAYOUT_AUTO, ABQ_LAYOUT_PLANES, ABQ_LAYOUT_FIELDS, ABQ_LAYOUT_BOTH = 0, 1, 2
 ABQ_LAYOUT_FIELDS_G128 = 4
 ABQ_USE_PLANES, ABQ_USE_FIELDS = 0x10, 0x20
 ABQ_MAX_K = 131072
+ABQ_STATIC_SCRATCH_BYTES = 32 << 20
 
 # every symbol include/abq.h declares: (restype, argtypes)
 _c = ctypes
@@ -51,6 +52,7 @@ _SIGNATURES = {
     "abq_silu_mul_quant_act": (_c.c_int, [_c.c_int] * 3 + [_c.c_void_p] * 7),
     "abq_gemm_act_codes": (_c.c_int, [_c.c_int] * 5 + [_c.c_void_p] * 4 + [_c.c_int, _c.c_void_p, _c.c_void_p,
                                                                           _c.c_void_p, _c.c_size_t, _c.c_void_p]),
+    "abq_gemm_act_codes_static": (_c.c_int, [_c.c_int] * 5 + [_c.c_void_p] * 4 + [_c.c_int, _c.c_void_p, _c.c_void_p, _c.c_void_p]),
 }
 
 _lib = None
@@ -228,6 +230,13 @@ def abq_gemm_act_codes(p, q, M, N, K, a_codes, a_scale, a_zero, packed_w, w_layo
     _check(lib.abq_gemm_act_codes(p, q, M, N, K, _ptr(a_codes), _ptr(a_scale), _ptr(a_zero), _ptr(packed_w), w_layout,
                                   _ptr(y), _ptr(acc), _ptr(workspace), 0 if workspace is None else workspace.numel(),
                                   _stream()), "abq_gemm_act_codes")
+    return y, acc
+
+
+def abq_gemm_act_codes_static(p, q, M, N, K, a_codes, a_scale, a_zero, packed_w, w_layout, y, acc=None):
+    """abq_gemm_act_codes without a workspace and without any allocation: the caller passes every buffer."""
+    _check(load().abq_gemm_act_codes_static(p, q, M, N, K, _ptr(a_codes), _ptr(a_scale), _ptr(a_zero), _ptr(packed_w), w_layout,
+                                            _ptr(y), _ptr(acc), _stream()), "abq_gemm_act_codes_static")
     return y, acc
 
 

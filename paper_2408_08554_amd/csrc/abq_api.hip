@@ -12,6 +12,11 @@
 #include <mutex>
 #include <vector>
 
+// Scratch of abq_gemm_act_codes_static: the packed activations of its two-kernel path live here instead of in
+// a caller's workspace.  In host code this name is a stand-in, not a device address: host code uses the
+// per-device pointer that static_scratch_ptr() obtains with hipGetSymbolAddress.
+static __device__ __align__(256) unsigned char scratch[ABQ_STATIC_SCRATCH_BYTES];
+
 namespace abq {
 
 static thread_local int g_last_hip_error = 0;
@@ -112,6 +117,29 @@ bool lookup_plan(int p, int q, int M, int N, int K, PlanOverride* out)
 }
 
 static bool misaligned(const void* p) { return ((uintptr_t)p & 15u) != 0; }
+
+// Device address of `scratch` on the current device (each GPU holds its own copy of the array at its own
+// address): looked up once per device, with that device current, and kept.
+static hipError_t static_scratch_ptr(void** out)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex mutex;
+    static void* ptrs[kMaxDevices] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mutex);
+    if (!ptrs[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        ptrs[dev] = p;
+    }
+    *out = ptrs[dev];
+    return hipSuccess;
+}
 
 static int check_bits_shape(int bits, int R, int K)
 {
@@ -434,6 +462,27 @@ int abq_gemm_act_codes(int p, int q, int M, int N, int K, const uint8_t* a_codes
     if (int e = abq_pack_act_codes(q, M, K, a_codes, a_scale, a_zero, act_layout, workspace, act_bytes, stream)) return e;
     return abq_gemm(p, q, M, N, K, workspace, act_layout, packed_w, w_layout, y_fp16, acc_i32,
                     (uint8_t*)workspace + act_bytes, workspace_bytes - act_bytes, stream);
+}
+
+int abq_gemm_act_codes_static(int p, int q, int M, int N, int K, const uint8_t* a_codes, const float* a_scale,
+                              const int32_t* a_zero, const void* packed_w, int w_layout, uint16_t* y_fp16, int32_t* acc_i32,
+                              void* stream)
+{
+    if (!a_codes || !a_scale || !a_zero || !packed_w || !y_fp16) return ABQ_ERR_NULL;
+    if (int e = check_gemm_shape(p, q, M, N, K)) return e;
+    const int force = w_layout & (ABQ_USE_PLANES | ABQ_USE_FIELDS);
+    WeightLayout W;
+    if (force == (ABQ_USE_PLANES | ABQ_USE_FIELDS) || !make_weight_layout(p, N, K, w_layout & ~(ABQ_USE_PLANES | ABQ_USE_FIELDS), &W))
+        return ABQ_ERR_LAYOUT;
+    const size_t need = abq_gemm_act_codes_workspace_bytes(p, q, M, N, K, w_layout);
+    if (need > (size_t)ABQ_STATIC_SCRATCH_BYTES) return ABQ_ERR_SIZE;
+    void* ws = nullptr;
+    if (need > 0) {
+        if (int e = hip_status(static_scratch_ptr(&ws))) return e;
+    }
+    // every byte of the scratch that the matmul reads is written by the pack step of the same call first, so
+    // nothing needs clearing between calls
+    return abq_gemm_act_codes(p, q, M, N, K, a_codes, a_scale, a_zero, packed_w, w_layout, y_fp16, acc_i32, ws, need, stream);
 }
 
 // Validation and layouts of a group; fills the per-problem arrays (sized by the caller) and says whether one
