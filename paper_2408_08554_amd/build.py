@@ -1,7 +1,8 @@
 """Compile the HIP sources under csrc/ for gfx950 into paper_2408_08554_amd/libabq.so.
 
 Run here on the CPU container (hipcc cross-compiles); the built library travels with the
-tree.  `python -m paper_2408_08554_amd.build` rebuilds everything.
+tree.  `python -m paper_2408_08554_amd.build` rebuilds everything
+(`--incremental`: only what changed).
 """
 import concurrent.futures
 import glob
@@ -22,17 +23,22 @@ FLAGS = [
 ]
 
 
-def _compile(src: str) -> str:
+def _compile(src: str, newest_header: float = 0.0) -> str:
     obj = os.path.join(OBJ, os.path.basename(src) + ".o")
+    if newest_header and os.path.exists(obj) and os.path.getmtime(obj) >= max(newest_header, os.path.getmtime(src)):
+        return obj   # --incremental: neither the source nor any header is newer than the object
     subprocess.run([HIPCC, *FLAGS, "-c", src, "-o", obj], check=True, stderr=subprocess.PIPE, text=True)
     return obj
 
 
-def build(verbose: bool = False) -> str:
+def build(verbose: bool = False, incremental: bool = False) -> str:
+    """Compiles every source (always, unless `incremental`: then only what is older than its source or a header)."""
     os.makedirs(OBJ, exist_ok=True)
     srcs = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
+    headers = glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(HERE, "..", "include", "*.h")) + [__file__]
+    newest = max(os.path.getmtime(h) for h in headers) if incremental else 0.0
     with concurrent.futures.ThreadPoolExecutor(max_workers=min(8, len(srcs))) as ex:
-        futs = {ex.submit(_compile, s): s for s in srcs}
+        futs = {ex.submit(_compile, s, newest): s for s in srcs}
         objs = []
         for f, s in futs.items():
             try:
@@ -46,4 +52,5 @@ def build(verbose: bool = False) -> str:
 
 
 if __name__ == "__main__":
-    print(build(verbose=True))
+    import sys
+    print(build(verbose=True, incremental="--incremental" in sys.argv))
