@@ -6,12 +6,14 @@ BitPacking, then the matmul with fused bit reduction and dequant, against packed
 were prepared offline.  For the decode shapes the two run as ONE kernel (abq_gemm_act_codes:
 the codes are offset and their row sums taken while the matmul kernel stages them); for every
 other shape, or with --step two, as abq_pack_act_codes followed by abq_gemm.  Successive steps use
-different weight buffers (round-robin over >= 1 GiB) so that the 256 MB last-level cache
-cannot serve the weight stream — as in real decoding, where every layer has its own weights.
+different weight buffers (round-robin over >= 1 GiB whatever --steps is, and the cache is swept
+before every timed region) so that the 256 MB last-level cache cannot serve the weight stream —
+as in real decoding, where every layer has its own weights.
 
 Prints one JSON line.  `value` is effective TOPS = 2*M*N*K / time (the paper's metric,
 independent of p and q).  `roofline` prices the matmul kernel alone against the HBM peak on
-algorithmic bytes, from HIP-event timing of a gemm-only region on the launch stream.
+algorithmic bytes, from HIP-event timing of a gemm-only region of its own (>= 200 launches, at least
+one round of the rotation set) on the launch stream.
 `cpu_baseline` is the CPU oracle timed on this machine's host cores.
 """
 import argparse
@@ -26,19 +28,49 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0           # MI355X published HBM3E bandwidth
 INT8_MFMA_PEAK_TOPS = 5000.0    # MI355X published dense int8
 
-# HBM bytes per abq_gemm launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch), each
-# scaled by what the same counter reads for a plain copy of known size in the same run (FETCH_SIZE
-# reads 0.5015x on this chip, WRITE_SIZE 1.000x); figures and commands are in profiles/.
-MEASURED_TRAFFIC_BYTES = {
-    "C2 W4A8 GEMV 4096x4096": int((4233.0 * 8256.25 / 4141.0 + 8.0) * 1024),
-    "C3 W2A8 GEMV M=1 11008->4096": int((5822.0 * 11328.25 / 5677.5 + 8.0) * 1024),
-    "C5 W8A8 M=1 K=5120 N=13824": int((34782.1 * 69336.25 / 34687.75 + 27.0) * 1024),
-    "C2 W4A8 GEMV 4096x4096 g128": int((4482.0 * 8768.2 / 4396.6 + 8.0) * 1024),
-    "C5 W4A8 M=1 K=5120 N=13824 g128": int((18575.5 * 36936.2 / 18483.2 + 27.0) * 1024),
-    "C4 W6A6 GEMM M=512 4096->11008": int((26750.5 * 33196.2 / 16612.3 + 11008.1) * 1024),
-    "C5 W4A4 M=2048 K=5120 N=13824": int((125201.5 * 34776.2 / 17402.1 + 55296.0) * 1024),
-    "C5 W2A8 M=2048 K=5120 N=13824": int((70795.0 * 17496.2 / 8762.0 + 55296.0) * 1024),
+# HBM bytes per launch of the dominant kernel come from the rocprofv3 --pmc summaries under profiles/ (FETCH_SIZE and
+# WRITE_SIZE per dispatch, each scaled by what the same counter reads for a plain copy of known size in the same
+# run).  Every summary carries two machine-readable lines, `traffic_bytes_per_launch: N` and `kernel_avg_ns: T`;
+# the JSON line names the file the figure comes from and says whether this run's kernel time agrees with it.
+PROFILE_OF = {
+    "C2 W4A8 GEMV 4096x4096": "skinny_kernel_w4a8_gemv_m1_k4096_n4096.md",
+    "C3 W2A8 GEMV M=1 11008->4096": "skinny_kernel_w2a8_gemv_m1_k11008_n4096.md",
+    "C3 W2A8 GEMV M=8 11008->4096": "skinny_kernel_w2a8_gemv_m8_k11008_n4096.md",
+    "C5 W8A8 M=1 K=5120 N=13824": "skinny_kernel_w8a8_gemv_m1_k5120_n13824.md",
+    "C2 W4A8 GEMV 4096x4096 g128": "skinny_kernel_w4a8_g128_gemv_m1_k4096_n4096.md",
+    "C5 W4A8 M=1 K=5120 N=13824 g128": "skinny_kernel_w4a8_g128_gemv_m1_k5120_n13824.md",
+    "C4 W6A6 GEMM M=512 4096->11008": "tiled_kernel_w6a6_gemm_m512_k4096_n11008.md",
+    "C4 W6A6 GEMM M=128 4096->11008": "tiled_kernel_w6a6_gemm_m128_k4096_n11008.md",
+    "C5 W4A4 M=2048 K=5120 N=13824": "tiled_kernel_w4a4_gemm_m2048_k5120_n13824.md",
+    "C5 W2A8 M=2048 K=5120 N=13824": "tiled_kernel_w2a8_gemm_m2048_k5120_n13824.md",
+    ("block", 4, 8, 1): "grouped_kernel_w4a8_m1_llama7b_block.md",
+    ("block", 8, 8, 1): "grouped_kernel_w8a8_m1_llama7b_block.md",
+    ("block", 2, 8, 1): "grouped_kernel_w2a8_m1_llama7b_block.md",
 }
+
+
+def profile_figures(key, kernel_us=None):
+    """{"traffic": bytes or None, "traffic_source": file, "profile_kernel_us": .., "profile_agrees": ..} for a workload."""
+    import re
+    name = PROFILE_OF.get(key)
+    out = {"traffic": None}
+    if not name:
+        return out
+    path = os.path.join(ROOT, "profiles", name)
+    try:
+        text = open(path).read()
+    except OSError:
+        return out
+    m = re.search(r"^traffic_bytes_per_launch:\s*(\d+)", text, re.M)
+    k = re.search(r"^kernel_avg_ns:\s*(\d+)", text, re.M)
+    if m:
+        out["traffic"] = int(m.group(1))
+        out["traffic_source"] = "profiles/" + name
+    if k:
+        out["profile_kernel_us"] = int(k.group(1)) / 1e3
+        if kernel_us is not None:   # under the tracer a launch reads a few percent longer than between HIP events
+            out["profile_agrees"] = abs(out["profile_kernel_us"] - kernel_us) <= 0.10 * kernel_us
+    return out
 
 
 def build_case(name):
@@ -87,12 +119,14 @@ def child_summary(flags):
     """Runs this script once more with `flags` (no cpu baseline, no grouped leg, no further children) and returns
     the few figures of its JSON line that the parent reports; None fields when the child fails."""
     import subprocess
-    cmd = [sys.executable, os.path.abspath(__file__), *flags, "--cpu-seconds", "0", "--grouped-steps", "0"]
+    cmd = [sys.executable, os.path.abspath(__file__), *flags, "--cpu-seconds", "0", "--grouped-steps", "0", "--no-other-paths", "--no-peaks"]
     try:
         r = subprocess.run(cmd, capture_output=True, text=True, timeout=300)
         d = json.loads([l for l in r.stdout.splitlines() if l.startswith("{")][-1])
+        keep = ("bound", "achieved", "peak", "unit", "frac", "traffic", "traffic_source", "launches", "algorithmic_bytes", "frac_of_plain_read_same_size")
         return {"workload": d["config"]["workload"], "step": d["config"]["step"], "kernel_us": d["roofline"]["kernel_us_hip_events"],
-                "value": d["value"], "unit": d["unit"], "roofline": {k: d["roofline"][k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")}}
+                "rotating_bytes": d["config"]["rotating_bytes"], "tops_kernel": d["gemm_only"]["tops"], "weight_gbs_kernel": d["gemm_only"]["weight_gbs"],
+                "roofline": {k: d["roofline"][k] for k in keep if k in d["roofline"]}}
     except Exception as e:   # the main figures stand on their own
         return {"error": f"{type(e).__name__}: {e}"}
 
@@ -102,7 +136,7 @@ def measured_peaks(pool, workload_bytes, launches=200):
     probe kernels, graph-launched like the workload: a plain streaming read (of the workload's own size and of
     64 MiB, rotating through `pool` so that the last-level cache cannot serve it) and a dense int8 MFMA loop."""
     import torch
-    from paper_2408_08554_amd import binding as abq
+    from paper_2408_08554_amd import probe as abq
     sink = torch.zeros(4096, dtype=torch.uint8, device="cuda")
     stream = torch.cuda.Stream()
 
@@ -136,9 +170,6 @@ def measured_peaks(pool, workload_bytes, launches=200):
         out[key] = {"us": t * 1e6, "tops": abq.abq_probe_mfma_i8_ops(iters) / t / 1e12}
     return out
 
-
-# HBM bytes per abq_gemm_grouped launch over BLOCK_7B, measured the same way (profiles/grouped_kernel_*), by (p, q, M).
-MEASURED_GROUPED_TRAFFIC_BYTES = {(4, 8, 1): 103116232, (8, 8, 1): 204653570}
 
 # The seven linear layers of one LLaMA-7B decoder block as (name, N, K): the shapes the paper's engine
 # replaces in a block (Sec. 3.4; Appendix D measures these layer shapes one by one).
@@ -252,10 +283,11 @@ def bench_grouped(p, q, M, steps, warmup, rotate_gib, check=True, g128=False):
     alg = sum(metrics.gemm_algorithmic_bytes(p, q, M, c.N, c.K) + (3 * c.N * ((c.K + 127) // 128) if g128 else 0) for c in cases)
     wbytes = sum(metrics.packed_weight_stream_bytes(p, c.N, c.K) for c in cases)
     t = times["grouped"]
+    prof = {} if g128 else profile_figures(("block", p, q, M), t * 1e6)
     return {"workload": f"LLaMA-7B decoder block, 7 linear layers, W{p}A{q}{' g128' if g128 else ''} M={M}, one abq_gemm_grouped launch",
             "us_per_block": t * 1e6, "tops": ops / t / 1e12, "weight_gbs": wbytes / t / 1e9,
             "roofline": {"bound": "hbm", "achieved": alg / t / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                         "frac": alg / t / 1e9 / HBM_PEAK_GBS, "traffic": None if g128 else MEASURED_GROUPED_TRAFFIC_BYTES.get((p, q, M)),
+                         "frac": alg / t / 1e9 / HBM_PEAK_GBS, "traffic": prof.get("traffic"), **{k: v for k, v in prof.items() if k != "traffic"},
                          "algorithmic_bytes": alg,
                          "kernel": "abq_gemm_grouped", "launches": steps},
             "seven_single_launches_us": times["single"] * 1e6, "rotating_weight_sets": R, "rotating_bytes": R * set_bytes,
@@ -334,6 +366,9 @@ def main():
                          "for the table shipped with the package (default: the library's own rules only)")
     ap.add_argument("--no-other-paths", dest="other_paths", action="store_false",
                     help="skip the two short child runs (g128 decode, prefill) that the default run reports beside the main workload")
+    ap.add_argument("--roofline-launches", type=int, default=400,
+                    help="launches of the roofline leg (the kernel alone, HIP events), independent of --steps; never fewer than one round of the rotation set")
+    ap.add_argument("--no-peaks", dest="peaks", action="store_false", help="skip the measured-peak probes")
     ap.add_argument("--grouped-steps", type=int, default=200,
                     help="launches of the grouped decoder-block leg reported beside the main workload (0 = skip)")
     args = ap.parse_args()
@@ -379,8 +414,8 @@ def main():
     else:
         blob0 = abq.abq_pack_weights(p, w_codes, w_scale, w_zero, layout)
     blob_bytes = blob0.numel()
+    # the rotation set never depends on --steps: always >= rotate_gib GiB of distinct blobs
     R = max(2, int(np.ceil(args.rotate_gib * 2 ** 30 / blob_bytes)))
-    R = min(R, max(2, args.steps))
     stride = (blob_bytes + 255) // 256 * 256
     pool = torch.empty(R * stride, dtype=torch.uint8, device="cuda")
     blobs = [pool[i * stride:i * stride + blob_bytes] for i in range(R)]
@@ -465,6 +500,18 @@ def main():
                 yerr = np.abs(y.cpu().numpy()[ms, ns].astype(np.float64) - yref)
                 assert np.all(yerr <= ytol), f"fp16 parity failure ({name}) on rotation slot {slot}"
 
+    # A timed region never finds its weights in the 256 MB last-level cache: before it, a buffer of 768 MiB that is
+    # no part of the rotation set is streamed through the cache (the probe library's plain read).  That matters
+    # when --steps is smaller than the rotation set: the graph's untimed upload replay has just touched the very
+    # slots the timed replay reads.
+    from paper_2408_08554_amd import probe
+    evict_buf = torch.empty(768 << 20, dtype=torch.uint8, device="cuda")
+    evict_buf.zero_()
+    sink = torch.zeros(4096, dtype=torch.uint8, device="cuda")
+
+    def evict():
+        probe.abq_probe_stream_read(evict_buf, evict_buf.numel(), sink)
+
     stream = torch.cuda.Stream()
     with torch.cuda.stream(stream):
         for i in range(args.warmup):
@@ -472,7 +519,7 @@ def main():
         stream.synchronize()
 
         def timed_region(fn, n):
-            """(wall seconds, HIP-event seconds) for n calls of fn on `stream`."""
+            """(wall seconds, HIP-event seconds) for n calls of fn on `stream` (launch i uses rotation slot i % R)."""
             if args.mode == "graph":
                 g = torch.cuda.CUDAGraph()
                 with torch.cuda.graph(g, stream=stream):
@@ -485,6 +532,7 @@ def main():
                 def run():
                     for i in range(n):
                         fn(i)
+            evict()
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             torch.cuda.synchronize()
             t0 = time.perf_counter()
@@ -496,11 +544,15 @@ def main():
             return t1 - t0, e0.elapsed_time(e1) * 1e-3
 
         wall, ev = timed_region(step, args.steps)
-        _, ev_gemm = timed_region(gemm_only, args.steps)
-        _, ev_two = timed_region(two_step, args.steps) if fused else (wall, ev)
+        # the roofline leg: the kernel alone over its own launch count (at least 200 and at least once round the
+        # rotation set), whatever --steps is; the median of three such regions, so that one stray
+        # region (clock ramp, another tenant of the node) does not set the figure
+        n_roof = max(args.roofline_launches, min(R, 4096))
+        ev_gemm = sorted(timed_region(gemm_only, n_roof)[1] for _ in range(3))[1]
+        ev_two = timed_region(two_step, max(args.steps, 200))[1] / max(args.steps, 200) if fused else ev / args.steps
 
     sec_per_step = wall / args.steps
-    gemm_s = ev_gemm / args.steps
+    gemm_s = ev_gemm / n_roof
     alg_bytes = metrics.gemm_algorithmic_bytes(p, q, M, N, K)
     if args.g128:
         alg_bytes += 3 * N * ((K + 127) // 128)   # a binary16 scale and a one-byte zero-point per channel and group
@@ -513,9 +565,9 @@ def main():
         achieved = 2.0 * M * N * K / gemm_s / 1e12
         roof = {"bound": "mfma", "achieved": achieved, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
                 "frac": achieved / INT8_MFMA_PEAK_TOPS, "traffic": None}
-    roof["traffic"] = MEASURED_TRAFFIC_BYTES.get(c.name)
+    roof.update(profile_figures(c.name, gemm_s * 1e6))
     roof.update({"kernel": "abq_gemm_act_codes" if gemm_only is fused_step else "abq_gemm", "kernel_us_hip_events": gemm_s * 1e6, "algorithmic_bytes": alg_bytes,
-                 "launches": args.steps})
+                 "launches": n_roof})
 
     out = {
         "metric": "effective TOPS (2*M*N*K/s)", "value": metrics.effective_tops(M, N, K, sec_per_step), "unit": "TOPS",
@@ -529,18 +581,19 @@ def main():
         "gemm_only": {"us": gemm_s * 1e6, "tops": metrics.effective_tops(M, N, K, gemm_s),
                       "weight_gbs": metrics.weight_gbs(p, N, K, gemm_s)},
         "hip_event_ms_per_step": ev / args.steps * 1e3,
-        "two_call_step": {"ms_per_step": ev_two / args.steps * 1e3, "tops": metrics.effective_tops(M, N, K, ev_two / args.steps),
+        "two_call_step": {"ms_per_step": ev_two * 1e3, "tops": metrics.effective_tops(M, N, K, ev_two),
                           "step": "abq_pack_act_codes + abq_gemm"},
         "roofline": roof,
     }
-    peaks = measured_peaks(pool, alg_bytes)
-    out["measured_peaks"] = peaks
-    roof["measured_peak"] = peaks["stream_read_64MiB"]["gbs"] if hbm_bound else peaks["mfma_i8_nonzero_operand_bytes"]["tops"]
-    roof["frac_of_measured_peak"] = achieved / roof["measured_peak"]
-    if hbm_bound:   # a plain read of the same number of bytes in a launch of its own: the floor for this size
-        roof["frac_of_plain_read_same_size"] = peaks["stream_read_workload_size"]["us"] / (gemm_s * 1e6)
+    if args.peaks:
+        peaks = measured_peaks(pool, alg_bytes)
+        out["measured_peaks"] = peaks
+        roof["measured_peak"] = peaks["stream_read_64MiB"]["gbs"] if hbm_bound else peaks["mfma_i8_nonzero_operand_bytes"]["tops"]
+        roof["frac_of_measured_peak"] = achieved / roof["measured_peak"]
+        if hbm_bound:   # a plain read of the same number of bytes in a launch of its own: the floor for this size
+            roof["frac_of_plain_read_same_size"] = peaks["stream_read_workload_size"]["us"] / (gemm_s * 1e6)
     if args.grouped_steps > 0 and M <= 16:
-        del pool, blobs
+        del pool, blobs, evict_buf
         torch.cuda.empty_cache()
         out["grouped_decoder_block"] = bench_grouped(p, q, M, args.grouped_steps, 20, args.rotate_gib, not args.no_check, args.g128)
     if args.cpu_seconds > 0:
@@ -548,9 +601,15 @@ def main():
     if args.other_paths and not args.g128 and args.workload == "c2" and args.grouped_steps > 0:
         # the other kernels of the path, each as a short run of this script in a child process (own parity check):
         # the same decode step on per-group (g128) weight parameters, and a prefill matmul on the tiled kernel
+        short = ["--steps", "20", "--warmup", "5"]
         out["other_paths"] = {
-            "decode_g128_weights": child_summary(["--workload", "c2", "--g128", "--steps", "500", "--warmup", "50"]),
-            "prefill_w4a4_m2048": child_summary(["--workload", "c5:4,4,0,3", "--step", "two", "--steps", "30", "--warmup", "5"]),
+            "decode_w2a8_m1_c3": child_summary(["--workload", "c3m1", *short]),
+            "decode_w2a8_m8_c3": child_summary(["--workload", "c3m8", *short]),
+            "decode_w8a8_m1_13b": child_summary(["--workload", "c5:8,8,0,0", *short]),
+            "decode_g128_weights": child_summary(["--workload", "c2", "--g128", *short]),
+            "prefill_w6a6_m128_c4": child_summary(["--workload", "c4m128", "--step", "two", *short]),
+            "prefill_w6a6_m512_c4": child_summary(["--workload", "c4m512", "--step", "two", *short]),
+            "prefill_w4a4_m2048": child_summary(["--workload", "c5:4,4,0,3", "--step", "two", "--roofline-launches", "60", *short]),
         }
     print(json.dumps(out), flush=True)
 

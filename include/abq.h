@@ -175,6 +175,16 @@ int abq_unpack_act(int q, int M, int K, int layout, const void* packed, int whic
                    uint8_t* a_codes_out, float* a_scale_out, int32_t* a_zero_out,
                    int32_t* a_sum_out, void* stream);
 
+/* Load-time validation of a packed blob.  The matmul calls take a blob's geometry from their own arguments and
+ * never read its header (that would cost a synchronising copy per call), so a p/q, N/M, K or layout value that
+ * differs from pack time makes them read outside the blob.  This call is the check: it copies the blob's header
+ * to the host — it SYNCHRONISES with `stream` — and compares magic, format version, bit width, rows, K and
+ * layout with the arguments, and packed_bytes with the size query.
+ *   kind: 0 = packed weights (bits = p, rows = N), 1 = packed activations (bits = q, rows = M)
+ * ABQ_OK on a match; ABQ_ERR_LAYOUT on any mismatch (also for an unknown kind or layout value); ABQ_ERR_SIZE
+ * when packed_bytes is smaller than the size query (checked before the first HIP call). */
+int abq_check_packed(int kind, int bits, int rows, int K, int layout, const void* packed, size_t packed_bytes, void* stream);
+
 /* ------------------------------------------------------------------------------------------
  * Matmul + bit reduction + fused dequant (Sec. 3.4 steps 2–6, Appendix B, Fig. 3b "DeQuant").
  * ------------------------------------------------------------------------------------------ */
@@ -284,25 +294,6 @@ size_t abq_gemm_grouped_workspace_bytes(int p, int q, int M, int count, const ab
                                         int a_layout, int w_layout);
 int abq_gemm_grouped(int p, int q, int M, int count, const abq_problem* host_problems,
                      int a_layout, int w_layout, void* workspace, size_t workspace_bytes, void* stream);
-
-/* ------------------------------------------------------------------------------------------
- * Measurement aids (no part of the method; for callers that price achieved figures against what
- * the machine delivers, beside its published peaks).  Each enqueues ONE kernel; the caller times it.
- * ------------------------------------------------------------------------------------------ */
-
-/* Streaming read of `bytes` bytes (a multiple of 16) at `buf` with 128-bit non-temporal loads, the access
- * the decode kernel uses for its weights; nothing is written (`sink`: >= 2 KiB of device memory that
- * stays untouched in practice). */
-int abq_probe_stream_read(const void* buf, size_t bytes, void* sink, void* stream);
-
-/* Dense int8 MFMA issue loop on every CU: `iters` rounds of eight independent 16x16x64 MFMAs per wave,
- * 32 waves per CU.  pattern 0: three of four operand bytes zero; pattern 1: every operand byte non-zero
- * and varying from lane to lane (the sustained rate depends on the data: the chip lowers its clock on
- * the latter).  abq_probe_mfma_i8_ops(iters) is the
- * number of integer operations (2 per MAC) one such launch performs on the current device (0 for
- * iters < 1). */
-int abq_probe_mfma_i8(int iters, int pattern, void* sink, void* stream);
-double abq_probe_mfma_i8_ops(int iters);
 
 #ifdef __cplusplus
 }

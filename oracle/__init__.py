@@ -127,24 +127,6 @@ def dequant_grouped(A, W, a_zero, a_scale, w_zero, w_scale_half, gs=128, want_ma
     return (y, y16, mag) if want_mag else (y, y16)
 
 
-def dequant_flat(accc, a_scale_per_elem, w_scale_per_elem):
-    """Same as dequant for a flat list of sampled elements with their own scales."""
-    accc = np.ascontiguousarray(accc, dtype=np.int64).reshape(-1)
-    n = accc.shape[0]
-    y = np.empty(n, dtype=np.float64)
-    y16 = np.empty(n, dtype=np.uint16)
-    a = np.ascontiguousarray(a_scale_per_elem, dtype=np.float32).reshape(-1)
-    w = np.ascontiguousarray(w_scale_per_elem, dtype=np.float32).reshape(-1)
-    lib = _load()
-    one = np.empty(1, dtype=np.float64)
-    one16 = np.empty(1, dtype=np.uint16)
-    for i in range(n):
-        lib.abq_oracle_dequant(1, 1, _p(accc[i:i + 1]), _p(a[i:i + 1]), _p(w[i:i + 1]), _p(one), _p(one16))
-        y[i] = one[0]
-        y16[i] = one16[0]
-    return y, y16
-
-
 def half_bits(v: float) -> int:
     return int(_load().abq_oracle_half_bits(float(v)))
 

@@ -44,14 +44,12 @@ _SIGNATURES = {
     "abq_gemm_act_codes_workspace_bytes": (_c.c_size_t, [_c.c_int] * 6),
     "abq_gemm_grouped_workspace_bytes": (_c.c_size_t, [_c.c_int] * 4 + [_c.c_void_p, _c.c_int, _c.c_int]),
     "abq_gemm_grouped": (_c.c_int, [_c.c_int] * 4 + [_c.c_void_p, _c.c_int, _c.c_int, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
-    "abq_probe_stream_read": (_c.c_int, [_c.c_void_p, _c.c_size_t, _c.c_void_p, _c.c_void_p]),
-    "abq_probe_mfma_i8": (_c.c_int, [_c.c_int, _c.c_int, _c.c_void_p, _c.c_void_p]),
-    "abq_probe_mfma_i8_ops": (_c.c_double, [_c.c_int]),
     "abq_rmsnorm_quant_act": (_c.c_int, [_c.c_int] * 3 + [_c.c_void_p, _c.c_void_p, _c.c_float] + [_c.c_void_p] * 5),
     "abq_add_rmsnorm_quant_act": (_c.c_int, [_c.c_int] * 3 + [_c.c_void_p] * 3 + [_c.c_float] + [_c.c_void_p] * 6),
     "abq_silu_mul_quant_act": (_c.c_int, [_c.c_int] * 3 + [_c.c_void_p] * 7),
     "abq_gemm_act_codes": (_c.c_int, [_c.c_int] * 5 + [_c.c_void_p] * 4 + [_c.c_int, _c.c_void_p, _c.c_void_p,
                                                                           _c.c_void_p, _c.c_size_t, _c.c_void_p]),
+    "abq_check_packed": (_c.c_int, [_c.c_int] * 5 + [_c.c_void_p, _c.c_size_t, _c.c_void_p]),
     "abq_gemm_act_codes_static": (_c.c_int, [_c.c_int] * 5 + [_c.c_void_p] * 4 + [_c.c_int, _c.c_void_p, _c.c_void_p, _c.c_void_p]),
 }
 
@@ -149,6 +147,11 @@ def abq_pack_weights_g128(p, w_codes, w_scale_fp16, w_zero, out=None):
     _check(lib.abq_pack_weights_g128(p, N, K, _ptr(w_codes), _ptr(w_scale_fp16), _ptr(w_zero), _ptr(out), out.numel(),
                                      _stream()), "abq_pack_weights_g128")
     return out
+
+
+def abq_check_packed(kind, bits, rows, K, layout, packed):
+    """Status of the load-time header check (0 = the blob matches; synchronises)."""
+    return load().abq_check_packed(kind, bits, rows, K, layout, _ptr(packed), packed.numel(), _stream())
 
 
 def abq_unpack_weights(p, N, K, layout, packed, which):
@@ -300,18 +303,6 @@ def abq_plan_get(p, q, M, N, K):
 
 def abq_plan_clear():
     load().abq_plan_clear()
-
-
-def abq_probe_stream_read(buf, nbytes, sink):
-    _check(load().abq_probe_stream_read(_ptr(buf), nbytes, _ptr(sink), _stream()), "abq_probe_stream_read")
-
-
-def abq_probe_mfma_i8(iters, pattern, sink):
-    _check(load().abq_probe_mfma_i8(iters, pattern, _ptr(sink), _stream()), "abq_probe_mfma_i8")
-
-
-def abq_probe_mfma_i8_ops(iters):
-    return load().abq_probe_mfma_i8_ops(iters)
 
 
 def abq_rmsnorm_quant_act(q, x_fp16, gamma_fp16, eps, want_y=False):

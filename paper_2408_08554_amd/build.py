@@ -13,6 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libabq.so")
+PROBE_LIB = os.path.join(HERE, "libabq_probe.so")   # measurement aids of the benchmark, not part of libabq.so
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -21,10 +22,12 @@ FLAGS = [
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option",
 ]
+if os.environ.get("ABQ_BUILD_TUNING") == "1":   # the tuner's A/B builds only: lets ABQ_* environment variables override launch plans
+    FLAGS.append("-DABQ_TUNING_ENV")
 
 
 def _compile(src: str, newest_header: float = 0.0) -> str:
-    obj = os.path.join(OBJ, os.path.basename(src) + ".o")
+    obj = os.path.join(OBJ, os.path.relpath(src, CSRC).replace(os.sep, "_") + ".o")
     if newest_header and os.path.exists(obj) and os.path.getmtime(obj) >= max(newest_header, os.path.getmtime(src)):
         return obj   # --incremental: neither the source nor any header is newer than the object
     subprocess.run([HIPCC, *FLAGS, "-c", src, "-o", obj], check=True, stderr=subprocess.PIPE, text=True)
@@ -35,19 +38,21 @@ def build(verbose: bool = False, incremental: bool = False) -> str:
     """Compiles every source (always, unless `incremental`: then only what is older than its source or a header)."""
     os.makedirs(OBJ, exist_ok=True)
     srcs = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
+    probe_srcs = sorted(glob.glob(os.path.join(CSRC, "probe", "*.hip")))
     headers = glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(HERE, "..", "include", "*.h")) + [__file__]
     newest = max(os.path.getmtime(h) for h in headers) if incremental else 0.0
     with concurrent.futures.ThreadPoolExecutor(max_workers=min(8, len(srcs))) as ex:
-        futs = {ex.submit(_compile, s, newest): s for s in srcs}
-        objs = []
+        futs = {ex.submit(_compile, s, newest): s for s in srcs + probe_srcs}
+        objs, probe_objs = [], []
         for f, s in futs.items():
             try:
-                objs.append(f.result())
+                (probe_objs if s in probe_srcs else objs).append(f.result())
             except subprocess.CalledProcessError as e:
                 raise RuntimeError(f"hipcc failed on {s}:\n{e.stderr}") from None
             if verbose:
                 print("compiled", os.path.basename(s), flush=True)
     subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *sorted(objs), "-o", LIB], check=True)
+    subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *sorted(probe_objs), "-o", PROBE_LIB], check=True)
     return LIB
 
 

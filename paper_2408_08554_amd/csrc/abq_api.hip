@@ -299,6 +299,34 @@ int abq_silu_mul_quant_act(int q, int M, int K, const uint16_t* gate_fp16, const
                                             (hipStream_t)stream));
 }
 
+int abq_check_packed(int kind, int bits, int rows, int K, int layout, const void* packed, size_t packed_bytes, void* stream)
+{
+    if (!packed) return ABQ_ERR_NULL;
+    if (int e = check_bits_shape(bits, rows, K)) return e;
+    size_t total = 0;
+    if (kind == 0) {
+        WeightLayout L;
+        if (!make_weight_layout(bits, rows, K, layout, &L)) return ABQ_ERR_LAYOUT;
+        total = L.total;
+    } else if (kind == 1) {
+        ActLayout L;
+        if (!make_act_layout(bits, rows, K, layout, &L)) return ABQ_ERR_LAYOUT;
+        total = L.total;
+    } else {
+        return ABQ_ERR_LAYOUT;
+    }
+    if (misaligned(packed)) return ABQ_ERR_ALIGN;
+    if (packed_bytes < total) return ABQ_ERR_SIZE;
+    uint32_t hdr[6] = {0, 0, 0, 0, 0, 0};   // magic, format version, bits, rows, K, layout
+    hipStream_t s = (hipStream_t)stream;
+    if (int e = hip_status(hipMemcpyAsync(hdr, packed, sizeof(hdr), hipMemcpyDeviceToHost, s))) return e;
+    if (int e = hip_status(hipStreamSynchronize(s))) return e;
+    const uint32_t want[6] = {kind == 0 ? kMagicW : kMagicA, 1u, (uint32_t)bits, (uint32_t)rows, (uint32_t)K, (uint32_t)layout};
+    for (int i = 0; i < 6; ++i)
+        if (hdr[i] != want[i]) return ABQ_ERR_LAYOUT;
+    return ABQ_OK;
+}
+
 static int check_gemm_shape(int p, int q, int M, int N, int K)
 {
     if (p < 1 || p > 8 || q < 1 || q > 8) return ABQ_ERR_BITS;
@@ -329,13 +357,8 @@ static const int kSkinnyMaxM = 16;   // one MFMA tile of activation rows: the st
 static bool streaming_shape(int M, int N)
 {
     if (M <= kSkinnyMaxM) return true;
-    static int max_m = -1, max_wgs = -1;   // tuning overrides, read once: ABQ_STREAM_MAX_M, ABQ_STREAM_MAX_WGS
-    if (max_m < 0) {
-        const char* e = getenv("ABQ_STREAM_MAX_M");
-        max_m = e ? atoi(e) : 64;
-        e = getenv("ABQ_STREAM_MAX_WGS");
-        max_wgs = e ? atoi(e) : 128;
-    }
+    const int env_m = tuning_env("ABQ_STREAM_MAX_M"), env_wgs = tuning_env("ABQ_STREAM_MAX_WGS");
+    const int max_m = env_m > 0 ? env_m : 64, max_wgs = env_wgs > 0 ? env_wgs : 128;
     const long tiled_wgs = (long)((M + 63) / 64) * ((N + 63) / 64);
     return M <= max_m && tiled_wgs < max_wgs;
 }

@@ -345,11 +345,9 @@ static hipError_t launch_shape(const TiledParams& prm, dim3 grid, int cus, int p
     // 11008-wide layer and up) the traffic through L2, not the latency of a step, is the bound and they lose.
     // With long K (13824) the plan search found them 6-7 % ahead up to 1.25 workgroups per CU as well, and at
     // p = 8 up to 2.5 per CU (M = 512, 5120 channels: 75 vs 84 us); narrower weights lose there (W2A8: 53 vs 44 us).
-    // Overrides: the plan table (plan_wd), else ABQ_TILED_WD=<2|4> (read once).
+    // Override: the plan table (plan_wd).
     constexpr bool has_deep = MT == 4 && (NTW == 1 || (NTW == 2 && P <= 6));
-    static int env_forced = -1;
-    if (env_forced < 0) { const char* e = getenv("ABQ_TILED_WD"); env_forced = e ? atoi(e) : 0; }
-    const int forced = plan_wd > 0 ? plan_wd : env_forced;
+    const int forced = plan_wd > 0 ? plan_wd : tuning_env("ABQ_TILED_WD");
     if constexpr (has_deep) {
         if (forced == 4 || (forced != 2 && ((long)grid.x <= (long)cus || ((long)grid.x <= (P == 8 ? 3L : 2L) * cus && prm.K >= 8192)))) {
             tiled_kernel<P, NTW, MT, 4><<<grid, 256, 0, s>>>(prm);
@@ -401,13 +399,11 @@ hipError_t launch_gemm_tiled(const GemmArgs& g, const ActLayout& A, const Weight
     else if (g.p <= 4 && g.M >= 1024) { mt = 4; ntw = wgs(4, 4) >= 3L * cus ? 4 : 2; }
     if (mt == 4 && ntw == 2 && 2 * wgs(4, 2) < 3L * cus) ntw = 1;
     {
-        static int forced_mt = -1, forced_ntw = -1;   // tuning overrides, read once: ABQ_TILED_MT=<4|8>, ABQ_TILED_NTW=<1|2|4>
-        if (forced_mt < 0) { const char* e = getenv("ABQ_TILED_MT"); forced_mt = e ? atoi(e) : 0; }
-        if (forced_ntw < 0) { const char* e = getenv("ABQ_TILED_NTW"); forced_ntw = e ? atoi(e) : 0; }
+        const int forced_mt = tuning_env("ABQ_TILED_MT"), forced_ntw = tuning_env("ABQ_TILED_NTW");
         if (forced_mt == 4 || forced_mt == 8) mt = forced_mt;
         if (forced_ntw == 1 || forced_ntw == 2 || forced_ntw == 4) ntw = forced_ntw;
     }
-    PlanOverride ov;   // the plan table entry of this exact problem goes before the environment
+    PlanOverride ov;   // the plan table entry of this exact problem
     lookup_plan(g.p, g.q, g.M, g.N, g.K, &ov);
     if (ov.tiled_mt > 0) mt = ov.tiled_mt;
     if (ov.tiled_ntw > 0) ntw = ov.tiled_ntw;
@@ -418,8 +414,7 @@ hipError_t launch_gemm_tiled(const GemmArgs& g, const ActLayout& A, const Weight
     // column blocks of W (p/8 byte per element): least near band_m = sqrt(8p) blocks of 128 rows, and measured
     // so on M = 2048 and 8192: bands of 512 rows of A for p <= 4, 1024 above.
     {
-        static int forced_band = -1;   // tuning override, read once: ABQ_TILED_BAND=<row blocks per band>
-        if (forced_band < 0) { const char* e = getenv("ABQ_TILED_BAND"); forced_band = e ? atoi(e) : 0; }
+        const int forced_band = tuning_env("ABQ_TILED_BAND");
         const int cap = ov.tiled_band > 0 ? ov.tiled_band : (forced_band > 0 ? forced_band : (g.p <= 4 ? 512 : 1024) / (mt * 16));
         const int bands = (prm.tiles_m + cap - 1) / cap;
         prm.band_m = (prm.tiles_m + bands - 1) / bands;

@@ -4,6 +4,7 @@
 #include <hip/hip_fp16.h>
 #include <stddef.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 namespace abq {
 
@@ -33,6 +34,20 @@ constexpr uint32_t kMagicW = 0x57514241u;   // "ABQW"
 constexpr uint32_t kMagicA = 0x41514241u;   // "ABQA"
 
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// The library reads no environment variable: launch plans come from closed-form rules and from the plan table of
+// the ABI.  Only a build made with -DABQ_TUNING_ENV (the tuner's own A/B experiments) looks at ABQ_* variables,
+// afresh on every call, so that no mutable state is kept.
+static inline int tuning_env(const char* name)
+{
+#ifdef ABQ_TUNING_ENV
+    const char* e = getenv(name);
+    return e ? atoi(e) : 0;
+#else
+    (void)name;
+    return 0;
+#endif
+}
 
 // Packed-weight blob:
 //   [header 256 B][wparams N x {int32 wsum, float scale, int32 zero, int32 0}]

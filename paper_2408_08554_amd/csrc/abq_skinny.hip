@@ -16,23 +16,24 @@
 #include "abq_skinny_kernels.h"
 
 #include <math.h>
+#include <atomic>
 
 namespace abq {
 
 // ---- host side -------------------------------------------------------------------------------------
 
-static int g_num_cus = 0;
+static std::atomic<int> g_num_cus{0};   // a cached device property (every thread would store the same value)
 
 static int num_cus()
 {
-    if (g_num_cus == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-            g_num_cus = n;
-        else
-            g_num_cus = 256;
+    int n = g_num_cus.load(std::memory_order_relaxed);
+    if (n == 0) {
+        int dev = 0;
+        if (!(hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0))
+            n = 256;
+        g_num_cus.store(n, std::memory_order_relaxed);
     }
-    return g_num_cus;
+    return n;
 }
 
 // The kernels use up to 256 VGPRs, i.e. two waves per SIMD, eight per CU.
@@ -115,12 +116,6 @@ static bool make_plan(int S, int G, int M, int Kp, int ntiles, int cus, SkinnyPl
     return false;
 }
 
-static int env_int(const char* name)
-{
-    const char* e = getenv(name);
-    return e ? atoi(e) : 0;
-}
-
 // one_group: the kernel variant at hand has no K groups (then long K with many rows takes more passes over W).
 // forced / forced_g > 0: the K split / group count to use if it fits (from the plan table or the environment).
 static bool pick_plan(int M, int Kp, int ntiles, int cus, size_t stream_bytes, bool one_group, int forced, int forced_g,
@@ -200,6 +195,7 @@ static void fill_operands(SkinnyParams& prm, const GemmArgs& g, const ActLayout&
     prm.M = g.M; prm.N = g.N; prm.K = g.K; prm.Kp = A.Kp;
     prm.oa = (g.q == 8) ? 128 : 0;
     prm.ow = (g.p == 8) ? 128 : 0;
+    prm.a_mask = ((1u << g.q) - 1u) * 0x01010101u;
     prm.ntiles = W.NT;
 }
 
@@ -211,14 +207,11 @@ hipError_t launch_gemm_skinny(const GemmArgs& g, const ActLayout& A, const Weigh
     const int nsuper = A.Kp / kSuperK;
     SkinnyPlan pl;
     const size_t stream_bytes = (size_t)g.p * W.NT * 16 * (size_t)A.Kp / 8;
-    // overrides: the plan table entry of this exact problem, else the environment (read once):
-    // ABQ_SKINNY_WAVES=<S> forces the K split, ABQ_SKINNY_KGROUPS=<G> the group count
-    static int env_waves = -1, env_groups = -1;
-    if (env_waves < 0) { env_waves = env_int("ABQ_SKINNY_WAVES"); env_groups = env_int("ABQ_SKINNY_KGROUPS"); }
+    // override: the plan table entry of this exact problem (K split, K group count)
     PlanOverride ov;
     lookup_plan(g.p, g.q, g.M, g.N, g.K, &ov);
-    const int forced = ov.skinny_waves > 0 ? ov.skinny_waves : env_waves;
-    const int forced_g = ov.skinny_kgroups > 0 ? ov.skinny_kgroups : env_groups;
+    const int forced = ov.skinny_waves > 0 ? ov.skinny_waves : tuning_env("ABQ_SKINNY_WAVES");
+    const int forced_g = ov.skinny_kgroups > 0 ? ov.skinny_kgroups : tuning_env("ABQ_SKINNY_KGROUPS");
     if (!pick_plan(g.M, A.Kp, W.NT, cus, stream_bytes, W.g128, forced, forced_g, &pl)) return hipErrorInvalidValue;   // cannot happen for K <= ABQ_MAX_K
     const int waves = pl.waves, gx = pl.gx, mrows = pl.mrows;
     // LDS: staged rows of A (all of K, or one K group of it), the epilogue parameters, two reduction buffers
@@ -254,15 +247,13 @@ hipError_t launch_gemm_skinny(const GemmArgs& g, const ActLayout& A, const Weigh
 // Shape of a grouped launch, measured on the seven layer shapes of a LLaMA-7B block (W1/W2/W4/W8, M = 1, 4, 8):
 // few rows of A -> small workgroups (two waves for M <= 2, four for M <= 4) and four of them per CU, so that
 // the prologue and tail of one run hide behind the streams of the others; more rows -> eight waves, one
-// workgroup per CU, so that the rows of A are staged as seldom as possible.  Tuning overrides, read once:
-// ABQ_GROUP_WAVES=<S>, ABQ_GROUP_WGS=<workgroup count>.  A run never exceeds kMaxRun tiles (the epilogue
-// parameters of a run live in LDS).
+// workgroup per CU, so that the rows of A are staged as seldom as possible.  A run never exceeds kMaxRun tiles
+// (the epilogue parameters of a run live in LDS).
 constexpr int kMaxRun = 64;
 static int group_waves(int M) { return M <= 2 ? 2 : (M <= 4 ? 4 : 8); }
 static int group_workgroups(int tiles, int M, int cus)
 {
-    static int forced = -1;
-    if (forced < 0) forced = env_int("ABQ_GROUP_WGS");
+    const int forced = tuning_env("ABQ_GROUP_WGS");
     int gx = forced > 0 ? forced : (M <= 4 ? 4 * cus : cus);
     if (gx > tiles) gx = tiles;
     if ((tiles + gx - 1) / gx > kMaxRun) gx = (tiles + kMaxRun - 1) / kMaxRun;
@@ -281,9 +272,7 @@ static int group_partition(GroupedParams& gp, int first, int n, int M, const Act
     // Measured on the LLaMA-7B block (same box, A/B): with many small workgroups per CU (M <= 4) equal tile
     // counts, the longer runs first, beat every equal-work cut by 3-8 %; with one eight-wave workgroup per CU
     // (M > 4) equal work (super-chunks + a fixed cost of 16 per tile) is 10 % faster than equal counts.
-    // Tuning override, read once: ABQ_GROUP_TILE_COST=<fixed cost> forces the equal-work cut with that cost.
-    static int overhead = -1;
-    if (overhead < 0) { const char* e = getenv("ABQ_GROUP_TILE_COST"); overhead = e ? atoi(e) : 0; }
+    const int overhead = tuning_env("ABQ_GROUP_TILE_COST");   // > 0 forces the equal-work cut with that fixed cost
     gp.by_work = (overhead > 0 || M > 4) ? 1 : 0;
     for (int i = 0; i < kMaxGroup; ++i) {
         const int src = first + (i < n ? i : 0);
@@ -316,8 +305,7 @@ static int group_partition(GroupedParams& gp, int first, int n, int M, const Act
 bool gemm_grouped_fits(int M, int count, const GemmArgs* probs, const ActLayout* A, const WeightLayout* W, int* waves, size_t* lds_bytes)
 {
     if (M > 16 || count < 1) return false;
-    static int forced = -1;
-    if (forced < 0) forced = env_int("ABQ_GROUP_WAVES");
+    const int forced = tuning_env("ABQ_GROUP_WAVES");
     int S = forced >= 2 && forced <= 8 && forced != 3 ? forced : group_waves(M);
     for (int i = 0; i < count; ++i) {
         if (!W[i].has_fields) return false;

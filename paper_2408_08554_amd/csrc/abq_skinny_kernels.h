@@ -24,21 +24,12 @@
 
 #include <hip/hip_fp16.h>
 #include <stdlib.h>
+#include <atomic>
 
 namespace abq {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef unsigned int u4v __attribute__((ext_vector_type(4)));
-
-// Phase timestamps for kernel tuning; compiled out unless a harness defines ABQ_PHASE_TRACE.
-#ifdef ABQ_PHASE_TRACE
-__device__ unsigned long long g_phase_trace[1024 * 8 * 8];
-#define ABQ_TS(i) ts[i] = wall_clock64()
-#define ABQ_TSS(i) st.ts[i] = wall_clock64()
-#else
-#define ABQ_TS(i)
-#define ABQ_TSS(i)
-#endif
 
 struct SkinnyParams {
     const u4v* fields[3];     // per plane group
@@ -53,6 +44,7 @@ struct SkinnyParams {
     int32_t* acc;
     int M, N, K, Kp;
     int oa, ow;
+    uint32_t a_mask;          // (2^q - 1) in every byte: applied to unpacked activation codes while they are staged
     int ntiles;               // 16-row tiles of W
     int nsuper;               // Kp / 512
     int sc_q, sc_r;           // nsuper = sc_q * S + sc_r   (S = waves per workgroup): wave w owns sc_q + (w < sc_r) super-chunks
@@ -302,9 +294,6 @@ struct WaveState {
     int32_t* red;
     v4i acc[GroupInfo<P>::NACC];
     v4f facc;                      // per-group weight parameters: this wave's single-precision sum over its groups
-#ifdef ABQ_PHASE_TRACE
-    unsigned long long* ts;
-#endif
 };
 
 // Item order: (K group,) tile, super-chunk.
@@ -342,7 +331,6 @@ __device__ __forceinline__ void finish_tile(const SkinnyParams& prm, WaveState<P
 {
     using GI = GroupInfo<P>;
     static_assert(!(GQ && KG), "per-group weight parameters are not combined with K groups");
-    ABQ_TSS(3);
     v4i total;
     if constexpr (GQ) {
         // the wave's partial result is a single-precision sum; it travels through LDS as its bit pattern
@@ -372,9 +360,7 @@ __device__ __forceinline__ void finish_tile(const SkinnyParams& prm, WaveState<P
     int32_t* rb = st.red + st.parity * (st.S * 256);
 #pragma unroll
     for (int reg = 0; reg < 4; ++reg) rb[(st.wave * 4 + reg) * 64 + st.lane] = total[reg];
-    ABQ_TSS(4);
     __syncthreads();
-    ABQ_TSS(5);
     // thread t finishes C elements e = t + i*blockDim < 256; element e is register e/64 of lane e%64:
     // row 4*((e%64)/16) + e/64 of A, column e%16 of the tile (the 16x16 MFMA accumulator layout)
     const int tile = st.tile0 + st.ti * st.tstride;
@@ -474,11 +460,6 @@ __device__ __forceinline__ void skinny_body(const SkinnyParams& prm, const int t
     st.nsuper = prm.nsuper;
     st.tile0 = tile0; st.tstride = tstride;
     st.p_ti = 0; st.p_lsc = 0; st.ti = 0; st.lsc = 0; st.parity = 0;
-#ifdef ABQ_PHASE_TRACE
-    unsigned long long ts[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    st.ts = ts;
-#endif
-    ABQ_TS(0);
 
     st.nsw = prm.sc_q + (st.wave < prm.sc_r ? 1 : 0);                       // this wave's super-chunks per tile (>= 1)
     st.nitems = nmy * st.nsw;
@@ -514,6 +495,7 @@ __device__ __forceinline__ void skinny_body(const SkinnyParams& prm, const int t
     const uint8_t* a_base = RAW ? prm.a_raw + (size_t)st.m0 * prm.K : (const uint8_t*)prm.a_codes + (size_t)st.m0 * prm.Kp;
     const int a_ld = RAW ? prm.K : prm.Kp;
     const uint32_t flip = (RAW && prm.oa) ? 0x80808080u : 0u;
+    const uint32_t qmask = prm.a_mask;   // RAW: bits above q are ignored, as the packers ignore them
     int32_t my_sum = 0;
     // column of A in global memory / in LDS for slot pr + half of the run [st.gs, st.ge) being staged
     auto batch_col = [&](int pr) { return (st.wave + (st.gs + min(pr + half, st.ge - st.gs - 1)) * st.S) * kSuperK + vec * 16; };
@@ -538,6 +520,7 @@ __device__ __forceinline__ void skinny_body(const SkinnyParams& prm, const int t
             if (u > 0 && row0 + u >= mt) break;   // wave-uniform
             uint4 v = areg[u];
             if constexpr (RAW) {
+                v = uint4{v.x & qmask, v.y & qmask, v.z & qmask, v.w & qmask};
                 {
                     uint32_t part = 0;
                     part = __builtin_amdgcn_udot4(v.x, 0x01010101u, part, false);
@@ -615,11 +598,6 @@ __device__ __forceinline__ void skinny_body(const SkinnyParams& prm, const int t
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    ABQ_TS(1);
-#ifdef ABQ_PHASE_TRACE
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    ABQ_TS(2);
-#endif
 
     st.lds_lane = (r < mt ? lds + r * prm.a_stride : lds + prm.zero_off) + G * 16;
     st.k_mask = r < mt ? ~0 : 0;
@@ -675,11 +653,6 @@ __device__ __forceinline__ void skinny_body(const SkinnyParams& prm, const int t
                 if (it + d < st.nitems) item_step<P, EPT, RAW, KG, false, GQ>(prm, st, w[d], it + d + D < st.nitems, next_group);
         }
     }
-#ifdef ABQ_PHASE_TRACE
-    ABQ_TS(6);
-    if (st.lane == 0 && blockIdx.x < 1024 && st.wave < 8)
-        for (int i = 0; i < 8; ++i) g_phase_trace[((size_t)blockIdx.x * 8 + st.wave) * 8 + i] = ts[i];
-#endif
 }
 
 template <int P, int D, int EPT, bool RAW, bool FULL, bool KG, bool R16, bool GQ = false>
@@ -757,11 +730,11 @@ __global__ __launch_bounds__(512) void grouped_kernel(GroupedParams gp)
 template <int P, int D, int EPT, bool RAW, bool FULL, bool KG, bool R16, bool GQ = false>
 static hipError_t launch_variant_r(const SkinnyParams& prm, dim3 grid, int waves, size_t lds_bytes, hipStream_t s)
 {
-    static bool attr_set = false;
-    if (!attr_set) {
+    static std::atomic<bool> attr_set{false};   // (an idempotent call: a lost race only repeats it)
+    if (!attr_set.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute((const void*)skinny_kernel<P, D, EPT, RAW, FULL, KG, R16, GQ>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        attr_set.store(true, std::memory_order_release);
     }
     skinny_kernel<P, D, EPT, RAW, FULL, KG, R16, GQ><<<grid, waves * 64, lds_bytes, s>>>(prm);
     return hipGetLastError();
@@ -825,12 +798,12 @@ static hipError_t launch_pd(const SkinnyParams& prm, dim3 grid, int waves, size_
 template <int P, int D>
 static hipError_t launch_grouped_gq(const GroupedParams& gp, bool raw, unsigned grid, int waves, size_t lds_bytes, hipStream_t s)
 {
-    static bool attr_set = false;
-    if (!attr_set) {
+    static std::atomic<bool> attr_set{false};   // (an idempotent call: a lost race only repeats it)
+    if (!attr_set.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute((const void*)grouped_kernel<P, D, 1, true, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e == hipSuccess) e = hipFuncSetAttribute((const void*)grouped_kernel<P, D, 1, false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        attr_set.store(true, std::memory_order_release);
     }
     if (raw) grouped_kernel<P, D, 1, true, true><<<grid, waves * 64, lds_bytes, s>>>(gp);
     else grouped_kernel<P, D, 1, false, true><<<grid, waves * 64, lds_bytes, s>>>(gp);
@@ -841,14 +814,14 @@ template <int P, int D>
 static hipError_t launch_grouped_pd(const GroupedParams& gp, bool raw, unsigned grid, int waves, size_t lds_bytes, hipStream_t s)
 {
     if (gp.d[0].gparams) return launch_grouped_gq<P, gq_depth(P, D)>(gp, raw, grid, waves, lds_bytes, s);
-    static bool attr_set = false;
-    if (!attr_set) {
+    static std::atomic<bool> attr_set{false};   // (an idempotent call: a lost race only repeats it)
+    if (!attr_set.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute((const void*)grouped_kernel<P, D, 1, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e == hipSuccess) e = hipFuncSetAttribute((const void*)grouped_kernel<P, D, 1, false>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e == hipSuccess) e = hipFuncSetAttribute((const void*)grouped_kernel<P, D, 2, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e == hipSuccess) e = hipFuncSetAttribute((const void*)grouped_kernel<P, D, 2, false>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        attr_set.store(true, std::memory_order_release);
     }
     if (waves >= 4) {
         if (raw) grouped_kernel<P, D, 1, true><<<grid, waves * 64, lds_bytes, s>>>(gp);

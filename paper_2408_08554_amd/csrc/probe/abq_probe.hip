@@ -1,8 +1,10 @@
 // Measurement aids, not part of the method: a plain streaming read and an int8 MFMA issue loop, so that
 // achieved figures can be priced against what this machine delivers for the same kind of work, beside
-// the published peaks (HBM 8 TB/s, dense int8 5 POP/s).  The caller times the launches.
-#include "abq_internal.h"
-#include "../../include/abq.h"
+// the published peaks (HBM 8 TB/s, dense int8 5 POP/s).  The caller times the launches.  A library of its own
+// (libabq_probe.so); status values: 0 ok, -1 null pointer, -3 bad size, -4 misaligned pointer, -7 launch failed.
+#include "../../../include/abq_probe.h"
+
+#include <hip/hip_runtime.h>
 
 namespace abq {
 
@@ -61,9 +63,9 @@ extern "C" {
 
 int abq_probe_stream_read(const void* buf, size_t bytes, void* sink, void* stream)
 {
-    if (!buf || !sink) return ABQ_ERR_NULL;
-    if (bytes < 16 || bytes % 16 != 0) return ABQ_ERR_SHAPE;
-    if (((uintptr_t)buf & 15u) || ((uintptr_t)sink & 15u)) return ABQ_ERR_ALIGN;
+    if (!buf || !sink) return -1;
+    if (bytes < 16 || bytes % 16 != 0) return -3;
+    if (((uintptr_t)buf & 15u) || ((uintptr_t)sink & 15u)) return -4;
     // 256 threads; the most loads per thread (8, 4, 2, 1) that still leaves four workgroups per CU
     constexpr int threads = 256;
     const size_t nvec = bytes / 16;
@@ -71,7 +73,7 @@ int abq_probe_stream_read(const void* buf, size_t bytes, void* sink, void* strea
     while (U > 1 && nvec / ((size_t)threads * U) < 1024) U >>= 1;
     const size_t per_wg = (size_t)threads * U;
     const size_t grid = (nvec + per_wg - 1) / per_wg;
-    if (grid > 0x7fffffffu) return ABQ_ERR_SHAPE;
+    if (grid > 0x7fffffffu) return -3;
     hipStream_t s = (hipStream_t)stream;
     switch (U) {
         case 8: stream_read_kernel<8><<<(unsigned)grid, threads, 0, s>>>((const u4v*)buf, nvec, (uint32_t*)sink); break;
@@ -79,7 +81,7 @@ int abq_probe_stream_read(const void* buf, size_t bytes, void* sink, void* strea
         case 2: stream_read_kernel<2><<<(unsigned)grid, threads, 0, s>>>((const u4v*)buf, nvec, (uint32_t*)sink); break;
         default: stream_read_kernel<1><<<(unsigned)grid, threads, 0, s>>>((const u4v*)buf, nvec, (uint32_t*)sink); break;
     }
-    return hipGetLastError() == hipSuccess ? ABQ_OK : ABQ_ERR_HIP;
+    return hipGetLastError() == hipSuccess ? 0 : -7;
 }
 
 double abq_probe_mfma_i8_ops(int iters)
@@ -92,13 +94,13 @@ double abq_probe_mfma_i8_ops(int iters)
 
 int abq_probe_mfma_i8(int iters, int pattern, void* sink, void* stream)
 {
-    if (!sink) return ABQ_ERR_NULL;
-    if (iters < 1 || iters > (1 << 20) || pattern < 0 || pattern > 1) return ABQ_ERR_SHAPE;
-    if ((uintptr_t)sink & 15u) return ABQ_ERR_ALIGN;
+    if (!sink) return -1;
+    if (iters < 1 || iters > (1 << 20) || pattern < 0 || pattern > 1) return -3;
+    if ((uintptr_t)sink & 15u) return -4;
     int dev = 0, cus = 256;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
     mfma_i8_kernel<<<(unsigned)(cus * kProbeWgsPerCu), kProbeWaves * 64, 0, (hipStream_t)stream>>>(iters, pattern, (uint32_t*)sink);
-    return hipGetLastError() == hipSuccess ? ABQ_OK : ABQ_ERR_HIP;
+    return hipGetLastError() == hipSuccess ? 0 : -7;
 }
 
 }  // extern "C"

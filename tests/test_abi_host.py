@@ -18,6 +18,14 @@ def test_library_exports_every_declared_symbol():
     assert declared == set(B._SIGNATURES), declared ^ set(B._SIGNATURES)
     for name in declared:
         assert getattr(lib, name) is not None
+    # the measurement aids are a library and a header of their own
+    from paper_2408_08554_amd import probe
+    plib = probe.load()
+    pdeclared = set(re.findall(r"\b(abq_[a-z_0-9]+)\s*\(", open(os.path.join(ROOT, "include", "abq_probe.h")).read()))
+    assert pdeclared == set(probe._SIGNATURES) and not (pdeclared & declared)
+    for name in pdeclared:
+        assert getattr(plib, name) is not None
+        assert not hasattr(lib, name), "the product library must not export measurement probes"
     assert lib.abq_version() >= 100
     assert lib.abq_status_string(0) == b"ok"
     for st in range(-7, 0):
@@ -238,7 +246,8 @@ def test_gemm_grouped_rejects_and_workspace_query():
 
 
 def test_probe_rejects():
-    lib = B.load()
+    from paper_2408_08554_amd import probe
+    lib = probe.load()
     assert lib.abq_probe_stream_read(None, 4096, A16, None) == B.ABQ_ERR_NULL
     assert lib.abq_probe_stream_read(A16, 4096, None, None) == B.ABQ_ERR_NULL
     assert lib.abq_probe_stream_read(A16, 8, A16, None) == B.ABQ_ERR_SHAPE
@@ -335,3 +344,35 @@ def test_shipped_plan_table_is_well_formed():
         assert len(shape) == 5 and set(plan) <= set(tune.KNOBS)
         assert {k: v for k, v in B.abq_plan_get(*shape).items() if v} == plan
     B.abq_plan_clear()
+
+
+def test_check_packed_rejects_before_touching_the_device():
+    lib = B.load()
+    F = B.ABQ_LAYOUT_FIELDS
+    big = 1 << 30
+    assert lib.abq_check_packed(0, 4, 64, 512, F, None, big, None) == B.ABQ_ERR_NULL
+    assert lib.abq_check_packed(0, 0, 64, 512, F, A16, big, None) == B.ABQ_ERR_BITS
+    assert lib.abq_check_packed(0, 4, 0, 512, F, A16, big, None) == B.ABQ_ERR_SHAPE
+    assert lib.abq_check_packed(0, 4, 64, 512, 9, A16, big, None) == B.ABQ_ERR_LAYOUT
+    assert lib.abq_check_packed(2, 4, 64, 512, F, A16, big, None) == B.ABQ_ERR_LAYOUT          # unknown kind
+    assert lib.abq_check_packed(1, 4, 64, 512, B.ABQ_LAYOUT_FIELDS_G128, A16, big, None) == B.ABQ_ERR_LAYOUT   # weights-only layout
+    assert lib.abq_check_packed(0, 4, 64, 512, F, A16 + 8, big, None) == B.ABQ_ERR_ALIGN
+    assert lib.abq_check_packed(0, 4, 64, 512, F, A16, lib.abq_packed_weight_bytes(4, 64, 512, F) - 1, None) == B.ABQ_ERR_SIZE
+    assert lib.abq_check_packed(1, 8, 3, 512, F, A16, lib.abq_packed_act_bytes(8, 3, 512, F) - 1, None) == B.ABQ_ERR_SIZE
+
+
+def test_static_entry_point_rejects_before_touching_the_device():
+    lib = B.load()
+    F = B.ABQ_LAYOUT_FIELDS
+
+    def call(p=4, q=8, M=300, N=64, K=512, a=A16, s=A16, z=A16, w=A16, wl=F, y=A16, acc=None):
+        return lib.abq_gemm_act_codes_static(p, q, M, N, K, a, s, z, w, wl, y, acc, None)
+
+    assert call(a=None) == B.ABQ_ERR_NULL
+    assert call(y=None) == B.ABQ_ERR_NULL
+    assert call(p=9) == B.ABQ_ERR_BITS
+    assert call(K=0) == B.ABQ_ERR_SHAPE
+    assert call(wl=9) == B.ABQ_ERR_LAYOUT
+    # 4096 rows of K = 13824 need 54 MiB of packed activations: beyond the static buffer
+    assert lib.abq_gemm_act_codes_workspace_bytes(8, 8, 4096, 5120, 13824, F) > B.ABQ_STATIC_SCRATCH_BYTES
+    assert call(p=8, q=8, M=4096, N=5120, K=13824) == B.ABQ_ERR_SIZE

@@ -544,8 +544,39 @@ def test_graph_replays_match_eager(abq):
             check_against_oracle(c0, y1.cpu().numpy(), None)
 
 
+def test_check_packed_reads_the_blob_header(abq):
+    """abq_check_packed accepts a blob with the geometry it was packed with and names every mismatch."""
+    F, P, G128 = FIELDS, PLANES, abq.ABQ_LAYOUT_FIELDS_G128
+    c = synth.make_case(3, 5, 4, 40, 700, seed=77)
+    pw = abq.abq_pack_weights(3, to_dev(torch, c.W), to_dev(torch, c.w_scale), to_dev(torch, c.w_zero), F)
+    pa = abq.abq_pack_act_codes(5, to_dev(torch, c.A), to_dev(torch, c.a_scale), to_dev(torch, c.a_zero), P)
+    assert abq.abq_check_packed(0, 3, 40, 700, F, pw) == abq.ABQ_OK
+    assert abq.abq_check_packed(1, 5, 4, 700, P, pa) == abq.ABQ_OK
+    big = torch.zeros(1 << 22, dtype=torch.uint8, device="cuda")
+    big[:pw.numel()] = pw
+    for args in [(0, 4, 40, 700, F), (0, 3, 41, 700, F), (0, 3, 40, 701, F), (0, 3, 40, 700, abq.ABQ_LAYOUT_BOTH), (1, 3, 40, 700, F)]:
+        assert abq.abq_check_packed(*args, big) == abq.ABQ_ERR_LAYOUT, args
+    sh, zg = synth.group_quant_params(c)
+    pg = abq.abq_pack_weights_g128(3, to_dev(torch, c.W), to_dev(torch, sh.view(np.float16)), to_dev(torch, zg))
+    assert abq.abq_check_packed(0, 3, 40, 700, G128, pg) == abq.ABQ_OK
+    assert abq.abq_check_packed(0, 3, 40, 700, F, pg) == abq.ABQ_ERR_LAYOUT
+
+
+def test_fused_act_ignores_bits_above_q(abq):
+    """Unpacked codes with bits set above q: the one-kernel call masks them while staging, as the packers do."""
+    c = synth.make_case(4, 5, 3, 100, 2048, seed=78)
+    dirty = (c.A | (np.random.Generator(np.random.PCG64(3)).integers(0, 8, size=c.A.shape, dtype=np.uint8) << 5)).astype(np.uint8)
+    pw = abq.abq_pack_weights(4, to_dev(torch, c.W), to_dev(torch, c.w_scale), to_dev(torch, c.w_zero), FIELDS)
+    assert abq.abq_gemm_act_codes_workspace_bytes(4, 5, 3, 100, 2048, FIELDS) == 0
+    y, acc = abq.abq_gemm_act_codes(4, 5, 3, 100, 2048, to_dev(torch, dirty), to_dev(torch, c.a_scale), to_dev(torch, c.a_zero), pw,
+                                    FIELDS, want_acc=True)
+    torch.cuda.synchronize()
+    check_against_oracle(c, y.cpu().numpy(), acc.cpu().numpy())
+
+
 def test_measurement_probes_run(abq):
-    """The two probe kernels launch, finish and leave their sink alone."""
+    """The two probe kernels (a library of their own, used by the benchmark) launch, finish and leave their sink alone."""
+    from paper_2408_08554_amd import probe as abq   # noqa: F811
     buf = torch.ones(8 << 20, dtype=torch.uint8, device="cuda")
     sink = torch.zeros(4096, dtype=torch.uint8, device="cuda")
     abq.abq_probe_stream_read(buf, buf.numel(), sink)
