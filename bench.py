@@ -345,6 +345,88 @@ def bench_rmsnorm_quant(q, M, K, steps, warmup, check=True):
                          "kernel": "rmsnorm_quant_kernel", "launches": steps}, "steps": steps}
 
 
+def sweep(args):
+    """--sweep: config 5 (every (p, q) x both LLaMA-13B shapes x M in {1, 16, 256, 2048}, or the subset the
+    --sweep-* flags name) as a markdown table, one row per case: parity of the timed buffers against the oracle
+    (sampled outputs: int32 accumulator bit-exact, fp16 within tolerance), then the kernel time from a HIP-graph
+    replay over rotating weight blobs (>= 1 GiB), effective TOPS, packed-weight GB/s and the fraction of the bound
+    that applies (HBM 8 TB/s on algorithmic bytes while M <= 39 p, else dense int8 MFMA 5 POP/s)."""
+    import numpy as np
+    import torch
+    import oracle
+    from paper_2408_08554_amd import binding as abq, metrics, synth
+    layout = abq.ABQ_LAYOUT_PLANES if args.family == "bitserial" else abq.ABQ_LAYOUT_FIELDS
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    ints = lambda v: [int(x) for x in v.split(",")]
+    print("| K | N | M | p | q | parity | us | TOPS | weight GB/s | bound | frac |")
+    print("|---|---|---|---|---|---|---|---|---|---|---|")
+    for shape_idx in ints(args.sweep_shapes):
+        for m_idx in ints(args.sweep_m):
+            for p in ints(args.sweep_p):
+                for q in ints(args.sweep_q):
+                    c = synth.config5(p, q, shape_idx, m_idx)
+                    M, N, K = c.M, c.N, c.K
+                    blob0 = abq.abq_pack_weights(p, dev(c.W), dev(c.w_scale), dev(c.w_zero), layout)
+                    nb = blob0.numel()
+                    stride = (nb + 255) // 256 * 256
+                    R = max(2, -(-int(args.rotate_gib * 2 ** 30) // nb))
+                    pool = torch.empty(R * stride, dtype=torch.uint8, device="cuda")
+                    blobs = [pool[i * stride:i * stride + nb] for i in range(R)]
+                    for b in blobs:
+                        b.copy_(blob0)
+                    a, sc, zp = dev(c.A), dev(c.a_scale), dev(c.a_zero)
+                    pa = abq.abq_pack_act_codes(q, a, sc, zp, layout)
+                    y = torch.empty((M, N), dtype=torch.float16, device="cuda")
+                    acc = torch.empty((M, N), dtype=torch.int32, device="cuda")
+                    fused = args.family != "bitserial" and abq.abq_gemm_act_codes_workspace_bytes(p, q, M, N, K, layout) == 0
+
+                    def call(i, acc_out=None):
+                        if fused:
+                            abq.abq_gemm_act_codes(p, q, M, N, K, a, sc, zp, blobs[i % R], layout, y=y, acc=acc_out)
+                        else:
+                            abq.abq_gemm(p, q, M, N, K, pa, layout, blobs[i % R], layout, y=y, acc=acc_out)
+
+                    rng = np.random.Generator(np.random.PCG64(7))
+                    ms = rng.integers(0, M, 1024).astype(np.int32)
+                    ns = rng.integers(0, N, 1024).astype(np.int32)
+                    ref = oracle.acc_sampled(c.A, c.W, ms, ns)
+                    yref = oracle.acc_centered_sampled(c.A, c.W, c.a_zero, c.w_zero, ms, ns).astype(np.float64) * \
+                        c.a_scale[ms].astype(np.float64) * c.w_scale[ns].astype(np.float64)
+                    ytol = np.maximum(np.maximum(1e-2 * np.abs(yref), 2.0 ** (np.floor(np.log2(np.maximum(np.abs(yref), 2.0 ** -14))) - 9)), 2.0 ** -24)
+                    ok = True
+                    for slot in (0, R - 1):
+                        call(slot, acc)
+                        torch.cuda.synchronize()
+                        ok = ok and np.array_equal(acc.cpu().numpy()[ms, ns].astype(np.int64), ref) and \
+                            bool(np.all(np.abs(y.cpu().numpy()[ms, ns].astype(np.float64) - yref) <= ytol))
+                    launches = max(R, 200 if M <= 16 else (40 if M <= 256 else 12))
+                    stream = torch.cuda.Stream()
+                    with torch.cuda.stream(stream):
+                        graph = torch.cuda.CUDAGraph()
+                        with torch.cuda.graph(graph, stream=stream):
+                            for i in range(launches):
+                                call(i)
+                        graph.replay()
+                        stream.synchronize()
+                        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                        e0.record(stream)
+                        graph.replay()
+                        e1.record(stream)
+                        torch.cuda.synchronize()
+                    t = e0.elapsed_time(e1) * 1e-3 / launches
+                    tops = metrics.effective_tops(M, N, K, t)
+                    if M <= 39 * p:
+                        bound, frac = "hbm", metrics.gemm_algorithmic_bytes(p, q, M, N, K) / t / 1e9 / HBM_PEAK_GBS
+                    else:
+                        bound, frac = "mfma", tops / INT8_MFMA_PEAK_TOPS
+                    print(f"| {K} | {N} | {M} | {p} | {q} | {'ok' if ok else 'FAIL'} | {t * 1e6:.2f} | {tops:.1f} | "
+                          f"{metrics.weight_gbs(p, N, K, t):.0f} | {bound} | {frac:.3f} |", flush=True)
+                    del graph, pool, blobs
+                    torch.cuda.empty_cache()
+                    if not ok:
+                        raise SystemExit(f"parity failure in {c.name}")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -371,6 +453,11 @@ def main():
     ap.add_argument("--no-peaks", dest="peaks", action="store_false", help="skip the measured-peak probes")
     ap.add_argument("--grouped-steps", type=int, default=200,
                     help="launches of the grouped decoder-block leg reported beside the main workload (0 = skip)")
+    ap.add_argument("--sweep", action="store_true", help="config 5 as a parity-checked timing table (see sweep()); not the JSON line")
+    ap.add_argument("--sweep-p", default="1,2,3,4,5,6,7,8")
+    ap.add_argument("--sweep-q", default="1,2,3,4,5,6,7,8")
+    ap.add_argument("--sweep-m", default="0,1,2,3", help="indices into M = 1, 16, 256, 2048")
+    ap.add_argument("--sweep-shapes", default="0,1", help="0: K=5120 N=13824, 1: K=13824 N=5120")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
@@ -386,6 +473,9 @@ def main():
         from paper_2408_08554_amd import tune
         plans_loaded = tune.load_plans() if args.plans == "shipped" else tune.load_plans(args.plans)
 
+    if args.sweep:
+        sweep(args)
+        return
     if args.workload.startswith("block:"):
         # block:p,q,M — the grouped decoder-block launch as the timed workload, printed as its own JSON line
         bp, bq, bm = (int(v) for v in args.workload.split(":")[1].split(","))

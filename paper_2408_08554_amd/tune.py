@@ -7,7 +7,7 @@ that every candidate returns the default plan's result bit for bit (accumulator 
 and reports them fastest first.  `--save` merges the winner into a JSON file when it beats the rule
 by more than `--min-gain`; `load_plans(path)` installs such a file into the running process.
 
-Timing is as in sweep.py: a HIP-graph replay over rotating weight blobs (>= 1 GiB in total).  The timed
+Timing: a HIP-graph replay over rotating weight blobs (>= 1 GiB in total).  The timed
 call is abq_gemm_act_codes where that is one kernel, abq_gemm on packed activations elsewhere.
 """
 import argparse

@@ -603,7 +603,7 @@ def test_config2_w4a8_gemv_full(abq):
     check_against_oracle(c, y, acc)
 
 
-@pytest.mark.parametrize("M", [1, 3, 8])
+@pytest.mark.parametrize("M", [1, 2, 3, 4, 5, 6, 7, 8])
 def test_config3_w2a8_gemv_full(abq, M):
     c = synth.config3(M)
     y, acc = gpu_gemm(torch, abq, c, FIELDS, FIELDS)
@@ -863,5 +863,29 @@ def test_config4_w6a6_gemm_sampled(abq, M):
                                                  (4, 4, 0, 3), (7, 8, 1, 3)])
 def test_config5_sweep_samples(abq, p, q, shape_idx, m_idx):
     c = synth.config5(p, q, shape_idx, m_idx)
+    y, acc = gpu_gemm(torch, abq, c, FIELDS, FIELDS)
+    check_sampled(c, y, acc)
+
+
+# ---- config 5 in full: every (p, q) on both LLaMA-13B shapes ---------------------------------------------------
+@pytest.mark.parametrize("m_idx", [0, 1], ids=["M1", "M16"])
+@pytest.mark.parametrize("shape_idx", [0, 1], ids=["5120to13824", "13824to5120"])
+@pytest.mark.parametrize("p,q", list(itertools.product(range(1, 9), range(1, 9))))
+def test_config5_decode_every_pq(abq, p, q, shape_idx, m_idx):
+    """M = 1 and 16 through abq_gemm_act_codes (the one-kernel decode step), every output element against the oracle."""
+    c = synth.config5(p, q, shape_idx, m_idx)
+    say(c.name)
+    assert abq.abq_gemm_act_codes_workspace_bytes(p, q, c.M, c.N, c.K, FIELDS) == 0
+    y, acc = gpu_gemm_fused(torch, abq, c, FIELDS)
+    check_against_oracle(c, y, acc)
+
+
+@pytest.mark.parametrize("m_idx", [2, 3], ids=["M256", "M2048"])
+@pytest.mark.parametrize("shape_idx", [0, 1], ids=["5120to13824", "13824to5120"])
+@pytest.mark.parametrize("p,q", [(p, p) for p in range(1, 9)] + [(p, 8) for p in range(1, 8)])
+def test_config5_prefill_every_p(abq, p, q, shape_idx, m_idx):
+    """M = 256 and 2048 through abq_pack_act_codes + abq_gemm for every weight width (q = p and q = 8), sampled outputs."""
+    c = synth.config5(p, q, shape_idx, m_idx)
+    say(c.name)
     y, acc = gpu_gemm(torch, abq, c, FIELDS, FIELDS)
     check_sampled(c, y, acc)
