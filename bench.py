@@ -228,11 +228,7 @@ def bench_grouped(p, q, M, steps, warmup, rotate_gib, check=True, g128=False):
                 ns = np.unique(rng.integers(0, c.N, 128))
                 G = (c.K + 127) // 128
                 yref, _, mag = oracle.dequant_grouped(c.A, c.W[ns], c.a_zero, c.a_scale, zg[ns], sh[ns], gs=128, want_mag=True)
-                pad = np.zeros((len(ns), G * 128), dtype=np.int64)
-                pad[:, :c.K] = c.W[ns].astype(np.int64) - np.repeat(zg[ns], 128, axis=1)[:, :c.K]
-                t_abs = np.abs(sh[ns].view(np.float16).astype(np.float64) * pad.reshape(len(ns), G, 128).sum(axis=2)).sum(axis=1)
-                za = np.maximum(np.abs(c.a_zero), np.abs(c.a_zero - 128)).astype(np.float64)
-                size = mag + 2 * np.abs(c.a_scale.astype(np.float64))[:, None] * za[:, None] * t_abs[None, :] + np.abs(yref)
+                size = mag
                 tol = np.maximum(np.maximum(1e-2 * np.abs(yref), 2.0 ** (np.floor(np.log2(np.maximum(np.abs(yref), 2.0 ** -14))) - 9)),
                                  2.0 ** -24) + (G + 12) * 2.0 ** -24 * size
                 assert np.all(np.abs(ys[i].cpu().numpy()[:, ns].astype(np.float64) - yref) <= tol), f"fp16 parity failure in {c.name} (g128)"
@@ -549,11 +545,7 @@ def main():
         G = (K + 127) // 128
         yref, _, mag = oracle.dequant_grouped(c.A[ms], c.W[ns], c.a_zero[ms], c.a_scale[ms], g_zero[ns], g_scale_half[ns],
                                               gs=128, want_mag=True)
-        pad = np.zeros((len(ns), G * 128), dtype=np.int64)
-        pad[:, :K] = c.W[ns].astype(np.int64) - np.repeat(g_zero[ns], 128, axis=1)[:, :K]
-        t_abs = np.abs(g_scale_half[ns].view(np.float16).astype(np.float64) * pad.reshape(len(ns), G, 128).sum(axis=2)).sum(axis=1)
-        za = np.maximum(np.abs(c.a_zero[ms]), np.abs(c.a_zero[ms] - 128)).astype(np.float64)
-        size = mag + 2 * np.abs(c.a_scale[ms].astype(np.float64))[:, None] * za[:, None] * t_abs[None, :] + np.abs(yref)
+        size = mag
         ytol = np.maximum(np.maximum(1e-2 * np.abs(yref), 2.0 ** (np.floor(np.log2(np.maximum(np.abs(yref), 2.0 ** -14))) - 9)),
                           2.0 ** -24) + (G + 12) * 2.0 ** -24 * size
         for slot in (0, R - 1):

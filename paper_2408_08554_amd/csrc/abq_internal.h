@@ -55,8 +55,9 @@ static inline int tuning_env(const char* name)
 //   [group g: uint4 [NT][C_g][64 lanes]] for each group       if FIELDS/BOTH   (NT = ceil(N/16), C_g = b_g*ceil(K/512))
 //   [uint4 [NT][ceil(K/512)][16 channels]]                    if FIELDS_G128: per channel of a tile and super-chunk of 512 k
 //                                                             the four 128-k groups' binary16 scales (8 B), their zero-points
-//                                                             as int8 (zero - 128 when p == 8; 4 B), 4 B unused.  wparams then
-//                                                             holds {0, t[n], 0, 0} with t[n] = sum_g scale*(sum_k (w - zero)).
+//                                                             as int8 (zero - 128 when p == 8; 4 B), 4 B unused.  wparams is
+//                                                             all zero then, and k from K to the end of the last group holds
+//                                                             that group's zero-point instead of 0.
 struct WeightLayout {
     int p, N, K, layout;
     bool has_planes, has_fields, g128;

@@ -59,8 +59,11 @@ __global__ void unpack_planes_kernel(const uint32_t* __restrict__ planes, int bi
 // t = 0..8/b-1 at bit b*t, field t being weight (row nt*16+r, k = c*(512/b) + t*64 + G*16 + 4*j + cc).
 // Masking all four dwords with the mask of field t therefore yields the B operand of one MFMA
 // over the 64 k-values of slice t.  8-bit groups are stored as w - 128 (the MFMA is signed).
+// pad_zero (null for per-channel blobs): per-group zero-points [N][G]; k from K up to the end of the last group of
+// 128 is then filled with that group's zero-point instead of 0, so that (w - zero) vanishes there.
 __global__ void pack_fields_kernel(const uint8_t* __restrict__ w, int N, int K, int b, int shift, int chunks,
-                                   size_t total_dwords, uint32_t* __restrict__ out)
+                                   size_t total_dwords, uint32_t* __restrict__ out, const int32_t* __restrict__ pad_zero = nullptr,
+                                   int ngroups128 = 0)
 {
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= total_dwords) return;
@@ -76,7 +79,9 @@ __global__ void pack_fields_kernel(const uint8_t* __restrict__ w, int N, int K, 
         uint32_t byte = 0;
         for (int t = 0; t < T; ++t) {
             const int k = c * kchunk + t * 64 + G * 16 + 4 * j + cc;
-            uint32_t f = (n < N && k < K) ? ((w[(size_t)n * K + k] >> shift) & fmask) : 0u;
+            uint32_t code = (n < N && k < K) ? w[(size_t)n * K + k] : 0u;
+            if (pad_zero && n < N && k >= K && k < ngroups128 * 128) code = (uint32_t)pad_zero[(size_t)n * ngroups128 + (ngroups128 - 1)];
+            uint32_t f = (code >> shift) & fmask;
             if (b == 8) f ^= 0x80u;
             byte |= f << (b * t);
         }
@@ -142,25 +147,11 @@ __global__ void group_params_kernel(const uint16_t* __restrict__ scale_half, con
     out[idx] = uint4{sh[0] | (sh[1] << 16), sh[2] | (sh[3] << 16), zz, 0u};
 }
 
-// t[n] = sum_g scale[n][g] * sum_{k in group g} (w[n][k] - zero[n][g]): what the activation zero-point multiplies
-// in the epilogue.  One wave per channel, lanes over groups, the sum in double in a fixed butterfly order.
-__global__ void group_tail_kernel(const uint8_t* __restrict__ codes, int bits, int N, int K, int G,
-                                  const uint16_t* __restrict__ scale_half, const int32_t* __restrict__ zero,
-                                  RowParams* __restrict__ out)
+// g128 blobs keep the per-channel parameter area (all zero: every parameter lives in the group records).
+__global__ void zero_params_kernel(RowParams* __restrict__ out, int N)
 {
-    const int row = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-    const int lane = threadIdx.x & 63;
-    if (row >= N) return;
-    const uint32_t mask = (1u << bits) - 1u;
-    double acc = 0.0;
-    for (int g = lane; g < G; g += 64) {
-        const int k_end = min(g * 128 + 128, K), z = zero[(size_t)row * G + g];
-        int32_t s = 0;
-        for (int k = g * 128; k < k_end; ++k) s += (int32_t)(codes[(size_t)row * K + k] & mask) - z;
-        acc += (double)__half2float(__ushort_as_half(scale_half[(size_t)row * G + g])) * (double)s;
-    }
-    for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
-    if (lane == 0) out[row] = RowParams{0, (float)acc, 0, 0};
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < N) out[i] = RowParams{0, 0.0f, 0, 0};
 }
 
 // ---- activation rows: codes (given, or quantized here) -> int8 rows + 1-bit planes ---------------
@@ -432,11 +423,11 @@ hipError_t launch_pack_weights_g128(const WeightLayout& L, const uint8_t* w, con
 {
     const int G = (L.K + 127) / 128, nsuper = (L.K + kSuperK - 1) / kSuperK;
     write_header_kernel<<<1, 64, 0, s>>>((uint32_t*)blob, kMagicW, L.p, L.N, L.K, L.layout);
-    group_tail_kernel<<<blocks_for(L.N, 4), 256, 0, s>>>(w, L.p, L.N, L.K, G, w_scale_half, w_zero, (RowParams*)(blob + L.off_params));
+    zero_params_kernel<<<blocks_for(L.N, 256), 256, 0, s>>>((RowParams*)(blob + L.off_params), L.N);
     for (int g = 0; g < L.ngroups; ++g) {
         const size_t dwords = (size_t)L.NT * L.chunks[g] * 256;
         pack_fields_kernel<<<blocks_for(dwords, 256), 256, 0, s>>>(w, L.N, L.K, L.gb[g], L.gs[g], L.chunks[g], dwords,
-                                                                  (uint32_t*)(blob + L.off_fields[g]));
+                                                                  (uint32_t*)(blob + L.off_fields[g]), w_zero, G);
     }
     const size_t records = (size_t)L.NT * nsuper * 16;
     group_params_kernel<<<blocks_for(records, 256), 256, 0, s>>>(w_scale_half, w_zero, L.N, G, nsuper, L.NT, L.p == 8 ? 128 : 0,

@@ -228,32 +228,49 @@ __device__ __forceinline__ v4i pair_add(const u4v* w, const v4i* aop, v4i acc)
     acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[S0], placed_operand<B, S0 % T, SH>(w[S0 / T]), acc, 0, 0, 0);
     return __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[S1], placed_operand<B, S1 % T, SH>(w[S1 / T]), acc, 0, 0, 0);
 }
-// Group J of the super-chunk.  One accumulator, fresh for this group of 128 k, takes every plane group (fields
-// placed at their bit positions) and then the zero-point: sum_k a' (w' - z) = sum_k a' w' + sum_k a' (-z), the second
-// sum being one more MFMA pair against a B operand whose bytes all hold -z of the lane's channel (p <= 7: -z
-// fits a signed byte).  At p = 8 (z down to -128) the activation sum over the group comes from an MFMA pair against
-// ones instead and the product is subtracted in integers.  Either way the correction is exact and precedes any
-// float, so the large raw products never cancel in floating point.  Then one conversion and one multiply-add per
-// element into the single-precision sum over groups.
+// Group J of the super-chunk: the exact integer sum_k (a' - zc)(w' - z) over its 128 k, then one conversion and one
+// multiply-add per element with the group's scale into the single-precision sum over groups.  a' = a - oa and
+// w' = w - ow are the stored operands, z the group's zero-point less ow, zc the token's zero-point less oa.
+//   c = sum_k a' w' + sum_k a' (-z): every plane group (fields placed at their bit positions) and then one more
+//       MFMA pair against a B operand whose bytes all hold -z of the lane's channel (p <= 7: -z fits a signed byte);
+//   d = sum_k zc w' + sum_k zc (-z): the same B operands against an A operand whose bytes all hold zc of the lane's
+//       row (zc fits a signed byte; -zc would not when zc = -128, hence the second accumulator and c - d).
+// At p = 8 (z down to -128) the z terms come from an MFMA pair against ones and integer multiplies instead:
+//   sum = c - d - z (sum_k a' - 128 zc).
+// Every term is an exact integer before the first float operation, so nothing large cancels in floating point.
+// Padding: k past K holds a' = 0 and w' = z (the packer pads a g128 blob's last group with its zero-point), so
+// padded k add nothing to either accumulator; groups wholly past K carry scale 0.
 template <int P, int J>
-__device__ __forceinline__ void group_step(const u4v* w, const v4i* aop, const u4v gp, v4f& facc)
+__device__ __forceinline__ void group_step(const u4v* w, const v4i* aop, const u4v gp, const v4i& zc_op, const v4i& zc128, v4f& facc)
 {
     using GI = GroupInfo<P>;
-    v4i c{0, 0, 0, 0};
+    v4i c{0, 0, 0, 0}, d{0, 0, 0, 0};
+    const v4i zaop[8] = {zc_op, zc_op, zc_op, zc_op, zc_op, zc_op, zc_op, zc_op};
     c = pair_add<GI::b(0), 0, J>(w + GI::load_base(0), aop, c);
-    if constexpr (GI::NG > 1) c = pair_add<GI::b(1), GI::load_base(1), J>(w + GI::load_base(1), aop, c);
-    if constexpr (GI::NG > 2) c = pair_add<GI::b(2), GI::load_base(2), J>(w + GI::load_base(2), aop, c);
+    d = pair_add<GI::b(0), 0, J>(w + GI::load_base(0), zaop, d);
+    if constexpr (GI::NG > 1) {
+        c = pair_add<GI::b(1), GI::load_base(1), J>(w + GI::load_base(1), aop, c);
+        d = pair_add<GI::b(1), GI::load_base(1), J>(w + GI::load_base(1), zaop, d);
+    }
+    if constexpr (GI::NG > 2) {
+        c = pair_add<GI::b(2), GI::load_base(2), J>(w + GI::load_base(2), aop, c);
+        d = pair_add<GI::b(2), GI::load_base(2), J>(w + GI::load_base(2), zaop, d);
+    }
     const int z = ((int)(gp.z << (24 - 8 * J))) >> 24;
     if constexpr (P < 8) {
         const int zb = (int)(((uint32_t)(-z) & 0xFFu) * 0x01010101u);
         const v4i zop{zb, zb, zb, zb};
         c = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[2 * J], zop, c, 0, 0, 0);
         c = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[2 * J + 1], zop, c, 0, 0, 0);
+        d = __builtin_amdgcn_mfma_i32_16x16x64_i8(zc_op, zop, d, 0, 0, 0);
+        d = __builtin_amdgcn_mfma_i32_16x16x64_i8(zc_op, zop, d, 0, 0, 0);
+        c -= d;
     } else {
         const v4i zero{0, 0, 0, 0}, ones{0x01010101, 0x01010101, 0x01010101, 0x01010101};
         const v4i asum = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[2 * J + 1], ones,
                              __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[2 * J], ones, zero, 0, 0, 0), 0, 0, 0);
-        c = v4i{c.x - __mul24(z, asum.x), c.y - __mul24(z, asum.y), c.z - __mul24(z, asum.z), c.w - __mul24(z, asum.w)};
+        c -= d;
+        c = v4i{c.x - z * (asum.x - zc128.x), c.y - z * (asum.y - zc128.y), c.z - z * (asum.z - zc128.z), c.w - z * (asum.w - zc128.w)};
     }
     const uint32_t sbits = (J < 2 ? gp.x : gp.y) >> (16 * (J & 1));
     const float sc = __half2float(__ushort_as_half((unsigned short)(sbits & 0xFFFFu)));
@@ -263,16 +280,16 @@ __device__ __forceinline__ void group_step(const u4v* w, const v4i* aop, const u
     facc.w = fmaf((float)c.w, sc, facc.w);
 }
 template <int P>
-__device__ __forceinline__ void compute_super_gq(const u4v* w, const uint8_t* lds_row, v4f& facc)
+__device__ __forceinline__ void compute_super_gq(const u4v* w, const uint8_t* lds_row, const v4i& zc_op, const v4i& zc128, v4f& facc)
 {
     v4i aop[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) aop[j] = *reinterpret_cast<const v4i*>(lds_row + j * 64);
     const u4v gp = w[P];
-    group_step<P, 0>(w, aop, gp, facc);
-    group_step<P, 1>(w, aop, gp, facc);
-    group_step<P, 2>(w, aop, gp, facc);
-    group_step<P, 3>(w, aop, gp, facc);
+    group_step<P, 0>(w, aop, gp, zc_op, zc128, facc);
+    group_step<P, 1>(w, aop, gp, zc_op, zc128, facc);
+    group_step<P, 2>(w, aop, gp, zc_op, zc128, facc);
+    group_step<P, 3>(w, aop, gp, zc_op, zc128, facc);
 }
 
 // Per-wave streaming state (lives in registers once everything is inlined).
@@ -294,6 +311,7 @@ struct WaveState {
     int32_t* red;
     v4i acc[GroupInfo<P>::NACC];
     v4f facc;                      // per-group weight parameters: this wave's single-precision sum over its groups
+    v4i zc_op, zc128;              // the same: zero-point less oa of the lane's row of A in every operand byte; 128 times that of the lane's four accumulator rows
 };
 
 // Item order: (K group,) tile, super-chunk.
@@ -367,8 +385,8 @@ __device__ __forceinline__ void finish_tile(const SkinnyParams& prm, WaveState<P
     const int n = tile * kTileN + (st.tid & 15);
     const RowParams pw = st.par[16 + st.ti * 16 + (st.tid & 15)];
     if constexpr (GQ) {
-        // Y = a_scale * (sum over waves and groups - (az - oa) * t[n]), t[n] in pw.scale; the waves' sums are
-        // added in a fixed order.  Any workgroup size: thread t takes elements t, t + blockDim, ...
+        // Y = a_scale * (sum over waves and groups); the waves' sums are added in a fixed order.  Any workgroup
+        // size: thread t takes elements t, t + blockDim, ...
         for (int e = st.tid; e < 256; e += (int)blockDim.x) {
             const int row = 4 * ((e & 63) >> 4) + (e >> 6);
             if (row < st.mt && n < prm.N) {
@@ -377,7 +395,7 @@ __device__ __forceinline__ void finish_tile(const SkinnyParams& prm, WaveState<P
                 for (int ww = 0; ww < 8; ++ww) part[ww] = ww < st.S ? __int_as_float(rb[ww * 256 + e]) : 0.f;
                 const float sum = ((part[0] + part[1]) + (part[2] + part[3])) + ((part[4] + part[5]) + (part[6] + part[7]));
                 const RowParams pa = st.par[row];
-                const float v = pa.scale * (sum - (float)(pa.zero - prm.oa) * pw.scale);
+                const float v = pa.scale * sum;
                 prm.y[(size_t)(st.m0 + row) * prm.N + n] = __half_as_ushort(__float2half_rn(v));
             }
         }
@@ -414,7 +432,7 @@ __device__ __forceinline__ void finish_tile(const SkinnyParams& prm, WaveState<P
 template <int P, int EPT, bool RAW, bool KG, bool REFILL, bool GQ, typename F>
 __device__ __forceinline__ void item_step(const SkinnyParams& prm, WaveState<P>& st, u4v* slot, bool refill, F&& next_group)
 {
-    if constexpr (GQ) compute_super_gq<P>(slot, operand_row<P, KG>(prm, st), st.facc);
+    if constexpr (GQ) compute_super_gq<P>(slot, operand_row<P, KG>(prm, st), st.zc_op, st.zc128, st.facc);
     else compute_super<P>(slot, operand_row<P, KG>(prm, st), st.acc);
     if (REFILL) prefetch_item<P, KG, GQ>(prm, st, slot);
     else if (refill) prefetch_item<P, KG, GQ>(prm, st, slot);
@@ -484,6 +502,17 @@ __device__ __forceinline__ void skinny_body(const SkinnyParams& prm, const int t
         }
     };
     const RowParams par_first = load_par(min(st.tid, npar - 1));
+    if constexpr (GQ) {
+        // zero-points of the rows of A, less oa: of the lane's operand row (lane % 16) and of its four accumulator rows
+        auto zc_of = [&](int row) -> int {
+            const int m = min(st.m0 + row, prm.M - 1);
+            const int z = RAW ? prm.a_zero[m] : prm.aparams[m].zero;
+            return row < mt ? z - prm.oa : 0;
+        };
+        const int zb = (int)(((uint32_t)zc_of(r) & 0xFFu) * 0x01010101u);
+        st.zc_op = v4i{zb, zb, zb, zb};
+        st.zc128 = v4i{128 * zc_of(4 * G), 128 * zc_of(4 * G + 1), 128 * zc_of(4 * G + 2), 128 * zc_of(4 * G + 3)};
+    }
 
     // ---- this wave's part of A: columns of its own super-chunks, in every row (wave-private: only this
     // wave reads what it writes, so no barrier is needed before the first MFMA).  A load instruction
@@ -615,7 +644,7 @@ __device__ __forceinline__ void skinny_body(const SkinnyParams& prm, const int t
     for (int i = 0; i < GI::NACC; ++i) st.acc[i] = v4i{0, 0, 0, 0};
     st.facc = v4f{0.f, 0.f, 0.f, 0.f};
     auto compute = [&](const u4v* slot, const uint8_t* row) {
-        if constexpr (GQ) compute_super_gq<P>(slot, row, st.facc);
+        if constexpr (GQ) compute_super_gq<P>(slot, row, st.zc_op, st.zc128, st.facc);
         else compute_super<P>(slot, row, st.acc);
     };
 
