@@ -255,11 +255,14 @@ int abq_gemm_act_codes_static(int p, int q, int M, int N, int K,
  *   tiled_ntw       16-channel tiles of W per wave: 1, 2 or 4
  *   tiled_wd        operand steps in flight: 2 or 4 (4 exists for tiled_mt = 4 with tiled_ntw <= 2)
  *   tiled_band      row blocks of A per band of the tile order: >= 1
+ *   direct_r        decode kernel for M <= 16: -1 the streaming kernel (A staged in LDS, load ring); 1, 2 or 4 the
+ *                   direct kernel (A operand loaded into registers) with that many 512-k blocks per wave
  * abq_plan_set: plan == NULL removes the entry.  ABQ_ERR_BITS / ABQ_ERR_SHAPE as abq_gemm; ABQ_ERR_LAYOUT for a
  * value outside the lists above.  abq_plan_get fills *out (all zero when there is no entry). */
 typedef struct abq_plan {
     int skinny_waves, skinny_kgroups;
     int tiled_mt, tiled_ntw, tiled_wd, tiled_band;
+    int direct_r;
 } abq_plan;
 int  abq_plan_set(int p, int q, int M, int N, int K, const abq_plan* plan);
 int  abq_plan_get(int p, int q, int M, int N, int K, abq_plan* out);

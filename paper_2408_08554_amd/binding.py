@@ -285,7 +285,7 @@ def abq_gemm_grouped(p, q, M, problems, a_layout, w_layout, workspace=None):
 
 class AbqPlan(_c.Structure):
     """struct abq_plan of include/abq.h (0 = keep the library's rule for that knob)."""
-    _fields_ = [(n, _c.c_int) for n in ("skinny_waves", "skinny_kgroups", "tiled_mt", "tiled_ntw", "tiled_wd", "tiled_band")]
+    _fields_ = [(n, _c.c_int) for n in ("skinny_waves", "skinny_kgroups", "tiled_mt", "tiled_ntw", "tiled_wd", "tiled_band", "direct_r")]
 
 
 def abq_plan_set(p, q, M, N, K, plan=None, **knobs):

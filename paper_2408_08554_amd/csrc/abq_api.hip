@@ -107,7 +107,7 @@ static std::atomic<int> g_plan_count{0};   // launches skip the lock while the t
 
 bool lookup_plan(int p, int q, int M, int N, int K, PlanOverride* out)
 {
-    *out = PlanOverride{0, 0, 0, 0, 0, 0};
+    *out = PlanOverride{0, 0, 0, 0, 0, 0, 0};
     if (g_plan_count.load(std::memory_order_relaxed) == 0) return false;
     std::lock_guard<std::mutex> lock(g_plan_mutex);
     auto it = g_plans.find({p, q, M, N, K});
@@ -363,6 +363,40 @@ static bool streaming_shape(int M, int N)
     return M <= max_m && tiled_wgs < max_wgs;
 }
 
+// The two decode kernels (both on field-packed operands, M <= 16).  The direct kernel (A operand loaded straight into
+// registers, every load of a wave up front, no ring) is ahead while its operand loads stay few against the weight
+// loads; the streaming kernel (A staged in LDS once per workgroup and shared by all the tiles it walks) is ahead for
+// many rows of A over a long stream.  Measured on LLaMA-7B/13B shapes (W2/W4/W8, M = 1..16):
+//   M <= 4: direct everywhere (W4A8 M = 4 5120 -> 13824: 8.5 vs 11.0 us);
+//   streams up to 16 MiB: direct for every M <= 16 (W4A8 4096^2 M = 16: 4.9 vs 6.2 us; W2A8 M = 8 11008 -> 4096: 6.1 vs 7.9);
+//   M <= 8 with p <= 4 and K <= 8192: direct (W4A8 M = 8 5120 -> 13824: 10.3 vs 10.5 us);
+//   otherwise streaming (W4A8 M = 16 5120 -> 13824: 15.8 vs 12.3 us; W8A8 M = 8: 15.5 vs 13.3).
+// A plan-table entry can force either (direct_r = -1: streaming; 1, 2, 4: direct with that many super-chunks per wave).
+static bool direct_by_rule(int p, int M, int nsuper, const WeightLayout& W)
+{
+    if (M <= 4) return true;
+    const size_t stream = (size_t)p * W.NT * kTileN * (size_t)nsuper * kSuperK / 8;
+    if (stream <= ((size_t)16 << 20)) return true;
+    return M <= 8 && p <= 4 && nsuper <= 16;
+}
+static bool choose_direct(const GemmArgs& g, const ActLayout& A, const WeightLayout& W, DirectPlan* pl)
+{
+    if (g.M > 16 || W.g128 || !W.has_fields) return false;
+    PlanOverride ov;
+    lookup_plan(g.p, g.q, g.M, g.N, g.K, &ov);
+    const int env = tuning_env("ABQ_DIRECT_R");
+    const int forced = ov.direct_r != 0 ? ov.direct_r : env;
+    if (forced < 0) return false;
+    if (forced == 0 && !direct_by_rule(g.p, g.M, A.Kp / kSuperK, W)) return false;
+    return direct_plan(g.p, g.M, A.Kp / kSuperK, forced, pl);
+}
+static hipError_t launch_decode(const GemmArgs& g, const ActLayout& A, const WeightLayout& W, hipStream_t s)
+{
+    DirectPlan pl;
+    if (choose_direct(g, A, W, &pl)) return launch_gemm_direct(g, A, W, pl, s);
+    return launch_gemm_skinny(g, A, W, s);
+}
+
 int abq_plan_set(int p, int q, int M, int N, int K, const abq_plan* plan)
 {
     if (int e = check_gemm_shape(p, q, M, N, K)) return e;
@@ -371,10 +405,12 @@ int abq_plan_set(int p, int q, int M, int N, int K, const abq_plan* plan)
         g_plans.erase({p, q, M, N, K});
     } else {
         const int w = plan->skinny_waves, g = plan->skinny_kgroups, mt = plan->tiled_mt, nt = plan->tiled_ntw, wd = plan->tiled_wd;
+        const int dr = plan->direct_r;
         const bool ok = (w == 0 || w == 1 || w == 2 || (w >= 4 && w <= 8)) && g >= 0 && g <= 4 && (mt == 0 || mt == 4 || mt == 8) &&
-                        (nt == 0 || nt == 1 || nt == 2 || nt == 4) && (wd == 0 || wd == 2 || wd == 4) && plan->tiled_band >= 0;
+                        (nt == 0 || nt == 1 || nt == 2 || nt == 4) && (wd == 0 || wd == 2 || wd == 4) && plan->tiled_band >= 0 &&
+                        (dr == -1 || dr == 0 || dr == 1 || dr == 2 || dr == 4);
         if (!ok) return ABQ_ERR_LAYOUT;
-        g_plans[{p, q, M, N, K}] = PlanOverride{w, g, mt, nt, wd, plan->tiled_band};
+        g_plans[{p, q, M, N, K}] = PlanOverride{w, g, mt, nt, wd, plan->tiled_band, dr};
     }
     g_plan_count.store((int)g_plans.size(), std::memory_order_relaxed);
     return ABQ_OK;
@@ -386,7 +422,7 @@ int abq_plan_get(int p, int q, int M, int N, int K, abq_plan* out)
     if (int e = check_gemm_shape(p, q, M, N, K)) return e;
     PlanOverride o;
     lookup_plan(p, q, M, N, K, &o);
-    *out = abq_plan{o.skinny_waves, o.skinny_kgroups, o.tiled_mt, o.tiled_ntw, o.tiled_wd, o.tiled_band};
+    *out = abq_plan{o.skinny_waves, o.skinny_kgroups, o.tiled_mt, o.tiled_ntw, o.tiled_wd, o.tiled_band, o.direct_r};
     return ABQ_OK;
 }
 
@@ -428,7 +464,7 @@ int abq_gemm(int p, int q, int M, int N, int K, const void* packed_act, int a_la
     hipStream_t s = (hipStream_t)stream;
     if (W.g128) return hip_status(launch_gemm_skinny(g, A, W, s));   // every M: one pass over W per 16 rows
     if (!choose_fields(can_fields, can_planes, force, p, q, M, N)) return hip_status(launch_gemm_bitserial(g, A, W, s));
-    if (streaming_shape(M, N)) return hip_status(launch_gemm_skinny(g, A, W, s));
+    if (streaming_shape(M, N)) return hip_status(launch_decode(g, A, W, s));
     return hip_status(launch_gemm_tiled(g, A, W, s));
 }
 
@@ -474,7 +510,7 @@ int abq_gemm_act_codes(int p, int q, int M, int N, int K, const uint8_t* a_codes
         ActLayout A;
         if (!make_act_layout(q, M, K, ABQ_LAYOUT_FIELDS, &A)) return ABQ_ERR_LAYOUT;
         GemmArgs g{p, q, M, N, K, nullptr, a_codes, a_scale, a_zero, (const uint8_t*)packed_w, y_fp16, acc_i32, nullptr, 0};
-        return hip_status(launch_gemm_skinny(g, A, W, s));
+        return hip_status(launch_decode(g, A, W, s));
     }
     // Otherwise the two steps run back to back, the packed activations living in the caller's workspace.
     const int act_layout = W.g128 ? ABQ_LAYOUT_FIELDS : base_layout;
@@ -577,6 +613,11 @@ int abq_gemm_grouped(int p, int q, int M, int count, const abq_problem* host_pro
     if (int e = prepare_group(p, q, M, count, host_problems, a_layout, w_layout, args.data(), A.data(), W.data(), &raw, &fits, &waves, &lds))
         return e;
     if (misaligned(workspace)) return ABQ_ERR_ALIGN;
+    // grouped: the direct kernel for up to eight rows of A below p = 8 (measured on the LLaMA-7B block: W4A8 M = 1 19.6 vs
+    // 22.0 us, W2A8 13.9 vs 17.9, W4A8 M = 8 26.0 vs 25.1; at p = 8 its two launches, one per length of K, cost more than
+    // they gain: 34.8 vs 33.3 us)
+    if (fits && M <= 8 && p < 8 && tuning_env("ABQ_DIRECT_R") >= 0 && gemm_direct_grouped_fits(p, M, count, args.data(), A.data(), W.data()))
+        return hip_status(launch_gemm_direct_grouped(p, q, M, count, args.data(), A.data(), W.data(), (hipStream_t)stream));
     if (fits) return hip_status(launch_gemm_grouped(p, M, count, args.data(), A.data(), W.data(), waves, lds, (hipStream_t)stream));
     if (raw) {   // every problem's workspace need is checked before the first launch
         size_t need = 0;

@@ -1,0 +1,386 @@
+// Device code of the direct decode kernel and the templates that launch its variants.  Included by the host-side
+// translation unit (abq_direct.hip) for the argument structures and by one translation unit per pair of weight
+// widths (abq_direct_p12.hip ...), which hold the kernel instantiations, so that they compile in parallel.
+//
+// Decode-shaped matmul for few rows of A (M = 1 .. 16, built for M = 1 .. 8): the GEMV of Sec. 3.4 ("GEMV
+// elimination" / Table 4: a decode step is bound by the weight stream).  Nothing but the packed weights moves in
+// volume: they go HBM -> registers with 128-bit non-temporal loads, all of a wave's loads issued before its first
+// multiply, and the activation operand is loaded straight into the MFMA's register layout — no LDS staging, no
+// load ring, no loop.
+//
+// The A operand of the 16x16x64 int8 MFMA holds 16 rows.  With MR = 1, 2, 4, 8 or 16 rows of A in use (M <= MR)
+// the operand rows are filled with SL = 16/MR different 64-k slices of those rows (at most four for p >= 5, whose
+// wider streams leave fewer registers for the accumulators that every slice of a set needs): operand row i*MR + m
+// is row m of A over slice i of a set of SL consecutive slices, so one 16-byte load per lane serves SL slices.  An MFMA of that operand against the weights of slice i yields the
+// wanted products in rows i*MR .. i*MR+MR-1 of the accumulator and unrelated ones elsewhere; slices with the same
+// i (and, for field-packed weights, the same field position) share an accumulator, and after the last MFMA the
+// rows that belong to each accumulator are picked out (one select chain per lane) and summed.  Bit reduction
+// (Sec. 3.4 step 5 / Appendix B) happens in registers as in the streaming kernel: the activation side carries all q
+// planes as the int8 code, the weight side one plane group per accumulator set, recombined with shifts.
+//
+// Work decomposition: one workgroup per 16-channel tile of W; its S waves split K in runs of super-chunks (512 k).
+// The S partial tiles meet in LDS (one barrier) and 16*M threads apply the fused dequant epilogue (Fig. 3b).
+// A grouped launch is the same grid over the tiles of several problems.
+#pragma once
+#include "abq_internal.h"
+#include "../../include/abq.h"
+
+#include <hip/hip_fp16.h>
+
+namespace abq {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef unsigned int u4v __attribute__((ext_vector_type(4)));
+
+constexpr int kDirectMaxGroup = 8;
+
+struct DirectProblem {
+    const u4v* fields[3];      // per plane group
+    const int8_t* a_codes;     // [M][Kp] packed activations (code less oa), or null with a_raw
+    const RowParams* aparams;
+    const uint8_t* a_raw;      // [M][K] unpacked codes with a_scale / a_zero (activation pack fused in), K a multiple of 16
+    const float* a_scale;
+    const int32_t* a_zero;
+    const RowParams* wparams;
+    uint16_t* y;
+    int32_t* acc;              // may be null
+    int N, K, Kp, nsuper;
+    int rsplit;                // super-chunks per wave (<= R): wave w owns [w*rsplit, w*rsplit + rsplit) clipped to nsuper
+};
+
+struct DirectParams {
+    int count;                              // problems in this launch
+    int first_tile[kDirectMaxGroup + 1];    // where each problem's tiles start in the grid
+    int M, oa, ow;
+    uint32_t a_mask;                        // (2^q - 1) in every byte (unpacked codes are masked to q bits)
+    DirectProblem d[kDirectMaxGroup];
+};
+
+constexpr int dmax(int a, int b) { return a > b ? a : b; }
+constexpr int dmin(int a, int b) { return a < b ? a : b; }
+
+// Fewest operand rows per slice set for weight width p (every width takes a single row).
+__host__ __device__ constexpr int direct_min_rows(int p) { return p >= 1 ? 1 : 1; }
+
+// Field t of a b-bit group as a signed-byte MFMA operand dword, and the shift that undoes its scale (as in the
+// streaming kernel: the field that would touch the byte's sign bit is taken one bit lower, or as weight -128).
+template <int B, int T>
+__device__ __forceinline__ uint32_t dfield_bytes(uint32_t x)
+{
+    if constexpr (B == 8) return x;
+    else if constexpr (B == 4) return T == 0 ? (x & 0x0F0F0F0Fu) : ((x >> 1) & 0x78787878u);
+    else if constexpr (B == 2) return T == 3 ? ((x >> 1) & 0x60606060u) : (x & (0x03030303u << (2 * T)));
+    else return x & (0x01010101u << T);
+}
+template <int B, int T>
+__device__ __forceinline__ int32_t dfield_unscale(int32_t acc)
+{
+    if constexpr (B == 8) return acc;
+    else if constexpr (B == 4) return T == 0 ? acc : (acc >> 3);
+    else if constexpr (B == 2) return T == 3 ? (acc >> 5) : (acc >> (2 * T));
+    else return T == 7 ? -(acc >> 7) : (acc >> T);
+}
+template <int B, int T>
+__device__ __forceinline__ v4i dfield_operand(const u4v& w)
+{
+    return v4i{(int)dfield_bytes<B, T>(w.x), (int)dfield_bytes<B, T>(w.y), (int)dfield_bytes<B, T>(w.z), (int)dfield_bytes<B, T>(w.w)};
+}
+
+// Compile-time shape of one variant.
+template <int P, int MR, int R>
+struct DirectShape {
+    static constexpr int NG = group_count(P);
+    static constexpr int SL = dmin(16 / MR, P <= 4 ? 16 : 4);   // slices per A operand quad (operand rows past SL*MR stay zero)
+    static constexpr int NSL = 8 * R;                     // slices per wave
+    static constexpr int NQ = (NSL + SL - 1) / SL;        // A operand quads per wave
+    static constexpr int NI = dmin(SL, NSL);              // slice sets in use
+    __host__ __device__ static constexpr int b(int g) { return group_width(P, g); }
+    __host__ __device__ static constexpr int t(int g) { return 8 / group_width(P, g); }
+    __host__ __device__ static constexpr int na(int g) { return dmax(NI, t(g)); }                       // accumulators of group g
+    __host__ __device__ static constexpr int acc_base(int g) { return g == 0 ? 0 : (g == 1 ? na(0) : na(0) + na(1)); }
+    static constexpr int NACC = acc_base(NG - 1) + na(NG - 1);
+    __host__ __device__ static constexpr int load_base(int g) { return group_shift(P, g); }            // 1 KiB loads below group g in a super-chunk
+};
+
+// All MFMAs of one super-chunk (index RR of the wave's run) for plane group GI: chunk c holds slices c*T .. c*T+T-1.
+template <int P, int MR, int R, int RR, int GI, int C = 0, int T0 = 0>
+__device__ __forceinline__ void direct_group_mfma(const u4v* w, const v4i* aq, v4i* acc)
+{
+    using SH = DirectShape<P, MR, R>;
+    constexpr int B = SH::b(GI), T = SH::t(GI);
+    if constexpr (C < B) {
+        constexpr int s = RR * 8 + C * T + T0;            // slice inside the wave's run
+        v4i& a = acc[SH::acc_base(GI) + s % SH::na(GI)];
+        a = __builtin_amdgcn_mfma_i32_16x16x64_i8(aq[s / SH::SL], dfield_operand<B, T0>(w[SH::load_base(GI) + C]), a, 0, 0, 0);
+        if constexpr (T0 + 1 < T) direct_group_mfma<P, MR, R, RR, GI, C, T0 + 1>(w, aq, acc);
+        else direct_group_mfma<P, MR, R, RR, GI, C + 1, 0>(w, aq, acc);
+    }
+}
+
+// Every super-chunk of the wave's run (RR < nsc, wave-uniform) and every plane group.
+template <int P, int MR, int R, int RR = 0>
+__device__ __forceinline__ void direct_all_mfma(const u4v (*w)[P], const v4i* aq, v4i* acc, int nsc)
+{
+    using SH = DirectShape<P, MR, R>;
+    if constexpr (RR < R) {
+        if (RR < nsc) {
+            direct_group_mfma<P, MR, R, RR, 0>(w[RR], aq, acc);
+            if constexpr (SH::NG > 1) direct_group_mfma<P, MR, R, RR, 1>(w[RR], aq, acc);
+            if constexpr (SH::NG > 2) direct_group_mfma<P, MR, R, RR, 2>(w[RR], aq, acc);
+        }
+        direct_all_mfma<P, MR, R, RR + 1>(w, aq, acc, nsc);
+    }
+}
+
+// accI[i] += (sum of group GI's accumulators of slice set i, each unscaled by its field position) << shift of the group
+template <int P, int MR, int R, int GI, int A = 0>
+__device__ __forceinline__ void direct_fold(const v4i* acc, v4i* accI)
+{
+    using SH = DirectShape<P, MR, R>;
+    constexpr int B = SH::b(GI), T = SH::t(GI);
+    if constexpr (A < SH::na(GI)) {
+        const v4i& a = acc[SH::acc_base(GI) + A];
+        constexpr int sh = group_shift(P, GI);
+        accI[A % SH::NI] += v4i{dfield_unscale<B, A % T>(a.x) << sh, dfield_unscale<B, A % T>(a.y) << sh, dfield_unscale<B, A % T>(a.z) << sh,
+                                dfield_unscale<B, A % T>(a.w) << sh};
+        direct_fold<P, MR, R, GI, A + 1>(acc, accI);
+    }
+}
+
+// Lane (G, reg) of an accumulator holds operand row 4G + reg = slice set (4G+reg)/MR, row (4G+reg) % MR of A.  Picks
+// this lane's element of the accumulator of its slice set, then folds the registers that hold the same row of A
+// (MR = 1: all four; MR = 2: pairs).  Returns the number of values left in v[].
+template <int MR, int NI>
+__device__ __forceinline__ void direct_pick(const v4i* accI, int G, int32_t* v)
+{
+#pragma unroll
+    for (int reg = 0; reg < 4; ++reg) {
+        int32_t val = 0;
+        if constexpr (MR >= 4) {
+            // (4G + reg) / MR does not depend on reg
+#pragma unroll
+            for (int i = 0; i < NI; ++i) val = (4 * G / MR == i) ? accI[i][reg] : val;
+        } else {
+#pragma unroll
+            for (int i = 0; i < NI; ++i) val = ((4 * G + reg) / MR == i) ? accI[i][reg] : val;
+        }
+        v[reg] = val;
+    }
+    if constexpr (MR == 1) v[0] = (v[0] + v[1]) + (v[2] + v[3]);
+    else if constexpr (MR == 2) { v[0] += v[2]; v[1] += v[3]; }
+}
+
+// R = super-chunks per wave at most (all loaded before the first MFMA); RAW: the activation BitPacking step is fused
+// in (Fig. 3b packs activations online; Sec. 3.4 folds that cost into existing operators): A arrives as unpacked
+// codes, is masked to q bits and offset to signed bytes in registers, and its row sums for the zero-point correction
+// come from one more MFMA per operand quad against a B operand of ones.
+// GROUPED: several problems in one grid (the workgroup finds its problem from the tile starts); otherwise problem 0.
+// Either way the problem's descriptor is copied from the kernel arguments in one batch of scalar loads at the top:
+// read field by field where it is used, every first use would wait for a scalar load of its own.
+template <int P, int MR, int R, bool RAW, bool GROUPED>
+__global__ __launch_bounds__(1024) void direct_kernel(DirectParams gp)
+{
+    using SH = DirectShape<P, MR, R>;
+    constexpr int SL = SH::SL, NQ = SH::NQ, NI = SH::NI;
+    constexpr int NV = MR == 1 ? 1 : (MR == 2 ? 2 : 4);             // values per lane after direct_pick
+    constexpr int C = MR <= 4 ? 4 : (MR == 8 ? 2 : 1);              // lane groups G that hold partials of the same (row, channel)
+    extern __shared__ __align__(16) int32_t red[];                   // [S][MR][16][C] partial sums, then [S][MR][C] partial row sums of A
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int r = lane & 15, G = lane >> 4;
+    int g = 0, tile = (int)blockIdx.x;
+    if constexpr (GROUPED) {   // (slots past count start at the end of the grid)
+#pragma unroll
+        for (int i = 1; i < kDirectMaxGroup; ++i) g = (int)blockIdx.x >= gp.first_tile[i] ? i : g;
+        tile -= gp.first_tile[g];
+    }
+    const DirectProblem pr = gp.d[g];
+    // (pins the pointers in scalar registers here, so that the compiler fetches them with the sizes above in one
+    // batch instead of sinking each load next to its first use behind a branch)
+    const int S = (int)blockDim.x >> 6;
+    asm volatile("" ::"s"(pr.fields[0]), "s"(pr.fields[1]), "s"(pr.fields[2]), "s"(pr.wparams), "s"(pr.y), "s"(pr.acc), "s"(pr.N), "s"(pr.K),
+                 "s"(gp.oa), "s"(gp.ow), "s"(gp.a_mask), "s"(S));
+    if constexpr (RAW) asm volatile("" ::"s"(pr.a_raw), "s"(pr.a_scale), "s"(pr.a_zero));
+    else asm volatile("" ::"s"(pr.a_codes), "s"(pr.aparams));
+    const int M = gp.M, nsuper = pr.nsuper, Kp = pr.Kp;
+    const int sc0 = wave * pr.rsplit;
+    const int nsc = max(0, min(pr.rsplit, nsuper - sc0));            // this wave's super-chunks (<= R), wave-uniform
+
+    // ---- epilogue parameters of the first 16*M outputs' threads (requested first: cold lines of the blob, used after the barrier)
+    const int t0 = (int)threadIdx.x;
+    RowParams pa0{0, 0.f, 0, 0}, pw0{0, 0.f, 0, 0};
+    if (t0 < 16 * M) {
+        const int m = t0 >> 4;
+        if constexpr (RAW) pa0 = RowParams{0, pr.a_scale[m], pr.a_zero[m], 0};
+        else pa0 = pr.aparams[m];
+        pw0 = pr.wparams[min(tile * kTileN + (t0 & 15), pr.N - 1)];
+    }
+
+    // ---- the A operand quads: lane (r, G) holds row r % MR of A over 16 k of slice q*SL + r/MR of the wave's run
+    v4i aq[NQ];
+    const int m_l = r % MR, i_l = r / MR;                            // (i_l >= SL: an operand row that stays zero)
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+        const int sl = i_l < SL ? q * SL + i_l : 8 * R;
+        const int k = (sc0 * 8 + sl) * 64 + G * 16;
+        v4i v{0, 0, 0, 0};
+        if constexpr (RAW) {   // (masked and offset further down, behind the last load of this prologue: nothing waits in between)
+            if (m_l < M && sl < 8 * nsc && k < pr.K) v = *reinterpret_cast<const v4i*>(pr.a_raw + (size_t)m_l * pr.K + k);
+        } else {
+            if (m_l < M && sl < 8 * nsc) v = *reinterpret_cast<const v4i*>(pr.a_codes + (size_t)m_l * Kp + k);
+        }
+        aq[q] = v;
+    }
+    // ---- the weight stream, last in program order: everything above can be waited for while it is in flight.  The
+    // loads are unconditional (a wave with fewer than R super-chunks re-reads its last one, or the problem's last one
+    // when it has none: lines another wave of the tile fetches anyway) so that the wait counts in front of them are exact.
+    u4v w[R][P];
+#pragma unroll
+    for (int rr = 0; rr < R; ++rr) {
+        const int sc = min(sc0 + rr, nsuper - 1);
+#pragma unroll
+        for (int gi = 0; gi < SH::NG; ++gi) {
+            const int b = SH::b(gi);
+            const u4v* base = pr.fields[gi] + ((size_t)tile * nsuper + sc) * (b * 64) + lane;
+#pragma unroll
+            for (int i = 0; i < b; ++i) w[rr][SH::load_base(gi) + i] = __builtin_nontemporal_load(base + i * 64);
+        }
+    }
+    if constexpr (RAW) {
+        // unpacked codes -> operand bytes: bits above q dropped (as the packers drop them), less oa; positions that were
+        // not loaded (rows past M, k past K) become -oa here and are cleared again
+        const uint32_t flip = gp.oa ? 0x80808080u : 0u;
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) {
+            const int sl = i_l < SL ? q * SL + i_l : 8 * R;
+            const bool live = m_l < M && sl < 8 * nsc && (sc0 * 8 + sl) * 64 + G * 16 < pr.K;
+            const v4i c = aq[q];
+            aq[q] = live ? v4i{(int)(((uint32_t)c.x & gp.a_mask) ^ flip), (int)(((uint32_t)c.y & gp.a_mask) ^ flip),
+                               (int)(((uint32_t)c.z & gp.a_mask) ^ flip), (int)(((uint32_t)c.w & gp.a_mask) ^ flip)}
+                         : v4i{0, 0, 0, 0};
+        }
+    }
+
+    v4i asum_acc{0, 0, 0, 0};
+    if constexpr (RAW) {   // row sums of the operand bytes, while the weights are still on their way
+        const v4i ones{0x01010101, 0x01010101, 0x01010101, 0x01010101};
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) asum_acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(aq[q], ones, asum_acc, 0, 0, 0);
+    }
+
+    // ---- multiply
+    v4i acc[SH::NACC];
+#pragma unroll
+    for (int i = 0; i < SH::NACC; ++i) acc[i] = v4i{0, 0, 0, 0};
+    direct_all_mfma<P, MR, R>(w, aq, acc, nsc);
+
+    // ---- bit reduction over fields and plane groups, then the rows that belong to each accumulator
+    v4i accI[NI];
+#pragma unroll
+    for (int i = 0; i < NI; ++i) accI[i] = v4i{0, 0, 0, 0};
+    direct_fold<P, MR, R, 0>(acc, accI);
+    if constexpr (SH::NG > 1) direct_fold<P, MR, R, 1>(acc, accI);
+    if constexpr (SH::NG > 2) direct_fold<P, MR, R, 2>(acc, accI);
+    int32_t v[4];
+    direct_pick<MR, NI>(accI, G, v);
+    // lane (G, r): v[i] is a partial sum for row m of A and channel r of the tile, m = i (MR <= 4), 4*(G&1)+i (MR = 8),
+    // 4*G+i (MR = 16); C lane groups hold partials of the same element: red[((wave*MR + m)*16 + r)*C + c]
+    const int c_l = MR <= 4 ? G : (MR == 8 ? (G >> 1) : 0);
+    const int m_base = MR <= 4 ? 0 : (MR == 8 ? 4 * (G & 1) : 4 * G);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) red[((wave * MR + m_base + i) * 16 + r) * C + c_l] = v[i];
+    int32_t* reda = red + S * MR * 16 * C;
+    if constexpr (RAW) {
+        // every row of asum_acc holds the sum of its operand row over the wave's quads, the same in all 16 columns
+        int32_t s4[4] = {asum_acc.x, asum_acc.y, asum_acc.z, asum_acc.w};
+        if constexpr (MR == 1) s4[0] = (s4[0] + s4[1]) + (s4[2] + s4[3]);
+        else if constexpr (MR == 2) { s4[0] += s4[2]; s4[1] += s4[3]; }
+        if (r == 0) {
+#pragma unroll
+            for (int i = 0; i < NV; ++i) reda[(wave * MR + m_base + i) * C + c_l] = s4[i];
+        }
+    }
+    __syncthreads();
+
+    // ---- sum over waves (and lane groups), fused dequant epilogue
+    for (int t = t0; t < 16 * M; t += (int)blockDim.x) {
+        const int m = t >> 4, nl = t & 15, n = tile * kTileN + nl;
+        int32_t sum = 0;
+        for (int ww = 0; ww < S; ++ww) {
+            const int32_t* p = red + ((ww * MR + m) * 16 + nl) * C;
+            if constexpr (C == 4) { const v4i x = *reinterpret_cast<const v4i*>(p); sum += (x.x + x.y) + (x.z + x.w); }
+            else if constexpr (C == 2) sum += p[0] + p[1];
+            else sum += p[0];
+        }
+        RowParams pa = pa0, pw = pw0;
+        if (t != t0) {   // (more outputs than threads: M > 4 with fewer than four waves)
+            if constexpr (RAW) pa = RowParams{0, pr.a_scale[m], pr.a_zero[m], 0};
+            else pa = pr.aparams[m];
+            pw = pr.wparams[min(n, pr.N - 1)];
+        }
+        if constexpr (RAW) {
+            int32_t as = 0;
+            for (int ww = 0; ww < S; ++ww) {
+                const int32_t* p = reda + (ww * MR + m) * C;
+                if constexpr (C == 4) { const v4i x = *reinterpret_cast<const v4i*>(p); as += (x.x + x.y) + (x.z + x.w); }
+                else if constexpr (C == 2) as += p[0] + p[1];
+                else as += p[0];
+            }
+            pa.sum = as + gp.oa * pr.K;   // the operand bytes are the codes less oa; padding holds zero bytes
+        }
+        if (n < pr.N) epilogue_store(sum, gp.oa, gp.ow, pr.K, pa, pw, (size_t)m * pr.N + n, pr.y, pr.acc);
+    }
+}
+
+inline size_t direct_lds_bytes(int S, int MR)
+{
+    const int C = MR <= 4 ? 4 : (MR == 8 ? 2 : 1);
+    return (size_t)S * MR * 16 * C * 4 + (size_t)S * MR * C * 4;
+}
+
+template <int P, int MR, int R, bool RAW>
+static hipError_t direct_launch_one(const DirectParams& gp, unsigned grid, int waves, hipStream_t s)
+{
+    if (gp.count > 1) direct_kernel<P, MR, R, RAW, true><<<grid, waves * 64, direct_lds_bytes(waves, MR), s>>>(gp);
+    else direct_kernel<P, MR, R, RAW, false><<<grid, waves * 64, direct_lds_bytes(waves, MR), s>>>(gp);
+    return hipGetLastError();
+}
+
+template <int P, int MR, int R>
+static hipError_t direct_launch_r(const DirectParams& gp, bool raw, unsigned grid, int waves, hipStream_t s)
+{
+    return raw ? direct_launch_one<P, MR, R, true>(gp, grid, waves, s) : direct_launch_one<P, MR, R, false>(gp, grid, waves, s);
+}
+
+template <int P, int MR>
+static hipError_t direct_launch_mr(const DirectParams& gp, int R, bool raw, unsigned grid, int waves, hipStream_t s)
+{
+    if constexpr (MR < direct_min_rows(P)) return hipErrorInvalidValue;
+    else {
+        // (four super-chunks per wave only where the registers hold them: narrow weights, at most four operand rows)
+        if (R == 1) return direct_launch_r<P, MR, 1>(gp, raw, grid, waves, s);
+        if (R == 2) return direct_launch_r<P, MR, 2>(gp, raw, grid, waves, s);
+        if constexpr (P <= 4 && MR <= 4) { if (R == 4) return direct_launch_r<P, MR, 4>(gp, raw, grid, waves, s); }
+        return hipErrorInvalidValue;
+    }
+}
+
+template <int P>
+static hipError_t direct_launch_p(const DirectParams& gp, int MR, int R, bool raw, unsigned grid, int waves, hipStream_t s)
+{
+    switch (MR) {
+        case 1: return direct_launch_mr<P, 1>(gp, R, raw, grid, waves, s);
+        case 2: return direct_launch_mr<P, 2>(gp, R, raw, grid, waves, s);
+        case 4: return direct_launch_mr<P, 4>(gp, R, raw, grid, waves, s);
+        case 8: return direct_launch_mr<P, 8>(gp, R, raw, grid, waves, s);
+        case 16: return direct_launch_mr<P, 16>(gp, R, raw, grid, waves, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+// Entry points of the per-width translation units.
+hipError_t direct_launch_p12(int p, const DirectParams& gp, int MR, int R, bool raw, unsigned grid, int waves, hipStream_t s);
+hipError_t direct_launch_p34(int p, const DirectParams& gp, int MR, int R, bool raw, unsigned grid, int waves, hipStream_t s);
+hipError_t direct_launch_p56(int p, const DirectParams& gp, int MR, int R, bool raw, unsigned grid, int waves, hipStream_t s);
+hipError_t direct_launch_p78(int p, const DirectParams& gp, int MR, int R, bool raw, unsigned grid, int waves, hipStream_t s);
+
+}  // namespace abq

@@ -103,7 +103,7 @@ hipError_t launch_silu_mul_quant(int q, int M, int K, const uint16_t* gate, cons
                                  int32_t* zero, uint16_t* h_out, hipStream_t s);
 
 // Launch-plan override for one exact problem size (0 = keep the library's rule); see abq_plan in the ABI header.
-struct PlanOverride { int skinny_waves, skinny_kgroups, tiled_mt, tiled_ntw, tiled_wd, tiled_band; };
+struct PlanOverride { int skinny_waves, skinny_kgroups, tiled_mt, tiled_ntw, tiled_wd, tiled_band, direct_r; };
 bool lookup_plan(int p, int q, int M, int N, int K, PlanOverride* out);   // false (and *out all zero) when none is set
 
 struct GemmArgs {
@@ -123,6 +123,13 @@ bool gemm_grouped_fits(int M, int count, const GemmArgs* probs, const ActLayout*
                        size_t* lds_bytes);
 hipError_t launch_gemm_grouped(int p, int M, int count, const GemmArgs* probs, const ActLayout* A, const WeightLayout* W,
                                int waves, size_t lds_bytes, hipStream_t s);
+// The direct decode kernel (few rows of A): plan = operand rows per slice set, super-chunks per wave, waves per workgroup.
+struct DirectPlan { int MR, R, S; };
+bool direct_plan(int p, int M, int nsuper, int forced_r, DirectPlan* out);   // false: the problem does not fit this kernel
+hipError_t launch_gemm_direct(const GemmArgs& g, const ActLayout& A, const WeightLayout& W, const DirectPlan& pl, hipStream_t s);
+bool gemm_direct_grouped_fits(int p, int M, int count, const GemmArgs* probs, const ActLayout* A, const WeightLayout* W);
+hipError_t launch_gemm_direct_grouped(int p, int q, int M, int count, const GemmArgs* probs, const ActLayout* A, const WeightLayout* W,
+                                      hipStream_t s);
 hipError_t launch_gemm_tiled(const GemmArgs& g, const ActLayout& A, const WeightLayout& W, hipStream_t s);
 hipError_t launch_gemm_bitserial(const GemmArgs& g, const ActLayout& A, const WeightLayout& W, hipStream_t s);
 
@@ -143,7 +150,12 @@ __device__ __forceinline__ uint16_t epilogue_value(int32_t S, int oa, int ow, in
     const uint32_t az = (uint32_t)ap.zero, wz = (uint32_t)wp.zero;
     const int32_t centered = (int32_t)(raw - wz * asum - az * wsum + uK * az * wz);
     const float v = ((float)centered * ap.scale) * wp.scale;
-    return __half_as_ushort(__float2half_rn(v));
+    // the conversion as the instruction itself: left to the compiler, the last product and the conversion may merge
+    // into one mixed-precision operation with a single rounding, which differs from the stated two roundings when
+    // the binary32 product is a tie between two binary16 values, and then kernels would not agree bit for bit
+    uint32_t h;
+    asm("v_cvt_f16_f32 %0, %1" : "=v"(h) : "v"(v));
+    return (uint16_t)h;
 }
 
 __device__ __forceinline__ void epilogue_store(int32_t S, int oa, int ow, int K, const RowParams& ap,

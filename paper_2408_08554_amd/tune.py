@@ -20,20 +20,27 @@ import torch
 
 from . import binding as abq
 
-KNOBS = ("skinny_waves", "skinny_kgroups", "tiled_mt", "tiled_ntw", "tiled_wd", "tiled_band")
+KNOBS = ("skinny_waves", "skinny_kgroups", "tiled_mt", "tiled_ntw", "tiled_wd", "tiled_band", "direct_r")
 
 
 def candidates(p, q, M, N, K):
     """Plans worth timing for this problem (the knobs of the kernel family that does not run are left 0)."""
     out = [{}]
     nsuper = -(-K // 512)
-    if M <= 64:     # decode kernel (M <= 16 always; up to 64 when there are few output tiles)
+    if M <= 16:     # the direct decode kernel with 1, 2 or 4 super-chunks per wave (a value that does not fit leaves the rule)
+        for r in (1, 2, 4):
+            if -(-nsuper // r) <= 16:
+                out.append({"direct_r": r})
+    if M <= 64:     # the streaming decode kernel (M <= 16 always; up to 64 when there are few output tiles)
+        direct_off = {"direct_r": -1} if M <= 16 else {}
+        if direct_off:
+            out.append(dict(direct_off))
         for w in (1, 2, 4, 5, 6, 7, 8):
             if w <= nsuper:
-                out.append({"skinny_waves": w})
+                out.append({"skinny_waves": w, **direct_off})
         if M > 8 and K >= 8192:
             for w, g in itertools.product((4, 6, 8), (2, 3, 4)):
-                out.append({"skinny_waves": w, "skinny_kgroups": g})
+                out.append({"skinny_waves": w, "skinny_kgroups": g, **direct_off})
     if M > 16:      # prefill kernel
         bands = sorted({b for b in (2, 4, 8, 16) if b <= max(2, -(-M // 64))})
         for mt, ntw in itertools.product((4, 8), (1, 2, 4)):

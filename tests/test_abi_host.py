@@ -107,9 +107,11 @@ def test_g128_pack_rejects_and_size_query():
 def test_plan_table_set_get_clear_and_rejects():
     B.load()
     B.abq_plan_clear()
-    zero = dict(skinny_waves=0, skinny_kgroups=0, tiled_mt=0, tiled_ntw=0, tiled_wd=0, tiled_band=0)
+    zero = dict(skinny_waves=0, skinny_kgroups=0, tiled_mt=0, tiled_ntw=0, tiled_wd=0, tiled_band=0, direct_r=0)
     assert B.abq_plan_get(4, 8, 1, 4096, 4096) == zero
     B.abq_plan_set(4, 8, 1, 4096, 4096, skinny_waves=6)
+    B.abq_plan_set(2, 8, 1, 4096, 11008, direct_r=-1)
+    assert B.abq_plan_get(2, 8, 1, 4096, 11008) == dict(zero, direct_r=-1)
     B.abq_plan_set(6, 6, 512, 11008, 4096, tiled_mt=4, tiled_ntw=2, tiled_wd=4, tiled_band=8)
     assert B.abq_plan_get(4, 8, 1, 4096, 4096) == dict(zero, skinny_waves=6)
     assert B.abq_plan_get(6, 6, 512, 11008, 4096) == dict(zero, tiled_mt=4, tiled_ntw=2, tiled_wd=4, tiled_band=8)
@@ -121,7 +123,7 @@ def test_plan_table_set_get_clear_and_rejects():
     assert B.abq_plan_get(6, 6, 512, 11008, 4096) == zero
     lib = B.load()
     for bad in (dict(skinny_waves=3), dict(skinny_waves=9), dict(skinny_kgroups=5), dict(tiled_mt=6), dict(tiled_ntw=3),
-                dict(tiled_wd=3), dict(tiled_band=-1)):
+                dict(tiled_wd=3), dict(tiled_band=-1), dict(direct_r=3), dict(direct_r=-2)):
         plan = B.AbqPlan(**bad)
         assert lib.abq_plan_set(4, 8, 1, 64, 64, ctypes.addressof(plan)) == B.ABQ_ERR_LAYOUT, bad
     plan = B.AbqPlan(skinny_waves=4)
