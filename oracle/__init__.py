@@ -179,6 +179,19 @@ def quant_act(x_half, q):
     return codes, sc, zp
 
 
+def requant(y_half, q, scale, zero):
+    """Codes of a binary16 matrix under given per-row (Delta, z): uint8 [M,N]."""
+    y_half = np.ascontiguousarray(y_half)
+    assert y_half.dtype == np.float16
+    M, N = y_half.shape
+    scale = np.ascontiguousarray(scale, dtype=np.float32)
+    zero = np.ascontiguousarray(zero, dtype=np.int32)
+    assert scale.shape == (M,) and zero.shape == (M,)
+    codes = np.empty((M, N), dtype=np.uint8)
+    _load().abq_oracle_requant(q, M, N, _p(y_half.view(np.uint16)), _p(scale), _p(zero), _p(codes))
+    return codes
+
+
 def add_half(a_half, b_half):
     """Element-wise binary16 sum: one binary32 addition, one rounding to binary16 (the residual add in front of RMSNorm)."""
     a_half = np.ascontiguousarray(a_half)

@@ -33,6 +33,8 @@
  * weight scales and zero-points, Appendix C): pinned by its reductions to the per-channel result (one group;
  * equal parameters in every group), a long-double dequantise-then-multiply with every weight under its own
  * group's parameters, and single-live-group closed forms including the short last group.
+ * abq_oracle_requant (the matmul output quantized again with given per-token parameters): PARITY UNPINNED by the
+ * paper; pinned by its reduction to abq_oracle_quant_act, grid round trips, saturation, ties and monotonicity.
  */
 #include <stdint.h>
 #include <stddef.h>
@@ -256,6 +258,34 @@ static float half_to_float(uint16_t h)
     else if (ex == 31) v = fr ? NAN : INFINITY;
     else v = ldexp((double)(fr + 1024), ex - 25);
     return (float)(sign ? -v : v);
+}
+
+/* ReQuant of a matmul output with parameters fixed ahead of the call (Fig. 3b: the kernel's output is quantized
+ * again for the next layer; the last paragraph of Sec. 3.4 folds that step into a neighbouring operator, here the
+ * matmul's own epilogue).  A token's range is not known before its whole output row exists, so the fused step takes
+ * Delta and z per token from the caller (a calibrated or previous-step range) and applies Eq. 3's
+ * clamp(round(x/Delta)+z) to the binary16 output value, in IEEE binary32 like the per-token quantizer below:
+ *   code[m,n] = clamp( clamp(rint(y[m,n] / Delta[m]), -2^24, 2^24) + z[m], 0, 2^q-1 )
+ * (the inner clamp only keeps the integer sum in range for any Delta > 0).  PARITY UNPINNED by the paper (it prints
+ * no formula for ReQuant); pinned by its reduction to abq_oracle_quant_act when Delta and z are that function's own,
+ * grid round trips, saturation, ties and monotonicity.  NaN/Inf inputs and Delta <= 0 are undefined. */
+void abq_oracle_requant(int q, int M, int N, const uint16_t* y_half, const float* scale, const int32_t* zero,
+                        uint8_t* codes)
+{
+    const int qmax = (1 << q) - 1;
+    for (int m = 0; m < M; ++m) {
+        volatile float delta = scale[m];
+        const int z = zero[m];
+        for (int n = 0; n < N; ++n) {
+            float y = half_to_float(y_half[(size_t)m * N + n]);
+            volatile float t = y / delta;
+            float rn = nearbyintf(t);
+            if (rn < -16777216.0f) rn = -16777216.0f;
+            if (rn > 16777216.0f) rn = 16777216.0f;
+            int c = (int)rn + z;
+            codes[(size_t)m * N + n] = (uint8_t)(c < 0 ? 0 : (c > qmax ? qmax : c));
+        }
+    }
 }
 
 /* Per-token activation quantizer (the paper says only "per-token", Sec. 4.1; Eq. 3 gives the

@@ -69,6 +69,12 @@ MUTATIONS = {
         ("inner += ((int64_t)A[(size_t)m * K + k] - az[m]) *", "inner += ((int64_t)A[(size_t)m * K + k] + az[m]) *"),
     "grouped: activation scale of row 0 for every row":
         ("const double v = (double)a_scale[m] * total;", "const double v = (double)a_scale[0] * total;"),
+    "requant: zero-point dropped":
+        ("            int c = (int)rn + z;", "            int c = (int)rn;"),
+    "requant: step of row 0 for every row":
+        ("volatile float delta = scale[m];\n        const int z = zero[m];", "volatile float delta = scale[0];\n        const int z = zero[m];"),
+    "requant: ties away from zero":
+        ("float rn = nearbyintf(t);", "float rn = roundf(t);"),
     "add: difference instead of sum":
         ("volatile float s = half_to_float(a_half[i]) + half_to_float(b_half[i]);", "volatile float s = half_to_float(a_half[i]) - half_to_float(b_half[i]);"),
     "add: second operand taken from the first":
@@ -90,6 +96,7 @@ CHECKS = [
     lambda: pins.test_pack_unpack_planes(5, 2, 100),
     lambda: pins.test_quant_act_invariants(4),
     lambda: pins.test_quant_act_invariants(8),
+    lambda: pins.test_requant_pins(4),
     lambda: pins.test_rmsnorm_matches_float64_definition(3, 1000, 1e-6),
     lambda: pins.test_rmsnorm_closed_forms(),
     lambda: pins.test_rmsnorm_invariances_are_bit_exact(),

@@ -259,6 +259,37 @@ def test_quant_act_invariants(q):
     assert np.all(np.diff(cd[0][order].astype(np.int32)) >= 0)
 
 
+# ---- ReQuant with given per-token parameters (parity unpinned by the paper) ---------------------
+
+@pytest.mark.parametrize("q", [1, 3, 4, 8])
+def test_requant_pins(q):
+    qmax = (1 << q) - 1
+    # (1) with the per-token quantizer's own Delta and z it IS that quantizer (a function pinned on its own)
+    x = synth.act_fp16(4321 + q, 5, 257)
+    cd, sc, zp = oracle.quant_act(x, q)
+    assert np.array_equal(oracle.requant(x, q, sc, zp), cd)
+    # (2) values on the grid Delta*(c - z) come back as c (Delta a power of two: the grid is exact in binary16)
+    for delta, z in ((0.25, 0), (2.0, qmax // 2), (0.5, qmax)):
+        c = np.arange(qmax + 1, dtype=np.int64)
+        y = (delta * (c - z)).astype(np.float16).reshape(1, -1)
+        got = oracle.requant(y, q, np.array([delta], np.float32), np.array([z], np.int32))
+        assert np.array_equal(got[0], c.astype(np.uint8))
+    # (3) saturation at both ends, also where the quotient is far outside any integer type's comfort
+    y = np.array([[65504.0, -65504.0, 0.0, 1e-4, -1e-4]], dtype=np.float16)
+    got = oracle.requant(y, q, np.array([1e-7], np.float32), np.array([qmax // 2], np.int32))
+    assert list(got[0]) == [qmax, 0, qmax // 2, qmax, 0]
+    # (4) ties go to the even integer: y / Delta = 0.5, 1.5, 2.5, -0.5 -> 0, 2, 2, 0 (before the zero-point)
+    if q >= 3:
+        y = np.array([[0.5, 1.5, 2.5, -0.5, 3.5]], dtype=np.float16)
+        got = oracle.requant(y, q, np.array([1.0], np.float32), np.array([1], np.int32))
+        assert list(got[0]) == [1, 3, 3, 1, 5]
+    # (5) the zero-point and the step are the row's own; monotone in y
+    y = np.sort(synth.act_fp16(99, 1, 400)[0]).reshape(1, -1).repeat(2, axis=0)
+    got = oracle.requant(y, q, np.array([0.125, 0.5], np.float32), np.array([0, qmax], np.int32))
+    assert np.all(np.diff(got.astype(np.int32), axis=1) >= 0)
+    assert got[1].max() == qmax and (q == 1 or not np.array_equal(got[0], got[1]))
+
+
 # ---- the metric itself, against the values the paper prints -------------------------------
 
 def test_tops_definition_matches_table4():
