@@ -226,6 +226,25 @@ int abq_gemm_act_codes(int p, int q, int M, int N, int K,
                        uint16_t* y_fp16, int32_t* acc_i32,
                        void* workspace, size_t workspace_bytes, void* stream);
 
+/* ReQuant fused into the matmul epilogue (Fig. 3b: the kernel's output is quantized again for the next layer; the last
+ * paragraph of Sec. 3.4 folds quantization into neighbouring operators — this is the consumer side, the producers
+ * above are the other).  abq_gemm_act_codes that also (or only) writes the next layer's activation codes.  A token's
+ * own range is unknown before its whole output row exists, so Delta and z per token are the caller's (a calibrated or
+ * previous-step range):
+ *   code[m,n] = clamp( clamp(rint(Y[m,n] / out_scale[m]), -2^24, 2^24) + out_zero[m], 0, 2^q_out − 1 )
+ * on the binary16 value Y[m,n] of abq_gemm, division and rint in IEEE binary32 (Eq. 3's clamp(round(x/Delta)+z)).
+ *   q_out      1..8;  out_scale [M] float > 0;  out_zero [M] int32  (device)
+ *   codes_out  [M,N] uint8, required: feeds the next abq_gemm_act_codes together with out_scale / out_zero
+ *   y_fp16     [M,N] binary16, optional here (NULL to skip)
+ *   the other arguments, the workspace and the errors as for abq_gemm_act_codes (same workspace query); ABQ_ERR_BITS
+ *   also for q_out; ABQ_ERR_LAYOUT for ABQ_LAYOUT_FIELDS_G128 blobs (not built for them).  NaN/Inf outputs and
+ *   out_scale <= 0 are undefined. */
+int abq_gemm_act_codes_requant(int p, int q, int M, int N, int K,
+                               const uint8_t* a_codes, const float* a_scale, const int32_t* a_zero,
+                               const void* packed_w, int w_layout,
+                               int q_out, const float* out_scale, const int32_t* out_zero, uint8_t* codes_out,
+                               uint16_t* y_fp16, void* workspace, size_t workspace_bytes, void* stream);
+
 /* abq_gemm_act_codes for callers that cannot allocate device memory or bring a workspace (code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc): the same call with no workspace argument.
  * Where abq_gemm_act_codes needs a workspace (the packed activations of its two-kernel path) this variant keeps

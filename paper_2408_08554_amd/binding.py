@@ -49,6 +49,7 @@ _SIGNATURES = {
     "abq_silu_mul_quant_act": (_c.c_int, [_c.c_int] * 3 + [_c.c_void_p] * 7),
     "abq_gemm_act_codes": (_c.c_int, [_c.c_int] * 5 + [_c.c_void_p] * 4 + [_c.c_int, _c.c_void_p, _c.c_void_p,
                                                                           _c.c_void_p, _c.c_size_t, _c.c_void_p]),
+    "abq_gemm_act_codes_requant": (_c.c_int, [_c.c_int] * 5 + [_c.c_void_p] * 4 + [_c.c_int, _c.c_int] + [_c.c_void_p] * 5 + [_c.c_size_t, _c.c_void_p]),
     "abq_check_packed": (_c.c_int, [_c.c_int] * 5 + [_c.c_void_p, _c.c_size_t, _c.c_void_p]),
     "abq_gemm_act_codes_static": (_c.c_int, [_c.c_int] * 5 + [_c.c_void_p] * 4 + [_c.c_int, _c.c_void_p, _c.c_void_p, _c.c_void_p]),
 }
@@ -234,6 +235,23 @@ def abq_gemm_act_codes(p, q, M, N, K, a_codes, a_scale, a_zero, packed_w, w_layo
                                   _ptr(y), _ptr(acc), _ptr(workspace), 0 if workspace is None else workspace.numel(),
                                   _stream()), "abq_gemm_act_codes")
     return y, acc
+
+
+def abq_gemm_act_codes_requant(p, q, M, N, K, a_codes, a_scale, a_zero, packed_w, w_layout, q_out, out_scale, out_zero,
+                               want_y=True, workspace=None):
+    """-> (codes uint8 [M,N] of the next layer under (out_scale, out_zero), y float16 [M,N] or None)."""
+    lib = load()
+    dev = packed_w.device
+    _dev(out_scale, torch.float32, (M,)), _dev(out_zero, torch.int32, (M,))
+    codes = torch.empty((M, N), dtype=torch.uint8, device=dev)
+    y = torch.empty((M, N), dtype=torch.float16, device=dev) if want_y else None
+    need = lib.abq_gemm_act_codes_workspace_bytes(p, q, M, N, K, w_layout)
+    if need and workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    _check(lib.abq_gemm_act_codes_requant(p, q, M, N, K, _ptr(a_codes), _ptr(a_scale), _ptr(a_zero), _ptr(packed_w), w_layout, q_out,
+                                          _ptr(out_scale), _ptr(out_zero), _ptr(codes), _ptr(y), _ptr(workspace),
+                                          0 if workspace is None else workspace.numel(), _stream()), "abq_gemm_act_codes_requant")
+    return codes, y
 
 
 def abq_gemm_act_codes_static(p, q, M, N, K, a_codes, a_scale, a_zero, packed_w, w_layout, y, acc=None):

@@ -439,10 +439,13 @@ size_t abq_gemm_workspace_bytes(int p, int q, int M, int N, int K)
     return 0;   // no kernel needs scratch at present
 }
 
-int abq_gemm(int p, int q, int M, int N, int K, const void* packed_act, int a_layout, const void* packed_w,
-             int w_layout, uint16_t* y_fp16, int32_t* acc_i32, void* workspace, size_t workspace_bytes, void* stream)
+static const Requant kNoRequant{nullptr, nullptr, nullptr, 0};
+
+static int gemm_impl(int p, int q, int M, int N, int K, const void* packed_act, int a_layout, const void* packed_w,
+                     int w_layout, uint16_t* y_fp16, int32_t* acc_i32, void* workspace, size_t workspace_bytes, void* stream,
+                     const Requant& rq)
 {
-    if (!packed_act || !packed_w || !y_fp16) return ABQ_ERR_NULL;
+    if (!packed_act || !packed_w || (!y_fp16 && !rq.codes)) return ABQ_ERR_NULL;
     if (int e = check_gemm_shape(p, q, M, N, K)) return e;
     const int force = w_layout & (ABQ_USE_PLANES | ABQ_USE_FIELDS);
     w_layout &= ~(ABQ_USE_PLANES | ABQ_USE_FIELDS);
@@ -457,15 +460,22 @@ int abq_gemm(int p, int q, int M, int N, int K, const void* packed_act, int a_la
         return ABQ_ERR_ALIGN;
     const size_t need = abq_gemm_workspace_bytes(p, q, M, N, K);
     if (need > 0 && (!workspace || workspace_bytes < need)) return workspace ? ABQ_ERR_SIZE : ABQ_ERR_NULL;
-    if (W.g128 && (acc_i32 || force == ABQ_USE_PLANES)) return ABQ_ERR_LAYOUT;
+    if (W.g128 && (acc_i32 || force == ABQ_USE_PLANES || rq.codes)) return ABQ_ERR_LAYOUT;
 
     GemmArgs g{p, q, M, N, K, (const uint8_t*)packed_act, nullptr, nullptr, nullptr, (const uint8_t*)packed_w, y_fp16, acc_i32,
-               workspace, workspace_bytes};
+               workspace, workspace_bytes, rq};
     hipStream_t s = (hipStream_t)stream;
     if (W.g128) return hip_status(launch_gemm_skinny(g, A, W, s));   // every M: one pass over W per 16 rows
     if (!choose_fields(can_fields, can_planes, force, p, q, M, N)) return hip_status(launch_gemm_bitserial(g, A, W, s));
     if (streaming_shape(M, N)) return hip_status(launch_decode(g, A, W, s));
     return hip_status(launch_gemm_tiled(g, A, W, s));
+}
+
+int abq_gemm(int p, int q, int M, int N, int K, const void* packed_act, int a_layout, const void* packed_w,
+             int w_layout, uint16_t* y_fp16, int32_t* acc_i32, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!y_fp16) return ABQ_ERR_NULL;
+    return gemm_impl(p, q, M, N, K, packed_act, a_layout, packed_w, w_layout, y_fp16, acc_i32, workspace, workspace_bytes, stream, kNoRequant);
 }
 
 // The fused call runs as one kernel when abq_gemm on the same problem would pick the streaming kernel
@@ -489,11 +499,11 @@ size_t abq_gemm_act_codes_workspace_bytes(int p, int q, int M, int N, int K, int
     return abq_packed_act_bytes(q, M, K, W.g128 ? ABQ_LAYOUT_FIELDS : w_layout) + abq_gemm_workspace_bytes(p, q, M, N, K);
 }
 
-int abq_gemm_act_codes(int p, int q, int M, int N, int K, const uint8_t* a_codes, const float* a_scale,
-                       const int32_t* a_zero, const void* packed_w, int w_layout, uint16_t* y_fp16, int32_t* acc_i32,
-                       void* workspace, size_t workspace_bytes, void* stream)
+static int gemm_act_codes_impl(int p, int q, int M, int N, int K, const uint8_t* a_codes, const float* a_scale,
+                               const int32_t* a_zero, const void* packed_w, int w_layout, uint16_t* y_fp16, int32_t* acc_i32,
+                               void* workspace, size_t workspace_bytes, void* stream, const Requant& rq)
 {
-    if (!a_codes || !a_scale || !a_zero || !packed_w || !y_fp16) return ABQ_ERR_NULL;
+    if (!a_codes || !a_scale || !a_zero || !packed_w || (!y_fp16 && !rq.codes)) return ABQ_ERR_NULL;
     if (int e = check_gemm_shape(p, q, M, N, K)) return e;
     const int force = w_layout & (ABQ_USE_PLANES | ABQ_USE_FIELDS);
     const int base_layout = w_layout & ~(ABQ_USE_PLANES | ABQ_USE_FIELDS);
@@ -504,12 +514,12 @@ int abq_gemm_act_codes(int p, int q, int M, int N, int K, const uint8_t* a_codes
     if (misaligned(a_codes) || misaligned(a_scale) || misaligned(a_zero) || misaligned(packed_w) || misaligned(y_fp16) ||
         misaligned(acc_i32) || misaligned(workspace))
         return ABQ_ERR_ALIGN;
-    if (W.g128 && acc_i32) return ABQ_ERR_LAYOUT;
+    if (W.g128 && (acc_i32 || rq.codes)) return ABQ_ERR_LAYOUT;
     hipStream_t s = (hipStream_t)stream;
     if (fused_act_direct(W, force, p, q, M, N, K)) {
         ActLayout A;
         if (!make_act_layout(q, M, K, ABQ_LAYOUT_FIELDS, &A)) return ABQ_ERR_LAYOUT;
-        GemmArgs g{p, q, M, N, K, nullptr, a_codes, a_scale, a_zero, (const uint8_t*)packed_w, y_fp16, acc_i32, nullptr, 0};
+        GemmArgs g{p, q, M, N, K, nullptr, a_codes, a_scale, a_zero, (const uint8_t*)packed_w, y_fp16, acc_i32, nullptr, 0, rq};
         return hip_status(launch_decode(g, A, W, s));
     }
     // Otherwise the two steps run back to back, the packed activations living in the caller's workspace.
@@ -519,8 +529,30 @@ int abq_gemm_act_codes(int p, int q, int M, int N, int K, const uint8_t* a_codes
     if (!workspace) return ABQ_ERR_NULL;
     if (workspace_bytes < need) return ABQ_ERR_SIZE;
     if (int e = abq_pack_act_codes(q, M, K, a_codes, a_scale, a_zero, act_layout, workspace, act_bytes, stream)) return e;
-    return abq_gemm(p, q, M, N, K, workspace, act_layout, packed_w, w_layout, y_fp16, acc_i32,
-                    (uint8_t*)workspace + act_bytes, workspace_bytes - act_bytes, stream);
+    return gemm_impl(p, q, M, N, K, workspace, act_layout, packed_w, w_layout, y_fp16, acc_i32,
+                     (uint8_t*)workspace + act_bytes, workspace_bytes - act_bytes, stream, rq);
+}
+
+int abq_gemm_act_codes(int p, int q, int M, int N, int K, const uint8_t* a_codes, const float* a_scale,
+                       const int32_t* a_zero, const void* packed_w, int w_layout, uint16_t* y_fp16, int32_t* acc_i32,
+                       void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!y_fp16) return ABQ_ERR_NULL;
+    return gemm_act_codes_impl(p, q, M, N, K, a_codes, a_scale, a_zero, packed_w, w_layout, y_fp16, acc_i32, workspace, workspace_bytes,
+                               stream, kNoRequant);
+}
+
+int abq_gemm_act_codes_requant(int p, int q, int M, int N, int K, const uint8_t* a_codes, const float* a_scale,
+                               const int32_t* a_zero, const void* packed_w, int w_layout, int q_out, const float* out_scale,
+                               const int32_t* out_zero, uint8_t* codes_out, uint16_t* y_fp16, void* workspace,
+                               size_t workspace_bytes, void* stream)
+{
+    if (!out_scale || !out_zero || !codes_out) return ABQ_ERR_NULL;
+    if (q_out < 1 || q_out > 8) return ABQ_ERR_BITS;
+    if (misaligned(out_scale) || misaligned(out_zero) || misaligned(codes_out)) return ABQ_ERR_ALIGN;
+    const Requant rq{codes_out, out_scale, out_zero, (1 << q_out) - 1};
+    return gemm_act_codes_impl(p, q, M, N, K, a_codes, a_scale, a_zero, packed_w, w_layout, y_fp16, nullptr, workspace, workspace_bytes,
+                               stream, rq);
 }
 
 int abq_gemm_act_codes_static(int p, int q, int M, int N, int K, const uint8_t* a_codes, const float* a_scale,

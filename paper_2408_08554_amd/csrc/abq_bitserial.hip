@@ -20,6 +20,7 @@ struct BitSerialParams {
     const RowParams* wparams;
     uint16_t* y;
     int32_t* acc;
+    Requant rq;
     int M, N, K, Kq;
 };
 
@@ -72,7 +73,7 @@ __global__ __launch_bounds__(256) void bitserial_kernel(BitSerialParams prm)
         for (int off = 8; off > 0; off >>= 1) v += __shfl_xor(v, off, 16);
         const int m = m0 + mm;
         if (sub == 0 && n_valid && m < prm.M)
-            epilogue_store(v, 0, 0, prm.K, prm.aparams[m], prm.wparams[n], (size_t)m * prm.N + n, prm.y, prm.acc);
+            epilogue_store(v, 0, 0, prm.K, prm.aparams[m], prm.wparams[n], (size_t)m * prm.N + n, prm.y, prm.acc, prm.rq, m);
     }
 }
 
@@ -111,6 +112,7 @@ hipError_t launch_gemm_bitserial(const GemmArgs& g, const ActLayout& A, const We
     prm.wparams = (const RowParams*)(g.w_blob + W.off_params);
     prm.y = g.y;
     prm.acc = g.acc;
+    prm.rq = g.rq;
     prm.M = g.M; prm.N = g.N; prm.K = g.K; prm.Kq = W.Kw / 4;
     switch (g.p) {
         case 1: return launch_p<1>(g.q, prm, s);

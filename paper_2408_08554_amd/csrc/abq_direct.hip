@@ -43,7 +43,7 @@ static void fill_problem(DirectProblem& d, const GemmArgs& g, const ActLayout& A
         d.a_raw = nullptr; d.a_scale = nullptr; d.a_zero = nullptr;
     }
     d.wparams = (const RowParams*)(g.w_blob + W.off_params);
-    d.y = g.y; d.acc = g.acc;
+    d.y = g.y; d.acc = g.acc; d.rq = g.rq;
     d.N = g.N; d.K = g.K; d.Kp = A.Kp; d.nsuper = A.Kp / kSuperK;
     d.rsplit = rsplit;
 }

@@ -42,8 +42,9 @@ struct DirectProblem {
     const float* a_scale;
     const int32_t* a_zero;
     const RowParams* wparams;
-    uint16_t* y;
+    uint16_t* y;               // may be null when rq.codes is given
     int32_t* acc;              // may be null
+    Requant rq;                // output codes of the next layer (codes == null: off)
     int N, K, Kp, nsuper;
     int rsplit;                // super-chunks per wave (<= R): wave w owns [w*rsplit, w*rsplit + rsplit) clipped to nsuper
 };
@@ -197,7 +198,7 @@ __global__ __launch_bounds__(1024) void direct_kernel(DirectParams gp)
     // (pins the pointers in scalar registers here, so that the compiler fetches them with the sizes above in one
     // batch instead of sinking each load next to its first use behind a branch)
     const int S = (int)blockDim.x >> 6;
-    asm volatile("" ::"s"(pr.fields[0]), "s"(pr.fields[1]), "s"(pr.fields[2]), "s"(pr.wparams), "s"(pr.y), "s"(pr.acc), "s"(pr.N), "s"(pr.K),
+    asm volatile("" ::"s"(pr.fields[0]), "s"(pr.fields[1]), "s"(pr.fields[2]), "s"(pr.wparams), "s"(pr.y), "s"(pr.acc), "s"(pr.rq.codes), "s"(pr.N), "s"(pr.K),
                  "s"(gp.oa), "s"(gp.ow), "s"(gp.a_mask), "s"(S));
     if constexpr (RAW) asm volatile("" ::"s"(pr.a_raw), "s"(pr.a_scale), "s"(pr.a_zero));
     else asm volatile("" ::"s"(pr.a_codes), "s"(pr.aparams));
@@ -327,7 +328,7 @@ __global__ __launch_bounds__(1024) void direct_kernel(DirectParams gp)
             }
             pa.sum = as + gp.oa * pr.K;   // the operand bytes are the codes less oa; padding holds zero bytes
         }
-        if (n < pr.N) epilogue_store(sum, gp.oa, gp.ow, pr.K, pa, pw, (size_t)m * pr.N + n, pr.y, pr.acc);
+        if (n < pr.N) epilogue_store(sum, gp.oa, gp.ow, pr.K, pa, pw, (size_t)m * pr.N + n, pr.y, pr.acc, pr.rq, m);
     }
 }
 

@@ -33,8 +33,9 @@ struct TiledParams {
     const int8_t* a_codes;
     const RowParams* aparams;
     const RowParams* wparams;
-    uint16_t* y;
+    uint16_t* y;              // may be null when rq.codes is given
     int32_t* acc;
+    Requant rq;               // output codes of the next layer (codes == null: off)
     int M, N, K, Kp, nsuper, ntiles;
     int oa, ow;
     int tiles_m, tiles_n;     // workgroup tiles along M and N (1-D grid of tiles_m * tiles_n workgroups)
@@ -305,8 +306,11 @@ __global__ __launch_bounds__(256, (WD == 4 ? 2 : (NTW <= 2 ? (MT == 4 ? 3 : 2) :
             for (int nt = 0; nt < NTW; ++nt) {
                 const int n = n0 + wave * kWCols + nt * 16 + r;
                 int32_t raw;
-                stage[ml * kWCols + nt * 16 + r] = epilogue_value(acc[mt][nt][reg], prm.oa, prm.ow, prm.K, pa, pw[nt], &raw);
+                const uint16_t h = epilogue_value(acc[mt][nt][reg], prm.oa, prm.ow, prm.K, pa, pw[nt], &raw);
+                stage[ml * kWCols + nt * 16 + r] = h;
                 if (prm.acc && m < prm.M && n < prm.N) prm.acc[(size_t)m * prm.N + n] = raw;
+                if (prm.rq.codes && m < prm.M && n < prm.N)
+                    prm.rq.codes[(size_t)m * prm.N + n] = requant_code(h, prm.rq.scale[m], prm.rq.zero[m], prm.rq.qmax);
             }
         }
     }
@@ -321,7 +325,7 @@ __global__ __launch_bounds__(256, (WD == 4 ? 2 : (NTW <= 2 ? (MT == 4 ? 3 : 2) :
         const int idx = it * 64 + lane;
         const int ml = idx / kPieces, piece = idx % kPieces;
         const int m = m0 + ml, n = n0 + wave * kWCols + piece * 8;
-        if (m < prm.M && n < prm.N) {
+        if (prm.y && m < prm.M && n < prm.N) {
             const uint4 v = *reinterpret_cast<const uint4*>(stage + ml * kWCols + piece * 8);
             uint16_t* dst = prm.y + (size_t)m * prm.N + n;
             if (vec_ok && n + 8 <= prm.N) {
@@ -380,6 +384,7 @@ hipError_t launch_gemm_tiled(const GemmArgs& g, const ActLayout& A, const Weight
     prm.wparams = (const RowParams*)(g.w_blob + W.off_params);
     prm.y = g.y;
     prm.acc = g.acc;
+    prm.rq = g.rq;
     prm.M = g.M; prm.N = g.N; prm.K = g.K; prm.Kp = A.Kp;
     prm.nsuper = A.Kp / kSuperK;
     prm.ntiles = W.NT;

@@ -106,6 +106,16 @@ hipError_t launch_silu_mul_quant(int q, int M, int K, const uint16_t* gate, cons
 struct PlanOverride { int skinny_waves, skinny_kgroups, tiled_mt, tiled_ntw, tiled_wd, tiled_band, direct_r; };
 bool lookup_plan(int p, int q, int M, int N, int K, PlanOverride* out);   // false (and *out all zero) when none is set
 
+// ReQuant fused into the matmul epilogue (Fig. 3b; the last paragraph of Sec. 3.4): besides (or instead of) the
+// binary16 output, the codes of the next layer's activations under per-token parameters the caller fixes ahead of
+// the call.  codes == nullptr: off.
+struct Requant {
+    uint8_t* codes;        // [M,N] uint8
+    const float* scale;    // [M] Delta of the output row
+    const int32_t* zero;   // [M] zero-point of the output row
+    int qmax;              // 2^q_out - 1
+};
+
 struct GemmArgs {
     int p, q, M, N, K;
     const uint8_t* act_blob;   // packed activations, or null when a_raw is given (streaming kernel only)
@@ -113,10 +123,11 @@ struct GemmArgs {
     const float* a_scale;
     const int32_t* a_zero;
     const uint8_t* w_blob;
-    uint16_t* y;
+    uint16_t* y;       // may be null when rq.codes is given
     int32_t* acc;      // may be null
     void* workspace;
     size_t workspace_bytes;
+    Requant rq = Requant{nullptr, nullptr, nullptr, 0};
 };
 hipError_t launch_gemm_skinny(const GemmArgs& g, const ActLayout& A, const WeightLayout& W, hipStream_t s);
 bool gemm_grouped_fits(int M, int count, const GemmArgs* probs, const ActLayout* A, const WeightLayout* W, int* waves,
@@ -158,12 +169,27 @@ __device__ __forceinline__ uint16_t epilogue_value(int32_t S, int oa, int ow, in
     return (uint16_t)h;
 }
 
+// code = clamp(clamp(rint(y / Delta), -2^24, 2^24) + z, 0, qmax) on the binary16 output value, every float step one
+// IEEE binary32 operation (Eq. 3's clamp(round(x/Delta)+z); the float results decide integer codes).
+__device__ __forceinline__ uint8_t requant_code(uint16_t h, float delta, int z, int qmax)
+{
+    const float yv = __half2float(__ushort_as_half(h));
+    float r = rintf(__fdiv_rn(yv, delta));
+    r = fminf(fmaxf(r, -16777216.0f), 16777216.0f);
+    const int c = (int)r + z;
+    return (uint8_t)(c < 0 ? 0 : (c > qmax ? qmax : c));
+}
+
+// m: the output row (for the ReQuant parameters).
 __device__ __forceinline__ void epilogue_store(int32_t S, int oa, int ow, int K, const RowParams& ap,
-                                               const RowParams& wp, size_t idx, uint16_t* y, int32_t* acc)
+                                               const RowParams& wp, size_t idx, uint16_t* y, int32_t* acc,
+                                               const Requant& rq = Requant{nullptr, nullptr, nullptr, 0}, int m = 0)
 {
     int32_t raw;
-    y[idx] = epilogue_value(S, oa, ow, K, ap, wp, &raw);
+    const uint16_t h = epilogue_value(S, oa, ow, K, ap, wp, &raw);
+    if (y) y[idx] = h;
     if (acc) acc[idx] = raw;
+    if (rq.codes) rq.codes[idx] = requant_code(h, rq.scale[m], rq.zero[m], rq.qmax);
 }
 
 }  // namespace abq

@@ -192,6 +192,7 @@ static void fill_operands(SkinnyParams& prm, const GemmArgs& g, const ActLayout&
     prm.gparams = W.g128 ? (const u4v*)(g.w_blob + W.off_gparams) : nullptr;
     prm.y = g.y;
     prm.acc = g.acc;
+    prm.rq = g.rq;
     prm.M = g.M; prm.N = g.N; prm.K = g.K; prm.Kp = A.Kp;
     prm.oa = (g.q == 8) ? 128 : 0;
     prm.ow = (g.p == 8) ? 128 : 0;

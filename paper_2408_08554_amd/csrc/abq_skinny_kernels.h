@@ -40,8 +40,9 @@ struct SkinnyParams {
     const float* a_scale;
     const int32_t* a_zero;
     const RowParams* wparams;
-    uint16_t* y;
+    uint16_t* y;              // may be null when rq.codes is given
     int32_t* acc;
+    Requant rq;               // output codes of the next layer (codes == null: off)
     int M, N, K, Kp;
     int oa, ow;
     uint32_t a_mask;          // (2^q - 1) in every byte: applied to unpacked activation codes while they are staged
@@ -420,7 +421,7 @@ __device__ __forceinline__ void finish_tile(const SkinnyParams& prm, WaveState<P
                 for (int ww = 0; ww < 8; ++ww) sp[ww] = ww < st.S ? st.asum[ww * 16 + row] : 0;
                 pa.sum = ((sp[0] + sp[1]) + (sp[2] + sp[3])) + ((sp[4] + sp[5]) + (sp[6] + sp[7]));
             }
-            epilogue_store(s, prm.oa, prm.ow, prm.K, pa, pw, (size_t)m * prm.N + n, prm.y, prm.acc);
+            epilogue_store(s, prm.oa, prm.ow, prm.K, pa, pw, (size_t)m * prm.N + n, prm.y, prm.acc, prm.rq, m);
         }
     }
     st.parity ^= 1;

@@ -378,3 +378,22 @@ def test_static_entry_point_rejects_before_touching_the_device():
     # 4096 rows of K = 13824 need 54 MiB of packed activations: beyond the static buffer
     assert lib.abq_gemm_act_codes_workspace_bytes(8, 8, 4096, 5120, 13824, F) > B.ABQ_STATIC_SCRATCH_BYTES
     assert call(p=8, q=8, M=4096, N=5120, K=13824) == B.ABQ_ERR_SIZE
+
+
+def test_requant_entry_point_rejects_before_touching_the_device():
+    lib = B.load()
+    F = B.ABQ_LAYOUT_FIELDS
+
+    def call(p=4, q=8, M=1, N=64, K=512, a=A16, s=A16, z=A16, w=A16, wl=F, qo=8, osc=A16, ozp=A16, codes=A16, y=None, ws=None, wsb=0):
+        return lib.abq_gemm_act_codes_requant(p, q, M, N, K, a, s, z, w, wl, qo, osc, ozp, codes, y, ws, wsb, None)
+
+    assert call(codes=None) == B.ABQ_ERR_NULL
+    assert call(osc=None) == B.ABQ_ERR_NULL
+    assert call(a=None) == B.ABQ_ERR_NULL
+    assert call(qo=0) == B.ABQ_ERR_BITS and call(qo=9) == B.ABQ_ERR_BITS and call(q=0) == B.ABQ_ERR_BITS
+    assert call(codes=A16 + 1) == B.ABQ_ERR_ALIGN
+    assert call(K=0) == B.ABQ_ERR_SHAPE
+    assert call(wl=B.ABQ_LAYOUT_FIELDS_G128) == B.ABQ_ERR_LAYOUT            # per-group blobs: not built
+    assert call(M=300) == B.ABQ_ERR_NULL                                      # the two-kernel path needs its workspace
+    assert call(M=300, ws=A16, wsb=16) == B.ABQ_ERR_SIZE
+    assert lib.abq_gemm_act_codes(4, 8, 1, 64, 512, A16, A16, A16, A16, F, None, None, None, 0, None) == B.ABQ_ERR_NULL   # y stays required there

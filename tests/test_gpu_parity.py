@@ -869,6 +869,59 @@ def test_config5_sweep_samples(abq, p, q, shape_idx, m_idx):
     check_sampled(c, y, acc)
 
 
+# ---- ReQuant fused into the matmul epilogue (the consumer side of Fig. 3b) --------------------------------------
+@pytest.mark.parametrize("p,q,q_out,M,N,K,layout", [(4, 8, 8, 1, 300, 4096, FIELDS),      # direct decode kernel
+                                                    (2, 8, 4, 7, 70, 1552, FIELDS),       # direct, ragged
+                                                    (8, 8, 8, 16, 2000, 13824, FIELDS),   # streaming decode kernel (long stream, 16 rows)
+                                                    (6, 6, 6, 130, 200, 2048, FIELDS),    # tiled prefill kernel
+                                                    (4, 4, 2, 300, 520, 1000, FIELDS),    # tiled, K ragged
+                                                    (3, 5, 3, 5, 33, 200, PLANES),        # bit-serial kernel (two-step path)
+                                                    (1, 1, 1, 2, 16, 512, FIELDS)])
+def test_gemm_requant_emits_the_next_layers_codes(abq, p, q, q_out, M, N, K, layout):
+    """abq_gemm_act_codes_requant: the codes equal the oracle's ReQuant of the kernel's own binary16 output bit for bit, the
+    binary16 output is the one abq_gemm_act_codes gives, and leaving it out changes no code."""
+    c = synth.make_case(p, q, M, N, K, seed=synth.case_seed(9, p, q, M, q_out), name=f"requant W{p}A{q}->A{q_out} {M}x{N}x{K}")
+    say(c.name)
+    pw = abq.abq_pack_weights(p, to_dev(torch, c.W), to_dev(torch, c.w_scale), to_dev(torch, c.w_zero), layout)
+    a, s, z = to_dev(torch, c.A), to_dev(torch, c.a_scale), to_dev(torch, c.a_zero)
+    y_plain, _ = abq.abq_gemm_act_codes(p, q, M, N, K, a, s, z, pw, layout)
+    # per-token output parameters as a calibration pass would fix them: the quantizer's own on the reference output
+    yref = check_against_oracle(c, y_plain.cpu().numpy(), None)
+    _, osc, ozp = oracle.quant_act(yref.astype(np.float16), q_out)
+    codes, y = abq.abq_gemm_act_codes_requant(p, q, M, N, K, a, s, z, pw, layout, q_out, to_dev(torch, osc), to_dev(torch, ozp))
+    codes_only, none = abq.abq_gemm_act_codes_requant(p, q, M, N, K, a, s, z, pw, layout, q_out, to_dev(torch, osc), to_dev(torch, ozp),
+                                                      want_y=False)
+    torch.cuda.synchronize()
+    assert none is None and torch.equal(codes, codes_only)
+    assert torch.equal(y.view(torch.int16), y_plain.view(torch.int16))
+    want = oracle.requant(y.cpu().numpy(), q_out, osc, ozp)
+    assert np.array_equal(codes.cpu().numpy(), want)
+    # against the oracle end to end: the codes can differ only where the binary16 outputs differ (both within tolerance)
+    y16ref = yref.astype(np.float16)
+    end_to_end = oracle.requant(y16ref, q_out, osc, ozp)
+    same_y = y.cpu().numpy().view(np.uint16) == y16ref.view(np.uint16)
+    assert np.array_equal(codes.cpu().numpy()[same_y], end_to_end[same_y])
+    assert np.abs(codes.cpu().numpy().astype(np.int32) - end_to_end.astype(np.int32)).max() <= 1
+
+
+def test_gemm_requant_chains_two_layers_without_a_quantizer_kernel(abq):
+    """Layer 1's epilogue writes layer 2's activation codes; layer 2 consumes them directly: two launches in all."""
+    M, K1, N1, N2 = 3, 2048, 1024, 64
+    c1 = synth.make_case(4, 8, M, N1, K1, seed=7701)
+    c2 = synth.make_case(4, 8, M, N2, N1, seed=7702)
+    pw1 = abq.abq_pack_weights(4, to_dev(torch, c1.W), to_dev(torch, c1.w_scale), to_dev(torch, c1.w_zero), FIELDS)
+    pw2 = abq.abq_pack_weights(4, to_dev(torch, c2.W), to_dev(torch, c2.w_scale), to_dev(torch, c2.w_zero), FIELDS)
+    acc1 = oracle.acc_centered(c1.A, c1.W, c1.a_zero, c1.w_zero)
+    y1ref, _ = oracle.dequant(acc1, c1.a_scale, c1.w_scale)
+    _, osc, ozp = oracle.quant_act(y1ref.astype(np.float16), 8)
+    codes, _ = abq.abq_gemm_act_codes_requant(4, 8, M, N1, K1, to_dev(torch, c1.A), to_dev(torch, c1.a_scale), to_dev(torch, c1.a_zero), pw1,
+                                              FIELDS, 8, to_dev(torch, osc), to_dev(torch, ozp), want_y=False)
+    y2, acc2 = abq.abq_gemm_act_codes(4, 8, M, N2, N1, codes, to_dev(torch, osc), to_dev(torch, ozp), pw2, FIELDS, want_acc=True)
+    torch.cuda.synchronize()
+    c2.A, c2.a_scale, c2.a_zero = codes.cpu().numpy(), osc, ozp     # layer 2 against the oracle on the codes it was given
+    check_against_oracle(c2, y2.cpu().numpy(), acc2.cpu().numpy())
+
+
 # ---- the direct decode kernel: every variant (operand rows 1..16, 1/2/4 super-chunks per wave, both activation forms) ------
 @pytest.mark.parametrize("fused", [False, True], ids=["packed", "fused"])
 @pytest.mark.parametrize("r", [1, 2, 4])
