@@ -102,9 +102,10 @@ int abq_pack_weights(int p, int N, int K,
  * The order of that binary32 sum follows the launch plan (how K is split over waves), so the same problem
  * through different entry points agrees to this bound, not to the bit.
  * abq_gemm, abq_gemm_act_codes and abq_gemm_grouped take such a blob with w_layout =
- * ABQ_LAYOUT_FIELDS_G128.  They run it on the streaming (decode) kernel for every M, one pass over the
- * weights per 16 rows of A, and cannot return the raw integer accumulator: acc_i32 must be NULL
- * (ABQ_ERR_LAYOUT otherwise).  abq_pack_weights rejects this layout value (ABQ_ERR_LAYOUT). */
+ * ABQ_LAYOUT_FIELDS_G128.  Up to 16 rows of A run on the streaming (decode) kernel, more rows on a tiled kernel
+ * that flushes its integer accumulators through the group's scale every 128 k.  They cannot return the raw integer
+ * accumulator: acc_i32 must be NULL (ABQ_ERR_LAYOUT otherwise).  abq_pack_weights rejects this layout value
+ * (ABQ_ERR_LAYOUT). */
 int abq_pack_weights_g128(int p, int N, int K,
                           const uint8_t* w_codes, const uint16_t* w_scale_fp16, const int32_t* w_zero,
                           void* packed_out, size_t packed_bytes, void* stream);

@@ -465,7 +465,8 @@ static int gemm_impl(int p, int q, int M, int N, int K, const void* packed_act, 
     GemmArgs g{p, q, M, N, K, (const uint8_t*)packed_act, nullptr, nullptr, nullptr, (const uint8_t*)packed_w, y_fp16, acc_i32,
                workspace, workspace_bytes, rq};
     hipStream_t s = (hipStream_t)stream;
-    if (W.g128) return hip_status(launch_gemm_skinny(g, A, W, s));   // every M: one pass over W per 16 rows
+    if (W.g128)   // per-group weight parameters: the streaming kernel up to 16 rows of A, the tiled per-group kernel above
+        return hip_status(M <= kSkinnyMaxM ? launch_gemm_skinny(g, A, W, s) : launch_gemm_tiled(g, A, W, s));
     if (!choose_fields(can_fields, can_planes, force, p, q, M, N)) return hip_status(launch_gemm_bitserial(g, A, W, s));
     if (streaming_shape(M, N)) return hip_status(launch_decode(g, A, W, s));
     return hip_status(launch_gemm_tiled(g, A, W, s));
@@ -483,7 +484,7 @@ int abq_gemm(int p, int q, int M, int N, int K, const void* packed_act, int a_la
 static bool fused_act_direct(const WeightLayout& W, int force, int p, int q, int M, int N, int K)
 {
     if (!W.has_fields || force == ABQ_USE_PLANES) return false;
-    if (W.g128) return K % 16 == 0;
+    if (W.g128) return M <= kSkinnyMaxM && K % 16 == 0;
     if (!choose_fields(true, W.has_planes, force, p, q, M, N)) return false;
     return streaming_shape(M, N) && K % 16 == 0;
 }

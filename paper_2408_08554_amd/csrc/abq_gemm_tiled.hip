@@ -15,6 +15,7 @@
 #include "../../include/abq.h"
 
 #include <stdlib.h>
+#include <type_traits>
 
 namespace abq {
 
@@ -38,6 +39,7 @@ struct TiledParams {
     Requant rq;               // output codes of the next layer (codes == null: off)
     int M, N, K, Kp, nsuper, ntiles;
     int oa, ow;
+    const u4v* gparams;       // per-group weight parameters (g128 blobs; null otherwise): [ntiles][nsuper][16 channels] records
     int tiles_m, tiles_n;     // workgroup tiles along M and N (1-D grid of tiles_m * tiles_n workgroups)
     int band_m;               // row blocks per band of the tile order (see the kernel's tile mapping)
 };
@@ -340,6 +342,206 @@ __global__ __launch_bounds__(256, (WD == 4 ? 2 : (NTW <= 2 ? (MT == 4 ? 3 : 2) :
     }
 }
 
+
+// ---- per-group weight parameters (groups of 128 along K, Appendix C) in the prefill shape ------------------------
+// Same tiling and operand paths as tiled_kernel (64 rows of A x 64*NTW rows of W per workgroup, weights HBM -> registers
+// one 256-k step ahead, rows of A global -> LDS double buffered), but a 256-k step is two groups of 128 k and every group
+// gets fresh integer accumulators that are flushed through the group's scale into a binary32 tile sum:
+//   sum_k (a' - zc)(w' - z) = c - z * sum_k a' - zc * (sum_k w' - 128 z)          (exact integers)
+// with c the MFMA sum of the stored operands a' = a - oa, w' = w - ow, z the group's zero-point less ow, zc the token's
+// zero-point less oa.  The two operand sums come from the matrix pipe as well: an MFMA of the A operand against ones
+// gives sum_k a' of every row in every column, an MFMA of ones against the B operand gives sum_k w' of every column
+// in every row — both already in the accumulator layout.  k past K holds a' = 0 and w' = z (the packer pads the last
+// group of a g128 blob with its zero-point), so padded k add nothing; groups wholly past K carry scale 0.
+// Then one conversion and one fused multiply-add per element and group: M*N*K/128 of them, which is what bounds
+// this kernel (the vector ALU, not the matrix pipe).
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+template <int P, int NTW, int MT, int PH>
+__device__ __forceinline__ void step_g128(const u4v (*w)[phase_regs(P)], const u4v* gq, const uint8_t* a_buf, int r, int G,
+                                          const v4i* zc, v4f (*facc)[NTW])
+{
+    const v4i ones{0x01010101, 0x01010101, 0x01010101, 0x01010101}, zero4{0, 0, 0, 0};
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {                      // group 2*PH + j of the super-chunk
+        v4i c[MT][NTW], asum[MT], wsum[NTW];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            asum[mt] = zero4;
+#pragma unroll
+            for (int nt = 0; nt < NTW; ++nt) c[mt][nt] = zero4;
+        }
+#pragma unroll
+        for (int nt = 0; nt < NTW; ++nt) wsum[nt] = zero4;
+        auto slice = [&](auto SLC) {
+            constexpr int SL = decltype(SLC)::value;   // slice inside the super-chunk
+            v4i aop[MT];
+            read_a_operands<MT>(a_buf, r, G, SL & 3, aop);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) asum[mt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[mt], ones, asum[mt], 0, 0, 0);
+#pragma unroll
+            for (int nt = 0; nt < NTW; ++nt) {
+                const v4i bop = merged_operand<P, SL>(w[nt]);
+                wsum[nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ones, bop, wsum[nt], 0, 0, 0);
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) c[mt][nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[mt], bop, c[mt][nt], 0, 0, 0);
+            }
+        };
+        if (j == 0) { slice(std::integral_constant<int, 4 * PH + 0>{}); slice(std::integral_constant<int, 4 * PH + 1>{}); }
+        else { slice(std::integral_constant<int, 4 * PH + 2>{}); slice(std::integral_constant<int, 4 * PH + 3>{}); }
+        const int gj = 2 * PH + j;
+#pragma unroll
+        for (int nt = 0; nt < NTW; ++nt) {
+            const int z = ((int)(gq[nt].z << (24 - 8 * gj))) >> 24;
+            const uint32_t sbits = (gj < 2 ? gq[nt].x : gq[nt].y) >> (16 * (gj & 1));
+            const float sc = __half2float(__ushort_as_half((unsigned short)(sbits & 0xFFFFu)));
+            const int wz = wsum[nt].x - 128 * z;       // (every row of wsum holds the column's sum)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+                for (int reg = 0; reg < 4; ++reg) {
+                    const int t = c[mt][nt][reg] - z * asum[mt][reg] - zc[mt][reg] * wz;
+                    facc[mt][nt][reg] = fmaf((float)t, sc, facc[mt][nt][reg]);
+                }
+            }
+        }
+    }
+}
+
+template <int P, int NTW>
+__global__ __launch_bounds__(256, 2) void tiled_g128_kernel(TiledParams prm)
+{
+    constexpr int MT = 4;
+    constexpr int kBM = MT * 16, kBN = 4 * NTW * kTileN;
+    __shared__ __align__(16) uint8_t lds_a0[kBM * kARow];
+    __shared__ __align__(16) uint8_t lds_a1[kBM * kARow];
+    __shared__ RowParams par_a[kBM];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int r = lane & 15, G = lane >> 4;
+    // tile order: as in tiled_kernel (a contiguous run of the banded order per XCD)
+    const int nwg = prm.tiles_m * prm.tiles_n;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int per = nwg >> 3, rem = nwg & 7;
+    const int vid = xcd * per + min(xcd, rem) + slot;
+    const int band = vid / (prm.band_m * prm.tiles_n), in_band = vid - band * prm.band_m * prm.tiles_n;
+    const int band_rows = min(prm.band_m, prm.tiles_m - band * prm.band_m);
+    const int m_blk = band * prm.band_m + in_band % band_rows, n_blk = in_band / band_rows;
+    const int m0 = m_blk * kBM, n0 = n_blk * kBN;
+    const int tile0 = n_blk * (kBN / kTileN) + wave * NTW;
+
+    u4v wa[NTW][phase_regs(P)], wb[NTW][phase_regs(P)], gq[NTW], gq_next[NTW];
+    auto load_records = [&](int sc, u4v* out) {   // the super-chunk's group parameters of this lane's channel, per tile
+#pragma unroll
+        for (int nt = 0; nt < NTW; ++nt)
+            out[nt] = prm.gparams[((size_t)min(tile0 + nt, prm.ntiles - 1) * prm.nsuper + sc) * 16 + r];
+    };
+    load_tiles<P, NTW>(prm, tile0, 0, 0, lane, wa);
+    load_records(0, gq);
+    if (tid < kBM) par_a[tid] = prm.aparams[min(m0 + tid, prm.M - 1)];
+
+    unsigned a_goff[MT];
+#pragma unroll
+    for (int u = 0; u < MT; ++u) {
+        const int row = 4 * (wave * MT + u) + (lane >> 4);
+        const int vec = (lane & 15) ^ (row & 15);
+        a_goff[u] = (unsigned)(min(m0 + row, prm.M - 1) - m0) * (unsigned)prm.Kp + vec * 16;
+    }
+    const int8_t* a_tile = prm.a_codes + (size_t)m0 * prm.Kp;
+    auto a_prefetch = [&](int step, uint8_t* buf) {
+        const int8_t* base = a_tile + (size_t)step * kStepK;
+#pragma unroll
+        for (int u = 0; u < MT; ++u)
+            __builtin_amdgcn_global_load_lds((const void*)(base + a_goff[u]),
+                                             (__attribute__((address_space(3))) void*)(buf + (wave * MT + u) * 1024), 16, 0, 0);
+    };
+    v4f facc[MT][NTW];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NTW; ++nt) facc[mt][nt] = v4f{0.f, 0.f, 0.f, 0.f};
+
+    a_prefetch(0, lds_a0);
+    __syncthreads();
+    // zero-points of this lane's accumulator rows, less oa
+    v4i zc[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int reg = 0; reg < 4; ++reg) zc[mt][reg] = par_a[mt * 16 + 4 * G + reg].zero - prm.oa;
+
+    const int nsteps = prm.nsuper * 2;
+    for (int sc = 0; sc < prm.nsuper; ++sc) {
+        const int scn = min(sc + 1, prm.nsuper - 1);
+        {
+            load_tiles<P, NTW>(prm, tile0, sc, 1, lane, wb);
+            load_records(scn, gq_next);
+            a_prefetch(2 * sc + 1, lds_a1);
+            step_g128<P, NTW, MT, 0>(wa, gq, lds_a0, r, G, zc, facc);
+            __syncthreads();
+        }
+        {
+            load_tiles<P, NTW>(prm, tile0, scn, 0, lane, wa);
+            a_prefetch(min(2 * sc + 2, nsteps - 1), lds_a0);
+            step_g128<P, NTW, MT, 1>(wb, gq, lds_a1, r, G, zc, facc);
+            __syncthreads();
+        }
+#pragma unroll
+        for (int nt = 0; nt < NTW; ++nt) gq[nt] = gq_next[nt];
+    }
+
+    // epilogue: Y = half(a_scale * sum over groups), rows leave in 16-byte pieces through LDS as in tiled_kernel
+    __syncthreads();
+    constexpr int kWCols = NTW * kTileN;
+    uint16_t* stage = reinterpret_cast<uint16_t*>((wave < 2 ? lds_a0 : lds_a1) + (wave & 1) * (kBM * kWCols * 2));
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+        for (int reg = 0; reg < 4; ++reg) {
+            const int ml = mt * 16 + 4 * G + reg;
+            const float sa = par_a[ml].scale;
+#pragma unroll
+            for (int nt = 0; nt < NTW; ++nt) {
+                const float v = sa * facc[mt][nt][reg];
+                uint32_t h;
+                asm("v_cvt_f16_f32 %0, %1" : "=v"(h) : "v"(v));
+                stage[ml * kWCols + nt * 16 + r] = (uint16_t)h;
+            }
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    constexpr int kPieces = kWCols / 8;
+    const bool vec_ok = (prm.N & 7) == 0;
+#pragma unroll
+    for (int it = 0; it < kBM * kPieces / 64; ++it) {
+        const int idx = it * 64 + lane;
+        const int ml = idx / kPieces, piece = idx % kPieces;
+        const int m = m0 + ml, n = n0 + wave * kWCols + piece * 8;
+        if (m < prm.M && n < prm.N) {
+            const uint4 v = *reinterpret_cast<const uint4*>(stage + ml * kWCols + piece * 8);
+            uint16_t* dst = prm.y + (size_t)m * prm.N + n;
+            if (vec_ok && n + 8 <= prm.N) {
+                *reinterpret_cast<uint4*>(dst) = v;
+            } else {
+                const uint32_t w4[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (n + e < prm.N) dst[e] = (uint16_t)(w4[e >> 1] >> (16 * (e & 1)));
+            }
+        }
+    }
+}
+
+template <int P>
+static hipError_t launch_g128_p(const TiledParams& prm, int ntw, dim3 grid, hipStream_t s)
+{
+    if (ntw == 1) tiled_g128_kernel<P, 1><<<grid, 256, 0, s>>>(prm);
+    else tiled_g128_kernel<P, 2><<<grid, 256, 0, s>>>(prm);
+    return hipGetLastError();
+}
+
 template <int P, int NTW, int MT>
 static hipError_t launch_shape(const TiledParams& prm, dim3 grid, int cus, int plan_wd, hipStream_t s)
 {
@@ -390,6 +592,30 @@ hipError_t launch_gemm_tiled(const GemmArgs& g, const ActLayout& A, const Weight
     prm.ntiles = W.NT;
     prm.oa = (g.q == 8) ? 128 : 0;
     prm.ow = (g.p == 8) ? 128 : 0;
+    prm.gparams = W.g128 ? (const u4v*)(g.w_blob + W.off_gparams) : nullptr;
+    if (W.g128) {
+        // per-group weight parameters: 64 rows of A against 128 (or, for few workgroups, 64) rows of W per workgroup
+        int cus_g = 256, dev_g = 0;
+        if (hipGetDevice(&dev_g) != hipSuccess || hipDeviceGetAttribute(&cus_g, hipDeviceAttributeMultiprocessorCount, dev_g) != hipSuccess || cus_g <= 0) cus_g = 256;
+        const long wg2 = (long)((g.M + 63) / 64) * ((g.N + 127) / 128);
+        const int ntw_g = 2 * wg2 >= 3L * cus_g ? 2 : 1;
+        prm.tiles_m = (g.M + 63) / 64;
+        prm.tiles_n = (g.N + 64 * ntw_g - 1) / (64 * ntw_g);
+        const int cap = (g.p <= 4 ? 512 : 1024) / 64;
+        const int bands = (prm.tiles_m + cap - 1) / cap;
+        prm.band_m = (prm.tiles_m + bands - 1) / bands;
+        dim3 grid_g((unsigned)(prm.tiles_m * prm.tiles_n));
+        switch (g.p) {
+            case 1: return launch_g128_p<1>(prm, ntw_g, grid_g, s);
+            case 2: return launch_g128_p<2>(prm, ntw_g, grid_g, s);
+            case 3: return launch_g128_p<3>(prm, ntw_g, grid_g, s);
+            case 4: return launch_g128_p<4>(prm, ntw_g, grid_g, s);
+            case 5: return launch_g128_p<5>(prm, ntw_g, grid_g, s);
+            case 6: return launch_g128_p<6>(prm, ntw_g, grid_g, s);
+            case 7: return launch_g128_p<7>(prm, ntw_g, grid_g, s);
+            default: return launch_g128_p<8>(prm, ntw_g, grid_g, s);
+        }
+    }
     // Tile shape (rows of A x rows of W per workgroup), measured on LLaMA-7B/13B prefill shapes: 128x128
     // while it yields at least 1.5 workgroups per CU (two or three share a CU), else 64x128, else 64x64.
     // Narrow weights (p <= 4) with M >= 1024 do better with 64 rows of A against 256 (or 128) rows of W: the

@@ -869,6 +869,35 @@ def test_config5_sweep_samples(abq, p, q, shape_idx, m_idx):
     check_sampled(c, y, acc)
 
 
+# ---- per-group weight parameters in the prefill shape (the tiled per-group kernel, M > 16) --------------------------
+@pytest.mark.parametrize("fused", [False, True], ids=["packed", "fused"])
+@pytest.mark.parametrize("M,N,K", [(128, 300, 2048), (512, 1000, 4096), (2048, 256, 1024), (70, 130, 1000), (17, 64, 127),
+                                   (200, 4100, 640)])
+@pytest.mark.parametrize("p,q", [(1, 8), (2, 8), (3, 5), (4, 4), (4, 8), (6, 6), (7, 3), (8, 8)])
+def test_g128_prefill_shapes(abq, p, q, M, N, K, fused):
+    if (M, N, K) in ((512, 1000, 4096), (2048, 256, 1024), (200, 4100, 640)) and (p, q) not in ((2, 8), (4, 8), (8, 8), (3, 5)):
+        pytest.skip("the large shapes run for four width pairs")
+    c = synth.make_case(p, q, M, N, K, seed=synth.case_seed(10, p, q, M % 97, N % 89), name=f"g128 prefill W{p}A{q} {M}x{N}x{K}")
+    say(c.name)
+    sh, zg = synth.group_quant_params(c)
+    check_g128(c, sh, zg, run_g128(abq, c, sh, zg, fused))
+
+
+def test_g128_prefill_exact_when_the_float_sum_is_exact(abq):
+    """Power-of-two scales and small codes: every product and partial sum is exact in binary32, so the tiled per-group
+    kernel must return the oracle's binary16 values bit for bit."""
+    M, N, K = 96, 80, 1024
+    c = synth.make_case(2, 4, M, N, K, seed=4242, name="g128 prefill exact")
+    rng = np.random.Generator(np.random.PCG64(5))
+    G = (K + 127) // 128
+    sh = (2.0 ** rng.integers(-6, -2, size=(N, G))).astype(np.float16).view(np.uint16)
+    zg = rng.integers(0, 4, size=(N, G)).astype(np.int32)
+    c.a_scale = (2.0 ** rng.integers(-8, -4, size=M)).astype(np.float32)
+    y = run_g128(abq, c, sh, zg, False)
+    _, y16ref = oracle.dequant_grouped(c.A, c.W, c.a_zero, c.a_scale, zg, sh, gs=128)
+    assert np.array_equal(y.view(np.uint16), y16ref)
+
+
 # ---- ReQuant fused into the matmul epilogue (the consumer side of Fig. 3b) --------------------------------------
 @pytest.mark.parametrize("p,q,q_out,M,N,K,layout", [(4, 8, 8, 1, 300, 4096, FIELDS),      # direct decode kernel
                                                     (2, 8, 4, 7, 70, 1552, FIELDS),       # direct, ragged
