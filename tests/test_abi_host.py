@@ -100,7 +100,8 @@ def test_g128_pack_rejects_and_size_query():
     assert gemm(lib, al=B.ABQ_LAYOUT_PLANES, wl=G128) == B.ABQ_ERR_LAYOUT
     assert gemm_fused(lib, wl=G128, acc=A16) == B.ABQ_ERR_LAYOUT
     q = lib.abq_gemm_act_codes_workspace_bytes
-    assert q(4, 8, 1, 4096, 4096, G128) == 0 and q(4, 8, 300, 4096, 4096, G128) == 0      # one launch for every M
+    assert q(4, 8, 1, 4096, 4096, G128) == 0 and q(4, 8, 16, 4096, 4096, G128) == 0       # one launch up to 16 rows
+    assert q(4, 8, 300, 4096, 4096, G128) == lib.abq_packed_act_bytes(8, 300, 4096, B.ABQ_LAYOUT_FIELDS)   # above: pack + tiled per-group kernel
     assert q(4, 8, 2, 64, 1000, G128) == lib.abq_packed_act_bytes(8, 2, 1000, B.ABQ_LAYOUT_FIELDS)   # K not a multiple of 16
 
 
