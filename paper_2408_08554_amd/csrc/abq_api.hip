@@ -364,20 +364,31 @@ static bool streaming_shape(int M, int N)
 }
 
 // The two decode kernels (both on field-packed operands, M <= 16).  The direct kernel (A operand loaded straight into
-// registers, every load of a wave up front, no ring) is ahead while its operand loads stay few against the weight
-// loads; the streaming kernel (A staged in LDS once per workgroup and shared by all the tiles it walks) is ahead for
-// many rows of A over a long stream.  Measured on LLaMA-7B/13B shapes (W2/W4/W8, M = 1..16):
-//   M <= 4: direct everywhere (W4A8 M = 4 5120 -> 13824: 8.5 vs 11.0 us);
-//   streams up to 16 MiB: direct for every M <= 16 (W4A8 4096^2 M = 16: 4.9 vs 6.2 us; W2A8 M = 8 11008 -> 4096: 6.1 vs 7.9);
-//   M <= 8 with p <= 4 and K <= 8192: direct (W4A8 M = 8 5120 -> 13824: 10.3 vs 10.5 us);
-//   otherwise streaming (W4A8 M = 16 5120 -> 13824: 15.8 vs 12.3 us; W8A8 M = 8: 15.5 vs 13.3).
+// registers, every load of a wave up front, no ring, one workgroup per 16-channel tile) is ahead while its operand loads
+// stay few against the weight loads; the streaming kernel (A staged in LDS once per workgroup and shared by all the tiles
+// it walks, a ring of weight loads) is ahead for many rows of A over many tiles and for the longest streams.  The rule
+// follows the launch-plan search over LLaMA-7B/13B shapes (p = 2, 3, 4, 6, 8; M = 1, 4, 8, 16; direct / streaming in us):
+//   M <= 4: direct (W4A8 M = 4 13824 ch: 8.6 / 11.2; W3A8 M = 1 11008 ch: 5.4 / 8.2), except
+//     p = 8 over more than 48 MiB (13824 x 5120, M = 1: 14.7 / 13.0; M = 4: 15.7 / 13.4) and
+//     p >= 5 with K > 12288 (W6A8 5120 x 13824: 14.5 / 13.0; W8A8: 16.8 / 14.6);
+//   4 < M <= 16 with K > 12288: streaming (W4A8 M = 8: 14.2 / 12.3);
+//   4 < M <= 16, at most one tile per CU: direct at every width (4096 ch, K = 11008, M = 8: W3A8 7.1 / 9.1, W6A8 9.3 / 11.4,
+//     W8A8 10.4 / 11.5; M = 16: W4A8 9.8 / 11.7, W2A8 8.6 / 11.5);
+//   4 < M <= 8, more tiles: direct for the single-group widths 1, 2, 4 (W4A8 13824 ch: 10.2 / 10.9; W2A8: 8.8 / 10.2),
+//     streaming for the others (W3A8 13824 ch: 14.1 / 11.8; W6A8: 14.3 / 12.4);
+//   8 < M <= 16, more tiles: streaming (W2A8 11008 ch: 8.9 / 8.0; W4A8: 10.0 / 8.7).
 // A plan-table entry can force either (direct_r = -1: streaming; 1, 2, 4: direct with that many super-chunks per wave).
 static bool direct_by_rule(int p, int M, int nsuper, const WeightLayout& W)
 {
-    if (M <= 4) return true;
-    const size_t stream = (size_t)p * W.NT * kTileN * (size_t)nsuper * kSuperK / 8;
-    if (stream <= ((size_t)16 << 20)) return true;
-    return M <= 8 && p <= 4 && nsuper <= 16;
+    const bool long_k = nsuper > 24;
+    if (M <= 4) {
+        const size_t stream = (size_t)p * W.NT * kTileN * (size_t)nsuper * kSuperK / 8;
+        if (p == 8 && stream > ((size_t)48 << 20)) return false;
+        return !(p >= 5 && long_k);
+    }
+    if (long_k) return false;
+    if (W.NT <= num_cus()) return true;
+    return M <= 8 && (p == 1 || p == 2 || p == 4);
 }
 static bool choose_direct(const GemmArgs& g, const ActLayout& A, const WeightLayout& W, DirectPlan* pl)
 {

@@ -62,6 +62,15 @@ constexpr int dmin(int a, int b) { return a < b ? a : b; }
 
 // Fewest operand rows per slice set for weight width p (every width takes a single row).
 __host__ __device__ constexpr int direct_min_rows(int p) { return p >= 1 ? 1 : 1; }
+// Which (weight width, operand rows, super-chunks per wave) variants exist: those the kernel's 128 registers hold
+// without spilling (the kernel runs up to sixteen waves per workgroup).  Two super-chunks per wave spill at p = 7 and,
+// with sixteen operand rows, at every width that has two plane groups or eight bits; four fit only single-group widths
+// up to four bits with at most four operand rows.  (A spilling variant is 2x slower: measured at p = 3, R = 4.)
+__host__ __device__ constexpr bool direct_has(int p, int MR, int R)
+{
+    const bool narrow_single_group = p == 1 || p == 2 || p == 4;
+    return R == 1 || (R == 2 && p != 7 && (MR < 16 || narrow_single_group)) || (R == 4 && narrow_single_group && MR <= 4);
+}
 
 // Field t of a b-bit group as a signed-byte MFMA operand dword, and the shift that undoes its scale (as in the
 // streaming kernel: the field that would touch the byte's sign bit is taken one bit lower, or as weight -128).
@@ -357,10 +366,9 @@ static hipError_t direct_launch_mr(const DirectParams& gp, int R, bool raw, unsi
 {
     if constexpr (MR < direct_min_rows(P)) return hipErrorInvalidValue;
     else {
-        // (four super-chunks per wave only where the registers hold them: narrow weights, at most four operand rows)
         if (R == 1) return direct_launch_r<P, MR, 1>(gp, raw, grid, waves, s);
-        if (R == 2) return direct_launch_r<P, MR, 2>(gp, raw, grid, waves, s);
-        if constexpr (P <= 4 && MR <= 4) { if (R == 4) return direct_launch_r<P, MR, 4>(gp, raw, grid, waves, s); }
+        if constexpr (direct_has(P, MR, 2)) { if (R == 2) return direct_launch_r<P, MR, 2>(gp, raw, grid, waves, s); }
+        if constexpr (direct_has(P, MR, 4)) { if (R == 4) return direct_launch_r<P, MR, 4>(gp, raw, grid, waves, s); }
         return hipErrorInvalidValue;
     }
 }

@@ -134,6 +134,7 @@ bool gemm_grouped_fits(int M, int count, const GemmArgs* probs, const ActLayout*
                        size_t* lds_bytes);
 hipError_t launch_gemm_grouped(int p, int M, int count, const GemmArgs* probs, const ActLayout* A, const WeightLayout* W,
                                int waves, size_t lds_bytes, hipStream_t s);
+int num_cus();   // compute units of the current device (cached)
 // The direct decode kernel (few rows of A): plan = operand rows per slice set, super-chunks per wave, waves per workgroup.
 struct DirectPlan { int MR, R, S; };
 bool direct_plan(int p, int M, int nsuper, int forced_r, DirectPlan* out);   // false: the problem does not fit this kernel

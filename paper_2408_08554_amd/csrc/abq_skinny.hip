@@ -24,7 +24,7 @@ namespace abq {
 
 static std::atomic<int> g_num_cus{0};   // a cached device property (every thread would store the same value)
 
-static int num_cus()
+int num_cus()
 {
     int n = g_num_cus.load(std::memory_order_relaxed);
     if (n == 0) {
