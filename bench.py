@@ -33,9 +33,9 @@ INT8_MFMA_PEAK_TOPS = 5000.0    # MI355X published dense int8
 # run).  Every summary carries two machine-readable lines, `traffic_bytes_per_launch: N` and `kernel_avg_ns: T`;
 # the JSON line names the file the figure comes from and says whether this run's kernel time agrees with it.
 PROFILE_OF = {
-    "C2 W4A8 GEMV 4096x4096": "skinny_kernel_w4a8_gemv_m1_k4096_n4096.md",
-    "C3 W2A8 GEMV M=1 11008->4096": "skinny_kernel_w2a8_gemv_m1_k11008_n4096.md",
-    "C3 W2A8 GEMV M=8 11008->4096": "skinny_kernel_w2a8_gemv_m8_k11008_n4096.md",
+    "C2 W4A8 GEMV 4096x4096": "direct_kernel_w4a8_gemv_m1_k4096_n4096.md",
+    "C3 W2A8 GEMV M=1 11008->4096": "direct_kernel_w2a8_gemv_m1_k11008_n4096.md",
+    "C3 W2A8 GEMV M=8 11008->4096": "direct_kernel_w2a8_gemv_m8_k11008_n4096.md",
     "C5 W8A8 M=1 K=5120 N=13824": "skinny_kernel_w8a8_gemv_m1_k5120_n13824.md",
     "C2 W4A8 GEMV 4096x4096 g128": "skinny_kernel_w4a8_g128_gemv_m1_k4096_n4096.md",
     "C5 W4A8 M=1 K=5120 N=13824 g128": "skinny_kernel_w4a8_g128_gemv_m1_k5120_n13824.md",
@@ -43,9 +43,10 @@ PROFILE_OF = {
     "C4 W6A6 GEMM M=128 4096->11008": "tiled_kernel_w6a6_gemm_m128_k4096_n11008.md",
     "C5 W4A4 M=2048 K=5120 N=13824": "tiled_kernel_w4a4_gemm_m2048_k5120_n13824.md",
     "C5 W2A8 M=2048 K=5120 N=13824": "tiled_kernel_w2a8_gemm_m2048_k5120_n13824.md",
-    ("block", 4, 8, 1): "grouped_kernel_w4a8_m1_llama7b_block.md",
+    "C5 W4A4 M=2048 K=5120 N=13824 g128": "tiled_g128_kernel_w4a4_gemm_m2048_k5120_n13824.md",
+    ("block", 4, 8, 1): "direct_kernel_grouped_w4a8_m1_llama7b_block.md",
     ("block", 8, 8, 1): "grouped_kernel_w8a8_m1_llama7b_block.md",
-    ("block", 2, 8, 1): "grouped_kernel_w2a8_m1_llama7b_block.md",
+    ("block", 2, 8, 1): "direct_kernel_grouped_w2a8_m1_llama7b_block.md",
 }
 
 

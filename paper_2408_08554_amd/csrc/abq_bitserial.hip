@@ -110,8 +110,17 @@ __global__ __launch_bounds__(256) void bitserial_rows_kernel(BitSerialParams prm
 {
     using SH = RowsShape<P, Q>;
     constexpr int BM = SH::BM, ND = SH::ND, NC = SH::NC;
-    const int n0 = blockIdx.x * (256 * NC) + threadIdx.x;  // this lane's channels: n0, n0 + 256, ...
-    const int m0 = blockIdx.y * BM;
+    // Workgroup b runs on XCD b % 8 (round-robin dispatch) and each XCD has its own L2: every XCD gets a contiguous run
+    // of the order (channel block, row block) with the row blocks fastest, so that the workgroups that read the same
+    // weight planes run next to each other on one XCD and the planes leave HBM once.  (With the channel blocks fastest
+    // every row block streamed all of W again: measured 1.39 GB of fetches for 17.7 MB of planes at W2A2 M = 256.)
+    const int row_blocks = (prm.M + BM - 1) / BM;
+    const int nwg = gridDim.x;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int per = nwg >> 3, rem = nwg & 7;
+    const int vid = xcd * per + min(xcd, rem) + slot;
+    const int n0 = (vid / row_blocks) * (256 * NC) + threadIdx.x;  // this lane's channels: n0, n0 + 256, ...
+    const int m0 = (vid % row_blocks) * BM;
     const uint4* __restrict__ wp = prm.w_planes;
     const uint4* __restrict__ ap = prm.a_planes;
     const int Kq = prm.Kq;
@@ -205,7 +214,7 @@ static hipError_t launch_pq(const BitSerialParams& prm, hipStream_t s)
 {
     if (prm.M >= 8) {
         constexpr int BM = RowsShape<P, Q>::BM, CH = 256 * RowsShape<P, Q>::NC;
-        bitserial_rows_kernel<P, Q><<<dim3((unsigned)((prm.N + CH - 1) / CH), (unsigned)((prm.M + BM - 1) / BM)), 256, 0, s>>>(prm);
+        bitserial_rows_kernel<P, Q><<<dim3((unsigned)(((prm.N + CH - 1) / CH) * ((prm.M + BM - 1) / BM))), 256, 0, s>>>(prm);
         return hipGetLastError();
     }
     const unsigned gx = (unsigned)((prm.N + 15) / 16);
