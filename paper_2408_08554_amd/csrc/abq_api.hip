@@ -369,7 +369,8 @@ static bool streaming_shape(int M, int N)
 // it walks, a ring of weight loads) is ahead for many rows of A over many tiles and for the longest streams.  The rule
 // follows the launch-plan search over LLaMA-7B/13B shapes (p = 2, 3, 4, 6, 8; M = 1, 4, 8, 16; direct / streaming in us):
 //   M <= 4: direct (W4A8 M = 4 13824 ch: 8.6 / 11.2; W3A8 M = 1 11008 ch: 5.4 / 8.2), except
-//     p = 8 over more than 48 MiB (13824 x 5120, M = 1: 14.7 / 13.0; M = 4: 15.7 / 13.4) and
+//     p = 8 over more than 48 MiB (13824 x 5120, M = 1: 14.7 / 13.0; M = 4: 15.7 / 13.4), p = 5 and 7 over more than
+//     40 MiB (W7A8 13824 x 5120 M = 1: 14.9 / 13.2, M = 4: 16.8 / 13.7; W5A8: 11.3 / 10.8, 13.8 / 12.5; W6A8 stays: 10.6 / 11.2) and
 //     p >= 5 with K > 12288 (W6A8 5120 x 13824: 14.5 / 13.0; W8A8: 16.8 / 14.6);
 //   4 < M <= 16 with K > 12288: streaming (W4A8 M = 8: 14.2 / 12.3);
 //   4 < M <= 16, at most one tile per CU: direct at every width (4096 ch, K = 11008, M = 8: W3A8 7.1 / 9.1, W6A8 9.3 / 11.4,
@@ -384,6 +385,7 @@ static bool direct_by_rule(int p, int M, int nsuper, const WeightLayout& W)
     if (M <= 4) {
         const size_t stream = (size_t)p * W.NT * kTileN * (size_t)nsuper * kSuperK / 8;
         if (p == 8 && stream > ((size_t)48 << 20)) return false;
+        if ((p == 5 || p == 7) && stream > ((size_t)40 << 20)) return false;   // (widths with a 1-bit group beside wider ones)
         return !(p >= 5 && long_k);
     }
     if (long_k) return false;
