@@ -226,8 +226,12 @@ __global__ __launch_bounds__(256, (WD == 4 ? 2 : (NTW <= 2 ? (MT == 4 ? 3 : 2) :
 #pragma unroll
         for (int nt = 0; nt < NTW; ++nt) acc[mt][nt] = v4i{0, 0, 0, 0};
 
+    // A wave's direct loads into an LDS buffer have to have landed before the wave enters the barrier behind which the other
+    // waves read that buffer.  The barrier's own fence covers LDS instructions, not these loads, so the wait is written out
+    // here and in the loop (the compiler usually places its own wait for the weight registers there too, but need not).
     a_prefetch(0, lds_a0);
-    __syncthreads();   // (the compiler waits for the direct loads before the barrier)
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
 
     if constexpr (WD == 4) {
         // two super-chunks per iteration, four steps; in every step the A tile of the next step is requested
@@ -277,12 +281,14 @@ __global__ __launch_bounds__(256, (WD == 4 ? 2 : (NTW <= 2 ? (MT == 4 ? 3 : 2) :
             load_tiles<P, NTW>(prm, tile0, sc, 1, lane, wb);
             a_prefetch(2 * sc + 1, lds_a1);
             step_mfma<P, NTW, MT, 0>(wa, lds_a0, r, G, acc);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
         }
         {   // step 2*sc+1: weights in wb, A in buffer 1
             load_tiles<P, NTW>(prm, tile0, scn, 0, lane, wa);
             a_prefetch(min(2 * sc + 2, nsteps - 1), lds_a0);
             step_mfma<P, NTW, MT, 1>(wb, lds_a1, r, G, acc);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
         }
     }
@@ -462,6 +468,7 @@ __global__ __launch_bounds__(256, 2) void tiled_g128_kernel(TiledParams prm)
         for (int nt = 0; nt < NTW; ++nt) facc[mt][nt] = v4f{0.f, 0.f, 0.f, 0.f};
 
     a_prefetch(0, lds_a0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // (a wave's direct loads land before it enters a barrier, here and below: see tiled_kernel)
     __syncthreads();
     // zero-points of this lane's accumulator rows, less oa
     v4i zc[MT];
@@ -478,12 +485,14 @@ __global__ __launch_bounds__(256, 2) void tiled_g128_kernel(TiledParams prm)
             load_records(scn, gq_next);
             a_prefetch(2 * sc + 1, lds_a1);
             step_g128<P, NTW, MT, 0>(wa, gq, lds_a0, r, G, zc, facc);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
         }
         {
             load_tiles<P, NTW>(prm, tile0, scn, 0, lane, wa);
             a_prefetch(min(2 * sc + 2, nsteps - 1), lds_a0);
             step_g128<P, NTW, MT, 1>(wb, gq, lds_a1, r, G, zc, facc);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
         }
 #pragma unroll
