@@ -122,10 +122,12 @@ __device__ __forceinline__ void step_mfma(const u4v (*w)[phase_regs(P)], const u
     read_a_operands<MT>(a_buf, r, G, 1, a1);
     __builtin_amdgcn_sched_barrier(0);
     slice_mfma<P, NTW, MT, 4 * PH + 0>(w, a0, acc);
+    __builtin_amdgcn_sched_barrier(0);
+    read_a_operands<MT>(a_buf, r, G, 2, a0);      // (travels under the MFMAs of slice 1)
+    __builtin_amdgcn_sched_barrier(0);
     slice_mfma<P, NTW, MT, 4 * PH + 1>(w, a1, acc);
     __builtin_amdgcn_sched_barrier(0);
-    read_a_operands<MT>(a_buf, r, G, 2, a0);
-    read_a_operands<MT>(a_buf, r, G, 3, a1);
+    read_a_operands<MT>(a_buf, r, G, 3, a1);      // (under those of slice 2)
     __builtin_amdgcn_sched_barrier(0);
     slice_mfma<P, NTW, MT, 4 * PH + 2>(w, a0, acc);
     slice_mfma<P, NTW, MT, 4 * PH + 3>(w, a1, acc);
