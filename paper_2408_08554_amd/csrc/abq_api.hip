@@ -337,15 +337,15 @@ static int check_gemm_shape(int p, int q, int M, int N, int K)
 }
 
 // Kernel family for a problem: true = int8-MFMA on field-packed operands, false = bit-serial
-// AND+popcount on the 1-bit planes.  Measured on MI355X (profiles/): the bit-serial kernel wins only
-// for a single token with very narrow operands over many output tiles (M = 1, p <= 2, q <= 4,
-// N >= 8192: 4.7 vs 6.3 us at W1A1 5120->13824), where its shorter fixed path matters more than
-// its 2*q VALU ops per weight word; everywhere else the MFMA path is faster, by up to 200x in prefill.
+// AND+popcount on the 1-bit planes.  Where a blob carries both representations the MFMA path is taken: measured on
+// MI355X over p, q in {1, 2, 4} it is the faster one everywhere (W1A1 M = 1 5120 -> 13824: 4.65 vs 4.58 us, the only
+// near tie; W2A2 5.5 vs 6.1; W1A1 M = 16 9.4 vs 48.9; M = 256 23.5 vs 55.4), and only it runs the fused one-launch
+// decode step.  The literal form runs on blobs that hold nothing but planes, or when forced (ABQ_USE_PLANES).
 static bool choose_fields(bool can_fields, bool can_planes, int force, int p, int q, int M, int N)
 {
+    (void)can_planes; (void)p; (void)q; (void)M; (void)N;
     if (force == ABQ_USE_PLANES) return false;
     if (force == ABQ_USE_FIELDS) return true;
-    if (can_fields && can_planes && M == 1 && p <= 2 && q <= 4 && N >= 8192) return false;
     return can_fields;
 }
 

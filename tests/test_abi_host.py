@@ -186,11 +186,11 @@ def test_gemm_act_codes_rejects_and_workspace_query():
     assert q(4, 8, 1, 4096, 4096, B.ABQ_LAYOUT_FIELDS) == 0
     assert q(2, 8, 8, 4096, 11008, B.ABQ_LAYOUT_AUTO) == 0
     assert q(6, 6, 16, 64, 48, B.ABQ_LAYOUT_BOTH) == 0
+    assert q(1, 1, 1, 13824, 5120, B.ABQ_LAYOUT_BOTH) == 0          # a blob with both representations takes the MFMA path
     # two kernels: the packed activations live in the workspace
     for args in [(4, 8, 1, 4096, 4090, B.ABQ_LAYOUT_FIELDS),      # K not a multiple of 16
                  (6, 6, 128, 11008, 4096, B.ABQ_LAYOUT_FIELDS),   # prefill shape
                  (2, 8, 1, 4096, 4096, B.ABQ_LAYOUT_PLANES),      # bit-serial family
-                 (1, 1, 1, 13824, 5120, B.ABQ_LAYOUT_BOTH),       # auto dispatch picks bit-serial here
                  (4, 8, 1, 4096, 4096, B.ABQ_LAYOUT_BOTH | B.ABQ_USE_PLANES)]:
         p_, q_, M, N, K, wl = args
         assert q(*args) == lib.abq_packed_act_bytes(q_, M, K, wl & 3) + lib.abq_gemm_workspace_bytes(p_, q_, M, N, K)
