@@ -60,8 +60,8 @@ struct DirectParams {
 constexpr int dmax(int a, int b) { return a > b ? a : b; }
 constexpr int dmin(int a, int b) { return a < b ? a : b; }
 
-// Fewest operand rows per slice set for weight width p (every width takes a single row).
-__host__ __device__ constexpr int direct_min_rows(int p) { return p >= 1 ? 1 : 1; }
+// Fewest operand rows per slice set for weight width p: every width takes a single row.
+__host__ __device__ constexpr int direct_min_rows(int) { return 1; }
 // Which (weight width, operand rows, super-chunks per wave) variants exist: those the kernel's 128 registers hold
 // without spilling (the kernel runs up to sixteen waves per workgroup).  Two super-chunks per wave spill at p = 7 and,
 // with sixteen operand rows, at every width that has two plane groups or eight bits; four fit only single-group widths
