@@ -124,7 +124,7 @@ def child_summary(flags):
     try:
         r = subprocess.run(cmd, capture_output=True, text=True, timeout=300)
         d = json.loads([l for l in r.stdout.splitlines() if l.startswith("{")][-1])
-        keep = ("bound", "achieved", "peak", "unit", "frac", "traffic", "traffic_source", "launches", "algorithmic_bytes", "frac_of_plain_read_same_size")
+        keep = ("bound", "achieved", "peak", "unit", "frac", "traffic", "traffic_source", "profile_kernel_us", "profile_agrees", "launches", "algorithmic_bytes", "frac_of_plain_read_same_size")
         return {"workload": d["config"]["workload"], "step": d["config"]["step"], "kernel_us": d["roofline"]["kernel_us_hip_events"],
                 "rotating_bytes": d["config"]["rotating_bytes"], "tops_kernel": d["gemm_only"]["tops"], "weight_gbs_kernel": d["gemm_only"]["weight_gbs"],
                 "roofline": {k: d["roofline"][k] for k in keep if k in d["roofline"]}}
