@@ -394,7 +394,10 @@ static bool direct_by_rule(int p, int M, int nsuper, const WeightLayout& W)
 }
 static bool choose_direct(const GemmArgs& g, const ActLayout& A, const WeightLayout& W, DirectPlan* pl)
 {
-    if (g.M > 16 || W.g128 || !W.has_fields) return false;
+    if (g.M > 16 || !W.has_fields) return false;
+    if (W.g128)   // per-group weight parameters: the direct kernel has a variant for one row of A, one super-chunk per wave and
+                  // p <= 4 (wider weights share accumulators between slices there, which the per-group sums cannot)
+        return g.M == 1 && g.p <= 4 && !g.acc && !g.rq.codes && direct_plan(g.p, 1, A.Kp / kSuperK, 1, pl) && pl->R == 1;
     PlanOverride ov;
     lookup_plan(g.p, g.q, g.M, g.N, g.K, &ov);
     const int env = tuning_env("ABQ_DIRECT_R");
@@ -479,7 +482,7 @@ static int gemm_impl(int p, int q, int M, int N, int K, const void* packed_act, 
                workspace, workspace_bytes, rq};
     hipStream_t s = (hipStream_t)stream;
     if (W.g128)   // per-group weight parameters: the streaming kernel up to 16 rows of A, the tiled per-group kernel above
-        return hip_status(M <= kSkinnyMaxM ? launch_gemm_skinny(g, A, W, s) : launch_gemm_tiled(g, A, W, s));
+        return hip_status(M <= kSkinnyMaxM ? launch_decode(g, A, W, s) : launch_gemm_tiled(g, A, W, s));
     if (!choose_fields(can_fields, can_planes, force, p, q, M, N)) return hip_status(launch_gemm_bitserial(g, A, W, s));
     if (streaming_shape(M, N)) return hip_status(launch_decode(g, A, W, s));
     return hip_status(launch_gemm_tiled(g, A, W, s));

@@ -45,6 +45,7 @@ static void fill_problem(DirectProblem& d, const GemmArgs& g, const ActLayout& A
         d.a_raw = nullptr; d.a_scale = nullptr; d.a_zero = nullptr;
     }
     d.wparams = (const RowParams*)(g.w_blob + W.off_params);
+    d.gparams = W.g128 ? (const u4v*)(g.w_blob + W.off_gparams) : nullptr;
     d.y = g.y; d.acc = g.acc; d.rq = g.rq;
     d.N = g.N; d.K = g.K; d.Kp = A.Kp; d.nsuper = A.Kp / kSuperK;
     d.rsplit = rsplit;

@@ -47,6 +47,7 @@ struct DirectProblem {
     Requant rq;                // output codes of the next layer (codes == null: off)
     int N, K, Kp, nsuper;
     int rsplit;                // super-chunks per wave (<= R): wave w owns [w*rsplit, w*rsplit + rsplit) clipped to nsuper
+    const u4v* gparams;        // per-group weight parameters (g128 blobs; null otherwise): [tiles][nsuper][16 channels] records
 };
 
 struct DirectParams {
@@ -187,9 +188,18 @@ __device__ __forceinline__ void direct_pick(const v4i* accI, int G, int32_t* v)
 // GROUPED: several problems in one grid (the workgroup finds its problem from the tile starts); otherwise problem 0.
 // Either way the problem's descriptor is copied from the kernel arguments in one batch of scalar loads at the top:
 // read field by field where it is used, every first use would wait for a scalar load of its own.
-template <int P, int MR, int R, bool RAW, bool GROUPED>
+// GQ: per-group weight parameters (groups of 128 along K, Appendix C), built for one row of A, one super-chunk per
+// wave (MR = R = 1) and p <= 4.  Then every 64-k slice of the wave's super-chunk has an accumulator of its own (eight slices, eight
+// operand rows), so the integer sum of every group of 128 k is there after the MFMAs without any change to them, and
+// the other eight operand rows, unused at M = 1, are filled with ones: row 8 of accumulator s then holds sum_k w' of slice
+// s for every channel — the operand sum that the activation zero-point needs — for free.  sum_k a' per slice comes from
+// one MFMA of the operand against ones.  Per group: t = c - z * sum a' - zc * (sum w' - 128 z) in exact integers
+// (z: the group's zero-point, zc: the token's, both less the stored offsets; padded k hold a' = 0 and w' = z), then one
+// conversion and one fma with the group's scale; the 16 threads of the epilogue add groups and waves in a fixed order.
+template <int P, int MR, int R, bool RAW, bool GROUPED, bool GQ = false>
 __global__ __launch_bounds__(1024) void direct_kernel(DirectParams gp)
 {
+    static_assert(!GQ || (MR == 1 && R == 1 && P <= 4), "per-group parameters: one row of A, one super-chunk per wave, an accumulator per slice");
     using SH = DirectShape<P, MR, R>;
     constexpr int SL = SH::SL, NQ = SH::NQ, NI = SH::NI;
     constexpr int NV = MR == 1 ? 1 : (MR == 2 ? 2 : 4);             // values per lane after direct_pick
@@ -211,6 +221,7 @@ __global__ __launch_bounds__(1024) void direct_kernel(DirectParams gp)
                  "s"(gp.oa), "s"(gp.ow), "s"(gp.a_mask), "s"(S));
     if constexpr (RAW) asm volatile("" ::"s"(pr.a_raw), "s"(pr.a_scale), "s"(pr.a_zero));
     else asm volatile("" ::"s"(pr.a_codes), "s"(pr.aparams));
+    if constexpr (GQ) asm volatile("" ::"s"(pr.gparams));
     const int M = gp.M, nsuper = pr.nsuper, Kp = pr.Kp;
     const int sc0 = wave * pr.rsplit;
     const int nsc = max(0, min(pr.rsplit, nsuper - sc0));            // this wave's super-chunks (<= R), wave-uniform
@@ -239,6 +250,13 @@ __global__ __launch_bounds__(1024) void direct_kernel(DirectParams gp)
             if (m_l < M && sl < 8 * nsc) v = *reinterpret_cast<const v4i*>(pr.a_codes + (size_t)m_l * Kp + k);
         }
         aq[q] = v;
+    }
+    u4v grec{0, 0, 0, 0};       // GQ: the group record of this lane's channel and this wave's super-chunk
+    int zc_all = 0;             // GQ: the token's zero-point less oa (M = 1: the same for every lane)
+    if constexpr (GQ) {
+        grec = __builtin_nontemporal_load(pr.gparams + ((size_t)tile * nsuper + min(sc0, nsuper - 1)) * 16 + r);
+        if constexpr (RAW) zc_all = pr.a_zero[0] - gp.oa;
+        else zc_all = pr.aparams[0].zero - gp.oa;
     }
     // ---- the weight stream, last in program order: everything above can be waited for while it is in flight.  The
     // loads are unconditional (a wave with fewer than R super-chunks re-reads its last one, or the problem's last one
@@ -270,8 +288,12 @@ __global__ __launch_bounds__(1024) void direct_kernel(DirectParams gp)
         }
     }
 
+    if constexpr (GQ) {
+        // operand rows 8..15 (no slice lives there at MR = R = 1) become rows of ones
+        if (r >= 8) aq[0] = v4i{0x01010101, 0x01010101, 0x01010101, 0x01010101};
+    }
     v4i asum_acc{0, 0, 0, 0};
-    if constexpr (RAW) {   // row sums of the operand bytes, while the weights are still on their way
+    if constexpr (RAW || GQ) {   // row sums of the operand bytes, while the weights are still on their way
         const v4i ones{0x01010101, 0x01010101, 0x01010101, 0x01010101};
 #pragma unroll
         for (int q = 0; q < NQ; ++q) asum_acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(aq[q], ones, asum_acc, 0, 0, 0);
@@ -282,6 +304,46 @@ __global__ __launch_bounds__(1024) void direct_kernel(DirectParams gp)
 #pragma unroll
     for (int i = 0; i < SH::NACC; ++i) acc[i] = v4i{0, 0, 0, 0};
     direct_all_mfma<P, MR, R>(w, aq, acc, nsc);
+
+    if constexpr (GQ) {
+        v4i accS[NI];           // accS[s]: accumulator of slice s, fields and plane groups recombined
+#pragma unroll
+        for (int i = 0; i < NI; ++i) accS[i] = v4i{0, 0, 0, 0};
+        direct_fold<P, MR, R, 0>(acc, accS);
+        if constexpr (SH::NG > 1) direct_fold<P, MR, R, 1>(acc, accS);
+        if constexpr (SH::NG > 2) direct_fold<P, MR, R, 2>(acc, accS);
+        // lane (G, reg) holds operand row 4G + reg: rows 0..7 = slice 4G + reg against itself (the wanted product sum),
+        // rows 8..15 = the ones rows (sum of the weights of slice 4(G-2) + reg).  Either way the lane takes element reg of
+        // accumulator 4(G & 1) + reg and adds the two slices of each group: lanes of G = 0, 1 then hold the product sums of
+        // groups 2G, 2G+1 of their channel, lanes of G = 2, 3 the weight sums of the same groups, 32 lanes further up.
+        int32_t e[4];
+#pragma unroll
+        for (int reg = 0; reg < 4; ++reg) e[reg] = (G & 1) ? accS[4 + reg][reg] : accS[reg][reg];
+        const int c0 = e[0] + e[1], c1 = e[2] + e[3];
+        const int ws0 = __shfl(c0, (lane + 32) & 63), ws1 = __shfl(c1, (lane + 32) & 63);
+        // every column of asum_acc holds the row sums of the operand: this lane's rows are slices 4G .. 4G+3 (G < 2)
+        const int as0 = asum_acc.x + asum_acc.y, as1 = asum_acc.z + asum_acc.w;
+        const int g0 = 2 * (G & 1);                                    // this lane's first group of the super-chunk
+        const int z0 = ((int)(grec.z << (24 - 8 * g0))) >> 24, z1 = ((int)(grec.z << (16 - 8 * g0))) >> 24;
+        const uint32_t sb = (G & 1) ? grec.y : grec.x;                 // the two binary16 scales of groups g0, g0 + 1
+        const float s0 = __half2float(__ushort_as_half((unsigned short)(sb & 0xFFFFu)));
+        const float s1 = __half2float(__ushort_as_half((unsigned short)(sb >> 16)));
+        const int t0g = c0 - z0 * as0 - zc_all * (ws0 - 128 * z0);
+        const int t1g = c1 - z1 * as1 - zc_all * (ws1 - 128 * z1);
+        float f = (float)t0g * s0;
+        f = __builtin_fmaf((float)t1g, s1, f);
+        f += __shfl(f, lane ^ 16);                                      // groups 0, 1 (G = 0) + groups 2, 3 (G = 1): same order in both lanes
+        float* fpart = reinterpret_cast<float*>(red);                  // [wave][channel]
+        if (G == 0) fpart[wave * 16 + r] = f;
+        __syncthreads();
+        if (t0 < 16) {           // (M = 1: one output per channel of the tile); the waves' sums are added in a fixed order
+            const int n = tile * kTileN + t0;
+            float fsum = 0.f;
+            for (int ww = 0; ww < S; ++ww) fsum += fpart[ww * 16 + t0];
+            if (n < pr.N) pr.y[n] = __half_as_ushort(__float2half_rn(pa0.scale * fsum));
+        }
+        return;
+    }
 
     // ---- bit reduction over fields and plane groups, then the rows that belong to each accumulator
     v4i accI[NI];
@@ -341,8 +403,9 @@ __global__ __launch_bounds__(1024) void direct_kernel(DirectParams gp)
     }
 }
 
-inline size_t direct_lds_bytes(int S, int MR)
+inline size_t direct_lds_bytes(int S, int MR, bool gq)
 {
+    if (gq) return (size_t)S * 16 * 4;   // one binary32 partial per wave and channel (MR = 1)
     const int C = MR <= 4 ? 4 : (MR == 8 ? 2 : 1);
     return (size_t)S * MR * 16 * C * 4 + (size_t)S * MR * C * 4;
 }
@@ -350,8 +413,17 @@ inline size_t direct_lds_bytes(int S, int MR)
 template <int P, int MR, int R, bool RAW>
 static hipError_t direct_launch_one(const DirectParams& gp, unsigned grid, int waves, hipStream_t s)
 {
-    if (gp.count > 1) direct_kernel<P, MR, R, RAW, true><<<grid, waves * 64, direct_lds_bytes(waves, MR), s>>>(gp);
-    else direct_kernel<P, MR, R, RAW, false><<<grid, waves * 64, direct_lds_bytes(waves, MR), s>>>(gp);
+    if (gp.d[0].gparams) {   // per-group weight parameters (every problem of a launch is of the same kind)
+        if constexpr (MR == 1 && R == 1 && P <= 4) {
+            if (gp.count > 1) direct_kernel<P, MR, R, RAW, true, true><<<grid, waves * 64, direct_lds_bytes(waves, MR, true), s>>>(gp);
+            else direct_kernel<P, MR, R, RAW, false, true><<<grid, waves * 64, direct_lds_bytes(waves, MR, true), s>>>(gp);
+            return hipGetLastError();
+        } else {
+            return hipErrorInvalidValue;
+        }
+    }
+    if (gp.count > 1) direct_kernel<P, MR, R, RAW, true><<<grid, waves * 64, direct_lds_bytes(waves, MR, false), s>>>(gp);
+    else direct_kernel<P, MR, R, RAW, false><<<grid, waves * 64, direct_lds_bytes(waves, MR, false), s>>>(gp);
     return hipGetLastError();
 }
 
