@@ -397,7 +397,7 @@ static bool choose_direct(const GemmArgs& g, const ActLayout& A, const WeightLay
     if (g.M > 16 || !W.has_fields) return false;
     if (W.g128)   // per-group weight parameters: the direct kernel has a variant for one row of A, one super-chunk per wave and
                   // p <= 4 (wider weights share accumulators between slices there, which the per-group sums cannot)
-        return g.M == 1 && g.p <= 4 && !g.acc && !g.rq.codes && direct_plan(g.p, 1, A.Kp / kSuperK, 1, pl) && pl->R == 1;
+        return gemm_direct_g128_fits(g.p, g.M, g, A, W) && direct_plan(g.p, 1, A.Kp / kSuperK, 1, pl);
     PlanOverride ov;
     lookup_plan(g.p, g.q, g.M, g.N, g.K, &ov);
     const int env = tuning_env("ABQ_DIRECT_R");
@@ -667,6 +667,28 @@ int abq_gemm_grouped(int p, int q, int M, int count, const abq_problem* host_pro
     // they gain: 34.8 vs 33.3 us)
     if (fits && M <= 8 && p < 8 && tuning_env("ABQ_DIRECT_R") >= 0 && gemm_direct_grouped_fits(p, M, count, args.data(), A.data(), W.data()))
         return hip_status(launch_gemm_direct_grouped(p, q, M, count, args.data(), A.data(), W.data(), (hipStream_t)stream));
+    if (fits && W[0].g128 && tuning_env("ABQ_DIRECT_R") >= 0) {
+        // per-group blobs: the members the direct kernel's g128 variant takes (K <= 8192) go there in one launch, the others
+        // to the streaming kernel's grouped launch (LLaMA-7B block W4A8 g128 M = 1: 28.2 us as one streaming launch)
+        std::vector<GemmArgs> a1, a2;
+        std::vector<ActLayout> A1, A2;
+        std::vector<WeightLayout> W1, W2;
+        for (int i = 0; i < count; ++i) {
+            const bool d = gemm_direct_g128_fits(p, M, args[i], A[i], W[i]);
+            (d ? a1 : a2).push_back(args[i]);
+            (d ? A1 : A2).push_back(A[i]);
+            (d ? W1 : W2).push_back(W[i]);
+        }
+        if (!a1.empty()) {
+            if (int e = hip_status(launch_gemm_direct_grouped(p, q, M, (int)a1.size(), a1.data(), A1.data(), W1.data(), (hipStream_t)stream))) return e;
+            if (a2.empty()) return ABQ_OK;
+            if (a2.size() == 1) return hip_status(launch_gemm_skinny(a2[0], A2[0], W2[0], (hipStream_t)stream));   // (a set of one: the single launch's plan)
+            int waves2 = 0;
+            size_t lds2 = 0;
+            if (!gemm_grouped_fits(M, (int)a2.size(), a2.data(), A2.data(), W2.data(), &waves2, &lds2)) return ABQ_ERR_SHAPE;   // (a subset of a set that fits)
+            return hip_status(launch_gemm_grouped(p, M, (int)a2.size(), a2.data(), A2.data(), W2.data(), waves2, lds2, (hipStream_t)stream));
+        }
+    }
     if (fits) return hip_status(launch_gemm_grouped(p, M, count, args.data(), A.data(), W.data(), waves, lds, (hipStream_t)stream));
     if (raw) {   // every problem's workspace need is checked before the first launch
         size_t need = 0;

@@ -86,6 +86,15 @@ bool gemm_direct_grouped_fits(int p, int M, int count, const GemmArgs* probs, co
     return true;
 }
 
+// Per-group (g128) blobs: the direct kernel's variant takes one row of A, p <= 4 and at most 16 super-chunks of K.
+bool gemm_direct_g128_fits(int p, int M, const GemmArgs& g, const ActLayout& A, const WeightLayout& W)
+{
+    DirectPlan pl;
+    if (!W.g128 || !W.has_fields || M != 1 || p > 4 || g.acc || g.rq.codes) return false;
+    if (g.a_raw ? (g.K % 16 != 0) : !A.has_fields) return false;
+    return direct_plan(p, 1, A.Kp / kSuperK, 1, &pl) && pl.R == 1;
+}
+
 hipError_t launch_gemm_direct_grouped(int p, int q, int M, int count, const GemmArgs* probs, const ActLayout* A, const WeightLayout* W, hipStream_t s)
 {
     // Problems with the same plan (super-chunks per wave, waves per workgroup) share a launch, eight at most: one
@@ -93,7 +102,7 @@ hipError_t launch_gemm_direct_grouped(int p, int q, int M, int count, const Gemm
     std::vector<DirectPlan> plans(count);
     std::vector<char> done(count, 0);
     for (int i = 0; i < count; ++i)
-        if (!direct_plan(p, M, A[i].Kp / kSuperK, 0, &plans[i])) return hipErrorInvalidValue;   // (callers check gemm_direct_grouped_fits)
+        if (!direct_plan(p, M, A[i].Kp / kSuperK, W[i].g128 ? 1 : 0, &plans[i])) return hipErrorInvalidValue;   // (callers check the fits functions; g128: one super-chunk per wave)
     for (int lead = 0; lead < count; ++lead) {
         if (done[lead]) continue;
         const DirectPlan pl = plans[lead];
