@@ -397,7 +397,7 @@ static bool choose_direct(const GemmArgs& g, const ActLayout& A, const WeightLay
     if (g.M > 16 || !W.has_fields) return false;
     if (W.g128)   // per-group weight parameters: the direct kernel has a variant for one row of A, one super-chunk per wave and
                   // p <= 4 (wider weights share accumulators between slices there, which the per-group sums cannot)
-        return gemm_direct_g128_fits(g.p, g.M, g, A, W) && direct_plan(g.p, 1, A.Kp / kSuperK, 1, pl);
+        return gemm_direct_g128_fits(g.p, g.M, g, A, W) && direct_plan_g128(g.p, A.Kp / kSuperK, pl);
     PlanOverride ov;
     lookup_plan(g.p, g.q, g.M, g.N, g.K, &ov);
     const int env = tuning_env("ABQ_DIRECT_R");

@@ -86,13 +86,23 @@ bool gemm_direct_grouped_fits(int p, int M, int count, const GemmArgs* probs, co
     return true;
 }
 
-// Per-group (g128) blobs: the direct kernel's variant takes one row of A, p <= 4 and at most 16 super-chunks of K.
+// Plan for per-group (g128) blobs, one row of A: one super-chunk per wave where sixteen waves cover K, else two (the
+// widths with a single plane group only).
+bool direct_plan_g128(int p, int nsuper, DirectPlan* out)
+{
+    for (int R : {1, 2})
+        if (direct_has_gq(p, 1, R) && direct_plan(p, 1, nsuper, R, out) && out->R == R) return true;
+    return false;
+}
+
+// Per-group (g128) blobs: the direct kernel's variant takes one row of A, p <= 4 and at most 16 super-chunks of K
+// (32 for p = 1, 2, 4).
 bool gemm_direct_g128_fits(int p, int M, const GemmArgs& g, const ActLayout& A, const WeightLayout& W)
 {
     DirectPlan pl;
     if (!W.g128 || !W.has_fields || M != 1 || p > 4 || g.acc || g.rq.codes) return false;
     if (g.a_raw ? (g.K % 16 != 0) : !A.has_fields) return false;
-    return direct_plan(p, 1, A.Kp / kSuperK, 1, &pl) && pl.R == 1;
+    return direct_plan_g128(p, A.Kp / kSuperK, &pl);
 }
 
 hipError_t launch_gemm_direct_grouped(int p, int q, int M, int count, const GemmArgs* probs, const ActLayout* A, const WeightLayout* W, hipStream_t s)
@@ -102,7 +112,8 @@ hipError_t launch_gemm_direct_grouped(int p, int q, int M, int count, const Gemm
     std::vector<DirectPlan> plans(count);
     std::vector<char> done(count, 0);
     for (int i = 0; i < count; ++i)
-        if (!direct_plan(p, M, A[i].Kp / kSuperK, W[i].g128 ? 1 : 0, &plans[i])) return hipErrorInvalidValue;   // (callers check the fits functions; g128: one super-chunk per wave)
+        if (!(W[i].g128 ? direct_plan_g128(p, A[i].Kp / kSuperK, &plans[i]) : direct_plan(p, M, A[i].Kp / kSuperK, 0, &plans[i])))
+            return hipErrorInvalidValue;   // (callers check the fits functions)
     for (int lead = 0; lead < count; ++lead) {
         if (done[lead]) continue;
         const DirectPlan pl = plans[lead];

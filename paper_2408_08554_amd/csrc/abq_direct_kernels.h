@@ -73,6 +73,13 @@ __host__ __device__ constexpr bool direct_has(int p, int MR, int R)
     return R == 1 || (R == 2 && p != 7 && (MR < 16 || narrow_single_group)) || (R == 4 && narrow_single_group && MR <= 4);
 }
 
+// Variants for per-group (g128) weight parameters: one row of A; one super-chunk per wave for p <= 4, two for the
+// single-group widths (sixteen slices, sixteen accumulators: two plane groups would need thirty-two).
+__host__ __device__ constexpr bool direct_has_gq(int p, int MR, int R)
+{
+    return MR == 1 && ((R == 1 && p <= 4) || (R == 2 && (p == 1 || p == 2 || p == 4)));
+}
+
 // Field t of a b-bit group as a signed-byte MFMA operand dword, and the shift that undoes its scale (as in the
 // streaming kernel: the field that would touch the byte's sign bit is taken one bit lower, or as weight -128).
 template <int B, int T>
@@ -143,6 +150,36 @@ __device__ __forceinline__ void direct_all_mfma(const u4v (*w)[P], const v4i* aq
     }
 }
 
+// Per-slice sums of the weights for the per-group path with two super-chunks per wave (single-group widths): the A operand
+// of MFMA s holds ones in row s only, so row s of accW[field position] collects sum_k w' of slice s and nothing else.
+template <int P, int R, int RR = 0, int C = 0, int T0 = 0>
+__device__ __forceinline__ void direct_wsum_mfma(const u4v (*w)[P], int r, int nsc, v4i* accW)
+{
+    constexpr int B = group_width(P, 0), T = 8 / B;
+    if constexpr (RR < R) {
+        if constexpr (C < B) {
+            constexpr int s = RR * 8 + C * T + T0;
+            if (RR < nsc) {
+                const int one = r == s ? 0x01010101 : 0;
+                accW[T0] = __builtin_amdgcn_mfma_i32_16x16x64_i8(v4i{one, one, one, one}, dfield_operand<B, T0>(w[RR][C]), accW[T0], 0, 0, 0);
+            }
+            if constexpr (T0 + 1 < T) direct_wsum_mfma<P, R, RR, C, T0 + 1>(w, r, nsc, accW);
+            else direct_wsum_mfma<P, R, RR, C + 1, 0>(w, r, nsc, accW);
+        } else {
+            direct_wsum_mfma<P, R, RR + 1, 0, 0>(w, r, nsc, accW);
+        }
+    }
+}
+template <int B, int T0 = 0>
+__device__ __forceinline__ v4i direct_wsum_unscale(const v4i* accW)
+{
+    constexpr int T = 8 / B;
+    const v4i& a = accW[T0];
+    v4i v{dfield_unscale<B, T0>(a.x), dfield_unscale<B, T0>(a.y), dfield_unscale<B, T0>(a.z), dfield_unscale<B, T0>(a.w)};
+    if constexpr (T0 + 1 < T) v += direct_wsum_unscale<B, T0 + 1>(accW);
+    return v;
+}
+
 // accI[i] += (sum of group GI's accumulators of slice set i, each unscaled by its field position) << shift of the group
 template <int P, int MR, int R, int GI, int A = 0>
 __device__ __forceinline__ void direct_fold(const v4i* acc, v4i* accI)
@@ -199,7 +236,7 @@ __device__ __forceinline__ void direct_pick(const v4i* accI, int G, int32_t* v)
 template <int P, int MR, int R, bool RAW, bool GROUPED, bool GQ = false>
 __global__ __launch_bounds__(1024) void direct_kernel(DirectParams gp)
 {
-    static_assert(!GQ || (MR == 1 && R == 1 && P <= 4), "per-group parameters: one row of A, one super-chunk per wave, an accumulator per slice");
+    static_assert(!GQ || direct_has_gq(P, MR, R), "per-group parameters: one row of A and an accumulator per slice");
     using SH = DirectShape<P, MR, R>;
     constexpr int SL = SH::SL, NQ = SH::NQ, NI = SH::NI;
     constexpr int NV = MR == 1 ? 1 : (MR == 2 ? 2 : 4);             // values per lane after direct_pick
@@ -254,7 +291,8 @@ __global__ __launch_bounds__(1024) void direct_kernel(DirectParams gp)
     u4v grec{0, 0, 0, 0};       // GQ: the group record of this lane's channel and this wave's super-chunk
     int zc_all = 0;             // GQ: the token's zero-point less oa (M = 1: the same for every lane)
     if constexpr (GQ) {
-        grec = __builtin_nontemporal_load(pr.gparams + ((size_t)tile * nsuper + min(sc0, nsuper - 1)) * 16 + r);
+        // (R = 2: lanes of G = 2, 3 work on the wave's second super-chunk and take its record)
+        grec = __builtin_nontemporal_load(pr.gparams + ((size_t)tile * nsuper + min(sc0 + (R == 2 ? (G >> 1) : 0), nsuper - 1)) * 16 + r);
         if constexpr (RAW) zc_all = pr.a_zero[0] - gp.oa;
         else zc_all = pr.aparams[0].zero - gp.oa;
     }
@@ -289,8 +327,8 @@ __global__ __launch_bounds__(1024) void direct_kernel(DirectParams gp)
     }
 
     if constexpr (GQ) {
-        // operand rows 8..15 (no slice lives there at MR = R = 1) become rows of ones
-        if (r >= 8) aq[0] = v4i{0x01010101, 0x01010101, 0x01010101, 0x01010101};
+        // R = 1: operand rows 8..15 (no slice lives there) become rows of ones
+        if (R == 1 && r >= 8) aq[0] = v4i{0x01010101, 0x01010101, 0x01010101, 0x01010101};
     }
     v4i asum_acc{0, 0, 0, 0};
     if constexpr (RAW || GQ) {   // row sums of the operand bytes, while the weights are still on their way
@@ -316,12 +354,32 @@ __global__ __launch_bounds__(1024) void direct_kernel(DirectParams gp)
         // rows 8..15 = the ones rows (sum of the weights of slice 4(G-2) + reg).  Either way the lane takes element reg of
         // accumulator 4(G & 1) + reg and adds the two slices of each group: lanes of G = 0, 1 then hold the product sums of
         // groups 2G, 2G+1 of their channel, lanes of G = 2, 3 the weight sums of the same groups, 32 lanes further up.
-        int32_t e[4];
+        int c0, c1, ws0, ws1;
+        bool live = true;
+        if constexpr (R == 1) {
+            int32_t e[4];
 #pragma unroll
-        for (int reg = 0; reg < 4; ++reg) e[reg] = (G & 1) ? accS[4 + reg][reg] : accS[reg][reg];
-        const int c0 = e[0] + e[1], c1 = e[2] + e[3];
-        const int ws0 = __shfl(c0, (lane + 32) & 63), ws1 = __shfl(c1, (lane + 32) & 63);
-        // every column of asum_acc holds the row sums of the operand: this lane's rows are slices 4G .. 4G+3 (G < 2)
+            for (int reg = 0; reg < 4; ++reg) e[reg] = (G & 1) ? accS[4 + reg][reg] : accS[reg][reg];
+            c0 = e[0] + e[1]; c1 = e[2] + e[3];
+            ws0 = __shfl(c0, (lane + 32) & 63); ws1 = __shfl(c1, (lane + 32) & 63);
+        } else {
+            // R = 2: all sixteen operand rows are slices; lane (G, reg) takes element reg of accumulator 4G + reg, and the
+            // weight sums come from MFMAs of their own whose A operand holds ones in one row only
+            v4i accW[8 / group_width(P, 0)];
+#pragma unroll
+            for (int i = 0; i < 8 / group_width(P, 0); ++i) accW[i] = v4i{0, 0, 0, 0};
+            direct_wsum_mfma<P, R>(w, r, nsc, accW);
+            const v4i wsv = direct_wsum_unscale<group_width(P, 0)>(accW);
+            int32_t e[4] = {0, 0, 0, 0};
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4)
+#pragma unroll
+                for (int reg = 0; reg < 4; ++reg) e[reg] = G == g4 ? accS[4 * g4 + reg][reg] : e[reg];
+            c0 = e[0] + e[1]; c1 = e[2] + e[3];
+            ws0 = wsv.x + wsv.y; ws1 = wsv.z + wsv.w;
+            live = (G >> 1) < nsc;                                     // (a wave with one super-chunk: its second half adds nothing)
+        }
+        // every column of asum_acc holds the row sums of the operand: this lane's rows are slices 4G .. 4G+3
         const int as0 = asum_acc.x + asum_acc.y, as1 = asum_acc.z + asum_acc.w;
         const int g0 = 2 * (G & 1);                                    // this lane's first group of the super-chunk
         const int z0 = ((int)(grec.z << (24 - 8 * g0))) >> 24, z1 = ((int)(grec.z << (16 - 8 * g0))) >> 24;
@@ -332,7 +390,9 @@ __global__ __launch_bounds__(1024) void direct_kernel(DirectParams gp)
         const int t1g = c1 - z1 * as1 - zc_all * (ws1 - 128 * z1);
         float f = (float)t0g * s0;
         f = __builtin_fmaf((float)t1g, s1, f);
+        if (!live) f = 0.f;
         f += __shfl(f, lane ^ 16);                                      // groups 0, 1 (G = 0) + groups 2, 3 (G = 1): same order in both lanes
+        if constexpr (R == 2) f += __shfl(f, lane ^ 32);               // + the second super-chunk's four groups
         float* fpart = reinterpret_cast<float*>(red);                  // [wave][channel]
         if (G == 0) fpart[wave * 16 + r] = f;
         __syncthreads();
@@ -414,7 +474,7 @@ template <int P, int MR, int R, bool RAW>
 static hipError_t direct_launch_one(const DirectParams& gp, unsigned grid, int waves, hipStream_t s)
 {
     if (gp.d[0].gparams) {   // per-group weight parameters (every problem of a launch is of the same kind)
-        if constexpr (MR == 1 && R == 1 && P <= 4) {
+        if constexpr (direct_has_gq(P, MR, R)) {
             if (gp.count > 1) direct_kernel<P, MR, R, RAW, true, true><<<grid, waves * 64, direct_lds_bytes(waves, MR, true), s>>>(gp);
             else direct_kernel<P, MR, R, RAW, false, true><<<grid, waves * 64, direct_lds_bytes(waves, MR, true), s>>>(gp);
             return hipGetLastError();

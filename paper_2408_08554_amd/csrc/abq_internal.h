@@ -140,6 +140,7 @@ struct DirectPlan { int MR, R, S; };
 bool direct_plan(int p, int M, int nsuper, int forced_r, DirectPlan* out);   // false: the problem does not fit this kernel
 hipError_t launch_gemm_direct(const GemmArgs& g, const ActLayout& A, const WeightLayout& W, const DirectPlan& pl, hipStream_t s);
 bool gemm_direct_grouped_fits(int p, int M, int count, const GemmArgs* probs, const ActLayout* A, const WeightLayout* W);
+bool direct_plan_g128(int p, int nsuper, DirectPlan* out);   // per-group blobs, one row of A
 bool gemm_direct_g128_fits(int p, int M, const GemmArgs& g, const ActLayout& A, const WeightLayout& W);
 hipError_t launch_gemm_direct_grouped(int p, int q, int M, int count, const GemmArgs* probs, const ActLayout* A, const WeightLayout* W,
                                       hipStream_t s);

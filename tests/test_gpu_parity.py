@@ -724,6 +724,18 @@ def test_g128_shapes(abq, M, N, K, p, q, fused):
     check_g128(c, sh, zg, run_g128(abq, c, sh, zg, fused))
 
 
+@pytest.mark.parametrize("fused", [False, True], ids=["packed", "fused"])
+@pytest.mark.parametrize("N,K", [(48, 8704), (33, 9000), (20, 16384), (16, 16000), (100, 8320)])
+@pytest.mark.parametrize("p,q", [(1, 8), (2, 8), (4, 8), (4, 4), (2, 3)])
+def test_g128_one_row_long_k(abq, N, K, p, q, fused):
+    # one row of A over more than sixteen super-chunks of K: the decode kernel's waves take two each (an odd count
+    # leaves the last wave with one, K = 16384 is the most the variant covers, 9000 and 16000 end inside a group)
+    say(f"g128 long K N={N} K={K} p={p} q={q} fused={fused}")
+    c = synth.make_case(p, q, 1, N, K, seed=9300 + N + K + p + q)
+    sh, zg = synth.group_quant_params(c)
+    check_g128(c, sh, zg, run_g128(abq, c, sh, zg, fused))
+
+
 @pytest.mark.parametrize("p", [1, 2, 4, 7, 8])
 @pytest.mark.parametrize("kind", ["zero_points_at_both_ends", "all_codes_maximal", "all_codes_zero", "zero_scales"])
 def test_g128_extremes(abq, p, kind):
