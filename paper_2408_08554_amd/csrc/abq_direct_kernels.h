@@ -225,14 +225,17 @@ __device__ __forceinline__ void direct_pick(const v4i* accI, int G, int32_t* v)
 // GROUPED: several problems in one grid (the workgroup finds its problem from the tile starts); otherwise problem 0.
 // Either way the problem's descriptor is copied from the kernel arguments in one batch of scalar loads at the top:
 // read field by field where it is used, every first use would wait for a scalar load of its own.
-// GQ: per-group weight parameters (groups of 128 along K, Appendix C), built for one row of A, one super-chunk per
-// wave (MR = R = 1) and p <= 4.  Then every 64-k slice of the wave's super-chunk has an accumulator of its own (eight slices, eight
-// operand rows), so the integer sum of every group of 128 k is there after the MFMAs without any change to them, and
-// the other eight operand rows, unused at M = 1, are filled with ones: row 8 of accumulator s then holds sum_k w' of slice
-// s for every channel — the operand sum that the activation zero-point needs — for free.  sum_k a' per slice comes from
-// one MFMA of the operand against ones.  Per group: t = c - z * sum a' - zc * (sum w' - 128 z) in exact integers
-// (z: the group's zero-point, zc: the token's, both less the stored offsets; padded k hold a' = 0 and w' = z), then one
-// conversion and one fma with the group's scale; the 16 threads of the epilogue add groups and waves in a fixed order.
+// GQ: per-group weight parameters (groups of 128 along K, Appendix C), built for one row of A and p <= 4.  Every 64-k
+// slice of the wave's run then has an accumulator of its own, so the integer sum of every group of 128 k is there after
+// the MFMAs without any change to them.  sum_k a' per slice comes from one MFMA of the operand against ones.  sum_k w'
+// per slice — the operand sum that the activation zero-point needs — comes, with one super-chunk per wave (eight slices,
+// eight operand rows), for free: the other eight operand rows, unused at M = 1, are filled with ones, and row 8 of
+// accumulator s then holds it for every channel.  With two super-chunks per wave (p = 1, 2, 4; K up to 16384) all
+// sixteen rows are slices, and the sums come from one more MFMA per slice whose A operand holds ones in that slice's
+// row only.  Per group: t = c - z * sum a' - zc * (sum w' - 128 z) in exact integers (z: the group's zero-point, zc: the
+// token's, both less the stored offsets; padded k hold a' = 0 and w' = z), then one conversion and one fma with the
+// group's scale; the lanes of a wave add their groups by lane exchange, and the 16 threads of the epilogue add the
+// waves in a fixed order.
 template <int P, int MR, int R, bool RAW, bool GROUPED, bool GQ = false>
 __global__ __launch_bounds__(1024) void direct_kernel(DirectParams gp)
 {
@@ -288,7 +291,7 @@ __global__ __launch_bounds__(1024) void direct_kernel(DirectParams gp)
         }
         aq[q] = v;
     }
-    u4v grec{0, 0, 0, 0};       // GQ: the group record of this lane's channel and this wave's super-chunk
+    u4v grec{0, 0, 0, 0};       // GQ: the group record of this lane's channel and super-chunk
     int zc_all = 0;             // GQ: the token's zero-point less oa (M = 1: the same for every lane)
     if constexpr (GQ) {
         // (R = 2: lanes of G = 2, 3 work on the wave's second super-chunk and take its record)
@@ -350,10 +353,10 @@ __global__ __launch_bounds__(1024) void direct_kernel(DirectParams gp)
         direct_fold<P, MR, R, 0>(acc, accS);
         if constexpr (SH::NG > 1) direct_fold<P, MR, R, 1>(acc, accS);
         if constexpr (SH::NG > 2) direct_fold<P, MR, R, 2>(acc, accS);
-        // lane (G, reg) holds operand row 4G + reg: rows 0..7 = slice 4G + reg against itself (the wanted product sum),
-        // rows 8..15 = the ones rows (sum of the weights of slice 4(G-2) + reg).  Either way the lane takes element reg of
-        // accumulator 4(G & 1) + reg and adds the two slices of each group: lanes of G = 0, 1 then hold the product sums of
-        // groups 2G, 2G+1 of their channel, lanes of G = 2, 3 the weight sums of the same groups, 32 lanes further up.
+        // R = 1: lane (G, reg) holds operand row 4G + reg: rows 0..7 = slice 4G + reg against itself (the wanted product
+        // sum), rows 8..15 = the ones rows (sum of the weights of slice 4(G-2) + reg).  Either way the lane takes element
+        // reg of accumulator 4(G & 1) + reg and adds the two slices of each group: lanes of G = 0, 1 then hold the product
+        // sums of groups 2G, 2G+1 of their channel, lanes of G = 2, 3 the weight sums of the same groups, 32 lanes further up.
         int c0, c1, ws0, ws1;
         bool live = true;
         if constexpr (R == 1) {
