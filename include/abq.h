@@ -68,6 +68,12 @@ extern "C" {
 int         abq_version(void);                 /* major*10000 + minor*100 + patch */
 const char* abq_status_string(int status);     /* static string, never NULL */
 int         abq_last_hip_error(void);          /* hipError_t of the last failing HIP call on this thread */
+/* Test hook: which decode kernel (Sec. 3.4, GEMV case) the last abq_gemm / abq_gemm_act_codes* call of this thread with
+ * M <= 16 on field-packed operands launched; 0 before the first such call. */
+#define ABQ_DECODE_DIRECT          1   /* A operand loaded into registers, one workgroup per tile */
+#define ABQ_DECODE_STREAMING       2   /* A staged in LDS, ring of weight loads, workgroups walking tiles */
+#define ABQ_DECODE_SHARED_OPERAND  3   /* one copy of A in LDS per workgroup of several tiles, every load up front */
+int         abq_last_decode_kernel(void);
 
 /* ------------------------------------------------------------------------------------------
  * Weights, offline (Sec. 3.4 step 1 "BitPacking"; "weight BitPacking is implemented offline").
@@ -276,7 +282,9 @@ int abq_gemm_act_codes_static(int p, int q, int M, int N, int K,
  *   tiled_wd        operand steps in flight: 2 or 4 (4 exists for tiled_mt = 4 with tiled_ntw <= 2)
  *   tiled_band      row blocks of A per band of the tile order: >= 1
  *   direct_r        decode kernel for M <= 16: -1 the streaming kernel (A staged in LDS, load ring); 1, 2 or 4 the
- *                   direct kernel (A operand loaded into registers) with that many 512-k blocks per wave
+ *                   direct kernel (A operand loaded into registers) with that many 512-k blocks per wave; -2 the
+ *                   shared-operand kernel (one copy of A in LDS per workgroup of several tiles) where it fits, else the
+ *                   streaming kernel
  * abq_plan_set: plan == NULL removes the entry.  ABQ_ERR_BITS / ABQ_ERR_SHAPE as abq_gemm; ABQ_ERR_LAYOUT for a
  * value outside the lists above.  abq_plan_get fills *out (all zero when there is no entry). */
 typedef struct abq_plan {

@@ -27,6 +27,7 @@ _SIGNATURES = {
     "abq_version": (_c.c_int, []),
     "abq_status_string": (_c.c_char_p, [_c.c_int]),
     "abq_last_hip_error": (_c.c_int, []),
+    "abq_last_decode_kernel": (_c.c_int, []),
     "abq_packed_weight_bytes": (_c.c_size_t, [_c.c_int] * 4),
     "abq_pack_weights": (_c.c_int, [_c.c_int] * 3 + [_c.c_void_p] * 3 + [_c.c_int, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
     "abq_pack_weights_g128": (_c.c_int, [_c.c_int] * 3 + [_c.c_void_p] * 3 + [_c.c_void_p, _c.c_size_t, _c.c_void_p]),
@@ -317,6 +318,14 @@ def abq_plan_get(p, q, M, N, K):
     out = AbqPlan()
     _check(load().abq_plan_get(p, q, M, N, K, _c.addressof(out)), "abq_plan_get")
     return {n: getattr(out, n) for n, _ in AbqPlan._fields_}
+
+
+ABQ_DECODE_DIRECT, ABQ_DECODE_STREAMING, ABQ_DECODE_SHARED_OPERAND = 1, 2, 3
+
+
+def abq_last_decode_kernel():
+    """Test hook: ABQ_DECODE_* of the last M <= 16 matmul call of this thread."""
+    return load().abq_last_decode_kernel()
 
 
 def abq_plan_clear():

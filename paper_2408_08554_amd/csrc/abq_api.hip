@@ -20,6 +20,7 @@ static __device__ __align__(256) unsigned char scratch[ABQ_STATIC_SCRATCH_BYTES]
 namespace abq {
 
 static thread_local int g_last_hip_error = 0;
+static thread_local int g_last_decode_kernel = 0;   // test hook: which decode kernel the last single-problem call on this thread launched
 
 static int hip_status(hipError_t e)
 {
@@ -172,6 +173,7 @@ const char* abq_status_string(int status)
 }
 
 int abq_last_hip_error(void) { return g_last_hip_error; }
+int abq_last_decode_kernel(void) { return g_last_decode_kernel; }
 
 size_t abq_packed_weight_bytes(int p, int N, int K, int layout)
 {
@@ -406,10 +408,31 @@ static bool choose_direct(const GemmArgs& g, const ActLayout& A, const WeightLay
     if (forced == 0 && !direct_by_rule(g.p, g.M, A.Kp / kSuperK, W)) return false;
     return direct_plan(g.p, g.M, A.Kp / kSuperK, forced, pl);
 }
+// The shared-operand kernel (one copy of A in LDS per workgroup, several tiles per workgroup, every load up front): where
+// neither of the two above is at home — more than eight rows of A over more tiles than compute units, narrow weights.
+// Measured (shared / streaming / direct, us; M = 16 unless said): 13824 ch x 5120: W1A8 8.0 / 10.5 / 14.1, W2A8 8.8 / 11.0 /
+// 14.5, W3A8 11.4 / 12.5 / 18.1, W4A8 11.4 / 12.2 / 16.2 (M = 9: 10.7 / 10.8), W5A8 14.0 / 13.2; 11008 ch x 4096: W1A8 7.1 / 7.9 /
+// 8.8, W2A8 7.4 / 8.0, W3A8 8.8 / 9.1, W4A8 8.8 / 8.7, W8A8 11.7 / 10.7.  Hence: p <= 3, and p = 4 over more than three
+// tiles per compute unit.  A plan-table entry direct_r = -2 forces it wherever it fits.
+static bool choose_shared_a(const GemmArgs& g, const ActLayout& A, const WeightLayout& W, SharedAPlan* pl)
+{
+    if (g.M > 16 || !W.has_fields || W.g128) return false;
+    if (g.a_raw ? (g.K % 16 != 0) : !A.has_fields) return false;
+    PlanOverride ov;
+    lookup_plan(g.p, g.q, g.M, g.N, g.K, &ov);
+    const int env = tuning_env("ABQ_DIRECT_R");
+    const int forced = ov.direct_r != 0 ? ov.direct_r : env;
+    if (forced != 0 && forced != -2) return false;
+    if (forced == 0 && (g.M <= 8 || g.p > 4 || (g.p == 4 && W.NT <= 3 * num_cus()))) return false;
+    return shared_a_plan(g.p, g.M, W.NT, A.Kp, g.a_raw != nullptr, g.K, forced == -2, pl);
+}
 static hipError_t launch_decode(const GemmArgs& g, const ActLayout& A, const WeightLayout& W, hipStream_t s)
 {
     DirectPlan pl;
-    if (choose_direct(g, A, W, &pl)) return launch_gemm_direct(g, A, W, pl, s);
+    SharedAPlan sp;
+    if (choose_direct(g, A, W, &pl)) { g_last_decode_kernel = ABQ_DECODE_DIRECT; return launch_gemm_direct(g, A, W, pl, s); }
+    if (choose_shared_a(g, A, W, &sp)) { g_last_decode_kernel = ABQ_DECODE_SHARED_OPERAND; return launch_gemm_shared_a(g, A, W, sp, s); }
+    g_last_decode_kernel = ABQ_DECODE_STREAMING;
     return launch_gemm_skinny(g, A, W, s);
 }
 
@@ -424,7 +447,7 @@ int abq_plan_set(int p, int q, int M, int N, int K, const abq_plan* plan)
         const int dr = plan->direct_r;
         const bool ok = (w == 0 || w == 1 || w == 2 || (w >= 4 && w <= 8)) && g >= 0 && g <= 4 && (mt == 0 || mt == 4 || mt == 8) &&
                         (nt == 0 || nt == 1 || nt == 2 || nt == 4) && (wd == 0 || wd == 2 || wd == 4) && plan->tiled_band >= 0 &&
-                        (dr == -1 || dr == 0 || dr == 1 || dr == 2 || dr == 4);
+                        (dr == -2 || dr == -1 || dr == 0 || dr == 1 || dr == 2 || dr == 4);
         if (!ok) return ABQ_ERR_LAYOUT;
         g_plans[{p, q, M, N, K}] = PlanOverride{w, g, mt, nt, wd, plan->tiled_band, dr};
     }

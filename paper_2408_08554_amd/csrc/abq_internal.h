@@ -140,6 +140,11 @@ struct DirectPlan { int MR, R, S; };
 bool direct_plan(int p, int M, int nsuper, int forced_r, DirectPlan* out);   // false: the problem does not fit this kernel
 hipError_t launch_gemm_direct(const GemmArgs& g, const ActLayout& A, const WeightLayout& W, const DirectPlan& pl, hipStream_t s);
 bool gemm_direct_grouped_fits(int p, int M, int count, const GemmArgs* probs, const ActLayout* A, const WeightLayout* W);
+// The shared-operand decode kernel (9 .. 16 rows of A over more tiles than compute units): workgroups, waves per
+// workgroup, super-chunks per wave at most.
+struct SharedAPlan { int nwg, S, R; };
+bool shared_a_plan(int p, int M, int NT, int Kp, bool raw, int K, bool forced, SharedAPlan* out);   // false: the problem does not fit this kernel
+hipError_t launch_gemm_shared_a(const GemmArgs& g, const ActLayout& A, const WeightLayout& W, const SharedAPlan& pl, hipStream_t s);
 bool direct_plan_g128(int p, int nsuper, DirectPlan* out);   // per-group blobs, one row of A
 bool gemm_direct_g128_fits(int p, int M, const GemmArgs& g, const ActLayout& A, const WeightLayout& W);
 hipError_t launch_gemm_direct_grouped(int p, int q, int M, int count, const GemmArgs* probs, const ActLayout* A, const WeightLayout* W,

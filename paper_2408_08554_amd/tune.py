@@ -35,6 +35,7 @@ def candidates(p, q, M, N, K):
         direct_off = {"direct_r": -1} if M <= 16 else {}
         if direct_off:
             out.append(dict(direct_off))
+            out.append({"direct_r": -2})    # the shared-operand kernel (falls back to the streaming kernel where it does not fit)
         for w in (1, 2, 4, 5, 6, 7, 8):
             if w <= nsuper:
                 out.append({"skinny_waves": w, **direct_off})

@@ -124,7 +124,7 @@ def test_plan_table_set_get_clear_and_rejects():
     assert B.abq_plan_get(6, 6, 512, 11008, 4096) == zero
     lib = B.load()
     for bad in (dict(skinny_waves=3), dict(skinny_waves=9), dict(skinny_kgroups=5), dict(tiled_mt=6), dict(tiled_ntw=3),
-                dict(tiled_wd=3), dict(tiled_band=-1), dict(direct_r=3), dict(direct_r=-2)):
+                dict(tiled_wd=3), dict(tiled_band=-1), dict(direct_r=3), dict(direct_r=-3)):
         plan = B.AbqPlan(**bad)
         assert lib.abq_plan_set(4, 8, 1, 64, 64, ctypes.addressof(plan)) == B.ABQ_ERR_LAYOUT, bad
     plan = B.AbqPlan(skinny_waves=4)

@@ -996,6 +996,58 @@ def test_direct_and_streaming_decode_kernels_agree_bitwise(abq):
         check_against_oracle(c, *out[1])
 
 
+# ---- the shared-operand decode kernel (one copy of A in LDS per workgroup of several tiles) ------------------------------
+@pytest.mark.parametrize("fused", [False, True], ids=["packed", "fused"])
+@pytest.mark.parametrize("M", [1, 7, 9, 13, 16])
+@pytest.mark.parametrize("p,q", [(1, 8), (2, 8), (3, 4), (4, 8), (5, 3), (6, 6), (7, 1), (8, 8)])
+def test_shared_operand_decode_kernel_forced(abq, p, q, M, fused):
+    """The plan table forces the kernel on small problems (two tiles per workgroup, the second one partly or wholly past
+    the end of N; K spanning whole and partial super-chunks, one to three per wave)."""
+    for N, K in ((40, 1552), (17, 4096), (90, 2608), (33, 5120)):
+        c = synth.make_case(p, q, M, N, K, seed=synth.case_seed(8, p, q, M, 11), name=f"shared-A W{p}A{q} M={M} N={N} K={K}")
+        say(c.name)
+        abq.abq_plan_set(p, q, M, N, K, direct_r=-2)
+        try:
+            y, acc = gpu_gemm_fused(torch, abq, c, FIELDS) if fused else gpu_gemm(torch, abq, c, FIELDS, FIELDS)
+        finally:
+            abq.abq_plan_set(p, q, M, N, K)
+        assert abq.abq_last_decode_kernel() == abq.ABQ_DECODE_SHARED_OPERAND
+        check_against_oracle(c, y, acc)
+
+
+@pytest.mark.parametrize("fused", [False, True], ids=["packed", "fused"])
+@pytest.mark.parametrize("p,q,M,N,K", [(1, 8, 16, 4100, 1024), (4, 8, 9, 8200, 3000), (2, 4, 16, 12304, 5120), (6, 6, 12, 12290, 4608),
+                                       (8, 8, 16, 8208, 4096), (3, 8, 10, 28000, 2048), (2, 8, 16, 28690, 6144), (4, 4, 16, 13824, 5120)])
+def test_shared_operand_decode_kernel_many_tiles(abq, p, q, M, N, K, fused):
+    """More tiles than compute units: the kernel's own plans (two to eight tiles per workgroup, up to six super-chunks per
+    wave), whichever decode kernel the rule takes being forced aside."""
+    c = synth.make_case(p, q, M, N, K, seed=synth.case_seed(8, p, q, M, 12), name=f"shared-A W{p}A{q} M={M} N={N} K={K}")
+    say(c.name)
+    abq.abq_plan_set(p, q, M, N, K, direct_r=-2)
+    try:
+        y, acc = gpu_gemm_fused(torch, abq, c, FIELDS) if fused else gpu_gemm(torch, abq, c, FIELDS, FIELDS)
+    finally:
+        abq.abq_plan_set(p, q, M, N, K)
+    assert abq.abq_last_decode_kernel() == abq.ABQ_DECODE_SHARED_OPERAND
+    check_against_oracle(c, y, acc)
+
+
+def test_shared_operand_and_streaming_decode_kernels_agree_bitwise(abq):
+    """Same problems on both kernels, with the accumulator output and the ReQuant epilogue: equal bits."""
+    for p, q, M, N, K in [(4, 8, 16, 4200, 2048), (2, 8, 11, 70, 2048), (8, 8, 9, 33, 5120)]:
+        c = synth.make_case(p, q, M, N, K, seed=synth.case_seed(8, p, q, M, 13))
+        out = []
+        for r in (-1, -2):
+            abq.abq_plan_set(p, q, M, N, K, direct_r=r)
+            try:
+                out.append(gpu_gemm_fused(torch, abq, c, FIELDS))
+            finally:
+                abq.abq_plan_set(p, q, M, N, K)
+            assert abq.abq_last_decode_kernel() == (abq.ABQ_DECODE_STREAMING if r == -1 else abq.ABQ_DECODE_SHARED_OPERAND)
+        assert np.array_equal(out[0][1], out[1][1]) and np.array_equal(out[0][0].view(np.uint16), out[1][0].view(np.uint16))
+        check_against_oracle(c, *out[1])
+
+
 # ---- config 5 in full: every (p, q) on both LLaMA-13B shapes ---------------------------------------------------
 @pytest.mark.parametrize("m_idx", [0, 1], ids=["M1", "M16"])
 @pytest.mark.parametrize("shape_idx", [0, 1], ids=["5120to13824", "13824to5120"])
