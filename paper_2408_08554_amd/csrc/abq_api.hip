@@ -413,7 +413,9 @@ static bool choose_direct(const GemmArgs& g, const ActLayout& A, const WeightLay
 // Measured (shared / streaming / direct, us; M = 16 unless said): 13824 ch x 5120: W1A8 8.0 / 10.5 / 14.1, W2A8 8.8 / 11.0 /
 // 14.5, W3A8 11.4 / 12.5 / 18.1, W4A8 11.4 / 12.2 / 16.2 (M = 9: 10.7 / 10.8), W5A8 14.0 / 13.2; 11008 ch x 4096: W1A8 7.1 / 7.9 /
 // 8.8, W2A8 7.4 / 8.0, W3A8 8.8 / 9.1, W4A8 8.8 / 8.7, W8A8 11.7 / 10.7.  Hence: p <= 3, and p = 4 over more than three
-// tiles per compute unit.  A plan-table entry direct_r = -2 forces it wherever it fits.
+// tiles per compute unit.  Where A is larger than LDS (K > 6144) the kernel cuts K in two phases; those variants exist
+// for p <= 2 (5120 ch x 13824, M = 16: W1A8 11.9 / 14.3, W2A8 13.2 / 14.4; W4A8 would spill: 20.7 / 16.2).  A plan-table entry
+// direct_r = -2 forces it wherever it fits.
 static bool choose_shared_a(const GemmArgs& g, const ActLayout& A, const WeightLayout& W, SharedAPlan* pl)
 {
     if (g.M > 16 || !W.has_fields || W.g128) return false;

@@ -141,8 +141,8 @@ bool direct_plan(int p, int M, int nsuper, int forced_r, DirectPlan* out);   // 
 hipError_t launch_gemm_direct(const GemmArgs& g, const ActLayout& A, const WeightLayout& W, const DirectPlan& pl, hipStream_t s);
 bool gemm_direct_grouped_fits(int p, int M, int count, const GemmArgs* probs, const ActLayout* A, const WeightLayout* W);
 // The shared-operand decode kernel (9 .. 16 rows of A over more tiles than compute units): workgroups, waves per
-// workgroup, super-chunks per wave at most.
-struct SharedAPlan { int nwg, S, R; };
+// workgroup, super-chunks per wave and phase at most, phases of K (1 or 2), super-chunks per phase.
+struct SharedAPlan { int nwg, S, R, phases, H; };
 bool shared_a_plan(int p, int M, int NT, int Kp, bool raw, int K, bool forced, SharedAPlan* out);   // false: the problem does not fit this kernel
 hipError_t launch_gemm_shared_a(const GemmArgs& g, const ActLayout& A, const WeightLayout& W, const SharedAPlan& pl, hipStream_t s);
 bool direct_plan_g128(int p, int nsuper, DirectPlan* out);   // per-group blobs, one row of A

@@ -1032,6 +1032,24 @@ def test_shared_operand_decode_kernel_many_tiles(abq, p, q, M, N, K, fused):
     check_against_oracle(c, y, acc)
 
 
+@pytest.mark.parametrize("fused", [False, True], ids=["packed", "fused"])
+@pytest.mark.parametrize("p,q,M,N,K", [(1, 8, 16, 5120, 13824), (2, 8, 9, 5120, 13824), (2, 8, 16, 5120, 13824), (1, 4, 13, 4200, 11008),
+                                       (2, 3, 16, 100, 8000), (1, 1, 11, 40, 7000), (2, 8, 16, 33, 12288), (2, 8, 16, 8200, 6656),
+                                       (1, 8, 10, 48, 14336)])
+def test_shared_operand_decode_kernel_two_phases_of_k(abq, p, q, M, N, K, fused):
+    """A larger than LDS: K is cut in two phases whose halves of A take turns in LDS (an odd number of super-chunks, a
+    second phase that ends inside a super-chunk, few and many tiles)."""
+    c = synth.make_case(p, q, M, N, K, seed=synth.case_seed(8, p, q, M, 14), name=f"shared-A two phases W{p}A{q} M={M} N={N} K={K}")
+    say(c.name)
+    abq.abq_plan_set(p, q, M, N, K, direct_r=-2)
+    try:
+        y, acc = gpu_gemm_fused(torch, abq, c, FIELDS) if fused else gpu_gemm(torch, abq, c, FIELDS, FIELDS)
+    finally:
+        abq.abq_plan_set(p, q, M, N, K)
+    assert abq.abq_last_decode_kernel() == abq.ABQ_DECODE_SHARED_OPERAND
+    check_against_oracle(c, y, acc)
+
+
 def test_shared_operand_and_streaming_decode_kernels_agree_bitwise(abq):
     """Same problems on both kernels, with the accumulator output and the ReQuant epilogue: equal bits."""
     for p, q, M, N, K in [(4, 8, 16, 4200, 2048), (2, 8, 11, 70, 2048), (8, 8, 9, 33, 5120)]:
