@@ -914,6 +914,8 @@ def test_g128_prefill_exact_when_the_float_sum_is_exact(abq):
 @pytest.mark.parametrize("p,q,q_out,M,N,K,layout", [(4, 8, 8, 1, 300, 4096, FIELDS),      # direct decode kernel
                                                     (2, 8, 4, 7, 70, 1552, FIELDS),       # direct, ragged
                                                     (8, 8, 8, 16, 2000, 13824, FIELDS),   # streaming decode kernel (long stream, 16 rows)
+                                                    (2, 8, 8, 16, 4400, 2048, FIELDS),    # shared-operand decode kernel (more tiles than units)
+                                                    (1, 8, 4, 12, 4200, 7168, FIELDS),    # shared-operand, K in two phases
                                                     (6, 6, 6, 130, 200, 2048, FIELDS),    # tiled prefill kernel
                                                     (4, 4, 2, 300, 520, 1000, FIELDS),    # tiled, K ragged
                                                     (3, 5, 3, 5, 33, 200, PLANES),        # bit-serial kernel (two-step path)
