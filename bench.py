@@ -37,6 +37,7 @@ PROFILE_OF = {
     "C3 W2A8 GEMV M=1 11008->4096": "direct_kernel_w2a8_gemv_m1_k11008_n4096.md",
     "C3 W2A8 GEMV M=8 11008->4096": "direct_kernel_w2a8_gemv_m8_k11008_n4096.md",
     "C5 W8A8 M=1 K=5120 N=13824": "skinny_kernel_w8a8_gemv_m1_k5120_n13824.md",
+    "C5 W2A8 M=16 K=5120 N=13824": "shared_a_kernel_w2a8_gemv_m16_k5120_n13824.md",
     "C2 W4A8 GEMV 4096x4096 g128": "direct_kernel_w4a8_g128_gemv_m1_k4096_n4096.md",
     "C5 W4A8 M=1 K=5120 N=13824 g128": "direct_kernel_w4a8_g128_gemv_m1_k5120_n13824.md",
     "C4 W6A6 GEMM M=512 4096->11008": "tiled_kernel_w6a6_gemm_m512_k4096_n11008.md",
@@ -696,6 +697,7 @@ def main():
             "decode_w2a8_m1_c3": child_summary(["--workload", "c3m1", *short]),
             "decode_w2a8_m8_c3": child_summary(["--workload", "c3m8", *short]),
             "decode_w8a8_m1_13b": child_summary(["--workload", "c5:8,8,0,0", *short]),
+            "decode_w2a8_m16_13b": child_summary(["--workload", "c5:2,8,0,1", *short]),
             "decode_g128_weights": child_summary(["--workload", "c2", "--g128", *short]),
             "prefill_w6a6_m128_c4": child_summary(["--workload", "c4m128", "--step", "two", *short]),
             "prefill_w6a6_m512_c4": child_summary(["--workload", "c4m512", "--step", "two", *short]),
