@@ -70,8 +70,8 @@ def profile_figures(key, kernel_us=None):
         out["traffic_source"] = "profiles/" + name
     if k:
         out["profile_kernel_us"] = int(k.group(1)) / 1e3
-        if kernel_us is not None:   # under the tracer a launch reads a few percent longer than between HIP events
-            out["profile_agrees"] = abs(out["profile_kernel_us"] - kernel_us) <= 0.10 * kernel_us
+        if kernel_us is not None:   # under the tracer a launch reads a few percent, and up to ~0.7 us, longer than between HIP events
+            out["profile_agrees"] = abs(out["profile_kernel_us"] - kernel_us) <= max(0.10 * kernel_us, 0.75)
     return out
 
 
