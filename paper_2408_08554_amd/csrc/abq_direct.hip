@@ -13,7 +13,7 @@ static int next_pow2(int v) { int p = 1; while (p < v) p <<= 1; return p; }
 // Narrow weights (p <= 2) over ten or more super-chunks take two per wave (measured on 5120 -> 13824: a 2 KiB item
 // per wave leaves the reduction across waves too large a share), and over more than 24 super-chunks the variants
 // with four per wave are ahead of two (K = 13824, M = 1: W2A8 6.5 vs 7.3 us, W4A8 9.2 vs 9.9; W4A8 M = 4: 11.0 vs 11.6;
-// but W2A8 M = 4: 8.3 vs 8.0, which keeps two).  forced_r > 0 (plan table) replaces the rule where it fits.
+// W1A8 M = 4: 7.2 vs 8.1; but W2A8 M = 4: 8.3 vs 8.0, which keeps two).  forced_r > 0 (plan table) replaces the rule where it fits.
 bool direct_plan(int p, int M, int nsuper, int forced_r, DirectPlan* out)
 {
     if (M < 1 || M > 16 || nsuper < 1) return false;
@@ -26,7 +26,7 @@ bool direct_plan(int p, int M, int nsuper, int forced_r, DirectPlan* out)
         for (int cand : {1, 2, 4})
             if (fits(cand)) { R = cand; break; }
         if (R == 1 && p <= 2 && nsuper >= 10 && fits(2)) R = 2;
-        if (R == 2 && nsuper > 24 && fits(4) && (M == 1 || p == 4)) R = 4;
+        if (R == 2 && nsuper > 24 && fits(4) && (M == 1 || p == 4 || p == 1)) R = 4;
     }
     if (R == 0) return false;
     out->MR = MR; out->R = R; out->S = (nsuper + R - 1) / R;
