@@ -170,6 +170,10 @@ def measured_peaks(pool, workload_bytes, launches=200):
     for key, pattern in (("mfma_i8_mostly_zero_operand_bytes", 0), ("mfma_i8_nonzero_operand_bytes", 1)):
         t = timed(lambda i: abq.abq_probe_mfma_i8(iters, pattern, sink), 10)
         out[key] = {"us": t * 1e6, "tops": abq.abq_probe_mfma_i8_ops(iters) / t / 1e12}
+    # the 4-bit floating-point MFMA (codes of up to two bits are E2M1 values): what a very-low-bit prefill kernel could reach
+    for key, pattern in (("mfma_f4_mostly_zero_operands", 0), ("mfma_f4_nonzero_operands", 1)):
+        t = timed(lambda i: abq.abq_probe_mfma_f4(iters, pattern, sink), 10)
+        out[key] = {"us": t * 1e6, "tops": abq.abq_probe_mfma_f4_ops(iters) / t / 1e12}
     return out
 
 

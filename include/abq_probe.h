@@ -30,6 +30,13 @@ int abq_probe_stream_read(const void* buf, size_t bytes, void* sink, void* strea
 int abq_probe_mfma_i8(int iters, int pattern, void* sink, void* stream);
 double abq_probe_mfma_i8_ops(int iters);
 
+/* The same issue loop on gfx950's 4-bit floating-point MFMA (16x16x128, E2M1 operands, binary32 accumulate, block
+ * scales of one; the codes of a 1- or 2-bit operand are E2M1 values and their product sums stay exact): the rate a
+ * very-low-bit prefill kernel could price itself against.  Arguments, patterns and errors as abq_probe_mfma_i8;
+ * abq_probe_mfma_f4_ops(iters) counts 2 operations per multiply-accumulate. */
+int abq_probe_mfma_f4(int iters, int pattern, void* sink, void* stream);
+double abq_probe_mfma_f4_ops(int iters);
+
 #ifdef __cplusplus
 }
 #endif

@@ -52,6 +52,33 @@ __global__ void mfma_i8_kernel(int iters, int pattern, uint32_t* sink)   // (no 
     if (s == 0x12345 && iters < 0) sink[t] = (uint32_t)s;
 }
 
+// The same issue loop on the 4-bit floating-point MFMA of gfx950 (16x16x128, E2M1 operands, binary32 accumulate, block
+// scales of one): the codes 0..3 of a 1- or 2-bit operand are E2M1 values, and sums of their products stay exact in
+// binary32 far beyond any K here, so this is the rate a W<=2 A<=2 prefill kernel could price itself against.  Operand
+// patterns as above (E2M1 has no infinity or NaN encodings).
+typedef int v8i_probe __attribute__((ext_vector_type(8)));
+typedef float v4f_probe __attribute__((ext_vector_type(4)));
+__global__ void mfma_f4_kernel(int iters, int pattern, uint32_t* sink)
+{
+    v4f_probe acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = v4f_probe{0.f, 0.f, 0.f, 0.f};
+    const int t = (int)threadIdx.x;
+    const int h = (t * 0x9E3779B1) ^ (t << 13);
+    // (32 E2M1 values per lane: the low four of the eight operand registers)
+    const v8i_probe a = pattern ? v8i_probe{h, h * 3 + 0x5A5A5A5A, ~h, h * 7 + 0x33CC33CC, 0, 0, 0, 0} : v8i_probe{t & 0x22, 2, 0, 0x20, 0, 0, 0, 0};
+    const v8i_probe b = pattern ? v8i_probe{h * 5, ~(h * 11), h * 13 + 0x0F0F0F0F, h * 17, 0, 0, 0, 0} : v8i_probe{0x200, 0, 2, t & 0x22, 0, 0, 0, 0};
+    const int one = 0x7F7F7F7F;   // E8M0 block scales of 2^0
+    for (int i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, acc[j], 4, 4, 0, one, 0, one);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) s += acc[j].x + acc[j].y + acc[j].z + acc[j].w;
+    if (s == 12345.f && iters < 0) sink[t] = (uint32_t)s;
+}
+
 static const int kProbeWaveMfmas = 8;          // per round
 static const int kProbeWgsPerCu = 8, kProbeWaves = 4;
 
@@ -90,6 +117,22 @@ double abq_probe_mfma_i8_ops(int iters)
     int dev = 0, cus = 256;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
     return 2.0 * 16 * 16 * 64 * (double)kProbeWaveMfmas * iters * kProbeWaves * kProbeWgsPerCu * cus;
+}
+
+double abq_probe_mfma_f4_ops(int iters)
+{
+    return 2.0 * abq_probe_mfma_i8_ops(iters);   // (twice the K per instruction)
+}
+
+int abq_probe_mfma_f4(int iters, int pattern, void* sink, void* stream)
+{
+    if (!sink) return -1;
+    if (iters < 1 || iters > (1 << 20) || pattern < 0 || pattern > 1) return -3;
+    if ((uintptr_t)sink & 15u) return -4;
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+    mfma_f4_kernel<<<(unsigned)(cus * kProbeWgsPerCu), kProbeWaves * 64, 0, (hipStream_t)stream>>>(iters, pattern, (uint32_t*)sink);
+    return hipGetLastError() == hipSuccess ? 0 : -7;
 }
 
 int abq_probe_mfma_i8(int iters, int pattern, void* sink, void* stream)

@@ -13,6 +13,8 @@ _SIGNATURES = {
     "abq_probe_stream_read": (_c.c_int, [_c.c_void_p, _c.c_size_t, _c.c_void_p, _c.c_void_p]),
     "abq_probe_mfma_i8": (_c.c_int, [_c.c_int, _c.c_int, _c.c_void_p, _c.c_void_p]),
     "abq_probe_mfma_i8_ops": (_c.c_double, [_c.c_int]),
+    "abq_probe_mfma_f4": (_c.c_int, [_c.c_int, _c.c_int, _c.c_void_p, _c.c_void_p]),
+    "abq_probe_mfma_f4_ops": (_c.c_double, [_c.c_int]),
 }
 _lib = None
 
@@ -47,3 +49,11 @@ def abq_probe_mfma_i8(iters, pattern, sink):
 
 def abq_probe_mfma_i8_ops(iters):
     return load().abq_probe_mfma_i8_ops(iters)
+
+
+def abq_probe_mfma_f4(iters, pattern, sink):
+    _run(load().abq_probe_mfma_f4(iters, pattern, sink.data_ptr(), torch.cuda.current_stream().cuda_stream), "abq_probe_mfma_f4")
+
+
+def abq_probe_mfma_f4_ops(iters):
+    return load().abq_probe_mfma_f4_ops(iters)

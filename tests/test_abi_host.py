@@ -260,6 +260,10 @@ def test_probe_rejects():
     assert lib.abq_probe_mfma_i8(0, 0, A16, None) == B.ABQ_ERR_SHAPE
     assert lib.abq_probe_mfma_i8(10, 2, A16, None) == B.ABQ_ERR_SHAPE
     assert lib.abq_probe_mfma_i8_ops(0) == 0.0
+    assert lib.abq_probe_mfma_f4(10, 0, None, None) == B.ABQ_ERR_NULL
+    assert lib.abq_probe_mfma_f4(0, 0, A16, None) == B.ABQ_ERR_SHAPE
+    assert lib.abq_probe_mfma_f4(10, 2, A16, None) == B.ABQ_ERR_SHAPE
+    assert lib.abq_probe_mfma_f4_ops(0) == 0.0
 
 
 def test_rmsnorm_quant_act_rejects():

@@ -583,6 +583,8 @@ def test_measurement_probes_run(abq):
     abq.abq_probe_stream_read(buf[256:], 4096 + 16, sink)       # a ragged size: the last workgroup clamps its reads
     abq.abq_probe_mfma_i8(100, 0, sink)
     abq.abq_probe_mfma_i8(100, 1, sink)
+    abq.abq_probe_mfma_f4(100, 0, sink)
+    abq.abq_probe_mfma_f4(100, 1, sink)
     torch.cuda.synchronize()
     assert int(sink.sum()) == 0
     assert abq.abq_probe_mfma_i8_ops(1) == 2.0 * 16 * 16 * 64 * 8 * 4 * 8 * torch.cuda.get_device_properties(0).multi_processor_count
