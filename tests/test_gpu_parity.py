@@ -544,6 +544,43 @@ def test_graph_replays_match_eager(abq):
             check_against_oracle(c0, y1.cpu().numpy(), None)
 
 
+def test_graph_replays_match_eager_on_the_shared_operand_kernel(abq):
+    """Sixteen rows over more tiles than compute units (the shared-operand decode kernel, by rule), captured and replayed
+    with new activations: every replay equals the eager result and the oracle."""
+    p, q, M, N, K = 2, 8, 16, 4400, 2048
+    c = synth.make_case(p, q, M, N, K, seed=611)
+    pw = abq.abq_pack_weights(p, to_dev(torch, c.W), to_dev(torch, c.w_scale), to_dev(torch, c.w_zero), FIELDS)
+    codes = torch.zeros((M, K), dtype=torch.uint8, device="cuda")
+    scale, zero = to_dev(torch, c.a_scale), to_dev(torch, c.a_zero)
+    y = torch.empty((M, N), dtype=torch.float16, device="cuda")
+    rng = np.random.Generator(np.random.PCG64(612))
+
+    def run():
+        abq.abq_gemm_act_codes(p, q, M, N, K, codes, scale, zero, pw, FIELDS, y=y)
+
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        run()
+        stream.synchronize()
+        assert abq.abq_last_decode_kernel() == abq.ABQ_DECODE_SHARED_OPERAND
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            run()
+        for rep in range(3):
+            a = rng.integers(0, 1 << q, size=(M, K), dtype=np.uint8)
+            codes.copy_(torch.from_numpy(a).cuda())
+            y.fill_(float("nan"))
+            graph.replay()
+            stream.synchronize()
+            got = y.clone()
+            y.fill_(float("nan"))
+            run()
+            stream.synchronize()
+            assert torch.equal(got.view(torch.int16), y.view(torch.int16)), f"replay {rep} differs from the eager run"
+            c.A = a
+            check_against_oracle(c, y.cpu().numpy(), None)
+
+
 def test_check_packed_reads_the_blob_header(abq):
     """abq_check_packed accepts a blob with the geometry it was packed with and names every mismatch."""
     F, P, G128 = FIELDS, PLANES, abq.ABQ_LAYOUT_FIELDS_G128
