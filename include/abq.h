@@ -268,6 +268,26 @@ int abq_gemm_act_codes_static(int p, int q, int M, int N, int K,
                               const void* packed_w, int w_layout,
                               uint16_t* y_fp16, int32_t* acc_i32, void* stream);
 
+/* Very low bit widths on gfx950's 4-bit floating-point MFMA (Sec. 3.4 / Table 4: narrower operands should run faster;
+ * Appendix B's sum over 1-bit planes is what makes that true on tensor cores that multiply bits).  For weights AND
+ * activations of one or two bits the codes 0..3 are E2M1 values and the sums of their products are exact in the
+ * instruction's binary32 accumulator for every K <= ABQ_MAX_K, so abq_f4_gemm returns the same int32 accumulator and
+ * binary16 output as abq_gemm, at twice the matrix rate of the int8 path.  Both operands use one packed layout:
+ *   abq_f4_packed_bytes(bits, rows, K)  size of the blob for a [rows][K] operand (0 for arguments out of range)
+ *   abq_f4_pack_codes   codes u8 [rows][K] (device, row-major; bits above `bits` are dropped), scale f32 [rows] and
+ *                       zero i32 [rows] (device) -> blob `packed_out` (device, caller-owned, >= the size above); for
+ *                       the weights rows = N, for the activations rows = M
+ *   abq_f4_gemm         Y[M,N] = dequant(A . W^T) from two such blobs (p: bits of W, q: bits of A, both 1 or 2);
+ *                       y_fp16 [M][N] device, acc_i32 [M][N] device or NULL
+ * Device pointers 16-byte aligned; work is enqueued on `stream`; nothing is allocated.  ABQ_ERR_NULL, ABQ_ERR_BITS
+ * (bits outside 1..2), ABQ_ERR_SHAPE, ABQ_ERR_ALIGN, ABQ_ERR_SIZE, ABQ_ERR_HIP as elsewhere.  The blobs are not
+ * interchangeable with those of abq_pack_weights / abq_pack_act_codes. */
+size_t abq_f4_packed_bytes(int bits, int rows, int K);
+int abq_f4_pack_codes(int bits, int rows, int K, const uint8_t* codes, const float* scale, const int32_t* zero,
+                      void* packed_out, size_t packed_bytes, void* stream);
+int abq_f4_gemm(int p, int q, int M, int N, int K, const void* packed_act, const void* packed_w,
+                uint16_t* y_fp16, int32_t* acc_i32, void* stream);
+
 /* Launch-plan table (Appendix D, "auto kernel search": the engine picks, per problem size, the fastest of a
  * set of kernel configurations found by timing them).  The library chooses every launch plan from closed-form
  * rules; this table lets a tuner (paper_2408_08554_amd/tune.py times the candidates on the device) replace the

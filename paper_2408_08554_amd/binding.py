@@ -34,6 +34,9 @@ _SIGNATURES = {
     "abq_plan_set": (_c.c_int, [_c.c_int] * 5 + [_c.c_void_p]),
     "abq_plan_get": (_c.c_int, [_c.c_int] * 5 + [_c.c_void_p]),
     "abq_plan_clear": (None, []),
+    "abq_f4_packed_bytes": (_c.c_size_t, [_c.c_int] * 3),
+    "abq_f4_pack_codes": (_c.c_int, [_c.c_int] * 3 + [_c.c_void_p] * 3 + [_c.c_void_p, _c.c_size_t, _c.c_void_p]),
+    "abq_f4_gemm": (_c.c_int, [_c.c_int] * 5 + [_c.c_void_p] * 4 + [_c.c_void_p]),
     "abq_unpack_weights": (_c.c_int, [_c.c_int] * 4 + [_c.c_void_p, _c.c_int, _c.c_void_p, _c.c_void_p]),
     "abq_packed_act_bytes": (_c.c_size_t, [_c.c_int] * 4),
     "abq_quant_pack_act": (_c.c_int, [_c.c_int] * 3 + [_c.c_void_p, _c.c_int, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
@@ -185,6 +188,30 @@ def abq_pack_act_codes(q, a_codes, a_scale, a_zero, layout=ABQ_LAYOUT_AUTO, out=
     _check(lib.abq_pack_act_codes(q, M, K, _ptr(a_codes), _ptr(a_scale), _ptr(a_zero), layout, _ptr(out), out.numel(),
                                   _stream()), "abq_pack_act_codes")
     return out
+
+
+def abq_f4_pack_codes(bits, codes, scale, zero, out=None):
+    """codes uint8 [rows,K] (weights: rows = N; activations: rows = M) -> blob of the 4-bit floating-point MFMA path."""
+    lib = load()
+    rows, K = codes.shape
+    _dev(codes, torch.uint8), _dev(scale, torch.float32, (rows,)), _dev(zero, torch.int32, (rows,))
+    nbytes = lib.abq_f4_packed_bytes(bits, rows, K)
+    if out is None:
+        out = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=codes.device)
+    _check(lib.abq_f4_pack_codes(bits, rows, K, _ptr(codes), _ptr(scale), _ptr(zero), _ptr(out), out.numel(), _stream()),
+           "abq_f4_pack_codes")
+    return out
+
+
+def abq_f4_gemm(p, q, M, N, K, packed_act, packed_w, y=None, acc=None, want_acc=False):
+    """-> (y float16 [M,N], acc int32 [M,N] or None)."""
+    dev = packed_w.device
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.float16, device=dev)
+    if acc is None and want_acc:
+        acc = torch.empty((M, N), dtype=torch.int32, device=dev)
+    _check(load().abq_f4_gemm(p, q, M, N, K, _ptr(packed_act), _ptr(packed_w), _ptr(y), _ptr(acc), _stream()), "abq_f4_gemm")
+    return y, acc
 
 
 def abq_unpack_act(q, M, K, layout, packed, which):

@@ -438,6 +438,33 @@ static hipError_t launch_decode(const GemmArgs& g, const ActLayout& A, const Wei
     return launch_gemm_skinny(g, A, W, s);
 }
 
+size_t abq_f4_packed_bytes(int bits, int rows, int K)
+{
+    if (bits < 1 || bits > 2 || rows < 1 || K < 1 || K > ABQ_MAX_K) return 0;
+    return f4_packed_bytes(rows, K);
+}
+
+int abq_f4_pack_codes(int bits, int rows, int K, const uint8_t* codes, const float* scale, const int32_t* zero, void* packed_out,
+                      size_t packed_bytes, void* stream)
+{
+    if (!codes || !scale || !zero || !packed_out) return ABQ_ERR_NULL;
+    if (bits < 1 || bits > 2) return ABQ_ERR_BITS;
+    if (rows < 1 || K < 1 || K > ABQ_MAX_K) return ABQ_ERR_SHAPE;
+    if (misaligned(codes) || misaligned(scale) || misaligned(zero) || misaligned(packed_out)) return ABQ_ERR_ALIGN;
+    if (packed_bytes < f4_packed_bytes(rows, K)) return ABQ_ERR_SIZE;
+    return hip_status(launch_f4_pack(bits, rows, K, codes, scale, zero, (uint8_t*)packed_out, (hipStream_t)stream));
+}
+
+int abq_f4_gemm(int p, int q, int M, int N, int K, const void* packed_act, const void* packed_w, uint16_t* y_fp16, int32_t* acc_i32,
+                void* stream)
+{
+    if (!packed_act || !packed_w || !y_fp16) return ABQ_ERR_NULL;
+    if (p < 1 || p > 2 || q < 1 || q > 2) return ABQ_ERR_BITS;
+    if (M < 1 || N < 1 || K < 1 || K > ABQ_MAX_K) return ABQ_ERR_SHAPE;
+    if (misaligned(packed_act) || misaligned(packed_w) || misaligned(y_fp16) || misaligned(acc_i32)) return ABQ_ERR_ALIGN;
+    return hip_status(launch_f4_gemm(M, N, K, (const uint8_t*)packed_act, (const uint8_t*)packed_w, y_fp16, acc_i32, (hipStream_t)stream));
+}
+
 int abq_plan_set(int p, int q, int M, int N, int K, const abq_plan* plan)
 {
     if (int e = check_gemm_shape(p, q, M, N, K)) return e;

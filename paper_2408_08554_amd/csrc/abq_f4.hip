@@ -1,0 +1,284 @@
+// The very-low-bit matmul on gfx950's 4-bit floating-point MFMA: operands of one or two bits (weights AND activations).
+//
+// Appendix B decomposes a p x q-bit matmul into p*q binary ones because the tensor cores it targets multiply 1-bit
+// planes; the point of Sec. 3.4 / Table 4 is that narrower operands should run faster.  The int8 MFMA path of this
+// library carries a whole byte per operand whatever p and q are.  gfx950 has a 16x16x128 MFMA on 4-bit E2M1 operands at
+// twice the int8 rate, and the codes 0..3 are E2M1 values (0, 1, 2, 3 = 0b0000, 0b0010, 0b0100, 0b0101): their products
+// (<= 9) and the sums of them are exact in the instruction's binary32 accumulator as long as K * 9 < 2^24, far beyond
+// any K the library accepts, so the accumulator converts to the same int32 the other kernels produce, and the fused
+// dequant epilogue (Fig. 3b) is theirs.  Block scales of the instruction are 2^0.
+//
+// Both operands use ONE packed layout (so one packer serves weights and activations): after the header and the row
+// parameters, [row tiles of 16][K blocks of 128][64 lanes][16 bytes] — 1 KiB per (16 rows x 128 k), lane L holding row
+// L % 16, k = 128 block + 32 (L / 16) .. + 31 as 32 nibbles, which is the MFMA operand of that block as it stands.
+// Rows past the end and k past K hold code 0.
+//
+// Kernel: workgroup tile 256 rows of A x 128 channels of W, four waves of 64 x 128 each (32 accumulator tiles), K in
+// steps of 128: the step's 16 + 8 operand blocks go global -> LDS with direct 128-bit loads (a block is one wave
+// instruction and lands in LDS as the operand layout: conflict-free 128-bit reads), requested two steps ahead (three
+// buffers), one barrier per step; two workgroups share a compute unit and hide each other's waits.
+#include "abq_internal.h"
+#include "../../include/abq.h"
+
+#include <atomic>
+
+namespace abq {
+
+typedef int v4i_f4 __attribute__((ext_vector_type(4)));
+typedef int v8i_f4 __attribute__((ext_vector_type(8)));
+typedef float v4f_f4 __attribute__((ext_vector_type(4)));
+
+constexpr int kF4BlockK = 128;                 // k per operand block
+constexpr int kF4TileM = 256, kF4TileN = 128;  // workgroup tile
+constexpr int kF4StepBytes = (kF4TileM + kF4TileN) / 16 * 1024;   // operand blocks of one 128-k step
+constexpr size_t kF4LdsBytes = 3 * kF4StepBytes + (kF4TileM + kF4TileN) * sizeof(RowParams);
+
+static inline int f4_row_tiles(int rows) { return (rows + 15) / 16; }
+static inline int f4_k_blocks(int K) { return (K + kF4BlockK - 1) / kF4BlockK; }
+
+size_t f4_packed_bytes(int rows, int K)
+{
+    return kHeaderBytes + align_up((size_t)rows * sizeof(RowParams), 256) + (size_t)f4_row_tiles(rows) * f4_k_blocks(K) * 1024;
+}
+static inline size_t f4_off_params() { return kHeaderBytes; }
+static inline size_t f4_off_blocks(int rows) { return kHeaderBytes + align_up((size_t)rows * sizeof(RowParams), 256); }
+
+// ---- packer ---------------------------------------------------------------------------------------------------------
+// One thread per (row tile, K block, lane): 32 codes of one row -> 32 E2M1 nibbles (16 bytes).
+__global__ void f4_pack_blocks_kernel(const uint8_t* codes, int rows, int K, int kblocks, uint32_t mask, v4i_f4* out, size_t nvec)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= nvec) return;
+    const int lane = (int)(i & 63);
+    const size_t blk = i >> 6;
+    const int kb = (int)(blk % kblocks), rt = (int)(blk / kblocks);
+    const int row = rt * 16 + (lane & 15), k0 = kb * kF4BlockK + (lane >> 4) * 32;
+    uint32_t w[4] = {0, 0, 0, 0};
+    if (row < rows) {
+        const uint8_t* src = codes + (size_t)row * K;
+        for (int e = 0; e < 32; ++e) {
+            const int k = k0 + e;
+            const uint32_t c = k < K ? (src[k] & mask) : 0u;
+            const uint32_t nib = c == 3 ? 5u : (c << 1);      // 0, 1, 2, 3 as E2M1
+            w[e >> 3] |= nib << (4 * (e & 7));
+        }
+    }
+    out[i] = v4i_f4{(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
+}
+
+// Row parameters {sum of the row's codes, scale, zero}: one workgroup per row.
+__global__ void f4_row_params_kernel(const uint8_t* codes, int K, uint32_t mask, const float* scale, const int32_t* zero, RowParams* out)
+{
+    __shared__ int32_t part[256];
+    const int row = (int)blockIdx.x;
+    const uint8_t* src = codes + (size_t)row * K;
+    int32_t s = 0;
+    for (int k = (int)threadIdx.x; k < K; k += (int)blockDim.x) s += (int32_t)(src[k] & mask);
+    part[threadIdx.x] = s;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) part[threadIdx.x] += part[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) out[row] = RowParams{part[0], scale[row], zero[row], 0};
+}
+
+__global__ void f4_header_kernel(uint32_t* hdr, uint32_t magic, int bits, int rows, int K)
+{
+    const int t = (int)threadIdx.x;
+    if (t < 64) hdr[t] = t == 0 ? magic : (t == 1 ? 0x34460001u : (t == 2 ? (uint32_t)bits : (t == 3 ? (uint32_t)rows : (t == 4 ? (uint32_t)K : 0u))));
+}
+
+hipError_t launch_f4_pack(int bits, int rows, int K, const uint8_t* codes, const float* scale, const int32_t* zero, uint8_t* blob, hipStream_t s)
+{
+    const uint32_t mask = (1u << bits) - 1u;
+    f4_header_kernel<<<1, 64, 0, s>>>((uint32_t*)blob, 0x34514241u /* "ABQ4" */, bits, rows, K);
+    f4_row_params_kernel<<<(unsigned)rows, 256, 0, s>>>(codes, K, mask, scale, zero, (RowParams*)(blob + f4_off_params()));
+    const size_t nvec = (size_t)f4_row_tiles(rows) * f4_k_blocks(K) * 64;
+    f4_pack_blocks_kernel<<<(unsigned)((nvec + 255) / 256), 256, 0, s>>>(codes, rows, K, f4_k_blocks(K), mask, (v4i_f4*)(blob + f4_off_blocks(rows)), nvec);
+    return hipGetLastError();
+}
+
+// ---- matmul ---------------------------------------------------------------------------------------------------------
+struct F4Params {
+    const v4i_f4* a_blocks;    // [row tiles][kblocks][64]
+    const v4i_f4* w_blocks;
+    const RowParams* aparams;
+    const RowParams* wparams;
+    uint16_t* y;
+    int32_t* acc;              // may be null
+    int M, N, K, kblocks;
+    int a_tiles, w_tiles;      // 16-row tiles of the two operands
+    int tiles_m, tiles_n;      // workgroup tiles
+};
+
+__global__ __launch_bounds__(256, 2) void f4_gemm_kernel(F4Params prm)
+{
+    // three buffers of a step's operands: 16 blocks of A (256 rows) then 8 blocks of W (128 channels), 1 KiB each; then
+    // the epilogue parameters
+    extern __shared__ __align__(16) uint8_t lds_f4[];
+    uint8_t* const buf0 = lds_f4;
+    uint8_t* const buf1 = lds_f4 + kF4StepBytes;
+    uint8_t* const buf2 = lds_f4 + 2 * kF4StepBytes;
+    RowParams* const par_a = reinterpret_cast<RowParams*>(lds_f4 + 3 * kF4StepBytes);
+    RowParams* const par_w = par_a + kF4TileM;
+    const int tid = (int)threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // Workgroup b runs on XCD b % 8 and each XCD has its own L2: give every XCD a contiguous run of the tile order, row
+    // blocks fastest, so that the workgroups resident on one XCD share their column blocks of W and a few row blocks of A.
+    const int nwg = prm.tiles_m * prm.tiles_n;
+    const int xcd = (int)blockIdx.x & 7, slot = (int)blockIdx.x >> 3;
+    const int per = nwg >> 3, rem = nwg & 7;
+    const int vid = xcd * per + min(xcd, rem) + slot;
+    const int m_blk = vid % prm.tiles_m, n_blk = vid / prm.tiles_m;
+    const int m0 = m_blk * kF4TileM, n0 = n_blk * kF4TileN;
+
+    // epilogue parameters
+    par_a[tid] = prm.aparams[min(m0 + tid, prm.M - 1)];
+    if (tid < kF4TileN) par_w[tid] = prm.wparams[min(n0 + tid, prm.N - 1)];
+
+    // this wave's six blocks of a step: blocks 6 wave .. 6 wave + 5 of the 24 (0..15: A row tiles, 16..23: W tiles); tiles
+    // past the operand's end re-read its last tile (their outputs are never stored)
+    const v4i_f4* src[6];
+#pragma unroll
+    for (int u = 0; u < 6; ++u) {
+        const int blk = wave * 6 + u;   // wave-uniform
+        if (blk < 16) src[u] = prm.a_blocks + ((size_t)min(m0 / 16 + blk, prm.a_tiles - 1) * prm.kblocks) * 64 + lane;
+        else src[u] = prm.w_blocks + ((size_t)min(n0 / 16 + (blk - 16), prm.w_tiles - 1) * prm.kblocks) * 64 + lane;
+    }
+    auto prefetch = [&](int step, uint8_t* buf) {
+#pragma unroll
+        for (int u = 0; u < 6; ++u)
+            __builtin_amdgcn_global_load_lds((const void*)(src[u] + (size_t)step * 64),
+                                             (__attribute__((address_space(3))) void*)(buf + (wave * 6 + u) * 1024), 16, 0, 0);
+    };
+
+    v4f_f4 acc[4][8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[i][j] = v4f_f4{0.f, 0.f, 0.f, 0.f};
+
+    const int one = 0x7F7F7F7F;   // block scales of 2^0
+    auto multiply = [&](const uint8_t* buf) {
+        // wave w: rows 64 w .. 64 w + 63 of the workgroup tile (A blocks 4 w .. 4 w + 3), all eight W blocks
+        v8i_f4 a[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const v4i_f4 x = *reinterpret_cast<const v4i_f4*>(buf + (wave * 4 + i) * 1024 + lane * 16);
+            a[i] = v8i_f4{x.x, x.y, x.z, x.w, 0, 0, 0, 0};
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const v4i_f4 x = *reinterpret_cast<const v4i_f4*>(buf + (16 + j) * 1024 + lane * 16);
+            const v8i_f4 b = v8i_f4{x.x, x.y, x.z, x.w, 0, 0, 0, 0};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a[i], b, acc[i][j], 4, 4, 0, one, 0, one);
+        }
+    };
+
+    // Operands are requested two steps ahead.  The direct loads of a buffer have to have landed before the barrier behind
+    // which the other waves read it (the barrier's own fence covers LDS instructions, not these loads), so the wait is
+    // written out: all but the youngest step's six loads, which stay in flight across the barrier.
+    const int nsteps = prm.kblocks;
+    prefetch(0, buf0);
+    if (nsteps > 1) prefetch(1, buf1);
+    if (nsteps > 1) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    auto one_step = [&](int step, uint8_t* cur, uint8_t* ahead) {   // ahead: the buffer read in step - 1
+        if (step + 2 < nsteps) prefetch(step + 2, ahead);
+        multiply(cur);
+        if (step + 2 < nsteps) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+    };
+    for (int step = 0; step < nsteps; step += 3) {
+        one_step(step, buf0, buf2);
+        if (step + 1 < nsteps) one_step(step + 1, buf1, buf0);
+        if (step + 2 < nsteps) one_step(step + 2, buf2, buf1);
+    }
+
+    // ---- epilogue: lane (G, r) of accumulator (i, j) holds rows 64 wave + 16 i + 4 G + reg, channel 16 j + r.
+    // With 128 outputs per lane the epilogue is a third of the kernel if every output is stored on its own (2 bytes per
+    // lane and instruction), so the usual case (no accumulator output, rows of Y a whole number of 16-byte vectors) goes
+    // through LDS: every wave stages its 64 x 128 binary16 results in its own part of the operand buffers (free after
+    // the loop's last barrier; row stride 272 bytes keeps the four row groups of a write on different banks) and writes
+    // them out as 128-bit vectors.  The arithmetic is the fused dequant of the other kernels (Fig. 3b), with the terms
+    // that depend on the column only taken out of the inner loop: centered = S - wz asum - az (wsum - K wz).
+    const int r = lane & 15, G = lane >> 4;
+    if (prm.acc == nullptr && (prm.N & 7) == 0) {
+        constexpr int kRowBytes = 272;
+        uint8_t* const stage = lds_f4 + wave * (64 * kRowBytes);
+        uint32_t wz[8], cw[8];
+        float sw[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const RowParams pw = par_w[16 * j + r];
+            wz[j] = (uint32_t)pw.zero;
+            cw[j] = (uint32_t)pw.sum - (uint32_t)prm.K * (uint32_t)pw.zero;
+            sw[j] = pw.scale;
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int reg = 0; reg < 4; ++reg) {
+                const int rl = 16 * i + 4 * G + reg;            // row inside the wave's 64
+                const RowParams pa = par_a[64 * wave + rl];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const uint32_t S = (uint32_t)(int32_t)acc[i][j][reg];
+                    const int32_t centered = (int32_t)(S - wz[j] * (uint32_t)pa.sum - (uint32_t)pa.zero * cw[j]);
+                    const float v = ((float)centered * pa.scale) * sw[j];
+                    uint32_t h;
+                    asm("v_cvt_f16_f32 %0, %1" : "=v"(h) : "v"(v));   // (the instruction itself: see epilogue_value)
+                    *reinterpret_cast<uint16_t*>(stage + rl * kRowBytes + (16 * j + r) * 2) = (uint16_t)h;
+                }
+            }
+        // (the wave reads back what its own lanes wrote: no barrier, the LDS counter orders it)
+#pragma unroll
+        for (int it = 0; it < 16; ++it) {
+            const int c = it * 64 + lane, rl = c >> 4, cc = c & 15;
+            const v4i_f4 x = *reinterpret_cast<const v4i_f4*>(stage + rl * kRowBytes + cc * 16);
+            const int m = m0 + 64 * wave + rl, n = n0 + 8 * cc;
+            if (m < prm.M && n < prm.N) *reinterpret_cast<v4i_f4*>(prm.y + (size_t)m * prm.N + n) = x;
+        }
+        return;
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int nl = 16 * j + r, n = n0 + nl;
+#pragma unroll
+            for (int reg = 0; reg < 4; ++reg) {
+                const int ml = 64 * wave + 16 * i + 4 * G + reg, m = m0 + ml;
+                if (m < prm.M && n < prm.N)
+                    epilogue_store((int32_t)acc[i][j][reg], 0, 0, prm.K, par_a[ml], par_w[nl], (size_t)m * prm.N + n, prm.y, prm.acc);
+            }
+        }
+}
+
+hipError_t launch_f4_gemm(int M, int N, int K, const uint8_t* act_blob, const uint8_t* w_blob, uint16_t* y, int32_t* acc, hipStream_t s)
+{
+    F4Params prm;
+    prm.a_blocks = (const v4i_f4*)(act_blob + f4_off_blocks(M));
+    prm.w_blocks = (const v4i_f4*)(w_blob + f4_off_blocks(N));
+    prm.aparams = (const RowParams*)(act_blob + f4_off_params());
+    prm.wparams = (const RowParams*)(w_blob + f4_off_params());
+    prm.y = y; prm.acc = acc;
+    prm.M = M; prm.N = N; prm.K = K; prm.kblocks = f4_k_blocks(K);
+    prm.a_tiles = f4_row_tiles(M); prm.w_tiles = f4_row_tiles(N);
+    prm.tiles_m = (M + kF4TileM - 1) / kF4TileM;
+    prm.tiles_n = (N + kF4TileN - 1) / kF4TileN;
+    static std::atomic<bool> attr_set{false};   // (an idempotent call: a lost race only repeats it)
+    if (!attr_set.load(std::memory_order_acquire)) {
+        const hipError_t e = hipFuncSetAttribute((const void*)f4_gemm_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kF4LdsBytes);
+        if (e != hipSuccess) return e;
+        attr_set.store(true, std::memory_order_release);
+    }
+    f4_gemm_kernel<<<(unsigned)(prm.tiles_m * prm.tiles_n), 256, kF4LdsBytes, s>>>(prm);
+    return hipGetLastError();
+}
+
+}  // namespace abq

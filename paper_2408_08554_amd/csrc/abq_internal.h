@@ -140,6 +140,10 @@ struct DirectPlan { int MR, R, S; };
 bool direct_plan(int p, int M, int nsuper, int forced_r, DirectPlan* out);   // false: the problem does not fit this kernel
 hipError_t launch_gemm_direct(const GemmArgs& g, const ActLayout& A, const WeightLayout& W, const DirectPlan& pl, hipStream_t s);
 bool gemm_direct_grouped_fits(int p, int M, int count, const GemmArgs* probs, const ActLayout* A, const WeightLayout* W);
+// The very-low-bit path on the 4-bit floating-point MFMA (operands of one or two bits): one packed layout for both operands.
+size_t f4_packed_bytes(int rows, int K);
+hipError_t launch_f4_pack(int bits, int rows, int K, const uint8_t* codes, const float* scale, const int32_t* zero, uint8_t* blob, hipStream_t s);
+hipError_t launch_f4_gemm(int M, int N, int K, const uint8_t* act_blob, const uint8_t* w_blob, uint16_t* y, int32_t* acc, hipStream_t s);
 // The shared-operand decode kernel (9 .. 16 rows of A over more tiles than compute units): workgroups, waves per
 // workgroup, super-chunks per wave and phase at most, phases of K (1 or 2), super-chunks per phase.
 struct SharedAPlan { int nwg, S, R, phases, H; };

@@ -248,6 +248,22 @@ def test_gemm_grouped_rejects_and_workspace_query():
     assert query(_problems(codes), p=0) == 0
 
 
+def test_f4_entry_points_reject_bad_arguments():
+    lib = B.load()
+    assert lib.abq_f4_packed_bytes(2, 16, 128) == 256 + 256 + 1024
+    assert lib.abq_f4_packed_bytes(2, 17, 129) == 256 + 512 + 4 * 1024
+    assert lib.abq_f4_packed_bytes(3, 16, 128) == 0 and lib.abq_f4_packed_bytes(2, 0, 128) == 0
+    assert lib.abq_f4_pack_codes(2, 16, 128, None, A16, A16, A16, 4096, None) == B.ABQ_ERR_NULL
+    assert lib.abq_f4_pack_codes(3, 16, 128, A16, A16, A16, A16, 4096, None) == B.ABQ_ERR_BITS
+    assert lib.abq_f4_pack_codes(2, 0, 128, A16, A16, A16, A16, 4096, None) == B.ABQ_ERR_SHAPE
+    assert lib.abq_f4_pack_codes(2, 16, 128, A16 + 4, A16, A16, A16, 4096, None) == B.ABQ_ERR_ALIGN
+    assert lib.abq_f4_pack_codes(2, 16, 128, A16, A16, A16, A16, 1535, None) == B.ABQ_ERR_SIZE
+    assert lib.abq_f4_gemm(2, 2, 1, 1, 1, None, A16, A16, None, None) == B.ABQ_ERR_NULL
+    assert lib.abq_f4_gemm(3, 2, 1, 1, 1, A16, A16, A16, None, None) == B.ABQ_ERR_BITS
+    assert lib.abq_f4_gemm(2, 2, 1, 0, 1, A16, A16, A16, None, None) == B.ABQ_ERR_SHAPE
+    assert lib.abq_f4_gemm(2, 2, 1, 1, 1, A16, A16, A16 + 2, None, None) == B.ABQ_ERR_ALIGN
+
+
 def test_probe_rejects():
     from paper_2408_08554_amd import probe
     lib = probe.load()
