@@ -27,6 +27,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0           # MI355X published HBM3E bandwidth
 INT8_MFMA_PEAK_TOPS = 5000.0    # MI355X published dense int8
+F4_MFMA_PEAK_TOPS = 10100.0     # MI355X published dense fp4 (the 4-bit floating-point MFMA of the very-low-bit path)
 
 # HBM bytes per launch of the dominant kernel come from the rocprofv3 --pmc summaries under profiles/ (FETCH_SIZE and
 # WRITE_SIZE per dispatch, each scaled by what the same counter reads for a plain copy of known size in the same
@@ -437,7 +438,8 @@ def main():
     ap.add_argument("--workload", default="c2", help="c1 | c2 | c3m<M> | w2starm<M> | c4m<M> | c5:p,q,shape,m | custom:p,q,M,N,K")
     ap.add_argument("--mode", default="graph", choices=["graph", "eager"],
                     help="graph: the timed steps are replayed from one captured HIP graph; eager: launched one by one")
-    ap.add_argument("--family", default="auto", choices=["auto", "mfma", "bitserial"])
+    ap.add_argument("--family", default="auto", choices=["auto", "mfma", "bitserial", "f4"],
+                    help="f4: the very-low-bit path on the 4-bit floating-point MFMA (p, q <= 2; abq_f4_pack_codes + abq_f4_gemm)")
     ap.add_argument("--step", default="auto", choices=["auto", "fused", "two"],
                     help="fused: abq_gemm_act_codes; two: abq_pack_act_codes + abq_gemm; auto: fused where that is one kernel")
     ap.add_argument("--rotate-gib", type=float, default=1.0, help="total size of the rotating weight buffers")
@@ -492,7 +494,9 @@ def main():
         return
     c = build_case(args.workload)
     p, q, M, N, K = c.p, c.q, c.M, c.N, c.K
-    layout = {"auto": abq.ABQ_LAYOUT_FIELDS, "mfma": abq.ABQ_LAYOUT_FIELDS, "bitserial": abq.ABQ_LAYOUT_PLANES}[args.family]
+    f4 = args.family == "f4"
+    assert not f4 or (p <= 2 and q <= 2 and not args.g128 and args.step != "fused"), "--family f4: p, q <= 2, two-call step"
+    layout = {"auto": abq.ABQ_LAYOUT_FIELDS, "mfma": abq.ABQ_LAYOUT_FIELDS, "bitserial": abq.ABQ_LAYOUT_PLANES, "f4": abq.ABQ_LAYOUT_FIELDS}[args.family]
     wl = layout   # layout value of the weight blob
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
@@ -505,6 +509,9 @@ def main():
         wl = abq.ABQ_LAYOUT_FIELDS_G128
         blob0 = abq.abq_pack_weights_g128(p, w_codes, dev(g_scale_half.view(np.float16)), dev(g_zero))
         c.name += " g128"
+    elif f4:
+        blob0 = abq.abq_f4_pack_codes(p, w_codes, w_scale, w_zero)
+        c.name += " f4"
     else:
         blob0 = abq.abq_pack_weights(p, w_codes, w_scale, w_zero, layout)
     blob_bytes = blob0.numel()
@@ -518,16 +525,20 @@ def main():
     del w_codes
 
     a_codes, a_scale, a_zero = dev(c.A), dev(c.a_scale), dev(c.a_zero)
-    pa = torch.empty(abq.abq_packed_act_bytes(q, M, K, layout), dtype=torch.uint8, device="cuda")
+    pa = torch.empty(abq.load().abq_f4_packed_bytes(q, M, K) if f4 else abq.abq_packed_act_bytes(q, M, K, layout), dtype=torch.uint8, device="cuda")
     y = torch.empty((M, N), dtype=torch.float16, device="cuda")
     ws_bytes = abq.abq_gemm_workspace_bytes(p, q, M, N, K)
     ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
 
     fused_ws_bytes = abq.abq_gemm_act_codes_workspace_bytes(p, q, M, N, K, wl)
-    fused = args.step == "fused" or (args.step == "auto" and fused_ws_bytes == 0)
+    fused = not f4 and (args.step == "fused" or (args.step == "auto" and fused_ws_bytes == 0))
     fws = torch.empty(max(fused_ws_bytes, 16), dtype=torch.uint8, device="cuda")
 
     def two_step(i):
+        if f4:
+            abq.abq_f4_pack_codes(q, a_codes, a_scale, a_zero, out=pa)
+            abq.abq_f4_gemm(p, q, M, N, K, pa, blobs[i % R], y=y)
+            return
         abq.abq_pack_act_codes(q, a_codes, a_scale, a_zero, layout, out=pa)
         abq.abq_gemm(p, q, M, N, K, pa, layout, blobs[i % R], wl, y=y, workspace=ws)
 
@@ -535,6 +546,9 @@ def main():
         abq.abq_gemm_act_codes(p, q, M, N, K, a_codes, a_scale, a_zero, blobs[i % R], wl, y=y, workspace=fws)
 
     def gemm_alone(i):
+        if f4:
+            abq.abq_f4_gemm(p, q, M, N, K, pa, blobs[i % R], y=y)
+            return
         abq.abq_gemm(p, q, M, N, K, pa, layout, blobs[i % R], wl, y=y, workspace=ws)
 
     step = fused_step if fused else two_step
@@ -568,7 +582,10 @@ def main():
     elif not args.no_check:
         import oracle
         acc = torch.empty((M, N), dtype=torch.int32, device="cuda")
-        abq.abq_pack_act_codes(q, a_codes, a_scale, a_zero, layout, out=pa)
+        if f4:
+            abq.abq_f4_pack_codes(q, a_codes, a_scale, a_zero, out=pa)
+        else:
+            abq.abq_pack_act_codes(q, a_codes, a_scale, a_zero, layout, out=pa)
         rng = np.random.Generator(np.random.PCG64(7))
         ms = rng.integers(0, M, 2048).astype(np.int32)
         ns = rng.integers(0, N, 2048).astype(np.int32)
@@ -578,8 +595,10 @@ def main():
         ytol = np.maximum(np.maximum(1e-2 * np.abs(yref), 2.0 ** (np.floor(np.log2(np.maximum(np.abs(yref), 2.0 ** -14))) - 9)),
                           2.0 ** -24)
         for slot in (0, R - 1):
-            for name in ("two calls", "fused"):
-                if name == "fused":
+            for name in (("two calls",) if f4 else ("two calls", "fused")):
+                if f4:
+                    abq.abq_f4_gemm(p, q, M, N, K, pa, blobs[slot], y=y, acc=acc)
+                elif name == "fused":
                     abq.abq_gemm_act_codes(p, q, M, N, K, a_codes, a_scale, a_zero, blobs[slot], layout, y=y, acc=acc,
                                            workspace=fws)
                 else:
@@ -651,27 +670,27 @@ def main():
     alg_bytes = metrics.gemm_algorithmic_bytes(p, q, M, N, K)
     if args.g128:
         alg_bytes += 3 * N * ((K + 127) // 128)   # a binary16 scale and a one-byte zero-point per channel and group
-    hbm_bound = M <= 39 * p
+    hbm_bound = M <= 39 * p and not f4
     if hbm_bound:
         achieved = alg_bytes / gemm_s / 1e9
         roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": achieved / HBM_PEAK_GBS, "traffic": None}
     else:
         achieved = 2.0 * M * N * K / gemm_s / 1e12
-        roof = {"bound": "mfma", "achieved": achieved, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
-                "frac": achieved / INT8_MFMA_PEAK_TOPS, "traffic": None}
+        mfma_peak = F4_MFMA_PEAK_TOPS if f4 else INT8_MFMA_PEAK_TOPS
+        roof = {"bound": "mfma", "achieved": achieved, "peak": mfma_peak, "unit": "TOP/s", "frac": achieved / mfma_peak, "traffic": None}
     roof.update(profile_figures(c.name, gemm_s * 1e6))
-    roof.update({"kernel": "abq_gemm_act_codes" if gemm_only is fused_step else "abq_gemm", "kernel_us_hip_events": gemm_s * 1e6, "algorithmic_bytes": alg_bytes,
+    roof.update({"kernel": "abq_gemm_act_codes" if gemm_only is fused_step else ("abq_f4_gemm" if f4 else "abq_gemm"), "kernel_us_hip_events": gemm_s * 1e6, "algorithmic_bytes": alg_bytes,
                  "launches": n_roof})
 
     out = {
         "metric": "effective TOPS (2*M*N*K/s)", "value": metrics.effective_tops(M, N, K, sec_per_step), "unit": "TOPS",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": sec_per_step * 1e3,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f4" if f4 else "int8", "data": "synthetic",
         "config": {"workload": c.name, "p": p, "q": q, "M": M, "N": N, "K": K, "mode": args.mode,
                    "family": args.family, "launch_plans_loaded": plans_loaded, "rotating_weight_buffers": R, "rotating_bytes": R * stride,
                    "step": "abq_gemm_act_codes" + ("" if fused_ws_bytes == 0 else " (two kernels)") if fused
-                           else "abq_pack_act_codes + abq_gemm"},
+                           else ("abq_f4_pack_codes + abq_f4_gemm" if f4 else "abq_pack_act_codes + abq_gemm")},
         "weight_gbs": metrics.weight_gbs(p, N, K, sec_per_step),
         "gemm_only": {"us": gemm_s * 1e6, "tops": metrics.effective_tops(M, N, K, gemm_s),
                       "weight_gbs": metrics.weight_gbs(p, N, K, gemm_s)},
@@ -683,7 +702,7 @@ def main():
     if args.peaks:
         peaks = measured_peaks(pool, alg_bytes)
         out["measured_peaks"] = peaks
-        roof["measured_peak"] = peaks["stream_read_64MiB"]["gbs"] if hbm_bound else peaks["mfma_i8_nonzero_operand_bytes"]["tops"]
+        roof["measured_peak"] = peaks["stream_read_64MiB"]["gbs"] if hbm_bound else peaks["mfma_f4_nonzero_operands" if f4 else "mfma_i8_nonzero_operand_bytes"]["tops"]
         roof["frac_of_measured_peak"] = achieved / roof["measured_peak"]
         if hbm_bound:   # a plain read of the same number of bytes in a launch of its own: the floor for this size
             roof["frac_of_plain_read_same_size"] = peaks["stream_read_workload_size"]["us"] / (gemm_s * 1e6)
@@ -706,6 +725,7 @@ def main():
             "prefill_w6a6_m128_c4": child_summary(["--workload", "c4m128", "--step", "two", *short]),
             "prefill_w6a6_m512_c4": child_summary(["--workload", "c4m512", "--step", "two", *short]),
             "prefill_w4a4_m2048": child_summary(["--workload", "c5:4,4,0,3", "--step", "two", "--roofline-launches", "60", *short]),
+            "prefill_w2a2_m2048_f4_mfma": child_summary(["--workload", "c5:2,2,0,3", "--family", "f4", "--step", "two", "--roofline-launches", "60", *short]),
         }
     print(json.dumps(out), flush=True)
 

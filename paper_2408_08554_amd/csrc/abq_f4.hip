@@ -15,8 +15,9 @@
 //
 // Kernel: workgroup tile 256 rows of A x 128 channels of W, four waves of 64 x 128 each (32 accumulator tiles), K in
 // steps of 128: the step's 16 + 8 operand blocks go global -> LDS with direct 128-bit loads (a block is one wave
-// instruction and lands in LDS as the operand layout: conflict-free 128-bit reads), requested two steps ahead (three
-// buffers), one barrier per step; two workgroups share a compute unit and hide each other's waits.
+// instruction and lands in LDS as the operand layout: conflict-free 128-bit reads), one barrier per step; three workgroups
+// share a compute unit with two operand buffers each, or two with three buffers each (launch_f4_gemm says when), and
+// hide each other's waits.
 #include "abq_internal.h"
 #include "../../include/abq.h"
 
@@ -31,7 +32,6 @@ typedef float v4f_f4 __attribute__((ext_vector_type(4)));
 constexpr int kF4BlockK = 128;                 // k per operand block
 constexpr int kF4TileM = 256, kF4TileN = 128;  // workgroup tile
 constexpr int kF4StepBytes = (kF4TileM + kF4TileN) / 16 * 1024;   // operand blocks of one 128-k step
-constexpr size_t kF4LdsBytes = 3 * kF4StepBytes + (kF4TileM + kF4TileN) * sizeof(RowParams);
 
 static inline int f4_row_tiles(int rows) { return (rows + 15) / 16; }
 static inline int f4_k_blocks(int K) { return (K + kF4BlockK - 1) / kF4BlockK; }
@@ -44,8 +44,19 @@ static inline size_t f4_off_params() { return kHeaderBytes; }
 static inline size_t f4_off_blocks(int rows) { return kHeaderBytes + align_up((size_t)rows * sizeof(RowParams), 256); }
 
 // ---- packer ---------------------------------------------------------------------------------------------------------
-// One thread per (row tile, K block, lane): 32 codes of one row -> 32 E2M1 nibbles (16 bytes).
-__global__ void f4_pack_blocks_kernel(const uint8_t* codes, int rows, int K, int kblocks, uint32_t mask, v4i_f4* out, size_t nvec)
+// Four codes in the bytes of a dword (already masked to 0..3) -> their four E2M1 nibbles in the low 16 bits: a code c
+// becomes c << 1, except 3, which becomes 5 (0, 1, 2, 3 = 0b0000, 0b0010, 0b0100, 0b0101).
+__device__ __forceinline__ uint32_t f4_nibbles(uint32_t x)
+{
+    const uint32_t three = x & (x >> 1) & 0x01010101u;             // 1 in the bytes that hold 3
+    const uint32_t nib = (x << 1) ^ (three * 3u);                  // one E2M1 value per byte
+    const uint32_t pairs = (nib | (nib >> 4)) & 0x00FF00FFu;       // bytes 0, 2: nibble pairs (0,1), (2,3)
+    return (pairs | (pairs >> 8)) & 0xFFFFu;
+}
+
+// One thread per (row tile, K block, lane): 32 codes of one row -> 32 E2M1 nibbles (16 bytes).  vec: K is a multiple
+// of 16 and the rows are 16-byte aligned, so the 32 codes are two 128-bit loads.
+__global__ void f4_pack_blocks_kernel(const uint8_t* codes, int rows, int K, int kblocks, uint32_t mask, int vec, v4i_f4* out, size_t nvec)
 {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= nvec) return;
@@ -56,25 +67,46 @@ __global__ void f4_pack_blocks_kernel(const uint8_t* codes, int rows, int K, int
     uint32_t w[4] = {0, 0, 0, 0};
     if (row < rows) {
         const uint8_t* src = codes + (size_t)row * K;
-        for (int e = 0; e < 32; ++e) {
-            const int k = k0 + e;
-            const uint32_t c = k < K ? (src[k] & mask) : 0u;
-            const uint32_t nib = c == 3 ? 5u : (c << 1);      // 0, 1, 2, 3 as E2M1
-            w[e >> 3] |= nib << (4 * (e & 7));
+        if (vec && k0 + 32 <= K) {
+            const uint32_t m4 = mask * 0x01010101u;
+            const v4i_f4 lo = *reinterpret_cast<const v4i_f4*>(src + k0), hi = *reinterpret_cast<const v4i_f4*>(src + k0 + 16);
+            w[0] = f4_nibbles((uint32_t)lo.x & m4) | (f4_nibbles((uint32_t)lo.y & m4) << 16);
+            w[1] = f4_nibbles((uint32_t)lo.z & m4) | (f4_nibbles((uint32_t)lo.w & m4) << 16);
+            w[2] = f4_nibbles((uint32_t)hi.x & m4) | (f4_nibbles((uint32_t)hi.y & m4) << 16);
+            w[3] = f4_nibbles((uint32_t)hi.z & m4) | (f4_nibbles((uint32_t)hi.w & m4) << 16);
+        } else {
+            for (int e = 0; e < 32; ++e) {
+                const int k = k0 + e;
+                const uint32_t c = k < K ? (src[k] & mask) : 0u;
+                const uint32_t nib = c == 3 ? 5u : (c << 1);
+                w[e >> 3] |= nib << (4 * (e & 7));
+            }
         }
     }
     out[i] = v4i_f4{(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
 }
 
 // Row parameters {sum of the row's codes, scale, zero}: one workgroup per row.
-__global__ void f4_row_params_kernel(const uint8_t* codes, int K, uint32_t mask, const float* scale, const int32_t* zero, RowParams* out)
+__global__ void f4_row_params_kernel(const uint8_t* codes, int K, uint32_t mask, int vec, const float* scale, const int32_t* zero, RowParams* out)
 {
     __shared__ int32_t part[256];
     const int row = (int)blockIdx.x;
     const uint8_t* src = codes + (size_t)row * K;
-    int32_t s = 0;
-    for (int k = (int)threadIdx.x; k < K; k += (int)blockDim.x) s += (int32_t)(src[k] & mask);
-    part[threadIdx.x] = s;
+    uint32_t s = 0;
+    int done = 0;
+    if (vec) {   // 128-bit loads, byte sums four at a time
+        const uint32_t m4 = mask * 0x01010101u;
+        done = K & ~15;
+        for (int k = (int)threadIdx.x * 16; k < done; k += (int)blockDim.x * 16) {
+            const v4i_f4 x = *reinterpret_cast<const v4i_f4*>(src + k);
+            s = __builtin_amdgcn_sad_u8((uint32_t)x.x & m4, 0u, s);
+            s = __builtin_amdgcn_sad_u8((uint32_t)x.y & m4, 0u, s);
+            s = __builtin_amdgcn_sad_u8((uint32_t)x.z & m4, 0u, s);
+            s = __builtin_amdgcn_sad_u8((uint32_t)x.w & m4, 0u, s);
+        }
+    }
+    for (int k = done + (int)threadIdx.x; k < K; k += (int)blockDim.x) s += (uint32_t)(src[k] & mask);
+    part[threadIdx.x] = (int32_t)s;
     __syncthreads();
     for (int w = 128; w > 0; w >>= 1) {
         if ((int)threadIdx.x < w) part[threadIdx.x] += part[threadIdx.x + w];
@@ -93,9 +125,10 @@ hipError_t launch_f4_pack(int bits, int rows, int K, const uint8_t* codes, const
 {
     const uint32_t mask = (1u << bits) - 1u;
     f4_header_kernel<<<1, 64, 0, s>>>((uint32_t*)blob, 0x34514241u /* "ABQ4" */, bits, rows, K);
-    f4_row_params_kernel<<<(unsigned)rows, 256, 0, s>>>(codes, K, mask, scale, zero, (RowParams*)(blob + f4_off_params()));
+    const int vec = (K % 16 == 0) ? 1 : 0;   // (the entry point checks that `codes` is 16-byte aligned)
+    f4_row_params_kernel<<<(unsigned)rows, 256, 0, s>>>(codes, K, mask, vec, scale, zero, (RowParams*)(blob + f4_off_params()));
     const size_t nvec = (size_t)f4_row_tiles(rows) * f4_k_blocks(K) * 64;
-    f4_pack_blocks_kernel<<<(unsigned)((nvec + 255) / 256), 256, 0, s>>>(codes, rows, K, f4_k_blocks(K), mask, (v4i_f4*)(blob + f4_off_blocks(rows)), nvec);
+    f4_pack_blocks_kernel<<<(unsigned)((nvec + 255) / 256), 256, 0, s>>>(codes, rows, K, f4_k_blocks(K), mask, vec, (v4i_f4*)(blob + f4_off_blocks(rows)), nvec);
     return hipGetLastError();
 }
 
@@ -112,15 +145,18 @@ struct F4Params {
     int tiles_m, tiles_n;      // workgroup tiles
 };
 
-__global__ __launch_bounds__(256, 2) void f4_gemm_kernel(F4Params prm)
+// NBUF = 2: operands requested one step ahead, 48 KiB of LDS, three workgroups per compute unit; NBUF = 3: two steps ahead,
+// 72 KiB, two workgroups per unit.
+template <int NBUF>
+__global__ __launch_bounds__(256, NBUF == 2 ? 3 : 2) void f4_gemm_kernel(F4Params prm)
 {
-    // three buffers of a step's operands: 16 blocks of A (256 rows) then 8 blocks of W (128 channels), 1 KiB each; then
-    // the epilogue parameters
+    // NBUF buffers of a step's operands: 16 blocks of A (256 rows) then 8 blocks of W (128 channels), 1 KiB each.  After
+    // the K loop the same memory holds the epilogue's staging area (first 34 KiB) and parameters (from 36 KiB).
     extern __shared__ __align__(16) uint8_t lds_f4[];
     uint8_t* const buf0 = lds_f4;
     uint8_t* const buf1 = lds_f4 + kF4StepBytes;
-    uint8_t* const buf2 = lds_f4 + 2 * kF4StepBytes;
-    RowParams* const par_a = reinterpret_cast<RowParams*>(lds_f4 + 3 * kF4StepBytes);
+    uint8_t* const buf2 = lds_f4 + (NBUF - 1) * kF4StepBytes;   // (NBUF = 2: unused)
+    RowParams* const par_a = reinterpret_cast<RowParams*>(lds_f4 + 36 * 1024);
     RowParams* const par_w = par_a + kF4TileM;
     const int tid = (int)threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -132,10 +168,6 @@ __global__ __launch_bounds__(256, 2) void f4_gemm_kernel(F4Params prm)
     const int vid = xcd * per + min(xcd, rem) + slot;
     const int m_blk = vid % prm.tiles_m, n_blk = vid / prm.tiles_m;
     const int m0 = m_blk * kF4TileM, n0 = n_blk * kF4TileN;
-
-    // epilogue parameters
-    par_a[tid] = prm.aparams[min(m0 + tid, prm.M - 1)];
-    if (tid < kF4TileN) par_w[tid] = prm.wparams[min(n0 + tid, prm.N - 1)];
 
     // this wave's six blocks of a step: blocks 6 wave .. 6 wave + 5 of the 24 (0..15: A row tiles, 16..23: W tiles); tiles
     // past the operand's end re-read its last tile (their outputs are never stored)
@@ -177,39 +209,60 @@ __global__ __launch_bounds__(256, 2) void f4_gemm_kernel(F4Params prm)
         }
     };
 
-    // Operands are requested two steps ahead.  The direct loads of a buffer have to have landed before the barrier behind
-    // which the other waves read it (the barrier's own fence covers LDS instructions, not these loads), so the wait is
-    // written out: all but the youngest step's six loads, which stay in flight across the barrier.
+    // Operands are requested NBUF - 1 steps ahead.  The direct loads of a buffer have to have landed before the barrier
+    // behind which the other waves read it (the barrier's own fence covers LDS instructions, not these loads), so the wait
+    // is written out: with three buffers all but the youngest step's six loads, which stay in flight across the barrier.
     const int nsteps = prm.kblocks;
     prefetch(0, buf0);
-    if (nsteps > 1) prefetch(1, buf1);
-    if (nsteps > 1) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    auto one_step = [&](int step, uint8_t* cur, uint8_t* ahead) {   // ahead: the buffer read in step - 1
-        if (step + 2 < nsteps) prefetch(step + 2, ahead);
-        multiply(cur);
-        if (step + 2 < nsteps) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+    if constexpr (NBUF == 2) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        for (int step = 0; step < nsteps; step += 2) {
+            if (step + 1 < nsteps) prefetch(step + 1, buf1);
+            multiply(buf0);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            if (step + 1 < nsteps) {
+                if (step + 2 < nsteps) prefetch(step + 2, buf0);
+                multiply(buf1);
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                __syncthreads();
+            }
+        }
+    } else {
+        if (nsteps > 1) prefetch(1, buf1);
+        if (nsteps > 1) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
         else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-    };
-    for (int step = 0; step < nsteps; step += 3) {
-        one_step(step, buf0, buf2);
-        if (step + 1 < nsteps) one_step(step + 1, buf1, buf0);
-        if (step + 2 < nsteps) one_step(step + 2, buf2, buf1);
+        auto one_step = [&](int step, uint8_t* cur, uint8_t* ahead) {   // ahead: the buffer read in step - 1
+            if (step + 2 < nsteps) prefetch(step + 2, ahead);
+            multiply(cur);
+            if (step + 2 < nsteps) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+        };
+        for (int step = 0; step < nsteps; step += 3) {
+            one_step(step, buf0, buf2);
+            if (step + 1 < nsteps) one_step(step + 1, buf1, buf0);
+            if (step + 2 < nsteps) one_step(step + 2, buf2, buf1);
+        }
     }
+    // epilogue parameters into the freed operand memory (the other workgroups of the unit hide this round trip)
+    par_a[tid] = prm.aparams[min(m0 + tid, prm.M - 1)];
+    if (tid < kF4TileN) par_w[tid] = prm.wparams[min(n0 + tid, prm.N - 1)];
+    __syncthreads();
 
     // ---- epilogue: lane (G, r) of accumulator (i, j) holds rows 64 wave + 16 i + 4 G + reg, channel 16 j + r.
     // With 128 outputs per lane the epilogue is a third of the kernel if every output is stored on its own (2 bytes per
     // lane and instruction), so the usual case (no accumulator output, rows of Y a whole number of 16-byte vectors) goes
-    // through LDS: every wave stages its 64 x 128 binary16 results in its own part of the operand buffers (free after
-    // the loop's last barrier; row stride 272 bytes keeps the four row groups of a write on different banks) and writes
-    // them out as 128-bit vectors.  The arithmetic is the fused dequant of the other kernels (Fig. 3b), with the terms
+    // through LDS: every wave stages its binary16 results, 32 rows x 128 at a time, in its own part of the operand buffers
+    // (free after the loop's last barrier; row stride 272 bytes keeps the four row groups of a write on different banks)
+    // and writes them out as 128-bit vectors.  The arithmetic is the fused dequant of the other kernels (Fig. 3b), with the terms
     // that depend on the column only taken out of the inner loop: centered = S - wz asum - az (wsum - K wz).
     const int r = lane & 15, G = lane >> 4;
     if (prm.acc == nullptr && (prm.N & 7) == 0) {
         constexpr int kRowBytes = 272;
-        uint8_t* const stage = lds_f4 + wave * (64 * kRowBytes);
+        uint8_t* const stage = lds_f4 + wave * (32 * kRowBytes);   // 32 rows of this wave at a time
         uint32_t wz[8], cw[8];
         float sw[8];
 #pragma unroll
@@ -220,28 +273,33 @@ __global__ __launch_bounds__(256, 2) void f4_gemm_kernel(F4Params prm)
             sw[j] = pw.scale;
         }
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int half = 0; half < 2; ++half) {
 #pragma unroll
-            for (int reg = 0; reg < 4; ++reg) {
-                const int rl = 16 * i + 4 * G + reg;            // row inside the wave's 64
-                const RowParams pa = par_a[64 * wave + rl];
+            for (int i2 = 0; i2 < 2; ++i2)
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const uint32_t S = (uint32_t)(int32_t)acc[i][j][reg];
-                    const int32_t centered = (int32_t)(S - wz[j] * (uint32_t)pa.sum - (uint32_t)pa.zero * cw[j]);
-                    const float v = ((float)centered * pa.scale) * sw[j];
-                    uint32_t h;
-                    asm("v_cvt_f16_f32 %0, %1" : "=v"(h) : "v"(v));   // (the instruction itself: see epilogue_value)
-                    *reinterpret_cast<uint16_t*>(stage + rl * kRowBytes + (16 * j + r) * 2) = (uint16_t)h;
+                for (int reg = 0; reg < 4; ++reg) {
+                    const int i = 2 * half + i2;
+                    const int rl = 16 * i2 + 4 * G + reg;            // row inside this half of the wave's 64
+                    const RowParams pa = par_a[64 * wave + 32 * half + rl];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        const uint32_t S = (uint32_t)(int32_t)acc[i][j][reg];
+                        const int32_t centered = (int32_t)(S - wz[j] * (uint32_t)pa.sum - (uint32_t)pa.zero * cw[j]);
+                        const float v = ((float)centered * pa.scale) * sw[j];
+                        uint32_t h;
+                        asm("v_cvt_f16_f32 %0, %1" : "=v"(h) : "v"(v));   // (the instruction itself: see epilogue_value)
+                        *reinterpret_cast<uint16_t*>(stage + rl * kRowBytes + (16 * j + r) * 2) = (uint16_t)h;
+                    }
                 }
-            }
-        // (the wave reads back what its own lanes wrote: no barrier, the LDS counter orders it)
+            // (the wave reads back what its own lanes wrote, and rewrites the area only after it has read it: no barrier,
+            // the LDS counter orders it)
 #pragma unroll
-        for (int it = 0; it < 16; ++it) {
-            const int c = it * 64 + lane, rl = c >> 4, cc = c & 15;
-            const v4i_f4 x = *reinterpret_cast<const v4i_f4*>(stage + rl * kRowBytes + cc * 16);
-            const int m = m0 + 64 * wave + rl, n = n0 + 8 * cc;
-            if (m < prm.M && n < prm.N) *reinterpret_cast<v4i_f4*>(prm.y + (size_t)m * prm.N + n) = x;
+            for (int it = 0; it < 8; ++it) {
+                const int c = it * 64 + lane, rl = c >> 4, cc = c & 15;
+                const v4i_f4 x = *reinterpret_cast<const v4i_f4*>(stage + rl * kRowBytes + cc * 16);
+                const int m = m0 + 64 * wave + 32 * half + rl, n = n0 + 8 * cc;
+                if (m < prm.M && n < prm.N) *reinterpret_cast<v4i_f4*>(prm.y + (size_t)m * prm.N + n) = x;
+            }
         }
         return;
     }
@@ -271,13 +329,23 @@ hipError_t launch_f4_gemm(int M, int N, int K, const uint8_t* act_blob, const ui
     prm.a_tiles = f4_row_tiles(M); prm.w_tiles = f4_row_tiles(N);
     prm.tiles_m = (M + kF4TileM - 1) / kF4TileM;
     prm.tiles_n = (N + kF4TileN - 1) / kF4TileN;
-    static std::atomic<bool> attr_set{false};   // (an idempotent call: a lost race only repeats it)
-    if (!attr_set.load(std::memory_order_acquire)) {
-        const hipError_t e = hipFuncSetAttribute((const void*)f4_gemm_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kF4LdsBytes);
-        if (e != hipSuccess) return e;
-        attr_set.store(true, std::memory_order_release);
+    // Two or three workgroups per compute unit: three hide more latency, but the grid runs in rounds of (units x resident
+    // workgroups) and a nearly empty last round costs a whole one, so the count that wastes fewer workgroup slots is
+    // taken (M = 8192, 4096 x 4096: 1024 workgroups are two full rounds of 512 but 1.33 rounds of 768: 73 vs 85 us); with
+    // two, the LDS left over holds a third operand buffer.
+    const long nwg = (long)prm.tiles_m * prm.tiles_n, cus = num_cus();
+    const long slots3 = (nwg + 3 * cus - 1) / (3 * cus) * 3, slots2 = (nwg + 2 * cus - 1) / (2 * cus) * 2;
+    if (nwg > 2 * cus && slots2 < slots3) {   // (a grid that leaves units idle anyway: the two-buffer kernel, less to set up)
+        static std::atomic<bool> attr_set{false};   // (an idempotent call: a lost race only repeats it)
+        if (!attr_set.load(std::memory_order_acquire)) {
+            const hipError_t e = hipFuncSetAttribute((const void*)f4_gemm_kernel<3>, hipFuncAttributeMaxDynamicSharedMemorySize, 3 * kF4StepBytes);
+            if (e != hipSuccess) return e;
+            attr_set.store(true, std::memory_order_release);
+        }
+        f4_gemm_kernel<3><<<(unsigned)nwg, 256, 3 * kF4StepBytes, s>>>(prm);
+    } else {
+        f4_gemm_kernel<2><<<(unsigned)nwg, 256, 2 * kF4StepBytes, s>>>(prm);
     }
-    f4_gemm_kernel<<<(unsigned)(prm.tiles_m * prm.tiles_n), 256, kF4LdsBytes, s>>>(prm);
     return hipGetLastError();
 }
 
