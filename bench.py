@@ -46,6 +46,7 @@ PROFILE_OF = {
     "C5 W4A4 M=2048 K=5120 N=13824": "tiled_kernel_w4a4_gemm_m2048_k5120_n13824.md",
     "C5 W2A8 M=2048 K=5120 N=13824": "tiled_kernel_w2a8_gemm_m2048_k5120_n13824.md",
     "C5 W4A4 M=2048 K=5120 N=13824 g128": "tiled_g128_kernel_w4a4_gemm_m2048_k5120_n13824.md",
+    "C5 W2A2 M=2048 K=5120 N=13824 f4": "f4_gemm_kernel_w2a2_gemm_m2048_k5120_n13824.md",
     ("block", 4, 8, 1): "direct_kernel_grouped_w4a8_m1_llama7b_block.md",
     ("block", 8, 8, 1): "grouped_kernel_w8a8_m1_llama7b_block.md",
     ("block", 2, 8, 1): "direct_kernel_grouped_w2a8_m1_llama7b_block.md",
