@@ -370,7 +370,11 @@ def sweep(args):
                 for q in ints(args.sweep_q):
                     c = synth.config5(p, q, shape_idx, m_idx)
                     M, N, K = c.M, c.N, c.K
-                    blob0 = abq.abq_pack_weights(p, dev(c.W), dev(c.w_scale), dev(c.w_zero), layout)
+                    f4 = args.family == "f4"
+                    if f4 and (p > 2 or q > 2):
+                        continue
+                    blob0 = abq.abq_f4_pack_codes(p, dev(c.W), dev(c.w_scale), dev(c.w_zero)) if f4 else \
+                        abq.abq_pack_weights(p, dev(c.W), dev(c.w_scale), dev(c.w_zero), layout)
                     nb = blob0.numel()
                     stride = (nb + 255) // 256 * 256
                     R = max(2, -(-int(args.rotate_gib * 2 ** 30) // nb))
@@ -379,13 +383,15 @@ def sweep(args):
                     for b in blobs:
                         b.copy_(blob0)
                     a, sc, zp = dev(c.A), dev(c.a_scale), dev(c.a_zero)
-                    pa = abq.abq_pack_act_codes(q, a, sc, zp, layout)
+                    pa = abq.abq_f4_pack_codes(q, a, sc, zp) if f4 else abq.abq_pack_act_codes(q, a, sc, zp, layout)
                     y = torch.empty((M, N), dtype=torch.float16, device="cuda")
                     acc = torch.empty((M, N), dtype=torch.int32, device="cuda")
-                    fused = args.family != "bitserial" and abq.abq_gemm_act_codes_workspace_bytes(p, q, M, N, K, layout) == 0
+                    fused = args.family not in ("bitserial", "f4") and abq.abq_gemm_act_codes_workspace_bytes(p, q, M, N, K, layout) == 0
 
                     def call(i, acc_out=None):
-                        if fused:
+                        if f4:
+                            abq.abq_f4_gemm(p, q, M, N, K, pa, blobs[i % R], y=y, acc=acc_out)
+                        elif fused:
                             abq.abq_gemm_act_codes(p, q, M, N, K, a, sc, zp, blobs[i % R], layout, y=y, acc=acc_out)
                         else:
                             abq.abq_gemm(p, q, M, N, K, pa, layout, blobs[i % R], layout, y=y, acc=acc_out)
@@ -419,7 +425,9 @@ def sweep(args):
                         torch.cuda.synchronize()
                     t = e0.elapsed_time(e1) * 1e-3 / launches
                     tops = metrics.effective_tops(M, N, K, t)
-                    if M <= 39 * p:
+                    if f4:
+                        bound, frac = "mfma (fp4)", tops / F4_MFMA_PEAK_TOPS
+                    elif M <= 39 * p:
                         bound, frac = "hbm", metrics.gemm_algorithmic_bytes(p, q, M, N, K) / t / 1e9 / HBM_PEAK_GBS
                     else:
                         bound, frac = "mfma", tops / INT8_MFMA_PEAK_TOPS

@@ -13,7 +13,8 @@
 // L % 16, k = 128 block + 32 (L / 16) .. + 31 as 32 nibbles, which is the MFMA operand of that block as it stands.
 // Rows past the end and k past K hold code 0.
 //
-// Kernel: workgroup tile 256 rows of A x 128 channels of W, four waves of 64 x 128 each (32 accumulator tiles), K in
+// Kernel: workgroup tile 256 rows of A x 128 channels of W, four waves of 64 x 128 each (32 accumulator tiles; 64 x 128
+// with waves of 16 x 128 for problems of few tiles), K in
 // steps of 128: the step's 16 + 8 operand blocks go global -> LDS with direct 128-bit loads (a block is one wave
 // instruction and lands in LDS as the operand layout: conflict-free 128-bit reads), one barrier per step; three workgroups
 // share a compute unit with two operand buffers each, or two with three buffers each (launch_f4_gemm says when), and
@@ -30,8 +31,7 @@ typedef int v8i_f4 __attribute__((ext_vector_type(8)));
 typedef float v4f_f4 __attribute__((ext_vector_type(4)));
 
 constexpr int kF4BlockK = 128;                 // k per operand block
-constexpr int kF4TileM = 256, kF4TileN = 128;  // workgroup tile
-constexpr int kF4StepBytes = (kF4TileM + kF4TileN) / 16 * 1024;   // operand blocks of one 128-k step
+constexpr int kF4TileN = 128;                  // channels of W per workgroup tile (the rows of A: F4Shape)
 
 static inline int f4_row_tiles(int rows) { return (rows + 15) / 16; }
 static inline int f4_k_blocks(int K) { return (K + kF4BlockK - 1) / kF4BlockK; }
@@ -145,19 +145,33 @@ struct F4Params {
     int tiles_m, tiles_n;      // workgroup tiles
 };
 
-// NBUF = 2: operands requested one step ahead, 48 KiB of LDS, three workgroups per compute unit; NBUF = 3: two steps ahead,
-// 72 KiB, two workgroups per unit.
-template <int NBUF>
-__global__ __launch_bounds__(256, NBUF == 2 ? 3 : 2) void f4_gemm_kernel(F4Params prm)
+// RT: 16-row tiles of A per wave (4: workgroup tile 256 x 128, the shape for large M; 1: 64 x 128, for problems that would
+// otherwise leave compute units idle).  NBUF: operand buffers (2: requested one step ahead; 3: two steps ahead).
+template <int RT> struct F4Shape {
+    static constexpr int kTileM = 64 * RT;
+    static constexpr int kABlocks = 4 * RT, kBlocks = kABlocks + 8;     // operand blocks of a step (A rows, then W channels)
+    static constexpr int kStepBytes = kBlocks * 1024;
+    static constexpr int kLoads = kBlocks / 4;                          // blocks a wave requests per step
+    static constexpr int kPassRows = RT >= 2 ? 32 : 16;                 // rows a wave stages per pass of the epilogue
+    static constexpr int kStageBytes = 4 * kPassRows * 272;
+    static constexpr int kParamOffset = (kStageBytes + 1023) / 1024 * 1024;
+    static constexpr int kEpilogueBytes = kParamOffset + (kTileM + kF4TileN) * (int)sizeof(RowParams);
+    static constexpr int lds_bytes(int nbuf) { return nbuf * kStepBytes > kEpilogueBytes ? nbuf * kStepBytes : kEpilogueBytes; }
+    static constexpr int wgs_per_cu(int nbuf) { return RT == 4 ? (nbuf == 2 ? 3 : 2) : 4; }
+};
+
+template <int NBUF, int RT>
+__global__ __launch_bounds__(256, F4Shape<RT>::wgs_per_cu(NBUF)) void f4_gemm_kernel(F4Params prm)
 {
-    // NBUF buffers of a step's operands: 16 blocks of A (256 rows) then 8 blocks of W (128 channels), 1 KiB each.  After
-    // the K loop the same memory holds the epilogue's staging area (first 34 KiB) and parameters (from 36 KiB).
+    using SH = F4Shape<RT>;
+    // NBUF buffers of a step's operands, 1 KiB per block.  After the K loop the same memory holds the epilogue's staging
+    // area and, behind it, the parameters.
     extern __shared__ __align__(16) uint8_t lds_f4[];
     uint8_t* const buf0 = lds_f4;
-    uint8_t* const buf1 = lds_f4 + kF4StepBytes;
-    uint8_t* const buf2 = lds_f4 + (NBUF - 1) * kF4StepBytes;   // (NBUF = 2: unused)
-    RowParams* const par_a = reinterpret_cast<RowParams*>(lds_f4 + 36 * 1024);
-    RowParams* const par_w = par_a + kF4TileM;
+    uint8_t* const buf1 = lds_f4 + SH::kStepBytes;
+    uint8_t* const buf2 = lds_f4 + (NBUF - 1) * SH::kStepBytes;   // (NBUF = 2: unused)
+    RowParams* const par_a = reinterpret_cast<RowParams*>(lds_f4 + SH::kParamOffset);
+    RowParams* const par_w = par_a + SH::kTileM;
     const int tid = (int)threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     // Workgroup b runs on XCD b % 8 and each XCD has its own L2: give every XCD a contiguous run of the tile order, row
@@ -167,51 +181,57 @@ __global__ __launch_bounds__(256, NBUF == 2 ? 3 : 2) void f4_gemm_kernel(F4Param
     const int per = nwg >> 3, rem = nwg & 7;
     const int vid = xcd * per + min(xcd, rem) + slot;
     const int m_blk = vid % prm.tiles_m, n_blk = vid / prm.tiles_m;
-    const int m0 = m_blk * kF4TileM, n0 = n_blk * kF4TileN;
+    const int m0 = m_blk * SH::kTileM, n0 = n_blk * kF4TileN;
 
-    // this wave's six blocks of a step: blocks 6 wave .. 6 wave + 5 of the 24 (0..15: A row tiles, 16..23: W tiles); tiles
+    // this wave's blocks of a step: kLoads consecutive ones of the kBlocks (first the A row tiles, then the W tiles); tiles
     // past the operand's end re-read its last tile (their outputs are never stored)
-    const v4i_f4* src[6];
+    const v4i_f4* src[SH::kLoads];
 #pragma unroll
-    for (int u = 0; u < 6; ++u) {
-        const int blk = wave * 6 + u;   // wave-uniform
-        if (blk < 16) src[u] = prm.a_blocks + ((size_t)min(m0 / 16 + blk, prm.a_tiles - 1) * prm.kblocks) * 64 + lane;
-        else src[u] = prm.w_blocks + ((size_t)min(n0 / 16 + (blk - 16), prm.w_tiles - 1) * prm.kblocks) * 64 + lane;
+    for (int u = 0; u < SH::kLoads; ++u) {
+        const int blk = wave * SH::kLoads + u;   // wave-uniform
+        if (blk < SH::kABlocks) src[u] = prm.a_blocks + ((size_t)min(m0 / 16 + blk, prm.a_tiles - 1) * prm.kblocks) * 64 + lane;
+        else src[u] = prm.w_blocks + ((size_t)min(n0 / 16 + (blk - SH::kABlocks), prm.w_tiles - 1) * prm.kblocks) * 64 + lane;
     }
     auto prefetch = [&](int step, uint8_t* buf) {
 #pragma unroll
-        for (int u = 0; u < 6; ++u)
+        for (int u = 0; u < SH::kLoads; ++u)
             __builtin_amdgcn_global_load_lds((const void*)(src[u] + (size_t)step * 64),
-                                             (__attribute__((address_space(3))) void*)(buf + (wave * 6 + u) * 1024), 16, 0, 0);
+                                             (__attribute__((address_space(3))) void*)(buf + (wave * SH::kLoads + u) * 1024), 16, 0, 0);
     };
 
-    v4f_f4 acc[4][8];
+    v4f_f4 acc[RT][8];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < RT; ++i)
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[i][j] = v4f_f4{0.f, 0.f, 0.f, 0.f};
 
     const int one = 0x7F7F7F7F;   // block scales of 2^0
     auto multiply = [&](const uint8_t* buf) {
-        // wave w: rows 64 w .. 64 w + 63 of the workgroup tile (A blocks 4 w .. 4 w + 3), all eight W blocks
-        v8i_f4 a[4];
+        // wave w: rows 16 RT w .. + 16 RT - 1 of the workgroup tile (A blocks RT w ..), all eight W blocks
+        v8i_f4 a[RT];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const v4i_f4 x = *reinterpret_cast<const v4i_f4*>(buf + (wave * 4 + i) * 1024 + lane * 16);
+        for (int i = 0; i < RT; ++i) {
+            const v4i_f4 x = *reinterpret_cast<const v4i_f4*>(buf + (wave * RT + i) * 1024 + lane * 16);
             a[i] = v8i_f4{x.x, x.y, x.z, x.w, 0, 0, 0, 0};
         }
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            const v4i_f4 x = *reinterpret_cast<const v4i_f4*>(buf + (16 + j) * 1024 + lane * 16);
+            const v4i_f4 x = *reinterpret_cast<const v4i_f4*>(buf + (SH::kABlocks + j) * 1024 + lane * 16);
             const v8i_f4 b = v8i_f4{x.x, x.y, x.z, x.w, 0, 0, 0, 0};
 #pragma unroll
-            for (int i = 0; i < 4; ++i) acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a[i], b, acc[i][j], 4, 4, 0, one, 0, one);
+            for (int i = 0; i < RT; ++i) acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a[i], b, acc[i][j], 4, 4, 0, one, 0, one);
         }
     };
+    // wait until all but the youngest step's loads of this wave have landed
+    auto wait_all_but_one_step = [&]() {
+        if constexpr (SH::kLoads == 6) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
+    };
+    static_assert(SH::kLoads == 6 || SH::kLoads == 3, "the wait counts above");
 
     // Operands are requested NBUF - 1 steps ahead.  The direct loads of a buffer have to have landed before the barrier
     // behind which the other waves read it (the barrier's own fence covers LDS instructions, not these loads), so the wait
-    // is written out: with three buffers all but the youngest step's six loads, which stay in flight across the barrier.
+    // is written out: with three buffers all but the youngest step's loads, which stay in flight across the barrier.
     const int nsteps = prm.kblocks;
     prefetch(0, buf0);
     if constexpr (NBUF == 2) {
@@ -231,13 +251,13 @@ __global__ __launch_bounds__(256, NBUF == 2 ? 3 : 2) void f4_gemm_kernel(F4Param
         }
     } else {
         if (nsteps > 1) prefetch(1, buf1);
-        if (nsteps > 1) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+        if (nsteps > 1) wait_all_but_one_step();
         else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         auto one_step = [&](int step, uint8_t* cur, uint8_t* ahead) {   // ahead: the buffer read in step - 1
             if (step + 2 < nsteps) prefetch(step + 2, ahead);
             multiply(cur);
-            if (step + 2 < nsteps) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+            if (step + 2 < nsteps) wait_all_but_one_step();
             else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
         };
@@ -248,21 +268,23 @@ __global__ __launch_bounds__(256, NBUF == 2 ? 3 : 2) void f4_gemm_kernel(F4Param
         }
     }
     // epilogue parameters into the freed operand memory (the other workgroups of the unit hide this round trip)
-    par_a[tid] = prm.aparams[min(m0 + tid, prm.M - 1)];
+    if (tid < SH::kTileM) par_a[tid] = prm.aparams[min(m0 + tid, prm.M - 1)];
     if (tid < kF4TileN) par_w[tid] = prm.wparams[min(n0 + tid, prm.N - 1)];
     __syncthreads();
 
-    // ---- epilogue: lane (G, r) of accumulator (i, j) holds rows 64 wave + 16 i + 4 G + reg, channel 16 j + r.
-    // With 128 outputs per lane the epilogue is a third of the kernel if every output is stored on its own (2 bytes per
-    // lane and instruction), so the usual case (no accumulator output, rows of Y a whole number of 16-byte vectors) goes
-    // through LDS: every wave stages its binary16 results, 32 rows x 128 at a time, in its own part of the operand buffers
-    // (free after the loop's last barrier; row stride 272 bytes keeps the four row groups of a write on different banks)
-    // and writes them out as 128-bit vectors.  The arithmetic is the fused dequant of the other kernels (Fig. 3b), with the terms
-    // that depend on the column only taken out of the inner loop: centered = S - wz asum - az (wsum - K wz).
+    // ---- epilogue: lane (G, r) of accumulator (i, j) holds rows 16 RT wave + 16 i + 4 G + reg, channel 16 j + r.
+    // With up to 128 outputs per lane the epilogue is a third of the kernel if every output is stored on its own (2 bytes
+    // per lane and instruction), so the usual case (no accumulator output, rows of Y a whole number of 16-byte vectors)
+    // goes through LDS: every wave stages its binary16 results, up to 32 rows x 128 at a time, in its own part of the
+    // operand buffers (free after the loop's last barrier; row stride 272 bytes keeps the four row groups of a write on
+    // different banks) and writes them out as 128-bit vectors.  The arithmetic is the fused dequant of the other kernels
+    // (Fig. 3b), with the terms that depend on the column only taken out of the inner loop:
+    // centered = S - wz asum - az (wsum - K wz).
     const int r = lane & 15, G = lane >> 4;
+    constexpr int kWaveRows = 16 * RT;
     if (prm.acc == nullptr && (prm.N & 7) == 0) {
-        constexpr int kRowBytes = 272;
-        uint8_t* const stage = lds_f4 + wave * (32 * kRowBytes);   // 32 rows of this wave at a time
+        constexpr int kRowBytes = 272, kPassRows = SH::kPassRows, kPassTiles = kPassRows / 16;
+        uint8_t* const stage = lds_f4 + wave * (kPassRows * kRowBytes);
         uint32_t wz[8], cw[8];
         float sw[8];
 #pragma unroll
@@ -273,14 +295,14 @@ __global__ __launch_bounds__(256, NBUF == 2 ? 3 : 2) void f4_gemm_kernel(F4Param
             sw[j] = pw.scale;
         }
 #pragma unroll
-        for (int half = 0; half < 2; ++half) {
+        for (int pass = 0; pass < kWaveRows / kPassRows; ++pass) {
 #pragma unroll
-            for (int i2 = 0; i2 < 2; ++i2)
+            for (int i2 = 0; i2 < kPassTiles; ++i2)
 #pragma unroll
                 for (int reg = 0; reg < 4; ++reg) {
-                    const int i = 2 * half + i2;
-                    const int rl = 16 * i2 + 4 * G + reg;            // row inside this half of the wave's 64
-                    const RowParams pa = par_a[64 * wave + 32 * half + rl];
+                    const int i = kPassTiles * pass + i2;
+                    const int rl = 16 * i2 + 4 * G + reg;            // row inside this pass
+                    const RowParams pa = par_a[kWaveRows * wave + kPassRows * pass + rl];
 #pragma unroll
                     for (int j = 0; j < 8; ++j) {
                         const uint32_t S = (uint32_t)(int32_t)acc[i][j][reg];
@@ -294,27 +316,43 @@ __global__ __launch_bounds__(256, NBUF == 2 ? 3 : 2) void f4_gemm_kernel(F4Param
             // (the wave reads back what its own lanes wrote, and rewrites the area only after it has read it: no barrier,
             // the LDS counter orders it)
 #pragma unroll
-            for (int it = 0; it < 8; ++it) {
+            for (int it = 0; it < kPassRows / 4; ++it) {
                 const int c = it * 64 + lane, rl = c >> 4, cc = c & 15;
                 const v4i_f4 x = *reinterpret_cast<const v4i_f4*>(stage + rl * kRowBytes + cc * 16);
-                const int m = m0 + 64 * wave + 32 * half + rl, n = n0 + 8 * cc;
+                const int m = m0 + kWaveRows * wave + kPassRows * pass + rl, n = n0 + 8 * cc;
                 if (m < prm.M && n < prm.N) *reinterpret_cast<v4i_f4*>(prm.y + (size_t)m * prm.N + n) = x;
             }
         }
         return;
     }
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < RT; ++i)
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const int nl = 16 * j + r, n = n0 + nl;
 #pragma unroll
             for (int reg = 0; reg < 4; ++reg) {
-                const int ml = 64 * wave + 16 * i + 4 * G + reg, m = m0 + ml;
+                const int ml = kWaveRows * wave + 16 * i + 4 * G + reg, m = m0 + ml;
                 if (m < prm.M && n < prm.N)
                     epilogue_store((int32_t)acc[i][j][reg], 0, 0, prm.K, par_a[ml], par_w[nl], (size_t)m * prm.N + n, prm.y, prm.acc);
             }
         }
+}
+
+template <int NBUF, int RT>
+static hipError_t f4_launch(const F4Params& prm, unsigned grid, hipStream_t s)
+{
+    constexpr int lds = F4Shape<RT>::lds_bytes(NBUF);
+    if constexpr (lds > 64 * 1024) {
+        static std::atomic<bool> attr_set{false};   // (an idempotent call: a lost race only repeats it)
+        if (!attr_set.load(std::memory_order_acquire)) {
+            const hipError_t e = hipFuncSetAttribute((const void*)f4_gemm_kernel<NBUF, RT>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+            if (e != hipSuccess) return e;
+            attr_set.store(true, std::memory_order_release);
+        }
+    }
+    f4_gemm_kernel<NBUF, RT><<<grid, 256, lds, s>>>(prm);
+    return hipGetLastError();
 }
 
 hipError_t launch_f4_gemm(int M, int N, int K, const uint8_t* act_blob, const uint8_t* w_blob, uint16_t* y, int32_t* acc, hipStream_t s)
@@ -327,26 +365,24 @@ hipError_t launch_f4_gemm(int M, int N, int K, const uint8_t* act_blob, const ui
     prm.y = y; prm.acc = acc;
     prm.M = M; prm.N = N; prm.K = K; prm.kblocks = f4_k_blocks(K);
     prm.a_tiles = f4_row_tiles(M); prm.w_tiles = f4_row_tiles(N);
-    prm.tiles_m = (M + kF4TileM - 1) / kF4TileM;
     prm.tiles_n = (N + kF4TileN - 1) / kF4TileN;
+    const long cus = num_cus();
+    // Workgroup tile: 256 rows where that still gives every compute unit a workgroup, else 64 rows (four times the
+    // workgroups; more LDS reads per MFMA, but the chip is busy).
+    const long nwg_big = (long)((M + 255) / 256) * prm.tiles_n;
+    if (nwg_big < cus) {
+        prm.tiles_m = (M + 63) / 64;
+        return f4_launch<3, 1>(prm, (unsigned)(prm.tiles_m * prm.tiles_n), s);
+    }
+    prm.tiles_m = (M + 255) / 256;
     // Two or three workgroups per compute unit: three hide more latency, but the grid runs in rounds of (units x resident
     // workgroups) and a nearly empty last round costs a whole one, so the count that wastes fewer workgroup slots is
     // taken (M = 8192, 4096 x 4096: 1024 workgroups are two full rounds of 512 but 1.33 rounds of 768: 73 vs 85 us); with
     // two, the LDS left over holds a third operand buffer.
-    const long nwg = (long)prm.tiles_m * prm.tiles_n, cus = num_cus();
+    const long nwg = nwg_big;
     const long slots3 = (nwg + 3 * cus - 1) / (3 * cus) * 3, slots2 = (nwg + 2 * cus - 1) / (2 * cus) * 2;
-    if (nwg > 2 * cus && slots2 < slots3) {   // (a grid that leaves units idle anyway: the two-buffer kernel, less to set up)
-        static std::atomic<bool> attr_set{false};   // (an idempotent call: a lost race only repeats it)
-        if (!attr_set.load(std::memory_order_acquire)) {
-            const hipError_t e = hipFuncSetAttribute((const void*)f4_gemm_kernel<3>, hipFuncAttributeMaxDynamicSharedMemorySize, 3 * kF4StepBytes);
-            if (e != hipSuccess) return e;
-            attr_set.store(true, std::memory_order_release);
-        }
-        f4_gemm_kernel<3><<<(unsigned)nwg, 256, 3 * kF4StepBytes, s>>>(prm);
-    } else {
-        f4_gemm_kernel<2><<<(unsigned)nwg, 256, 2 * kF4StepBytes, s>>>(prm);
-    }
-    return hipGetLastError();
+    if (nwg > 2 * cus && slots2 < slots3) return f4_launch<3, 4>(prm, (unsigned)nwg, s);
+    return f4_launch<2, 4>(prm, (unsigned)nwg, s);
 }
 
 }  // namespace abq

@@ -82,6 +82,14 @@ def test_f4_drops_bits_above_the_width(abq):
     check_against_oracle(c, y.cpu().numpy(), acc.cpu().numpy())
 
 
+def test_f4_large_tile_two_buffers_sampled(abq):
+    """256 workgroups of the 256-row tile (the two-buffer variant, three workgroups per unit), ragged K: sampled outputs."""
+    c = synth.make_case(2, 2, 1024, 8192, 1000, seed=synth.case_seed(11, 2, 2, 55, 66), name="f4 W2A2 1024x8192x1000")
+    say(c.name)
+    y, acc = run_f4(abq, c)
+    check_sampled(c, y, acc)
+
+
 @pytest.mark.parametrize("p,q", [(2, 2), (1, 1)])
 def test_f4_config5_prefill_shape_sampled(abq, p, q):
     """M = 2048 on the LLaMA-13B up-projection, the launch the bench times: sampled outputs against the oracle."""
