@@ -30,8 +30,30 @@ def _compile(src: str, newest_header: float = 0.0) -> str:
     obj = os.path.join(OBJ, os.path.relpath(src, CSRC).replace(os.sep, "_") + ".o")
     if newest_header and os.path.exists(obj) and os.path.getmtime(obj) >= max(newest_header, os.path.getmtime(src)):
         return obj   # --incremental: neither the source nor any header is newer than the object
-    subprocess.run([HIPCC, *FLAGS, "-c", src, "-o", obj], check=True, stderr=subprocess.PIPE, text=True)
+    extra = ["-Rpass-analysis=kernel-resource-usage"] if os.path.basename(src) in NO_SCRATCH else []
+    done = subprocess.run([HIPCC, *FLAGS, *extra, "-c", src, "-o", obj], check=True, stderr=subprocess.PIPE, text=True)
+    if extra:
+        _check_no_scratch(src, done.stderr, NO_SCRATCH[os.path.basename(src)])
     return obj
+
+
+# Kernels that load registers with hand-written load instructions and wait for them by hand: the compiler does not know
+# that such a register fills later, so it must not spill it in between.  The build fails if one of them uses scratch memory.
+NO_SCRATCH = {"abq_f4.hip": "f4_gemm_kernel"}
+
+
+def _check_no_scratch(src: str, remarks: str, kernel: str) -> None:
+    name, seen = None, 0
+    for line in remarks.splitlines():
+        if "Function Name:" in line:
+            name = line.split("Function Name:")[1].strip()
+        elif "ScratchSize [bytes/lane]:" in line and name and kernel in name:
+            seen += 1
+            if int(line.split(":")[-1].split()[0]) != 0:
+                os.remove(os.path.join(OBJ, os.path.relpath(src, CSRC).replace(os.sep, "_") + ".o"))
+                raise RuntimeError(f"{src}: kernel {name} uses scratch memory; its hand-written loads would be spilled before they land")
+    if not seen:
+        raise RuntimeError(f"{src}: no resource-usage remark for {kernel}; the scratch check did not run")
 
 
 def build(verbose: bool = False, incremental: bool = False) -> str:

@@ -22,7 +22,6 @@
 #include "abq_internal.h"
 #include "../../include/abq.h"
 
-#include <atomic>
 
 namespace abq {
 
@@ -146,127 +145,26 @@ struct F4Params {
 };
 
 // RT: 16-row tiles of A per wave (4: workgroup tile 256 x 128, the shape for large M; 1: 64 x 128, for problems that would
-// otherwise leave compute units idle).  NBUF: operand buffers (2: requested one step ahead; 3: two steps ahead).
+// otherwise leave compute units idle).
 template <int RT> struct F4Shape {
     static constexpr int kTileM = 64 * RT;
-    static constexpr int kABlocks = 4 * RT, kBlocks = kABlocks + 8;     // operand blocks of a step (A rows, then W channels)
-    static constexpr int kStepBytes = kBlocks * 1024;
-    static constexpr int kLoads = kBlocks / 4;                          // blocks a wave requests per step
+    static constexpr int kWBufBytes = 8 * 1024;                         // the eight W blocks of a step
     static constexpr int kPassRows = RT >= 2 ? 32 : 16;                 // rows a wave stages per pass of the epilogue
     static constexpr int kStageBytes = 4 * kPassRows * 272;
     static constexpr int kParamOffset = (kStageBytes + 1023) / 1024 * 1024;
     static constexpr int kEpilogueBytes = kParamOffset + (kTileM + kF4TileN) * (int)sizeof(RowParams);
-    static constexpr int lds_bytes(int nbuf) { return nbuf * kStepBytes > kEpilogueBytes ? nbuf * kStepBytes : kEpilogueBytes; }
-    static constexpr int wgs_per_cu(int nbuf) { return RT == 4 ? (nbuf == 2 ? 3 : 2) : 4; }
+    static constexpr int kLdsBytes = 3 * kWBufBytes > kEpilogueBytes ? 3 * kWBufBytes : kEpilogueBytes;
 };
 
-template <int NBUF, int RT>
-__global__ __launch_bounds__(256, F4Shape<RT>::wgs_per_cu(NBUF)) void f4_gemm_kernel(F4Params prm)
+// The epilogue of the matmul kernel: parameters of the tile's rows and columns into LDS, then the dequantised
+// outputs, staged through LDS for 128-bit stores where the output allows it.  lds_f4 is free for reuse when it starts (the
+// caller has passed a barrier after its last read, and none of its loads into LDS is in flight).
+template <int RT>
+__device__ __forceinline__ void f4_epilogue(const F4Params& prm, v4f_f4 (*acc)[8], uint8_t* lds_f4, int tid, int lane, int wave, int m0, int n0)
 {
     using SH = F4Shape<RT>;
-    // NBUF buffers of a step's operands, 1 KiB per block.  After the K loop the same memory holds the epilogue's staging
-    // area and, behind it, the parameters.
-    extern __shared__ __align__(16) uint8_t lds_f4[];
-    uint8_t* const buf0 = lds_f4;
-    uint8_t* const buf1 = lds_f4 + SH::kStepBytes;
-    uint8_t* const buf2 = lds_f4 + (NBUF - 1) * SH::kStepBytes;   // (NBUF = 2: unused)
     RowParams* const par_a = reinterpret_cast<RowParams*>(lds_f4 + SH::kParamOffset);
     RowParams* const par_w = par_a + SH::kTileM;
-    const int tid = (int)threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    // Workgroup b runs on XCD b % 8 and each XCD has its own L2: give every XCD a contiguous run of the tile order, row
-    // blocks fastest, so that the workgroups resident on one XCD share their column blocks of W and a few row blocks of A.
-    const int nwg = prm.tiles_m * prm.tiles_n;
-    const int xcd = (int)blockIdx.x & 7, slot = (int)blockIdx.x >> 3;
-    const int per = nwg >> 3, rem = nwg & 7;
-    const int vid = xcd * per + min(xcd, rem) + slot;
-    const int m_blk = vid % prm.tiles_m, n_blk = vid / prm.tiles_m;
-    const int m0 = m_blk * SH::kTileM, n0 = n_blk * kF4TileN;
-
-    // this wave's blocks of a step: kLoads consecutive ones of the kBlocks (first the A row tiles, then the W tiles); tiles
-    // past the operand's end re-read its last tile (their outputs are never stored)
-    const v4i_f4* src[SH::kLoads];
-#pragma unroll
-    for (int u = 0; u < SH::kLoads; ++u) {
-        const int blk = wave * SH::kLoads + u;   // wave-uniform
-        if (blk < SH::kABlocks) src[u] = prm.a_blocks + ((size_t)min(m0 / 16 + blk, prm.a_tiles - 1) * prm.kblocks) * 64 + lane;
-        else src[u] = prm.w_blocks + ((size_t)min(n0 / 16 + (blk - SH::kABlocks), prm.w_tiles - 1) * prm.kblocks) * 64 + lane;
-    }
-    auto prefetch = [&](int step, uint8_t* buf) {
-#pragma unroll
-        for (int u = 0; u < SH::kLoads; ++u)
-            __builtin_amdgcn_global_load_lds((const void*)(src[u] + (size_t)step * 64),
-                                             (__attribute__((address_space(3))) void*)(buf + (wave * SH::kLoads + u) * 1024), 16, 0, 0);
-    };
-
-    v4f_f4 acc[RT][8];
-#pragma unroll
-    for (int i = 0; i < RT; ++i)
-#pragma unroll
-        for (int j = 0; j < 8; ++j) acc[i][j] = v4f_f4{0.f, 0.f, 0.f, 0.f};
-
-    const int one = 0x7F7F7F7F;   // block scales of 2^0
-    auto multiply = [&](const uint8_t* buf) {
-        // wave w: rows 16 RT w .. + 16 RT - 1 of the workgroup tile (A blocks RT w ..), all eight W blocks
-        v8i_f4 a[RT];
-#pragma unroll
-        for (int i = 0; i < RT; ++i) {
-            const v4i_f4 x = *reinterpret_cast<const v4i_f4*>(buf + (wave * RT + i) * 1024 + lane * 16);
-            a[i] = v8i_f4{x.x, x.y, x.z, x.w, 0, 0, 0, 0};
-        }
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const v4i_f4 x = *reinterpret_cast<const v4i_f4*>(buf + (SH::kABlocks + j) * 1024 + lane * 16);
-            const v8i_f4 b = v8i_f4{x.x, x.y, x.z, x.w, 0, 0, 0, 0};
-#pragma unroll
-            for (int i = 0; i < RT; ++i) acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a[i], b, acc[i][j], 4, 4, 0, one, 0, one);
-        }
-    };
-    // wait until all but the youngest step's loads of this wave have landed
-    auto wait_all_but_one_step = [&]() {
-        if constexpr (SH::kLoads == 6) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
-    };
-    static_assert(SH::kLoads == 6 || SH::kLoads == 3, "the wait counts above");
-
-    // Operands are requested NBUF - 1 steps ahead.  The direct loads of a buffer have to have landed before the barrier
-    // behind which the other waves read it (the barrier's own fence covers LDS instructions, not these loads), so the wait
-    // is written out: with three buffers all but the youngest step's loads, which stay in flight across the barrier.
-    const int nsteps = prm.kblocks;
-    prefetch(0, buf0);
-    if constexpr (NBUF == 2) {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        for (int step = 0; step < nsteps; step += 2) {
-            if (step + 1 < nsteps) prefetch(step + 1, buf1);
-            multiply(buf0);
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __syncthreads();
-            if (step + 1 < nsteps) {
-                if (step + 2 < nsteps) prefetch(step + 2, buf0);
-                multiply(buf1);
-                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-                __syncthreads();
-            }
-        }
-    } else {
-        if (nsteps > 1) prefetch(1, buf1);
-        if (nsteps > 1) wait_all_but_one_step();
-        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        auto one_step = [&](int step, uint8_t* cur, uint8_t* ahead) {   // ahead: the buffer read in step - 1
-            if (step + 2 < nsteps) prefetch(step + 2, ahead);
-            multiply(cur);
-            if (step + 2 < nsteps) wait_all_but_one_step();
-            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __syncthreads();
-        };
-        for (int step = 0; step < nsteps; step += 3) {
-            one_step(step, buf0, buf2);
-            if (step + 1 < nsteps) one_step(step + 1, buf1, buf0);
-            if (step + 2 < nsteps) one_step(step + 2, buf2, buf1);
-        }
-    }
     // epilogue parameters into the freed operand memory (the other workgroups of the unit hide this round trip)
     if (tid < SH::kTileM) par_a[tid] = prm.aparams[min(m0 + tid, prm.M - 1)];
     if (tid < kF4TileN) par_w[tid] = prm.wparams[min(n0 + tid, prm.N - 1)];
@@ -339,19 +237,138 @@ __global__ __launch_bounds__(256, F4Shape<RT>::wgs_per_cu(NBUF)) void f4_gemm_ke
         }
 }
 
-template <int NBUF, int RT>
+// Y = dequant(A W^T) on the 4-bit floating-point MFMA.  Four waves; wave w owns rows 16 RT w .. of the tile and all 128
+// columns.  Its A blocks go global -> registers (a wave's rows are its own: nothing to share), the eight W blocks of a step
+// go global -> LDS, where every wave reads them: per MFMA a wave reads 0.25 KiB of LDS.
+template <int RT>
+__global__ __launch_bounds__(256, RT == 4 ? 2 : 4) void f4_gemm_kernel(F4Params prm)
+{
+    using SH = F4Shape<RT>;
+    // Three buffers of a step's W blocks, 1 KiB per block.  After the K loop the same memory holds the epilogue's staging
+    // area and, behind it, the parameters.
+    extern __shared__ __align__(16) uint8_t lds_f4[];
+    uint8_t* const buf0 = lds_f4;
+    uint8_t* const buf1 = lds_f4 + SH::kWBufBytes;
+    uint8_t* const buf2 = lds_f4 + 2 * SH::kWBufBytes;
+    const int tid = (int)threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // Workgroup b runs on XCD b % 8 and each XCD has its own L2: give every XCD a contiguous run of the tile order, so
+    // that the workgroups resident on one XCD share their column blocks of W and their row blocks of A.
+    const int nwg = prm.tiles_m * prm.tiles_n;
+    const int xcd = (int)blockIdx.x & 7, slot = (int)blockIdx.x >> 3;
+    const int per = nwg >> 3, rem = nwg & 7;
+    const int vid = xcd * per + min(xcd, rem) + slot;
+    // Within the order, row tiles go in panels of eight: the workgroups resident on an XCD at one time then cover about as
+    // many row tiles as column tiles, which is the least operand traffic into its L2 for that many tiles.
+    const int panel_wgs = 8 * prm.tiles_n, panel = vid / panel_wgs, in_panel = vid - panel * panel_wgs;
+    const int panel_rows = min(8, prm.tiles_m - 8 * panel);
+    const int m_blk = 8 * panel + in_panel % panel_rows, n_blk = in_panel / panel_rows;
+    const int m0 = m_blk * SH::kTileM, n0 = n_blk * kF4TileN;
+
+    const v4i_f4* a_src[RT];
+#pragma unroll
+    for (int i = 0; i < RT; ++i) a_src[i] = prm.a_blocks + ((size_t)min(m0 / 16 + wave * RT + i, prm.a_tiles - 1) * prm.kblocks) * 64 + lane;
+    const v4i_f4* w_src[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) w_src[u] = prm.w_blocks + ((size_t)min(n0 / 16 + wave * 2 + u, prm.w_tiles - 1) * prm.kblocks) * 64 + lane;
+
+    v4f_f4 acc[RT][8];
+#pragma unroll
+    for (int i = 0; i < RT; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[i][j] = v4f_f4{0.f, 0.f, 0.f, 0.f};
+
+    const int one = 0x7F7F7F7F;   // block scales of 2^0
+    // One step of K: the W blocks are read from LDS two at a time, one pair ahead of the MFMAs that use them, so that a
+    // wave's LDS latency runs under its own MFMAs (the scheduling barriers keep the reads where they are written).
+    auto multiply = [&](const uint8_t* buf, const v4i_f4* ar) {
+        v8i_f4 a[RT];
+#pragma unroll
+        for (int i = 0; i < RT; ++i) a[i] = v8i_f4{ar[i].x, ar[i].y, ar[i].z, ar[i].w, 0, 0, 0, 0};
+        const uint8_t* const mine = buf + lane * 16;
+        v4i_f4 x[2][2];
+        x[0][0] = *reinterpret_cast<const v4i_f4*>(mine);
+        x[0][1] = *reinterpret_cast<const v4i_f4*>(mine + 1024);
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            if (g < 3) {
+                x[(g + 1) & 1][0] = *reinterpret_cast<const v4i_f4*>(mine + (2 * g + 2) * 1024);
+                x[(g + 1) & 1][1] = *reinterpret_cast<const v4i_f4*>(mine + (2 * g + 3) * 1024);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const v4i_f4 xb = x[g & 1][h];
+                const v8i_f4 b = v8i_f4{xb.x, xb.y, xb.z, xb.w, 0, 0, 0, 0};
+#pragma unroll
+                for (int i = 0; i < RT; ++i)
+                    acc[i][2 * g + h] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a[i], b, acc[i][2 * g + h], 4, 4, 0, one, 0, one);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    // Two steps ahead: three LDS buffers for W and three register sets for A, used in rotation.  A wave issues RT + 2
+    // vector-memory loads per step, in order, so "at most RT + 2 outstanding" means the step before the newest has landed.
+    // The body of the main loop has no branch: past the last step it loads that step again into a buffer and a register
+    // set that nothing reads any more.  The wait and the barrier are written out: a workgroup fence would wait for every
+    // outstanding load (the loads into LDS count as LDS writes), the newest included, and the scheduling barriers keep
+    // the MFMAs above the wait.
+    const int nsteps = prm.kblocks;
+    v4i_f4 a0[RT], a1[RT], a2[RT];
+    auto load_step = [&](int step, v4i_f4* ar, uint8_t* buf) {
+        const size_t off = (size_t)min(step, nsteps - 1) * 64;
+        // The register loads are written as instructions: the compiler, seeing register loads and loads into LDS mixed
+        // on one counter, would wait for all of them before the first use of these registers.  It does not know that
+        // the registers fill later: between here and the MFMAs that read them it must neither copy nor spill them,
+        // which the build checks (no scratch memory for this kernel).
+#pragma unroll
+        for (int i = 0; i < RT; ++i) asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(ar[i]) : "v"(a_src[i] + off));
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+            __builtin_amdgcn_global_load_lds((const void*)(w_src[u] + off), (__attribute__((address_space(3))) void*)(buf + (wave * 2 + u) * 1024), 16, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto sync_keep_newest = [&]() {
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (RT == 4) asm volatile("s_waitcnt vmcnt(6)" ::: "memory"); else asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    static_assert(RT == 4 || RT == 1, "the wait counts above are RT + 2");
+    load_step(0, a0, buf0);
+    load_step(1, a1, buf1);
+    sync_keep_newest();
+    int step = 0;
+    for (; step + 3 <= nsteps; step += 3) {
+        load_step(step + 2, a2, buf2);   // (each buffer and register set was last read one step before it is loaded again)
+        multiply(buf0, a0);
+        sync_keep_newest();
+        load_step(step + 3, a0, buf0);
+        multiply(buf1, a1);
+        sync_keep_newest();
+        load_step(step + 4, a1, buf1);
+        multiply(buf2, a2);
+        sync_keep_newest();
+    }
+    // the steps left are in a0 / buf0 and a1 / buf1; no load is in flight when the epilogue reuses LDS
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+    if (step < nsteps) multiply(buf0, a0);
+    if (step + 1 < nsteps) multiply(buf1, a1);
+    __builtin_amdgcn_sched_barrier(0);
+    __syncthreads();
+    f4_epilogue<RT>(prm, acc, lds_f4, tid, lane, wave, m0, n0);
+}
+
+template <int RT>
 static hipError_t f4_launch(const F4Params& prm, unsigned grid, hipStream_t s)
 {
-    constexpr int lds = F4Shape<RT>::lds_bytes(NBUF);
-    if constexpr (lds > 64 * 1024) {
-        static std::atomic<bool> attr_set{false};   // (an idempotent call: a lost race only repeats it)
-        if (!attr_set.load(std::memory_order_acquire)) {
-            const hipError_t e = hipFuncSetAttribute((const void*)f4_gemm_kernel<NBUF, RT>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-            if (e != hipSuccess) return e;
-            attr_set.store(true, std::memory_order_release);
-        }
-    }
-    f4_gemm_kernel<NBUF, RT><<<grid, 256, lds, s>>>(prm);
+    f4_gemm_kernel<RT><<<grid, 256, F4Shape<RT>::kLdsBytes, s>>>(prm);   // (under 64 KiB: no attribute to raise)
     return hipGetLastError();
 }
 
@@ -372,17 +389,10 @@ hipError_t launch_f4_gemm(int M, int N, int K, const uint8_t* act_blob, const ui
     const long nwg_big = (long)((M + 255) / 256) * prm.tiles_n;
     if (nwg_big < cus) {
         prm.tiles_m = (M + 63) / 64;
-        return f4_launch<3, 1>(prm, (unsigned)(prm.tiles_m * prm.tiles_n), s);
+        return f4_launch<1>(prm, (unsigned)(prm.tiles_m * prm.tiles_n), s);
     }
     prm.tiles_m = (M + 255) / 256;
-    // Two or three workgroups per compute unit: three hide more latency, but the grid runs in rounds of (units x resident
-    // workgroups) and a nearly empty last round costs a whole one, so the count that wastes fewer workgroup slots is
-    // taken (M = 8192, 4096 x 4096: 1024 workgroups are two full rounds of 512 but 1.33 rounds of 768: 73 vs 85 us); with
-    // two, the LDS left over holds a third operand buffer.
-    const long nwg = nwg_big;
-    const long slots3 = (nwg + 3 * cus - 1) / (3 * cus) * 3, slots2 = (nwg + 2 * cus - 1) / (2 * cus) * 2;
-    if (nwg > 2 * cus && slots2 < slots3) return f4_launch<3, 4>(prm, (unsigned)nwg, s);
-    return f4_launch<2, 4>(prm, (unsigned)nwg, s);
+    return f4_launch<4>(prm, (unsigned)nwg_big, s);
 }
 
 }  // namespace abq
