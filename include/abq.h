@@ -275,8 +275,9 @@ int abq_gemm_act_codes_static(int p, int q, int M, int N, int K,
  * binary16 output as abq_gemm, at twice the matrix rate of the int8 path.  Both operands use one packed layout:
  *   abq_f4_packed_bytes(bits, rows, K)  size of the blob for a [rows][K] operand (0 for arguments out of range)
  *   abq_f4_pack_codes   codes u8 [rows][K] (device, row-major; bits above `bits` are dropped), scale f32 [rows] and
- *                       zero i32 [rows] (device) -> blob `packed_out` (device, caller-owned, >= the size above); for
- *                       the weights rows = N, for the activations rows = M
+ *                       zero i32 [rows] (device; the zero-point of a `bits`-bit code, 0..2^bits-1: the matmul's
+ *                       epilogue relies on it) -> blob `packed_out` (device, caller-owned, >= the size above);
+ *                       for the weights rows = N, for the activations rows = M
  *   abq_f4_gemm         Y[M,N] = dequant(A . W^T) from two such blobs (p: bits of W, q: bits of A, both 1 or 2);
  *                       y_fp16 [M][N] device, acc_i32 [M][N] device or NULL
  * Device pointers 16-byte aligned; work is enqueued on `stream`; nothing is allocated.  ABQ_ERR_NULL, ABQ_ERR_BITS

@@ -183,13 +183,15 @@ __device__ __forceinline__ void f4_epilogue(const F4Params& prm, v4f_f4 (*acc)[8
     if (prm.acc == nullptr && (prm.N & 7) == 0) {
         constexpr int kRowBytes = 272, kPassRows = SH::kPassRows, kPassTiles = kPassRows / 16;
         uint8_t* const stage = lds_f4 + wave * (kPassRows * kRowBytes);
-        uint32_t wz[8], cw[8];
-        float sw[8];
+        // Every term here is an integer below 2^24 in magnitude (K * 9 < 2^24: the entry point checks it), and so is every
+        // partial sum, so binary32 fused multiply-adds give the int32 arithmetic's value exactly, at four times the rate
+        // of 32-bit integer multiplies; the accumulator needs no conversion either.
+        float wz[8], cw[8], sw[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const RowParams pw = par_w[16 * j + r];
-            wz[j] = (uint32_t)pw.zero;
-            cw[j] = (uint32_t)pw.sum - (uint32_t)prm.K * (uint32_t)pw.zero;
+            wz[j] = -(float)pw.zero;
+            cw[j] = (float)(pw.sum - prm.K * pw.zero);
             sw[j] = pw.scale;
         }
 #pragma unroll
@@ -201,11 +203,11 @@ __device__ __forceinline__ void f4_epilogue(const F4Params& prm, v4f_f4 (*acc)[8
                     const int i = kPassTiles * pass + i2;
                     const int rl = 16 * i2 + 4 * G + reg;            // row inside this pass
                     const RowParams pa = par_a[kWaveRows * wave + kPassRows * pass + rl];
+                    const float asum = (float)pa.sum, az = -(float)pa.zero;
 #pragma unroll
                     for (int j = 0; j < 8; ++j) {
-                        const uint32_t S = (uint32_t)(int32_t)acc[i][j][reg];
-                        const int32_t centered = (int32_t)(S - wz[j] * (uint32_t)pa.sum - (uint32_t)pa.zero * cw[j]);
-                        const float v = ((float)centered * pa.scale) * sw[j];
+                        const float centered = __builtin_fmaf(az, cw[j], __builtin_fmaf(wz[j], asum, acc[i][j][reg]));
+                        const float v = (centered * pa.scale) * sw[j];
                         uint32_t h;
                         asm("v_cvt_f16_f32 %0, %1" : "=v"(h) : "v"(v));   // (the instruction itself: see epilogue_value)
                         *reinterpret_cast<uint16_t*>(stage + rl * kRowBytes + (16 * j + r) * 2) = (uint16_t)h;
