@@ -42,6 +42,7 @@ struct TiledParams {
     const u4v* gparams;       // per-group weight parameters (g128 blobs; null otherwise): [ntiles][nsuper][16 channels] records
     int tiles_m, tiles_n;     // workgroup tiles along M and N (1-D grid of tiles_m * tiles_n workgroups)
     int band_m;               // row blocks per band of the tile order (see the kernel's tile mapping)
+    int narrow_sums;          // 1: every row sum of codes is below 2^23 (the epilogue then multiplies at the 24-bit rate)
 };
 
 // Weights are held one phase (half a super-chunk, 256 k, four 64-k slices) at a time.  A b-bit
@@ -302,28 +303,57 @@ __global__ __launch_bounds__(256, (WD == 4 ? 2 : (NTW <= 2 ? (MT == 4 ? 3 : 2) :
     __syncthreads();   // every wave is done reading A
     constexpr int kWCols = NTW * kTileN;                       // columns of Y this wave owns
     uint16_t* stage = reinterpret_cast<uint16_t*>((wave < 2 ? lds_a0 : lds_a1) + (wave & 1) * (kBM * kWCols * 2));
+    // Eq. 3's affine dequant in the integers, with everything that depends on the row or on the column alone taken out of
+    // the element loop:  raw = S + ow sumA + oa sumW - K oa ow  (the sum over the codes themselves; S is over the stored,
+    // offset operands) and centered = raw - wz sumA - az (sumW - K wz), all modulo 2^32 as in epilogue_value.  That
+    // leaves two multiplies per element.  32-bit integer multiplies run at a quarter of the vector rate and made this
+    // epilogue a third of a prefill launch; where every factor fits 24 bits (sums of codes below 2^23: the host checks
+    // K (2^p - 1) and K (2^q - 1)) the 24-bit multiply-add gives the same low 32 bits at the full rate.
     RowParams pw[NTW];
+    int32_t col_raw[NTW], col_cw[NTW], col_nwz[NTW];
 #pragma unroll
-    for (int nt = 0; nt < NTW; ++nt) pw[nt] = par_w[wave * kWCols + nt * 16 + r];
+    for (int nt = 0; nt < NTW; ++nt) {
+        pw[nt] = par_w[wave * kWCols + nt * 16 + r];
+        col_raw[nt] = (int32_t)((uint32_t)prm.oa * (uint32_t)pw[nt].sum - (uint32_t)prm.K * (uint32_t)prm.oa * (uint32_t)prm.ow);
+        col_cw[nt] = (int32_t)((uint32_t)pw[nt].sum - (uint32_t)prm.K * (uint32_t)pw[nt].zero);
+        col_nwz[nt] = -pw[nt].zero;
+    }
+    auto dequant_tile = [&](auto narrow, auto plain) {
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
+        for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
-        for (int reg = 0; reg < 4; ++reg) {
-            const int ml = mt * 16 + 4 * G + reg;
-            const int m = m0 + ml;
-            const RowParams pa = par_a[ml];
+            for (int reg = 0; reg < 4; ++reg) {
+                const int ml = mt * 16 + 4 * G + reg;
+                const int m = m0 + ml;
+                const RowParams pa = par_a[ml];
+                const int32_t row_raw = (int32_t)((uint32_t)prm.ow * (uint32_t)pa.sum), naz = -pa.zero;
 #pragma unroll
-            for (int nt = 0; nt < NTW; ++nt) {
-                const int n = n0 + wave * kWCols + nt * 16 + r;
-                int32_t raw;
-                const uint16_t h = epilogue_value(acc[mt][nt][reg], prm.oa, prm.ow, prm.K, pa, pw[nt], &raw);
-                stage[ml * kWCols + nt * 16 + r] = h;
-                if (prm.acc && m < prm.M && n < prm.N) prm.acc[(size_t)m * prm.N + n] = raw;
-                if (prm.rq.codes && m < prm.M && n < prm.N)
-                    prm.rq.codes[(size_t)m * prm.N + n] = requant_code(h, prm.rq.scale[m], prm.rq.zero[m], prm.rq.qmax);
+                for (int nt = 0; nt < NTW; ++nt) {
+                    const int32_t raw = (int32_t)((uint32_t)acc[mt][nt][reg] + (uint32_t)row_raw + (uint32_t)col_raw[nt]);
+                    int32_t centered;
+                    if constexpr (decltype(narrow)::value)
+                        centered = __mul24(naz, col_cw[nt]) + (__mul24(col_nwz[nt], pa.sum) + raw);
+                    else
+                        centered = (int32_t)((uint32_t)raw + (uint32_t)col_nwz[nt] * (uint32_t)pa.sum + (uint32_t)naz * (uint32_t)col_cw[nt]);
+                    const float v = ((float)centered * pa.scale) * pw[nt].scale;
+                    uint32_t hv;
+                    asm("v_cvt_f16_f32 %0, %1" : "=v"(hv) : "v"(v));   // (the instruction itself: see epilogue_value)
+                    const uint16_t h = (uint16_t)hv;
+                    stage[ml * kWCols + nt * 16 + r] = h;
+                    if constexpr (!decltype(plain)::value) {
+                        const int n = n0 + wave * kWCols + nt * 16 + r;
+                        if (prm.acc && m < prm.M && n < prm.N) prm.acc[(size_t)m * prm.N + n] = raw;
+                        if (prm.rq.codes && m < prm.M && n < prm.N)
+                            prm.rq.codes[(size_t)m * prm.N + n] = requant_code(h, prm.rq.scale[m], prm.rq.zero[m], prm.rq.qmax);
+                    }
+                }
             }
         }
-    }
+    };
+    const bool plain_out = prm.acc == nullptr && prm.rq.codes == nullptr;   // (the same for every thread, as is narrow_sums)
+    if (prm.narrow_sums && plain_out) dequant_tile(std::true_type{}, std::true_type{});
+    else if (prm.narrow_sums) dequant_tile(std::true_type{}, std::false_type{});
+    else dequant_tile(std::false_type{}, std::false_type{});
     // only this wave reads what it wrote; same-wave LDS accesses execute in order
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -604,6 +634,7 @@ hipError_t launch_gemm_tiled(const GemmArgs& g, const ActLayout& A, const Weight
     prm.oa = (g.q == 8) ? 128 : 0;
     prm.ow = (g.p == 8) ? 128 : 0;
     prm.gparams = W.g128 ? (const u4v*)(g.w_blob + W.off_gparams) : nullptr;
+    prm.narrow_sums = ((long)g.K * ((1 << g.p) - 1) < (1L << 23) && (long)g.K * ((1 << g.q) - 1) < (1L << 23)) ? 1 : 0;
     if (W.g128) {
         // per-group weight parameters: 64 rows of A against 128 (or, for few workgroups, 64) rows of W per workgroup
         int cus_g = 256, dev_g = 0;
