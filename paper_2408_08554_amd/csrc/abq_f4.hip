@@ -53,81 +53,70 @@ __device__ __forceinline__ uint32_t f4_nibbles(uint32_t x)
     return (pairs | (pairs >> 8)) & 0xFFFFu;
 }
 
-// One thread per (row tile, K block, lane): 32 codes of one row -> 32 E2M1 nibbles (16 bytes).  vec: K is a multiple
-// of 16 and the rows are 16-byte aligned, so the 32 codes are two 128-bit loads.
-__global__ void f4_pack_blocks_kernel(const uint8_t* codes, int rows, int K, int kblocks, uint32_t mask, int vec, v4i_f4* out, size_t nvec)
+// The whole blob in one launch (a pack of the activations sits in front of every matmul: three dependent launches
+// cost more than the work).  One workgroup of sixteen waves per tile of 16 rows; wave w packs the K blocks w, w + 16, ...:
+// lane L takes 32 codes of row L % 16 at k = 128 kb + 32 (L / 16) -> 32 E2M1 nibbles (16 bytes, the operand layout), and
+// keeps the sum of its codes; the sums meet across the lanes of a row, then across the waves through LDS, and become the
+// rows' parameter records {sum of codes, scale, zero}.  vec: K is a multiple of 16 and the rows are 16-byte aligned, so
+// the 32 codes are two 128-bit loads.  Workgroup 0 also writes the header.
+constexpr int kF4PackWaves = 16;
+__global__ __launch_bounds__(64 * kF4PackWaves) void f4_pack_kernel(const uint8_t* codes, int rows, int K, int kblocks, uint32_t mask, int vec,
+                                                                    const float* scale, const int32_t* zero, int bits, uint32_t* hdr,
+                                                                    RowParams* params, v4i_f4* out)
 {
-    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= nvec) return;
-    const int lane = (int)(i & 63);
-    const size_t blk = i >> 6;
-    const int kb = (int)(blk % kblocks), rt = (int)(blk / kblocks);
-    const int row = rt * 16 + (lane & 15), k0 = kb * kF4BlockK + (lane >> 4) * 32;
-    uint32_t w[4] = {0, 0, 0, 0};
-    if (row < rows) {
-        const uint8_t* src = codes + (size_t)row * K;
+    __shared__ uint32_t part[kF4PackWaves][16];
+    const int tid = (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int rt = (int)blockIdx.x;
+    const int row = rt * 16 + (lane & 15);
+    const uint8_t* src = codes + (size_t)min(row, rows - 1) * K;   // (rows past the end: a valid row is read, zeros are stored)
+    const uint32_t m4 = mask * 0x01010101u;
+    uint32_t sum = 0;
+#pragma unroll 2
+    for (int kb = wave; kb < kblocks; kb += kF4PackWaves) {
+        const int k0 = kb * kF4BlockK + (lane >> 4) * 32;
+        uint32_t w[4] = {0, 0, 0, 0};
         if (vec && k0 + 32 <= K) {
-            const uint32_t m4 = mask * 0x01010101u;
             const v4i_f4 lo = *reinterpret_cast<const v4i_f4*>(src + k0), hi = *reinterpret_cast<const v4i_f4*>(src + k0 + 16);
-            w[0] = f4_nibbles((uint32_t)lo.x & m4) | (f4_nibbles((uint32_t)lo.y & m4) << 16);
-            w[1] = f4_nibbles((uint32_t)lo.z & m4) | (f4_nibbles((uint32_t)lo.w & m4) << 16);
-            w[2] = f4_nibbles((uint32_t)hi.x & m4) | (f4_nibbles((uint32_t)hi.y & m4) << 16);
-            w[3] = f4_nibbles((uint32_t)hi.z & m4) | (f4_nibbles((uint32_t)hi.w & m4) << 16);
+            const uint32_t c[8] = {(uint32_t)lo.x & m4, (uint32_t)lo.y & m4, (uint32_t)lo.z & m4, (uint32_t)lo.w & m4,
+                                   (uint32_t)hi.x & m4, (uint32_t)hi.y & m4, (uint32_t)hi.z & m4, (uint32_t)hi.w & m4};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sum = __builtin_amdgcn_sad_u8(c[e], 0u, sum);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) w[e] = f4_nibbles(c[2 * e]) | (f4_nibbles(c[2 * e + 1]) << 16);
         } else {
             for (int e = 0; e < 32; ++e) {
                 const int k = k0 + e;
                 const uint32_t c = k < K ? (src[k] & mask) : 0u;
+                sum += c;
                 const uint32_t nib = c == 3 ? 5u : (c << 1);
                 w[e >> 3] |= nib << (4 * (e & 7));
             }
         }
+        if (row >= rows) w[0] = w[1] = w[2] = w[3] = 0;
+        out[((size_t)rt * kblocks + kb) * 64 + lane] = v4i_f4{(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
     }
-    out[i] = v4i_f4{(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
-}
-
-// Row parameters {sum of the row's codes, scale, zero}: one workgroup per row.
-__global__ void f4_row_params_kernel(const uint8_t* codes, int K, uint32_t mask, int vec, const float* scale, const int32_t* zero, RowParams* out)
-{
-    __shared__ int32_t part[256];
-    const int row = (int)blockIdx.x;
-    const uint8_t* src = codes + (size_t)row * K;
-    uint32_t s = 0;
-    int done = 0;
-    if (vec) {   // 128-bit loads, byte sums four at a time
-        const uint32_t m4 = mask * 0x01010101u;
-        done = K & ~15;
-        for (int k = (int)threadIdx.x * 16; k < done; k += (int)blockDim.x * 16) {
-            const v4i_f4 x = *reinterpret_cast<const v4i_f4*>(src + k);
-            s = __builtin_amdgcn_sad_u8((uint32_t)x.x & m4, 0u, s);
-            s = __builtin_amdgcn_sad_u8((uint32_t)x.y & m4, 0u, s);
-            s = __builtin_amdgcn_sad_u8((uint32_t)x.z & m4, 0u, s);
-            s = __builtin_amdgcn_sad_u8((uint32_t)x.w & m4, 0u, s);
-        }
-    }
-    for (int k = done + (int)threadIdx.x; k < K; k += (int)blockDim.x) s += (uint32_t)(src[k] & mask);
-    part[threadIdx.x] = (int32_t)s;
+    sum += (uint32_t)__shfl_xor((int)sum, 16);
+    sum += (uint32_t)__shfl_xor((int)sum, 32);
+    if (lane < 16) part[wave][lane] = sum;
     __syncthreads();
-    for (int w = 128; w > 0; w >>= 1) {
-        if ((int)threadIdx.x < w) part[threadIdx.x] += part[threadIdx.x + w];
-        __syncthreads();
+    if (tid < 16 && row < rows) {
+        uint32_t total = 0;
+#pragma unroll
+        for (int w = 0; w < kF4PackWaves; ++w) total += part[w][tid];
+        params[row] = RowParams{(int32_t)total, scale[row], zero[row], 0};
     }
-    if (threadIdx.x == 0) out[row] = RowParams{part[0], scale[row], zero[row], 0};
-}
-
-__global__ void f4_header_kernel(uint32_t* hdr, uint32_t magic, int bits, int rows, int K)
-{
-    const int t = (int)threadIdx.x;
-    if (t < 64) hdr[t] = t == 0 ? magic : (t == 1 ? 0x34460001u : (t == 2 ? (uint32_t)bits : (t == 3 ? (uint32_t)rows : (t == 4 ? (uint32_t)K : 0u))));
+    if (rt == 0 && tid >= 64 && tid < 128) {
+        const int t = tid - 64;
+        hdr[t] = t == 0 ? 0x34514241u /* "ABQ4" */ : (t == 1 ? 0x34460001u : (t == 2 ? (uint32_t)bits : (t == 3 ? (uint32_t)rows : (t == 4 ? (uint32_t)K : 0u))));
+    }
 }
 
 hipError_t launch_f4_pack(int bits, int rows, int K, const uint8_t* codes, const float* scale, const int32_t* zero, uint8_t* blob, hipStream_t s)
 {
     const uint32_t mask = (1u << bits) - 1u;
-    f4_header_kernel<<<1, 64, 0, s>>>((uint32_t*)blob, 0x34514241u /* "ABQ4" */, bits, rows, K);
     const int vec = (K % 16 == 0) ? 1 : 0;   // (the entry point checks that `codes` is 16-byte aligned)
-    f4_row_params_kernel<<<(unsigned)rows, 256, 0, s>>>(codes, K, mask, vec, scale, zero, (RowParams*)(blob + f4_off_params()));
-    const size_t nvec = (size_t)f4_row_tiles(rows) * f4_k_blocks(K) * 64;
-    f4_pack_blocks_kernel<<<(unsigned)((nvec + 255) / 256), 256, 0, s>>>(codes, rows, K, f4_k_blocks(K), mask, vec, (v4i_f4*)(blob + f4_off_blocks(rows)), nvec);
+    f4_pack_kernel<<<(unsigned)f4_row_tiles(rows), 64 * kF4PackWaves, 0, s>>>(codes, rows, K, f4_k_blocks(K), mask, vec, scale, zero, bits, (uint32_t*)blob,
+                                                                              (RowParams*)(blob + f4_off_params()), (v4i_f4*)(blob + f4_off_blocks(rows)));
     return hipGetLastError();
 }
 
