@@ -149,14 +149,15 @@ template <int RT> struct F4Shape {
 // outputs, staged through LDS for 128-bit stores where the output allows it.  lds_f4 is free for reuse when it starts (the
 // caller has passed a barrier after its last read, and none of its loads into LDS is in flight).
 template <int RT>
-__device__ __forceinline__ void f4_epilogue(const F4Params& prm, v4f_f4 (*acc)[8], uint8_t* lds_f4, int tid, int lane, int wave, int m0, int n0)
+__device__ __forceinline__ void f4_epilogue(const F4Params& prm, v4f_f4 (*acc)[8], uint8_t* lds_f4, int tid, int lane, int wave, int m0, int n0,
+                                            v4i_f4 my_a, v4i_f4 my_w)
 {
     using SH = F4Shape<RT>;
     RowParams* const par_a = reinterpret_cast<RowParams*>(lds_f4 + SH::kParamOffset);
     RowParams* const par_w = par_a + SH::kTileM;
-    // epilogue parameters into the freed operand memory (the other workgroups of the unit hide this round trip)
-    if (tid < SH::kTileM) par_a[tid] = prm.aparams[min(m0 + tid, prm.M - 1)];
-    if (tid < kF4TileN) par_w[tid] = prm.wparams[min(n0 + tid, prm.N - 1)];
+    // epilogue parameters (fetched by the kernel before its K loop: no memory round trip here) into the freed operand memory
+    if (tid < SH::kTileM) *reinterpret_cast<v4i_f4*>(par_a + tid) = my_a;
+    if (tid < kF4TileN) *reinterpret_cast<v4i_f4*>(par_w + tid) = my_w;
     __syncthreads();
 
     // ---- epilogue: lane (G, r) of accumulator (i, j) holds rows 16 RT wave + 16 i + 4 G + reg, channel 16 j + r.
@@ -256,6 +257,11 @@ __global__ __launch_bounds__(256, RT == 4 ? 2 : 4) void f4_gemm_kernel(F4Params 
     const int m_blk = 8 * panel + in_panel % panel_rows, n_blk = in_panel / panel_rows;
     const int m0 = m_blk * SH::kTileM, n0 = n_blk * kF4TileN;
 
+    // the epilogue's parameters of this tile's rows and channels, one record per thread: on their way during the K loop
+    v4i_f4 my_a = v4i_f4{0, 0, 0, 0}, my_w = my_a;   // (a record is 16 bytes)
+    if (tid < SH::kTileM) my_a = *reinterpret_cast<const v4i_f4*>(prm.aparams + min(m0 + tid, prm.M - 1));
+    if (tid < kF4TileN) my_w = *reinterpret_cast<const v4i_f4*>(prm.wparams + min(n0 + tid, prm.N - 1));
+
     const v4i_f4* a_src[RT];
 #pragma unroll
     for (int i = 0; i < RT; ++i) a_src[i] = prm.a_blocks + ((size_t)min(m0 / 16 + wave * RT + i, prm.a_tiles - 1) * prm.kblocks) * 64 + lane;
@@ -353,7 +359,7 @@ __global__ __launch_bounds__(256, RT == 4 ? 2 : 4) void f4_gemm_kernel(F4Params 
     if (step + 1 < nsteps) multiply(buf1, a1);
     __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
-    f4_epilogue<RT>(prm, acc, lds_f4, tid, lane, wave, m0, n0);
+    f4_epilogue<RT>(prm, acc, lds_f4, tid, lane, wave, m0, n0, my_a, my_w);
 }
 
 template <int RT>
