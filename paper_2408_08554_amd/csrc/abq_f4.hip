@@ -71,29 +71,45 @@ __global__ __launch_bounds__(64 * kF4PackWaves) void f4_pack_kernel(const uint8_
     const uint8_t* src = codes + (size_t)min(row, rows - 1) * K;   // (rows past the end: a valid row is read, zeros are stored)
     const uint32_t m4 = mask * 0x01010101u;
     uint32_t sum = 0;
-#pragma unroll 2
-    for (int kb = wave; kb < kblocks; kb += kF4PackWaves) {
-        const int k0 = kb * kF4BlockK + (lane >> 4) * 32;
-        uint32_t w[4] = {0, 0, 0, 0};
-        if (vec && k0 + 32 <= K) {
-            const v4i_f4 lo = *reinterpret_cast<const v4i_f4*>(src + k0), hi = *reinterpret_cast<const v4i_f4*>(src + k0 + 16);
-            const uint32_t c[8] = {(uint32_t)lo.x & m4, (uint32_t)lo.y & m4, (uint32_t)lo.z & m4, (uint32_t)lo.w & m4,
-                                   (uint32_t)hi.x & m4, (uint32_t)hi.y & m4, (uint32_t)hi.z & m4, (uint32_t)hi.w & m4};
+    // up to four K blocks of the wave at a time: their loads are all requested before the first is packed
+    constexpr int NB = 4;
+    for (int kb0 = wave; kb0 < kblocks; kb0 += kF4PackWaves * NB) {
+        v4i_f4 lo[NB], hi[NB];
+        bool fast[NB];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) sum = __builtin_amdgcn_sad_u8(c[e], 0u, sum);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) w[e] = f4_nibbles(c[2 * e]) | (f4_nibbles(c[2 * e + 1]) << 16);
-        } else {
-            for (int e = 0; e < 32; ++e) {
-                const int k = k0 + e;
-                const uint32_t c = k < K ? (src[k] & mask) : 0u;
-                sum += c;
-                const uint32_t nib = c == 3 ? 5u : (c << 1);
-                w[e >> 3] |= nib << (4 * (e & 7));
+        for (int u = 0; u < NB; ++u) {
+            const int kb = kb0 + kF4PackWaves * u, k0 = kb * kF4BlockK + (lane >> 4) * 32;
+            fast[u] = vec && kb < kblocks && k0 + 32 <= K;
+            lo[u] = hi[u] = v4i_f4{0, 0, 0, 0};
+            if (fast[u]) {
+                lo[u] = *reinterpret_cast<const v4i_f4*>(src + k0);
+                hi[u] = *reinterpret_cast<const v4i_f4*>(src + k0 + 16);
             }
         }
-        if (row >= rows) w[0] = w[1] = w[2] = w[3] = 0;
-        out[((size_t)rt * kblocks + kb) * 64 + lane] = v4i_f4{(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
+#pragma unroll
+        for (int u = 0; u < NB; ++u) {
+            const int kb = kb0 + kF4PackWaves * u, k0 = kb * kF4BlockK + (lane >> 4) * 32;
+            if (kb >= kblocks) break;   // (the same for the whole wave)
+            uint32_t w[4] = {0, 0, 0, 0};
+            if (fast[u]) {
+                const uint32_t c[8] = {(uint32_t)lo[u].x & m4, (uint32_t)lo[u].y & m4, (uint32_t)lo[u].z & m4, (uint32_t)lo[u].w & m4,
+                                       (uint32_t)hi[u].x & m4, (uint32_t)hi[u].y & m4, (uint32_t)hi[u].z & m4, (uint32_t)hi[u].w & m4};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) sum = __builtin_amdgcn_sad_u8(c[e], 0u, sum);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) w[e] = f4_nibbles(c[2 * e]) | (f4_nibbles(c[2 * e + 1]) << 16);
+            } else {
+                for (int e = 0; e < 32; ++e) {
+                    const int k = k0 + e;
+                    const uint32_t c = k < K ? (src[k] & mask) : 0u;
+                    sum += c;
+                    const uint32_t nib = c == 3 ? 5u : (c << 1);
+                    w[e >> 3] |= nib << (4 * (e & 7));
+                }
+            }
+            if (row >= rows) w[0] = w[1] = w[2] = w[3] = 0;
+            out[((size_t)rt * kblocks + kb) * 64 + lane] = v4i_f4{(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
+        }
     }
     sum += (uint32_t)__shfl_xor((int)sum, 16);
     sum += (uint32_t)__shfl_xor((int)sum, 32);

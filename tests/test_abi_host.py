@@ -418,3 +418,29 @@ def test_requant_entry_point_rejects_before_touching_the_device():
     assert call(M=300) == B.ABQ_ERR_NULL                                      # the two-kernel path needs its workspace
     assert call(M=300, ws=A16, wsb=16) == B.ABQ_ERR_SIZE
     assert lib.abq_gemm_act_codes(4, 8, 1, 64, 512, A16, A16, A16, A16, F, None, None, None, 0, None) == B.ABQ_ERR_NULL   # y stays required there
+
+
+def test_build_refuses_scratch_memory_in_kernels_with_hand_written_loads(tmp_path, monkeypatch):
+    """The F4 matmul kernel fills registers with load instructions the compiler does not track; a spill of such a
+    register would save it before the data lands.  The build reads the compiler's resource-usage remarks and must fail
+    on any scratch memory in that kernel, and when the remarks are missing."""
+    from paper_2408_08554_amd import build as bld
+
+    def remarks(scratch):
+        return ("abq_f4.hip:1:0: remark: Function Name: _ZN3abq14f4_gemm_kernelILi4EEEvNS_8F4ParamsE [-Rpass-analysis=kernel-resource-usage]\n"
+                "abq_f4.hip:1:0: remark:     VGPRs: 228 [-Rpass-analysis=kernel-resource-usage]\n"
+                f"abq_f4.hip:1:0: remark:     ScratchSize [bytes/lane]: {scratch} [-Rpass-analysis=kernel-resource-usage]\n"
+                "abq_f4.hip:2:0: remark: Function Name: _ZN3abq14f4_pack_kernelEPKh [-Rpass-analysis=kernel-resource-usage]\n"
+                "abq_f4.hip:2:0: remark:     ScratchSize [bytes/lane]: 16 [-Rpass-analysis=kernel-resource-usage]\n")
+
+    monkeypatch.setattr(bld, "OBJ", str(tmp_path))
+    src = os.path.join(bld.CSRC, "abq_f4.hip")
+    obj = tmp_path / "abq_f4.hip.o"
+    bld._check_no_scratch(src, remarks(0), "f4_gemm_kernel")      # other kernels may use scratch; this one does not: passes
+    obj.write_bytes(b"x")
+    with pytest.raises(RuntimeError, match="scratch"):
+        bld._check_no_scratch(src, remarks(48), "f4_gemm_kernel")
+    assert not obj.exists()                                       # the object of a refused build is removed
+    with pytest.raises(RuntimeError, match="did not run"):
+        bld._check_no_scratch(src, "", "f4_gemm_kernel")
+    assert "abq_f4.hip" in bld.NO_SCRATCH
