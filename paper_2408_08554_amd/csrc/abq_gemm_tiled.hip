@@ -391,8 +391,8 @@ __global__ __launch_bounds__(256, (WD == 4 ? 2 : (NTW <= 2 ? (MT == 4 ? 3 : 2) :
 // gives sum_k a' of every row in every column, an MFMA of ones against the B operand gives sum_k w' of every column
 // in every row — both already in the accumulator layout.  k past K holds a' = 0 and w' = z (the packer pads the last
 // group of a g128 blob with its zero-point), so padded k add nothing; groups wholly past K carry scale 0.
-// Then one conversion and one fused multiply-add per element and group: M*N*K/128 of them, which is what bounds
-// this kernel (the vector ALU, not the matrix pipe).
+// Then two 24-bit integer multiply-adds, one conversion and one fused multiply-add per element and group: M*N*K/128
+// of each, which is what bounds this kernel (the vector ALU, not the matrix pipe).
 typedef float v4f __attribute__((ext_vector_type(4)));
 
 template <int P, int NTW, int MT, int PH>
@@ -438,7 +438,9 @@ __device__ __forceinline__ void step_g128(const u4v (*w)[phase_regs(P)], const u
             for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
                 for (int reg = 0; reg < 4; ++reg) {
-                    const int t = c[mt][nt][reg] - z * asum[mt][reg] - zc[mt][reg] * wz;
+                    // (24-bit multiply-adds, full rate: a group's sums are below 2^17 and the zero-points below 2^8, and the
+                    // products are exact in 32 bits; 32-bit multiplies run at a quarter of the rate and were this kernel's bound)
+                    const int t = __mul24(-zc[mt][reg], wz) + (__mul24(-z, asum[mt][reg]) + c[mt][nt][reg]);
                     facc[mt][nt][reg] = fmaf((float)t, sc, facc[mt][nt][reg]);
                 }
             }
