@@ -21,6 +21,15 @@ extern "C" {
  * stays untouched in practice). */
 int abq_probe_stream_read(const void* buf, size_t bytes, void* sink, void* stream);
 
+/* Reads that hit in L2: 8 regions of `region_bytes` (a multiple of 32 KiB, at most 64 MiB) lie back to back at `buf`;
+ * every compute unit runs `wgs_per_cu` (1..8) workgroups of 256 threads, and a workgroup reads the whole region of its
+ * XCD `passes` times with 128-bit loads, eight in flight per lane.  With regions of one or two MiB the data stays in
+ * each XCD's L2 after the first pass.  `buf` holds 8 * region_bytes (the caller's to guarantee).  Status as the other
+ * probes (null pointer, argument out of range, misaligned pointer).  abq_probe_l2_read_bytes: the bytes one such
+ * launch requests. */
+int abq_probe_l2_read(const void* buf, size_t region_bytes, int passes, int wgs_per_cu, void* sink, void* stream);
+double abq_probe_l2_read_bytes(size_t region_bytes, int passes, int wgs_per_cu);
+
 /* Dense int8 MFMA issue loop on every CU: `iters` rounds of eight independent 16x16x64 MFMAs per wave,
  * 32 waves per CU.  pattern 0: three of four operand bytes zero; pattern 1: every operand byte non-zero
  * and varying from lane to lane (the sustained rate depends on the data: the chip lowers its clock on

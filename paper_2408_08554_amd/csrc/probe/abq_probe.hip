@@ -29,6 +29,30 @@ __global__ __launch_bounds__(512) void stream_read_kernel(const u4v* src, size_t
     if (s == 0x9E3779B9u) sink[threadIdx.x] = s;
 }
 
+// Reads that hit in L2: workgroup b (on XCD b % 8: round-robin dispatch) reads the region of its XCD, `region_vecs`
+// 16-byte vectors, `passes` times with ordinary 128-bit loads, eight in flight per lane, every workgroup starting at a
+// different offset.  After the first pass a region of a megabyte or two lives in that XCD's L2, so the rate of a
+// launch is the rate at which the compute units can pull operands that hit there.
+__global__ __launch_bounds__(256) void l2_read_kernel(const u4v* src, unsigned region_vecs, int passes, uint32_t* sink)
+{
+    const u4v* region = src + (size_t)(blockIdx.x & 7) * region_vecs;
+    const unsigned chunk = 256u * 8u;                                    // vectors a workgroup reads per round
+    const unsigned rounds = region_vecs / chunk;
+    unsigned at = ((blockIdx.x >> 3) * 7u) % rounds;
+    uint32_t s = 0;
+    for (int p = 0; p < passes; ++p)
+        for (unsigned i = 0; i < rounds; ++i) {
+            const u4v* base = region + (size_t)at * chunk + threadIdx.x;
+            u4v v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = base[u * 256];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+            at = at + 1 == rounds ? 0 : at + 1;
+        }
+    if (s == 0x9E3779B9u) sink[threadIdx.x] = s;
+}
+
 // Eight independent 16x16x64 int8 MFMA chains per wave, `iters` rounds.  pattern 0: three of four operand
 // bytes are zero; pattern 1: every operand byte is non-zero and differs from lane to lane.  The sustained
 // rate depends on the data: measured on MI355X, the chip holds its clock on the former (4.1-4.9 POP/s)
@@ -109,6 +133,24 @@ int abq_probe_stream_read(const void* buf, size_t bytes, void* sink, void* strea
         default: stream_read_kernel<1><<<(unsigned)grid, threads, 0, s>>>((const u4v*)buf, nvec, (uint32_t*)sink); break;
     }
     return hipGetLastError() == hipSuccess ? 0 : -7;
+}
+
+int abq_probe_l2_read(const void* buf, size_t region_bytes, int passes, int wgs_per_cu, void* sink, void* stream)
+{
+    if (!buf || !sink) return -1;
+    if (region_bytes < 32768 || region_bytes % 32768 != 0 || region_bytes > (64u << 20) || passes < 1 || passes > 4096 || wgs_per_cu < 1 || wgs_per_cu > 8) return -3;
+    if (((uintptr_t)buf & 15u) || ((uintptr_t)sink & 15u)) return -4;
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+    l2_read_kernel<<<(unsigned)(cus * wgs_per_cu), 256, 0, (hipStream_t)stream>>>((const u4v*)buf, (unsigned)(region_bytes / 16), passes, (uint32_t*)sink);
+    return hipGetLastError() == hipSuccess ? 0 : -7;
+}
+
+double abq_probe_l2_read_bytes(size_t region_bytes, int passes, int wgs_per_cu)
+{
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+    return (double)region_bytes * passes * wgs_per_cu * cus;
 }
 
 double abq_probe_mfma_i8_ops(int iters)

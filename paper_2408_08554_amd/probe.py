@@ -11,6 +11,8 @@ LIB_PATH = os.path.join(HERE, "libabq_probe.so")
 _c = ctypes
 _SIGNATURES = {
     "abq_probe_stream_read": (_c.c_int, [_c.c_void_p, _c.c_size_t, _c.c_void_p, _c.c_void_p]),
+    "abq_probe_l2_read": (_c.c_int, [_c.c_void_p, _c.c_size_t, _c.c_int, _c.c_int, _c.c_void_p, _c.c_void_p]),
+    "abq_probe_l2_read_bytes": (_c.c_double, [_c.c_size_t, _c.c_int, _c.c_int]),
     "abq_probe_mfma_i8": (_c.c_int, [_c.c_int, _c.c_int, _c.c_void_p, _c.c_void_p]),
     "abq_probe_mfma_i8_ops": (_c.c_double, [_c.c_int]),
     "abq_probe_mfma_f4": (_c.c_int, [_c.c_int, _c.c_int, _c.c_void_p, _c.c_void_p]),
@@ -41,6 +43,15 @@ def _run(status, where):
 def abq_probe_stream_read(buf, nbytes, sink):
     _run(load().abq_probe_stream_read(buf.data_ptr(), nbytes, sink.data_ptr(), torch.cuda.current_stream().cuda_stream),
          "abq_probe_stream_read")
+
+
+def abq_probe_l2_read(buf, region_bytes, passes, wgs_per_cu, sink):
+    _run(load().abq_probe_l2_read(buf.data_ptr(), region_bytes, passes, wgs_per_cu, sink.data_ptr(), torch.cuda.current_stream().cuda_stream),
+         "abq_probe_l2_read")
+
+
+def abq_probe_l2_read_bytes(region_bytes, passes, wgs_per_cu):
+    return float(load().abq_probe_l2_read_bytes(region_bytes, passes, wgs_per_cu))
 
 
 def abq_probe_mfma_i8(iters, pattern, sink):

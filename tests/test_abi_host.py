@@ -272,6 +272,12 @@ def test_probe_rejects():
     assert lib.abq_probe_stream_read(A16, 8, A16, None) == B.ABQ_ERR_SHAPE
     assert lib.abq_probe_stream_read(A16, 4100, A16, None) == B.ABQ_ERR_SHAPE
     assert lib.abq_probe_stream_read(A16 + 4, 4096, A16, None) == B.ABQ_ERR_ALIGN
+    assert lib.abq_probe_l2_read(None, 1 << 20, 1, 1, A16, None) == B.ABQ_ERR_NULL
+    assert lib.abq_probe_l2_read(A16, 1 << 20, 1, 1, None, None) == B.ABQ_ERR_NULL
+    assert lib.abq_probe_l2_read(A16, 1000, 1, 1, A16, None) == B.ABQ_ERR_SHAPE          # not a multiple of 32 KiB
+    assert lib.abq_probe_l2_read(A16, 1 << 20, 0, 1, A16, None) == B.ABQ_ERR_SHAPE
+    assert lib.abq_probe_l2_read(A16, 1 << 20, 1, 9, A16, None) == B.ABQ_ERR_SHAPE
+    assert lib.abq_probe_l2_read(A16 + 4, 1 << 20, 1, 1, A16, None) == B.ABQ_ERR_ALIGN
     assert lib.abq_probe_mfma_i8(10, 0, None, None) == B.ABQ_ERR_NULL
     assert lib.abq_probe_mfma_i8(0, 0, A16, None) == B.ABQ_ERR_SHAPE
     assert lib.abq_probe_mfma_i8(10, 2, A16, None) == B.ABQ_ERR_SHAPE

@@ -612,7 +612,7 @@ def test_fused_act_ignores_bits_above_q(abq):
 
 
 def test_measurement_probes_run(abq):
-    """The two probe kernels (a library of their own, used by the benchmark) launch, finish and leave their sink alone."""
+    """The probe kernels (a library of their own, used by the benchmark and the design measurements) launch, finish and leave their sink alone."""
     from paper_2408_08554_amd import probe as abq   # noqa: F811
     buf = torch.ones(8 << 20, dtype=torch.uint8, device="cuda")
     sink = torch.zeros(4096, dtype=torch.uint8, device="cuda")
@@ -622,6 +622,9 @@ def test_measurement_probes_run(abq):
     abq.abq_probe_mfma_i8(100, 1, sink)
     abq.abq_probe_mfma_f4(100, 0, sink)
     abq.abq_probe_mfma_f4(100, 1, sink)
+    abq.abq_probe_l2_read(buf, 1 << 20, 2, 2, sink)             # eight regions of 1 MiB: the whole of buf
+    abq.abq_probe_l2_read(buf, 32768, 1, 1, sink)               # the smallest region: one round per pass
+    assert abq.abq_probe_l2_read_bytes(1 << 20, 2, 2) == float((1 << 20) * 2 * 2 * torch.cuda.get_device_properties(0).multi_processor_count)
     torch.cuda.synchronize()
     assert int(sink.sum()) == 0
     assert abq.abq_probe_mfma_i8_ops(1) == 2.0 * 16 * 16 * 64 * 8 * 4 * 8 * torch.cuda.get_device_properties(0).multi_processor_count
