@@ -169,6 +169,22 @@ def test_longest_k(abq):
     check_against_oracle(c, y, acc)
 
 
+def test_prefill_long_k_sums_of_codes_beyond_24_bits(abq):
+    """M > 16 with K * (2^q - 1) or K * (2^p - 1) at or above 2^23: the prefill kernel's epilogue must leave its 24-bit
+    multiply-adds for 32-bit multiplies (the host decides), with and without the accumulator output."""
+    for p, q, M, N, K in [(2, 8, 40, 70, 40000), (8, 2, 33, 130, 36000), (1, 8, 70, 24, 131072)]:
+        assert K * ((1 << max(p, q)) - 1) >= 1 << 23
+        c = synth.make_case(p, q, M, N, K, seed=31 + p + q)
+        say(c.name)
+        y, acc = gpu_gemm(torch, abq, c, FIELDS, FIELDS)
+        check_against_oracle(c, y, acc)
+        pw = abq.abq_pack_weights(p, to_dev(torch, c.W), to_dev(torch, c.w_scale), to_dev(torch, c.w_zero), FIELDS)
+        pa = abq.abq_pack_act_codes(q, to_dev(torch, c.A), to_dev(torch, c.a_scale), to_dev(torch, c.a_zero), FIELDS)
+        y_only, _ = abq.abq_gemm(p, q, M, N, K, pa, FIELDS, pw, FIELDS)
+        torch.cuda.synchronize()
+        assert np.array_equal(y_only.cpu().numpy().view(np.uint16), np.asarray(y).view(np.uint16))
+
+
 # Long K with up to 16 rows of A: the streaming kernel stages A one K group at a time and keeps per-tile
 # partial sums between the groups (several tiles per workgroup at the larger N).
 KGROUP_SHAPES = [(16, 70, 13824), (16, 4096, 11008), (12, 40, 20000), (9, 48, 16384), (16, 8200, 11008),
