@@ -49,7 +49,7 @@ def test_f4_matmul_against_oracle(abq, p, q, M, N, K):
 
 def test_f4_extreme_codes(abq):
     """All codes maximal (the largest sums: K * 9), all zero, and zero-points at both ends."""
-    for p, q, K in [(2, 2, 8192), (1, 2, 3000), (2, 1, 4096)]:
+    for p, q, K in [(2, 2, 8192), (1, 2, 3000), (2, 1, 4096), (2, 2, 131072)]:   # (the last: the longest K the ABI takes)
         c = synth.make_case(p, q, 40, 70, K, seed=5, name=f"f4 max W{p}A{q} K={K}")
         c.A[:] = (1 << q) - 1
         c.W[:] = (1 << p) - 1
