@@ -592,13 +592,14 @@ static hipError_t launch_shape(const TiledParams& prm, dim3 grid, int cus, int p
     // registers run out) and run two workgroups per CU instead of three.  Measured: with at most one workgroup
     // per CU (M = 64..128 on a 4096-wide layer) they are 20 % faster, with more workgroups (M = 128 on an
     // 11008-wide layer and up) the traffic through L2, not the latency of a step, is the bound and they lose.
-    // With long K (13824) the plan search found them 6-7 % ahead up to 1.25 workgroups per CU as well, and at
-    // p = 8 up to 2.5 per CU (M = 512, 5120 channels: 75 vs 84 us); narrower weights lose there (W2A8: 53 vs 44 us).
+    // With long K (13824) and p = 8 the plan search found them ahead up to 2.5 workgroups per CU (M = 512, 5120 channels:
+    // 75 vs 84 us); narrower weights lose or tie there (between one and two workgroups per CU, K = 11008..13824: W1A8
+    // 38 vs 33 us, W2A8 35 vs 28, W4A8 and W6A8 within 1 %), because the deep rings hold two workgroups per CU, not three.
     // Override: the plan table (plan_wd).
     constexpr bool has_deep = MT == 4 && (NTW == 1 || (NTW == 2 && P <= 6));
     const int forced = plan_wd > 0 ? plan_wd : tuning_env("ABQ_TILED_WD");
     if constexpr (has_deep) {
-        if (forced == 4 || (forced != 2 && ((long)grid.x <= (long)cus || ((long)grid.x <= (P == 8 ? 3L : 2L) * cus && prm.K >= 8192)))) {
+        if (forced == 4 || (forced != 2 && ((long)grid.x <= (long)cus || (P == 8 && (long)grid.x <= 3L * cus && prm.K >= 8192)))) {
             tiled_kernel<P, NTW, MT, 4><<<grid, 256, 0, s>>>(prm);
             return hipGetLastError();
         }
@@ -672,7 +673,13 @@ hipError_t launch_gemm_tiled(const GemmArgs& g, const ActLayout& A, const Weight
     int mt = 8, ntw = 2;
     if (g.M <= 64 || 2 * wgs(8, 2) < 3L * cus) { mt = 4; ntw = 2; }
     else if (g.p <= 4 && g.M >= 1024) { mt = 4; ntw = wgs(4, 4) >= 3L * cus ? 4 : 2; }
-    if (mt == 4 && ntw == 2 && 2 * wgs(4, 2) < 3L * cus) ntw = 1;
+    // Long K, p = 4..6 and between 0.5 and 1.25 workgroups of 64 x 128 per CU: that tile on the deep rings is
+    // 4-11 % ahead of 64 x 64 (plan search, K = 11008 and 13824: M = 256 on 5120 channels, M = 512 on 4096 and 5120); with
+    // fewer workgroups 64 x 64 on the deep rings wins by a wide margin (M = 256 on 4096 channels: 24 vs 33 us), with two
+    // per CU the shallow rings do (M = 1024 on 4096 channels: 60 vs 66 us), and narrower weights prefer those anyway.
+    int rule_wd = 0;
+    if (mt == 4 && ntw == 2 && g.p >= 4 && g.p <= 6 && g.K >= 8192 && 2 * wgs(4, 2) > (long)cus && 4 * wgs(4, 2) <= 5L * cus) rule_wd = 4;
+    if (mt == 4 && ntw == 2 && rule_wd == 0 && 2 * wgs(4, 2) < 3L * cus) ntw = 1;
     {
         const int forced_mt = tuning_env("ABQ_TILED_MT"), forced_ntw = tuning_env("ABQ_TILED_NTW");
         if (forced_mt == 4 || forced_mt == 8) mt = forced_mt;
@@ -682,6 +689,7 @@ hipError_t launch_gemm_tiled(const GemmArgs& g, const ActLayout& A, const Weight
     lookup_plan(g.p, g.q, g.M, g.N, g.K, &ov);
     if (ov.tiled_mt > 0) mt = ov.tiled_mt;
     if (ov.tiled_ntw > 0) ntw = ov.tiled_ntw;
+    const int wd_arg = ov.tiled_wd > 0 ? ov.tiled_wd : ((mt == 4 && ntw == 2) ? rule_wd : 0);
     prm.tiles_m = (g.M + mt * 16 - 1) / (mt * 16);
     prm.tiles_n = (g.N + 64 * ntw - 1) / (64 * ntw);
     // Bands of equal height.  The workgroups resident on one XCD (about 64) form a band_m x (64 / band_m)
@@ -696,14 +704,14 @@ hipError_t launch_gemm_tiled(const GemmArgs& g, const ActLayout& A, const Weight
     }
     dim3 grid((unsigned)(prm.tiles_m * prm.tiles_n));
     switch (g.p) {
-        case 1: return launch_p<1>(prm, ntw, mt, grid, cus, ov.tiled_wd, s);
-        case 2: return launch_p<2>(prm, ntw, mt, grid, cus, ov.tiled_wd, s);
-        case 3: return launch_p<3>(prm, ntw, mt, grid, cus, ov.tiled_wd, s);
-        case 4: return launch_p<4>(prm, ntw, mt, grid, cus, ov.tiled_wd, s);
-        case 5: return launch_p<5>(prm, ntw, mt, grid, cus, ov.tiled_wd, s);
-        case 6: return launch_p<6>(prm, ntw, mt, grid, cus, ov.tiled_wd, s);
-        case 7: return launch_p<7>(prm, ntw, mt, grid, cus, ov.tiled_wd, s);
-        default: return launch_p<8>(prm, ntw, mt, grid, cus, ov.tiled_wd, s);
+        case 1: return launch_p<1>(prm, ntw, mt, grid, cus, wd_arg, s);
+        case 2: return launch_p<2>(prm, ntw, mt, grid, cus, wd_arg, s);
+        case 3: return launch_p<3>(prm, ntw, mt, grid, cus, wd_arg, s);
+        case 4: return launch_p<4>(prm, ntw, mt, grid, cus, wd_arg, s);
+        case 5: return launch_p<5>(prm, ntw, mt, grid, cus, wd_arg, s);
+        case 6: return launch_p<6>(prm, ntw, mt, grid, cus, wd_arg, s);
+        case 7: return launch_p<7>(prm, ntw, mt, grid, cus, wd_arg, s);
+        default: return launch_p<8>(prm, ntw, mt, grid, cus, wd_arg, s);
     }
 }
 
