@@ -671,14 +671,19 @@ hipError_t launch_gemm_tiled(const GemmArgs& g, const ActLayout& A, const Weight
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
     auto wgs = [&](int mt_, int ntw_) { return (long)((g.M + mt_ * 16 - 1) / (mt_ * 16)) * ((g.N + 64 * ntw_ - 1) / (64 * ntw_)); };
     int mt = 8, ntw = 2;
-    if (g.M <= 64 || 2 * wgs(8, 2) < 3L * cus) { mt = 4; ntw = 2; }
-    else if (g.p <= 4 && g.M >= 1024) { mt = 4; ntw = wgs(4, 4) >= 3L * cus ? 4 : 2; }
-    // Long K, p = 4..6 and between 0.5 and 1.25 workgroups of 64 x 128 per CU: that tile on the deep rings is
-    // 4-11 % ahead of 64 x 64 (plan search, K = 11008 and 13824: M = 256 on 5120 channels, M = 512 on 4096 and 5120); with
+    // (p = 8: 128 x 128 also with 0.8..1 workgroups per CU, where it halves the weight bytes through L2 and every CU still
+    // has one: M = 256 on 13824 channels 40 -> 37 us, M = 1024 on 4096 channels 71 -> 67; with 1.25 per CU it loses 8 %.  64 x 256 also where it fills the chip exactly once
+    // at two workgroups per CU, 1.5..2 per CU: M = 2048 on 4096 channels, W4A8 K = 11008 95 -> 83 us.)
+    const bool mt8 = 2 * wgs(8, 2) >= 3L * cus || (g.p == 8 && 5 * wgs(8, 2) >= 4L * cus && wgs(8, 2) <= (long)cus);
+    if (g.M <= 64 || !mt8) { mt = 4; ntw = 2; }
+    else if (g.p <= 4 && g.M >= 1024) { mt = 4; ntw = (wgs(4, 4) >= 3L * cus || (wgs(4, 4) <= 2L * cus && 2 * wgs(4, 4) > 3L * cus)) ? 4 : 2; }
+    // K >= 5120, p = 4..6 and between 0.5 and 1.25 workgroups of 64 x 128 per CU: that tile on the deep rings is
+    // 4-11 % ahead of 64 x 64 (plan search, K = 5120, 11008, 13824: M = 128 on 13824 channels, M = 256 on 5120, M = 512 on
+    // 4096 and 5120; at K = 4096, M = 128 on 11008 channels, it is 3 % behind); with
     // fewer workgroups 64 x 64 on the deep rings wins by a wide margin (M = 256 on 4096 channels: 24 vs 33 us), with two
     // per CU the shallow rings do (M = 1024 on 4096 channels: 60 vs 66 us), and narrower weights prefer those anyway.
     int rule_wd = 0;
-    if (mt == 4 && ntw == 2 && g.p >= 4 && g.p <= 6 && g.K >= 8192 && 2 * wgs(4, 2) > (long)cus && 4 * wgs(4, 2) <= 5L * cus) rule_wd = 4;
+    if (mt == 4 && ntw == 2 && g.p >= 4 && g.p <= 6 && g.K >= 5120 && 2 * wgs(4, 2) > (long)cus && 4 * wgs(4, 2) <= 5L * cus) rule_wd = 4;
     if (mt == 4 && ntw == 2 && rule_wd == 0 && 2 * wgs(4, 2) < 3L * cus) ntw = 1;
     {
         const int forced_mt = tuning_env("ABQ_TILED_MT"), forced_ntw = tuning_env("ABQ_TILED_NTW");
