@@ -82,12 +82,15 @@ def test_f4_drops_bits_above_the_width(abq):
     check_against_oracle(c, y.cpu().numpy(), acc.cpu().numpy())
 
 
-def test_f4_large_tile_two_buffers_sampled(abq):
-    """256 workgroups of the 256-row tile (the two-buffer variant, three workgroups per unit), ragged K: sampled outputs."""
-    c = synth.make_case(2, 2, 1024, 8192, 1000, seed=synth.case_seed(11, 2, 2, 55, 66), name="f4 W2A2 1024x8192x1000")
-    say(c.name)
-    y, acc = run_f4(abq, c)
-    check_sampled(c, y, acc)
+def test_f4_large_tile_sampled(abq):
+    """256 workgroups of the 256-row tile (one per compute unit: the smallest grid that takes this tile), ragged K (eight
+    steps: two turns of the three-buffer ring and a tail of two): sampled outputs.  A second case with several panels of
+    row tiles and a partial last panel."""
+    for M, N, K in [(1024, 8192, 1000), (2600, 3300, 640)]:
+        c = synth.make_case(2, 2, M, N, K, seed=synth.case_seed(11, 2, 2, 55, 66), name=f"f4 W2A2 {M}x{N}x{K}")
+        say(c.name)
+        y, acc = run_f4(abq, c)
+        check_sampled(c, y, acc)
 
 
 @pytest.mark.parametrize("p,q", [(2, 2), (1, 1)])
