@@ -309,6 +309,7 @@ __global__ __launch_bounds__(256, RT == 4 ? 2 : 4) void f4_gemm_kernel(F4Params 
                 x[(g + 1) & 1][1] = *reinterpret_cast<const v4i_f4*>(mine + (2 * g + 3) * 1024);
             }
             __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_setprio(1);   // (the wave that has its operands goes first: 1-2 % with two workgroups per unit)
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 const v4i_f4 xb = x[g & 1][h];
@@ -317,6 +318,7 @@ __global__ __launch_bounds__(256, RT == 4 ? 2 : 4) void f4_gemm_kernel(F4Params 
                 for (int i = 0; i < RT; ++i)
                     acc[i][2 * g + h] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a[i], b, acc[i][2 * g + h], 4, 4, 0, one, 0, one);
             }
+            __builtin_amdgcn_s_setprio(0);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
