@@ -62,24 +62,27 @@ __device__ __forceinline__ uint32_t f4_nibbles(uint32_t x)
 constexpr int kF4PackWaves = 16;
 __global__ __launch_bounds__(64 * kF4PackWaves) void f4_pack_kernel(const uint8_t* codes, int rows, int K, int kblocks, uint32_t mask, int vec,
                                                                     const float* scale, const int32_t* zero, int bits, uint32_t* hdr,
-                                                                    RowParams* params, v4i_f4* out)
+                                                                    RowParams* params, v4i_f4* out, int ksplit)
 {
     __shared__ uint32_t part[kF4PackWaves][16];
     const int tid = (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int rt = (int)blockIdx.x;
+    // ksplit = 2: two workgroups per row tile, one per half of the K blocks (a pack of 2048 rows is otherwise 128
+    // workgroups: half the chip); the second writes its sums of codes into the record's spare word
+    const int rt = (int)blockIdx.x / ksplit, half = (int)blockIdx.x % ksplit;
+    const int kb_per = (kblocks + ksplit - 1) / ksplit, kb_lo = half * kb_per, kb_hi = min(kblocks, kb_lo + kb_per);
     const int row = rt * 16 + (lane & 15);
     const uint8_t* src = codes + (size_t)min(row, rows - 1) * K;   // (rows past the end: a valid row is read, zeros are stored)
     const uint32_t m4 = mask * 0x01010101u;
     uint32_t sum = 0;
     // up to four K blocks of the wave at a time: their loads are all requested before the first is packed
     constexpr int NB = 4;
-    for (int kb0 = wave; kb0 < kblocks; kb0 += kF4PackWaves * NB) {
+    for (int kb0 = kb_lo + wave; kb0 < kb_hi; kb0 += kF4PackWaves * NB) {
         v4i_f4 lo[NB], hi[NB];
         bool fast[NB];
 #pragma unroll
         for (int u = 0; u < NB; ++u) {
             const int kb = kb0 + kF4PackWaves * u, k0 = kb * kF4BlockK + (lane >> 4) * 32;
-            fast[u] = vec && kb < kblocks && k0 + 32 <= K;
+            fast[u] = vec && kb < kb_hi && k0 + 32 <= K;
             lo[u] = hi[u] = v4i_f4{0, 0, 0, 0};
             if (fast[u]) {
                 lo[u] = *reinterpret_cast<const v4i_f4*>(src + k0);
@@ -89,7 +92,7 @@ __global__ __launch_bounds__(64 * kF4PackWaves) void f4_pack_kernel(const uint8_
 #pragma unroll
         for (int u = 0; u < NB; ++u) {
             const int kb = kb0 + kF4PackWaves * u, k0 = kb * kF4BlockK + (lane >> 4) * 32;
-            if (kb >= kblocks) break;   // (the same for the whole wave)
+            if (kb >= kb_hi) break;   // (the same for the whole wave)
             uint32_t w[4] = {0, 0, 0, 0};
             if (fast[u]) {
                 const uint32_t c[8] = {(uint32_t)lo[u].x & m4, (uint32_t)lo[u].y & m4, (uint32_t)lo[u].z & m4, (uint32_t)lo[u].w & m4,
@@ -119,9 +122,16 @@ __global__ __launch_bounds__(64 * kF4PackWaves) void f4_pack_kernel(const uint8_
         uint32_t total = 0;
 #pragma unroll
         for (int w = 0; w < kF4PackWaves; ++w) total += part[w][tid];
-        params[row] = RowParams{(int32_t)total, scale[row], zero[row], 0};
+        if (half == 0) {
+            params[row].sum = (int32_t)total;
+            params[row].scale = scale[row];
+            params[row].zero = zero[row];
+            if (ksplit == 1) params[row].pad = 0;
+        } else {
+            params[row].pad = (int32_t)total;   // (the matmul adds the two)
+        }
     }
-    if (rt == 0 && tid >= 64 && tid < 128) {
+    if (blockIdx.x == 0 && tid >= 64 && tid < 128) {
         const int t = tid - 64;
         hdr[t] = t == 0 ? 0x34514241u /* "ABQ4" */ : (t == 1 ? 0x34460001u : (t == 2 ? (uint32_t)bits : (t == 3 ? (uint32_t)rows : (t == 4 ? (uint32_t)K : 0u))));
     }
@@ -131,8 +141,9 @@ hipError_t launch_f4_pack(int bits, int rows, int K, const uint8_t* codes, const
 {
     const uint32_t mask = (1u << bits) - 1u;
     const int vec = (K % 16 == 0) ? 1 : 0;   // (the entry point checks that `codes` is 16-byte aligned)
-    f4_pack_kernel<<<(unsigned)f4_row_tiles(rows), 64 * kF4PackWaves, 0, s>>>(codes, rows, K, f4_k_blocks(K), mask, vec, scale, zero, bits, (uint32_t*)blob,
-                                                                              (RowParams*)(blob + f4_off_params()), (v4i_f4*)(blob + f4_off_blocks(rows)));
+    const int ksplit = (f4_k_blocks(K) >= 32 && 2L * f4_row_tiles(rows) <= (long)num_cus()) ? 2 : 1;
+    f4_pack_kernel<<<(unsigned)(f4_row_tiles(rows) * ksplit), 64 * kF4PackWaves, 0, s>>>(codes, rows, K, f4_k_blocks(K), mask, vec, scale, zero, bits, (uint32_t*)blob,
+                                                                                         (RowParams*)(blob + f4_off_params()), (v4i_f4*)(blob + f4_off_blocks(rows)), ksplit);
     return hipGetLastError();
 }
 
@@ -172,8 +183,9 @@ __device__ __forceinline__ void f4_epilogue(const F4Params& prm, v4f_f4 (*acc)[8
     RowParams* const par_a = reinterpret_cast<RowParams*>(lds_f4 + SH::kParamOffset);
     RowParams* const par_w = par_a + SH::kTileM;
     // epilogue parameters (fetched by the kernel before its K loop: no memory round trip here) into the freed operand memory
-    if (tid < SH::kTileM) *reinterpret_cast<v4i_f4*>(par_a + tid) = my_a;
-    if (tid < kF4TileN) *reinterpret_cast<v4i_f4*>(par_w + tid) = my_w;
+    // (a record's sum of codes may come in two parts, the second in its spare word: see f4_pack_kernel)
+    if (tid < SH::kTileM) *reinterpret_cast<v4i_f4*>(par_a + tid) = v4i_f4{my_a.x + my_a.w, my_a.y, my_a.z, 0};
+    if (tid < kF4TileN) *reinterpret_cast<v4i_f4*>(par_w + tid) = v4i_f4{my_w.x + my_w.w, my_w.y, my_w.z, 0};
     __syncthreads();
 
     // ---- epilogue: lane (G, r) of accumulator (i, j) holds rows 16 RT wave + 16 i + 4 G + reg, channel 16 j + r.
