@@ -176,6 +176,10 @@ def measured_peaks(pool, workload_bytes, launches=200):
     for key, pattern in (("mfma_f4_mostly_zero_operands", 0), ("mfma_f4_nonzero_operands", 1)):
         t = timed(lambda i: abq.abq_probe_mfma_f4(iters, pattern, sink), 10)
         out[key] = {"us": t * 1e6, "tops": abq.abq_probe_mfma_f4_ops(iters) / t / 1e12}
+    # reads that hit in L2 (every workgroup re-reads its XCD's 1 MiB region): what the compute units can pull from the caches
+    region, passes, wgs = 1 << 20, 8, 4
+    t = timed(lambda i: abq.abq_probe_l2_read(pool, region, passes, wgs, sink), 5)
+    out["l2_hit_read"] = {"us": t * 1e6, "gbs": abq.abq_probe_l2_read_bytes(region, passes, wgs) / t / 1e9}
     return out
 
 
