@@ -68,3 +68,32 @@ def abq_probe_mfma_f4(iters, pattern, sink):
 
 def abq_probe_mfma_f4_ops(iters):
     return load().abq_probe_mfma_f4_ops(iters)
+
+
+def l2_read_table(regions_mib=(0.5, 1, 2, 3, 8, 32), wgs_per_cu=(1, 2, 4, 8)):
+    """Times abq_probe_l2_read over region sizes and workgroups per compute unit; rows of (MiB per XCD, passes,
+    workgroups per CU, microseconds, TB/s).  `python -m paper_2408_08554_amd.probe` prints them."""
+    sink = torch.zeros(4096, dtype=torch.uint8, device="cuda")
+    rows = []
+    for region_mib in regions_mib:
+        region = int(region_mib * (1 << 20))
+        passes = max(1, int(8 // region_mib))
+        buf = torch.randint(0, 255, (8 * region,), dtype=torch.uint8, device="cuda")
+        for wgs in wgs_per_cu:
+            for _ in range(2):
+                abq_probe_l2_read(buf, region, passes, wgs, sink)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            abq_probe_l2_read(buf, region, passes, wgs, sink)
+            e1.record()
+            torch.cuda.synchronize()
+            t = e0.elapsed_time(e1) * 1e-3
+            rows.append((region_mib, passes, wgs, t * 1e6, abq_probe_l2_read_bytes(region, passes, wgs) / t / 1e12))
+    return rows
+
+
+if __name__ == "__main__":
+    print("| MiB per XCD | passes | workgroups per CU | us | TB/s |\n|---|---|---|---|---|")
+    for r in l2_read_table():
+        print(f"| {r[0]} | {r[1]} | {r[2]} | {r[3]:.0f} | {r[4]:.1f} |")
